@@ -1,0 +1,303 @@
+"""CPU oracle for DAG-structured attention (MedVerse attention, paper sections 3.2-3.3, 4.2, 4.3).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain, fp64 definition of what the GPU library
+computes.  It may be imported by tests/, by __graft_entry__.smoke() and by the cpu_baseline leg of
+bench.py, and by nothing else.  It shares no code with the HIP path and never imports it.
+
+Conventions (the paper is silent or loose on several; these are the readings used):
+  * A sequence is a DAG of N nodes (reasoning states / Petri-net places, section 3.1-3.2).  Node v
+    has L[v] >= 1 tokens.  Tokens are stored node after node in node-id order, and node ids are a
+    topological order: anc(v) is a subset of {0..v-1}.
+  * anc is a uint64 array [N][W]; bit u of row v set  <=>  node u is an ancestor of node v.  The
+    self bit is ignored on input.
+  * Visibility (section 4.2 Eq. 3 generalised to the ancestor closure the engine text of section
+    3.3 / 4.3 describes): token i sees token j  iff  (same node and j <= i) or node(j) in
+    anc(node(i)).  A caller who wants the literal layer-wise Eq. 3 passes anc(v) = all nodes of
+    earlier layers.
+  * Adaptive positions (section 4.2, "Adaptive Position Indices"): a node without ancestors starts
+    at 0; otherwise it starts one past the largest position used by any ancestor.  Siblings with
+    the same ancestor set therefore start at the same index (fork alignment) and a join resumes
+    after its longest predecessor.
+  * P(i) of Eq. 2 is rotary embedding, rotate-half pairing (m, m + D/2), frequency theta^(-2m/D).
+  * Scores are scaled by softmax_scale (1/sqrt(D) by default), which Eq. 2 leaves out.
+  * Paged KV (section 3.2 token tau=(h,k): KV passed by page reference; section 4.3 Fork: the
+    prefix pages are shared by all sibling branches).  Page size 16.  Pool storage formats:
+        K pool [n_pages][Hkv][D/8][16][8]   element (page, h, slot, d) at [page, h, d//8, slot, d%8]
+        V pool [n_pages][Hkv][D][16]        element (page, h, slot, d) at [page, h, d, slot]
+"""
+import numpy as np
+
+PAGE = 16
+SKIP, PARTIAL, FULL = 0, 1, 2
+
+
+# ----------------------------------------------------------------------------- node level
+def _has_bit(anc, v, u):
+    return (int(anc[v, u >> 6]) >> (u & 63)) & 1 == 1
+
+
+def ancestors(anc, v):
+    """Ancestor ids of node v as a list (self bit ignored)."""
+    n = anc.shape[0]
+    return [u for u in range(n) if u != v and _has_bit(anc, v, u)]
+
+
+def node_tables(node_len, anc):
+    """Section 4.2 adaptive position rule at node granularity.
+
+    Returns (tok_start[N+1], pos_start[N]) as int64.
+    """
+    L = [int(x) for x in node_len]
+    n = len(L)
+    tok_start = np.zeros(n + 1, dtype=np.int64)
+    for v in range(n):
+        tok_start[v + 1] = tok_start[v] + L[v]
+    pos_start = np.zeros(n, dtype=np.int64)
+    for v in range(n):
+        a = ancestors(anc, v)
+        if a:
+            pos_start[v] = 1 + max(int(pos_start[u]) + L[u] - 1 for u in a)
+    return tok_start, pos_start
+
+
+def token_meta(node_len, anc):
+    """Per-token node id and adaptive position id (int64 arrays of length T)."""
+    tok_start, pos_start = node_tables(node_len, anc)
+    n = len(node_len)
+    T = int(tok_start[n])
+    tok_node = np.zeros(T, dtype=np.int64)
+    pos_ids = np.zeros(T, dtype=np.int64)
+    for v in range(n):
+        t0, t1 = int(tok_start[v]), int(tok_start[v + 1])
+        tok_node[t0:t1] = v
+        pos_ids[t0:t1] = int(pos_start[v]) + np.arange(t1 - t0)
+    return tok_node, pos_ids
+
+
+def node_vis(anc):
+    """Visibility bitset per node: ancestors plus the node itself."""
+    out = np.array(anc, dtype=np.uint64, copy=True)
+    for v in range(out.shape[0]):
+        out[v, v >> 6] |= np.uint64(1) << np.uint64(v & 63)
+    return out
+
+
+def node_allow_matrix(anc):
+    """A[v][u] = True iff u is an ancestor of v (self excluded)."""
+    n = anc.shape[0]
+    A = np.zeros((n, n), dtype=bool)
+    for v in range(n):
+        for u in ancestors(anc, v):
+            A[v, u] = True
+    return A
+
+
+# ----------------------------------------------------------------------------- mask
+def mask_rows(node_len, anc, i0, i1):
+    """Rows [i0, i1) of the explicit T x T boolean visibility mask (Eq. 3, ancestor reading)."""
+    tok_node, _ = token_meta(node_len, anc)
+    A = node_allow_matrix(anc)
+    T = tok_node.shape[0]
+    i = np.arange(i0, i1)[:, None]
+    j = np.arange(T)[None, :]
+    ni = tok_node[i0:i1][:, None]
+    nj = tok_node[None, :]
+    same = (ni == nj) & (j <= i)
+    return same | A[ni, nj]
+
+
+def explicit_mask(node_len, anc):
+    T = int(np.sum(node_len))
+    return mask_rows(node_len, anc, 0, T)
+
+
+def useful_pairs(node_len, anc):
+    """Number of visible (query, key) pairs, counted from the explicit mask."""
+    T = int(np.sum(node_len))
+    total = 0
+    for i0 in range(0, T, 1024):
+        total += int(mask_rows(node_len, anc, i0, min(T, i0 + 1024)).sum())
+    return total
+
+
+def block_map(node_len, anc, tile_m, tile_n):
+    """Tile classification by brute force over in-range pairs: 0 skip / 1 partial / 2 full.
+
+    Tiles restart at the beginning of the sequence; returns uint8 [QT][KT].
+    """
+    T = int(np.sum(node_len))
+    QT = (T + tile_m - 1) // tile_m
+    KT = (T + tile_n - 1) // tile_n
+    out = np.zeros((QT, KT), dtype=np.uint8)
+    for a in range(QT):
+        rows = mask_rows(node_len, anc, a * tile_m, min(T, (a + 1) * tile_m))
+        for b in range(KT):
+            sub = rows[:, b * tile_n:min(T, (b + 1) * tile_n)]
+            if not sub.any():
+                out[a, b] = SKIP
+            elif sub.all():
+                out[a, b] = FULL
+            else:
+                out[a, b] = PARTIAL
+    return out
+
+
+def block_map_csr(bmap):
+    """CSR over the non-skip tiles of a dense block map, key tiles ascending."""
+    QT, KT = bmap.shape
+    row_ptr = np.zeros(QT + 1, dtype=np.int64)
+    col, flag = [], []
+    for a in range(QT):
+        for b in range(KT):
+            if bmap[a, b] != SKIP:
+                col.append(b)
+                flag.append(int(bmap[a, b]))
+        row_ptr[a + 1] = len(col)
+    return row_ptr, np.array(col, dtype=np.int64), np.array(flag, dtype=np.uint8)
+
+
+# ----------------------------------------------------------------------------- rotary embedding
+def rope(x, pos, theta):
+    """Rotate x[T][H][D] (any float dtype, upcast to fp64) by angle pos[t] * theta^(-2m/D).
+
+    Pairing is (m, m + D/2) for m in [0, D/2)  (Eq. 2's P(i) read as rotary embedding).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    D = x.shape[-1]
+    half = D // 2
+    m = np.arange(half, dtype=np.float64)
+    omega = np.float64(theta) ** (-2.0 * m / D)
+    phi = np.asarray(pos, dtype=np.float64)[:, None] * omega[None, :]      # [T][half]
+    c = np.cos(phi)[:, None, :]
+    s = np.sin(phi)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    out = np.empty_like(x)
+    out[..., :half] = lo * c - hi * s
+    out[..., half:] = hi * c + lo * s
+    return out
+
+
+# ----------------------------------------------------------------------------- prefill attention
+def attn_prefill(q, k, v, node_len, anc, scale=None, row_block=128, rows=None, heads=None):
+    """O_i = sum_j softmax_j(q_i . k_j * scale + M_ij) v_j with the DAG mask (Eq. 2 + Eq. 3).
+
+    q [T][Hq][D], k, v [T][Hkv][D] are the already-rotated inputs.  Query head h uses KV head
+    h // (Hq/Hkv).  Returns (O [T][Hq][D], lse [T][Hq]) in fp64.  `rows` / `heads` optionally
+    restrict the computation to a subset (other entries are left NaN).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    O = np.full((T, Hq, D), np.nan)
+    lse = np.full((T, Hq), np.nan)
+    head_list = list(range(Hq)) if heads is None else list(heads)
+    if rows is None:
+        blocks = [np.arange(i0, min(T, i0 + row_block)) for i0 in range(0, T, row_block)]
+    else:
+        rows = np.asarray(rows)
+        blocks = [rows[i:i + row_block] for i in range(0, len(rows), row_block)]
+    tok_node, _ = token_meta(node_len, anc)
+    A = node_allow_matrix(anc)
+    j = np.arange(T)[None, :]
+    for blk in blocks:
+        ni = tok_node[blk][:, None]
+        allow = ((ni == tok_node[None, :]) & (j <= blk[:, None])) | A[ni, tok_node[None, :]]
+        for h in head_list:
+            S = (q[blk, h, :] @ k[:, h // G, :].T) * scale
+            S[~allow] = -np.inf
+            mrow = S.max(axis=1, keepdims=True)
+            P = np.exp(S - mrow)
+            lrow = P.sum(axis=1, keepdims=True)
+            O[blk, h, :] = (P @ v[:, h // G, :]) / lrow
+            lse[blk, h] = (mrow + np.log(lrow))[:, 0]
+    return O, lse
+
+
+# ----------------------------------------------------------------------------- paged KV
+def pool_get_k(k_pool, page, h, slot):
+    """Key vector [D] of (page, kv head, slot) from the K pool format [P][Hkv][D/8][16][8]."""
+    return np.asarray(k_pool[page, h, :, slot, :], dtype=np.float64).reshape(-1)
+
+
+def pool_get_v(v_pool, page, h, slot):
+    """Value vector [D] of (page, kv head, slot) from the V pool format [P][Hkv][D][16]."""
+    return np.asarray(v_pool[page, h, :, slot], dtype=np.float64)
+
+
+def kv_append_rope(desc, k_new, v_new, k_pool, v_pool, theta):
+    """Write each live branch's new token into the tail of its own page list (in place).
+
+    The key is rotated at the branch's adaptive position; the slot is branch_len-1 counted over
+    the branch's own pages.  Pools are float arrays in the formats above; stores keep the pool's
+    dtype rounding to the caller (the caller passes arrays of the storage precision).
+    """
+    n_live = len(desc["branch_len"])
+    k_rot = rope(k_new, desc["branch_pos"], theta)
+    for r in range(n_live):
+        idx = int(desc["branch_len"][r]) - 1
+        page = int(desc["branch_pages"][int(desc["branch_page_off"][r]) + idx // PAGE])
+        slot = idx % PAGE
+        Hkv = k_pool.shape[1]
+        for h in range(Hkv):
+            k_pool[page, h, :, slot, :] = k_rot[r, h].reshape(-1, 8)
+            v_pool[page, h, :, slot] = np.asarray(v_new[r, h], dtype=np.float64)
+    return k_rot
+
+
+def gather_context(desc, r, h, k_pool, v_pool):
+    """K, V [ctx][D] seen by live branch r on KV head h: shared tokens, then its own tokens."""
+    g = int(np.searchsorted(np.asarray(desc["group_branch_off"]), r, side="right") - 1)
+    Ks, Vs = [], []
+    for t in range(int(desc["shared_len"][g])):
+        page = int(desc["shared_pages"][int(desc["shared_page_off"][g]) + t // PAGE])
+        Ks.append(pool_get_k(k_pool, page, h, t % PAGE))
+        Vs.append(pool_get_v(v_pool, page, h, t % PAGE))
+    for t in range(int(desc["branch_len"][r])):
+        page = int(desc["branch_pages"][int(desc["branch_page_off"][r]) + t // PAGE])
+        Ks.append(pool_get_k(k_pool, page, h, t % PAGE))
+        Vs.append(pool_get_v(v_pool, page, h, t % PAGE))
+    return np.array(Ks), np.array(Vs)
+
+
+def attn_decode(desc, q, k_pool, v_pool, scale=None, branches=None):
+    """One decode step: o = softmax(q . K^T * scale) V over each branch's context, fp64.
+
+    q [n_live][Hq][D] already rotated.  Returns O [n_live][Hq][D] (NaN for branches not asked).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    n_live, Hq, D = q.shape
+    Hkv = k_pool.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    O = np.full((n_live, Hq, D), np.nan)
+    for r in (range(n_live) if branches is None else branches):
+        for hk in range(Hkv):
+            K, V = gather_context(desc, r, hk, k_pool, v_pool)
+            for h in range(hk * G, (hk + 1) * G):
+                s = (K @ q[r, h]) * scale
+                p = np.exp(s - s.max())
+                O[r, h] = (p @ V) / p.sum()
+    return O
+
+
+# ----------------------------------------------------------------------------- log-sum-exp merge
+def partial_attention(qvec, K, V, scale):
+    """Un-normalised partial over a key subset: (o = sum_j e^{s_j-m} v_j, m = max s, l = sum e^{s_j-m})."""
+    s = (np.asarray(K, dtype=np.float64) @ np.asarray(qvec, dtype=np.float64)) * scale
+    m = s.max()
+    p = np.exp(s - m)
+    return p @ np.asarray(V, dtype=np.float64), m, p.sum()
+
+
+def lse_merge(partials):
+    """Combine partials [(o, m, l), ...]: m = max m_s; l = sum l_s e^{m_s-m}; o = sum o_s e^{m_s-m} / l."""
+    m = max(p[1] for p in partials)
+    l = sum(p[2] * np.exp(p[1] - m) for p in partials)
+    o = sum(p[0] * np.exp(p[1] - m) for p in partials)
+    return o / l

@@ -1,0 +1,405 @@
+"""Pins for the CPU oracle: every function of oracle/dag_oracle.py is checked against something
+other than itself -- hand-enumerated fixtures, closed forms, library routines (torch fp64
+scaled_dot_product_attention) and invariants -- so that a dropped term, a wrong sign or index, or a
+transposed operand fails at least one test.  No GPU needed.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dag_oracle as orc
+from workloads import dags
+
+GOLDEN = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "tiny_dags.json")))
+
+
+def _dag_from_parents(node_len, parents):
+    return (np.asarray(node_len, dtype=np.int32),
+            dags.bits_from_sets(dags.closure_from_parents(parents)))
+
+
+def _rand(seed, *shape):
+    return np.random.Generator(np.random.PCG64(seed)).standard_normal(shape)
+
+
+def _sdpa_causal(q, k, v, scale):
+    """Library routine: fp64 causal attention. q [T][H][D], k/v [T][H][D] (same head count)."""
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(k).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(v).permute(1, 0, 2)[None]
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=scale)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+# ------------------------------------------------------------------ positions (section 4.2)
+def test_positions_diamond_golden():
+    g = GOLDEN["diamond"]
+    L, anc = _dag_from_parents(g["node_len"], g["parents"])
+    tok_node, pos = orc.token_meta(L, anc)
+    assert tok_node.tolist() == g["tok_node"]
+    assert pos.tolist() == g["pos_ids"]
+
+
+def test_positions_config1_statement():
+    g = GOLDEN["config1_positions"]
+    L, anc = dags.fork_join(g["prefix"], [g["branch"]] * g["n_branch"], g["join"])
+    tok_start, pos_start = orc.node_tables(L, anc)
+    assert pos_start[0] == 0
+    assert all(pos_start[1 + b] == g["branch_start"] for b in range(g["n_branch"]))
+    assert pos_start[-1] == g["join_start"]
+    _, pos = orc.token_meta(L, anc)
+    assert pos[:128].tolist() == list(range(128))
+    assert pos[-64:].tolist() == list(range(192, 256))
+
+
+@pytest.mark.parametrize("lens", [[5, 3, 9, 1], [7, 7, 7], [1, 20, 4, 4, 2]])
+def test_positions_fork_join_closed_form(lens):
+    prefix, branches, join = lens[0], lens[1:-1], lens[-1]
+    L, anc = dags.fork_join(prefix, branches, join)
+    _, pos_start = orc.node_tables(L, anc)
+    assert all(pos_start[1 + b] == prefix for b in range(len(branches)))
+    assert pos_start[-1] == prefix + max(branches)
+
+
+def test_positions_linear_chain_is_arange():
+    L, anc = dags.linear_chain([3, 1, 5, 2, 8])
+    tok_node, pos = orc.token_meta(L, anc)
+    assert pos.tolist() == list(range(19))
+    assert tok_node.tolist() == [0] * 3 + [1] + [2] * 5 + [3] * 2 + [4] * 8
+
+
+def test_skip_level_discriminates_the_two_mask_readings():
+    g = GOLDEN["skip_level"]
+    L, anc = _dag_from_parents(g["node_len"], g["parents"])
+    _, pos = orc.token_meta(L, anc)
+    m = orc.explicit_mask(L, anc)
+    assert np.flatnonzero(m[5]).tolist() == g["ancestor_reading"]["row_of_D"]
+    assert pos.tolist() == g["ancestor_reading"]["pos_ids"]
+    anc_layer = dags.layerwise_bits(g["levels"])
+    _, pos2 = orc.token_meta(L, anc_layer)
+    m2 = orc.explicit_mask(L, anc_layer)
+    assert np.flatnonzero(m2[5]).tolist() == g["layer_reading"]["row_of_D"]
+    assert pos2.tolist() == g["layer_reading"]["pos_ids"]
+    # literal Eq. 3 on the layer reading: masked iff j > i, or same layer and different step
+    lev = np.repeat(g["levels"], g["node_len"])
+    node = np.repeat(np.arange(4), g["node_len"])
+    for i in range(6):
+        for j in range(6):
+            masked = (j > i) or (lev[i] == lev[j] and node[i] != node[j])
+            assert m2[i, j] == (not masked)
+
+
+# ------------------------------------------------------------------ mask (Eq. 3)
+def test_mask_diamond_golden():
+    g = GOLDEN["diamond"]
+    L, anc = _dag_from_parents(g["node_len"], g["parents"])
+    m = orc.explicit_mask(L, anc)
+    for i, allowed in enumerate(g["allowed"]):
+        assert np.flatnonzero(m[i]).tolist() == allowed
+    assert orc.useful_pairs(L, anc) == g["useful_pairs"]
+
+
+def _closed_form_pairs(L, anc):
+    sets = dags.sets_from_bits(anc)
+    total = 0
+    for v, lv in enumerate(L):
+        total += int(lv) * sum(int(L[u]) for u in sets[v] if u != v) + int(lv) * (int(lv) + 1) // 2
+    return total
+
+
+def test_mask_counts_closed_form():
+    L, anc = dags.fork_join(128, [64] * 4, 64)
+    assert orc.useful_pairs(L, anc) == 76000 == _closed_form_pairs(L, anc)
+    L, anc = dags.fork_join(2048, [256] * 8, 512)
+    assert orc.useful_pairs(L, anc) == 8784128 == _closed_form_pairs(L, anc)
+    rng = np.random.Generator(np.random.PCG64(7))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=20, depth=4, len_lo=1, len_hi=9)
+    assert orc.useful_pairs(L, anc) == _closed_form_pairs(L, anc)
+
+
+def test_mask_linear_chain_is_lower_triangular():
+    L, anc = dags.linear_chain([4, 1, 6])
+    assert np.array_equal(orc.explicit_mask(L, anc), np.tril(np.ones((11, 11), dtype=bool)))
+
+
+def test_mask_rows_have_self_and_no_future():
+    rng = np.random.Generator(np.random.PCG64(11))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=30, depth=5, len_lo=1, len_hi=7)
+    m = orc.explicit_mask(L, anc)
+    assert m.diagonal().all()
+    assert not np.triu(m, 1).any()
+
+
+# ------------------------------------------------------------------ block map
+def test_block_map_diamond_golden():
+    g = GOLDEN["diamond"]
+    L, anc = _dag_from_parents(g["node_len"], g["parents"])
+    bm = orc.block_map(L, anc, *g["tile"])
+    assert bm.tolist() == g["block_map"]
+    rp, col, flag = orc.block_map_csr(bm)
+    assert rp.tolist() == [0, 1, 3, 6, 10]
+    assert col.tolist() == [0, 0, 1, 0, 1, 2, 0, 1, 2, 3]
+    assert flag.tolist() == [1, 2, 1, 2, 1, 1, 2, 2, 2, 2]
+
+
+def test_block_map_config2_census():
+    # 128x128 tiles: prefix 16 tiles, 8 branches of 2 tiles, join 4 tiles (36 tiles a side).
+    # By hand: FULL = prefix below-diagonal 120 + branches x prefix 256 + in-branch 8
+    #                 + join x (prefix+branches) 128 + in-join 6 = 518; PARTIAL = 36 diagonal tiles.
+    L, anc = dags.fork_join(2048, [256] * 8, 512)
+    bm = orc.block_map(L, anc, 128, 128)
+    assert bm.shape == (36, 36)
+    assert int((bm == orc.FULL).sum()) == 518
+    assert int((bm == orc.PARTIAL).sum()) == 36
+    assert 518 * 16384 + 36 * 8256 == 8784128
+
+
+def test_block_map_consistent_with_mask_on_ragged_random_dag():
+    rng = np.random.Generator(np.random.PCG64(5))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=12, depth=4, len_lo=1, len_hi=11)
+    m = orc.explicit_mask(L, anc)
+    T = m.shape[0]
+    for tm, tn in [(4, 8), (8, 4), (5, 3)]:
+        bm = orc.block_map(L, anc, tm, tn)
+        cover = np.zeros_like(m)
+        for a in range(bm.shape[0]):
+            for b in range(bm.shape[1]):
+                sub = m[a * tm:(a + 1) * tm, b * tn:(b + 1) * tn]
+                if bm[a, b] == orc.FULL:
+                    assert sub.all()
+                    cover[a * tm:(a + 1) * tm, b * tn:(b + 1) * tn] = True
+                elif bm[a, b] == orc.SKIP:
+                    assert not sub.any()
+                else:
+                    assert sub.any() and not sub.all()
+                    cover[a * tm:(a + 1) * tm, b * tn:(b + 1) * tn] = True
+        assert not (m & ~cover).any()
+        assert bm.shape == (-(-T // tm), -(-T // tn))
+
+
+# ------------------------------------------------------------------ rotary embedding
+def test_rope_closed_forms():
+    # D = 2: one pair, frequency 1: (1, 0) at position p -> (cos p, sin p); (0, 1) -> (-sin p, cos p)
+    for p in [0, 1, 5, 1000]:
+        out = orc.rope(np.array([[[1.0, 0.0]], [[0.0, 1.0]]]), [p, p], 10000.0)
+        assert np.allclose(out[0, 0], [np.cos(p), np.sin(p)], atol=1e-12)
+        assert np.allclose(out[1, 0], [-np.sin(p), np.cos(p)], atol=1e-12)
+    # D = 4, theta = 10000: pair m = 1 is (x[1], x[3]) and rotates at frequency 10000^(-1/2) = 0.01
+    x = np.zeros((1, 1, 4))
+    x[0, 0, 1] = 1.0
+    out = orc.rope(x, [7], 10000.0)
+    assert np.allclose(out[0, 0], [0.0, np.cos(0.07), 0.0, np.sin(0.07)], atol=1e-12)
+    # D = 8, theta = 16: frequencies 16^(-m/4) = 1, 1/2, 1/4, 1/8
+    x = np.zeros((1, 1, 8))
+    x[0, 0, 7] = 2.0                          # second element of pair m = 3
+    out = orc.rope(x, [4], 16.0)
+    assert np.allclose(out[0, 0, 3], -2.0 * np.sin(0.5), atol=1e-12)
+    assert np.allclose(out[0, 0, 7], 2.0 * np.cos(0.5), atol=1e-12)
+
+
+def test_rope_identity_norm_and_relative_property():
+    x = _rand(1, 6, 3, 16)
+    assert np.allclose(orc.rope(x, np.zeros(6), 1e4), x)
+    pos = np.array([0, 3, 17, 17, 250, 40000])
+    y = orc.rope(x, pos, 5e5)
+    assert np.allclose((y ** 2).sum(-1), (x ** 2).sum(-1), rtol=1e-12)
+    # <rope(a, p1), rope(b, p2)> depends only on p1 - p2
+    a, b = _rand(2, 1, 1, 16), _rand(3, 1, 1, 16)
+    d1 = (orc.rope(a, [10], 1e4) * orc.rope(b, [3], 1e4)).sum()
+    d2 = (orc.rope(a, [1010], 1e4) * orc.rope(b, [1003], 1e4)).sum()
+    assert abs(d1 - d2) < 1e-9
+
+
+# ------------------------------------------------------------------ attention values
+def test_linear_chain_equals_library_causal_attention():
+    T, H, D = 37, 3, 16
+    L, anc = dags.linear_chain([10, 1, 20, 6])
+    q, k, v = _rand(4, T, H, D), _rand(5, T, H, D), _rand(6, T, H, D)
+    scale = 0.3
+    O, lse = orc.attn_prefill(q, k, v, L, anc, scale=scale, row_block=8)
+    ref = _sdpa_causal(q, k, v, scale)
+    assert np.abs(O - ref).max() < 1e-12
+    # lse against the definition log sum exp over the visible prefix
+    s = (q[20, 1] @ k[:21, 1].T) * scale
+    assert abs(lse[20, 1] - np.log(np.exp(s).sum())) < 1e-12
+
+
+def test_gqa_head_mapping_against_library():
+    T, Hq, Hkv, D = 19, 6, 2, 8
+    L, anc = dags.linear_chain([19])
+    q, k, v = _rand(7, T, Hq, D), _rand(8, T, Hkv, D), _rand(9, T, Hkv, D)
+    O, _ = orc.attn_prefill(q, k, v, L, anc)
+    kk = np.repeat(k, Hq // Hkv, axis=1)          # query head h -> kv head h // G
+    vv = np.repeat(v, Hq // Hkv, axis=1)
+    assert np.abs(O - _sdpa_causal(q, kk, vv, 1.0 / np.sqrt(D))).max() < 1e-12
+
+
+def test_fork_join_equals_causal_attention_on_each_path():
+    """Fork: a branch inherits exactly the prefix context (sections 3.3, 4.3); a branch token's
+    output equals plain causal attention with ordinary positions over [prefix, that branch].
+    Join: sees prefix and all branches; equals causal attention over the whole concatenation with
+    the adaptive rotation applied beforehand."""
+    prefix, branches, join = 9, [5, 7, 3], 4
+    L, anc = dags.fork_join(prefix, branches, join)
+    T, H, D, theta = int(L.sum()), 2, 8, 100.0
+    q, k, v = _rand(10, T, H, D), _rand(11, T, H, D), _rand(12, T, H, D)
+    _, pos = orc.token_meta(L, anc)
+    qr, kr = orc.rope(q, pos, theta), orc.rope(k, pos, theta)
+    O, _ = orc.attn_prefill(qr, kr, v, L, anc)
+    scale = 1.0 / np.sqrt(D)
+    start = prefix
+    for bl in branches:
+        idx = np.r_[0:prefix, start:start + bl]
+        ordinary = np.arange(len(idx))
+        ref = _sdpa_causal(orc.rope(q[idx], ordinary, theta), orc.rope(k[idx], ordinary, theta),
+                           v[idx], scale)
+        assert np.abs(O[idx] - ref).max() < 1e-12
+        start += bl
+    ref = _sdpa_causal(qr, kr, v, scale)
+    assert np.abs(O[-join:] - ref[-join:]).max() < 1e-12
+    # and the branches really are isolated: a middle-branch token differs from full causal
+    assert np.abs(O[prefix + branches[0] + 1] - ref[prefix + branches[0] + 1]).max() > 1e-6
+
+
+def test_sibling_order_permutation_invariance():
+    prefix, branches, join = 6, [4, 7, 2], 5
+    L, anc = dags.fork_join(prefix, branches, join)
+    T, H, D, theta = int(L.sum()), 2, 8, 1e4
+    q, k, v = _rand(13, T, H, D), _rand(14, T, H, D), _rand(15, T, H, D)
+    _, pos = orc.token_meta(L, anc)
+    O, _ = orc.attn_prefill(orc.rope(q, pos, theta), orc.rope(k, pos, theta), v, L, anc)
+    order = [2, 0, 1]
+    starts = np.cumsum([prefix] + branches)
+    blocks = [np.arange(starts[b], starts[b] + branches[b]) for b in range(3)]
+    perm = np.concatenate([np.arange(prefix)] + [blocks[b] for b in order] + [np.arange(T - join, T)])
+    L2, anc2 = dags.fork_join(prefix, [branches[b] for b in order], join)
+    _, pos2 = orc.token_meta(L2, anc2)
+    O2, _ = orc.attn_prefill(orc.rope(q[perm], pos2, theta), orc.rope(k[perm], pos2, theta),
+                             v[perm], L2, anc2)
+    assert np.abs(O2 - O[perm]).max() < 1e-12
+
+
+def test_value_probes_ones_and_one_hot_nodes():
+    rng = np.random.Generator(np.random.PCG64(21))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=10, depth=4, len_lo=1, len_hi=6)
+    T, N = int(L.sum()), len(L)
+    q, k = _rand(16, T, 2, 8), _rand(17, T, 1, 8)
+    O, _ = orc.attn_prefill(q, k, np.ones((T, 1, 8)), L, anc)
+    assert np.abs(O - 1.0).max() < 1e-12
+    tok_node, _ = orc.token_meta(L, anc)
+    onehot = np.zeros((T, 1, N))
+    onehot[np.arange(T), 0, tok_node] = 1.0
+    kk = _rand(18, T, 1, N)
+    qq = _rand(19, T, 2, N)
+    M, _ = orc.attn_prefill(qq, kk, onehot, L, anc)   # M[i, h, c] = attention mass on node c
+    sets = dags.sets_from_bits(anc)
+    for i in range(T):
+        vi = int(tok_node[i])
+        for c in range(N):
+            if c != vi and c not in sets[vi]:
+                assert M[i, 0, c] == 0.0 and M[i, 1, c] == 0.0
+        assert abs(M[i, 0].sum() - 1.0) < 1e-12
+
+
+def test_position_shift_invariance():
+    L, anc = dags.fork_join(5, [3, 4], 2)
+    T = int(L.sum())
+    q, k, v = _rand(22, T, 2, 8), _rand(23, T, 2, 8), _rand(24, T, 2, 8)
+    _, pos = orc.token_meta(L, anc)
+    O1, _ = orc.attn_prefill(orc.rope(q, pos, 1e4), orc.rope(k, pos, 1e4), v, L, anc)
+    O2, _ = orc.attn_prefill(orc.rope(q, pos + 777, 1e4), orc.rope(k, pos + 777, 1e4), v, L, anc)
+    assert np.abs(O1 - O2).max() < 1e-9
+
+
+def test_rows_and_heads_subset_matches_full():
+    L, anc = dags.fork_join(6, [3, 3], 4)
+    T = int(L.sum())
+    q, k, v = _rand(25, T, 4, 8), _rand(26, T, 2, 8), _rand(27, T, 2, 8)
+    O, lse = orc.attn_prefill(q, k, v, L, anc)
+    Os, lses = orc.attn_prefill(q, k, v, L, anc, rows=[2, 9, 15], heads=[1, 3])
+    assert np.array_equal(Os[[2, 9, 15]][:, [1, 3]], O[[2, 9, 15]][:, [1, 3]])
+    assert np.isnan(Os[0]).all() and np.isnan(Os[2, 0]).all()
+
+
+# ------------------------------------------------------------------ paged KV and decode
+def _decode_fixture(seed=31, shared=40, blens=(17, 5, 32), hq=4, hkv=2, d=16):
+    st = dags.decode_state(seed, n_seqs=1, n_branches=len(blens), shared_len=shared, branch_len=0,
+                           hq=hq, hkv=hkv, d=d, dtype=torch.float64, branch_len_list=list(blens))
+    return st
+
+
+def test_pool_formats_against_independent_packing():
+    n_pages, hkv, d = 3, 2, 16
+    k_tok = torch.from_numpy(_rand(32, n_pages * 16, hkv, d))
+    v_tok = torch.from_numpy(_rand(33, n_pages * 16, hkv, d))
+    kp, vp = dags.pack_k_pages(k_tok).numpy(), dags.pack_v_pages(v_tok).numpy()
+    for t in [0, 1, 15, 16, 37, 47]:
+        for h in range(hkv):
+            assert np.array_equal(orc.pool_get_k(kp, t // 16, h, t % 16), k_tok[t, h].numpy())
+            assert np.array_equal(orc.pool_get_v(vp, t // 16, h, t % 16), v_tok[t, h].numpy())
+
+
+def test_decode_equals_last_row_of_prefill():
+    shared, blens, hq, hkv, d = 40, (17, 5, 32), 4, 2, 16
+    st = _decode_fixture(shared=shared, blens=blens, hq=hq, hkv=hkv, d=d)
+    desc, kp, vp = st["desc"], st["k_pool"].numpy(), st["v_pool"].numpy()
+    qd = st["q"].numpy()
+    Od = orc.attn_decode(desc, qd, kp, vp)
+    for r, bl in enumerate(blens):
+        K = np.stack([orc.gather_context(desc, r, h, kp, vp)[0] for h in range(hkv)], axis=1)
+        V = np.stack([orc.gather_context(desc, r, h, kp, vp)[1] for h in range(hkv)], axis=1)
+        T = shared + bl
+        assert K.shape == (T, hkv, d)
+        L, anc = dags.linear_chain([T])
+        q = np.zeros((T, hq, d))
+        q[-1] = qd[r]
+        O, _ = orc.attn_prefill(q, K, V, L, anc)
+        assert np.abs(O[-1] - Od[r]).max() < 1e-12
+
+
+def test_decode_siblings_share_prefix_pages_and_own_the_rest():
+    st = _decode_fixture()
+    desc = st["desc"]
+    kp, vp = st["k_pool"].numpy(), st["v_pool"].numpy()
+    K0, _ = orc.gather_context(desc, 0, 0, kp, vp)
+    K1, _ = orc.gather_context(desc, 1, 0, kp, vp)
+    assert np.array_equal(K0[:40], K1[:40])
+    assert K0.shape[0] == 40 + 17 and K1.shape[0] == 40 + 5
+    # first shared token comes from the first shared page, slot 0
+    p0 = int(desc["shared_pages"][0])
+    assert np.array_equal(K0[0], kp[p0, 0, :, 0, :].reshape(-1))
+    # last own token of branch 0 (index 16) sits in its second own page, slot 0
+    pb = int(desc["branch_pages"][int(desc["branch_page_off"][0]) + 1])
+    assert np.array_equal(K0[-1], kp[pb, 0, :, 0, :].reshape(-1))
+
+
+def test_lse_merge_any_partition_equals_unsplit():
+    K, V, q = _rand(34, 50, 8), _rand(35, 50, 8), _rand(36, 8)
+    s = (K @ q) * 0.4
+    p = np.exp(s - s.max())
+    ref = (p @ V) / p.sum()
+    for cuts in [[0, 50], [0, 1, 50], [0, 16, 32, 48, 50], [0, 7, 8, 30, 50]]:
+        parts = [orc.partial_attention(q, K[a:b], V[a:b], 0.4) for a, b in zip(cuts[:-1], cuts[1:])]
+        assert np.abs(orc.lse_merge(parts) - ref).max() < 1e-12
+
+
+def test_kv_append_places_rotated_key_in_tail_slot():
+    st = _decode_fixture(blens=(17, 5, 32))
+    desc = st["desc"]
+    kp, vp = st["k_pool"].numpy().copy(), st["v_pool"].numpy().copy()
+    before_k = kp.copy()
+    k_new, v_new = st["k_new"].numpy(), st["v_new"].numpy()
+    orc.kv_append_rope(desc, k_new, v_new, kp, vp, theta=1e4)
+    changed = np.argwhere(np.abs(kp - before_k).sum(axis=(1, 2, 4)) > 0)   # (page, slot)
+    # exactly one (page, slot) per live branch
+    assert len(changed) == 3
+    for r, bl in enumerate((17, 5, 32)):
+        K, V = orc.gather_context(desc, r, 1, kp, vp)
+        pos = int(desc["branch_pos"][r])
+        assert pos == 40 + bl - 1
+        expect = orc.rope(k_new[r:r + 1], [pos], 1e4)[0, 1]
+        assert np.abs(K[-1] - expect).max() < 1e-15
+        assert np.array_equal(V[-1], v_new[r, 1])

@@ -1,0 +1,276 @@
+"""Seeded synthetic inputs shared by the tests, the benchmark and the smoke check.
+
+This module only *builds inputs*: DAG node tables (lengths + ancestor bitsets), random Q/K/V
+values, page tables and the storage packing of the paged KV pools.  It contains none of the
+attention method's arithmetic (no positions, masks, rotary embedding, softmax) and imports neither
+the GPU library nor the CPU oracle.
+
+The DAG shapes stand in for the topologies the paper reports (Table 3: a single linear chain,
+multiple independent chains = fork/join, complex intersecting = multi-level DAG with joins); the
+paper's own dataset is not used.
+"""
+import numpy as np
+import torch
+
+SEED0 = 260207529
+PAGE = 16
+
+
+# ----------------------------------------------------------------------------- DAG node tables
+def words_for(n_nodes):
+    return max(1, (n_nodes + 63) // 64)
+
+
+def bits_from_sets(anc_sets, n_words=None):
+    """anc_sets: list of iterables of ancestor ids -> uint64 [N][W]."""
+    n = len(anc_sets)
+    W = words_for(n) if n_words is None else n_words
+    out = np.zeros((n, W), dtype=np.uint64)
+    for v, s in enumerate(anc_sets):
+        for u in s:
+            out[v, u >> 6] |= np.uint64(1) << np.uint64(u & 63)
+    return out
+
+
+def sets_from_bits(anc):
+    n = anc.shape[0]
+    return [{u for u in range(n) if (int(anc[v, u >> 6]) >> (u & 63)) & 1} for v in range(n)]
+
+
+def closure_from_parents(parents):
+    """parents[v] = iterable of direct predecessors (< v).  Returns transitive ancestor sets."""
+    anc = []
+    for v, ps in enumerate(parents):
+        s = set()
+        for p in ps:
+            assert p < v
+            s.add(p)
+            s |= anc[p]
+        anc.append(s)
+    return anc
+
+
+def linear_chain(lengths):
+    """Single chain: node v depends on v-1."""
+    parents = [[] if v == 0 else [v - 1] for v in range(len(lengths))]
+    return np.asarray(lengths, dtype=np.int32), bits_from_sets(closure_from_parents(parents))
+
+
+def fork_join(prefix_len, branch_lens, join_len=None):
+    """prefix -> len(branch_lens) sibling branches -> (optional) one join node."""
+    lens = [prefix_len] + list(branch_lens)
+    parents = [[]] + [[0] for _ in branch_lens]
+    if join_len is not None:
+        lens.append(join_len)
+        parents.append(list(range(1, 1 + len(branch_lens))))
+    return np.asarray(lens, dtype=np.int32), bits_from_sets(closure_from_parents(parents))
+
+
+def random_dag(rng, n_nodes=64, depth=6, fan_lo=1, fan_hi=4, join_prob=0.3,
+               len_lo=32, len_hi=256):
+    """Multi-level DAG: `depth` levels, exactly `n_nodes` nodes, fan-out U{fan_lo..fan_hi} per
+    node, nodes at level >= 2 become joins of 2-3 parents with probability join_prob.
+    Node ids are assigned level by level, so they are a topological order.
+    Returns (node_len int32[N], anc uint64[N][W], parents list, level list).
+    """
+    while True:
+        levels = [[0]]
+        parents = [[]]
+        nxt = 1
+        ok = True
+        for lv in range(1, depth):
+            remaining_levels = depth - 1 - lv          # levels still to come after this one
+            budget = n_nodes - nxt - remaining_levels  # nodes this level may take at most
+            if budget < 1:
+                ok = False
+                break
+            # keep the level sizes balanced: at most twice an even share of what is left
+            budget = min(budget, 2 * -(-(n_nodes - nxt) // (remaining_levels + 1)))
+            cur = []
+            for p in levels[lv - 1]:
+                f = int(rng.integers(fan_lo, fan_hi + 1))
+                for _ in range(f):
+                    if len(cur) < budget:
+                        parents.append([p])
+                        cur.append(nxt)
+                        nxt += 1
+            if lv == depth - 1:
+                # last level absorbs what is left so that the node count is exact
+                while nxt < n_nodes:
+                    p = levels[lv - 1][int(rng.integers(0, len(levels[lv - 1])))]
+                    parents.append([p])
+                    cur.append(nxt)
+                    nxt += 1
+            if not cur:
+                ok = False
+                break
+            levels.append(cur)
+        if ok and nxt == n_nodes and len(levels) == depth:
+            break
+    level_of = [0] * n_nodes
+    for lv, ids in enumerate(levels):
+        for v in ids:
+            level_of[v] = lv
+    for lv in range(2, depth):
+        prev = levels[lv - 1]
+        for v in levels[lv]:
+            if len(prev) >= 2 and rng.random() < join_prob:
+                extra = int(rng.integers(1, 3))
+                cand = [p for p in prev if p not in parents[v]]
+                rng.shuffle(cand)
+                parents[v] = sorted(parents[v] + cand[:extra])
+    anc = closure_from_parents(parents)
+    lens = rng.integers(len_lo, len_hi + 1, size=n_nodes).astype(np.int32)
+    return lens, bits_from_sets(anc), parents, level_of
+
+
+def layerwise_bits(level_of):
+    """Ancestor bitsets of the literal layer-wise mask: every node of an earlier layer is visible."""
+    n = len(level_of)
+    return bits_from_sets([{u for u in range(v) if level_of[u] < level_of[v]} for v in range(n)])
+
+
+def batch_desc(dags):
+    """Concatenate per-sequence (node_len, anc) pairs into the batched host description."""
+    n_seqs = len(dags)
+    W = max(a.shape[1] for _, a in dags)
+    node_offsets = np.zeros(n_seqs + 1, dtype=np.int32)
+    lens, bits = [], []
+    for b, (l, a) in enumerate(dags):
+        node_offsets[b + 1] = node_offsets[b] + len(l)
+        lens.append(np.asarray(l, dtype=np.int32))
+        aa = np.zeros((a.shape[0], W), dtype=np.uint64)
+        aa[:, :a.shape[1]] = a
+        bits.append(aa)
+    return node_offsets, np.concatenate(lens), np.concatenate(bits, axis=0), W
+
+
+# ----------------------------------------------------------------------------- values
+def normal_tensor(rng, shape, scale, dtype):
+    """Standard normal fp32 * scale, rounded once (RNE) to `dtype` (torch.float32 / bfloat16)."""
+    x = rng.standard_normal(size=shape, dtype=np.float32) * np.float32(scale)
+    return torch.from_numpy(x).to(dtype)
+
+
+def make_qkv(seed, T, hq, hkv, d, scale, dtype):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q = normal_tensor(rng, (T, hq, d), scale, dtype)
+    k = normal_tensor(rng, (T, hkv, d), scale, dtype)
+    v = normal_tensor(rng, (T, hkv, d), scale, dtype)
+    return q, k, v
+
+
+def to_f64(t):
+    """Exact upcast of a torch tensor (fp32 / bf16) to a numpy fp64 array."""
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+# ----------------------------------------------------------------------------- paged KV storage
+def pack_k_pages(k_tok):
+    """k_tok [n_pages*16][Hkv][D] (token-major) -> K pool format [n_pages][Hkv][D/8][16][8]."""
+    n, hkv, d = k_tok.shape
+    assert n % PAGE == 0 and d % 8 == 0
+    x = k_tok.reshape(n // PAGE, PAGE, hkv, d // 8, 8)
+    return x.permute(0, 2, 3, 1, 4).contiguous()
+
+
+def pack_v_pages(v_tok):
+    """v_tok [n_pages*16][Hkv][D] -> V pool format [n_pages][Hkv][D][16]."""
+    n, hkv, d = v_tok.shape
+    assert n % PAGE == 0
+    x = v_tok.reshape(n // PAGE, PAGE, hkv, d)
+    return x.permute(0, 2, 3, 1).contiguous()
+
+
+def decode_state(seed, n_seqs, n_branches, shared_len, branch_len, hq, hkv, d,
+                 kv_scale=1.0, q_scale=1.0, dtype=torch.bfloat16, spare_pages=0,
+                 branch_len_list=None):
+    """Branch-parallel decode state: every sequence is one sibling group whose `n_branches`
+    live branches share `shared_len` context tokens and own `branch_len` tokens each (the
+    last own token is the one being decoded).  Page ids are a seeded random permutation of the
+    pool, so pages are non-contiguous.  `branch_len_list` (length n_seqs*n_branches) overrides
+    the per-branch own length.  Pools are filled with N(0,1)*kv_scale directly in pool format.
+    Returns a dict with the pools, q, and the int32 description arrays (numpy).
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n_live = n_seqs * n_branches
+    if branch_len_list is None:
+        branch_len_list = [branch_len] * n_live
+    blens = np.asarray(branch_len_list, dtype=np.int32)
+    shared_pages_per = (shared_len + PAGE - 1) // PAGE
+    bpages = (blens + PAGE - 1) // PAGE
+    n_pages = n_seqs * shared_pages_per + int(bpages.sum()) + spare_pages
+    perm = rng.permutation(n_pages).astype(np.int32)
+    cur = 0
+    group_branch_off = np.arange(0, n_live + 1, n_branches, dtype=np.int32)
+    shared_page_off = np.zeros(n_seqs + 1, dtype=np.int32)
+    shared_pages = []
+    for g in range(n_seqs):
+        shared_pages.append(perm[cur:cur + shared_pages_per])
+        cur += shared_pages_per
+        shared_page_off[g + 1] = shared_page_off[g] + shared_pages_per
+    branch_page_off = np.zeros(n_live + 1, dtype=np.int32)
+    branch_pages = []
+    for r in range(n_live):
+        branch_pages.append(perm[cur:cur + bpages[r]])
+        cur += int(bpages[r])
+        branch_page_off[r + 1] = branch_page_off[r] + bpages[r]
+    k_pool = normal_tensor(rng, (n_pages, hkv, d // 8, PAGE, 8), kv_scale, dtype)
+    v_pool = normal_tensor(rng, (n_pages, hkv, d, PAGE), kv_scale, dtype)
+    q = normal_tensor(rng, (n_live, hq, d), q_scale, dtype)
+    k_new = normal_tensor(rng, (n_live, hkv, d), kv_scale, dtype)
+    v_new = normal_tensor(rng, (n_live, hkv, d), kv_scale, dtype)
+    desc = dict(
+        n_groups=n_seqs, n_live=n_live, page_size=PAGE,
+        group_branch_off=group_branch_off,
+        shared_page_off=shared_page_off,
+        shared_pages=np.concatenate(shared_pages).astype(np.int32) if shared_pages_per else np.zeros(0, np.int32),
+        shared_len=np.full(n_seqs, shared_len, dtype=np.int32),
+        branch_page_off=branch_page_off,
+        branch_pages=np.concatenate(branch_pages).astype(np.int32),
+        branch_len=blens,
+        branch_pos=(shared_len + blens - 1).astype(np.int32),
+    )
+    return dict(desc=desc, k_pool=k_pool, v_pool=v_pool, q=q, k_new=k_new, v_new=v_new,
+                n_pages=n_pages)
+
+
+def decode_algorithmic_bytes(desc, hkv, d, elem_bytes=2):
+    """Bytes one decode step must read: every shared page once per sibling group plus every
+    branch's own tokens, K and V."""
+    toks = int(np.sum(desc["shared_len"])) + int(np.sum(desc["branch_len"]))
+    return toks * hkv * d * 2 * elem_bytes
+
+
+# ----------------------------------------------------------------------------- the five configs
+def config(idx):
+    """Shapes of the five benchmark configurations (index 0..4)."""
+    cfgs = [
+        dict(name="tiny_fork_join_f32", kind="prefill", batch=1, prefix=128, n_branch=4, branch=64,
+             join=64, hq=4, hkv=4, d=64, scale=1.0, theta=10000.0, dtype="f32"),
+        dict(name="llama3_8b_prefill_bf16", kind="prefill", batch=4, prefix=2048, n_branch=8,
+             branch=256, join=512, hq=32, hkv=8, d=128, scale=0.5, theta=500000.0, dtype="bf16"),
+        dict(name="branch_decode_bf16", kind="decode", n_seqs=16, n_branch=8, shared=8192,
+             branch=1024, hq=32, hkv=8, d=128, scale=1.0, theta=500000.0, dtype="bf16"),
+        dict(name="random_dag_prefill_bf16", kind="prefill_random", batch=8, n_nodes=64, depth=6,
+             hq=32, hkv=8, d=128, scale=0.5, theta=500000.0, dtype="bf16"),
+        dict(name="qwen32b_long_bf16", kind="prefill+decode", batch=2, prefix=32768, n_branch=32,
+             branch=512, join=1024, decode_steps=256, hq=40, hkv=8, d=128, scale=0.5,
+             theta=1000000.0, dtype="bf16"),
+    ]
+    c = dict(cfgs[idx])
+    c["seed"] = SEED0 + idx
+    return c
+
+
+def config_dags(c):
+    """List of per-sequence (node_len, anc) for a prefill-type config."""
+    if c["kind"] == "prefill_random":
+        rng = np.random.Generator(np.random.PCG64(c["seed"]))
+        out = []
+        for _ in range(c["batch"]):
+            lens, anc, _, _ = random_dag(rng, c["n_nodes"], c["depth"])
+            out.append((lens, anc))
+        return out
+    one = fork_join(c["prefix"], [c["branch"]] * c["n_branch"], c["join"])
+    return [one for _ in range(c["batch"])]
