@@ -1,0 +1,192 @@
+/*
+ * dagattn -- DAG-structured attention for AMD MI355X (gfx950).  C ABI.
+ *
+ * The operation is the attention of MedVerse (arXiv 2602.07529), section 4.2: a token sequence is
+ * organised as a DAG of reasoning nodes (the places of the Petri net of section 3.2); a token
+ * attends causally inside its own node and fully to every ancestor node (Eq. 3 in its
+ * ancestor-closure form, i.e. the Fork/Join semantics of sections 3.3 and 4.3), and carries an
+ * adaptive position index (section 4.2, "Adaptive Position Indices"): sibling branches restart at
+ * their fork point and a join resumes one past the largest position of its predecessors.
+ *
+ * General conventions
+ *   - Every function returns DAG_OK (0) or a negative dag_status_t; dag_strerror() names it.
+ *   - "HOST" pointers are read synchronously during the call.  "DEVICE" pointers are caller-owned
+ *     GPU memory (for instance torch tensors); the library never allocates or frees device memory,
+ *     scratch comes from a caller-provided workspace.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All GPU work is
+ *     enqueued on it and the call returns without synchronising.  Host-side validation happens
+ *     before anything is enqueued; on a validation error no GPU work has been submitted.
+ *   - Tensors are token-major packed variable-length: q [T][Hq][D], k/v [T][Hkv][D], contiguous,
+ *     16-byte aligned.  Sequences are concatenated; tokens of a sequence are stored node after
+ *     node in node-id order and node ids must be a topological order of the DAG.
+ *   - No global state; calls on different streams may overlap if their buffers do not.
+ */
+#ifndef DAGATTN_H
+#define DAGATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DAG_PAGE_SIZE 16
+
+typedef enum {
+  DAG_OK = 0,
+  DAG_ERR_NULL = -1,            /* a required pointer is NULL                                   */
+  DAG_ERR_BAD_LEN = -2,         /* a node length < 1, a negative count, or an inconsistent size  */
+  DAG_ERR_NOT_TOPOLOGICAL = -3, /* ancestor bit u >= v set in row v (also rejects cycles)        */
+  DAG_ERR_NOT_CLOSED = -4,      /* DAG_STRICT_CLOSURE set and the bitsets are not transitive     */
+  DAG_ERR_POS_OVERFLOW = -5,    /* a sequence has more tokens than fit an int32 position         */
+  DAG_ERR_WORKSPACE = -6,       /* workspace missing or too small                                */
+  DAG_ERR_UNSUPPORTED = -7,     /* head_dim / head counts / page size / tile shape not supported */
+  DAG_ERR_ALIGN = -8,           /* a tensor pointer is not 16-byte aligned                       */
+  DAG_ERR_HIP = -9              /* the HIP runtime reported an error at launch                   */
+} dag_status_t;
+
+typedef enum { DAG_F32 = 0, DAG_BF16 = 1 } dag_dtype_t;
+
+/* dag_desc_t.flags */
+#define DAG_STRICT_CLOSURE 1u /* reject ancestor bitsets that are not transitively closed */
+
+/* Block-map tile classes */
+#define DAG_TILE_SKIP 0
+#define DAG_TILE_PARTIAL 1
+#define DAG_TILE_FULL 2
+
+/* Node table of a batch of DAGs (sections 3.1-3.2: nodes = reasoning states).  HOST memory. */
+typedef struct {
+  int32_t n_seqs;
+  const int32_t* node_offsets; /* [n_seqs+1] prefix sum of node counts                          */
+  const int32_t* node_len;     /* [total_nodes] tokens per node, each >= 1                      */
+  const uint64_t* anc_bits;    /* [total_nodes][words_per_node]; bit u of row v set <=> node u
+                                  (local id within the sequence) is an ancestor of node v.  The
+                                  self bit is ignored.                                           */
+  int32_t words_per_node;      /* >= ceil(max nodes per sequence / 64)                          */
+  int32_t tile_m, tile_n;      /* block-map tile shape; use dag_prefill_tile_shape()            */
+  uint32_t flags;
+} dag_desc_t;
+
+/* Element counts a caller needs to allocate dag_meta_t (all filled by dag_meta_sizes). */
+typedef struct {
+  int64_t total_nodes;
+  int64_t total_tokens;    /* T                                                                */
+  int64_t total_qtiles;    /* sum over sequences of ceil(T_b / tile_m)                         */
+  int64_t total_tiles;     /* sum over sequences of QT_b * KT_b  (bytes of the dense map)      */
+  int64_t csr_capacity;    /* upper bound on the number of non-skip tiles                      */
+  int64_t workspace_bytes; /* device scratch needed by dag_build_meta                          */
+} dag_meta_sizes_t;
+
+/* Derived per-token / per-tile tables.  The struct lives on the HOST; every pointer is DEVICE
+ * memory allocated by the caller with the element counts of dag_meta_sizes_t.  Written by
+ * dag_build_meta, read by dag_rope_qk (pos_ids) and dag_attn_prefill. */
+typedef struct {
+  /* scalars copied from the description / sizes by the caller */
+  int32_t n_seqs, words_per_node, tile_m, tile_n;
+  dag_meta_sizes_t sizes;
+  /* device arrays */
+  int32_t* cu_seqlens;     /* [n_seqs+1] token offset of each sequence                         */
+  int32_t* node_start;     /* [n_seqs+1] device copy of the node offsets                       */
+  int32_t* tok_node;       /* [T] node id (local to the sequence) of every token               */
+  int32_t* pos_ids;        /* [T] adaptive position of every token                             */
+  int32_t* node_tok_start; /* [total_nodes] first token of the node, relative to its sequence  */
+  int32_t* node_pos_start; /* [total_nodes] adaptive position of the node's first token        */
+  uint64_t* node_vis;      /* [total_nodes][words_per_node] ancestors | self                   */
+  int32_t* qtile_start;    /* [n_seqs+1] index of each sequence's first query tile             */
+  int64_t* block_map_off;  /* [n_seqs+1] offset of each sequence's dense map                   */
+  uint8_t* block_map;      /* [total_tiles] per sequence row-major [QT_b][KT_b], DAG_TILE_*    */
+  int32_t* qtile_rowptr;   /* [total_qtiles+1] CSR over non-skip tiles, key tiles ascending    */
+  int32_t* qtile_col;      /* [csr_capacity] key-tile index                                    */
+  uint8_t* qtile_flag;     /* [csr_capacity] DAG_TILE_PARTIAL or DAG_TILE_FULL                 */
+  int32_t* qtile_order;    /* [total_qtiles] query tiles sorted by descending tile count
+                              (ties: ascending index); the prefill launch order                */
+  int64_t* useful_pairs;   /* [n_seqs] number of visible (query, key) pairs                    */
+} dag_meta_t;
+
+/* Tile shape the prefill kernel for this head configuration works on (section 4.2 gives no
+ * kernel; the block map is this library's own device for skipping fully masked tiles).
+ * Output pointers are HOST. */
+int dag_prefill_tile_shape(int32_t hq, int32_t hkv, int32_t head_dim, dag_dtype_t dtype,
+                           int32_t* tile_m, int32_t* tile_n);
+
+/* Sizes of everything dag_build_meta writes.  Host only; validates lengths and counts. */
+int dag_meta_sizes(const dag_desc_t* desc, dag_meta_sizes_t* out);
+
+/* Section 4.2 (Eq. 3 + adaptive position indices): from the node table derive, on the GPU, the
+ * per-token node ids and position ids, the per-node visibility bitsets, the tile-level block map
+ * (dense + CSR), the launch order and the visible-pair counts.  The host validates the DAG first
+ * (lengths >= 1, topological bitsets -- the paper's DAG validity check of its data pipeline,
+ * section 4.1 --, optional closure check) and returns an error before any GPU work is enqueued.
+ * `ws` is DEVICE scratch of at least sizes.workspace_bytes, 16-byte aligned. */
+int dag_build_meta(const dag_desc_t* desc, const dag_meta_t* meta, void* ws, size_t ws_bytes,
+                   void* stream);
+
+/* Eq. 2's position embedding P(i) as rotary embedding at the adaptive positions: rotates q
+ * [n_tokens][hq][head_dim] and k [n_tokens][hkv][head_dim] in place (either may be NULL) by the
+ * angle pos_ids[t] * theta^(-2m/head_dim), pairing elements (m, m + head_dim/2).  All DEVICE.
+ * head_dim must be even and <= 256. */
+int dag_rope_qk(const int32_t* pos_ids, int64_t n_tokens, void* q, void* k, int32_t hq,
+                int32_t hkv, int32_t head_dim, float theta, dag_dtype_t dtype, void* stream);
+
+/* Eq. 2 + Eq. 3: out[i] = sum_j softmax_j(q_i . k_j * softmax_scale + M_ij) v_j, where M is the
+ * DAG mask described by `meta`.  q/out [T][hq][head_dim], k/v [T][hkv][head_dim] DEVICE, already
+ * rotated; lse (nullable) [T][hq] fp32 receives log sum exp of the scaled scores.  Fully masked
+ * tiles are skipped through the block map; only PARTIAL tiles evaluate per-token masks.
+ * Supported: DAG_BF16 with head_dim 64 or 128 (MFMA path, fp32 accumulation); DAG_F32 with
+ * head_dim 64 or 128; hq a multiple of hkv.  meta->tile_m/tile_n must equal
+ * dag_prefill_tile_shape() for the same configuration. */
+int dag_attn_prefill(const dag_meta_t* meta, const void* q, const void* k, const void* v,
+                     void* out, float* lse, int32_t hq, int32_t hkv, int32_t head_dim,
+                     float softmax_scale, dag_dtype_t dtype, void* stream);
+
+/* One decode step over a paged KV cache (section 3.2: a token carries KV-cache indices, not
+ * copies; section 4.3 Fork: sibling branches share the prefix KV without copying).  The struct
+ * lives on the HOST; arrays are DEVICE int32.  A sibling group is a set of live branches that
+ * share one context (list of pages); each live branch additionally owns a page list.
+ * Pool storage formats (bf16, page size 16), P = number of pages:
+ *   K pool [P][hkv][head_dim/8][16][8]   element (page, h, slot, d) at [page][h][d/8][slot][d%8]
+ *   V pool [P][hkv][head_dim][16]        element (page, h, slot, d) at [page][h][d][slot]       */
+typedef struct {
+  int32_t n_groups, n_live, page_size;
+  int32_t max_shared_pages; /* HOST upper bound on pages of any group's shared context          */
+  int32_t max_branch_pages; /* HOST upper bound on pages owned by any live branch               */
+  int32_t max_group_size;   /* HOST upper bound on live branches in any group                   */
+  const int32_t* group_branch_off; /* [n_groups+1] live branches of group g are contiguous     */
+  const int32_t* shared_page_off;  /* [n_groups+1] into shared_pages                           */
+  const int32_t* shared_pages;     /* page ids of the shared contexts, in token order          */
+  const int32_t* shared_len;       /* [n_groups] tokens in the shared context                  */
+  const int32_t* branch_page_off;  /* [n_live+1] into branch_pages                             */
+  const int32_t* branch_pages;     /* page ids owned by each live branch                       */
+  const int32_t* branch_len;       /* [n_live] tokens in own pages, incl. the one being decoded */
+  const int32_t* branch_pos;       /* [n_live] adaptive position of the token being decoded    */
+} dag_decode_desc_t;
+
+/* Section 3.2 ("maps the corresponding memory blocks to k"): store the new token of every live
+ * branch -- key rotated at branch_pos (Eq. 2's P(i)), value as is -- into slot branch_len-1 of
+ * the branch's own page list.  k_new/v_new [n_live][hkv][head_dim] bf16 DEVICE. */
+int dag_kv_append_rope(const dag_decode_desc_t* desc, const void* k_new, const void* v_new,
+                       void* k_pool, void* v_pool, int32_t hkv, int32_t head_dim, float theta,
+                       void* stream);
+
+/* Bytes of DEVICE workspace dag_attn_decode needs for this description (0 on bad arguments). */
+size_t dag_decode_workspace_bytes(const dag_decode_desc_t* desc, int32_t hq, int32_t hkv,
+                                  int32_t head_dim);
+
+/* Attention of every live branch's query over (shared context, own tokens): Eq. 2 without a mask
+ * other than membership.  The shared pages of a group are streamed once for all its siblings
+ * (section 4.3 Fork), own pages once per branch, and the partial results are combined by
+ * log-sum-exp.  q/out [n_live][hq][head_dim] bf16 DEVICE, q already rotated.  head_dim 128 or
+ * 64, page_size 16, hq a multiple of hkv with hq/hkv <= 32. */
+int dag_attn_decode(const dag_decode_desc_t* desc, const void* q, const void* k_pool,
+                    const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
+                    float softmax_scale, void* ws, size_t ws_bytes, void* stream);
+
+const char* dag_strerror(int code);
+int dag_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAGATTN_H */

@@ -1,0 +1,239 @@
+"""ctypes binding of libdagattn.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch is used for device memory and
+for the current stream handle.  There is no CPU fallback: if the library is missing, loading
+raises.  Function names match the C ABI declared in include/dagattn.h.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libdagattn.so")
+
+DAG_F32, DAG_BF16 = 0, 1
+DAG_STRICT_CLOSURE = 1
+TILE_SKIP, TILE_PARTIAL, TILE_FULL = 0, 1, 2
+PAGE = 16
+
+
+class DagError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("dagattn error %d: %s" % (code, msg))
+        self.code = code
+
+
+class dag_desc_t(C.Structure):
+    _fields_ = [("n_seqs", C.c_int32), ("node_offsets", C.c_void_p), ("node_len", C.c_void_p),
+                ("anc_bits", C.c_void_p), ("words_per_node", C.c_int32), ("tile_m", C.c_int32),
+                ("tile_n", C.c_int32), ("flags", C.c_uint32)]
+
+
+class dag_meta_sizes_t(C.Structure):
+    _fields_ = [("total_nodes", C.c_int64), ("total_tokens", C.c_int64), ("total_qtiles", C.c_int64),
+                ("total_tiles", C.c_int64), ("csr_capacity", C.c_int64), ("workspace_bytes", C.c_int64)]
+
+
+_META_ARRAYS = [("cu_seqlens", torch.int32), ("node_start", torch.int32), ("tok_node", torch.int32),
+                ("pos_ids", torch.int32), ("node_tok_start", torch.int32), ("node_pos_start", torch.int32),
+                ("node_vis", torch.int64), ("qtile_start", torch.int32), ("block_map_off", torch.int64),
+                ("block_map", torch.uint8), ("qtile_rowptr", torch.int32), ("qtile_col", torch.int32),
+                ("qtile_flag", torch.uint8), ("qtile_order", torch.int32), ("useful_pairs", torch.int64)]
+
+
+class dag_meta_t(C.Structure):
+    _fields_ = ([("n_seqs", C.c_int32), ("words_per_node", C.c_int32), ("tile_m", C.c_int32),
+                 ("tile_n", C.c_int32), ("sizes", dag_meta_sizes_t)] +
+                [(name, C.c_void_p) for name, _ in _META_ARRAYS])
+
+
+class dag_decode_desc_t(C.Structure):
+    _fields_ = [("n_groups", C.c_int32), ("n_live", C.c_int32), ("page_size", C.c_int32),
+                ("max_shared_pages", C.c_int32), ("max_branch_pages", C.c_int32),
+                ("max_group_size", C.c_int32),
+                ("group_branch_off", C.c_void_p), ("shared_page_off", C.c_void_p),
+                ("shared_pages", C.c_void_p), ("shared_len", C.c_void_p),
+                ("branch_page_off", C.c_void_p), ("branch_pages", C.c_void_p),
+                ("branch_len", C.c_void_p), ("branch_pos", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libdagattn.so is not built: run `python -m paper_2602_07529_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        L.dag_prefill_tile_shape.argtypes = [i32, i32, i32, C.c_int, C.POINTER(i32), C.POINTER(i32)]
+        L.dag_meta_sizes.argtypes = [C.POINTER(dag_desc_t), C.POINTER(dag_meta_sizes_t)]
+        L.dag_build_meta.argtypes = [C.POINTER(dag_desc_t), C.POINTER(dag_meta_t), vp, C.c_size_t, vp]
+        L.dag_rope_qk.argtypes = [vp, i64, vp, vp, i32, i32, i32, f32, C.c_int, vp]
+        L.dag_attn_prefill.argtypes = [C.POINTER(dag_meta_t), vp, vp, vp, vp, vp, i32, i32, i32, f32,
+                                       C.c_int, vp]
+        L.dag_kv_append_rope.argtypes = [C.POINTER(dag_decode_desc_t), vp, vp, vp, vp, i32, i32, f32, vp]
+        L.dag_decode_workspace_bytes.argtypes = [C.POINTER(dag_decode_desc_t), i32, i32, i32]
+        L.dag_decode_workspace_bytes.restype = C.c_size_t
+        L.dag_attn_decode.argtypes = [C.POINTER(dag_decode_desc_t), vp, vp, vp, vp, i32, i32, i32, f32,
+                                      vp, C.c_size_t, vp]
+        L.dag_strerror.argtypes = [C.c_int]
+        L.dag_strerror.restype = C.c_char_p
+        L.dag_version.restype = C.c_int
+        for name in ("dag_prefill_tile_shape", "dag_meta_sizes", "dag_build_meta", "dag_rope_qk",
+                     "dag_attn_prefill", "dag_kv_append_rope", "dag_attn_decode"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise DagError(rc, lib().dag_strerror(rc).decode())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return DAG_F32
+    if t.dtype == torch.bfloat16:
+        return DAG_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def dag_strerror(code):
+    return lib().dag_strerror(code).decode()
+
+
+def dag_version():
+    return lib().dag_version()
+
+
+def dag_prefill_tile_shape(hq, hkv, head_dim, dtype_code):
+    tm, tn = C.c_int32(0), C.c_int32(0)
+    _check(lib().dag_prefill_tile_shape(hq, hkv, head_dim, dtype_code, C.byref(tm), C.byref(tn)))
+    return tm.value, tn.value
+
+
+class DagDesc:
+    """Host-side node table (keeps the numpy arrays alive for the ctypes struct)."""
+
+    def __init__(self, node_offsets, node_len, anc_bits, words_per_node, tile_m, tile_n, flags=0):
+        self.node_offsets = np.ascontiguousarray(node_offsets, dtype=np.int32)
+        self.node_len = np.ascontiguousarray(node_len, dtype=np.int32)
+        self.anc_bits = np.ascontiguousarray(anc_bits, dtype=np.uint64)
+        self.c = dag_desc_t(len(self.node_offsets) - 1, self.node_offsets.ctypes.data,
+                            self.node_len.ctypes.data, self.anc_bits.ctypes.data,
+                            words_per_node, tile_m, tile_n, flags)
+
+
+def dag_meta_sizes(desc):
+    out = dag_meta_sizes_t()
+    _check(lib().dag_meta_sizes(C.byref(desc.c), C.byref(out)))
+    return out
+
+
+class DagMeta:
+    """Device tables written by dag_build_meta (torch tensors + the ctypes struct pointing at them)."""
+
+    def __init__(self, desc, sizes, device):
+        n = desc.c.n_seqs
+        W = desc.c.words_per_node
+        counts = dict(cu_seqlens=n + 1, node_start=n + 1, tok_node=sizes.total_tokens,
+                      pos_ids=sizes.total_tokens, node_tok_start=sizes.total_nodes,
+                      node_pos_start=sizes.total_nodes, node_vis=sizes.total_nodes * W,
+                      qtile_start=n + 1, block_map_off=n + 1, block_map=sizes.total_tiles,
+                      qtile_rowptr=sizes.total_qtiles + 1, qtile_col=sizes.csr_capacity,
+                      qtile_flag=sizes.csr_capacity, qtile_order=sizes.total_qtiles, useful_pairs=n)
+        self.sizes = sizes
+        self.t = {name: torch.empty(max(int(counts[name]), 1), dtype=dt, device=device)
+                  for name, dt in _META_ARRAYS}
+        self.counts = counts
+        self.c = dag_meta_t()
+        self.c.n_seqs, self.c.words_per_node = n, W
+        self.c.tile_m, self.c.tile_n = desc.c.tile_m, desc.c.tile_n
+        self.c.sizes = sizes
+        for name, _ in _META_ARRAYS:
+            setattr(self.c, name, self.t[name].data_ptr())
+        self.workspace = torch.empty(max(int(sizes.workspace_bytes), 16), dtype=torch.uint8, device=device)
+
+    def get(self, name):
+        """Valid prefix of a table as a torch tensor."""
+        return self.t[name][:int(self.counts[name])]
+
+
+def dag_build_meta(desc, meta):
+    _check(lib().dag_build_meta(C.byref(desc.c), C.byref(meta.c), _ptr(meta.workspace),
+                                meta.workspace.numel(), _stream()))
+
+
+def dag_rope_qk(pos_ids, q, k, theta):
+    ref = q if q is not None else k
+    n_tokens, d = ref.shape[0], ref.shape[-1]
+    hq = q.shape[1] if q is not None else 0
+    hkv = k.shape[1] if k is not None else 0
+    _check(lib().dag_rope_qk(_ptr(pos_ids), n_tokens, _ptr(q), _ptr(k), hq, hkv, d, float(theta),
+                             _dtype_code(ref), _stream()))
+
+
+def dag_attn_prefill(meta, q, k, v, out, lse=None, softmax_scale=None):
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    if softmax_scale is None:
+        softmax_scale = 1.0 / float(d) ** 0.5
+    _check(lib().dag_attn_prefill(C.byref(meta.c), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
+                                  hq, hkv, d, float(softmax_scale), _dtype_code(q), _stream()))
+
+
+class DecodeDesc:
+    """Device copies of the decode description arrays + the ctypes struct."""
+
+    def __init__(self, desc, device):
+        self.t = {}
+        for name in ("group_branch_off", "shared_page_off", "shared_pages", "shared_len",
+                     "branch_page_off", "branch_pages", "branch_len", "branch_pos"):
+            arr = np.ascontiguousarray(desc[name], dtype=np.int32)
+            if arr.size == 0:
+                arr = np.zeros(1, dtype=np.int32)
+            self.t[name] = torch.from_numpy(arr).to(device)
+        ng, nl = int(desc["n_groups"]), int(desc["n_live"])
+        sp = np.diff(np.asarray(desc["shared_page_off"])) if ng else np.zeros(0)
+        bp = np.diff(np.asarray(desc["branch_page_off"])) if nl else np.zeros(0)
+        gs = np.diff(np.asarray(desc["group_branch_off"])) if ng else np.zeros(0)
+        self.c = dag_decode_desc_t(ng, nl, int(desc["page_size"]),
+                                   int(sp.max()) if sp.size else 0, int(bp.max()) if bp.size else 0,
+                                   int(gs.max()) if gs.size else 0,
+                                   *[self.t[n].data_ptr() for n in
+                                     ("group_branch_off", "shared_page_off", "shared_pages", "shared_len",
+                                      "branch_page_off", "branch_pages", "branch_len", "branch_pos")])
+
+
+def dag_kv_append_rope(ddesc, k_new, v_new, k_pool, v_pool, theta):
+    hkv, d = k_new.shape[1], k_new.shape[2]
+    _check(lib().dag_kv_append_rope(C.byref(ddesc.c), _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool),
+                                    hkv, d, float(theta), _stream()))
+
+
+def dag_decode_workspace_bytes(ddesc, hq, hkv, head_dim):
+    return int(lib().dag_decode_workspace_bytes(C.byref(ddesc.c), hq, hkv, head_dim))
+
+
+def dag_attn_decode(ddesc, q, k_pool, v_pool, out, workspace, softmax_scale=None):
+    n_live, hq, d = q.shape
+    hkv = k_pool.shape[1]
+    if softmax_scale is None:
+        softmax_scale = 1.0 / float(d) ** 0.5
+    _check(lib().dag_attn_decode(C.byref(ddesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(out), hq, hkv, d,
+                                 float(softmax_scale), _ptr(workspace), workspace.numel(), _stream()))

@@ -1,0 +1,64 @@
+// C-ABI entry points that only validate and dispatch: dag_attn_prefill, dag_strerror, dag_version.
+#include "common.h"
+#include "prefill_launch.h"
+
+extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* k, const void* v, void* out,
+                                float* lse, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale,
+                                dag_dtype_t dtype, void* stream_) {
+  if (!m) return DAG_ERR_NULL;
+  if (dtype != DAG_F32 && dtype != DAG_BF16) return DAG_ERR_UNSUPPORTED;
+  int32_t tm = 0, tn = 0;
+  const int rc = dag_prefill_tile_shape(hq, hkv, head_dim, dtype, &tm, &tn);
+  if (rc != DAG_OK) return rc;
+  if (m->tile_m != tm || m->tile_n != tn) return DAG_ERR_UNSUPPORTED;
+  if (m->n_seqs < 0 || m->sizes.total_tokens < 0 || m->sizes.total_qtiles < 0 || m->words_per_node < 1)
+    return DAG_ERR_BAD_LEN;
+  if (m->n_seqs == 0 || m->sizes.total_tokens == 0) return DAG_OK;
+  if (!q || !k || !v || !out) return DAG_ERR_NULL;
+  if (!m->cu_seqlens || !m->node_start || !m->tok_node || !m->node_vis || !m->qtile_start || !m->qtile_rowptr ||
+      !m->qtile_col || !m->qtile_flag || !m->qtile_order)
+    return DAG_ERR_NULL;
+  if (!dag_aligned16(q) || !dag_aligned16(k) || !dag_aligned16(v) || !dag_aligned16(out)) return DAG_ERR_ALIGN;
+  if (m->sizes.total_qtiles * (int64_t)hq > INT32_MAX) return DAG_ERR_UNSUPPORTED;
+  PrefillArgs a;
+  a.q = q;
+  a.k = k;
+  a.v = v;
+  a.out = out;
+  a.lse = lse;
+  a.cu_seqlens = m->cu_seqlens;
+  a.node_start = m->node_start;
+  a.tok_node = m->tok_node;
+  a.node_vis = m->node_vis;
+  a.qtile_start = m->qtile_start;
+  a.rowptr = m->qtile_rowptr;
+  a.col = m->qtile_col;
+  a.flag = m->qtile_flag;
+  a.qtile_order = m->qtile_order;
+  a.n_seqs = m->n_seqs;
+  a.W = m->words_per_node;
+  a.hq = hq;
+  a.hkv = hkv;
+  a.total_qtiles = m->sizes.total_qtiles;
+  a.scale = softmax_scale;
+  hipStream_t stream = (hipStream_t)stream_;
+  return dtype == DAG_F32 ? launch_prefill_f32(a, head_dim, stream) : launch_prefill_bf16(a, head_dim, stream);
+}
+
+extern "C" const char* dag_strerror(int code) {
+  switch (code) {
+    case DAG_OK: return "ok";
+    case DAG_ERR_NULL: return "a required pointer is NULL";
+    case DAG_ERR_BAD_LEN: return "bad length or inconsistent size";
+    case DAG_ERR_NOT_TOPOLOGICAL: return "ancestor bitset is not in topological order (or the graph has a cycle)";
+    case DAG_ERR_NOT_CLOSED: return "ancestor bitset is not transitively closed";
+    case DAG_ERR_POS_OVERFLOW: return "token or position count exceeds int32";
+    case DAG_ERR_WORKSPACE: return "workspace missing or too small";
+    case DAG_ERR_UNSUPPORTED: return "unsupported configuration";
+    case DAG_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case DAG_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+extern "C" int dag_version(void) { return 100; }

@@ -1,0 +1,450 @@
+// Branch-parallel decode over a paged KV cache (paper section 3.2: tokens carry KV-cache
+// references; section 4.3 Fork: sibling branches share the prefix KV without copying).
+//
+// dag_kv_append_rope : store each live branch's new (rotated) key and value into its tail page.
+// dag_attn_decode    : cascade attention.  One launch of independent single-wave work items:
+//     shared items  (group, kv head, 32-row block, page split): the queries of ALL siblings of the
+//                   group (siblings x query heads of the kv head, stacked as MFMA columns) against
+//                   a slice of the shared pages -- each shared page is fetched once per group;
+//     own items     (branch, kv head, page split): the branch's query heads against its own pages.
+//   Every item writes an un-normalised partial (o, m, l); a second launch merges the partials of
+//   each (branch, head) by log-sum-exp.
+//
+// Pool formats (bf16, 16 tokens per page) are chosen so that global loads land directly in MFMA
+// operand layout, fully coalesced, with no LDS staging:
+//   K pool [P][hkv][D/8][16][8] : for a fixed 8-wide d-chunk the 16 keys of a page are contiguous;
+//                                 one load instruction of a wave reads 2 x 512 contiguous bytes.
+//   V pool [P][hkv][D][16]      : for a fixed d the 16 keys of a page are contiguous (the
+//                                 contraction dimension of P.V); one load reads 1 KiB contiguous.
+// Scores are computed transposed (S^T = K Q^T, 32 keys x 32 query rows per MFMA block) and MFMA
+// row i is mapped to key pi(i), so the probabilities come out of the first product already in the
+// B-operand layout of the second (O^T = V^T P^T).
+#include <stdlib.h>
+
+#include "common.h"
+
+namespace {
+
+constexpr int PAGE = DAG_PAGE_SIZE;
+
+struct DecodeArgs {
+  const int32_t* group_branch_off;
+  const int32_t* shared_page_off;
+  const int32_t* shared_pages;
+  const int32_t* shared_len;
+  const int32_t* branch_page_off;
+  const int32_t* branch_pages;
+  const int32_t* branch_len;
+  const uint16_t* q;
+  const uint16_t* k_pool;
+  const uint16_t* v_pool;
+  uint16_t* out;
+  float* part_o_a;   // [items_a][32][D]
+  float* part_ml_a;  // [items_a][32][2]
+  float* part_o_b;   // [items_b][G][D]
+  float* part_ml_b;  // [items_b][G][2]
+  int n_groups, n_live, hq, hkv, G;
+  int rb_max;        // 32-row blocks per (group, kv head)
+  int chunk_a, splits_a, chunk_b, splits_b;
+  int items_a, items_b;
+  float sc;          // softmax_scale * log2(e)
+  float scale;
+};
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+typedef __attribute__((ext_vector_type(8))) float f32x8;
+
+// MFMA row i (0..31) of a 32-key block -> (page 0/1, slot 0..15): registers 0..7 / 8..15 of the
+// transposed score block then hold slots 8H..8H+7 of page 0 / page 1.
+__device__ __forceinline__ int key_of_row(int i) {
+  const int a = i >> 3, hh = (i >> 2) & 1, c = i & 3;
+  return 16 * (a >> 1) + 8 * hh + 4 * (a & 1) + c;
+}
+
+template <int D>
+struct KVBlock {           // one 32-key block (2 pages) in operand layout
+  bf16x8 k[D / 16];        // k[s]: d-chunk 2s+H of key pi(L)
+  bf16x8 v[2][D / 32];     // v[page][db]: keys 8H..8H+7 of dimension 32db+L
+};
+
+template <int D>
+__device__ __forceinline__ void load_block(KVBlock<D>& blk, const DecodeArgs& a, const int32_t* pages, int pb,
+                                           int p_last, int hk, int L, int H, int kpage_sel, int kslot) {
+  const int pg0 = pages[pb];
+  const int pg1 = pages[min(pb + 1, p_last)];
+  const size_t kbase0 = ((size_t)pg0 * a.hkv + hk) * (size_t)(D * PAGE);
+  const size_t kbase1 = ((size_t)pg1 * a.hkv + hk) * (size_t)(D * PAGE);
+  const uint16_t* kp = a.k_pool + (kpage_sel ? kbase1 : kbase0) + kslot * 8 + H * (PAGE * 8);
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) blk.k[s] = *(const bf16x8*)(kp + s * (2 * PAGE * 8));
+  const uint16_t* vp0 = a.v_pool + kbase0 + L * PAGE + H * 8;
+  const uint16_t* vp1 = a.v_pool + kbase1 + L * PAGE + H * 8;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db) {
+    blk.v[0][db] = *(const bf16x8*)(vp0 + db * 32 * PAGE);
+    blk.v[1][db] = *(const bf16x8*)(vp1 + db * 32 * PAGE);
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void compute_block(const KVBlock<D>& blk, const bf16x8* qf, f32x16* O, float& m, float& l,
+                                              float sc, int key0, int len, int H) {
+  f32x16 S;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) S[r] = 0.f;
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) S = mfma32(blk.k[s], qf[s], S);
+  if (key0 + 32 > len) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = key0 + 16 * (r >> 3) + 8 * H + (r & 7);
+      S[r] = key < len ? S[r] : -INFINITY;
+    }
+  }
+  float bm = S[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) bm = fmaxf(bm, S[r]);
+  bm = fmaxf(bm, __shfl_xor(bm, 32));
+  const float m_new = fmaxf(m, bm);
+  const float alpha = __builtin_amdgcn_exp2f((m - m_new) * sc);
+  const float msc = m_new * sc;
+  m = m_new;
+  f32x8 p0, p1;
+  float rowsum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    p0[r] = __builtin_amdgcn_exp2f(fmaf(S[r], sc, -msc));
+    p1[r] = __builtin_amdgcn_exp2f(fmaf(S[8 + r], sc, -msc));
+    rowsum += p0[r] + p1[r];
+  }
+  l = l * alpha + rowsum;
+  const bf16x8 pb0 = __builtin_convertvector(p0, bf16x8);
+  const bf16x8 pb1 = __builtin_convertvector(p1, bf16x8);
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) O[db][r] *= alpha;
+    O[db] = mfma32(blk.v[0][db], pb0, O[db]);
+    O[db] = mfma32(blk.v[1][db], pb1, O[db]);
+  }
+}
+
+template <int D>
+__global__ void __launch_bounds__(64) k_decode(DecodeArgs a) {
+  const int item = blockIdx.x;
+  const int lane = threadIdx.x, L = lane & 31, H = lane >> 5;
+  const bool is_a = item < a.items_a;
+  int hk, split, chunk, len, nrows, row0, branch0;
+  const int32_t* pages;
+  if (is_a) {
+    int x = item;
+    split = x % a.splits_a; x /= a.splits_a;
+    const int rb = x % a.rb_max; x /= a.rb_max;
+    hk = x % a.hkv;
+    const int g = x / a.hkv;
+    branch0 = a.group_branch_off[g];
+    nrows = (a.group_branch_off[g + 1] - branch0) * a.G;
+    row0 = rb * 32;
+    pages = a.shared_pages + a.shared_page_off[g];
+    len = a.shared_len[g];
+    chunk = a.chunk_a;
+  } else {
+    int x = item - a.items_a;
+    split = x % a.splits_b; x /= a.splits_b;
+    hk = x % a.hkv;
+    branch0 = x / a.hkv;
+    nrows = a.G;
+    row0 = 0;
+    pages = a.branch_pages + a.branch_page_off[branch0];
+    len = a.branch_len[branch0];
+    chunk = a.chunk_b;
+  }
+  const int npages = (len + PAGE - 1) / PAGE;
+  const int p0 = split * chunk, p1 = min(p0 + chunk, npages);
+  const int row = row0 + L;
+  const bool row_ok = row < nrows;
+
+  float* po;
+  float* pml;
+  if (is_a) {
+    po = a.part_o_a + ((size_t)item * 32 + L) * D;
+    pml = a.part_ml_a + ((size_t)item * 32 + L) * 2;
+  } else {
+    po = a.part_o_b + ((size_t)(item - a.items_a) * a.G + L) * D;
+    pml = a.part_ml_b + ((size_t)(item - a.items_a) * a.G + L) * 2;
+  }
+  if (p0 >= p1 || row0 >= nrows) {  // empty slice: neutral partial
+    if (row_ok && H == 0) {
+      pml[0] = -1e30f;
+      pml[1] = 0.f;
+    }
+    return;
+  }
+
+  bf16x8 qf[D / 16];
+  {
+    const int rr = row_ok ? row : 0;
+    const int br = branch0 + rr / a.G, head = hk * a.G + rr % a.G;
+    const uint16_t* qp = a.q + ((size_t)br * a.hq + head) * D + 8 * H;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) qf[s] = *(const bf16x8*)(qp + 16 * s);
+  }
+  const int kr = key_of_row(L);
+  const int kpage_sel = kr >> 4, kslot = kr & 15;
+
+  f32x16 O[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
+  float m = -1e30f, l = 0.f;
+
+  KVBlock<D> b0, b1;
+  load_block<D>(b0, a, pages, p0, p1 - 1, hk, L, H, kpage_sel, kslot);
+  int pb = p0;
+  while (true) {
+    if (pb + 2 < p1) load_block<D>(b1, a, pages, pb + 2, p1 - 1, hk, L, H, kpage_sel, kslot);
+    compute_block<D>(b0, qf, O, m, l, a.sc, pb * PAGE, len, H);
+    pb += 2;
+    if (pb >= p1) break;
+    if (pb + 2 < p1) load_block<D>(b0, a, pages, pb + 2, p1 - 1, hk, L, H, kpage_sel, kslot);
+    compute_block<D>(b1, qf, O, m, l, a.sc, pb * PAGE, len, H);
+    pb += 2;
+    if (pb >= p1) break;
+  }
+
+  const float l_tot = l + __shfl_xor(l, 32);
+  if (row_ok) {
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 o = {O[db][4 * r4], O[db][4 * r4 + 1], O[db][4 * r4 + 2], O[db][4 * r4 + 3]};
+        *(f32x4*)(po + 32 * db + 8 * r4 + 4 * H) = o;
+      }
+    if (H == 0) {
+      pml[0] = m;
+      pml[1] = l_tot;
+    }
+  }
+}
+
+// One wave per (branch, query head): log-sum-exp combination of its partials.
+template <int D>
+__global__ void __launch_bounds__(64) k_decode_merge(DecodeArgs a) {
+  const int r = blockIdx.x / a.hq, head = blockIdx.x % a.hq;
+  const int hk = head / a.G, j = head % a.G;
+  const int lane = threadIdx.x;
+  const int g = dag_find_segment(a.group_branch_off, a.n_groups, r);
+  const int row = (r - a.group_branch_off[g]) * a.G + j;
+  const int rb = row >> 5, rr = row & 31;
+  const size_t ia0 = (((size_t)g * a.hkv + hk) * a.rb_max + rb) * a.splits_a;
+  const size_t ib0 = ((size_t)r * a.hkv + hk) * a.splits_b;
+  float mx = -1e30f;
+  for (int s = 0; s < a.splits_a; ++s) mx = fmaxf(mx, a.part_ml_a[((ia0 + s) * 32 + rr) * 2]);
+  for (int s = 0; s < a.splits_b; ++s) mx = fmaxf(mx, a.part_ml_b[((ib0 + s) * a.G + j) * 2]);
+  constexpr int PER = D / 64;  // output elements per lane
+  float acc[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+  float lsum = 0.f;
+  for (int s = 0; s < a.splits_a; ++s) {
+    const size_t base = (ia0 + s) * 32 + rr;
+    const float ls = a.part_ml_a[base * 2 + 1];
+    if (ls > 0.f) {
+      const float wgt = __builtin_amdgcn_exp2f((a.part_ml_a[base * 2] - mx) * a.sc);
+      lsum += ls * wgt;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) acc[e] += wgt * a.part_o_a[base * D + lane * PER + e];
+    }
+  }
+  for (int s = 0; s < a.splits_b; ++s) {
+    const size_t base = (ib0 + s) * a.G + j;
+    const float ls = a.part_ml_b[base * 2 + 1];
+    if (ls > 0.f) {
+      const float wgt = __builtin_amdgcn_exp2f((a.part_ml_b[base * 2] - mx) * a.sc);
+      lsum += ls * wgt;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) acc[e] += wgt * a.part_o_b[base * D + lane * PER + e];
+    }
+  }
+  const float inv = 1.f / lsum;
+  uint16_t* o = a.out + ((size_t)r * a.hq + head) * D + lane * PER;
+  if (PER == 2) {
+    *(uint32_t*)o = dag_pack_bf2(acc[0] * inv, acc[PER - 1] * inv);
+  } else {
+    o[0] = (uint16_t)dag_f2bf(acc[0] * inv);
+  }
+}
+
+// One block per live branch: rotate the new key at the branch's adaptive position and scatter
+// key and value into the pool formats.
+__global__ void __launch_bounds__(256) k_kv_append(const int32_t* branch_page_off, const int32_t* branch_pages,
+                                                   const int32_t* branch_len, const int32_t* branch_pos,
+                                                   const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
+                                                   uint16_t* v_pool, int hkv, int D, float theta) {
+  const int r = blockIdx.x;
+  const int idx = branch_len[r] - 1;
+  if (idx < 0) return;
+  const int page = branch_pages[branch_page_off[r] + idx / PAGE];
+  const int slot = idx % PAGE;
+  const int half = D / 2;
+  const double pos = (double)branch_pos[r];
+  for (int x = threadIdx.x; x < hkv * half; x += blockDim.x) {
+    const int h = x / half, mi = x % half;
+    double sn, cs;
+    sincos(pos * pow((double)theta, -2.0 * (double)mi / (double)D), &sn, &cs);
+    const size_t src = ((size_t)r * hkv + h) * D;
+    const float lo = __uint_as_float((uint32_t)k_new[src + mi] << 16);
+    const float hi = __uint_as_float((uint32_t)k_new[src + mi + half] << 16);
+    const float c = (float)cs, s = (float)sn;
+    const size_t pb = ((size_t)page * hkv + h) * (size_t)(D * PAGE);
+    const int d0 = mi, d1 = mi + half;
+    k_pool[pb + (size_t)(d0 >> 3) * (PAGE * 8) + slot * 8 + (d0 & 7)] = (uint16_t)dag_f2bf(lo * c - hi * s);
+    k_pool[pb + (size_t)(d1 >> 3) * (PAGE * 8) + slot * 8 + (d1 & 7)] = (uint16_t)dag_f2bf(hi * c + lo * s);
+    v_pool[pb + (size_t)d0 * PAGE + slot] = v_new[src + d0];
+    v_pool[pb + (size_t)d1 * PAGE + slot] = v_new[src + d1];
+  }
+}
+
+struct DecodePlan {
+  int rb_max, chunk_a, splits_a, chunk_b, splits_b, items_a, items_b;
+  size_t off_o_a, off_ml_a, off_o_b, off_ml_b, bytes;
+};
+
+int env_int(const char* name, int dflt) {
+  const char* s = getenv(name);
+  if (!s || !*s) return dflt;
+  const int v = atoi(s);
+  return v > 0 ? v : dflt;
+}
+
+// Split sizes: long slices for the shared phase (a partial costs 32 rows of D floats, so few of
+// them), short ones for the own-token phase (G rows per partial); both even so that a 32-key
+// block never straddles a split.
+int make_plan(const dag_decode_desc_t* d, int hq, int hkv, int D, DecodePlan* p) {
+  if (!d) return DAG_ERR_NULL;
+  if (d->n_groups < 0 || d->n_live < 0 || d->max_shared_pages < 0 || d->max_branch_pages < 0 || d->max_group_size < 0)
+    return DAG_ERR_BAD_LEN;
+  if (d->page_size != PAGE) return DAG_ERR_UNSUPPORTED;
+  if (hq < 1 || hkv < 1 || hq % hkv != 0 || hq / hkv > 32) return DAG_ERR_UNSUPPORTED;
+  if (D != 64 && D != 128) return DAG_ERR_UNSUPPORTED;
+  const int G = hq / hkv;
+  p->rb_max = (int)dag_ceil_div((int64_t)d->max_group_size * G, 32);
+  if (p->rb_max < 1) p->rb_max = 1;
+  const int64_t base_a = (int64_t)d->n_groups * hkv * p->rb_max;
+  const int64_t base_b = (int64_t)d->n_live * hkv;
+  int ca = env_int("DAGATTN_DECODE_CHUNK_A", 64), cb = env_int("DAGATTN_DECODE_CHUNK_B", 16);
+  ca += ca & 1;
+  cb += cb & 1;
+  if (!getenv("DAGATTN_DECODE_CHUNK_A"))
+    while (ca > 8 && base_a * dag_ceil_div(d->max_shared_pages, ca) < 1024) ca /= 2;
+  if (!getenv("DAGATTN_DECODE_CHUNK_B"))
+    while (cb > 4 && base_b * dag_ceil_div(d->max_branch_pages, cb) < 2048) cb /= 2;
+  p->chunk_a = ca;
+  p->chunk_b = cb;
+  p->splits_a = d->max_shared_pages > 0 ? (int)dag_ceil_div(d->max_shared_pages, ca) : 0;
+  p->splits_b = d->max_branch_pages > 0 ? (int)dag_ceil_div(d->max_branch_pages, cb) : 0;
+  const int64_t ia = base_a * p->splits_a, ib = base_b * p->splits_b;
+  if (ia + ib > INT32_MAX) return DAG_ERR_UNSUPPORTED;
+  p->items_a = (int)ia;
+  p->items_b = (int)ib;
+  size_t off = 0;
+  p->off_o_a = off;  off += dag_align_up((size_t)ia * 32 * D * 4, 256);
+  p->off_ml_a = off; off += dag_align_up((size_t)ia * 32 * 2 * 4, 256);
+  p->off_o_b = off;  off += dag_align_up((size_t)ib * G * D * 4, 256);
+  p->off_ml_b = off; off += dag_align_up((size_t)ib * G * 2 * 4, 256);
+  p->bytes = off + 256;
+  return DAG_OK;
+}
+
+}  // namespace
+
+extern "C" size_t dag_decode_workspace_bytes(const dag_decode_desc_t* desc, int32_t hq, int32_t hkv,
+                                             int32_t head_dim) {
+  DecodePlan p;
+  if (make_plan(desc, hq, hkv, head_dim, &p) != DAG_OK) return 0;
+  return p.bytes;
+}
+
+extern "C" int dag_kv_append_rope(const dag_decode_desc_t* d, const void* k_new, const void* v_new, void* k_pool,
+                                  void* v_pool, int32_t hkv, int32_t head_dim, float theta, void* stream_) {
+  if (!d) return DAG_ERR_NULL;
+  if (d->n_live < 0) return DAG_ERR_BAD_LEN;
+  if (d->page_size != PAGE) return DAG_ERR_UNSUPPORTED;
+  if (hkv < 1 || head_dim < 16 || head_dim % 16 != 0 || head_dim > 256 || !(theta > 0.f)) return DAG_ERR_UNSUPPORTED;
+  if (d->n_live == 0) return DAG_OK;
+  if (!k_new || !v_new || !k_pool || !v_pool || !d->branch_page_off || !d->branch_pages || !d->branch_len ||
+      !d->branch_pos)
+    return DAG_ERR_NULL;
+  hipLaunchKernelGGL(k_kv_append, dim3(d->n_live), dim3(256), 0, (hipStream_t)stream_, d->branch_page_off,
+                     d->branch_pages, d->branch_len, d->branch_pos, (const uint16_t*)k_new, (const uint16_t*)v_new,
+                     (uint16_t*)k_pool, (uint16_t*)v_pool, hkv, head_dim, theta);
+  DAG_LAUNCH_CHECK();
+  return DAG_OK;
+}
+
+extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const void* k_pool, const void* v_pool,
+                               void* out, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale, void* ws,
+                               size_t ws_bytes, void* stream_) {
+  DecodePlan p;
+  const int rc = make_plan(d, hq, hkv, head_dim, &p);
+  if (rc != DAG_OK) return rc;
+  if (d->n_live == 0) return DAG_OK;
+  if (!q || !k_pool || !v_pool || !out || !d->group_branch_off || !d->branch_page_off || !d->branch_pages ||
+      !d->branch_len)
+    return DAG_ERR_NULL;
+  if (d->n_groups < 1) return DAG_ERR_BAD_LEN;
+  if (p.items_a > 0 && (!d->shared_page_off || !d->shared_pages || !d->shared_len)) return DAG_ERR_NULL;
+  if (p.items_a + p.items_b == 0) return DAG_ERR_BAD_LEN;  // a query needs at least its own token
+  if (!dag_aligned16(q) || !dag_aligned16(k_pool) || !dag_aligned16(v_pool) || !dag_aligned16(out))
+    return DAG_ERR_ALIGN;
+  if (!ws || ws_bytes < p.bytes) return DAG_ERR_WORKSPACE;
+  char* base = (char*)dag_align_up((size_t)(uintptr_t)ws, 256);
+  DecodeArgs a;
+  a.group_branch_off = d->group_branch_off;
+  a.shared_page_off = d->shared_page_off;
+  a.shared_pages = d->shared_pages;
+  a.shared_len = d->shared_len;
+  a.branch_page_off = d->branch_page_off;
+  a.branch_pages = d->branch_pages;
+  a.branch_len = d->branch_len;
+  a.q = (const uint16_t*)q;
+  a.k_pool = (const uint16_t*)k_pool;
+  a.v_pool = (const uint16_t*)v_pool;
+  a.out = (uint16_t*)out;
+  a.part_o_a = (float*)(base + p.off_o_a);
+  a.part_ml_a = (float*)(base + p.off_ml_a);
+  a.part_o_b = (float*)(base + p.off_o_b);
+  a.part_ml_b = (float*)(base + p.off_ml_b);
+  a.n_groups = d->n_groups;
+  a.n_live = d->n_live;
+  a.hq = hq;
+  a.hkv = hkv;
+  a.G = hq / hkv;
+  a.rb_max = p.rb_max;
+  a.chunk_a = p.chunk_a;
+  a.splits_a = p.splits_a;
+  a.chunk_b = p.chunk_b;
+  a.splits_b = p.splits_b;
+  a.items_a = p.items_a;
+  a.items_b = p.items_b;
+  a.scale = softmax_scale;
+  a.sc = softmax_scale * 1.4426950408889634f;
+  hipStream_t stream = (hipStream_t)stream_;
+  const unsigned items = (unsigned)(p.items_a + p.items_b);
+  const unsigned nout = (unsigned)(d->n_live * hq);
+  if (head_dim == 128) {
+    hipLaunchKernelGGL(k_decode<128>, dim3(items), dim3(64), 0, stream, a);
+    DAG_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_decode_merge<128>, dim3(nout), dim3(64), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL(k_decode<64>, dim3(items), dim3(64), 0, stream, a);
+    DAG_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_decode_merge<64>, dim3(nout), dim3(64), 0, stream, a);
+  }
+  DAG_LAUNCH_CHECK();
+  return DAG_OK;
+}

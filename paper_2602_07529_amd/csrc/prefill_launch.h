@@ -1,0 +1,26 @@
+// Kernel argument block shared by the prefill kernels (internal).
+#pragma once
+#include "common.h"
+
+struct PrefillArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  float* lse;
+  const int32_t* cu_seqlens;
+  const int32_t* node_start;
+  const int32_t* tok_node;
+  const uint64_t* node_vis;
+  const int32_t* qtile_start;
+  const int32_t* rowptr;
+  const int32_t* col;
+  const uint8_t* flag;
+  const int32_t* qtile_order;
+  int n_seqs, W, hq, hkv;
+  int64_t total_qtiles;
+  float scale;
+};
+
+int launch_prefill_f32(const PrefillArgs& a, int head_dim, hipStream_t stream);
+int launch_prefill_bf16(const PrefillArgs& a, int head_dim, hipStream_t stream);

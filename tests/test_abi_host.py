@@ -1,0 +1,170 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol include/dagattn.h
+declares, and its host-side validation returns the documented error codes before any GPU work
+(no compute call is made here, so no GPU is needed)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2602_07529_amd import binding as B
+from workloads import dags
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a non-null, 16-byte aligned "device pointer"; never dereferenced on these paths
+
+
+def _declared_functions():
+    txt = open(os.path.join(ROOT, "include", "dagattn.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(dag_[a-z_0-9]+)\s*\(", txt)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"dag_meta_sizes", "dag_build_meta", "dag_rope_qk", "dag_attn_prefill", "dag_kv_append_rope",
+            "dag_attn_decode", "dag_decode_workspace_bytes", "dag_prefill_tile_shape", "dag_strerror",
+            "dag_version"} <= set(names)
+    L = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_strerror():
+    assert B.dag_version() >= 100
+    assert B.dag_strerror(0) == "ok"
+    for code in range(-9, 0):
+        assert B.dag_strerror(code) not in ("ok", "unknown error")
+    assert B.dag_strerror(-99) == "unknown error"
+
+
+def test_tile_shape_table():
+    assert B.dag_prefill_tile_shape(4, 4, 64, B.DAG_F32) == (64, 64)
+    assert B.dag_prefill_tile_shape(32, 8, 128, B.DAG_BF16) == (32, 64)
+    assert B.dag_prefill_tile_shape(40, 8, 128, B.DAG_BF16) == (32, 64)
+    assert B.dag_prefill_tile_shape(16, 8, 64, B.DAG_BF16) == (64, 64)
+    assert B.dag_prefill_tile_shape(8, 8, 128, B.DAG_BF16) == (128, 64)
+    with pytest.raises(B.DagError) as e:
+        B.dag_prefill_tile_shape(6, 4, 128, B.DAG_BF16)
+    assert e.value.code == -7
+    with pytest.raises(B.DagError):
+        B.dag_prefill_tile_shape(8, 8, 96, B.DAG_BF16)
+
+
+def _desc(dag_list, tile=(32, 64), flags=0, words=None):
+    off, lens, bits, W = dags.batch_desc(dag_list)
+    return B.DagDesc(off, lens, bits, W if words is None else words, tile[0], tile[1], flags)
+
+
+def test_meta_sizes_counts():
+    one = dags.fork_join(2048, [256] * 8, 512)
+    s = B.dag_meta_sizes(_desc([one] * 4))
+    assert s.total_nodes == 40 and s.total_tokens == 18432
+    assert s.total_qtiles == 4 * 144 and s.total_tiles == 4 * 144 * 72
+    # ragged: T = 100 with 32x64 tiles -> 4 query tiles, 2 key tiles
+    s = B.dag_meta_sizes(_desc([dags.linear_chain([100])]))
+    assert (s.total_qtiles, s.total_tiles) == (4, 8)
+    assert s.csr_capacity == 1 + 1 + 2 + 2
+    # empty batch and an empty sequence
+    s = B.dag_meta_sizes(B.DagDesc(np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros((0, 1), np.uint64), 1, 32, 64))
+    assert s.total_tokens == 0 and s.total_qtiles == 0
+    s = B.dag_meta_sizes(B.DagDesc(np.array([0, 0, 1], np.int32), np.array([5], np.int32), np.zeros((1, 1), np.uint64), 1, 32, 64))
+    assert s.total_tokens == 5 and s.total_qtiles == 1
+
+
+def _build_rc(desc, ws_bytes=1 << 20):
+    sizes = B.dag_meta_sizes(desc)
+    m = B.dag_meta_t()
+    m.n_seqs, m.words_per_node = desc.c.n_seqs, desc.c.words_per_node
+    m.tile_m, m.tile_n = desc.c.tile_m, desc.c.tile_n
+    m.sizes = sizes
+    for name, _ in B._META_ARRAYS:
+        setattr(m, name, FAKE)
+    return B.lib().dag_build_meta(C.byref(desc.c), C.byref(m), C.c_void_p(FAKE), ws_bytes, None)
+
+
+def test_build_meta_rejects_invalid_dags_before_any_gpu_work():
+    # node length < 1
+    with pytest.raises(B.DagError) as e:
+        B.dag_meta_sizes(B.DagDesc(np.array([0, 2], np.int32), np.array([3, 0], np.int32), np.zeros((2, 1), np.uint64), 1, 32, 64))
+    assert e.value.code == -2
+    # not topological: node 0 lists node 1 as an ancestor (a cycle 0 <-> 1 looks the same)
+    bits = dags.bits_from_sets([{1}, {0}])
+    d = B.DagDesc(np.array([0, 2], np.int32), np.array([3, 3], np.int32), bits, 1, 32, 64)
+    assert _build_rc(d) == -3
+    # self bit alone is ignored, not an error; rejected later only for the tiny workspace
+    bits = dags.bits_from_sets([{0}, {0, 1}])
+    d = B.DagDesc(np.array([0, 2], np.int32), np.array([3, 3], np.int32), bits, 1, 32, 64)
+    assert _build_rc(d, ws_bytes=8) == -6
+    # strict closure: 2 lists 1 but not 1's ancestor 0
+    bits = dags.bits_from_sets([set(), {0}, {1}])
+    d = B.DagDesc(np.array([0, 3], np.int32), np.array([1, 1, 1], np.int32), bits, 1, 32, 64, B.DAG_STRICT_CLOSURE)
+    assert _build_rc(d) == -4
+    d = B.DagDesc(np.array([0, 3], np.int32), np.array([1, 1, 1], np.int32), bits, 1, 32, 64, 0)
+    assert _build_rc(d, ws_bytes=8) == -6          # lax mode accepts it (fails only on the workspace)
+    # too few bitset words for the node count
+    L, anc = dags.linear_chain([1] * 70)
+    with pytest.raises(B.DagError) as e:
+        B.dag_meta_sizes(B.DagDesc(np.array([0, 70], np.int32), L, anc[:, :1].copy(), 1, 32, 64))
+    assert e.value.code == -2
+    # sizes in the meta struct must match the description
+    d = _desc([dags.linear_chain([10, 10])])
+    sizes = B.dag_meta_sizes(d)
+    m = B.dag_meta_t()
+    m.n_seqs, m.words_per_node, m.tile_m, m.tile_n = 1, 1, 32, 64
+    sizes.total_tokens += 1
+    m.sizes = sizes
+    assert B.lib().dag_build_meta(C.byref(d.c), C.byref(m), C.c_void_p(FAKE), 1 << 20, None) == -2
+    # null description
+    assert B.lib().dag_build_meta(None, C.byref(m), C.c_void_p(FAKE), 1 << 20, None) == -1
+
+
+def test_position_overflow_is_reported():
+    lens = np.full(3, 2 ** 30, dtype=np.int32)
+    _, anc = dags.linear_chain([1, 1, 1])
+    with pytest.raises(B.DagError) as e:
+        B.dag_meta_sizes(B.DagDesc(np.array([0, 3], np.int32), lens, anc, 1, 1024, 1024))
+    assert e.value.code == -5
+
+
+def test_rope_and_prefill_argument_errors():
+    L = B.lib()
+    assert L.dag_rope_qk(C.c_void_p(FAKE), 4, C.c_void_p(FAKE), None, 2, 0, 100, 1e4, B.DAG_BF16, None) == -7
+    assert L.dag_rope_qk(C.c_void_p(FAKE), 4, C.c_void_p(FAKE + 4), None, 2, 0, 64, 1e4, B.DAG_BF16, None) == -8
+    assert L.dag_rope_qk(None, 4, C.c_void_p(FAKE), None, 2, 0, 64, 1e4, B.DAG_BF16, None) == -1
+    assert L.dag_rope_qk(None, 0, C.c_void_p(FAKE), None, 2, 0, 64, 1e4, B.DAG_BF16, None) == 0
+    d = _desc([dags.linear_chain([10, 10])])
+    m = B.dag_meta_t()
+    m.n_seqs, m.words_per_node, m.tile_m, m.tile_n = 1, 1, 32, 64
+    m.sizes = B.dag_meta_sizes(d)
+    for name, _ in B._META_ARRAYS:
+        setattr(m, name, FAKE)
+    p = C.c_void_p(FAKE)
+    # tile shape of the meta does not match the kernel for this head configuration (MHA wants 128x64)
+    assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 8, 8, 128, 0.1, B.DAG_BF16, None) == -7
+    assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 96, 0.1, B.DAG_BF16, None) == -7
+    assert L.dag_attn_prefill(C.byref(m), None, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None) == -1
+    assert L.dag_attn_prefill(C.byref(m), C.c_void_p(FAKE + 2), p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None) == -8
+    assert L.dag_attn_prefill(None, p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None) == -1
+
+
+def test_decode_argument_errors():
+    L = B.lib()
+    dd = B.dag_decode_desc_t(1, 2, 16, 4, 2, 2, *([FAKE] * 8))
+    p = C.c_void_p(FAKE)
+    need = L.dag_decode_workspace_bytes(C.byref(dd), 32, 8, 128)
+    assert need > 0
+    assert L.dag_attn_decode(C.byref(dd), p, p, p, p, 32, 8, 128, 0.1, p, need - 1, None) == -6
+    assert L.dag_attn_decode(C.byref(dd), p, p, p, p, 32, 8, 128, 0.1, None, need, None) == -6
+    assert L.dag_attn_decode(C.byref(dd), p, p, p, p, 32, 8, 96, 0.1, p, need, None) == -7
+    assert L.dag_attn_decode(C.byref(dd), p, p, p, p, 30, 8, 128, 0.1, p, need, None) == -7
+    assert L.dag_attn_decode(C.byref(dd), None, p, p, p, 32, 8, 128, 0.1, p, need, None) == -1
+    bad_page = B.dag_decode_desc_t(1, 2, 32, 4, 2, 2, *([FAKE] * 8))
+    assert L.dag_attn_decode(C.byref(bad_page), p, p, p, p, 32, 8, 128, 0.1, p, need, None) == -7
+    assert L.dag_decode_workspace_bytes(C.byref(bad_page), 32, 8, 128) == 0
+    assert L.dag_kv_append_rope(C.byref(bad_page), p, p, p, p, 8, 128, 1e4, None) == -7
+    assert L.dag_kv_append_rope(C.byref(dd), None, p, p, p, 8, 128, 1e4, None) == -1
+    empty = B.dag_decode_desc_t(0, 0, 16, 0, 0, 0, *([0] * 8))
+    assert L.dag_attn_decode(C.byref(empty), p, p, p, p, 32, 8, 128, 0.1, None, 0, None) == 0
+    assert L.dag_kv_append_rope(C.byref(empty), p, p, p, p, 8, 128, 1e4, None) == 0

@@ -1,0 +1,98 @@
+"""GPU parity: dag_build_meta against the oracle, bit-exact for every table."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_07529_amd import binding as B
+from workloads import dags
+from tests.gpu_util import DEV, assert_meta_equal, build_meta, oracle_meta
+
+pytestmark = pytest.mark.gpu
+GOLDEN = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "tiny_dags.json")))
+
+
+def _build_with_tiles(dag_list, tm, tn, flags=0):
+    off, lens, bits, W = dags.batch_desc(dag_list)
+    desc = B.DagDesc(off, lens, bits, W, tm, tn, flags)
+    meta = B.DagMeta(desc, B.dag_meta_sizes(desc), DEV)
+    B.dag_build_meta(desc, meta)
+    return meta
+
+
+def test_diamond_golden_values_on_gpu():
+    g = GOLDEN["diamond"]
+    L = np.asarray(g["node_len"], dtype=np.int32)
+    anc = dags.bits_from_sets(dags.closure_from_parents(g["parents"]))
+    meta = _build_with_tiles([(L, anc)], 2, 2)
+    torch.cuda.synchronize()
+    assert meta.get("tok_node").cpu().tolist() == g["tok_node"]
+    assert meta.get("pos_ids").cpu().tolist() == g["pos_ids"]
+    assert meta.get("block_map").cpu().reshape(4, 4).tolist() == g["block_map"]
+    assert meta.get("useful_pairs").cpu().tolist() == [g["useful_pairs"]]
+
+
+@pytest.mark.parametrize("tm,tn", [(32, 64), (64, 64), (128, 64), (5, 3)])
+def test_meta_small_dags_all_tables(tm, tn):
+    rng = np.random.Generator(np.random.PCG64(101))
+    dag_list = [dags.fork_join(128, [64] * 4, 64),
+                dags.linear_chain([7, 1, 90]),
+                dags.random_dag(rng, n_nodes=12, depth=4, len_lo=1, len_hi=40)[:2],
+                dags.linear_chain([1])]
+    meta = _build_with_tiles(dag_list, tm, tn, flags=B.DAG_STRICT_CLOSURE)
+    assert_meta_equal(meta, oracle_meta(dag_list, tm, tn))
+
+
+def test_meta_config1_and_config2_shapes():
+    c1 = [dags.fork_join(128, [64] * 4, 64)]
+    _, meta = build_meta(c1, 4, 4, 64, torch.float32)
+    assert_meta_equal(meta, oracle_meta(c1, 64, 64))
+    c2 = [dags.fork_join(2048, [256] * 8, 512)] * 4
+    _, meta = build_meta(c2, 32, 8, 128, torch.bfloat16)
+    ref = oracle_meta(c2, 32, 64)
+    assert_meta_equal(meta, ref)
+    assert ref["useful_pairs"].tolist() == [8784128] * 4
+    assert meta.get("pos_ids")[2048].item() == 2048 and meta.get("pos_ids")[4096].item() == 2304
+
+
+def test_meta_random_multilevel_dags_config4_recipe():
+    c = dags.config(3)
+    dag_list = dags.config_dags(c)[:3]
+    _, meta = build_meta(dag_list, c["hq"], c["hkv"], c["d"], torch.bfloat16)
+    assert_meta_equal(meta, oracle_meta(dag_list, 32, 64))
+
+
+def test_meta_more_than_64_nodes_uses_two_bitset_words():
+    rng = np.random.Generator(np.random.PCG64(77))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=100, depth=7, len_lo=1, len_hi=9)
+    assert anc.shape[1] == 2
+    dag_list = [(L, anc), dags.linear_chain([3, 3])]
+    meta = _build_with_tiles(dag_list, 32, 64)
+    assert_meta_equal(meta, oracle_meta(dag_list, 32, 64))
+
+
+def test_meta_layerwise_bitsets_literal_eq3():
+    rng = np.random.Generator(np.random.PCG64(5))
+    L, _, _, level = dags.random_dag(rng, n_nodes=20, depth=5, len_lo=1, len_hi=30)
+    dag_list = [(L, dags.layerwise_bits(level))]
+    meta = _build_with_tiles(dag_list, 32, 64, flags=B.DAG_STRICT_CLOSURE)
+    assert_meta_equal(meta, oracle_meta(dag_list, 32, 64))
+
+
+def test_meta_empty_batch_and_empty_sequence():
+    desc = B.DagDesc(np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros((0, 1), np.uint64), 1, 32, 64)
+    meta = B.DagMeta(desc, B.dag_meta_sizes(desc), DEV)
+    B.dag_build_meta(desc, meta)
+    torch.cuda.synchronize()
+    L, anc = dags.linear_chain([40, 2])
+    desc = B.DagDesc(np.array([0, 0, 2, 2], np.int32), L, anc, 1, 32, 64)
+    meta = B.DagMeta(desc, B.dag_meta_sizes(desc), DEV)
+    B.dag_build_meta(desc, meta)
+    torch.cuda.synchronize()
+    assert meta.get("cu_seqlens").cpu().tolist() == [0, 0, 42, 42]
+    assert meta.get("qtile_start").cpu().tolist() == [0, 0, 2, 2]
+    assert meta.get("pos_ids").cpu().tolist() == list(range(42))
+    assert meta.get("useful_pairs").cpu().tolist() == [0, 42 * 43 // 2, 0]
+    assert meta.get("qtile_rowptr").cpu().tolist() == [0, 1, 2]

@@ -1,0 +1,99 @@
+"""GPU parity: dag_attn_prefill (through the C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dag_oracle as orc
+from paper_2602_07529_amd import binding as B
+from workloads import dags
+from tests.gpu_util import DEV, check_close, oracle_prefill, run_prefill
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_and_check(dag_list, hq, hkv, d, dtype, scale, theta, seed, rows_per_seq=None, want_lse=True):
+    T = int(sum(int(np.sum(L)) for L, _ in dag_list))
+    q, k, v = dags.make_qkv(seed, T, hq, hkv, d, scale, dtype)
+    out, lse, meta, _, _ = run_prefill(dag_list, q, k, v, theta, want_lse=want_lse)
+    ref, ref_lse, rows = oracle_prefill(dag_list, q, k, v, theta, rows_per_seq=rows_per_seq, seed=seed)
+    res = check_close(out[rows], ref[rows], dtype, "prefill out")
+    if want_lse:
+        l = lse.cpu().double().numpy()[rows]
+        assert np.abs(l - ref_lse[rows]).max() < (1e-4 if dtype == torch.float32 else 2e-2)
+    return res
+
+
+def test_config1_tiny_fork_join_fp32():
+    c = dags.config(0)
+    dag_list = dags.config_dags(c)
+    max_abs, rel = _run_and_check(dag_list, c["hq"], c["hkv"], c["d"], torch.float32, c["scale"], c["theta"], c["seed"])
+    assert max_abs < 1e-4
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 1, 128), (8, 2, 64), (5, 1, 128), (2, 1, 128), (6, 3, 64),
+                                      (3, 3, 128), (1, 1, 64), (8, 1, 128), (5, 1, 64)])
+def test_bf16_small_dags_every_kernel_variant(hq, hkv, d):
+    rng = np.random.Generator(np.random.PCG64(1000 + hq * 10 + d))
+    dag_list = [dags.fork_join(100, [37, 64, 5], 70),               # ragged everywhere
+                dags.random_dag(rng, n_nodes=14, depth=4, len_lo=1, len_hi=45)[:2],
+                dags.linear_chain([1]),
+                dags.linear_chain([200])]
+    _run_and_check(dag_list, hq, hkv, d, torch.bfloat16, 0.5, 5e5, 2000 + hq + d)
+
+
+def test_fp32_ragged_and_gqa_and_d128():
+    rng = np.random.Generator(np.random.PCG64(9))
+    dag_list = [dags.fork_join(70, [33, 64], 31), dags.random_dag(rng, n_nodes=10, depth=4, len_lo=1, len_hi=30)[:2]]
+    _run_and_check(dag_list, 4, 2, 128, torch.float32, 1.0, 1e4, 31)
+    _run_and_check(dag_list, 3, 1, 64, torch.float32, 1.0, 1e4, 32)
+
+
+def test_bf16_more_than_64_nodes():
+    rng = np.random.Generator(np.random.PCG64(78))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=90, depth=6, len_lo=1, len_hi=12)
+    _run_and_check([(L, anc)], 4, 1, 128, torch.bfloat16, 0.5, 5e5, 33)
+
+
+def test_bf16_linear_chain_is_causal_attention_of_the_library_kind():
+    # independent of the oracle: compare with torch's fp32 SDPA on the GPU-rotated inputs
+    dag_list = [dags.linear_chain([50, 150, 56])]
+    q, k, v = dags.make_qkv(41, 256, 8, 2, 128, 0.5, torch.bfloat16)
+    out, _, _, qd, kd = run_prefill(dag_list, q, k, v, 5e5)
+    qf = qd.float().permute(1, 0, 2)[None].cpu()
+    kf = kd.float().permute(1, 0, 2)[None].repeat_interleave(4, dim=1).cpu()
+    vf = v.float().permute(1, 0, 2)[None].repeat_interleave(4, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(qf, kf, vf, is_causal=True)[0].permute(1, 0, 2)
+    check_close(out, ref.double().numpy(), torch.bfloat16, "vs sdpa")
+
+
+def test_config2_llama_shape_full_size_sampled_rows():
+    c = dags.config(1)
+    dag_list = dags.config_dags(c)
+    _run_and_check(dag_list, c["hq"], c["hkv"], c["d"], torch.bfloat16, c["scale"], c["theta"], c["seed"],
+                   rows_per_seq=96)
+
+
+def test_config4_random_multilevel_full_size_sampled_rows():
+    c = dags.config(3)
+    dag_list = dags.config_dags(c)
+    _run_and_check(dag_list, c["hq"], c["hkv"], c["d"], torch.bfloat16, c["scale"], c["theta"], c["seed"],
+                   rows_per_seq=64)
+
+
+def test_config2_one_sequence_every_row_of_one_kv_group():
+    c = dags.config(1)
+    dag_list = dags.config_dags(c)[:1]
+    T = 4608
+    q, k, v = dags.make_qkv(c["seed"] + 100, T, c["hq"], c["hkv"], c["d"], c["scale"], torch.bfloat16)
+    out, _, _, _, _ = run_prefill(dag_list, q, k, v, c["theta"])
+    heads = [4, 5, 6, 7]
+    ref, _, _ = oracle_prefill(dag_list, q, k, v, c["theta"], heads=heads)
+    check_close(out[:, heads], ref[:, heads], torch.bfloat16, "config2 all rows, kv group 1")
+
+
+def test_prefill_is_deterministic_run_to_run():
+    dag_list = [dags.fork_join(300, [100, 90], 50)]
+    q, k, v = dags.make_qkv(51, 540, 8, 2, 128, 0.5, torch.bfloat16)
+    o1, _, _, _, _ = run_prefill(dag_list, q, k, v, 5e5)
+    o2, _, _, _, _ = run_prefill(dag_list, q, k, v, 5e5)
+    assert torch.equal(o1, o2)
