@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the DAG-attention hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of seeded synthetic input:
+  prefill segment (workload "llama3_8b_prefill_bf16", benchmark config 2):
+      dag_build_meta -> dag_rope_qk -> dag_attn_prefill
+  decode segment  (workload "branch_decode_bf16", benchmark config 3):
+      dag_kv_append_rope -> dag_attn_decode (shared-prefix items + own items + LSE merge)
+Inputs are resident in HBM before the timed region.  `value` is the prefill segment's useful
+TFLOP/s (4*D*Hq*visible pairs / segment time); the decode segment is reported in "decode".
+Prints ONE JSON line on stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2602_07529_amd import binding as B  # noqa: E402
+from workloads import dags  # noqa: E402
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+
+
+def _ensure_built():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2602_07529_amd import build
+        build.build()
+
+
+class PrefillWork:
+    def __init__(self, cfg, dev):
+        self.cfg = cfg
+        self.dag_list = dags.config_dags(cfg)
+        self.T = int(sum(int(np.sum(L)) for L, _ in self.dag_list))
+        hq, hkv, d = cfg["hq"], cfg["hkv"], cfg["d"]
+        dtype = torch.float32 if cfg["dtype"] == "f32" else torch.bfloat16
+        q, k, v = dags.make_qkv(cfg["seed"], self.T, hq, hkv, d, cfg["scale"], dtype)
+        self.q0, self.k0, self.v = q.to(dev), k.to(dev), v.to(dev)
+        self.q, self.k = torch.empty_like(self.q0), torch.empty_like(self.k0)
+        self.out = torch.empty_like(self.q0)
+        code = B.DAG_F32 if dtype == torch.float32 else B.DAG_BF16
+        tm, tn = B.dag_prefill_tile_shape(hq, hkv, d, code)
+        off, lens, bits, W = dags.batch_desc(self.dag_list)
+        self.desc = B.DagDesc(off, lens, bits, W, tm, tn, 0)
+        self.meta = B.DagMeta(self.desc, B.dag_meta_sizes(self.desc), dev)
+        self.theta = cfg["theta"]
+        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+
+    def refresh_inputs(self):
+        """Untimed: restore the un-rotated Q/K (RoPE works in place)."""
+        self.q.copy_(self.q0)
+        self.k.copy_(self.k0)
+
+    def run(self, timed=False):
+        if timed:
+            self.ev[0].record()
+        B.dag_build_meta(self.desc, self.meta)
+        B.dag_rope_qk(self.meta.get("pos_ids"), self.q, self.k, self.theta)
+        if timed:
+            self.ev[1].record()
+        B.dag_attn_prefill(self.meta, self.q, self.k, self.v, self.out)
+        if timed:
+            self.ev[2].record()
+
+    def useful_flops(self):
+        pairs = int(self.meta.get("useful_pairs").sum().item())
+        return 4.0 * self.cfg["d"] * self.cfg["hq"] * pairs, pairs
+
+
+class DecodeWork:
+    def __init__(self, cfg, dev):
+        self.cfg = cfg
+        st = dags.decode_state(cfg["seed"], cfg["n_seqs"], cfg["n_branch"], cfg["shared"], cfg["branch"],
+                               cfg["hq"], cfg["hkv"], cfg["d"])
+        self.desc_np = st["desc"]
+        self.dd = B.DecodeDesc(st["desc"], dev)
+        self.kp, self.vp = st["k_pool"].to(dev), st["v_pool"].to(dev)
+        self.q, self.k_new, self.v_new = st["q"].to(dev), st["k_new"].to(dev), st["v_new"].to(dev)
+        self.out = torch.empty_like(self.q)
+        self.ws = torch.empty(B.dag_decode_workspace_bytes(self.dd, cfg["hq"], cfg["hkv"], cfg["d"]),
+                              dtype=torch.uint8, device=dev)
+        self.bytes = dags.decode_algorithmic_bytes(st["desc"], cfg["hkv"], cfg["d"])
+        self.n_live = st["desc"]["n_live"]
+        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def run(self, timed=False):
+        if timed:
+            self.ev[0].record()
+        B.dag_kv_append_rope(self.dd, self.k_new, self.v_new, self.kp, self.vp, self.cfg["theta"])
+        if timed:
+            self.ev[1].record()
+        B.dag_attn_decode(self.dd, self.q, self.kp, self.vp, self.out, self.ws)
+        if timed:
+            self.ev[2].record()
+
+
+def cpu_baseline(pw):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the prefill workload:
+    sequence 0, every row, every query head."""
+    from oracle import dag_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    cfg = pw.cfg
+    L, anc = pw.dag_list[0]
+    Tb = int(np.sum(L))
+    G = cfg["hq"] // cfg["hkv"]
+    heads = list(range(cfg["hq"]))
+    q64 = dags.to_f64(pw.q0[:Tb].cpu())
+    k64 = dags.to_f64(pw.k0[:Tb].cpu())
+    v64 = dags.to_f64(pw.v[:Tb].cpu())
+    t0 = time.perf_counter()
+    _, pos = orc.token_meta(L, anc)
+    qs, ks = orc.rope(q64, pos, cfg["theta"]), orc.rope(k64, pos, cfg["theta"])
+    orc.attn_prefill(qs, ks, v64, L, anc, heads=heads)
+    dt = time.perf_counter() - t0
+    pairs = orc.useful_pairs(L, anc)
+    flops = 4.0 * cfg["d"] * len(heads) * pairs
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "sequence 0 of %d, all %d rows, %d of %d query heads, fp64 numpy; %.1f s"
+                      % (cfg["batch"], Tb, len(heads), cfg["hq"], dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (one-GPU boxes; the path shards without "
+              "exchange inside attention, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    _ensure_built()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    pw = PrefillWork(dags.config(1), dev)
+    dw = DecodeWork(dags.config(2), dev)
+
+    for _ in range(args.warmup):
+        pw.refresh_inputs()
+        pw.run()
+        dw.run()
+    torch.cuda.synchronize()
+
+    step_ms, pre_ms, attn_ms, dec_ms, deck_ms = [], [], [], [], []
+    wall0 = time.perf_counter()
+    for _ in range(args.steps):
+        pw.refresh_inputs()          # untimed restore of the raw Q/K
+        torch.cuda.synchronize()
+        pw.run(timed=True)
+        dw.run(timed=True)
+        torch.cuda.synchronize()
+        p_total = pw.ev[0].elapsed_time(pw.ev[2])
+        d_total = dw.ev[0].elapsed_time(dw.ev[2])
+        pre_ms.append(p_total)
+        attn_ms.append(pw.ev[1].elapsed_time(pw.ev[2]))
+        dec_ms.append(d_total)
+        deck_ms.append(dw.ev[1].elapsed_time(dw.ev[2]))
+        step_ms.append(pw.ev[0].elapsed_time(dw.ev[2]))
+    wall = time.perf_counter() - wall0
+
+    flops, pairs = pw.useful_flops()
+    mean = lambda xs: float(np.mean(xs))
+    ms_step, ms_pre, ms_attn, ms_dec, ms_deck = map(mean, (step_ms, pre_ms, attn_ms, dec_ms, deck_ms))
+    tflops_seg = flops / (ms_pre * 1e-3) / 1e12
+    tflops_kernel = flops / (ms_attn * 1e-3) / 1e12
+    dec_gbs = dw.bytes / (ms_deck * 1e-3) / 1e9
+    cfg = pw.cfg
+    res = {
+        "metric": "dag_attn_prefill_useful_tflops",
+        "value": tflops_seg,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg["name"], "batch": cfg["batch"], "tokens_per_seq": pw.T // cfg["batch"],
+                   "dag": "prefix %d -> %d branches x %d -> join %d" % (cfg["prefix"], cfg["n_branch"], cfg["branch"], cfg["join"]),
+                   "hq": cfg["hq"], "hkv": cfg["hkv"], "head_dim": cfg["d"], "useful_pairs": pairs,
+                   "decode_workload": dw.cfg["name"]},
+        "segments_ms": {"prefill_path(meta+rope+attn)": ms_pre, "prefill_attn_kernel": ms_attn,
+                        "decode_path(append+attn+merge)": ms_dec, "decode_attn_kernels": ms_deck,
+                        "min_prefill_attn_kernel": float(np.min(attn_ms)), "min_decode_attn_kernels": float(np.min(deck_ms))},
+        "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16", "achieved": tflops_kernel,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops_kernel / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None},
+        "decode": {"metric": "branch_decode_tok_per_s_one_attention_layer",
+                   "value": dw.n_live / (ms_dec * 1e-3), "unit": "tok/s", "ms_per_decode_step": ms_dec,
+                   "config": {"workload": dw.cfg["name"], "n_seqs": dw.cfg["n_seqs"], "live_branches": dw.n_live,
+                              "shared_prefix": dw.cfg["shared"], "branch_len": dw.cfg["branch"], "page_size": 16},
+                   "roofline": {"bound": "hbm", "kernel": "k_decode(+k_decode_merge)", "achieved": dec_gbs,
+                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
+                                "algorithmic_bytes": dw.bytes, "traffic": None}},
+        "wall_s_timed_loop": wall,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(pw)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
