@@ -97,9 +97,11 @@ typedef struct {
   int32_t* qtile_start;    /* [n_seqs+1] index of each sequence's first query tile             */
   int64_t* block_map_off;  /* [n_seqs+1] offset of each sequence's dense map                   */
   uint8_t* block_map;      /* [total_tiles] per sequence row-major [QT_b][KT_b], DAG_TILE_*    */
-  int32_t* qtile_rowptr;   /* [total_qtiles+1] CSR over non-skip tiles, key tiles ascending    */
+  int32_t* qtile_rowptr;   /* [total_qtiles+1] CSR over non-skip tiles; within a row the FULL
+                              tiles come first (key tiles ascending), then the PARTIAL ones   */
   int32_t* qtile_col;      /* [csr_capacity] key-tile index                                    */
   uint8_t* qtile_flag;     /* [csr_capacity] DAG_TILE_PARTIAL or DAG_TILE_FULL                 */
+  int32_t* qtile_nfull;    /* [total_qtiles] number of FULL tiles in the row                   */
   int32_t* qtile_order;    /* [total_qtiles] query tiles sorted by descending tile count
                               (ties: ascending index); the prefill launch order                */
   int64_t* useful_pairs;   /* [n_seqs] number of visible (query, key) pairs                    */

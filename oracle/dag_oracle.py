@@ -156,6 +156,25 @@ def block_map_csr(bmap):
     return row_ptr, np.array(col, dtype=np.int64), np.array(flag, dtype=np.uint8)
 
 
+def block_map_csr_full_first(bmap):
+    """The library's CSR row order: within a row the FULL tiles first (key tiles ascending), then
+    the PARTIAL tiles (ascending).  Also returns the number of FULL tiles per row."""
+    QT, KT = bmap.shape
+    row_ptr = np.zeros(QT + 1, dtype=np.int64)
+    nfull = np.zeros(QT, dtype=np.int64)
+    col, flag = [], []
+    for a in range(QT):
+        for want in (FULL, PARTIAL):
+            for b in range(KT):
+                if bmap[a, b] == want:
+                    col.append(b)
+                    flag.append(want)
+            if want == FULL:
+                nfull[a] = len(col) - row_ptr[a]
+        row_ptr[a + 1] = len(col)
+    return row_ptr, np.array(col, dtype=np.int64), np.array(flag, dtype=np.uint8), nfull
+
+
 # ----------------------------------------------------------------------------- rotary embedding
 def rope(x, pos, theta):
     """Rotate x[T][H][D] (any float dtype, upcast to fp64) by angle pos[t] * theta^(-2m/D).

@@ -40,7 +40,7 @@ _META_ARRAYS = [("cu_seqlens", torch.int32), ("node_start", torch.int32), ("tok_
                 ("pos_ids", torch.int32), ("node_tok_start", torch.int32), ("node_pos_start", torch.int32),
                 ("node_vis", torch.int64), ("qtile_start", torch.int32), ("block_map_off", torch.int64),
                 ("block_map", torch.uint8), ("qtile_rowptr", torch.int32), ("qtile_col", torch.int32),
-                ("qtile_flag", torch.uint8), ("qtile_order", torch.int32), ("useful_pairs", torch.int64)]
+                ("qtile_flag", torch.uint8), ("qtile_nfull", torch.int32), ("qtile_order", torch.int32), ("useful_pairs", torch.int64)]
 
 
 class dag_meta_t(C.Structure):
@@ -156,7 +156,7 @@ class DagMeta:
                       node_pos_start=sizes.total_nodes, node_vis=sizes.total_nodes * W,
                       qtile_start=n + 1, block_map_off=n + 1, block_map=sizes.total_tiles,
                       qtile_rowptr=sizes.total_qtiles + 1, qtile_col=sizes.csr_capacity,
-                      qtile_flag=sizes.csr_capacity, qtile_order=sizes.total_qtiles, useful_pairs=n)
+                      qtile_flag=sizes.csr_capacity, qtile_nfull=sizes.total_qtiles, qtile_order=sizes.total_qtiles, useful_pairs=n)
         self.sizes = sizes
         self.t = {name: torch.empty(max(int(counts[name]), 1), dtype=dt, device=device)
                   for name, dt in _META_ARRAYS}

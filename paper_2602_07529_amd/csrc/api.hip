@@ -16,7 +16,7 @@ extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* 
   if (m->n_seqs == 0 || m->sizes.total_tokens == 0) return DAG_OK;
   if (!q || !k || !v || !out) return DAG_ERR_NULL;
   if (!m->cu_seqlens || !m->node_start || !m->tok_node || !m->node_vis || !m->qtile_start || !m->qtile_rowptr ||
-      !m->qtile_col || !m->qtile_flag || !m->qtile_order)
+      !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order)
     return DAG_ERR_NULL;
   if (!dag_aligned16(q) || !dag_aligned16(k) || !dag_aligned16(v) || !dag_aligned16(out)) return DAG_ERR_ALIGN;
   if (m->sizes.total_qtiles * (int64_t)hq > INT32_MAX) return DAG_ERR_UNSUPPORTED;
@@ -34,6 +34,7 @@ extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* 
   a.rowptr = m->qtile_rowptr;
   a.col = m->qtile_col;
   a.flag = m->qtile_flag;
+  a.nfull = m->qtile_nfull;
   a.qtile_order = m->qtile_order;
   a.n_seqs = m->n_seqs;
   a.W = m->words_per_node;

@@ -283,27 +283,32 @@ __global__ void __launch_bounds__(1024) k_csr_scan(int total_qtiles, const int32
   if (threadIdx.x == 0) rowptr[total_qtiles] = carry;
 }
 
-// One wave per query tile: ordered compaction of the non-skip tiles.
+// One wave per query tile: ordered compaction of the non-skip tiles -- FULL tiles first (key
+// tiles ascending), then PARTIAL tiles (ascending) -- and the number of FULL tiles.
 __global__ void __launch_bounds__(64) k_csr_fill(int n_seqs, const int32_t* qtile_start,
                                                  const int64_t* block_map_off, const int32_t* cu_seqlens,
                                                  int tile_n, const uint8_t* block_map, const int32_t* rowptr,
-                                                 int32_t* col, uint8_t* flag) {
+                                                 int32_t* col, uint8_t* flag, int32_t* nfull) {
   const int qt = blockIdx.x, lane = threadIdx.x;
   const int b = dag_find_segment(qtile_start, n_seqs, qt);
   const int T = cu_seqlens[b + 1] - cu_seqlens[b];
   const int KT = (T + tile_n - 1) / tile_n;
   const uint8_t* row = block_map + block_map_off[b] + (int64_t)(qt - qtile_start[b]) * KT;
   int out = rowptr[qt];
-  for (int k0 = 0; k0 < KT; k0 += 64) {
-    const int k = k0 + lane;
-    const uint8_t f = k < KT ? row[k] : (uint8_t)DAG_TILE_SKIP;
-    const uint64_t m = __ballot(f != DAG_TILE_SKIP);
-    if (f != DAG_TILE_SKIP) {
-      const int p = out + __popcll(m & ((1ull << lane) - 1));
-      col[p] = k;
-      flag[p] = f;
+  for (int pass = 0; pass < 2; ++pass) {
+    const uint8_t want = pass == 0 ? DAG_TILE_FULL : DAG_TILE_PARTIAL;
+    for (int k0 = 0; k0 < KT; k0 += 64) {
+      const int k = k0 + lane;
+      const uint8_t f = k < KT ? row[k] : (uint8_t)DAG_TILE_SKIP;
+      const uint64_t m = __ballot(f == want);
+      if (f == want) {
+        const int p = out + __popcll(m & ((1ull << lane) - 1));
+        col[p] = k;
+        flag[p] = f;
+      }
+      out += __popcll(m);
     }
-    out += __popcll(m);
+    if (pass == 0 && lane == 0) nfull[qt] = out - rowptr[qt];
   }
 }
 
@@ -340,13 +345,9 @@ extern "C" int dag_prefill_tile_shape(int32_t hq, int32_t hkv, int32_t head_dim,
     return DAG_OK;
   }
   if (dtype != DAG_BF16) return DAG_ERR_UNSUPPORTED;
-  const int g = hq / hkv;
-  // A workgroup stacks the query heads of one KV head: (heads per workgroup) x (32-row blocks).
-  int rb;
-  if (g % 4 == 0 || g == 5) rb = 1;   // 4 or 5 heads x 1 row block
-  else if (g % 2 == 0) rb = 2;        // 2 heads x 2 row blocks
-  else rb = 4;                        // 1 head x 4 row blocks
-  *tile_m = 32 * rb;
+  // A workgroup owns two 32-row blocks of up to four stacked query heads: 64 query rows, and key
+  // tiles of 64 tokens, for every head configuration.
+  *tile_m = 64;
   *tile_n = 64;
   return DAG_OK;
 }
@@ -370,7 +371,7 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
   if (!m->cu_seqlens || !m->node_start || !m->qtile_start || !m->block_map_off || !m->qtile_rowptr || !m->useful_pairs)
     return DAG_ERR_NULL;
   if (s.total_tokens > 0 && (!m->tok_node || !m->pos_ids || !m->node_tok_start || !m->node_pos_start ||
-                             !m->node_vis || !m->block_map || !m->qtile_col || !m->qtile_flag || !m->qtile_order))
+                             !m->node_vis || !m->block_map || !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order))
     return DAG_ERR_NULL;
   rc = host_validate_bits(d);
   if (rc != DAG_OK) return rc;
@@ -422,7 +423,8 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
   hipLaunchKernelGGL(k_csr_scan, dim3(1), dim3(1024), 0, stream, (int)QT, d_cnt, m->qtile_rowptr);
   DAG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_csr_fill, dim3(QT), dim3(64), 0, stream, d->n_seqs, m->qtile_start, m->block_map_off,
-                     m->cu_seqlens, d->tile_n, m->block_map, m->qtile_rowptr, m->qtile_col, m->qtile_flag);
+                     m->cu_seqlens, d->tile_n, m->block_map, m->qtile_rowptr, m->qtile_col, m->qtile_flag,
+                     m->qtile_nfull);
   DAG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_order, dim3((QT + 255) / 256), dim3(256), 0, stream, (int)QT, d_cnt, m->qtile_order);
   DAG_LAUNCH_CHECK();

@@ -1,38 +1,47 @@
 // bf16 DAG attention prefill for gfx950 (paper Eq. 2 + Eq. 3), MFMA 32x32x16 with fp32 accumulation.
 //
-// Work decomposition.  A workgroup owns one query tile (32*RB token rows) of one KV head and stacks
-// HG of that KV head's query heads: wave w handles row block w / HG and head w % HG, so every wave
-// of the workgroup consumes the same K/V tiles.  K/V tiles of 64 tokens are staged through LDS
-// (double buffered, one barrier per tile); only the tiles the CSR block map lists are visited and
-// only PARTIAL (or ragged) tiles evaluate the per-token mask.
+// Work decomposition.  A workgroup owns one 64-row query tile of one KV head and stacks HG of that
+// KV head's query heads: wave w handles the 32-row block w / HG of head w % HG, so every wave of
+// the workgroup consumes the same K/V tiles.  With HG = 4 that is eight waves, two per SIMD, so
+// that one wave's softmax (vector ALU) overlaps the other's MFMAs.  Only the key tiles the block
+// map lists are visited.  The CSR row of a query tile lists its FULL tiles first: those run in a
+// loop that contains no mask code at all; the PARTIAL tiles (and a ragged last tile) follow in a
+// second loop that evaluates the per-token mask.
+//
+// Data movement.  K and V tiles of 64 tokens go from global memory straight into LDS
+// (global_load_lds, 16 bytes per lane, no staging registers) through a ring of NSTAGE buffers:
+// the loads of the next NSTAGE-1 tiles are in flight while a tile is computed, one barrier per
+// tile.  A wave-level load writes 1 KiB of consecutive LDS, so the bank-conflict-avoiding XOR
+// swizzle is applied to the *source* address each lane fetches:
+//   K tile [64 keys][D]  16-byte chunk c of key r is stored at chunk c ^ swzK(r)
+//   V tile [64 keys][D]  16-byte chunk c of key r is stored at chunk c ^ swzV(r)
 //
 // Register layout.  Scores are computed transposed, S^T = K Q^T, so that after the MFMA a lane
-// holds one query row (lane % 32) and 16 keys of each 32-key block in registers: the softmax
-// row reductions are in-register plus one exchange between the two half waves, and the
-// probabilities already sit in the B-operand layout of the second product O^T = V^T P^T.
-// The MFMA row i of a 32-key block is mapped to key pi(i) so that registers 0..7 / 8..15 of the
-// score block hold 8 consecutive keys; V is transposed while it is staged so that a lane reads its
-// 8 keys for one output dimension with a single 16-byte LDS load.
+// holds one query row (lane % 32) and 16 keys of each 32-key block in registers: the softmax row
+// reductions are in-register plus one exchange between the two half waves, and the probabilities
+// already sit in the B-operand layout of the second product O^T = V^T P^T.  MFMA row i of a
+// 32-key block is mapped to key pi(i) so that registers 0..7 / 8..15 of a score block hold 8
+// consecutive keys.  The V^T operand (8 keys of one output dimension per lane) is read from the
+// row-major V tile with the LDS transpose load ds_read_tr16_b64.
 //
-// LDS layouts (XOR swizzles at 16-byte granularity; reads are conflict free):
-//   K tile  [64 keys][D]      chunk' = chunk ^ fK(key)
-//   V^T tile [D][64 keys]     chunk' = chunk ^ gV(d)
+// Softmax.  Online softmax in the log2 domain.  The running maximum is only raised when some row
+// of the wave exceeds it by more than 2^8 (the accumulator rescale is then rare); probabilities
+// may exceed 1 by that factor, which fp32 accumulation and the final division absorb exactly.
 #include "common.h"
 #include "prefill_launch.h"
 
 namespace {
 
 constexpr int TN = 64;
+constexpr int TM = 64;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(8))) float f32x8;
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-typedef __attribute__((ext_vector_type(8))) float f32x8;
-
-__device__ __forceinline__ bf16x8 cvt8(const float* p) {
-  f32x8 v = {p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]};
-  return __builtin_convertvector(v, bf16x8);
 }
 
 // MFMA row i (0..31) of a 32-key block -> key index inside the block.
@@ -40,29 +49,40 @@ __device__ __forceinline__ int key_of_row(int i) {
   const int a = i >> 3, hh = (i >> 2) & 1, c = i & 3;
   return 16 * (a >> 1) + 8 * hh + 4 * (a & 1) + c;
 }
-
 template <int D>
-__device__ __forceinline__ int fK(int key) {
-  return D == 128 ? (key & 15) : ((key >> 1) & 7);
+__device__ __forceinline__ int swzK(int row) {
+  return D == 128 ? (row & 15) : ((row >> 1) & 7);
 }
-__device__ __forceinline__ int gV(int d) {
-  const int L = d & 31;
-  return ((L >> 1) ^ (L >> 4)) & 7;
+template <int D>
+__device__ __forceinline__ int swzV(int row) {
+  return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
 }
 
-template <int D, int HG, int RB>
-__global__ void __launch_bounds__(64 * HG * RB) k_prefill_bf16(PrefillArgs a) {
-  constexpr int NW = HG * RB, NT = 64 * NW, TM = 32 * RB;
-  constexpr int CH = D / 8;       // 16-byte chunks per K row
-  constexpr int KSTEPS = D / 16;  // MFMA steps of the score product
-  constexpr int DB = D / 32;      // 32-row blocks of O^T
-  constexpr int KCHUNKS = TN * CH, NKC = (KCHUNKS + NT - 1) / NT;
-  constexpr int VTASKS = (TN / 8) * (D / 4), NVT = (VTASKS + NT - 1) / NT;
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  uint16_t* Ks = (uint16_t*)smem_raw;          // [2][TN*D]
-  uint16_t* Vs = Ks + 2 * TN * D;              // [2][D*TN]
-  int* s_node = (int*)(Vs + 2 * D * TN);       // [2][TN]
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {  // s_waitcnt vmcnt(N) only (gfx9 encoding)
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int D, int HG, int NSTAGE>
+__global__ void __launch_bounds__(128 * HG, (HG == 4 ? 1 : 2)) k_prefill_bf16(PrefillArgs a) {
+  constexpr int NW = 2 * HG;                 // waves: two 32-row blocks x HG heads
+  constexpr int CH = D / 8;                  // 16-byte chunks per row
+  constexpr int KSTEPS = D / 16;             // MFMA steps of the score product
+  constexpr int DB = D / 32;                 // 32-row blocks of O^T
+  constexpr int RPI = 64 / CH;               // tile rows covered by one wave-level load
+  constexpr int IPW = TN / RPI / NW;         // wave-level loads per tile, tensor and wave
+  constexpr int LPT = 2 * IPW;               // loads per tile and wave (K and V)
+  constexpr int TILE_BYTES = TN * D * 2;
+  constexpr float TH_LOG2 = 8.f;
+  static_assert(IPW >= 1 && IPW * RPI * NW == TN, "tile loads must divide evenly over the waves");
+  static_assert((NSTAGE - 2) * LPT < 64, "vmcnt range");
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  // layout: K[NSTAGE][TILE_BYTES], V[NSTAGE][TILE_BYTES]
+  unsigned char* const Kbase = smem;
+  unsigned char* const Vbase = smem + NSTAGE * TILE_BYTES;
 
   const int G = a.hq / a.hkv;
   const int HS = G / HG;  // workgroups per KV head
@@ -78,30 +98,75 @@ __global__ void __launch_bounds__(64 * HG * RB) k_prefill_bf16(PrefillArgs a) {
   const int L = lane & 31, H = lane >> 5;
   const int rb = w / HG, hj = w % HG;
   const int head = hk * G + hs * HG + hj;
-  const int i_row = row0 + 32 * rb + L;         // row inside the sequence
+  const int i_row = row0 + 32 * rb + L;  // row inside the sequence
   const int tok = cu + min(i_row, T - 1);
 
   const uint16_t* qg = (const uint16_t*)a.q;
-  const uint16_t* kg = (const uint16_t*)a.k;
-  const uint16_t* vg = (const uint16_t*)a.v;
+  const unsigned char* kg = (const unsigned char*)a.k;
+  const unsigned char* vg = (const unsigned char*)a.v;
+  const uint32_t rowbytes = (uint32_t)a.hkv * D * 2;
 
   bf16x8 qf[KSTEPS];
 #pragma unroll
   for (int s = 0; s < KSTEPS; ++s)
     qf[s] = *(const bf16x8*)(qg + ((size_t)tok * a.hq + head) * D + 16 * s + 8 * H);
 
-  const int node_i = a.tok_node[tok];
-  const uint64_t* vis_row = a.node_vis + (int64_t)(a.node_start[b] + node_i) * a.W;
-  const uint64_t vis0 = vis_row[0];
+  // Source offsets of this lane's tile loads.  Load i of the wave covers rows RPI*(w + NW*i) ...;
+  // when NW is a multiple of 4 the swizzle terms do not depend on i and one offset serves all.
+  constexpr bool UNIFORM_SRC = (NW % 4 == 0);
+  constexpr int NSRC = UNIFORM_SRC ? 1 : IPW;
+  const int pos = lane % CH;
+  uint32_t ksrc[NSRC], vsrc[NSRC];
+#pragma unroll
+  for (int i = 0; i < NSRC; ++i) {
+    const int r = (w + NW * i) * RPI + lane / CH;
+    ksrc[i] = r * rowbytes + ((pos ^ swzK<D>(r)) * 16);
+    vsrc[i] = r * rowbytes + ((pos ^ swzV<D>(r)) * 16);
+  }
 
-  // per-lane LDS read offsets (elements)
+  auto issue_loads = [&](int buf, int j0) {
+    const unsigned char* kt = kg + ((size_t)(cu + j0) * a.hkv + hk) * (D * 2);
+    const unsigned char* vt = vg + ((size_t)(cu + j0) * a.hkv + hk) * (D * 2);
+    unsigned char* kl = Kbase + buf * TILE_BYTES + w * 1024;
+    unsigned char* vl = Vbase + buf * TILE_BYTES + w * 1024;
+    if (j0 + TN <= T) {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const size_t step = UNIFORM_SRC ? (size_t)i * (RPI * NW) * rowbytes : 0;
+        const uint32_t ks = ksrc[UNIFORM_SRC ? 0 : i], vs = vsrc[UNIFORM_SRC ? 0 : i];
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kt + step + ks), (lds_ptr_t)(kl + i * NW * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vt + step + vs), (lds_ptr_t)(vl + i * NW * 1024), 16, 0, 0);
+      }
+    } else {  // ragged last tile: rows past the end re-read the last valid row (masked later)
+      const int last = T - 1 - j0;
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int r = (w + NW * i) * RPI + lane / CH;
+        const uint32_t rc = (uint32_t)min(r, last) * rowbytes;
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kt + rc + ((pos ^ swzK<D>(r)) * 16)),
+                                         (lds_ptr_t)(kl + i * NW * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vt + rc + ((pos ^ swzV<D>(r)) * 16)),
+                                         (lds_ptr_t)(vl + i * NW * 1024), 16, 0, 0);
+      }
+    }
+  };
+
+  // per-lane LDS read offsets (bytes inside a tile)
   const int krow = key_of_row(L);
-  int koff[KSTEPS];
+  uint32_t koff[KSTEPS];
 #pragma unroll
-  for (int s = 0; s < KSTEPS; ++s) koff[s] = krow * D + (((2 * s + H) ^ fK<D>(krow)) * 8);
-  int voff[4];  // index 2*kb + t: chunk 4kb + 2t + H of V^T row L
+  for (int s = 0; s < KSTEPS; ++s) koff[s] = krow * (D * 2) + (((2 * s + H) ^ swzK<D>(krow)) * 16);
+  // transpose read: within a 16-lane group, lane j = 4e + c addresses key e (of 4), 8-byte piece c
+  const int tr_e = (lane & 15) >> 2, tr_c = lane & 3, dhalf = (lane >> 4) & 1;
+  uint32_t voff[2][DB];  // [rd][db]: keys 8H + 4rd + e of the first 16-key step; a step adds 16 rows
 #pragma unroll
-  for (int c = 0; c < 4; ++c) voff[c] = L * TN + ((((2 * c + H) ^ gV(L)) & 7) * 8);
+  for (int rd = 0; rd < 2; ++rd)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const int key = 8 * H + 4 * rd + tr_e;
+      const int c16 = 4 * db + 2 * dhalf + (tr_c >> 1);
+      voff[rd][db] = key * (D * 2) + ((c16 ^ swzV<D>(key)) * 16) + (tr_c & 1) * 8;
+    }
 
   f32x16 O[DB];
 #pragma unroll
@@ -110,156 +175,117 @@ __global__ void __launch_bounds__(64 * HG * RB) k_prefill_bf16(PrefillArgs a) {
     for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
   float m = -1e30f, l = 0.f;
   const float sc = a.scale * 1.4426950408889634f;
+  const float th = TH_LOG2 / sc;  // threshold in raw score units
 
-  // staging registers
-  u32x4 kst[NKC];
-  u32x2 vst[NVT][8];
-  int nst = 0;
-
-  auto stage_load = [&](int kt) {
-    const int j0 = kt * TN;
-#pragma unroll
-    for (int n = 0; n < NKC; ++n) {
-      const int c = tid + n * NT;
-      if (KCHUNKS % NT == 0 || c < KCHUNKS) {
-        const int row = c / CH, ch = c % CH;
-        const int jc = min(j0 + row, T - 1);
-        kst[n] = *(const u32x4*)(kg + ((size_t)(cu + jc) * a.hkv + hk) * D + ch * 8);
-      }
-    }
-#pragma unroll
-    for (int n = 0; n < NVT; ++n) {
-      const int c = tid + n * NT;
-      if (VTASKS % NT == 0 || c < VTASKS) {
-        const int kgp = c / (D / 4), dg = c % (D / 4);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int jc = min(j0 + 8 * kgp + e, T - 1);
-          vst[n][e] = *(const u32x2*)(vg + ((size_t)(cu + jc) * a.hkv + hk) * D + dg * 4);
-        }
-      }
-    }
-    if (tid < TN) nst = a.tok_node[cu + min(j0 + tid, T - 1)];
-  };
-
-  auto stage_store = [&](int buf) {
-    uint16_t* Kb = Ks + buf * TN * D;
-    uint16_t* Vb = Vs + buf * D * TN;
-#pragma unroll
-    for (int n = 0; n < NKC; ++n) {
-      const int c = tid + n * NT;
-      if (KCHUNKS % NT == 0 || c < KCHUNKS) {
-        const int row = c / CH, ch = c % CH;
-        *(u32x4*)(Kb + row * D + ((ch ^ fK<D>(row)) * 8)) = kst[n];
-      }
-    }
-#pragma unroll
-    for (int n = 0; n < NVT; ++n) {
-      const int c = tid + n * NT;
-      if (VTASKS % NT == 0 || c < VTASKS) {
-        const int kgp = c / (D / 4), dg = c % (D / 4);
-#pragma unroll
-        for (int dd = 0; dd < 4; ++dd) {
-          u32x4 o;
-#pragma unroll
-          for (int e2 = 0; e2 < 4; ++e2) {
-            const uint32_t lo = vst[n][2 * e2][dd >> 1], hi = vst[n][2 * e2 + 1][dd >> 1];
-            o[e2] = (dd & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-          }
-          const int d = dg * 4 + dd;
-          *(u32x4*)(Vb + d * TN + ((kgp ^ gV(d)) * 8)) = o;
-        }
-      }
-    }
-    if (tid < TN) s_node[buf * TN + tid] = nst;
-  };
-
-  const int c0 = a.rowptr[qt], c1 = a.rowptr[qt + 1];
-  if (c0 < c1) {
-    stage_load(a.col[c0]);
-    stage_store(0);
-  }
-  __syncthreads();
-
-  for (int it = c0; it < c1; ++it) {
-    const int buf = (it - c0) & 1;
-    const int kt = a.col[it];
-    const int j0 = kt * TN;
-    const bool need_mask = (a.flag[it] != DAG_TILE_FULL) || (j0 + TN > T);
-    const bool has_next = it + 1 < c1;
-    if (has_next) stage_load(a.col[it + 1]);
-
-    const uint16_t* Kb = Ks + buf * TN * D;
-    const uint16_t* Vb = Vs + buf * D * TN;
-
-    f32x16 S[2];
+  auto scores = [&](const unsigned char* Kb, f32x16* S) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
 #pragma unroll
       for (int s = 0; s < KSTEPS; ++s) {
-        const bf16x8 kf = *(const bf16x8*)(Kb + kb * 32 * D + koff[s]);
+        const bf16x8 kf = *(const bf16x8*)(Kb + kb * 32 * (D * 2) + koff[s]);
         S[kb] = mfma32(kf, qf[s], S[kb]);
       }
     }
+  };
 
-    if (need_mask) {
-      const int* sn = s_node + buf * TN;
+  // online softmax + accumulation of one tile whose scores are in S
+  auto softmax_accumulate = [&](const unsigned char* Vb, const f32x16* S) {
+    float bm = max3(S[0][0], S[0][1], S[0][2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) bm = max3(bm, S[0][r], S[0][r + 1]);
+    bm = fmaxf(bm, S[0][15]);
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) bm = max3(bm, S[1][r], S[1][r + 1]);
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    if (__builtin_amdgcn_ballot_w64(bm > m + th) != 0) {  // rare after the first tiles
+      const float m_new = fmaxf(m, bm);
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * sc);
+      m = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) O[db][r] *= alpha;
+    }
+    const float msc = m * sc;
+    float rowsum = 0.f;
+    bf16x8 pb[4];
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      f32x8 p;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(fmaf(S[st >> 1][8 * (st & 1) + e], sc, -msc));
+        rowsum += p[e];
+      }
+      pb[st] = __builtin_convertvector(p, bf16x8);
+    }
+    l += rowsum;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {  // keys 16*st + 8H .. +7
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(Vb + st * 16 * (D * 2) + voff[0][db]));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(Vb + st * 16 * (D * 2) + voff[1][db]));
+        const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        O[db] = mfma32(__builtin_bit_cast(bf16x8, v8), pb[st], O[db]);
+      }
+    }
+  };
+
+  const int c0 = a.rowptr[qt], c1 = a.rowptr[qt + 1];
+  // FULL tiles come first in the row; a ragged last key tile needs the masked loop as well
+  int c_fast = c0 + a.nfull[qt];
+  if (c_fast > c0 && a.col[c_fast - 1] * TN + TN > T) --c_fast;
+
+  // Ring pipeline step shared by both loops: wait for tile `it`, barrier, refill the freed buffer.
+  auto advance = [&](int it) {
+    const int ahead = min(NSTAGE - 2, c1 - 1 - it);  // later tiles whose loads may stay in flight
+    if (NSTAGE > 3 && ahead >= 2) wait_vmcnt<(NSTAGE > 3 ? 2 : 0) * LPT>();
+    else if (NSTAGE > 2 && ahead == 1) wait_vmcnt<(NSTAGE > 2 ? 1 : 0) * LPT>();
+    else wait_vmcnt<0>();
+    __syncthreads();  // everyone's loads have landed, and everyone has left the buffer refilled next
+    if (it + NSTAGE - 1 < c1) issue_loads((it - c0 + NSTAGE - 1) % NSTAGE, a.col[it + NSTAGE - 1] * TN);
+  };
+
+#pragma unroll
+  for (int p = 0; p < NSTAGE - 1; ++p)
+    if (c0 + p < c1) issue_loads(p, a.col[c0 + p] * TN);
+
+  for (int it = c0; it < c_fast; ++it) {  // FULL tiles: no mask
+    advance(it);
+    const int buf = (it - c0) % NSTAGE;
+    f32x16 S[2];
+    scores(Kbase + buf * TILE_BYTES, S);
+    softmax_accumulate(Vbase + buf * TILE_BYTES, S);
+  }
+
+  if (c_fast < c1) {  // PARTIAL / ragged tiles: per-token mask
+    const uint64_t* vis_row = a.node_vis + (int64_t)(a.node_start[b] + a.tok_node[tok]) * a.W;
+    const uint64_t vis0 = vis_row[0];
+    const int32_t* tn = a.tok_node + cu;
+    for (int it = c_fast; it < c1; ++it) {
+      advance(it);
+      const int buf = (it - c0) % NSTAGE;
+      const int j0 = a.col[it] * TN;
+      f32x16 S[2];
+      scores(Kbase + buf * TILE_BYTES, S);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int kl = 32 * kb + 16 * (r >> 3) + 8 * H + (r & 7);
-          const int j = j0 + kl;
-          const int nj = sn[kl];
+          const int j = j0 + 32 * kb + 16 * (r >> 3) + 8 * H + (r & 7);
+          const int nj = tn[min(j, T - 1)];
           const uint64_t word = (a.W == 1) ? vis0 : vis_row[nj >> 6];
           const bool ok = (j <= i_row) && (j < T) && ((word >> (nj & 63)) & 1);
           S[kb][r] = ok ? S[kb][r] : -INFINITY;
         }
+      softmax_accumulate(Vbase + buf * TILE_BYTES, S);
     }
-
-    float bm = S[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) bm = fmaxf(bm, S[kb][r]);
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
-    const float m_new = fmaxf(m, bm);
-    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * sc);
-    const float msc = m_new * sc;
-    m = m_new;
-    float rowsum = 0.f;
-    float P[2][16];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(S[kb][r], sc, -msc));
-        P[kb][r] = p;
-        rowsum += p;
-      }
-    l = l * alpha + rowsum;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) O[db][r] *= alpha;
-
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 pb = cvt8(&P[kb][8 * t]);
-        const int vo = voff[2 * kb + t];
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 vf = *(const bf16x8*)(Vb + db * 32 * TN + vo);
-          O[db] = mfma32(vf, pb, O[db]);
-        }
-      }
-
-    if (has_next) stage_store(buf ^ 1);
-    __syncthreads();
   }
 
   const float l_tot = l + __shfl_xor(l, 32);
@@ -279,14 +305,14 @@ __global__ void __launch_bounds__(64 * HG * RB) k_prefill_bf16(PrefillArgs a) {
   }
 }
 
-template <int D, int HG, int RB>
+template <int D, int HG, int NSTAGE>
 int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
-  constexpr size_t sm = (size_t)2 * TN * D * 2 * 2 + 2 * TN * 4;
-  if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, RB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+  constexpr size_t sm = (size_t)2 * NSTAGE * TN * D * 2;
+  if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, NSTAGE>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sm) != hipSuccess)
     return DAG_ERR_HIP;
   const unsigned grid = (unsigned)(a.total_qtiles * a.hkv * hs);
-  hipLaunchKernelGGL((k_prefill_bf16<D, HG, RB>), dim3(grid), dim3(64 * HG * RB), sm, stream, a);
+  hipLaunchKernelGGL((k_prefill_bf16<D, HG, NSTAGE>), dim3(grid), dim3(128 * HG), sm, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
@@ -294,10 +320,9 @@ int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
 template <int D>
 int launch_d(const PrefillArgs& a, hipStream_t stream) {
   const int g = a.hq / a.hkv;
-  if (g % 4 == 0) return launch_one<D, 4, 1>(a, g / 4, stream);
-  if (g == 5) return launch_one<D, 5, 1>(a, 1, stream);
-  if (g % 2 == 0) return launch_one<D, 2, 2>(a, g / 2, stream);
-  return launch_one<D, 1, 4>(a, g, stream);
+  if (g % 4 == 0) return launch_one<D, 4, 4>(a, g / 4, stream);  // 8 waves, one workgroup per CU
+  if (g % 2 == 0) return launch_one<D, 2, 2>(a, g / 2, stream);  // 4 waves, two workgroups per CU
+  return launch_one<D, 1, 2>(a, g, stream);                       // 2 waves per workgroup
 }
 
 }  // namespace

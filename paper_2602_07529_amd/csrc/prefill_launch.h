@@ -16,6 +16,7 @@ struct PrefillArgs {
   const int32_t* rowptr;
   const int32_t* col;
   const uint8_t* flag;
+  const int32_t* nfull;
   const int32_t* qtile_order;
   int n_seqs, W, hq, hkv;
   int64_t total_qtiles;

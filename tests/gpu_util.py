@@ -35,7 +35,8 @@ def oracle_meta(dag_list, tm, tn):
         tok_start, pos_start = orc.node_tables(L, anc)
         tn_, pos = orc.token_meta(L, anc)
         bm = orc.block_map(L, anc, tm, tn)
-        rp, col, flag = orc.block_map_csr(bm)
+        rp, col, flag, nfull = orc.block_map_csr_full_first(bm)
+        out.setdefault("nfull", []).append(nfull)
         out["cu_seqlens"].append(out["cu_seqlens"][-1] + len(tn_))
         out["tok_node"].append(tn_)
         out["pos_ids"].append(pos)
@@ -61,6 +62,7 @@ def oracle_meta(dag_list, tm, tn):
         qtile_start=np.array(out["qtile_start"]), block_map_off=np.array(out["block_map_off"]),
         block_map=cat(out["block_map"], np.uint8), qtile_rowptr=np.array(out["rowptr"]),
         qtile_col=cat(out["col"], np.int64), qtile_flag=cat(out["flag"], np.uint8),
+        qtile_nfull=cat(out.get("nfull", []), np.int64),
         useful_pairs=np.array(out["useful_pairs"], dtype=np.int64))
     cnt = np.array(out["cnt"], dtype=np.int64)
     # launch order: descending tile count, ties by ascending index
@@ -72,7 +74,7 @@ def assert_meta_equal(meta, ref):
     torch.cuda.synchronize()
     nnz = int(ref["qtile_rowptr"][-1])
     for name in ("cu_seqlens", "tok_node", "pos_ids", "node_tok_start", "node_pos_start", "qtile_start",
-                 "block_map_off", "block_map", "qtile_rowptr", "qtile_order", "useful_pairs"):
+                 "block_map_off", "block_map", "qtile_rowptr", "qtile_nfull", "qtile_order", "useful_pairs"):
         got = meta.get(name).cpu().numpy().astype(np.int64)
         assert got.shape == ref[name].shape, name
         assert np.array_equal(got, ref[name].astype(np.int64)), name

@@ -41,10 +41,10 @@ def test_version_and_strerror():
 
 def test_tile_shape_table():
     assert B.dag_prefill_tile_shape(4, 4, 64, B.DAG_F32) == (64, 64)
-    assert B.dag_prefill_tile_shape(32, 8, 128, B.DAG_BF16) == (32, 64)
-    assert B.dag_prefill_tile_shape(40, 8, 128, B.DAG_BF16) == (32, 64)
+    assert B.dag_prefill_tile_shape(32, 8, 128, B.DAG_BF16) == (64, 64)
+    assert B.dag_prefill_tile_shape(40, 8, 128, B.DAG_BF16) == (64, 64)
     assert B.dag_prefill_tile_shape(16, 8, 64, B.DAG_BF16) == (64, 64)
-    assert B.dag_prefill_tile_shape(8, 8, 128, B.DAG_BF16) == (128, 64)
+    assert B.dag_prefill_tile_shape(8, 8, 128, B.DAG_BF16) == (64, 64)
     with pytest.raises(B.DagError) as e:
         B.dag_prefill_tile_shape(6, 4, 128, B.DAG_BF16)
     assert e.value.code == -7
@@ -52,7 +52,7 @@ def test_tile_shape_table():
         B.dag_prefill_tile_shape(8, 8, 96, B.DAG_BF16)
 
 
-def _desc(dag_list, tile=(32, 64), flags=0, words=None):
+def _desc(dag_list, tile=(64, 64), flags=0, words=None):
     off, lens, bits, W = dags.batch_desc(dag_list)
     return B.DagDesc(off, lens, bits, W if words is None else words, tile[0], tile[1], flags)
 
@@ -61,9 +61,9 @@ def test_meta_sizes_counts():
     one = dags.fork_join(2048, [256] * 8, 512)
     s = B.dag_meta_sizes(_desc([one] * 4))
     assert s.total_nodes == 40 and s.total_tokens == 18432
-    assert s.total_qtiles == 4 * 144 and s.total_tiles == 4 * 144 * 72
+    assert s.total_qtiles == 4 * 72 and s.total_tiles == 4 * 72 * 72
     # ragged: T = 100 with 32x64 tiles -> 4 query tiles, 2 key tiles
-    s = B.dag_meta_sizes(_desc([dags.linear_chain([100])]))
+    s = B.dag_meta_sizes(_desc([dags.linear_chain([100])], tile=(32, 64)))
     assert (s.total_qtiles, s.total_tiles) == (4, 8)
     assert s.csr_capacity == 1 + 1 + 2 + 2
     # empty batch and an empty sequence
@@ -136,13 +136,15 @@ def test_rope_and_prefill_argument_errors():
     assert L.dag_rope_qk(None, 0, C.c_void_p(FAKE), None, 2, 0, 64, 1e4, B.DAG_BF16, None) == 0
     d = _desc([dags.linear_chain([10, 10])])
     m = B.dag_meta_t()
-    m.n_seqs, m.words_per_node, m.tile_m, m.tile_n = 1, 1, 32, 64
+    m.n_seqs, m.words_per_node, m.tile_m, m.tile_n = 1, 1, 64, 64
     m.sizes = B.dag_meta_sizes(d)
     for name, _ in B._META_ARRAYS:
         setattr(m, name, FAKE)
     p = C.c_void_p(FAKE)
-    # tile shape of the meta does not match the kernel for this head configuration (MHA wants 128x64)
+    # tile shape of the meta does not match the kernel's (64x64)
+    m.tile_m = 32
     assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 8, 8, 128, 0.1, B.DAG_BF16, None) == -7
+    m.tile_m = 64
     assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 96, 0.1, B.DAG_BF16, None) == -7
     assert L.dag_attn_prefill(C.byref(m), None, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None) == -1
     assert L.dag_attn_prefill(C.byref(m), C.c_void_p(FAKE + 2), p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None) == -8

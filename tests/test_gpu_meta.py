@@ -50,8 +50,8 @@ def test_meta_config1_and_config2_shapes():
     _, meta = build_meta(c1, 4, 4, 64, torch.float32)
     assert_meta_equal(meta, oracle_meta(c1, 64, 64))
     c2 = [dags.fork_join(2048, [256] * 8, 512)] * 4
-    _, meta = build_meta(c2, 32, 8, 128, torch.bfloat16)
-    ref = oracle_meta(c2, 32, 64)
+    desc, meta = build_meta(c2, 32, 8, 128, torch.bfloat16)
+    ref = oracle_meta(c2, desc.c.tile_m, desc.c.tile_n)
     assert_meta_equal(meta, ref)
     assert ref["useful_pairs"].tolist() == [8784128] * 4
     assert meta.get("pos_ids")[2048].item() == 2048 and meta.get("pos_ids")[4096].item() == 2304
@@ -60,8 +60,8 @@ def test_meta_config1_and_config2_shapes():
 def test_meta_random_multilevel_dags_config4_recipe():
     c = dags.config(3)
     dag_list = dags.config_dags(c)[:3]
-    _, meta = build_meta(dag_list, c["hq"], c["hkv"], c["d"], torch.bfloat16)
-    assert_meta_equal(meta, oracle_meta(dag_list, 32, 64))
+    desc, meta = build_meta(dag_list, c["hq"], c["hkv"], c["d"], torch.bfloat16)
+    assert_meta_equal(meta, oracle_meta(dag_list, desc.c.tile_m, desc.c.tile_n))
 
 
 def test_meta_more_than_64_nodes_uses_two_bitset_words():
