@@ -74,8 +74,9 @@ typedef struct {
   int64_t total_nodes;
   int64_t total_tokens;    /* T                                                                */
   int64_t total_qtiles;    /* sum over sequences of ceil(T_b / tile_m)                         */
+  int64_t total_ktiles;    /* sum over sequences of ceil(T_b / tile_n)                         */
   int64_t total_tiles;     /* sum over sequences of QT_b * KT_b  (bytes of the dense map)      */
-  int64_t csr_capacity;    /* upper bound on the number of non-skip tiles                      */
+  int64_t csr_capacity;    /* upper bound on the number of non-skip tiles, plus 8 spare entries */
   int64_t workspace_bytes; /* device scratch needed by dag_build_meta                          */
 } dag_meta_sizes_t;
 
@@ -95,6 +96,7 @@ typedef struct {
   int32_t* node_pos_start; /* [total_nodes] adaptive position of the node's first token        */
   uint64_t* node_vis;      /* [total_nodes][words_per_node] ancestors | self                   */
   int32_t* qtile_start;    /* [n_seqs+1] index of each sequence's first query tile             */
+  int32_t* ktile_start;    /* [n_seqs+1] index of each sequence's first key tile               */
   int64_t* block_map_off;  /* [n_seqs+1] offset of each sequence's dense map                   */
   uint8_t* block_map;      /* [total_tiles] per sequence row-major [QT_b][KT_b], DAG_TILE_*    */
   int32_t* qtile_rowptr;   /* [total_qtiles+1] CSR over non-skip tiles; within a row the FULL
@@ -102,8 +104,12 @@ typedef struct {
   int32_t* qtile_col;      /* [csr_capacity] key-tile index                                    */
   uint8_t* qtile_flag;     /* [csr_capacity] DAG_TILE_PARTIAL or DAG_TILE_FULL                 */
   int32_t* qtile_nfull;    /* [total_qtiles] number of FULL tiles in the row                   */
-  int32_t* qtile_order;    /* [total_qtiles] query tiles sorted by descending tile count
-                              (ties: ascending index); the prefill launch order                */
+  int32_t* qtile_order;    /* [total_qtiles] launch order: sequences in order, inside a sequence
+                              the query tiles by descending tile count (ties: ascending index) */
+  int32_t* qtile_desc;     /* [total_qtiles][8] per launch slot: token offset of the sequence,
+                              its token count, first row of the tile, CSR row start, tiles in
+                              the row, leading tiles that need no mask (FULL and not ragged),
+                              node offset of the sequence, first key tile of the sequence      */
   int64_t* useful_pairs;   /* [n_seqs] number of visible (query, key) pairs                    */
 } dag_meta_t;
 
@@ -138,10 +144,17 @@ int dag_rope_qk(const int32_t* pos_ids, int64_t n_tokens, void* q, void* k, int3
  * tiles are skipped through the block map; only PARTIAL tiles evaluate per-token masks.
  * Supported: DAG_BF16 with head_dim 64 or 128 (MFMA path, fp32 accumulation); DAG_F32 with
  * head_dim 64 or 128; hq a multiple of hkv.  meta->tile_m/tile_n must equal
- * dag_prefill_tile_shape() for the same configuration. */
+ * dag_prefill_tile_shape() for the same configuration.  `ws` is DEVICE scratch of at least
+ * dag_prefill_workspace_bytes() bytes, 256-byte aligned (the bf16 path keeps a key-tile-wise
+ * transposed copy of V there); it may be NULL when that size is 0. */
 int dag_attn_prefill(const dag_meta_t* meta, const void* q, const void* k, const void* v,
                      void* out, float* lse, int32_t hq, int32_t hkv, int32_t head_dim,
-                     float softmax_scale, dag_dtype_t dtype, void* stream);
+                     float softmax_scale, dag_dtype_t dtype, void* ws, size_t ws_bytes,
+                     void* stream);
+
+/* Bytes of DEVICE workspace dag_attn_prefill needs (host only; 0 for the fp32 path). */
+size_t dag_prefill_workspace_bytes(const dag_meta_t* meta, int32_t hkv, int32_t head_dim,
+                                   dag_dtype_t dtype);
 
 /* One decode step over a paged KV cache (section 3.2: a token carries KV-cache indices, not
  * copies; section 4.3 Fork: sibling branches share the prefix KV without copying).  The struct

@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libdagattn.so")
+LIB_PATH = os.environ.get("DAGATTN_LIB") or os.path.join(_PKG, "libdagattn.so")
 
 DAG_F32, DAG_BF16 = 0, 1
 DAG_STRICT_CLOSURE = 1
@@ -33,14 +33,17 @@ class dag_desc_t(C.Structure):
 
 class dag_meta_sizes_t(C.Structure):
     _fields_ = [("total_nodes", C.c_int64), ("total_tokens", C.c_int64), ("total_qtiles", C.c_int64),
-                ("total_tiles", C.c_int64), ("csr_capacity", C.c_int64), ("workspace_bytes", C.c_int64)]
+                ("total_ktiles", C.c_int64), ("total_tiles", C.c_int64), ("csr_capacity", C.c_int64),
+                ("workspace_bytes", C.c_int64)]
 
 
 _META_ARRAYS = [("cu_seqlens", torch.int32), ("node_start", torch.int32), ("tok_node", torch.int32),
                 ("pos_ids", torch.int32), ("node_tok_start", torch.int32), ("node_pos_start", torch.int32),
-                ("node_vis", torch.int64), ("qtile_start", torch.int32), ("block_map_off", torch.int64),
+                ("node_vis", torch.int64), ("qtile_start", torch.int32), ("ktile_start", torch.int32),
+                ("block_map_off", torch.int64),
                 ("block_map", torch.uint8), ("qtile_rowptr", torch.int32), ("qtile_col", torch.int32),
-                ("qtile_flag", torch.uint8), ("qtile_nfull", torch.int32), ("qtile_order", torch.int32), ("useful_pairs", torch.int64)]
+                ("qtile_flag", torch.uint8), ("qtile_nfull", torch.int32), ("qtile_order", torch.int32), ("qtile_desc", torch.int32),
+                ("useful_pairs", torch.int64)]
 
 
 class dag_meta_t(C.Structure):
@@ -76,7 +79,9 @@ def lib():
         L.dag_build_meta.argtypes = [C.POINTER(dag_desc_t), C.POINTER(dag_meta_t), vp, C.c_size_t, vp]
         L.dag_rope_qk.argtypes = [vp, i64, vp, vp, i32, i32, i32, f32, C.c_int, vp]
         L.dag_attn_prefill.argtypes = [C.POINTER(dag_meta_t), vp, vp, vp, vp, vp, i32, i32, i32, f32,
-                                       C.c_int, vp]
+                                       C.c_int, vp, C.c_size_t, vp]
+        L.dag_prefill_workspace_bytes.argtypes = [C.POINTER(dag_meta_t), i32, i32, C.c_int]
+        L.dag_prefill_workspace_bytes.restype = C.c_size_t
         L.dag_kv_append_rope.argtypes = [C.POINTER(dag_decode_desc_t), vp, vp, vp, vp, i32, i32, f32, vp]
         L.dag_decode_workspace_bytes.argtypes = [C.POINTER(dag_decode_desc_t), i32, i32, i32]
         L.dag_decode_workspace_bytes.restype = C.c_size_t
@@ -154,9 +159,10 @@ class DagMeta:
         counts = dict(cu_seqlens=n + 1, node_start=n + 1, tok_node=sizes.total_tokens,
                       pos_ids=sizes.total_tokens, node_tok_start=sizes.total_nodes,
                       node_pos_start=sizes.total_nodes, node_vis=sizes.total_nodes * W,
-                      qtile_start=n + 1, block_map_off=n + 1, block_map=sizes.total_tiles,
+                      qtile_start=n + 1, ktile_start=n + 1, block_map_off=n + 1, block_map=sizes.total_tiles,
                       qtile_rowptr=sizes.total_qtiles + 1, qtile_col=sizes.csr_capacity,
-                      qtile_flag=sizes.csr_capacity, qtile_nfull=sizes.total_qtiles, qtile_order=sizes.total_qtiles, useful_pairs=n)
+                      qtile_flag=sizes.csr_capacity, qtile_nfull=sizes.total_qtiles, qtile_order=sizes.total_qtiles, qtile_desc=sizes.total_qtiles * 8,
+                      useful_pairs=n)
         self.sizes = sizes
         self.t = {name: torch.empty(max(int(counts[name]), 1), dtype=dt, device=device)
                   for name, dt in _META_ARRAYS}
@@ -188,13 +194,27 @@ def dag_rope_qk(pos_ids, q, k, theta):
                              _dtype_code(ref), _stream()))
 
 
-def dag_attn_prefill(meta, q, k, v, out, lse=None, softmax_scale=None):
+def dag_prefill_workspace_bytes(meta, hkv, head_dim, dtype_code):
+    return int(lib().dag_prefill_workspace_bytes(C.byref(meta.c), hkv, head_dim, dtype_code))
+
+
+def dag_attn_prefill(meta, q, k, v, out, lse=None, softmax_scale=None, workspace=None):
+    """`workspace`: uint8 device tensor of dag_prefill_workspace_bytes(); when omitted one is
+    allocated (torch) and kept on `meta` for the following calls."""
     T, hq, d = q.shape
     hkv = k.shape[1]
     if softmax_scale is None:
         softmax_scale = 1.0 / float(d) ** 0.5
+    if workspace is None:
+        need = dag_prefill_workspace_bytes(meta, hkv, d, _dtype_code(q))
+        ws = getattr(meta, "prefill_ws", None)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+            meta.prefill_ws = ws
+        workspace = ws
     _check(lib().dag_attn_prefill(C.byref(meta.c), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
-                                  hq, hkv, d, float(softmax_scale), _dtype_code(q), _stream()))
+                                  hq, hkv, d, float(softmax_scale), _dtype_code(q), _ptr(workspace),
+                                  workspace.numel(), _stream()))
 
 
 class DecodeDesc:

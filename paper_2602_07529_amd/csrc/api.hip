@@ -2,9 +2,16 @@
 #include "common.h"
 #include "prefill_launch.h"
 
+extern "C" size_t dag_prefill_workspace_bytes(const dag_meta_t* m, int32_t hkv, int32_t head_dim,
+                                              dag_dtype_t dtype) {
+  if (!m || dtype != DAG_BF16 || hkv < 1 || head_dim < 1 || m->sizes.total_ktiles < 0) return 0;
+  // key-tile-wise transposed copy of V: [key tile][kv head][head_dim][tile_n] bf16
+  return (size_t)m->sizes.total_ktiles * hkv * head_dim * m->tile_n * 2 + 256;
+}
+
 extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* k, const void* v, void* out,
                                 float* lse, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale,
-                                dag_dtype_t dtype, void* stream_) {
+                                dag_dtype_t dtype, void* ws, size_t ws_bytes, void* stream_) {
   if (!m) return DAG_ERR_NULL;
   if (dtype != DAG_F32 && dtype != DAG_BF16) return DAG_ERR_UNSUPPORTED;
   int32_t tm = 0, tn = 0;
@@ -15,32 +22,38 @@ extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* 
     return DAG_ERR_BAD_LEN;
   if (m->n_seqs == 0 || m->sizes.total_tokens == 0) return DAG_OK;
   if (!q || !k || !v || !out) return DAG_ERR_NULL;
-  if (!m->cu_seqlens || !m->node_start || !m->tok_node || !m->node_vis || !m->qtile_start || !m->qtile_rowptr ||
-      !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order)
+  if (!m->cu_seqlens || !m->node_start || !m->tok_node || !m->node_vis || !m->qtile_start || !m->ktile_start ||
+      !m->qtile_rowptr || !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order || !m->qtile_desc)
     return DAG_ERR_NULL;
   if (!dag_aligned16(q) || !dag_aligned16(k) || !dag_aligned16(v) || !dag_aligned16(out)) return DAG_ERR_ALIGN;
   if (m->sizes.total_qtiles * (int64_t)hq > INT32_MAX) return DAG_ERR_UNSUPPORTED;
+  const size_t need = dag_prefill_workspace_bytes(m, hkv, head_dim, dtype);
+  if (need > 0 && (!ws || ws_bytes < need)) return DAG_ERR_WORKSPACE;
   PrefillArgs a;
   a.q = q;
   a.k = k;
   a.v = v;
   a.out = out;
   a.lse = lse;
+  a.vt = need > 0 ? (void*)dag_align_up((size_t)(uintptr_t)ws, 256) : nullptr;
   a.cu_seqlens = m->cu_seqlens;
   a.node_start = m->node_start;
   a.tok_node = m->tok_node;
   a.node_vis = m->node_vis;
   a.qtile_start = m->qtile_start;
+  a.ktile_start = m->ktile_start;
   a.rowptr = m->qtile_rowptr;
   a.col = m->qtile_col;
   a.flag = m->qtile_flag;
   a.nfull = m->qtile_nfull;
   a.qtile_order = m->qtile_order;
+  a.qtile_desc = m->qtile_desc;
   a.n_seqs = m->n_seqs;
   a.W = m->words_per_node;
   a.hq = hq;
   a.hkv = hkv;
   a.total_qtiles = m->sizes.total_qtiles;
+  a.total_ktiles = m->sizes.total_ktiles;
   a.scale = softmax_scale;
   hipStream_t stream = (hipStream_t)stream_;
   return dtype == DAG_F32 ? launch_prefill_f32(a, head_dim, stream) : launch_prefill_bf16(a, head_dim, stream);

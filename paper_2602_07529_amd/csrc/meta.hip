@@ -38,12 +38,14 @@ int host_dims(const dag_desc_t* d, std::vector<SeqDims>* per_seq, dag_meta_sizes
     if (per_seq) per_seq->push_back(sd);
     s.total_tokens += T;
     s.total_qtiles += sd.qtiles;
+    s.total_ktiles += sd.ktiles;
     s.total_tiles += sd.qtiles * sd.ktiles;
     for (int64_t a = 0; a < sd.qtiles; ++a) {
       int64_t last_row = (a + 1) * d->tile_m < T ? (a + 1) * d->tile_m : T;
       s.csr_capacity += (last_row - 1) / d->tile_n + 1;  // key tiles that start at or before the last row
     }
   }
+  s.csr_capacity += 8;  // spare entries: the prefill kernel reads the column list eight entries at a time
   if (s.total_tokens > INT32_MAX || s.total_qtiles > INT32_MAX || s.csr_capacity > INT32_MAX)
     return DAG_ERR_POS_OVERFLOW;
   if (d->n_seqs > 0) s.total_nodes = d->node_offsets[d->n_seqs];
@@ -94,7 +96,8 @@ int host_validate_bits(const dag_desc_t* d) {
 // ------------------------------------------------------------------------------------ kernels
 // One block: per-sequence token counts and the three prefix sums over sequences.
 __global__ void k_seq(int n_seqs, const int32_t* node_off, const int32_t* node_len, int tile_m, int tile_n,
-                      int32_t* cu_seqlens, int32_t* qtile_start, int64_t* block_map_off, int32_t* node_start) {
+                      int32_t* cu_seqlens, int32_t* qtile_start, int64_t* block_map_off, int32_t* node_start,
+                      int32_t* ktile_start) {
   for (int b = threadIdx.x; b <= n_seqs; b += blockDim.x) node_start[b] = node_off[b];
   for (int b = threadIdx.x; b < n_seqs; b += blockDim.x) {
     int t = 0;
@@ -103,19 +106,22 @@ __global__ void k_seq(int n_seqs, const int32_t* node_off, const int32_t* node_l
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    int cu = 0, qs = 0;
+    int cu = 0, qs = 0, ks = 0;
     int64_t mo = 0;
     cu_seqlens[0] = 0;
     qtile_start[0] = 0;
+    ktile_start[0] = 0;
     block_map_off[0] = 0;
     for (int b = 0; b < n_seqs; ++b) {
       int t = cu_seqlens[b + 1];
       int qt = (t + tile_m - 1) / tile_m, kt = (t + tile_n - 1) / tile_n;
       cu += t;
       qs += qt;
+      ks += kt;
       mo += (int64_t)qt * kt;
       cu_seqlens[b + 1] = cu;
       qtile_start[b + 1] = qs;
+      ktile_start[b + 1] = ks;
       block_map_off[b + 1] = mo;
     }
   }
@@ -312,24 +318,49 @@ __global__ void __launch_bounds__(64) k_csr_fill(int n_seqs, const int32_t* qtil
   }
 }
 
-// One thread per query tile: rank among all tiles by (count descending, index ascending).
-__global__ void k_order(int total_qtiles, const int32_t* cnt, int32_t* order) {
-  __shared__ int s[256];
+// One thread per query tile: launch order = sequences in order, inside a sequence the query
+// tiles by (tile count descending, index ascending).  Query tiles that run at the same time then
+// read the same sequence's K/V (L2 locality) and have similar amounts of work.
+__global__ void k_order(int n_seqs, int total_qtiles, const int32_t* qtile_start, const int32_t* cnt,
+                        int32_t* order) {
   const int qt = blockIdx.x * blockDim.x + threadIdx.x;
-  const int mine = qt < total_qtiles ? cnt[qt] : 0;
-  int rank = 0;
-  for (int c0 = 0; c0 < total_qtiles; c0 += 256) {
-    const int i = c0 + threadIdx.x;
-    s[threadIdx.x] = i < total_qtiles ? cnt[i] : -1;
-    __syncthreads();
-    const int lim = min(256, total_qtiles - c0);
-    for (int j = 0; j < lim; ++j) {
-      const int o = s[j];
-      rank += (o > mine) || (o == mine && c0 + j < qt);
-    }
-    __syncthreads();
+  if (qt >= total_qtiles) return;
+  const int b = dag_find_segment(qtile_start, n_seqs, qt);
+  const int q0 = qtile_start[b], q1 = qtile_start[b + 1];
+  const int mine = cnt[qt];
+  int rank = q0;
+  for (int j = q0; j < q1; ++j) {
+    const int o = cnt[j];
+    rank += (o > mine) || (o == mine && j < qt);
   }
-  if (qt < total_qtiles) order[rank] = qt;
+  order[rank] = qt;
+}
+
+// One thread per launch slot: everything the prefill kernel needs to start a query tile, in one
+// 32-byte record {token offset of the sequence, tokens in the sequence, first row of the tile,
+// CSR row start, tiles in the row, tiles that need no mask, node offset of the sequence, first key
+// tile of the sequence}.
+__global__ void k_desc(int n_seqs, int total_qtiles, int tile_m, int tile_n, const int32_t* order,
+                       const int32_t* qtile_start, const int32_t* cu_seqlens, const int32_t* node_start,
+                       const int32_t* ktile_start, const int32_t* rowptr, const int32_t* col,
+                       const int32_t* nfull, int32_t* desc) {
+  const int oi = blockIdx.x * blockDim.x + threadIdx.x;
+  if (oi >= total_qtiles) return;
+  const int qt = order[oi];
+  const int b = dag_find_segment(qtile_start, n_seqs, qt);
+  const int T = cu_seqlens[b + 1] - cu_seqlens[b];
+  const int c0 = rowptr[qt];
+  int nf = nfull[qt];
+  if (nf > 0 && (col[c0 + nf - 1] + 1) * tile_n > T) --nf;  // a ragged last key tile needs the mask path
+  int32_t* d = desc + (int64_t)oi * 8;
+  d[0] = cu_seqlens[b];
+  d[1] = T;
+  d[2] = (qt - qtile_start[b]) * tile_m;
+  d[3] = c0;
+  d[4] = rowptr[qt + 1] - c0;
+  d[5] = nf;
+  d[6] = node_start[b];
+  d[7] = ktile_start[b];
 }
 
 }  // namespace
@@ -368,10 +399,11 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
       m->sizes.csr_capacity != s.csr_capacity || m->sizes.total_nodes != s.total_nodes)
     return DAG_ERR_BAD_LEN;
   if (d->n_seqs == 0) return DAG_OK;
-  if (!m->cu_seqlens || !m->node_start || !m->qtile_start || !m->block_map_off || !m->qtile_rowptr || !m->useful_pairs)
+  if (!m->cu_seqlens || !m->node_start || !m->qtile_start || !m->ktile_start || !m->block_map_off ||
+      !m->qtile_rowptr || !m->useful_pairs)
     return DAG_ERR_NULL;
   if (s.total_tokens > 0 && (!m->tok_node || !m->pos_ids || !m->node_tok_start || !m->node_pos_start ||
-                             !m->node_vis || !m->block_map || !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order))
+                             !m->node_vis || !m->block_map || !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order || !m->qtile_desc))
     return DAG_ERR_NULL;
   rc = host_validate_bits(d);
   if (rc != DAG_OK) return rc;
@@ -399,7 +431,7 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
     if (n > max_nodes) max_nodes = n;
   }
   hipLaunchKernelGGL(k_seq, dim3(1), dim3(256), 0, stream, d->n_seqs, d_off, d_len, d->tile_m, d->tile_n,
-                     m->cu_seqlens, m->qtile_start, m->block_map_off, m->node_start);
+                     m->cu_seqlens, m->qtile_start, m->block_map_off, m->node_start, m->ktile_start);
   DAG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_node, dim3(d->n_seqs), dim3(64), (size_t)max_nodes * 8 + 8, stream, d_off, d_len, d_anc, W,
                      m->node_tok_start, m->node_pos_start, m->node_vis, m->useful_pairs);
@@ -426,7 +458,12 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
                      m->cu_seqlens, d->tile_n, m->block_map, m->qtile_rowptr, m->qtile_col, m->qtile_flag,
                      m->qtile_nfull);
   DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_order, dim3((QT + 255) / 256), dim3(256), 0, stream, (int)QT, d_cnt, m->qtile_order);
+  hipLaunchKernelGGL(k_order, dim3((QT + 255) / 256), dim3(256), 0, stream, d->n_seqs, (int)QT, m->qtile_start, d_cnt,
+                     m->qtile_order);
+  DAG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_desc, dim3((QT + 255) / 256), dim3(256), 0, stream, d->n_seqs, (int)QT, d->tile_m, d->tile_n,
+                     m->qtile_order, m->qtile_start, m->cu_seqlens, m->node_start, m->ktile_start, m->qtile_rowptr,
+                     m->qtile_col, m->qtile_nfull, m->qtile_desc);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }

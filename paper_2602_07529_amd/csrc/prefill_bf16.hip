@@ -1,28 +1,44 @@
 // bf16 DAG attention prefill for gfx950 (paper Eq. 2 + Eq. 3), MFMA 32x32x16 with fp32 accumulation.
 //
-// Work decomposition.  A workgroup owns one 64-row query tile of one KV head and stacks HG of that
-// KV head's query heads: wave w handles the 32-row block w / HG of head w % HG, so every wave of
-// the workgroup consumes the same K/V tiles.  With HG = 4 that is eight waves, two per SIMD, so
-// that one wave's softmax (vector ALU) overlaps the other's MFMAs.  Only the key tiles the block
-// map lists are visited.  The CSR row of a query tile lists its FULL tiles first: those run in a
-// loop that contains no mask code at all; the PARTIAL tiles (and a ragged last tile) follow in a
-// second loop that evaluates the per-token mask.
+// Work decomposition.  A work item is one 64-row query tile of one KV head with HG of that KV
+// head's query heads stacked: wave w handles the 32-row block w / HG of head w % HG, so every wave
+// of the workgroup consumes the same K/V tiles.  With HG = 4 that is eight waves, two per SIMD, so
+// that one wave's softmax (vector ALU) overlaps the other's MFMAs.  The kernel is persistent: the
+// grid has one workgroup per CU slot and workgroup g processes items g, g + grid, ... of the
+// launch list (sequences in order, heavy query tiles first).  The K/V stream of the next item is
+// prefetched while the current one finishes; and because workgroups are placed round-robin on
+// the eight XCDs, an XCD keeps working on one KV head of one sequence at a time, whose K/V then
+// stay in its L2.
 //
-// Data movement.  K and V tiles of 64 tokens go from global memory straight into LDS
-// (global_load_lds, 16 bytes per lane, no staging registers) through a ring of NSTAGE buffers:
-// the loads of the next NSTAGE-1 tiles are in flight while a tile is computed, one barrier per
-// tile.  A wave-level load writes 1 KiB of consecutive LDS, so the bank-conflict-avoiding XOR
-// swizzle is applied to the *source* address each lane fetches:
-//   K tile [64 keys][D]  16-byte chunk c of key r is stored at chunk c ^ swzK(r)
-//   V tile [64 keys][D]  16-byte chunk c of key r is stored at chunk c ^ swzV(r)
+// Only the key tiles the block map lists are visited.  The CSR row of a query tile lists its FULL
+// tiles first: those need no mask; PARTIAL tiles (and a ragged last tile) follow and evaluate the
+// per-token mask.
+//
+// Data movement.  K tiles (64 keys x D) and V^T tiles (D x 64 keys, from a key-tile-wise
+// transposed copy of V that a small pre-pass writes into the workspace) go from global memory
+// straight into LDS (global_load_lds, 16 bytes per lane, no staging registers) through a ring of
+// NSTAGE buffers.  Bare s_barrier + explicit vmcnt waits keep up to NSTAGE-1 tiles in flight (a
+// __syncthreads would drain them).  A wave-level load writes 1 KiB of consecutive LDS (a "block");
+// which 16-byte chunk of which row a lane fetches is chosen so that (a) four consecutive lanes
+// read 64 consecutive bytes of global memory (the texture path looks up one cache line per
+// such group; with four lines per group the waves stall issuing their loads), (b) the 16-byte
+// operand reads of the block are spread evenly over the LDS banks, and (c) their addresses are one
+// register plus immediates for all reads of a tile:
+//   K block = R keys x C chunks (R = 1024 / (2 D)), stride 1024 + 16 bytes:
+//             [chunk / 4][key % R][chunk % 4][16 B]
+//   V^T block = 8 output dimensions x 8 key groups, stride 1024 + 128 bytes: [key group][dim % 8][16 B]
+//             (the workspace copy is stored in this order, so its loads are linear)
+// The MFMA A operand of both products is then one ds_read_b128 per instruction: LDS bandwidth, not
+// the matrix pipe, is the scarce resource here (a 32x32x16 MFMA consumes a 1 KiB operand per wave
+// every 32 cycles), which is why V is transposed once in global memory instead of with the slower
+// LDS transpose loads.
 //
 // Register layout.  Scores are computed transposed, S^T = K Q^T, so that after the MFMA a lane
 // holds one query row (lane % 32) and 16 keys of each 32-key block in registers: the softmax row
 // reductions are in-register plus one exchange between the two half waves, and the probabilities
 // already sit in the B-operand layout of the second product O^T = V^T P^T.  MFMA row i of a
 // 32-key block is mapped to key pi(i) so that registers 0..7 / 8..15 of a score block hold 8
-// consecutive keys.  The V^T operand (8 keys of one output dimension per lane) is read from the
-// row-major V tile with the LDS transpose load ds_read_tr16_b64.
+// consecutive keys.
 //
 // Softmax.  Online softmax in the log2 domain.  The running maximum is only raised when some row
 // of the wave exceeds it by more than 2^8 (the accumulator rescale is then rare); probabilities
@@ -36,9 +52,8 @@ constexpr int TN = 64;
 constexpr int TM = 64;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(8))) float f32x8;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -49,14 +64,6 @@ __device__ __forceinline__ int key_of_row(int i) {
   const int a = i >> 3, hh = (i >> 2) & 1, c = i & 3;
   return 16 * (a >> 1) + 8 * hh + 4 * (a & 1) + c;
 }
-template <int D>
-__device__ __forceinline__ int swzK(int row) {
-  return D == 128 ? (row & 15) : ((row >> 1) & 7);
-}
-template <int D>
-__device__ __forceinline__ int swzV(int row) {
-  return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
-}
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
@@ -65,133 +72,181 @@ __device__ __forceinline__ void wait_vmcnt() {  // s_waitcnt vmcnt(N) only (gfx9
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+struct Item {  // wave-uniform description of a work item
+  int cu, T, row0, c0, N, nfast, nstart, ktb, hk, hs;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Pre-pass: V [T][hkv][D] -> V^T tiles [key tile][kv head][D / 8][8 key groups][8 dims][8 keys]
+// (keys past the end of the sequence are zero): the tile is stored as the image it has in LDS, so
+// the attention kernel streams it with fully linear reads.  One block per (key tile, kv head).
+template <int D>
+__global__ void __launch_bounds__(256) k_vt_prepare(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
+                                                    const int32_t* __restrict__ ktile_start,
+                                                    const int32_t* __restrict__ cu_seqlens, int n_seqs, int hkv) {
+  constexpr int LD = D + 8;  // padded row (elements)
+  __shared__ __attribute__((aligned(16))) uint16_t s[TN * LD];
+  const int tile = blockIdx.x, h = blockIdx.y;
+  const int b = dag_find_segment(ktile_start, n_seqs, tile);
+  const int T = cu_seqlens[b + 1] - cu_seqlens[b];
+  const int j0 = (tile - ktile_start[b]) * TN;
+  for (int c = threadIdx.x; c < TN * (D / 8); c += 256) {
+    const int r = c / (D / 8), ch = c % (D / 8);
+    u32x4 x = {0, 0, 0, 0};
+    if (j0 + r < T) x = *(const u32x4*)(v + ((size_t)(cu_seqlens[b] + j0 + r) * hkv + h) * D + ch * 8);
+    *(u32x4*)(s + r * LD + ch * 8) = x;
+  }
+  __syncthreads();
+  uint16_t* o = vt + ((size_t)tile * hkv + h) * (size_t)(D * TN);
+  for (int c = threadIdx.x; c < D * (TN / 8); c += 256) {  // 16-byte piece c of the tile image
+    const int d = 8 * (c / 64) + (c % 8), kc = (c / 8) % 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      w[e] = (uint32_t)s[(8 * kc + 2 * e) * LD + d] | ((uint32_t)s[(8 * kc + 2 * e + 1) * LD + d] << 16);
+    *(u32x4*)(o + (size_t)c * 8) = u32x4{w[0], w[1], w[2], w[3]};
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 template <int D, int HG, int NSTAGE>
 __global__ void __launch_bounds__(128 * HG, (HG == 4 ? 1 : 2)) k_prefill_bf16(PrefillArgs a) {
   constexpr int NW = 2 * HG;                 // waves: two 32-row blocks x HG heads
-  constexpr int CH = D / 8;                  // 16-byte chunks per row
+  constexpr int CH = D / 8;                  // 16-byte chunks per K row
   constexpr int KSTEPS = D / 16;             // MFMA steps of the score product
   constexpr int DB = D / 32;                 // 32-row blocks of O^T
-  constexpr int RPI = 64 / CH;               // tile rows covered by one wave-level load
-  constexpr int IPW = TN / RPI / NW;         // wave-level loads per tile, tensor and wave
-  constexpr int LPT = 2 * IPW;               // loads per tile and wave (K and V)
-  constexpr int TILE_BYTES = TN * D * 2;
+  constexpr int KPB = 64 / CH;               // keys per K block
+  constexpr int NBK = TN / KPB;              // K blocks per tile
+  constexpr int NBV = D / 8;                 // V^T blocks per tile (8 output dimensions each)
+  constexpr int IPK = NBK / NW, IPV = NBV / NW;  // blocks per tile and wave
+  constexpr int LPT = IPK + IPV;             // loads per tile and wave
+  constexpr int BLKK = 1024 + 16;            // block strides (skewed so that reads are conflict free)
+  constexpr int BLKV = 1024 + 16 * 8;
+  constexpr int KTILE = NBK * BLKK, VTILE = NBV * BLKV;
   constexpr float TH_LOG2 = 8.f;
-  static_assert(IPW >= 1 && IPW * RPI * NW == TN, "tile loads must divide evenly over the waves");
-  static_assert((NSTAGE - 2) * LPT < 64, "vmcnt range");
+  static_assert(IPK >= 1 && IPK * NW == NBK && IPV >= 1 && IPV * NW == NBV, "tile loads must divide over the waves");
+  static_assert((NSTAGE - 1) * LPT < 64 && NSTAGE >= 2 && NSTAGE <= 4, "vmcnt range / ring depth");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  // layout: K[NSTAGE][TILE_BYTES], V[NSTAGE][TILE_BYTES]
-  unsigned char* const Kbase = smem;
-  unsigned char* const Vbase = smem + NSTAGE * TILE_BYTES;
+  unsigned char* const Kbase = smem;                    // K[NSTAGE][KTILE]
+  unsigned char* const Vbase = smem + NSTAGE * KTILE;   // V^T[NSTAGE][VTILE]
 
   const int G = a.hq / a.hkv;
-  const int HS = G / HG;  // workgroups per KV head
+  const int HS = G / HG;  // items per (query tile, KV head)
   const int nhw = a.hkv * HS;
-  const int oi = blockIdx.x / nhw, hw = blockIdx.x % nhw;
-  const int hk = hw / HS, hs = hw % HS;
-  const int qt = a.qtile_order[oi];
-  const int b = dag_find_segment(a.qtile_start, a.n_seqs, qt);
-  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
-  const int row0 = (qt - a.qtile_start[b]) * TM;
+  const long n_items = (long)a.total_qtiles * nhw;
 
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int L = lane & 31, H = lane >> 5;
   const int rb = w / HG, hj = w % HG;
-  const int head = hk * G + hs * HG + hj;
-  const int i_row = row0 + 32 * rb + L;  // row inside the sequence
-  const int tok = cu + min(i_row, T - 1);
 
   const uint16_t* qg = (const uint16_t*)a.q;
   const unsigned char* kg = (const unsigned char*)a.k;
-  const unsigned char* vg = (const unsigned char*)a.v;
+  const unsigned char* vtg = (const unsigned char*)a.vt;
   const uint32_t rowbytes = (uint32_t)a.hkv * D * 2;
 
-  bf16x8 qf[KSTEPS];
-#pragma unroll
-  for (int s = 0; s < KSTEPS; ++s)
-    qf[s] = *(const bf16x8*)(qg + ((size_t)tok * a.hq + head) * D + 16 * s + 8 * H);
+  auto load_item = [&](long it) {
+    const int oi = (int)(it / nhw), hw = (int)(it % nhw);
+    const int32_t* d = a.qtile_desc + (size_t)oi * 8;
+    Item I;
+    I.cu = d[0]; I.T = d[1]; I.row0 = d[2]; I.c0 = d[3]; I.N = d[4]; I.nfast = d[5]; I.nstart = d[6]; I.ktb = d[7];
+    I.hk = hw / HS; I.hs = hw % HS;
+    return I;
+  };
+  auto token_of = [&](const Item& I) { return I.cu + min(I.row0 + 32 * rb + L, I.T - 1); };
+  auto head_of = [&](const Item& I) { return I.hk * G + I.hs * HG + hj; };
 
-  // Source offsets of this lane's tile loads.  Load i of the wave covers rows RPI*(w + NW*i) ...;
-  // when NW is a multiple of 4 the swizzle terms do not depend on i and one offset serves all.
-  constexpr bool UNIFORM_SRC = (NW % 4 == 0);
-  constexpr int NSRC = UNIFORM_SRC ? 1 : IPW;
-  const int pos = lane % CH;
-  uint32_t ksrc[NSRC], vsrc[NSRC];
-#pragma unroll
-  for (int i = 0; i < NSRC; ++i) {
-    const int r = (w + NW * i) * RPI + lane / CH;
-    ksrc[i] = r * rowbytes + ((pos ^ swzK<D>(r)) * 16);
-    vsrc[i] = r * rowbytes + ((pos ^ swzV<D>(r)) * 16);
-  }
+  // What this lane fetches in a wave-level load (LDS position 16*lane inside the block):
+  //   K:   key (lane / 4) % KPB of the block, chunk 4 * (lane / (4 * KPB)) + lane % 4: four
+  //        consecutive lanes fetch 64 consecutive bytes of one row (one cache-line lookup)
+  //   V^T: piece `lane` of the block (the workspace copy already has the LDS order)
+  const int kkey = (lane >> 2) % KPB;
+  const uint32_t kchunk = (4 * (lane / (4 * KPB)) + (lane & 3)) * 16;
+  const uint32_t ksrc = (w * KPB + kkey) * rowbytes + kchunk;
+  const uint32_t vsrc = w * 1024 + lane * 16;
 
-  auto issue_loads = [&](int buf, int j0) {
-    const unsigned char* kt = kg + ((size_t)(cu + j0) * a.hkv + hk) * (D * 2);
-    const unsigned char* vt = vg + ((size_t)(cu + j0) * a.hkv + hk) * (D * 2);
-    unsigned char* kl = Kbase + buf * TILE_BYTES + w * 1024;
-    unsigned char* vl = Vbase + buf * TILE_BYTES + w * 1024;
+  auto issue_loads = [&](int buf, int cu, int T, int hk, int ktb, int kt) {
+    const int j0 = kt * TN;
+    const unsigned char* ktile = kg + ((size_t)(cu + j0) * a.hkv + hk) * (D * 2);
+    const unsigned char* vtile = vtg + ((size_t)(ktb + kt) * a.hkv + hk) * (size_t)(D * TN * 2);
+    unsigned char* kl = Kbase + buf * KTILE + w * BLKK;
+    unsigned char* vl = Vbase + buf * VTILE + w * BLKV;
     if (j0 + TN <= T) {
 #pragma unroll
-      for (int i = 0; i < IPW; ++i) {
-        const size_t step = UNIFORM_SRC ? (size_t)i * (RPI * NW) * rowbytes : 0;
-        const uint32_t ks = ksrc[UNIFORM_SRC ? 0 : i], vs = vsrc[UNIFORM_SRC ? 0 : i];
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kt + step + ks), (lds_ptr_t)(kl + i * NW * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vt + step + vs), (lds_ptr_t)(vl + i * NW * 1024), 16, 0, 0);
-      }
+      for (int i = 0; i < IPK; ++i)
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ktile + (size_t)i * (NW * KPB) * rowbytes + ksrc),
+                                         (lds_ptr_t)(kl + i * NW * BLKK), 16, 0, 0);
     } else {  // ragged last tile: rows past the end re-read the last valid row (masked later)
       const int last = T - 1 - j0;
 #pragma unroll
-      for (int i = 0; i < IPW; ++i) {
-        const int r = (w + NW * i) * RPI + lane / CH;
-        const uint32_t rc = (uint32_t)min(r, last) * rowbytes;
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kt + rc + ((pos ^ swzK<D>(r)) * 16)),
-                                         (lds_ptr_t)(kl + i * NW * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vt + rc + ((pos ^ swzV<D>(r)) * 16)),
-                                         (lds_ptr_t)(vl + i * NW * 1024), 16, 0, 0);
+      for (int i = 0; i < IPK; ++i) {
+        const int rk = min((w + NW * i) * KPB + kkey, last);
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ktile + (uint32_t)rk * rowbytes + kchunk),
+                                         (lds_ptr_t)(kl + i * NW * BLKK), 16, 0, 0);
       }
     }
+#pragma unroll
+    for (int i = 0; i < IPV; ++i)  // the transposed copy is zero padded: no ragged case
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vtile + i * (NW * 1024) + vsrc),
+                                       (lds_ptr_t)(vl + i * NW * BLKV), 16, 0, 0);
   };
 
-  // per-lane LDS read offsets (bytes inside a tile)
+  // LDS read addresses (bytes inside a tile); every other read of the tile is an immediate away.
+  //   K, MFMA step s of key block kb:   koff + kb * (32 / KPB) * BLKK + (s / 2) * 64 * KPB + (s % 2) * 32
+  //   V^T, key step st, output block db: voff + db * 4 * BLKV + st * 256
   const int krow = key_of_row(L);
-  uint32_t koff[KSTEPS];
-#pragma unroll
-  for (int s = 0; s < KSTEPS; ++s) koff[s] = krow * (D * 2) + (((2 * s + H) ^ swzK<D>(krow)) * 16);
-  // transpose read: within a 16-lane group, lane j = 4e + c addresses key e (of 4), 8-byte piece c
-  const int tr_e = (lane & 15) >> 2, tr_c = lane & 3, dhalf = (lane >> 4) & 1;
-  uint32_t voff[2][DB];  // [rd][db]: keys 8H + 4rd + e of the first 16-key step; a step adds 16 rows
-#pragma unroll
-  for (int rd = 0; rd < 2; ++rd)
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const int key = 8 * H + 4 * rd + tr_e;
-      const int c16 = 4 * db + 2 * dhalf + (tr_c >> 1);
-      voff[rd][db] = key * (D * 2) + ((c16 ^ swzV<D>(key)) * 16) + (tr_c & 1) * 8;
-    }
+  const uint32_t koff = (krow / KPB) * BLKK + (krow % KPB) * 64 + H * 16;
+  const uint32_t voff = (L / 8) * BLKV + (L % 8) * 16 + H * 128;
 
   f32x16 O[DB];
+  float m, l;
+  auto reset_acc = [&]() {
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
-  float m = -1e30f, l = 0.f;
+      for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
+    m = -1e30f;
+    l = 0.f;
+  };
+  reset_acc();
   const float sc = a.scale * 1.4426950408889634f;
   const float th = TH_LOG2 / sc;  // threshold in raw score units
 
-  auto scores = [&](const unsigned char* Kb, f32x16* S) {
+  bf16x8 qf[KSTEPS];
+  auto load_q = [&](const Item& I) {
+    const uint16_t* qp = qg + ((size_t)token_of(I) * a.hq + head_of(I)) * D + 8 * H;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
-#pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) {
-        const bf16x8 kf = *(const bf16x8*)(Kb + kb * 32 * (D * 2) + koff[s]);
-        S[kb] = mfma32(kf, qf[s], S[kb]);
-      }
-    }
+    for (int s = 0; s < KSTEPS; ++s) qf[s] = *(const bf16x8*)(qp + 16 * s);
   };
 
-  // online softmax + accumulation of one tile whose scores are in S
-  auto softmax_accumulate = [&](const unsigned char* Vb, const f32x16* S) {
+  // LDS operand reads are issued a few MFMAs ahead of their use (software prefetch enforced with
+  // scheduling groups), so that the LDS latency is hidden behind the matrix pipe.
+  auto scores = [&](const unsigned char* Kb, f32x16* S) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
+    // the two key blocks alternate so that consecutive MFMAs never depend on each other
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16x8 kf = *(const bf16x8*)(Kb + koff + kb * (32 / KPB) * BLKK + (s >> 1) * 64 * KPB + (s & 1) * 32);
+        S[kb] = mfma32(kf, qf[s], S[kb]);
+      }
+    constexpr int NM = 2 * KSTEPS, PF = 4;
+    __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
+#pragma unroll
+    for (int i = 0; i < NM - PF; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, PF, 0);
+  };
+
+  // online softmax of one tile whose scores are in S: raises the running maximum (rarely) and
+  // returns the probabilities as bf16 B operands
+  auto softmax = [&](const f32x16* S, bf16x8* pb) {
     float bm = max3(S[0][0], S[0][1], S[0][2]);
 #pragma unroll
     for (int r = 3; r < 15; r += 2) bm = max3(bm, S[0][r], S[0][r + 1]);
@@ -211,7 +266,6 @@ __global__ void __launch_bounds__(128 * HG, (HG == 4 ? 1 : 2)) k_prefill_bf16(Pr
     }
     const float msc = m * sc;
     float rowsum = 0.f;
-    bf16x8 pb[4];
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
       f32x8 p;
@@ -223,95 +277,206 @@ __global__ void __launch_bounds__(128 * HG, (HG == 4 ? 1 : 2)) k_prefill_bf16(Pr
       pb[st] = __builtin_convertvector(p, bf16x8);
     }
     l += rowsum;
+  };
+
+  auto accumulate = [&](const unsigned char* Vb, const bf16x8* pb) {
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {  // keys 16*st + 8H .. +7
+    for (int st = 0; st < 4; ++st)  // keys 16*st + 8H .. +7
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(Vb + st * 16 * (D * 2) + voff[0][db]));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(Vb + st * 16 * (D * 2) + voff[1][db]));
-        const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        O[db] = mfma32(__builtin_bit_cast(bf16x8, v8), pb[st], O[db]);
+        const bf16x8 vf = *(const bf16x8*)(Vb + voff + db * 4 * BLKV + st * 256);
+        O[db] = mfma32(vf, pb[st], O[db]);
       }
-    }
-  };
-
-  const int c0 = a.rowptr[qt], c1 = a.rowptr[qt + 1];
-  // FULL tiles come first in the row; a ragged last key tile needs the masked loop as well
-  int c_fast = c0 + a.nfull[qt];
-  if (c_fast > c0 && a.col[c_fast - 1] * TN + TN > T) --c_fast;
-
-  // Ring pipeline step shared by both loops: wait for tile `it`, barrier, refill the freed buffer.
-  auto advance = [&](int it) {
-    const int ahead = min(NSTAGE - 2, c1 - 1 - it);  // later tiles whose loads may stay in flight
-    if (NSTAGE > 3 && ahead >= 2) wait_vmcnt<(NSTAGE > 3 ? 2 : 0) * LPT>();
-    else if (NSTAGE > 2 && ahead == 1) wait_vmcnt<(NSTAGE > 2 ? 1 : 0) * LPT>();
-    else wait_vmcnt<0>();
-    __syncthreads();  // everyone's loads have landed, and everyone has left the buffer refilled next
-    if (it + NSTAGE - 1 < c1) issue_loads((it - c0 + NSTAGE - 1) % NSTAGE, a.col[it + NSTAGE - 1] * TN);
-  };
-
+    constexpr int NM = 4 * DB, PF = 4;
+    __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
 #pragma unroll
-  for (int p = 0; p < NSTAGE - 1; ++p)
-    if (c0 + p < c1) issue_loads(p, a.col[c0 + p] * TN);
+    for (int i = 0; i < NM - PF; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, PF, 0);
+  };
 
-  for (int it = c0; it < c_fast; ++it) {  // FULL tiles: no mask
-    advance(it);
-    const int buf = (it - c0) % NSTAGE;
-    f32x16 S[2];
-    scores(Kbase + buf * TILE_BYTES, S);
-    softmax_accumulate(Vbase + buf * TILE_BYTES, S);
-  }
+  // ---------------------------------------------------------------- persistent loop over items
+  long item = blockIdx.x;
+  if (item >= n_items) return;
+  Item cur = load_item(item);
+  bool has_next = item + gridDim.x < n_items;
+  Item nxt = has_next ? load_item(item + gridDim.x) : cur;
 
-  if (c_fast < c1) {  // PARTIAL / ragged tiles: per-token mask
-    const uint64_t* vis_row = a.node_vis + (int64_t)(a.node_start[b] + a.tok_node[tok]) * a.W;
-    const uint64_t vis0 = vis_row[0];
-    const int32_t* tn = a.tok_node + cu;
-    for (int it = c_fast; it < c1; ++it) {
-      advance(it);
-      const int buf = (it - c0) % NSTAGE;
-      const int j0 = a.col[it] * TN;
+  // The K/V tile stream runs ahead of the computation, across the item boundary: `ti` tiles have
+  // been issued, `tc` consumed; tile t lives in ring slot t % NSTAGE.
+  int ti = 0, tc = 0;
+  int iss_next = 0, iss_idx = 0;  // issue cursor: item (0 current / 1 next) and tile index in its row
+  // the cursor's item, field by field (scalar registers)
+  int is_cu = cur.cu, is_T = cur.T, is_c0 = cur.c0, is_N = cur.N, is_hk = cur.hk, is_ktb = cur.ktb;
+  auto cursor_enter = [&](const Item& I) {
+    is_cu = I.cu; is_T = I.T; is_c0 = I.c0; is_N = I.N; is_hk = I.hk; is_ktb = I.ktb;
+    iss_idx = 0;
+  };
+  i32x8 colv = {0, 0, 0, 0, 0, 0, 0, 0};  // key-tile indices iss_idx & ~7 .. +7 of the cursor's row
+  auto try_issue = [&]() {
+    if (iss_idx >= is_N) {
+      if (iss_next || !has_next) return false;
+      iss_next = 1;
+      cursor_enter(nxt);
+    }
+    const int cu = is_cu, T = is_T, c0 = is_c0, hk = is_hk, ktb = is_ktb;
+    // Scalar load of the key-tile indices, eight at a time so that the load latency is paid once
+    // per eight tiles (the compiler would use a vector load here, whose wait drains the K/V
+    // prefetches, because it cannot prove the table is not written by the kernel).  The table
+    // has eight spare entries at its end, so the load never leaves it.
+    const int sub = iss_idx & 7;
+    if (sub == 0) {
+      const int32_t* cp = a.col + __builtin_amdgcn_readfirstlane(c0 + iss_idx);
+      asm volatile("s_load_dwordx8 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(colv) : "s"(cp) : "memory");
+    }
+    int kt = colv[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) kt = (sub == e) ? colv[e] : kt;
+#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 16)
+    kt = iss_idx;
+#endif
+#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 8)
+    (void)cu; (void)T; (void)hk; (void)ktb;
+#else
+    issue_loads(ti % NSTAGE, cu, T, hk, ktb, kt);
+#endif
+    ++ti;
+    ++iss_idx;
+    return true;
+  };
+#pragma unroll
+  for (int p = 0; p < NSTAGE - 1; ++p) try_issue();
+  load_q(cur);
+
+  while (true) {
+    const int i_row = cur.row0 + 32 * rb + L;  // row inside the sequence
+    const int tok = token_of(cur), head = head_of(cur);
+    const uint64_t* vis_row = nullptr;
+    uint64_t vis0 = 0;
+    if (cur.nfast < cur.N) {  // some tile of this item needs the per-token mask
+      vis_row = a.node_vis + (int64_t)(cur.nstart + a.tok_node[tok]) * a.W;
+      vis0 = vis_row[0];
+    }
+
+    // The Q rows were loaded with ordinary global loads; make them "arrive" here, outside the
+    // tile loop, so that no conservative wait on them ends up inside it (that wait would also
+    // drain the K/V prefetches every tile).
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) asm volatile("" ::"v"(qf[s]));
+    for (int n = 0; n < cur.N; ++n) {
+      if (ti == tc) try_issue();  // nothing in flight (only right after very short items)
+      const int younger = ti - tc - 1;  // tiles issued after the one needed now
+      if (NSTAGE > 3 && younger >= 3) wait_vmcnt<(NSTAGE > 3 ? 3 : 0) * LPT>();
+      else if (NSTAGE > 2 && younger == 2) wait_vmcnt<(NSTAGE > 2 ? 2 : 0) * LPT>();
+      else if (younger == 1) wait_vmcnt<LPT>();
+      else wait_vmcnt<0>();
+      // Bare barrier (no memory fence: __syncthreads would drain every outstanding prefetch).
+      // Everyone's loads of tile tc have landed (each wave waited for its own above) and
+      // everyone has left tile tc-1.
+#if !defined(DAGATTN_ABL) || !(DAGATTN_ABL & 32)
+      __builtin_amdgcn_s_barrier();
+#endif
+      asm volatile("" ::: "memory");
+      while (ti - tc < NSTAGE && try_issue()) {
+      }
+      const int buf = tc % NSTAGE;
       f32x16 S[2];
-      scores(Kbase + buf * TILE_BYTES, S);
+      bf16x8 pb[4];
+#ifdef DAGATTN_ABL  // development ablations: bit 0 no scores, 1 no softmax, 2 no accumulate
+      if (DAGATTN_ABL & 1) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = j0 + 32 * kb + 16 * (r >> 3) + 8 * H + (r & 7);
-          const int nj = tn[min(j, T - 1)];
-          const uint64_t word = (a.W == 1) ? vis0 : vis_row[nj >> 6];
-          const bool ok = (j <= i_row) && (j < T) && ((word >> (nj & 63)) & 1);
-          S[kb][r] = ok ? S[kb][r] : -INFINITY;
-        }
-      softmax_accumulate(Vbase + buf * TILE_BYTES, S);
-    }
-  }
-
-  const float l_tot = l + __shfl_xor(l, 32);
-  if (i_row < T) {
-    const float inv = 1.f / l_tot;
-    uint16_t* og = (uint16_t*)a.out + ((size_t)tok * a.hq + head) * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        u32x2 o;
-        o[0] = dag_pack_bf2(O[db][4 * r4] * inv, O[db][4 * r4 + 1] * inv);
-        o[1] = dag_pack_bf2(O[db][4 * r4 + 2] * inv, O[db][4 * r4 + 3] * inv);
-        *(u32x2*)(og + 32 * db + 8 * r4 + 4 * H) = o;
+          for (int r = 0; r < 16; ++r) S[kb][r] = (float)(n + r);
+      } else {
+        scores(Kbase + buf * KTILE, S);
       }
-    if (a.lse && H == 0) a.lse[(size_t)tok * a.hq + head] = m * a.scale + logf(l_tot);
+      if (n == cur.N - 1 && has_next) load_q(nxt);
+      if (DAGATTN_ABL & 2) {
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+          f32x8 p;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) p[e] = S[st >> 1][8 * (st & 1) + e];
+          pb[st] = __builtin_convertvector(p, bf16x8);
+        }
+      } else {
+        softmax(S, pb);
+      }
+      if (DAGATTN_ABL & 4) {
+        O[0][0] += (float)pb[0][0];
+      } else {
+        accumulate(Vbase + buf * VTILE, pb);
+      }
+      ++tc;
+      continue;
+#endif
+      scores(Kbase + buf * KTILE, S);
+      if (n == cur.N - 1 && has_next) load_q(nxt);  // the Q registers are free from here on
+      if (n >= cur.nfast) {
+        const int j0 = a.col[__builtin_amdgcn_readfirstlane(cur.c0 + n)] * TN;
+        const int32_t* tn = a.tok_node + cur.cu;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int j = j0 + 32 * kb + 16 * (r >> 3) + 8 * H + (r & 7);
+            const int nj = tn[min(j, cur.T - 1)];
+            const uint64_t word = (a.W == 1) ? vis0 : vis_row[nj >> 6];
+            const bool ok = (j <= i_row) && (j < cur.T) && ((word >> (nj & 63)) & 1);
+            S[kb][r] = ok ? S[kb][r] : -INFINITY;
+          }
+      }
+      softmax(S, pb);
+      accumulate(Vbase + buf * VTILE, pb);
+      ++tc;
+    }
+
+    const float l_tot = l + __shfl_xor(l, 32);
+    if (i_row < cur.T) {
+      const float inv = 1.f / l_tot;
+      uint16_t* og = (uint16_t*)a.out + ((size_t)tok * a.hq + head) * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          u32x2 o;
+          o[0] = dag_pack_bf2(O[db][4 * r4] * inv, O[db][4 * r4 + 1] * inv);
+          o[1] = dag_pack_bf2(O[db][4 * r4 + 2] * inv, O[db][4 * r4 + 3] * inv);
+          *(u32x2*)(og + 32 * db + 8 * r4 + 4 * H) = o;
+        }
+      if (a.lse && H == 0) a.lse[(size_t)tok * a.hq + head] = m * a.scale + logf(l_tot);
+    }
+    if (!has_next) break;
+    reset_acc();
+    item += gridDim.x;
+    cur = nxt;
+    has_next = item + gridDim.x < n_items;
+    if (has_next) nxt = load_item(item + gridDim.x);
+    if (iss_next) iss_next = 0;  // the cursor was already in what is now the current item
+    else cursor_enter(cur);      // (all tiles of the old item were issued: start of the new one)
   }
 }
 
 template <int D, int HG, int NSTAGE>
 int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
-  constexpr size_t sm = (size_t)2 * NSTAGE * TN * D * 2;
+  constexpr int KPB = 64 / (D / 8);
+  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128));
   if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, NSTAGE>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sm) != hipSuccess)
     return DAG_ERR_HIP;
-  const unsigned grid = (unsigned)(a.total_qtiles * a.hkv * hs);
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    return DAG_ERR_HIP;
+  hipLaunchKernelGGL((k_vt_prepare<D>), dim3((unsigned)a.total_ktiles, (unsigned)a.hkv), dim3(256), 0, stream,
+                     (const uint16_t*)a.v, (uint16_t*)a.vt, a.ktile_start, a.cu_seqlens, a.n_seqs, a.hkv);
+  DAG_LAUNCH_CHECK();
+  const long n_items = (long)a.total_qtiles * a.hkv * hs;
+  const long slots = (long)n_cu * (HG == 4 ? 1 : 2);
+  const unsigned grid = (unsigned)(n_items < slots ? n_items : slots);
   hipLaunchKernelGGL((k_prefill_bf16<D, HG, NSTAGE>), dim3(grid), dim3(128 * HG), sm, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;

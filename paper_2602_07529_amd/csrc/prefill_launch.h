@@ -8,18 +8,21 @@ struct PrefillArgs {
   const void* v;
   void* out;
   float* lse;
+  void* vt;  // workspace: key-tile-wise transposed V, [key tile][kv head][D][64] bf16 (bf16 path)
   const int32_t* cu_seqlens;
   const int32_t* node_start;
   const int32_t* tok_node;
   const uint64_t* node_vis;
   const int32_t* qtile_start;
+  const int32_t* ktile_start;
   const int32_t* rowptr;
   const int32_t* col;
   const uint8_t* flag;
   const int32_t* nfull;
   const int32_t* qtile_order;
+  const int32_t* qtile_desc;  // [total_qtiles][8], see dag_meta_t
   int n_seqs, W, hq, hkv;
-  int64_t total_qtiles;
+  int64_t total_qtiles, total_ktiles;
   float scale;
 };
 

@@ -65,16 +65,34 @@ def oracle_meta(dag_list, tm, tn):
         qtile_nfull=cat(out.get("nfull", []), np.int64),
         useful_pairs=np.array(out["useful_pairs"], dtype=np.int64))
     cnt = np.array(out["cnt"], dtype=np.int64)
-    # launch order: descending tile count, ties by ascending index
-    res["qtile_order"] = np.array(sorted(range(len(cnt)), key=lambda i: (-cnt[i], i)), dtype=np.int64)
+    # launch order: sequences in order; inside a sequence descending tile count, ties by ascending index
+    seq_of = np.repeat(np.arange(len(dag_list)), np.diff(res["qtile_start"]))
+    order = sorted(range(len(cnt)), key=lambda i: (seq_of[i], -cnt[i], i))
+    res["qtile_order"] = np.array(order, dtype=np.int64)
+    # launch descriptors: {token offset, tokens, first row, CSR start, tiles, mask-free tiles, node offset, tile id}
+    node_start = np.concatenate([[0], np.cumsum([len(L) for L, _ in dag_list])])
+    ktiles = [-(-int(np.sum(L)) // tn) for L, _ in dag_list]
+    res["ktile_start"] = np.concatenate([[0], np.cumsum(ktiles)]).astype(np.int64)
+    desc = np.zeros((len(cnt), 8), dtype=np.int64)
+    for oi, qt in enumerate(order):
+        b = int(seq_of[qt])
+        T = int(res["cu_seqlens"][b + 1] - res["cu_seqlens"][b])
+        c0 = int(res["qtile_rowptr"][qt])
+        nf = int(res["qtile_nfull"][qt])
+        if nf > 0 and (int(res["qtile_col"][c0 + nf - 1]) + 1) * tn > T:
+            nf -= 1
+        desc[oi] = [res["cu_seqlens"][b], T, (qt - res["qtile_start"][b]) * tm, c0, cnt[qt], nf, node_start[b],
+                    res["ktile_start"][b]]
+    res["qtile_desc"] = desc.reshape(-1)
     return res
 
 
 def assert_meta_equal(meta, ref):
     torch.cuda.synchronize()
     nnz = int(ref["qtile_rowptr"][-1])
-    for name in ("cu_seqlens", "tok_node", "pos_ids", "node_tok_start", "node_pos_start", "qtile_start",
-                 "block_map_off", "block_map", "qtile_rowptr", "qtile_nfull", "qtile_order", "useful_pairs"):
+    for name in ("cu_seqlens", "tok_node", "pos_ids", "node_tok_start", "node_pos_start", "qtile_start", "ktile_start",
+                 "block_map_off", "block_map", "qtile_rowptr", "qtile_nfull", "qtile_order", "qtile_desc",
+                 "useful_pairs"):
         got = meta.get(name).cpu().numpy().astype(np.int64)
         assert got.shape == ref[name].shape, name
         assert np.array_equal(got, ref[name].astype(np.int64)), name

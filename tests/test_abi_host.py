@@ -24,7 +24,8 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"dag_meta_sizes", "dag_build_meta", "dag_rope_qk", "dag_attn_prefill", "dag_kv_append_rope",
-            "dag_attn_decode", "dag_decode_workspace_bytes", "dag_prefill_tile_shape", "dag_strerror",
+            "dag_attn_decode", "dag_decode_workspace_bytes", "dag_prefill_workspace_bytes", "dag_prefill_tile_shape",
+            "dag_strerror",
             "dag_version"} <= set(names)
     L = C.CDLL(B.LIB_PATH)
     for n in names:
@@ -65,7 +66,7 @@ def test_meta_sizes_counts():
     # ragged: T = 100 with 32x64 tiles -> 4 query tiles, 2 key tiles
     s = B.dag_meta_sizes(_desc([dags.linear_chain([100])], tile=(32, 64)))
     assert (s.total_qtiles, s.total_tiles) == (4, 8)
-    assert s.csr_capacity == 1 + 1 + 2 + 2
+    assert s.csr_capacity == 1 + 1 + 2 + 2 + 8      # eight spare entries at the end
     # empty batch and an empty sequence
     s = B.dag_meta_sizes(B.DagDesc(np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros((0, 1), np.uint64), 1, 32, 64))
     assert s.total_tokens == 0 and s.total_qtiles == 0
@@ -142,13 +143,21 @@ def test_rope_and_prefill_argument_errors():
         setattr(m, name, FAKE)
     p = C.c_void_p(FAKE)
     # tile shape of the meta does not match the kernel's (64x64)
+    big = 1 << 30
     m.tile_m = 32
-    assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 8, 8, 128, 0.1, B.DAG_BF16, None) == -7
+    assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 8, 8, 128, 0.1, B.DAG_BF16, p, big, None) == -7
     m.tile_m = 64
-    assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 96, 0.1, B.DAG_BF16, None) == -7
-    assert L.dag_attn_prefill(C.byref(m), None, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None) == -1
-    assert L.dag_attn_prefill(C.byref(m), C.c_void_p(FAKE + 2), p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None) == -8
-    assert L.dag_attn_prefill(None, p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None) == -1
+    assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 96, 0.1, B.DAG_BF16, p, big, None) == -7
+    assert L.dag_attn_prefill(C.byref(m), None, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, big, None) == -1
+    assert L.dag_attn_prefill(C.byref(m), C.c_void_p(FAKE + 2), p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, big,
+                              None) == -8
+    assert L.dag_attn_prefill(None, p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, big, None) == -1
+    # workspace: the bf16 path needs room for the transposed copy of V, the fp32 path needs none
+    need = L.dag_prefill_workspace_bytes(C.byref(m), 8, 128, B.DAG_BF16)
+    assert need == 1 * 8 * 128 * 64 * 2 + 256          # one key tile x 8 kv heads
+    assert L.dag_prefill_workspace_bytes(C.byref(m), 8, 128, B.DAG_F32) == 0
+    assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, need - 1, None) == -6
+    assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None, 0, None) == -6
 
 
 def test_decode_argument_errors():
