@@ -1,23 +1,28 @@
 // bf16 DAG attention prefill for gfx950 (paper Eq. 2 + Eq. 3), MFMA 32x32x16 with fp32 accumulation.
 //
 // Work decomposition.  A work item is one 64-row query tile of one KV head with HG of that KV
-// head's query heads stacked: wave w handles the 32-row block w / HG of head w % HG, so every wave
-// of the workgroup consumes the same K/V tiles.  With HG = 4 that is eight waves, two per SIMD, so
-// that one wave's softmax (vector ALU) overlaps the other's MFMAs.  The kernel is persistent: the
-// grid has one workgroup per CU slot and workgroup g processes items g, g + grid, ... of the
-// launch list (sequences in order, heavy query tiles first).  The K/V stream of the next item is
-// prefetched while the current one finishes; and because workgroups are placed round-robin on
-// the eight XCDs, an XCD keeps working on one KV head of one sequence at a time, whose K/V then
-// stay in its L2.
+// head's query heads stacked, so every wave of the workgroup consumes the same K/V tiles.  A wave
+// owns RB 32-row blocks of one head (RB = 2: four waves, one per SIMD, each K/V operand read from
+// LDS feeds two MFMAs; RB = 1: eight waves).  The kernel is persistent: the grid has one
+// workgroup per CU and workgroup g processes items g, g + grid, ... of the launch list (sequences
+// in order, heavy query tiles first).  The K/V stream of the next item is prefetched while the
+// current one finishes; and because workgroups are placed round-robin on the eight XCDs, an XCD
+// keeps working on one KV head of one sequence at a time, whose K/V then stay in its L2.
 //
 // Only the key tiles the block map lists are visited.  The CSR row of a query tile lists its FULL
-// tiles first: those need no mask; PARTIAL tiles (and a ragged last tile) follow and evaluate the
-// per-token mask.
+// tiles first: those need no mask and run through the software pipeline below; PARTIAL tiles (and
+// a ragged last tile) follow and evaluate the per-token mask in a plain loop.
+//
+// Software pipeline.  The matrix pipe and the vector ALU of a SIMD run concurrently only if one
+// instruction stream feeds both, so a wave works in steps of half a key tile (32 keys) and each
+// step interleaves three independent pieces:  scores of half g + 1 (MFMA),  the exponentials of
+// half g (vector ALU),  and the P V product of half g - 1 (MFMA).  sched_group_barrier fixes the
+// interleaving (one MFMA, one LDS operand read, a few vector instructions, ...).
 //
 // Data movement.  K tiles (64 keys x D) and V^T tiles (D x 64 keys, from a key-tile-wise
 // transposed copy of V that a small pre-pass writes into the workspace) go from global memory
 // straight into LDS (global_load_lds, 16 bytes per lane, no staging registers) through a ring of
-// NSTAGE buffers.  Bare s_barrier + explicit vmcnt waits keep up to NSTAGE-1 tiles in flight (a
+// NSTAGE buffers.  Bare s_barrier + explicit vmcnt waits keep the ring's loads in flight (a
 // __syncthreads would drain them).  A wave-level load writes 1 KiB of consecutive LDS (a "block");
 // which 16-byte chunk of which row a lane fetches is chosen so that (a) four consecutive lanes
 // read 64 consecutive bytes of global memory (the texture path looks up one cache line per
@@ -28,13 +33,9 @@
 //             [chunk / 4][key % R][chunk % 4][16 B]
 //   V^T block = 8 output dimensions x 8 key groups, stride 1024 + 128 bytes: [key group][dim % 8][16 B]
 //             (the workspace copy is stored in this order, so its loads are linear)
-// The MFMA A operand of both products is then one ds_read_b128 per instruction: LDS bandwidth, not
-// the matrix pipe, is the scarce resource here (a 32x32x16 MFMA consumes a 1 KiB operand per wave
-// every 32 cycles), which is why V is transposed once in global memory instead of with the slower
-// LDS transpose loads.
 //
 // Register layout.  Scores are computed transposed, S^T = K Q^T, so that after the MFMA a lane
-// holds one query row (lane % 32) and 16 keys of each 32-key block in registers: the softmax row
+// holds one query row (lane % 32) and 16 keys of the 32-key half in registers: the softmax row
 // reductions are in-register plus one exchange between the two half waves, and the probabilities
 // already sit in the B-operand layout of the second product O^T = V^T P^T.  MFMA row i of a
 // 32-key block is mapped to key pi(i) so that registers 0..7 / 8..15 of a score block hold 8
@@ -43,6 +44,8 @@
 // Softmax.  Online softmax in the log2 domain.  The running maximum is only raised when some row
 // of the wave exceeds it by more than 2^8 (the accumulator rescale is then rare); probabilities
 // may exceed 1 by that factor, which fp32 accumulation and the final division absorb exactly.
+#include <type_traits>
+
 #include "common.h"
 #include "prefill_launch.h"
 
@@ -50,10 +53,15 @@ namespace {
 
 constexpr int TN = 64;
 constexpr int TM = 64;
+constexpr int NSTAGE = 4;  // ring depth: two tiles in use by the pipeline, two in flight
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
 typedef __attribute__((ext_vector_type(8))) float f32x8;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef std::true_type yes_t;
+typedef std::false_type no_t;
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -72,9 +80,31 @@ __device__ __forceinline__ void wait_vmcnt() {  // s_waitcnt vmcnt(N) only (gfx9
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+__device__ __forceinline__ void wait_lgkmcnt(int n) {  // s_waitcnt lgkmcnt(n) only, n = 0..3 (folds when n is constant)
+  switch (n) {
+    case 0: __builtin_amdgcn_s_waitcnt(0xC07F); break;
+    case 1: __builtin_amdgcn_s_waitcnt(0xC17F); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0xC27F); break;
+    default: __builtin_amdgcn_s_waitcnt(0xC37F); break;
+  }
+}
+
+__device__ __forceinline__ int sgpr(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {  // byte address inside LDS of a __shared__ pointer
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 4)
+#define DAGATTN_ABL_EX 1
+#else
+#define DAGATTN_ABL_EX 0
+#endif
+
 struct Item {  // wave-uniform description of a work item
   int cu, T, row0, c0, N, nfast, nstart, ktb, hk, hs;
 };
+
 
 // ---------------------------------------------------------------------------------------------
 // Pre-pass: V [T][hkv][D] -> V^T tiles [key tile][kv head][D / 8][8 key groups][8 dims][8 keys]
@@ -109,36 +139,42 @@ __global__ void __launch_bounds__(256) k_vt_prepare(const uint16_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int D, int HG, int NSTAGE>
-__global__ void __launch_bounds__(128 * HG, (HG == 4 ? 1 : 2)) k_prefill_bf16(PrefillArgs a) {
-  constexpr int NW = 2 * HG;                 // waves: two 32-row blocks x HG heads
+template <int D, int HG, int RB>
+__global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillArgs a) {
+  constexpr int NRG = 2 / RB;                // groups of RB row blocks, spread over waves
+  constexpr int NW = HG * NRG;               // waves
   constexpr int CH = D / 8;                  // 16-byte chunks per K row
   constexpr int KSTEPS = D / 16;             // MFMA steps of the score product
   constexpr int DB = D / 32;                 // 32-row blocks of O^T
   constexpr int KPB = 64 / CH;               // keys per K block
   constexpr int NBK = TN / KPB;              // K blocks per tile
   constexpr int NBV = D / 8;                 // V^T blocks per tile (8 output dimensions each)
-  constexpr int IPK = NBK / NW, IPV = NBV / NW;  // blocks per tile and wave
+  // Only the first NISS waves (one per SIMD) issue the K/V loads: the scalar work of an issue
+  // would otherwise run in both waves of a SIMD at the same time, right after the barrier, and
+  // leave the matrix pipe idle; this way the other wave of the SIMD computes meanwhile.
+  constexpr int NISS = NW == 8 ? 4 : NW;
+  constexpr int IPK = NBK / NISS, IPV = NBV / NISS;  // blocks per tile and issuing wave
   constexpr int LPT = IPK + IPV;             // loads per tile and wave
   constexpr int BLKK = 1024 + 16;            // block strides (skewed so that reads are conflict free)
   constexpr int BLKV = 1024 + 16 * 8;
   constexpr int KTILE = NBK * BLKK, VTILE = NBV * BLKV;
   constexpr float TH_LOG2 = 8.f;
-  static_assert(IPK >= 1 && IPK * NW == NBK && IPV >= 1 && IPV * NW == NBV, "tile loads must divide over the waves");
-  static_assert((NSTAGE - 1) * LPT < 64 && NSTAGE >= 2 && NSTAGE <= 4, "vmcnt range / ring depth");
+  static_assert(IPK >= 1 && IPK * NISS == NBK && IPV >= 1 && IPV * NISS == NBV, "tile loads must divide over the waves");
+  static_assert((NSTAGE - 2) * LPT < 64 && NSTAGE >= 3, "vmcnt range / ring depth");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* const Kbase = smem;                    // K[NSTAGE][KTILE]
   unsigned char* const Vbase = smem + NSTAGE * KTILE;   // V^T[NSTAGE][VTILE]
+  unsigned char* const Abase = smem + NSTAGE * (KTILE + VTILE);  // node ids of the keys [NSTAGE][64]
 
   const int G = a.hq / a.hkv;
   const int HS = G / HG;  // items per (query tile, KV head)
   const int nhw = a.hkv * HS;
   const long n_items = (long)a.total_qtiles * nhw;
 
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, w = sgpr(tid >> 6), lane = tid & 63;
   const int L = lane & 31, H = lane >> 5;
-  const int rb = w / HG, hj = w % HG;
+  const int rg = w / HG, hj = w % HG;
 
   const uint16_t* qg = (const uint16_t*)a.q;
   const unsigned char* kg = (const unsigned char*)a.k;
@@ -149,152 +185,246 @@ __global__ void __launch_bounds__(128 * HG, (HG == 4 ? 1 : 2)) k_prefill_bf16(Pr
     const int oi = (int)(it / nhw), hw = (int)(it % nhw);
     const int32_t* d = a.qtile_desc + (size_t)oi * 8;
     Item I;
-    I.cu = d[0]; I.T = d[1]; I.row0 = d[2]; I.c0 = d[3]; I.N = d[4]; I.nfast = d[5]; I.nstart = d[6]; I.ktb = d[7];
-    I.hk = hw / HS; I.hs = hw % HS;
+    I.cu = sgpr(d[0]); I.T = sgpr(d[1]); I.row0 = sgpr(d[2]); I.c0 = sgpr(d[3]);
+    I.N = sgpr(d[4]); I.nfast = sgpr(d[5]); I.nstart = sgpr(d[6]); I.ktb = sgpr(d[7]);
+    I.hk = sgpr(hw / HS); I.hs = sgpr(hw % HS);
     return I;
   };
-  auto token_of = [&](const Item& I) { return I.cu + min(I.row0 + 32 * rb + L, I.T - 1); };
+  auto row_of = [&](const Item& I, int r) { return I.row0 + 32 * (rg * RB + r) + L; };  // row inside the sequence
+  auto token_of = [&](const Item& I, int r) { return I.cu + min(row_of(I, r), I.T - 1); };
   auto head_of = [&](const Item& I) { return I.hk * G + I.hs * HG + hj; };
 
   // What this lane fetches in a wave-level load (LDS position 16*lane inside the block):
   //   K:   key (lane / 4) % KPB of the block, chunk 4 * (lane / (4 * KPB)) + lane % 4: four
   //        consecutive lanes fetch 64 consecutive bytes of one row (one cache-line lookup)
   //   V^T: piece `lane` of the block (the workspace copy already has the LDS order)
+  // Addresses are a wave-uniform 64-bit base plus one 32-bit per-lane offset.
   const int kkey = (lane >> 2) % KPB;
   const uint32_t kchunk = (4 * (lane / (4 * KPB)) + (lane & 3)) * 16;
-  const uint32_t ksrc = (w * KPB + kkey) * rowbytes + kchunk;
-  const uint32_t vsrc = w * 1024 + lane * 16;
+  const uint32_t ksrc = kkey * rowbytes + kchunk;
+  const uint32_t vsrc = lane * 16;
 
-  auto issue_loads = [&](int buf, int cu, int T, int hk, int ktb, int kt) {
+  // kbase / vbase: the cursor item's K rows (token cu, head hk) and V^T tiles (tile ktb, head hk,
+  // this wave's block); the tile adds a multiple of its index.
+  const uint32_t kt_kstride = (uint32_t)TN * rowbytes, kt_vstride = (uint32_t)a.hkv * (D * TN * 2);
+  auto issue_loads = [&](unsigned slot, const unsigned char* kbase, const unsigned char* vbase, int cu, int T, int kt,
+                         bool with_nodes) {
     const int j0 = kt * TN;
-    const unsigned char* ktile = kg + ((size_t)(cu + j0) * a.hkv + hk) * (D * 2);
-    const unsigned char* vtile = vtg + ((size_t)(ktb + kt) * a.hkv + hk) * (size_t)(D * TN * 2);
-    unsigned char* kl = Kbase + buf * KTILE + w * BLKK;
-    unsigned char* vl = Vbase + buf * VTILE + w * BLKV;
+    if (with_nodes) {  // a tile that needs the mask: node ids of its 64 keys (every wave writes the same record)
+      const int32_t* np = a.tok_node + cu + min(j0 + lane, T - 1);
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)np, (lds_ptr_t)(Abase + slot * 256), 4, 0, 0);
+    }
+    const unsigned char* ktile = kbase + (uint64_t)(uint32_t)kt * kt_kstride;
+    const unsigned char* vtile = vbase + (uint64_t)(uint32_t)kt * kt_vstride;
+    unsigned char* kl = Kbase + slot * KTILE + w * BLKK;
+    unsigned char* vl = Vbase + slot * VTILE + w * BLKV;
     if (j0 + TN <= T) {
 #pragma unroll
       for (int i = 0; i < IPK; ++i)
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ktile + (size_t)i * (NW * KPB) * rowbytes + ksrc),
-                                         (lds_ptr_t)(kl + i * NW * BLKK), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ktile + (size_t)((w + NISS * i) * KPB) * rowbytes + ksrc),
+                                         (lds_ptr_t)(kl + i * NISS * BLKK), 16, 0, 0);
     } else {  // ragged last tile: rows past the end re-read the last valid row (masked later)
       const int last = T - 1 - j0;
 #pragma unroll
       for (int i = 0; i < IPK; ++i) {
-        const int rk = min((w + NW * i) * KPB + kkey, last);
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ktile + (uint32_t)rk * rowbytes + kchunk),
-                                         (lds_ptr_t)(kl + i * NW * BLKK), 16, 0, 0);
+        const int rk = min((w + NISS * i) * KPB + kkey, last);
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ktile + ((uint32_t)rk * rowbytes + kchunk)),
+                                         (lds_ptr_t)(kl + i * NISS * BLKK), 16, 0, 0);
       }
     }
 #pragma unroll
     for (int i = 0; i < IPV; ++i)  // the transposed copy is zero padded: no ragged case
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vtile + i * (NW * 1024) + vsrc),
-                                       (lds_ptr_t)(vl + i * NW * BLKV), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vtile + i * (NISS * 1024) + vsrc), (lds_ptr_t)(vl + i * NISS * BLKV), 16,
+                                       0, 0);
   };
 
   // LDS read addresses (bytes inside a tile); every other read of the tile is an immediate away.
-  //   K, MFMA step s of key block kb:   koff + kb * (32 / KPB) * BLKK + (s / 2) * 64 * KPB + (s % 2) * 32
+  //   K, MFMA step s of key half h:      koff + h * (32 / KPB) * BLKK + (s / 2) * 64 * KPB + (s % 2) * 32
   //   V^T, key step st, output block db: voff + db * 4 * BLKV + st * 256
   const int krow = key_of_row(L);
   const uint32_t koff = (krow / KPB) * BLKK + (krow % KPB) * 64 + H * 16;
   const uint32_t voff = (L / 8) * BLKV + (L % 8) * 16 + H * 128;
 
-  f32x16 O[DB];
-  float m, l;
+  f32x16 O[RB][DB];
+  float m[RB], mth[RB], l[RB], bmax[RB];  // running maximum, maximum + threshold, row sum, block maximum
+  bf16x8 P0[RB][2], P1[RB][2];  // probabilities of the two key halves (B operands)
   auto reset_acc = [&]() {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
-    m = -1e30f;
-    l = 0.f;
-  };
-  reset_acc();
-  const float sc = a.scale * 1.4426950408889634f;
-  const float th = TH_LOG2 / sc;  // threshold in raw score units
-
-  bf16x8 qf[KSTEPS];
-  auto load_q = [&](const Item& I) {
-    const uint16_t* qp = qg + ((size_t)token_of(I) * a.hq + head_of(I)) * D + 8 * H;
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) qf[s] = *(const bf16x8*)(qp + 16 * s);
-  };
-
-  // LDS operand reads are issued a few MFMAs ahead of their use (software prefetch enforced with
-  // scheduling groups), so that the LDS latency is hidden behind the matrix pipe.
-  auto scores = [&](const unsigned char* Kb, f32x16* S) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
-    // the two key blocks alternate so that consecutive MFMAs never depend on each other
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 kf = *(const bf16x8*)(Kb + koff + kb * (32 / KPB) * BLKK + (s >> 1) * 64 * KPB + (s & 1) * 32);
-        S[kb] = mfma32(kf, qf[s], S[kb]);
-      }
-    constexpr int NM = 2 * KSTEPS, PF = 4;
-    __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
-#pragma unroll
-    for (int i = 0; i < NM - PF; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, PF, 0);
-  };
-
-  // online softmax of one tile whose scores are in S: raises the running maximum (rarely) and
-  // returns the probabilities as bf16 B operands
-  auto softmax = [&](const f32x16* S, bf16x8* pb) {
-    float bm = max3(S[0][0], S[0][1], S[0][2]);
-#pragma unroll
-    for (int r = 3; r < 15; r += 2) bm = max3(bm, S[0][r], S[0][r + 1]);
-    bm = fmaxf(bm, S[0][15]);
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) bm = max3(bm, S[1][r], S[1][r + 1]);
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
-    if (__builtin_amdgcn_ballot_w64(bm > m + th) != 0) {  // rare after the first tiles
-      const float m_new = fmaxf(m, bm);
-      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * sc);
-      m = m_new;
-      l *= alpha;
+    for (int r = 0; r < RB; ++r) {
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) O[db][r] *= alpha;
+        for (int e = 0; e < 16; ++e) O[r][db][e] = 0.f;
+      m[r] = -1e30f;
+      mth[r] = -1e30f;
+      l[r] = 0.f;
     }
-    const float msc = m * sc;
-    float rowsum = 0.f;
+  };
+  reset_acc();
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      f32x8 p;
+  for (int r = 0; r < RB; ++r)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(fmaf(S[st >> 1][8 * (st & 1) + e], sc, -msc));
-        rowsum += p[e];
+        P0[r][j][e] = (__bf16)0.f;
+        P1[r][j][e] = (__bf16)0.f;
       }
-      pb[st] = __builtin_convertvector(p, bf16x8);
+  const float sc = a.scale * 1.4426950408889634f;
+  const float th = TH_LOG2 / sc;  // threshold in raw score units
+
+  bf16x8 qf[RB][KSTEPS];
+  auto load_q = [&](const Item& I) {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const uint16_t* qp = qg + ((size_t)token_of(I, r) * a.hq + head_of(I)) * D + 8 * H;
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) qf[r][s] = *(const bf16x8*)(qp + 16 * s);
     }
-    l += rowsum;
   };
 
-  auto accumulate = [&](const unsigned char* Vb, const bf16x8* pb) {
+  // row maxima of a half; true when some row of the wave exceeds its running maximum by the threshold
+  auto row_max = [&](const f32x16* S) {
+    bool need = false;
 #pragma unroll
-    for (int st = 0; st < 4; ++st)  // keys 16*st + 8H .. +7
+    for (int r = 0; r < RB; ++r) {
+      float bm = max3(S[r][0], S[r][1], S[r][2]);
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 vf = *(const bf16x8*)(Vb + voff + db * 4 * BLKV + st * 256);
-        O[db] = mfma32(vf, pb[st], O[db]);
-      }
-    constexpr int NM = 4 * DB, PF = 4;
-    __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
-#pragma unroll
-    for (int i = 0; i < NM - PF; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      for (int e = 3; e < 15; e += 2) bm = max3(bm, S[r][e], S[r][e + 1]);
+      bm = fmaxf(bm, S[r][15]);
+      bmax[r] = bm;  // this lane's 16 keys only; the other half wave has the rest of the row
+      need |= bm > mth[r];
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, PF, 0);
+    return __builtin_amdgcn_ballot_w64(need) != 0;
+  };
+
+  // ---- one pipeline step, written slot by slot (a scheduling barrier after every slot keeps the
+  // order): slot = the LDS read of the operand needed PF slots later, RB MFMAs on one operand,
+  // and a share of the step's exponentials.  Pieces (each optional):
+  //   QK: Sn[r]  = K_h Q_r^T      scores of key half HQ of the tile at Kb (first KSTEPS slots)
+  //   PV: O[r]  += V_h^T Pp[r]    the 32 keys of half HV of the tile at Vb (last 2 DB slots)
+  //   EX: Pc[r]  = exp2(sc (Sc[r] - m[r]))  probabilities of a half, row sums added to l
+  // `extra` runs in slot 1 (used to issue the next K/V tile loads in the shadow of the MFMAs).
+  // With QK, the row maxima of Sn are taken two slots after the last score MFMA and the return
+  // value says whether they call for a rescale.
+  auto step = [&](auto qk_c, auto pv_c, auto ex_c, auto hq_c, auto hv_c, const unsigned char* Kb, f32x16* Sn,
+                  const unsigned char* Vb, const bf16x8 (*Pp)[2], const f32x16* Sc, bf16x8 (*Pc)[2], auto&& extra) {
+    constexpr bool QK = decltype(qk_c)::value, PV = decltype(pv_c)::value, EX = decltype(ex_c)::value;
+    constexpr int HQ = decltype(hq_c)::value, HV = decltype(hv_c)::value;
+    constexpr int NQ = QK ? KSTEPS : 0, NSLOT = NQ + (PV ? 2 * DB : 0), NU = EX ? 8 * RB : 0, PF = 3;
+    constexpr int MAXSLOT = NQ + 2 < NSLOT ? NQ + 2 : NSLOT;  // where the row maxima are taken
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    bf16x8 opnd[NSLOT];
+    float msc[RB], rs[RB];
+    bool need = false;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      msc[r] = EX ? m[r] * sc : 0.f;
+      rs[r] = 0.f;
+    }
+    // The operand reads are inline assembly with explicit lgkmcnt waits: LDS reads return in
+    // order, so before the MFMA of slot i exactly the reads of the slots after it may be pending
+    // (the compiler's own bookkeeping waits for all of them, which exposes the LDS latency).
+    const uint32_t kaddr = QK ? lds_addr(Kb) + koff : 0, vaddr = PV ? lds_addr(Vb) + voff : 0;
+    auto fetch = [&](int i) {
+#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 2)
+      opnd[i] = __builtin_bit_cast(bf16x8, u32x4{(uint32_t)i, 0u, 0u, 0u});
+      return;
+#endif
+      if (i < NQ)
+        asm volatile("ds_read_b128 %0, %1 offset:%2"
+                     : "=v"(opnd[i])
+                     : "v"(kaddr), "n"(HQ * (32 / KPB) * BLKK + (i >> 1) * 64 * KPB + (i & 1) * 32));
+      else
+        asm volatile("ds_read_b128 %0, %1 offset:%2"
+                     : "=v"(opnd[i])
+                     : "v"(vaddr), "n"(((i - NQ) % DB) * 4 * BLKV + (2 * HV + (i - NQ) / DB) * 256));
+    };
+#pragma unroll
+    for (int i = 0; i < PF && i < NSLOT; ++i) fetch(i);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < NSLOT; ++i) {
+      if (i + PF < NSLOT) fetch(i + PF);
+      wait_lgkmcnt(NSLOT - 1 - i < PF ? NSLOT - 1 - i : PF);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 1)
+        if (i < NQ) Sn[r][i] = (i == 0 ? 0.f : Sn[r][i]) + (float)opnd[i][0];
+        else O[r][(i - NQ) % DB][i] += (float)opnd[i][0];
+        continue;
+#endif
+        if (i < NQ) Sn[r] = mfma32(opnd[i], qf[r][i], i == 0 ? zero : Sn[r]);
+        else O[r][(i - NQ) % DB] = mfma32(opnd[i], Pp[r][(i - NQ) / DB], O[r][(i - NQ) % DB]);
+      }
+#if !defined(DAGATTN_ABL) || !(DAGATTN_ABL & 8)
+      if (i == 1) extra();
+#endif
+      if (QK && i == MAXSLOT) need = row_max(Sn);
+#pragma unroll
+      for (int u = (DAGATTN_ABL_EX ? 0 : i * NU / NSLOT); u < (DAGATTN_ABL_EX ? 0 : (i + 1) * NU / NSLOT); ++u) {  // two probabilities of one row
+        const int r = u / 8, e = 2 * (u % 8);
+        f32x2 p;
+        p[0] = __builtin_amdgcn_exp2f(fmaf(Sc[r][e], sc, -msc[r]));
+        p[1] = __builtin_amdgcn_exp2f(fmaf(Sc[r][e + 1], sc, -msc[r]));
+        rs[r] += p[0] + p[1];
+        asm volatile("" : "+v"(rs[r]));  // keep the running sum (no sum tree at the end of the step)
+        const bf16x2 pk = __builtin_convertvector(p, bf16x2);
+        Pc[r][e >> 3][e & 7] = pk[0];
+        Pc[r][e >> 3][(e & 7) + 1] = pk[1];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (QK && MAXSLOT == NSLOT) need = row_max(Sn);
+    if (EX) {
+#pragma unroll
+      for (int r = 0; r < RB; ++r) l[r] += rs[r];
+    }
+    return need;
+  };
+  typedef std::integral_constant<int, 0> h0_t;
+  typedef std::integral_constant<int, 1> h1_t;
+  auto nothing = []() {};
+  // raise the running maxima to bmax and rescale everything accumulated so far, including the
+  // probabilities that are still waiting for their P V product (rare after the first tiles)
+  auto rescale = [&]() {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const float m_new = fmaxf(m[r], fmaxf(bmax[r], __shfl_xor(bmax[r], 32)));
+      const float alpha = __builtin_amdgcn_exp2f((m[r] - m_new) * sc);
+      m[r] = m_new;
+      mth[r] = m_new + th;
+      l[r] *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) O[r][db][e] *= alpha;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        P0[r][j] = __builtin_convertvector(__builtin_convertvector(P0[r][j], f32x8) * alpha, bf16x8);
+        P1[r][j] = __builtin_convertvector(__builtin_convertvector(P1[r][j], f32x8) * alpha, bf16x8);
+      }
+    }
+  };
+  // probabilities of a half whose scores are in S (relative to the running maxima)
+  auto exp_half = [&](const f32x16* S, bf16x8 (*P)[2]) {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const float msc = m[r] * sc;
+      float rowsum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        f32x8 p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          p[e] = __builtin_amdgcn_exp2f(fmaf(S[r][8 * j + e], sc, -msc));
+          rowsum += p[e];
+        }
+        P[r][j] = __builtin_convertvector(p, bf16x8);
+      }
+      l[r] += rowsum;
+    }
   };
 
   // ---------------------------------------------------------------- persistent loop over items
@@ -305,166 +435,286 @@ __global__ void __launch_bounds__(128 * HG, (HG == 4 ? 1 : 2)) k_prefill_bf16(Pr
   Item nxt = has_next ? load_item(item + gridDim.x) : cur;
 
   // The K/V tile stream runs ahead of the computation, across the item boundary: `ti` tiles have
-  // been issued, `tc` consumed; tile t lives in ring slot t % NSTAGE.
-  int ti = 0, tc = 0;
+  // been issued, tile `tc` is the one being consumed; tile t lives in ring slot t % NSTAGE.
+  unsigned ti = 0, tc = 0;
   int iss_next = 0, iss_idx = 0;  // issue cursor: item (0 current / 1 next) and tile index in its row
-  // the cursor's item, field by field (scalar registers)
-  int is_cu = cur.cu, is_T = cur.T, is_c0 = cur.c0, is_N = cur.N, is_hk = cur.hk, is_ktb = cur.ktb;
-  auto cursor_enter = [&](const Item& I) {
-    is_cu = I.cu; is_T = I.T; is_c0 = I.c0; is_N = I.N; is_hk = I.hk; is_ktb = I.ktb;
+  // The cursor's item, field by field (scalar registers), with the bases of its K rows and V^T
+  // tiles, and 64 key-tile indices of its row in a vector register (lane e holds entry
+  // (iss_idx & ~63) + e; a scalar or vector load inside the tile loop would drain the K/V
+  // prefetches with its wait).  col_nxt is the same for the first 64 entries of the next item.
+  int is_cu, is_T, is_c0, is_N, is_nfast, col_iss, col_nxt;
+  const unsigned char *is_kbase, *is_vbase;
+  auto load_cols = [&](const Item& I, int first) { return a.col[I.c0 + min(first + lane, I.N - 1)]; };
+  auto cursor_enter = [&](const Item& I, int cols) {
+    is_cu = I.cu; is_T = I.T; is_c0 = I.c0; is_N = I.N; is_nfast = I.nfast;
+    is_kbase = kg + ((size_t)I.cu * a.hkv + I.hk) * (D * 2);
+    is_vbase = vtg + ((size_t)I.ktb * a.hkv + I.hk) * (size_t)(D * TN * 2) + w * 1024;
+    col_iss = cols;
     iss_idx = 0;
   };
-  i32x8 colv = {0, 0, 0, 0, 0, 0, 0, 0};  // key-tile indices iss_idx & ~7 .. +7 of the cursor's row
+  cursor_enter(cur, load_cols(cur, 0));
+  col_nxt = has_next ? load_cols(nxt, 0) : 0;
+  const bool issuer = w < NISS;
   auto try_issue = [&]() {
+    if (!issuer) return false;
     if (iss_idx >= is_N) {
       if (iss_next || !has_next) return false;
       iss_next = 1;
-      cursor_enter(nxt);
+      cursor_enter(nxt, col_nxt);
     }
-    const int cu = is_cu, T = is_T, c0 = is_c0, hk = is_hk, ktb = is_ktb;
-    // Scalar load of the key-tile indices, eight at a time so that the load latency is paid once
-    // per eight tiles (the compiler would use a vector load here, whose wait drains the K/V
-    // prefetches, because it cannot prove the table is not written by the kernel).  The table
-    // has eight spare entries at its end, so the load never leaves it.
-    const int sub = iss_idx & 7;
-    if (sub == 0) {
-      const int32_t* cp = a.col + __builtin_amdgcn_readfirstlane(c0 + iss_idx);
-      asm volatile("s_load_dwordx8 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(colv) : "s"(cp) : "memory");
+    if ((iss_idx & 63) == 0 && iss_idx != 0) {  // rows with more than 64 tiles: next 64 entries
+      col_iss = a.col[is_c0 + min(iss_idx + lane, is_N - 1)];
+      asm volatile("" ::"v"(col_iss));  // the wait for this load belongs here, not on the common path
     }
-    int kt = colv[0];
-#pragma unroll
-    for (int e = 1; e < 8; ++e) kt = (sub == e) ? colv[e] : kt;
-#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 16)
-    kt = iss_idx;
-#endif
-#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 8)
-    (void)cu; (void)T; (void)hk; (void)ktb;
-#else
-    issue_loads(ti % NSTAGE, cu, T, hk, ktb, kt);
-#endif
+    const int kt = __builtin_amdgcn_readlane(col_iss, iss_idx & 63);
+    issue_loads(ti % NSTAGE, is_kbase, is_vbase, is_cu, is_T, kt, iss_idx >= is_nfast);
     ++ti;
     ++iss_idx;
     return true;
   };
-#pragma unroll
-  for (int p = 0; p < NSTAGE - 1; ++p) try_issue();
+  // Moves on to the next tile of the stream: afterwards tile tc (if there is one) is visible to
+  // the whole workgroup, every wave has finished what it did before the call, and the ring slot
+  // that this frees is refilled.  The pipeline reads tiles tc - 1 and tc, so tiles up to
+  // tc + NSTAGE - 2 may be in the ring.
+#ifdef DAGATTN_TIMING
+  unsigned long long tacc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
+#define TSTAMP(x) const unsigned long long x = __builtin_amdgcn_s_memrealtime()
+#define TACC(i, a0, a1) tacc[i] += (a1) - (a0)
+#define TCOUNT(i) tacc[i] += 1
+#else
+#define TSTAMP(x)
+#define TACC(i, a0, a1)
+#define TCOUNT(i)
+#endif
+  auto sync_next = [&]() {
+    ++tc;
+    TSTAMP(tw0);
+    const int younger = (int)(ti - tc) - 1;  // tiles issued after the one needed now
+    if (!issuer) {
+    } else if (younger >= 2) wait_vmcnt<2 * LPT>();
+    else if (younger == 1) wait_vmcnt<LPT>();
+    else wait_vmcnt<0>();
+    TSTAMP(tw1);
+    TACC(8, tw0, tw1);
+    // Bare barrier (no memory fence: __syncthreads would drain every outstanding prefetch).
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  auto refill = [&]() {  // after sync_next: one more tile into the slot that became free
+    if (ti - tc < NSTAGE - 1) try_issue();
+  };
+  auto advance = [&]() {
+    sync_next();
+    refill();
+  };
+
+#pragma unroll 1
+  while (ti < NSTAGE - 1 && try_issue()) {
+  }
   load_q(cur);
+  // Row data for the mask: node of each row (rnode), word 0 of that node's visibility bitset
+  // (vis0), and the nodes of the next item's rows, fetched one item ahead so that the dependent
+  // vis0 load can go out together with the next Q rows.
+  int rnode[RB], rnode_nxt[RB];
+  uint64_t vis0[RB];
+#pragma unroll
+  for (int r = 0; r < RB; ++r) {
+    rnode[r] = a.tok_node[token_of(cur, r)];
+    rnode_nxt[r] = has_next ? a.tok_node[token_of(nxt, r)] : 0;
+  }
+#pragma unroll
+  for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(cur.nstart + rnode[r]) * a.W];
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
   while (true) {
-    const int i_row = cur.row0 + 32 * rb + L;  // row inside the sequence
-    const int tok = token_of(cur), head = head_of(cur);
-    const uint64_t* vis_row = nullptr;
-    uint64_t vis0 = 0;
-    if (cur.nfast < cur.N) {  // some tile of this item needs the per-token mask
-      vis_row = a.node_vis + (int64_t)(cur.nstart + a.tok_node[tok]) * a.W;
-      vis0 = vis_row[0];
+    // The Q rows and the row data were loaded with ordinary global loads; make them "arrive"
+    // here, outside the tile loops, so that no conservative wait on them ends up inside (that
+    // wait would also drain the K/V prefetches every tile).
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) asm volatile("" ::"v"(qf[r][s]));
+      asm volatile("" ::"v"(vis0[r]), "v"(rnode_nxt[r]));
     }
+    asm volatile("" ::"v"(col_iss), "v"(col_nxt));
 
-    // The Q rows were loaded with ordinary global loads; make them "arrive" here, outside the
-    // tile loop, so that no conservative wait on them ends up inside it (that wait would also
-    // drain the K/V prefetches every tile).
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) asm volatile("" ::"v"(qf[s]));
-    for (int n = 0; n < cur.N; ++n) {
-      if (ti == tc) try_issue();  // nothing in flight (only right after very short items)
-      const int younger = ti - tc - 1;  // tiles issued after the one needed now
-      if (NSTAGE > 3 && younger >= 3) wait_vmcnt<(NSTAGE > 3 ? 3 : 0) * LPT>();
-      else if (NSTAGE > 2 && younger == 2) wait_vmcnt<(NSTAGE > 2 ? 2 : 0) * LPT>();
-      else if (younger == 1) wait_vmcnt<LPT>();
-      else wait_vmcnt<0>();
-      // Bare barrier (no memory fence: __syncthreads would drain every outstanding prefetch).
-      // Everyone's loads of tile tc have landed (each wave waited for its own above) and
-      // everyone has left tile tc-1.
-#if !defined(DAGATTN_ABL) || !(DAGATTN_ABL & 32)
-      __builtin_amdgcn_s_barrier();
-#endif
-      asm volatile("" ::: "memory");
-      while (ti - tc < NSTAGE && try_issue()) {
+    const int F = cur.nfast;
+    f32x16 SA[RB], SB[RB];
+    auto Kt = [&](unsigned t) { return Kbase + (t % NSTAGE) * KTILE; };
+    auto Vt = [&](unsigned t) { return Vbase + (t % NSTAGE) * VTILE; };
+    const yes_t Y;
+    const no_t N_;
+    const h0_t H0;
+    const h1_t H1;
+    const bf16x8 (*const nop)[2] = nullptr;
+
+    TSTAMP(t_item0);
+    if (F > 0) {
+      // ---- FULL tiles: software pipeline in steps of half a tile
+      if (step(Y, N_, N_, H0, H0, Kt(tc), SA, nullptr, nop, nullptr, nullptr, nothing)) rescale();
+      bool need = step(Y, N_, Y, H1, H0, Kt(tc), SB, nullptr, nop, SA, P0, nothing);
+      TSTAMP(t_a);
+      TACC(0, t_item0, t_a);
+#pragma unroll 1
+      for (int n = 0; n + 1 < F; ++n) {
+        TSTAMP(t0);
+        sync_next();  // tile tc - 1 is the one in flight through the pipeline, tc the new one
+        TSTAMP(t1);
+        if (need) rescale();
+        need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, refill);
+        TSTAMP(t2);
+        if (need) rescale();
+        need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, nothing);
+        TSTAMP(t3);
+        TACC(1, t0, t1);
+        TACC(2, t1, t2);
+        TACC(3, t2, t3);
+        TCOUNT(7);
       }
-      const int buf = tc % NSTAGE;
-      f32x16 S[2];
-      bf16x8 pb[4];
-#ifdef DAGATTN_ABL  // development ablations: bit 0 no scores, 1 no softmax, 2 no accumulate
-      if (DAGATTN_ABL & 1) {
+      TSTAMP(t_b);
+      if (F == cur.N && has_next) {  // the Q registers are free from here on
+        load_q(nxt);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) S[kb][r] = (float)(n + r);
-      } else {
-        scores(Kbase + buf * KTILE, S);
+        for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
       }
-      if (n == cur.N - 1 && has_next) load_q(nxt);
-      if (DAGATTN_ABL & 2) {
+      sync_next();
+      if (need) rescale();
+      step(N_, Y, Y, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill);
+      step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc - 1), P1, nullptr, nullptr, nothing);
+      TSTAMP(t_c);
+      TACC(4, t_b, t_c);
+    }
+    TSTAMP(t_p0);
+
+    // ---- PARTIAL tiles (and a ragged last tile): per-token mask, plain loop.  The mask of a row
+    // is built as a 64-bit word over the keys of the tile: the key tile is cut into its node
+    // segments (node ids come with the tile, through the ring) and each segment is switched on
+    // for the rows whose node sees the segment's node (Eq. 3); the causal / length limit is one
+    // more AND.
+    auto partial_tile = [&](int n, auto last_c) {
+      constexpr bool LAST = decltype(last_c)::value;
+      step(Y, N_, N_, H0, H0, Kt(tc), SA, nullptr, nop, nullptr, nullptr, nothing);
+      step(Y, N_, N_, H1, H0, Kt(tc), SB, nullptr, nop, nullptr, nullptr, nothing);
+      if (LAST && has_next) load_q(nxt);  // the Q registers are free from here on
+      int kt;
+      const int32_t* cp = a.col + sgpr(cur.c0 + n);
+      asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(kt) : "s"(cp) : "memory");
+      const int j0 = kt * TN;
+      const int nj = *(const int*)(Abase + (tc % NSTAGE) * 256 + lane * 4);  // node of key j0 + lane
+      const int prev = __shfl_up(nj, 1);
+      uint64_t starts = __builtin_amdgcn_ballot_w64(lane == 0 || nj != prev);
+      uint64_t rowmask[RB];
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-          f32x8 p;
+      for (int r = 0; r < RB; ++r) rowmask[r] = 0;
+      while (starts) {  // wave-uniform loop over the node segments of the key tile
+        const int s0 = __builtin_ctzll(starts);
+        starts &= starts - 1;
+        const int s1 = starts ? __builtin_ctzll(starts) : 64;
+        const int ns = __builtin_amdgcn_readlane(nj, s0);
+        const uint64_t range = (s1 == 64 ? ~0ull : ((1ull << s1) - 1)) & ~((1ull << s0) - 1);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) p[e] = S[st >> 1][8 * (st & 1) + e];
-          pb[st] = __builtin_convertvector(p, bf16x8);
+        for (int r = 0; r < RB; ++r) {
+          const uint64_t word =
+              (a.W == 1) ? vis0[r] : a.node_vis[(int64_t)(cur.nstart + rnode[r]) * a.W + (ns >> 6)];
+          if ((word >> (ns & 63)) & 1) rowmask[r] |= range;
         }
-      } else {
-        softmax(S, pb);
       }
-      if (DAGATTN_ABL & 4) {
-        O[0][0] += (float)pb[0][0];
-      } else {
-        accumulate(Vbase + buf * VTILE, pb);
-      }
-      ++tc;
-      continue;
-#endif
-      scores(Kbase + buf * KTILE, S);
-      if (n == cur.N - 1 && has_next) load_q(nxt);  // the Q registers are free from here on
-      if (n >= cur.nfast) {
-        const int j0 = a.col[__builtin_amdgcn_readfirstlane(cur.c0 + n)] * TN;
-        const int32_t* tn = a.tok_node + cur.cu;
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+        const int cnt = min(row_of(cur, r), cur.T - 1) - j0 + 1;  // keys j0 .. j0 + cnt - 1 are not in the future
+        const uint64_t lim = cnt >= 64 ? ~0ull : (cnt <= 0 ? 0ull : ((1ull << cnt) - 1));
+        const uint64_t rm = (rowmask[r] & lim) >> (8 * H);
+        const uint32_t half[2] = {(uint32_t)rm, (uint32_t)(rm >> 32)};
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int j = j0 + 32 * kb + 16 * (r >> 3) + 8 * H + (r & 7);
-            const int nj = tn[min(j, cur.T - 1)];
-            const uint64_t word = (a.W == 1) ? vis0 : vis_row[nj >> 6];
-            const bool ok = (j <= i_row) && (j < cur.T) && ((word >> (nj & 63)) & 1);
-            S[kb][r] = ok ? S[kb][r] : -INFINITY;
+          for (int e = 0; e < 16; ++e) {  // this lane's key 32 kb + 16 (e / 8) + 8 H + e % 8
+            const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)half[kb], 16 * (e >> 3) + (e & 7), 1);
+            const float x = kb == 0 ? SA[r][e] : SB[r][e];
+            const float y = __uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep));
+            if (kb == 0) SA[r][e] = y;
+            else SB[r][e] = y;
           }
       }
-      softmax(S, pb);
-      accumulate(Vbase + buf * VTILE, pb);
-      ++tc;
-    }
+      const bool na = row_max(SA);
+      if (na) rescale();
+      if (row_max(SB)) rescale();
+      exp_half(SA, P0);
+      exp_half(SB, P1);
+      if (LAST && has_next) {  // row data of the next item (its node ids were loaded an item ago)
+#pragma unroll
+        for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
+      }
+      step(N_, Y, N_, H0, H0, nullptr, nullptr, Vt(tc), P0, nullptr, nullptr, nothing);
+      step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc), P1, nullptr, nullptr, nothing);
+      advance();
+    };
+#pragma unroll 1
+    for (int n = F; n + 1 < cur.N; ++n) partial_tile(n, no_t());
+    if (F < cur.N) partial_tile(cur.N - 1, yes_t());
 
-    const float l_tot = l + __shfl_xor(l, 32);
-    if (i_row < cur.T) {
-      const float inv = 1.f / l_tot;
-      uint16_t* og = (uint16_t*)a.out + ((size_t)tok * a.hq + head) * D;
+    TSTAMP(t_p1);
+    TACC(5, t_p0, t_p1);
+    // ---- output
+    const int head = head_of(cur);
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+    for (int r = 0; r < RB; ++r) {
+      const float l_tot = l[r] + __shfl_xor(l[r], 32);
+      if (row_of(cur, r) < cur.T) {
+        const int tok = token_of(cur, r);
+        const float inv = 1.f / l_tot;
+        uint16_t* og = (uint16_t*)a.out + ((size_t)tok * a.hq + head) * D;
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          u32x2 o;
-          o[0] = dag_pack_bf2(O[db][4 * r4] * inv, O[db][4 * r4 + 1] * inv);
-          o[1] = dag_pack_bf2(O[db][4 * r4 + 2] * inv, O[db][4 * r4 + 3] * inv);
-          *(u32x2*)(og + 32 * db + 8 * r4 + 4 * H) = o;
-        }
-      if (a.lse && H == 0) a.lse[(size_t)tok * a.hq + head] = m * a.scale + logf(l_tot);
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            u32x2 o;
+            o[0] = dag_pack_bf2(O[r][db][4 * r4] * inv, O[r][db][4 * r4 + 1] * inv);
+            o[1] = dag_pack_bf2(O[r][db][4 * r4 + 2] * inv, O[r][db][4 * r4 + 3] * inv);
+            *(u32x2*)(og + 32 * db + 8 * r4 + 4 * H) = o;
+          }
+        if (a.lse && H == 0) a.lse[(size_t)tok * a.hq + head] = m[r] * a.scale + logf(l_tot);
+      }
     }
+    TSTAMP(t_o);
+    TACC(6, t_p1, t_o);
     if (!has_next) break;
     reset_acc();
     item += gridDim.x;
     cur = nxt;
     has_next = item + gridDim.x < n_items;
     if (has_next) nxt = load_item(item + gridDim.x);
-    if (iss_next) iss_next = 0;  // the cursor was already in what is now the current item
-    else cursor_enter(cur);      // (all tiles of the old item were issued: start of the new one)
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      rnode[r] = rnode_nxt[r];
+      if (has_next) rnode_nxt[r] = a.tok_node[token_of(nxt, r)];
+    }
+    if (iss_next) iss_next = 0;     // the cursor was already in what is now the current item
+    else cursor_enter(cur, col_nxt);  // (all tiles of the old item were issued: start of the new one)
+    if (has_next) col_nxt = load_cols(nxt, 0);
+    // refill the ring (the cursor could not go past the end of the old `nxt`); the slot of tile
+    // tc - 1 stays untouched: other waves may still be reading it
+#pragma unroll 1
+    while (ti - tc < NSTAGE - 1 && try_issue()) {
+    }
   }
+#ifdef DAGATTN_TIMING
+  if (blockIdx.x == 0 && lane == 0) {
+    const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
+    printf("wave %d total %llu | prologue %llu sync %llu stepA %llu stepB %llu epi %llu partial %llu out %llu | pipelined tiles %llu vmwait %llu (x10ns)\n",
+           w, t_end - t_begin, tacc[0], tacc[1], tacc[2], tacc[3], tacc[4], tacc[5], tacc[6], tacc[7], tacc[8]);
+  }
+#endif
 }
 
-template <int D, int HG, int NSTAGE>
+template <int D, int HG, int RB>
 int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
   constexpr int KPB = 64 / (D / 8);
-  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128));
-  if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, NSTAGE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256);
+  if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, RB>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sm) != hipSuccess)
     return DAG_ERR_HIP;
   int dev = 0, n_cu = 0;
@@ -475,9 +725,8 @@ int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
                      (const uint16_t*)a.v, (uint16_t*)a.vt, a.ktile_start, a.cu_seqlens, a.n_seqs, a.hkv);
   DAG_LAUNCH_CHECK();
   const long n_items = (long)a.total_qtiles * a.hkv * hs;
-  const long slots = (long)n_cu * (HG == 4 ? 1 : 2);
-  const unsigned grid = (unsigned)(n_items < slots ? n_items : slots);
-  hipLaunchKernelGGL((k_prefill_bf16<D, HG, NSTAGE>), dim3(grid), dim3(128 * HG), sm, stream, a);
+  const unsigned grid = (unsigned)(n_items < n_cu ? n_items : n_cu);
+  hipLaunchKernelGGL((k_prefill_bf16<D, HG, RB>), dim3(grid), dim3(64 * HG * (2 / RB)), sm, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
@@ -485,9 +734,13 @@ int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
 template <int D>
 int launch_d(const PrefillArgs& a, hipStream_t stream) {
   const int g = a.hq / a.hkv;
-  if (g % 4 == 0) return launch_one<D, 4, 4>(a, g / 4, stream);  // 8 waves, one workgroup per CU
-  if (g % 2 == 0) return launch_one<D, 2, 2>(a, g / 2, stream);  // 4 waves, two workgroups per CU
-  return launch_one<D, 1, 2>(a, g, stream);                       // 2 waves per workgroup
+#ifdef DAGATTN_RB1
+  if (g % 4 == 0) return launch_one<D, 4, 1>(a, g / 4, stream);  // eight waves, 32 rows each
+#else
+  if (g % 4 == 0) return launch_one<D, 4, 2>(a, g / 4, stream);  // four waves (one per SIMD), 64 rows each
+#endif
+  if (g % 2 == 0) return launch_one<D, 2, 1>(a, g / 2, stream);  // four waves, 32 rows each
+  return launch_one<D, 1, 1>(a, g, stream);                       // two waves
 }
 
 }  // namespace
