@@ -734,10 +734,10 @@ int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
 template <int D>
 int launch_d(const PrefillArgs& a, hipStream_t stream) {
   const int g = a.hq / a.hkv;
-#ifdef DAGATTN_RB1
-  if (g % 4 == 0) return launch_one<D, 4, 1>(a, g / 4, stream);  // eight waves, 32 rows each
+#ifdef DAGATTN_RB2  // development variant: four waves (one per SIMD), 64 rows each; measured slower so far
+  if (g % 4 == 0) return launch_one<D, 4, 2>(a, g / 4, stream);
 #else
-  if (g % 4 == 0) return launch_one<D, 4, 2>(a, g / 4, stream);  // four waves (one per SIMD), 64 rows each
+  if (g % 4 == 0) return launch_one<D, 4, 1>(a, g / 4, stream);  // eight waves, 32 rows each
 #endif
   if (g % 2 == 0) return launch_one<D, 2, 1>(a, g / 2, stream);  // four waves, 32 rows each
   return launch_one<D, 1, 1>(a, g, stream);                       // two waves
