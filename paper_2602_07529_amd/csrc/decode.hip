@@ -69,11 +69,13 @@ struct KVBlock {           // one 32-key block (2 pages) in operand layout
   bf16x8 v[2][D / 32];     // v[page][db]: keys 8H..8H+7 of dimension 32db+L
 };
 
+// pgv: page ids of the item's slice, lane i holds page p0 + (i % 64) of the current 64-page window
+// (fetched once per window, so that no page-table load sits in front of every K/V load)
 template <int D>
-__device__ __forceinline__ void load_block(KVBlock<D>& blk, const DecodeArgs& a, const int32_t* pages, int pb,
-                                           int p_last, int hk, int L, int H, int kpage_sel, int kslot) {
-  const int pg0 = pages[pb];
-  const int pg1 = pages[min(pb + 1, p_last)];
+__device__ __forceinline__ void load_block(KVBlock<D>& blk, const DecodeArgs& a, int pgv, int pb_rel, int last_rel,
+                                           int hk, int L, int H, int kpage_sel, int kslot) {
+  const int pg0 = __builtin_amdgcn_readlane(pgv, pb_rel & 63);
+  const int pg1 = __builtin_amdgcn_readlane(pgv, min(pb_rel + 1, last_rel) & 63);
   const size_t kbase0 = ((size_t)pg0 * a.hkv + hk) * (size_t)(D * PAGE);
   const size_t kbase1 = ((size_t)pg1 * a.hkv + hk) * (size_t)(D * PAGE);
   const uint16_t* kp = a.k_pool + (kpage_sel ? kbase1 : kbase0) + kslot * 8 + H * (PAGE * 8);
@@ -88,14 +90,17 @@ __device__ __forceinline__ void load_block(KVBlock<D>& blk, const DecodeArgs& a,
   }
 }
 
+// qs: the query operands of the item in LDS, qs[s * 64 + lane] (they are needed once per 32-key
+// block; keeping them out of the register file lets two waves share a SIMD, which doubles the
+// bytes in flight)
 template <int D>
-__device__ __forceinline__ void compute_block(const KVBlock<D>& blk, const bf16x8* qf, f32x16* O, float& m, float& l,
+__device__ __forceinline__ void compute_block(const KVBlock<D>& blk, const bf16x8* qs, f32x16* O, float& m, float& l,
                                               float sc, int key0, int len, int H) {
   f32x16 S;
 #pragma unroll
   for (int r = 0; r < 16; ++r) S[r] = 0.f;
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) S = mfma32(blk.k[s], qf[s], S);
+  for (int s = 0; s < D / 16; ++s) S = mfma32(blk.k[s], qs[s * 64], S);
   if (key0 + 32 > len) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -132,7 +137,8 @@ __device__ __forceinline__ void compute_block(const KVBlock<D>& blk, const bf16x
 }
 
 template <int D>
-__global__ void __launch_bounds__(64) k_decode(DecodeArgs a) {
+__global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
+  __shared__ bf16x8 qs_all[(D / 16) * 64];
   const int item = blockIdx.x;
   const int lane = threadIdx.x, L = lane & 31, H = lane >> 5;
   const bool is_a = item < a.items_a;
@@ -183,13 +189,13 @@ __global__ void __launch_bounds__(64) k_decode(DecodeArgs a) {
     return;
   }
 
-  bf16x8 qf[D / 16];
+  const bf16x8* qf = qs_all + lane;
   {
     const int rr = row_ok ? row : 0;
     const int br = branch0 + rr / a.G, head = hk * a.G + rr % a.G;
     const uint16_t* qp = a.q + ((size_t)br * a.hq + head) * D + 8 * H;
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) qf[s] = *(const bf16x8*)(qp + 16 * s);
+    for (int s = 0; s < D / 16; ++s) qs_all[s * 64 + lane] = *(const bf16x8*)(qp + 16 * s);
   }
   const int kr = key_of_row(L);
   const int kpage_sel = kr >> 4, kslot = kr & 15;
@@ -201,18 +207,28 @@ __global__ void __launch_bounds__(64) k_decode(DecodeArgs a) {
     for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
   float m = -1e30f, l = 0.f;
 
+  // Page ids in windows of 64 (lane i: page p0 + 64 w + i); a block never straddles a window
+  // because windows and blocks both start at even offsets.
+  const int np = p1 - p0;
+  int pgv = pages[p0 + min(lane, np - 1)];
   KVBlock<D> b0, b1;
-  load_block<D>(b0, a, pages, p0, p1 - 1, hk, L, H, kpage_sel, kslot);
-  int pb = p0;
+  load_block<D>(b0, a, pgv, 0, np - 1, hk, L, H, kpage_sel, kslot);
+  int pb = 0;  // relative to p0
   while (true) {
-    if (pb + 2 < p1) load_block<D>(b1, a, pages, pb + 2, p1 - 1, hk, L, H, kpage_sel, kslot);
-    compute_block<D>(b0, qf, O, m, l, a.sc, pb * PAGE, len, H);
+    if (pb + 2 < np) {
+      if (((pb + 2) & 63) == 0) pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
+      load_block<D>(b1, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
+    }
+    compute_block<D>(b0, qf, O, m, l, a.sc, (p0 + pb) * PAGE, len, H);
     pb += 2;
-    if (pb >= p1) break;
-    if (pb + 2 < p1) load_block<D>(b0, a, pages, pb + 2, p1 - 1, hk, L, H, kpage_sel, kslot);
-    compute_block<D>(b1, qf, O, m, l, a.sc, pb * PAGE, len, H);
+    if (pb >= np) break;
+    if (pb + 2 < np) {
+      if (((pb + 2) & 63) == 0) pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
+      load_block<D>(b0, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
+    }
+    compute_block<D>(b1, qf, O, m, l, a.sc, (p0 + pb) * PAGE, len, H);
     pb += 2;
-    if (pb >= p1) break;
+    if (pb >= np) break;
   }
 
   const float l_tot = l + __shfl_xor(l, 32);
@@ -321,9 +337,9 @@ int env_int(const char* name, int dflt) {
   return v > 0 ? v : dflt;
 }
 
-// Split sizes: long slices for the shared phase (a partial costs 32 rows of D floats, so few of
-// them), short ones for the own-token phase (G rows per partial); both even so that a 32-key
-// block never straddles a split.
+// Split sizes: slices as long as the batch allows (every work item pays a start-up latency and
+// writes a partial, so fewer and longer items stream better) while still giving the GPU about two
+// waves per SIMD; both even so that a 32-key block never straddles a split.
 int make_plan(const dag_decode_desc_t* d, int hq, int hkv, int D, DecodePlan* p) {
   if (!d) return DAG_ERR_NULL;
   if (d->n_groups < 0 || d->n_live < 0 || d->max_shared_pages < 0 || d->max_branch_pages < 0 || d->max_group_size < 0)
@@ -336,13 +352,13 @@ int make_plan(const dag_decode_desc_t* d, int hq, int hkv, int D, DecodePlan* p)
   if (p->rb_max < 1) p->rb_max = 1;
   const int64_t base_a = (int64_t)d->n_groups * hkv * p->rb_max;
   const int64_t base_b = (int64_t)d->n_live * hkv;
-  int ca = env_int("DAGATTN_DECODE_CHUNK_A", 64), cb = env_int("DAGATTN_DECODE_CHUNK_B", 16);
+  int ca = env_int("DAGATTN_DECODE_CHUNK_A", 128), cb = env_int("DAGATTN_DECODE_CHUNK_B", 64);
   ca += ca & 1;
   cb += cb & 1;
   if (!getenv("DAGATTN_DECODE_CHUNK_A"))
-    while (ca > 8 && base_a * dag_ceil_div(d->max_shared_pages, ca) < 1024) ca /= 2;
+    while (ca > 8 && base_a * dag_ceil_div(d->max_shared_pages, ca) < 512) ca /= 2;
   if (!getenv("DAGATTN_DECODE_CHUNK_B"))
-    while (cb > 4 && base_b * dag_ceil_div(d->max_branch_pages, cb) < 2048) cb /= 2;
+    while (cb > 4 && base_b * dag_ceil_div(d->max_branch_pages, cb) < 1024) cb /= 2;
   p->chunk_a = ca;
   p->chunk_b = cb;
   p->splits_a = d->max_shared_pages > 0 ? (int)dag_ceil_div(d->max_shared_pages, ca) : 0;
