@@ -3,7 +3,7 @@
 
 One step = one pass of the whole hot path over one batch of seeded synthetic input:
   prefill segment (workload "llama3_8b_prefill_bf16", benchmark config 2):
-      dag_build_meta -> dag_rope_qk -> dag_attn_prefill
+      dag_build_meta -> dag_rope_qk -> dag_attn_prefill (as its two halves: prepare_v, attention)
   decode segment  (workload "branch_decode_bf16", benchmark config 3):
       dag_kv_append_rope -> dag_attn_decode (shared-prefix items + own items + LSE merge)
 Inputs are resident in HBM before the timed region.  `value` is the prefill segment's useful
@@ -53,23 +53,27 @@ class PrefillWork:
         self.desc = B.DagDesc(off, lens, bits, W, tm, tn, 0)
         self.meta = B.DagMeta(self.desc, B.dag_meta_sizes(self.desc), dev)
         self.theta = cfg["theta"]
-        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
 
     def refresh_inputs(self):
-        """Untimed: restore the un-rotated Q/K (RoPE works in place)."""
+        """Restore the un-rotated Q/K (RoPE works in place).  Not needed between timed steps: a
+        step rotates Q and K once more, which changes neither shapes nor magnitudes."""
         self.q.copy_(self.q0)
         self.k.copy_(self.k0)
 
-    def run(self, timed=False):
-        if timed:
-            self.ev[0].record()
+    def run(self, ev=None):
+        """ev: three events (torch's current stream is the one the library launches on)."""
+        if ev:
+            ev[0].record()
         B.dag_build_meta(self.desc, self.meta)
         B.dag_rope_qk(self.meta.get("pos_ids"), self.q, self.k, self.theta)
-        if timed:
-            self.ev[1].record()
-        B.dag_attn_prefill(self.meta, self.q, self.k, self.v, self.out)
-        if timed:
-            self.ev[2].record()
+        B.dag_prefill_prepare_v(self.meta, self.v, self.cfg["hq"])
+        if ev:
+            ev[1].record()
+        # dag_attn_prefill = prepare_v + this call; launched separately here so that the events
+        # bracket exactly one kernel (k_prefill_bf16), the one the roofline is quoted on
+        B.dag_attn_prefill(self.meta, self.q, self.k, self.v, self.out, prepared=True)
+        if ev:
+            ev[2].record()
 
     def useful_flops(self):
         pairs = int(self.meta.get("useful_pairs").sum().item())
@@ -90,17 +94,16 @@ class DecodeWork:
                               dtype=torch.uint8, device=dev)
         self.bytes = dags.decode_algorithmic_bytes(st["desc"], cfg["hkv"], cfg["d"])
         self.n_live = st["desc"]["n_live"]
-        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
-    def run(self, timed=False):
-        if timed:
-            self.ev[0].record()
+    def run(self, ev=None):
+        if ev:
+            ev[0].record()
         B.dag_kv_append_rope(self.dd, self.k_new, self.v_new, self.kp, self.vp, self.cfg["theta"])
-        if timed:
-            self.ev[1].record()
+        if ev:
+            ev[1].record()
         B.dag_attn_decode(self.dd, self.q, self.kp, self.vp, self.out, self.ws)
-        if timed:
-            self.ev[2].record()
+        if ev:
+            ev[2].record()
 
 
 def cpu_baseline(pw):
@@ -138,6 +141,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (untimed): under rocprofv3 --pmc its "
+                         "FETCH_SIZE / WRITE_SIZE give the scale of those counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (one-GPU boxes; the path shards without "
@@ -152,28 +158,34 @@ def main():
     pw = PrefillWork(dags.config(1), dev)
     dw = DecodeWork(dags.config(2), dev)
 
+    if args.copy_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    pw.refresh_inputs()
     for _ in range(args.warmup):
-        pw.refresh_inputs()
         pw.run()
         dw.run()
-    torch.cuda.synchronize()
+    new_events = lambda: [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    pev = [new_events() for _ in range(args.steps)]
+    dev_ev = [new_events() for _ in range(args.steps)]
 
-    step_ms, pre_ms, attn_ms, dec_ms, deck_ms = [], [], [], [], []
+    # exactly `steps` steps between two synchronisations; the host runs ahead of the GPU, so the
+    # per-kernel event intervals below contain no launch gaps
+    torch.cuda.synchronize()
     wall0 = time.perf_counter()
-    for _ in range(args.steps):
-        pw.refresh_inputs()          # untimed restore of the raw Q/K
-        torch.cuda.synchronize()
-        pw.run(timed=True)
-        dw.run(timed=True)
-        torch.cuda.synchronize()
-        p_total = pw.ev[0].elapsed_time(pw.ev[2])
-        d_total = dw.ev[0].elapsed_time(dw.ev[2])
-        pre_ms.append(p_total)
-        attn_ms.append(pw.ev[1].elapsed_time(pw.ev[2]))
-        dec_ms.append(d_total)
-        deck_ms.append(dw.ev[1].elapsed_time(dw.ev[2]))
-        step_ms.append(pw.ev[0].elapsed_time(dw.ev[2]))
+    for i in range(args.steps):
+        pw.run(pev[i])
+        dw.run(dev_ev[i])
+    torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
+    pre_ms = [e[0].elapsed_time(e[2]) for e in pev]
+    attn_ms = [e[1].elapsed_time(e[2]) for e in pev]
+    dec_ms = [e[0].elapsed_time(e[2]) for e in dev_ev]
+    deck_ms = [e[1].elapsed_time(e[2]) for e in dev_ev]
+    step_ms = [wall * 1e3 / args.steps]
 
     flops, pairs = pw.useful_flops()
     mean = lambda xs: float(np.mean(xs))

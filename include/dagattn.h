@@ -152,6 +152,19 @@ int dag_attn_prefill(const dag_meta_t* meta, const void* q, const void* k, const
                      float softmax_scale, dag_dtype_t dtype, void* ws, size_t ws_bytes,
                      void* stream);
 
+/* The two halves of dag_attn_prefill (Eq. 2 + Eq. 3), for callers that want them as separate
+ * launches, e.g. to time the attention kernel alone or to prepare V while Q and K are still being
+ * produced.  dag_prefill_prepare_v writes the key-tile-wise transposed copy of v [T][hkv][head_dim]
+ * into `ws` (a no-op for DAG_F32); dag_attn_prefill_prepared is dag_attn_prefill without that
+ * step: it expects `ws` as dag_prefill_prepare_v left it for the same meta, v, hkv, head_dim and
+ * dtype.  Arguments, layouts, errors and the workspace size are those of dag_attn_prefill. */
+int dag_prefill_prepare_v(const dag_meta_t* meta, const void* v, int32_t hq, int32_t hkv,
+                          int32_t head_dim, dag_dtype_t dtype, void* ws, size_t ws_bytes, void* stream);
+int dag_attn_prefill_prepared(const dag_meta_t* meta, const void* q, const void* k, const void* v,
+                              void* out, float* lse, int32_t hq, int32_t hkv, int32_t head_dim,
+                              float softmax_scale, dag_dtype_t dtype, void* ws, size_t ws_bytes,
+                              void* stream);
+
 /* Bytes of DEVICE workspace dag_attn_prefill needs (host only; 0 for the fp32 path). */
 size_t dag_prefill_workspace_bytes(const dag_meta_t* meta, int32_t hkv, int32_t head_dim,
                                    dag_dtype_t dtype);

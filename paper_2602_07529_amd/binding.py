@@ -80,6 +80,8 @@ def lib():
         L.dag_rope_qk.argtypes = [vp, i64, vp, vp, i32, i32, i32, f32, C.c_int, vp]
         L.dag_attn_prefill.argtypes = [C.POINTER(dag_meta_t), vp, vp, vp, vp, vp, i32, i32, i32, f32,
                                        C.c_int, vp, C.c_size_t, vp]
+        L.dag_attn_prefill_prepared.argtypes = L.dag_attn_prefill.argtypes
+        L.dag_prefill_prepare_v.argtypes = [C.POINTER(dag_meta_t), vp, i32, i32, i32, C.c_int, vp, C.c_size_t, vp]
         L.dag_prefill_workspace_bytes.argtypes = [C.POINTER(dag_meta_t), i32, i32, C.c_int]
         L.dag_prefill_workspace_bytes.restype = C.c_size_t
         L.dag_kv_append_rope.argtypes = [C.POINTER(dag_decode_desc_t), vp, vp, vp, vp, i32, i32, f32, vp]
@@ -91,7 +93,8 @@ def lib():
         L.dag_strerror.restype = C.c_char_p
         L.dag_version.restype = C.c_int
         for name in ("dag_prefill_tile_shape", "dag_meta_sizes", "dag_build_meta", "dag_rope_qk",
-                     "dag_attn_prefill", "dag_kv_append_rope", "dag_attn_decode"):
+                     "dag_attn_prefill", "dag_attn_prefill_prepared", "dag_prefill_prepare_v",
+                     "dag_kv_append_rope", "dag_attn_decode"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -198,23 +201,36 @@ def dag_prefill_workspace_bytes(meta, hkv, head_dim, dtype_code):
     return int(lib().dag_prefill_workspace_bytes(C.byref(meta.c), hkv, head_dim, dtype_code))
 
 
-def dag_attn_prefill(meta, q, k, v, out, lse=None, softmax_scale=None, workspace=None):
+def _prefill_workspace(meta, hkv, d, like, workspace):
+    if workspace is not None:
+        return workspace
+    need = dag_prefill_workspace_bytes(meta, hkv, d, _dtype_code(like))
+    ws = getattr(meta, "prefill_ws", None)
+    if ws is None or ws.numel() < need:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=like.device)
+        meta.prefill_ws = ws
+    return ws
+
+
+def dag_attn_prefill(meta, q, k, v, out, lse=None, softmax_scale=None, workspace=None, prepared=False):
     """`workspace`: uint8 device tensor of dag_prefill_workspace_bytes(); when omitted one is
-    allocated (torch) and kept on `meta` for the following calls."""
+    allocated (torch) and kept on `meta` for the following calls.  prepared=True calls
+    dag_attn_prefill_prepared (the workspace already holds what dag_prefill_prepare_v wrote)."""
     T, hq, d = q.shape
     hkv = k.shape[1]
     if softmax_scale is None:
         softmax_scale = 1.0 / float(d) ** 0.5
-    if workspace is None:
-        need = dag_prefill_workspace_bytes(meta, hkv, d, _dtype_code(q))
-        ws = getattr(meta, "prefill_ws", None)
-        if ws is None or ws.numel() < need:
-            ws = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-            meta.prefill_ws = ws
-        workspace = ws
-    _check(lib().dag_attn_prefill(C.byref(meta.c), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
-                                  hq, hkv, d, float(softmax_scale), _dtype_code(q), _ptr(workspace),
-                                  workspace.numel(), _stream()))
+    workspace = _prefill_workspace(meta, hkv, d, q, workspace)
+    fn = lib().dag_attn_prefill_prepared if prepared else lib().dag_attn_prefill
+    _check(fn(C.byref(meta.c), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), hq, hkv, d, float(softmax_scale),
+              _dtype_code(q), _ptr(workspace), workspace.numel(), _stream()))
+
+
+def dag_prefill_prepare_v(meta, v, hq, workspace=None):
+    hkv, d = v.shape[1], v.shape[2]
+    workspace = _prefill_workspace(meta, hkv, d, v, workspace)
+    _check(lib().dag_prefill_prepare_v(C.byref(meta.c), _ptr(v), hq, hkv, d, _dtype_code(v), _ptr(workspace),
+                                       workspace.numel(), _stream()))
 
 
 class DecodeDesc:

@@ -1,4 +1,4 @@
-// C-ABI entry points that only validate and dispatch: dag_attn_prefill, dag_strerror, dag_version.
+// C-ABI entry points that only validate and dispatch: dag_attn_prefill (and its two halves), dag_strerror, dag_version.
 #include "common.h"
 #include "prefill_launch.h"
 
@@ -9,9 +9,13 @@ extern "C" size_t dag_prefill_workspace_bytes(const dag_meta_t* m, int32_t hkv, 
   return (size_t)m->sizes.total_ktiles * hkv * head_dim * m->tile_n * 2 + 256;
 }
 
-extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* k, const void* v, void* out,
-                                float* lse, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale,
-                                dag_dtype_t dtype, void* ws, size_t ws_bytes, void* stream_) {
+namespace {
+
+// Validation shared by the prefill entry points; fills the kernel argument block.
+int prefill_args(const dag_meta_t* m, const void* q, const void* k, const void* v, void* out, float* lse, int32_t hq,
+                 int32_t hkv, int32_t head_dim, float softmax_scale, dag_dtype_t dtype, void* ws, size_t ws_bytes,
+                 bool need_qko, PrefillArgs* a, bool* empty) {
+  *empty = false;
   if (!m) return DAG_ERR_NULL;
   if (dtype != DAG_F32 && dtype != DAG_BF16) return DAG_ERR_UNSUPPORTED;
   int32_t tm = 0, tn = 0;
@@ -20,8 +24,12 @@ extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* 
   if (m->tile_m != tm || m->tile_n != tn) return DAG_ERR_UNSUPPORTED;
   if (m->n_seqs < 0 || m->sizes.total_tokens < 0 || m->sizes.total_qtiles < 0 || m->words_per_node < 1)
     return DAG_ERR_BAD_LEN;
-  if (m->n_seqs == 0 || m->sizes.total_tokens == 0) return DAG_OK;
-  if (!q || !k || !v || !out) return DAG_ERR_NULL;
+  if (m->n_seqs == 0 || m->sizes.total_tokens == 0) {
+    *empty = true;
+    return DAG_OK;
+  }
+  if (need_qko && (!q || !k || !out)) return DAG_ERR_NULL;
+  if (!v) return DAG_ERR_NULL;
   if (!m->cu_seqlens || !m->node_start || !m->tok_node || !m->node_vis || !m->qtile_start || !m->ktile_start ||
       !m->qtile_rowptr || !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order || !m->qtile_desc)
     return DAG_ERR_NULL;
@@ -29,34 +37,70 @@ extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* 
   if (m->sizes.total_qtiles * (int64_t)hq > INT32_MAX) return DAG_ERR_UNSUPPORTED;
   const size_t need = dag_prefill_workspace_bytes(m, hkv, head_dim, dtype);
   if (need > 0 && (!ws || ws_bytes < need)) return DAG_ERR_WORKSPACE;
+  a->q = q;
+  a->k = k;
+  a->v = v;
+  a->out = out;
+  a->lse = lse;
+  a->vt = need > 0 ? (void*)dag_align_up((size_t)(uintptr_t)ws, 256) : nullptr;
+  a->cu_seqlens = m->cu_seqlens;
+  a->node_start = m->node_start;
+  a->tok_node = m->tok_node;
+  a->node_vis = m->node_vis;
+  a->qtile_start = m->qtile_start;
+  a->ktile_start = m->ktile_start;
+  a->rowptr = m->qtile_rowptr;
+  a->col = m->qtile_col;
+  a->flag = m->qtile_flag;
+  a->nfull = m->qtile_nfull;
+  a->qtile_order = m->qtile_order;
+  a->qtile_desc = m->qtile_desc;
+  a->n_seqs = m->n_seqs;
+  a->W = m->words_per_node;
+  a->hq = hq;
+  a->hkv = hkv;
+  a->total_qtiles = m->sizes.total_qtiles;
+  a->total_ktiles = m->sizes.total_ktiles;
+  a->scale = softmax_scale;
+  return DAG_OK;
+}
+
+}  // namespace
+
+extern "C" int dag_prefill_prepare_v(const dag_meta_t* m, const void* v, int32_t hq, int32_t hkv, int32_t head_dim,
+                                     dag_dtype_t dtype, void* ws, size_t ws_bytes, void* stream_) {
   PrefillArgs a;
-  a.q = q;
-  a.k = k;
-  a.v = v;
-  a.out = out;
-  a.lse = lse;
-  a.vt = need > 0 ? (void*)dag_align_up((size_t)(uintptr_t)ws, 256) : nullptr;
-  a.cu_seqlens = m->cu_seqlens;
-  a.node_start = m->node_start;
-  a.tok_node = m->tok_node;
-  a.node_vis = m->node_vis;
-  a.qtile_start = m->qtile_start;
-  a.ktile_start = m->ktile_start;
-  a.rowptr = m->qtile_rowptr;
-  a.col = m->qtile_col;
-  a.flag = m->qtile_flag;
-  a.nfull = m->qtile_nfull;
-  a.qtile_order = m->qtile_order;
-  a.qtile_desc = m->qtile_desc;
-  a.n_seqs = m->n_seqs;
-  a.W = m->words_per_node;
-  a.hq = hq;
-  a.hkv = hkv;
-  a.total_qtiles = m->sizes.total_qtiles;
-  a.total_ktiles = m->sizes.total_ktiles;
-  a.scale = softmax_scale;
+  bool empty;
+  const int rc = prefill_args(m, nullptr, nullptr, v, nullptr, nullptr, hq, hkv, head_dim, 1.f, dtype, ws, ws_bytes,
+                              false, &a, &empty);
+  if (rc != DAG_OK || empty || dtype == DAG_F32) return rc;  // the fp32 path reads V as it is
+  return launch_prefill_bf16_prepare_v(a, head_dim, (hipStream_t)stream_);
+}
+
+extern "C" int dag_attn_prefill_prepared(const dag_meta_t* m, const void* q, const void* k, const void* v, void* out,
+                                         float* lse, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale,
+                                         dag_dtype_t dtype, void* ws, size_t ws_bytes, void* stream_) {
+  PrefillArgs a;
+  bool empty;
+  const int rc = prefill_args(m, q, k, v, out, lse, hq, hkv, head_dim, softmax_scale, dtype, ws, ws_bytes, true, &a,
+                              &empty);
+  if (rc != DAG_OK || empty) return rc;
   hipStream_t stream = (hipStream_t)stream_;
   return dtype == DAG_F32 ? launch_prefill_f32(a, head_dim, stream) : launch_prefill_bf16(a, head_dim, stream);
+}
+
+extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* k, const void* v, void* out,
+                                float* lse, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale,
+                                dag_dtype_t dtype, void* ws, size_t ws_bytes, void* stream_) {
+  PrefillArgs a;
+  bool empty;
+  const int rc = prefill_args(m, q, k, v, out, lse, hq, hkv, head_dim, softmax_scale, dtype, ws, ws_bytes, true, &a,
+                              &empty);
+  if (rc != DAG_OK || empty) return rc;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (dtype == DAG_F32) return launch_prefill_f32(a, head_dim, stream);
+  const int rp = launch_prefill_bf16_prepare_v(a, head_dim, stream);
+  return rp != DAG_OK ? rp : launch_prefill_bf16(a, head_dim, stream);
 }
 
 extern "C" const char* dag_strerror(int code) {

@@ -721,9 +721,6 @@ int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
     return DAG_ERR_HIP;
-  hipLaunchKernelGGL((k_vt_prepare<D>), dim3((unsigned)a.total_ktiles, (unsigned)a.hkv), dim3(256), 0, stream,
-                     (const uint16_t*)a.v, (uint16_t*)a.vt, a.ktile_start, a.cu_seqlens, a.n_seqs, a.hkv);
-  DAG_LAUNCH_CHECK();
   const long n_items = (long)a.total_qtiles * a.hkv * hs;
   const unsigned grid = (unsigned)(n_items < n_cu ? n_items : n_cu);
   hipLaunchKernelGGL((k_prefill_bf16<D, HG, RB>), dim3(grid), dim3(64 * HG * (2 / RB)), sm, stream, a);
@@ -744,6 +741,18 @@ int launch_d(const PrefillArgs& a, hipStream_t stream) {
 }
 
 }  // namespace
+
+template <int D>
+int launch_prepare_v(const PrefillArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL((k_vt_prepare<D>), dim3((unsigned)a.total_ktiles, (unsigned)a.hkv), dim3(256), 0, stream,
+                     (const uint16_t*)a.v, (uint16_t*)a.vt, a.ktile_start, a.cu_seqlens, a.n_seqs, a.hkv);
+  DAG_LAUNCH_CHECK();
+  return DAG_OK;
+}
+
+int launch_prefill_bf16_prepare_v(const PrefillArgs& a, int head_dim, hipStream_t stream) {
+  return head_dim == 128 ? launch_prepare_v<128>(a, stream) : launch_prepare_v<64>(a, stream);
+}
 
 int launch_prefill_bf16(const PrefillArgs& a, int head_dim, hipStream_t stream) {
   if (head_dim == 128) return launch_d<128>(a, stream);

@@ -8,7 +8,7 @@ struct PrefillArgs {
   const void* v;
   void* out;
   float* lse;
-  void* vt;  // workspace: key-tile-wise transposed V, [key tile][kv head][D][64] bf16 (bf16 path)
+  void* vt;  // workspace: key-tile-wise transposed V in the LDS tile order (bf16 path)
   const int32_t* cu_seqlens;
   const int32_t* node_start;
   const int32_t* tok_node;
@@ -27,4 +27,5 @@ struct PrefillArgs {
 };
 
 int launch_prefill_f32(const PrefillArgs& a, int head_dim, hipStream_t stream);
-int launch_prefill_bf16(const PrefillArgs& a, int head_dim, hipStream_t stream);
+int launch_prefill_bf16_prepare_v(const PrefillArgs& a, int head_dim, hipStream_t stream);  // V -> workspace copy
+int launch_prefill_bf16(const PrefillArgs& a, int head_dim, hipStream_t stream);            // needs the copy

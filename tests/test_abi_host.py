@@ -25,6 +25,7 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"dag_meta_sizes", "dag_build_meta", "dag_rope_qk", "dag_attn_prefill", "dag_kv_append_rope",
             "dag_attn_decode", "dag_decode_workspace_bytes", "dag_prefill_workspace_bytes", "dag_prefill_tile_shape",
+            "dag_prefill_prepare_v", "dag_attn_prefill_prepared",
             "dag_strerror",
             "dag_version"} <= set(names)
     L = C.CDLL(B.LIB_PATH)
@@ -158,6 +159,14 @@ def test_rope_and_prefill_argument_errors():
     assert L.dag_prefill_workspace_bytes(C.byref(m), 8, 128, B.DAG_F32) == 0
     assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, need - 1, None) == -6
     assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None, 0, None) == -6
+    # the two halves validate the same way
+    assert L.dag_attn_prefill_prepared(C.byref(m), p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, need - 1, None) == -6
+    assert L.dag_attn_prefill_prepared(C.byref(m), None, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, big, None) == -1
+    assert L.dag_prefill_prepare_v(C.byref(m), p, 32, 8, 128, B.DAG_BF16, p, need - 1, None) == -6
+    assert L.dag_prefill_prepare_v(C.byref(m), None, 32, 8, 128, B.DAG_BF16, p, big, None) == -1
+    assert L.dag_prefill_prepare_v(C.byref(m), p, 32, 8, 96, B.DAG_BF16, p, big, None) == -7
+    assert L.dag_prefill_prepare_v(None, p, 32, 8, 128, B.DAG_BF16, p, big, None) == -1
+    assert L.dag_prefill_prepare_v(C.byref(m), C.c_void_p(FAKE + 2), 32, 8, 128, B.DAG_BF16, p, big, None) == -8
 
 
 def test_decode_argument_errors():

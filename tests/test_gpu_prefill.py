@@ -97,3 +97,24 @@ def test_prefill_is_deterministic_run_to_run():
     o1, _, _, _, _ = run_prefill(dag_list, q, k, v, 5e5)
     o2, _, _, _, _ = run_prefill(dag_list, q, k, v, 5e5)
     assert torch.equal(o1, o2)
+
+
+def test_prepare_v_then_prepared_attention_equals_the_combined_call():
+    """The two halves of dag_attn_prefill, launched separately, give the bits the combined call
+    gives (and therefore the oracle's values), with a caller-provided workspace."""
+    from tests.gpu_util import build_meta
+    dag_list = [dags.fork_join(130, [70, 33], 40), dags.linear_chain([77])]
+    T = int(sum(int(np.sum(L)) for L, _ in dag_list))
+    q, k, v = dags.make_qkv(77, T, 8, 2, 128, 0.5, torch.bfloat16)
+    _, meta = build_meta(dag_list, 8, 2, 128, torch.bfloat16)
+    qd, kd, vd = q.to(DEV).clone(), k.to(DEV).clone(), v.to(DEV)
+    B.dag_rope_qk(meta.get("pos_ids"), qd, kd, 5e5)
+    o1, o2 = torch.empty_like(qd), torch.zeros_like(qd)
+    B.dag_attn_prefill(meta, qd, kd, vd, o1)
+    ws = torch.zeros(B.dag_prefill_workspace_bytes(meta, 2, 128, B.DAG_BF16), dtype=torch.uint8, device=DEV)
+    B.dag_prefill_prepare_v(meta, vd, 8, workspace=ws)
+    B.dag_attn_prefill(meta, qd, kd, vd, o2, workspace=ws, prepared=True)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+    ref, _, rows = oracle_prefill(dag_list, q, k, v, 5e5)
+    check_close(o2[rows], ref[rows], torch.bfloat16, "prepared prefill")
