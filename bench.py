@@ -28,6 +28,11 @@ from workloads import dags  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
+# what the same counters read for a plain 256 MiB copy (profiles/k_prefill_bf16__*.txt and
+# profiles/k_decode__*.txt hold the commands and the raw readings); measured, not computed here.
+TRAFFIC_PREFILL_KERNEL = (298724 + 149988) * 1024      # k_prefill_bf16, read + written
+TRAFFIC_DECODE_KERNELS = (1060302 + 12320 + 11821 + 1024) * 1024   # k_decode + k_decode_merge
 
 
 def _ensure_built():
@@ -74,6 +79,11 @@ class PrefillWork:
         B.dag_attn_prefill(self.meta, self.q, self.k, self.v, self.out, prepared=True)
         if ev:
             ev[2].record()
+
+    def algorithmic_bytes(self):
+        """Q read and out written once, K and the transposed V read once."""
+        c = self.cfg
+        return (2 * self.T * c["hq"] + 2 * self.T * c["hkv"]) * c["d"] * 2
 
     def useful_flops(self):
         pairs = int(self.meta.get("useful_pairs").sum().item())
@@ -211,14 +221,14 @@ def main():
                         "min_prefill_attn_kernel": float(np.min(attn_ms)), "min_decode_attn_kernels": float(np.min(deck_ms))},
         "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16", "achieved": tflops_kernel,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops_kernel / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None},
+                     "traffic": TRAFFIC_PREFILL_KERNEL, "algorithmic_bytes": pw.algorithmic_bytes()},
         "decode": {"metric": "branch_decode_tok_per_s_one_attention_layer",
                    "value": dw.n_live / (ms_dec * 1e-3), "unit": "tok/s", "ms_per_decode_step": ms_dec,
                    "config": {"workload": dw.cfg["name"], "n_seqs": dw.cfg["n_seqs"], "live_branches": dw.n_live,
                               "shared_prefix": dw.cfg["shared"], "branch_len": dw.cfg["branch"], "page_size": 16},
                    "roofline": {"bound": "hbm", "kernel": "k_decode(+k_decode_merge)", "achieved": dec_gbs,
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
-                                "algorithmic_bytes": dw.bytes, "traffic": None}},
+                                "algorithmic_bytes": dw.bytes, "traffic": TRAFFIC_DECODE_KERNELS}},
         "wall_s_timed_loop": wall,
     }
     if not args.no_cpu_baseline:

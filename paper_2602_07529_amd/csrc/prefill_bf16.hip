@@ -16,8 +16,9 @@
 // Software pipeline.  The matrix pipe and the vector ALU of a SIMD run concurrently only if one
 // instruction stream feeds both, so a wave works in steps of half a key tile (32 keys) and each
 // step interleaves three independent pieces:  scores of half g + 1 (MFMA),  the exponentials of
-// half g (vector ALU),  and the P V product of half g - 1 (MFMA).  sched_group_barrier fixes the
-// interleaving (one MFMA, one LDS operand read, a few vector instructions, ...).
+// half g (vector ALU),  and the P V product of half g - 1 (MFMA).  A step is written slot by slot
+// (one LDS operand read, the MFMAs on one operand, a few vector instructions) with a scheduling
+// barrier after every slot, so the instruction order in the binary is the one written here.
 //
 // Data movement.  K tiles (64 keys x D) and V^T tiles (D x 64 keys, from a key-tile-wise
 // transposed copy of V that a small pre-pass writes into the workspace) go from global memory
