@@ -197,23 +197,26 @@ def rope(x, pos, theta):
 
 
 # ----------------------------------------------------------------------------- prefill attention
-def attn_prefill(q, k, v, node_len, anc, scale=None, row_block=128, rows=None, heads=None):
+def attn_prefill(q, k, v, node_len, anc, scale=None, row_block=128, rows=None, heads=None, compact=False):
     """O_i = sum_j softmax_j(q_i . k_j * scale + M_ij) v_j with the DAG mask (Eq. 2 + Eq. 3).
 
     q [T][Hq][D], k, v [T][Hkv][D] are the already-rotated inputs.  Query head h uses KV head
     h // (Hq/Hkv).  Returns (O [T][Hq][D], lse [T][Hq]) in fp64.  `rows` / `heads` optionally
-    restrict the computation to a subset (other entries are left NaN).
+    restrict the computation to a subset (other entries are left NaN).  With compact=True (and
+    `rows` given) q holds only the selected rows, q[i] being row rows[i], and the outputs are
+    [len(rows)][Hq][...] in the same order: for sequences too long to hold whole in fp64.
     """
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
-    T, Hq, D = q.shape
+    T = k.shape[0]
+    _, Hq, D = q.shape
     Hkv = k.shape[1]
     G = Hq // Hkv
     if scale is None:
         scale = 1.0 / np.sqrt(D)
-    O = np.full((T, Hq, D), np.nan)
-    lse = np.full((T, Hq), np.nan)
+    O = np.full((q.shape[0], Hq, D), np.nan)
+    lse = np.full((q.shape[0], Hq), np.nan)
     head_list = list(range(Hq)) if heads is None else list(heads)
     if rows is None:
         blocks = [np.arange(i0, min(T, i0 + row_block)) for i0 in range(0, T, row_block)]
@@ -223,17 +226,21 @@ def attn_prefill(q, k, v, node_len, anc, scale=None, row_block=128, rows=None, h
     tok_node, _ = token_meta(node_len, anc)
     A = node_allow_matrix(anc)
     j = np.arange(T)[None, :]
+    done = 0
     for blk in blocks:
+        # where the rows of this block sit in q / O: at their own index, or packed in order
+        at = np.arange(done, done + len(blk)) if compact else blk
+        done += len(blk)
         ni = tok_node[blk][:, None]
         allow = ((ni == tok_node[None, :]) & (j <= blk[:, None])) | A[ni, tok_node[None, :]]
         for h in head_list:
-            S = (q[blk, h, :] @ k[:, h // G, :].T) * scale
+            S = (q[at, h, :] @ k[:, h // G, :].T) * scale
             S[~allow] = -np.inf
             mrow = S.max(axis=1, keepdims=True)
             P = np.exp(S - mrow)
             lrow = P.sum(axis=1, keepdims=True)
-            O[blk, h, :] = (P @ v[:, h // G, :]) / lrow
-            lse[blk, h] = (mrow + np.log(lrow))[:, 0]
+            O[at, h, :] = (P @ v[:, h // G, :]) / lrow
+            lse[at, h] = (mrow + np.log(lrow))[:, 0]
     return O, lse
 
 

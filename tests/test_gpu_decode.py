@@ -119,3 +119,17 @@ def test_decode_equals_last_row_of_gpu_prefill():
     B.dag_attn_decode(dd, qd[-1:].contiguous(), kp, vp, out, ws)
     torch.cuda.synchronize()
     assert (out[0].float() - out_p[-1].float()).abs().max().item() < 2e-2
+
+
+@pytest.mark.parametrize("own_len", [513, 768])
+def test_decode_config5_full_size_sampled_branches(own_len):
+    """Benchmark config 5 decode at full size: 2 sequences x 32 live branches, shared prefix 32,768
+    tokens, G = 5 (160 stacked rows per group and KV head), at its first and its last step."""
+    c = dags.config(4)
+    st = dags.decode_state(c["seed"] + own_len, 2, c["n_branch"], c["prefix"], own_len, c["hq"], c["hkv"], c["d"],
+                           kv_scale=0.5, q_scale=0.5)
+    out, kp, vp = _gpu_decode(st, c["hq"], c["hkv"], c["d"], c["theta"])
+    branches = [0, 31, 32, 50, 63]
+    ref = orc.attn_decode(st["desc"], dags.to_f64(st["q"]), dags.to_f64(kp), dags.to_f64(vp), branches=branches)
+    check_close(out[branches], ref[branches], torch.bfloat16, "config 5 decode")
+    assert torch.isfinite(out.float()).all()

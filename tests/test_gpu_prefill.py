@@ -118,3 +118,28 @@ def test_prepare_v_then_prepared_attention_equals_the_combined_call():
     assert torch.equal(o1, o2)
     ref, _, rows = oracle_prefill(dag_list, q, k, v, 5e5)
     check_close(o2[rows], ref[rows], torch.bfloat16, "prepared prefill")
+
+
+def test_config5_qwen_shape_full_size_sampled_rows():
+    """Benchmark config 5 prefill at full size (2 x 50,176 tokens, 40 query heads in groups of 5):
+    sampled rows against the oracle, which gets only those query rows (compact mode)."""
+    c = dags.config(4)
+    dag_list = dags.config_dags(c)
+    hq, hkv, d = c["hq"], c["hkv"], c["d"]
+    T = int(sum(int(np.sum(L)) for L, _ in dag_list))
+    q, k, v = dags.make_qkv(c["seed"], T, hq, hkv, d, c["scale"], torch.bfloat16)
+    out, _, meta, _, _ = run_prefill(dag_list, q, k, v, c["theta"])
+    assert int(meta.get("useful_pairs").sum().item()) == 2 * 1128817152
+    rng = np.random.Generator(np.random.PCG64(c["seed"]))
+    t0 = 0
+    for L, anc in dag_list:
+        Tb = int(np.sum(L))
+        _, pos = orc.token_meta(L, anc)
+        # first / last rows, the rows around the fork and the join, and a seeded sample
+        edges = [0, 1, 32767, 32768, 32768 + 511, 32768 + 512, 32768 + 32 * 512 - 1, 32768 + 32 * 512, Tb - 1]
+        rows = np.unique(np.concatenate([edges, rng.choice(Tb, size=16, replace=False)]))
+        ks = orc.rope(dags.to_f64(k[t0:t0 + Tb]), pos, c["theta"])
+        qs = orc.rope(dags.to_f64(q[t0:t0 + Tb][rows]), pos[rows], c["theta"])
+        ref, _ = orc.attn_prefill(qs, ks, dags.to_f64(v[t0:t0 + Tb]), L, anc, rows=rows, compact=True)
+        check_close(out[t0 + rows], ref, torch.bfloat16, "config 5 prefill")
+        t0 += Tb

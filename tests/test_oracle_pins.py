@@ -403,3 +403,15 @@ def test_kv_append_places_rotated_key_in_tail_slot():
         expect = orc.rope(k_new[r:r + 1], [pos], 1e4)[0, 1]
         assert np.abs(K[-1] - expect).max() < 1e-15
         assert np.array_equal(V[-1], v_new[r, 1])
+
+
+def test_attn_prefill_compact_rows_mode_is_the_same_computation():
+    """compact=True only changes where rows are read and written, not their values."""
+    L, anc = dags.fork_join(20, [7, 9], 11)
+    T = int(np.sum(L))
+    rng = np.random.Generator(np.random.PCG64(5))
+    q, k, v = rng.standard_normal((T, 4, 16)), rng.standard_normal((T, 2, 16)), rng.standard_normal((T, 2, 16))
+    rows = np.array([0, 5, 21, 30, T - 1])
+    O, lse = orc.attn_prefill(q, k, v, L, anc, rows=rows)
+    Oc, lsec = orc.attn_prefill(q[rows], k, v, L, anc, rows=rows, compact=True)
+    assert np.array_equal(O[rows], Oc) and np.array_equal(lse[rows], lsec)
