@@ -33,8 +33,13 @@ __device__ __forceinline__ uint32_t dag_f2bf(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
 }
+// Two fp32 -> packed bf16 pair (lo in bits 0..15) with the hardware conversion (round to nearest
+// even, one v_cvt_pk_bf16_f32).
 __device__ __forceinline__ uint32_t dag_pack_bf2(float lo, float hi) {
-  return dag_f2bf(lo) | (dag_f2bf(hi) << 16);
+  typedef __attribute__((ext_vector_type(2))) float dag_f32x2;
+  typedef __attribute__((ext_vector_type(2))) __bf16 dag_bf16x2;
+  const dag_f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, dag_bf16x2));
 }
 __device__ __forceinline__ float dag_bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float dag_bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

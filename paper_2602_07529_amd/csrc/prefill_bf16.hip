@@ -86,7 +86,10 @@ __device__ __forceinline__ void wait_lgkmcnt(int n) {  // s_waitcnt lgkmcnt(n) o
     case 0: __builtin_amdgcn_s_waitcnt(0xC07F); break;
     case 1: __builtin_amdgcn_s_waitcnt(0xC17F); break;
     case 2: __builtin_amdgcn_s_waitcnt(0xC27F); break;
-    default: __builtin_amdgcn_s_waitcnt(0xC37F); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0xC37F); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0xC47F); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0xC57F); break;
+    default: __builtin_amdgcn_s_waitcnt(0xC67F); break;
   }
 }
 
@@ -208,35 +211,48 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   // kbase / vbase: the cursor item's K rows (token cu, head hk) and V^T tiles (tile ktb, head hk,
   // this wave's block); the tile adds a multiple of its index.
   const uint32_t kt_kstride = (uint32_t)TN * rowbytes, kt_vstride = (uint32_t)a.hkv * (D * TN * 2);
-  auto issue_loads = [&](unsigned slot, const unsigned char* kbase, const unsigned char* vbase, int cu, int T, int kt,
+  // Issuing a tile is split into a set-up (addresses of the tile, optional node-id record) and
+  // LPT single loads, so that the pipeline can spread them over the slots of a step, in the
+  // shadow of the MFMAs; issue_loads does all of it at once.
+  const unsigned char *p_ktile = nullptr, *p_vtile = nullptr;  // pending tile (wave-uniform)
+  unsigned char *p_kl = nullptr, *p_vl = nullptr;
+  int p_last = 0;
+  bool p_ragged = false;
+  auto issue_setup = [&](unsigned slot, const unsigned char* kbase, const unsigned char* vbase, int cu, int T, int kt,
                          bool with_nodes) {
     const int j0 = kt * TN;
     if (with_nodes) {  // a tile that needs the mask: node ids of its 64 keys (every wave writes the same record)
       const int32_t* np = a.tok_node + cu + min(j0 + lane, T - 1);
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)np, (lds_ptr_t)(Abase + slot * 256), 4, 0, 0);
     }
-    const unsigned char* ktile = kbase + (uint64_t)(uint32_t)kt * kt_kstride;
-    const unsigned char* vtile = vbase + (uint64_t)(uint32_t)kt * kt_vstride;
-    unsigned char* kl = Kbase + slot * KTILE + w * BLKK;
-    unsigned char* vl = Vbase + slot * VTILE + w * BLKV;
-    if (j0 + TN <= T) {
-#pragma unroll
-      for (int i = 0; i < IPK; ++i)
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ktile + (size_t)((w + NISS * i) * KPB) * rowbytes + ksrc),
-                                         (lds_ptr_t)(kl + i * NISS * BLKK), 16, 0, 0);
-    } else {  // ragged last tile: rows past the end re-read the last valid row (masked later)
-      const int last = T - 1 - j0;
-#pragma unroll
-      for (int i = 0; i < IPK; ++i) {
-        const int rk = min((w + NISS * i) * KPB + kkey, last);
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ktile + ((uint32_t)rk * rowbytes + kchunk)),
-                                         (lds_ptr_t)(kl + i * NISS * BLKK), 16, 0, 0);
+    p_ktile = kbase + (uint64_t)(uint32_t)kt * kt_kstride;
+    p_vtile = vbase + (uint64_t)(uint32_t)kt * kt_vstride;
+    p_kl = Kbase + slot * KTILE + w * BLKK;
+    p_vl = Vbase + slot * VTILE + w * BLKV;
+    p_ragged = j0 + TN > T;  // ragged last tile: rows past the end re-read the last valid row (masked later)
+    p_last = T - 1 - j0;
+  };
+  auto issue_part = [&](int i) {  // i = 0 .. LPT - 1, a compile-time constant at every call site
+    if (i < IPK) {
+      if (!p_ragged) {
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_ktile + (size_t)((w + NISS * i) * KPB) * rowbytes + ksrc),
+                                         (lds_ptr_t)(p_kl + i * NISS * BLKK), 16, 0, 0);
+      } else {
+        const int rk = min((w + NISS * i) * KPB + kkey, p_last);
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_ktile + ((uint32_t)rk * rowbytes + kchunk)),
+                                         (lds_ptr_t)(p_kl + i * NISS * BLKK), 16, 0, 0);
       }
+    } else {  // the transposed copy is zero padded: no ragged case
+      const int iv = i - IPK;
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_vtile + iv * (NISS * 1024) + vsrc),
+                                       (lds_ptr_t)(p_vl + iv * NISS * BLKV), 16, 0, 0);
     }
+  };
+  auto issue_loads = [&](unsigned slot, const unsigned char* kbase, const unsigned char* vbase, int cu, int T, int kt,
+                         bool with_nodes) {
+    issue_setup(slot, kbase, vbase, cu, T, kt, with_nodes);
 #pragma unroll
-    for (int i = 0; i < IPV; ++i)  // the transposed copy is zero padded: no ragged case
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vtile + i * (NISS * 1024) + vsrc), (lds_ptr_t)(vl + i * NISS * BLKV), 16,
-                                       0, 0);
+    for (int i = 0; i < LPT; ++i) issue_part(i);
   };
 
   // LDS read addresses (bytes inside a tile); every other read of the tile is an immediate away.
@@ -305,14 +321,20 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   //   QK: Sn[r]  = K_h Q_r^T      scores of key half HQ of the tile at Kb (first KSTEPS slots)
   //   PV: O[r]  += V_h^T Pp[r]    the 32 keys of half HV of the tile at Vb (last 2 DB slots)
   //   EX: Pc[r]  = exp2(sc (Sc[r] - m[r]))  probabilities of a half, row sums added to l
-  // `extra` runs in slot 1 (used to issue the next K/V tile loads in the shadow of the MFMAs).
+  // `extra(slot, slots)` runs in every slot (used to issue the next K/V tile loads piecewise, in
+  // the shadow of the MFMAs).
   // With QK, the row maxima of Sn are taken two slots after the last score MFMA and the return
   // value says whether they call for a rescale.
   auto step = [&](auto qk_c, auto pv_c, auto ex_c, auto hq_c, auto hv_c, const unsigned char* Kb, f32x16* Sn,
                   const unsigned char* Vb, const bf16x8 (*Pp)[2], const f32x16* Sc, bf16x8 (*Pc)[2], auto&& extra) {
     constexpr bool QK = decltype(qk_c)::value, PV = decltype(pv_c)::value, EX = decltype(ex_c)::value;
     constexpr int HQ = decltype(hq_c)::value, HV = decltype(hv_c)::value;
-    constexpr int NQ = QK ? KSTEPS : 0, NSLOT = NQ + (PV ? 2 * DB : 0), NU = EX ? 8 * RB : 0, PF = 3;
+    constexpr int NQ = QK ? KSTEPS : 0, NSLOT = NQ + (PV ? 2 * DB : 0), NU = EX ? 8 * RB : 0;
+#ifdef DAGATTN_PF
+    constexpr int PF = DAGATTN_PF;
+#else
+    constexpr int PF = 3;
+#endif
     constexpr int MAXSLOT = NQ + 2 < NSLOT ? NQ + 2 : NSLOT;  // where the row maxima are taken
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 opnd[NSLOT];
@@ -360,7 +382,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
         else O[r][(i - NQ) % DB] = mfma32(opnd[i], Pp[r][(i - NQ) / DB], O[r][(i - NQ) % DB]);
       }
 #if !defined(DAGATTN_ABL) || !(DAGATTN_ABL & 8)
-      if (i == 1) extra();
+      extra(i, NSLOT);
 #endif
       if (QK && i == MAXSLOT) need = row_max(Sn);
 #pragma unroll
@@ -386,7 +408,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   };
   typedef std::integral_constant<int, 0> h0_t;
   typedef std::integral_constant<int, 1> h1_t;
-  auto nothing = []() {};
+  auto nothing = [](int, int) {};
   // raise the running maxima to bmax and rescale everything accumulated so far, including the
   // probabilities that are still waiting for their P V product (rare after the first tiles)
   auto rescale = [&]() {
@@ -456,7 +478,9 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   cursor_enter(cur, load_cols(cur, 0));
   col_nxt = has_next ? load_cols(nxt, 0) : 0;
   const bool issuer = w < NISS;
-  auto try_issue = [&]() {
+  // First half of issuing the next tile of the stream: cursor, tile index, addresses.  The LPT
+  // loads follow through issue_part (at once in try_issue, slot by slot in the pipeline).
+  auto try_issue_begin = [&]() {
     if (!issuer) return false;
     if (iss_idx >= is_N) {
       if (iss_next || !has_next) return false;
@@ -468,9 +492,15 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       asm volatile("" ::"v"(col_iss));  // the wait for this load belongs here, not on the common path
     }
     const int kt = __builtin_amdgcn_readlane(col_iss, iss_idx & 63);
-    issue_loads(ti % NSTAGE, is_kbase, is_vbase, is_cu, is_T, kt, iss_idx >= is_nfast);
+    issue_setup(ti % NSTAGE, is_kbase, is_vbase, is_cu, is_T, kt, iss_idx >= is_nfast);
     ++ti;
     ++iss_idx;
+    return true;
+  };
+  auto try_issue = [&]() {
+    if (!try_issue_begin()) return false;
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) issue_part(i);
     return true;
   };
   // Moves on to the next tile of the stream: afterwards tile tc (if there is one) is visible to
@@ -478,7 +508,8 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   // that this frees is refilled.  The pipeline reads tiles tc - 1 and tc, so tiles up to
   // tc + NSTAGE - 2 may be in the ring.
 #ifdef DAGATTN_TIMING
-  unsigned long long tacc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long tacc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long t_mid = 0;
   const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
 #define TSTAMP(x) const unsigned long long x = __builtin_amdgcn_s_memrealtime()
 #define TACC(i, a0, a1) tacc[i] += (a1) - (a0)
@@ -504,6 +535,27 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   };
   auto refill = [&]() {  // after sync_next: one more tile into the slot that became free
     if (ti - tc < NSTAGE - 1) try_issue();
+  };
+  // The same, spread over the slots of a pipeline step with NS slots (slot 1: set-up, the slots
+  // after it: the loads), so that the scalar work and the load issue hide behind the MFMAs.
+  // The texture path takes a 1 KiB load every 16 cycles at best, so the loads are spaced out: the
+  // K loads over the first step of a tile, the V^T loads over the second.
+  bool refill_pending = false;
+  auto refill_slot = [&](int i, int NS) {  // first step: set-up in slot 1, K load x in slot 2 + x (NS - 2) / IPK
+    if (i == 1) {
+      refill_pending = (ti - tc < NSTAGE - 1) && try_issue_begin();
+    } else if (i >= 2 && refill_pending) {
+#pragma unroll
+      for (int x = 0; x < IPK; ++x)
+        if (2 + x * (NS - 2) / IPK == i) issue_part(x);
+    }
+  };
+  auto refill_slot_v = [&](int i, int NS) {  // second step: V^T load x in slot x NS / IPV
+    if (refill_pending) {
+#pragma unroll
+      for (int x = 0; x < IPV; ++x)
+        if (x * NS / IPV == i) issue_part(IPK + x);
+    }
   };
   auto advance = [&]() {
     sync_next();
@@ -565,10 +617,26 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
         sync_next();  // tile tc - 1 is the one in flight through the pipeline, tc the new one
         TSTAMP(t1);
         if (need) rescale();
-        need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, refill);
+#ifdef DAGATTN_TIMING
+        need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, [&](int i, int NS) {
+          if (i == NS / 2) t_mid = __builtin_amdgcn_s_memrealtime();
+          refill_slot(i, NS);
+        });
+        TACC(9, t1, t_mid);
+#else
+        need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, refill_slot);
+#endif
         TSTAMP(t2);
         if (need) rescale();
-        need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, nothing);
+#ifdef DAGATTN_TIMING
+        need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, [&](int i, int NS) {
+          if (i == NS / 2) t_mid = __builtin_amdgcn_s_memrealtime();
+          refill_slot_v(i, NS);
+        });
+        TACC(10, t2, t_mid);
+#else
+        need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, refill_slot_v);
+#endif
         TSTAMP(t3);
         TACC(1, t0, t1);
         TACC(2, t1, t2);
@@ -576,15 +644,10 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
         TCOUNT(7);
       }
       TSTAMP(t_b);
-      if (F == cur.N && has_next) {  // the Q registers are free from here on
-        load_q(nxt);
-#pragma unroll
-        for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
-      }
       sync_next();
       if (need) rescale();
-      step(N_, Y, Y, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill);
-      step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc - 1), P1, nullptr, nullptr, nothing);
+      step(N_, Y, Y, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill_slot);
+      step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc - 1), P1, nullptr, nullptr, refill_slot_v);
       TSTAMP(t_c);
       TACC(4, t_b, t_c);
     }
@@ -604,7 +667,14 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       const int32_t* cp = a.col + sgpr(cur.c0 + n);
       asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(kt) : "s"(cp) : "memory");
       const int j0 = kt * TN;
-      const int nj = *(const int*)(Abase + (tc % NSTAGE) * 256 + lane * 4);  // node of key j0 + lane
+      // node of key j0 + lane (inline assembly: for a plain LDS read the compiler would first wait
+      // for every global-to-LDS load in flight, i.e. drain the ring; the record of this tile has
+      // landed, the barrier that published the tile covers it)
+      int nj;
+      asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                   : "=v"(nj)
+                   : "v"(lds_addr(Abase + (tc % NSTAGE) * 256 + lane * 4))
+                   : "memory");
       const int prev = __shfl_up(nj, 1);
       uint64_t starts = __builtin_amdgcn_ballot_w64(lane == 0 || nj != prev);
       uint64_t rowmask[RB];
@@ -618,8 +688,11 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
         const uint64_t range = (s1 == 64 ? ~0ull : ((1ull << s1) - 1)) & ~((1ull << s0) - 1);
 #pragma unroll
         for (int r = 0; r < RB; ++r) {
-          const uint64_t word =
-              (a.W == 1) ? vis0[r] : a.node_vis[(int64_t)(cur.nstart + rnode[r]) * a.W + (ns >> 6)];
+          uint64_t word = vis0[r];
+          if (a.W != 1) {  // more than 64 nodes: fetch the word (the wait for it stays in this branch)
+            word = a.node_vis[(int64_t)(cur.nstart + rnode[r]) * a.W + (ns >> 6)];
+            asm volatile("" ::"v"(word));
+          }
           if ((word >> (ns & 63)) & 1) rowmask[r] |= range;
         }
       }
@@ -655,29 +728,66 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     };
 #pragma unroll 1
     for (int n = F; n + 1 < cur.N; ++n) partial_tile(n, no_t());
-    if (F < cur.N) partial_tile(cur.N - 1, yes_t());
+    if (F < cur.N) {
+      partial_tile(cur.N - 1, yes_t());
+    } else if (has_next) {
+      // No PARTIAL tile (cannot happen with 64 x 64 tiles, whose diagonal tile is never FULL):
+      // fetch the next item's rows here.  Placed after the loop above on purpose: a load of the Q
+      // registers in front of it would make the compiler wait for everything in flight there.
+      load_q(nxt);
+#pragma unroll
+      for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
+    }
 
     TSTAMP(t_p1);
     TACC(5, t_p0, t_p1);
-    // ---- output
+    // ---- output.  A lane holds one row in 8-byte pieces scattered over the head dimension;
+    // stored like that, every store instruction would touch 32 rows.  The wave transposes its
+    // rows through a private 4 KiB piece of the ring slot of the tile that was finished last
+    // (free since the barrier of the last advance; 16 rows at a time, 16-byte chunks XOR-swizzled
+    // by the row so that writes and reads are conflict free), and stores full rows: 16 lanes x 16
+    // bytes per row.
     const int head = head_of(cur);
+    if (F == cur.N) {  // no PARTIAL tile: the last P V steps came after the last barrier
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    }
+    {
+      constexpr int CPR = D / 8;  // 16-byte chunks per row
+      unsigned char* stage = (w < NW / 2 || NW == 1 ? Kbase + ((tc - 1) % NSTAGE) * KTILE
+                                                     : Vbase + ((tc - 1) % NSTAGE) * VTILE) +
+                             (w % (NW > 1 ? NW / 2 : 1)) * (16 * D * 2);
 #pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      const float l_tot = l[r] + __shfl_xor(l[r], 32);
-      if (row_of(cur, r) < cur.T) {
-        const int tok = token_of(cur, r);
+      for (int r = 0; r < RB; ++r) {
+        const float l_tot = l[r] + __shfl_xor(l[r], 32);
         const float inv = 1.f / l_tot;
-        uint16_t* og = (uint16_t*)a.out + ((size_t)tok * a.hq + head) * D;
+        if (a.lse && H == 0 && row_of(cur, r) < cur.T)
+          a.lse[(size_t)token_of(cur, r) * a.hq + head] = m[r] * a.scale + logf(l_tot);
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int half = 0; half < 2; ++half) {  // rows 16 half .. 16 half + 15 of the block
+          if ((L >> 4) == half) {
+            const int rr = L & 15;
 #pragma unroll
-          for (int r4 = 0; r4 < 4; ++r4) {
-            u32x2 o;
-            o[0] = dag_pack_bf2(O[r][db][4 * r4] * inv, O[r][db][4 * r4 + 1] * inv);
-            o[1] = dag_pack_bf2(O[r][db][4 * r4 + 2] * inv, O[r][db][4 * r4 + 3] * inv);
-            *(u32x2*)(og + 32 * db + 8 * r4 + 4 * H) = o;
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+              for (int r4 = 0; r4 < 4; ++r4) {
+                u32x2 o;
+                o[0] = dag_pack_bf2(O[r][db][4 * r4] * inv, O[r][db][4 * r4 + 1] * inv);
+                o[1] = dag_pack_bf2(O[r][db][4 * r4 + 2] * inv, O[r][db][4 * r4 + 3] * inv);
+                const int c = 4 * db + r4;  // chunk of dimensions 32 db + 8 r4 .. + 7; this lane has half H of it
+                *(u32x2*)(stage + rr * (D * 2) + ((c ^ rr) % CPR) * 16 + 8 * H) = o;
+              }
           }
-        if (a.lse && H == 0) a.lse[(size_t)tok * a.hq + head] = m[r] * a.scale + logf(l_tot);
+          // read back: lane = (row, chunk); a store instruction covers 64 / CPR full rows
+#pragma unroll
+          for (int k = 0; k < 16 * CPR / 64; ++k) {
+            const int rr = k * (64 / CPR) + lane / CPR, c = lane % CPR;
+            const u32x4 o = *(const u32x4*)(stage + rr * (D * 2) + ((c ^ rr) % CPR) * 16);
+            const int row = cur.row0 + 32 * (rg * RB + r) + 16 * half + rr;
+            if (row < cur.T)
+              *(u32x4*)((uint16_t*)a.out + ((size_t)(cur.cu + row) * a.hq + head) * D + c * 8) = o;
+          }
+        }
       }
     }
     TSTAMP(t_o);
@@ -703,10 +813,15 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     }
   }
 #ifdef DAGATTN_TIMING
+  if (tid == 0 && (blockIdx.x & 7) == 1) {
+    const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
+    printf("blk %d begin %llu end %llu total %llu tiles %llu\n", (int)blockIdx.x, t_begin % 1000000ull, t_end % 1000000ull,
+           t_end - t_begin, tacc[7]);
+  }
   if (blockIdx.x == 0 && lane == 0) {
     const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
-    printf("wave %d total %llu | prologue %llu sync %llu stepA %llu stepB %llu epi %llu partial %llu out %llu | pipelined tiles %llu vmwait %llu (x10ns)\n",
-           w, t_end - t_begin, tacc[0], tacc[1], tacc[2], tacc[3], tacc[4], tacc[5], tacc[6], tacc[7], tacc[8]);
+    printf("wave %d total %llu | prologue %llu sync %llu stepA %llu stepB %llu epi %llu partial %llu out %llu | pipelined tiles %llu vmwait %llu A1 %llu B1 %llu (x10ns)\n",
+           w, t_end - t_begin, tacc[0], tacc[1], tacc[2], tacc[3], tacc[4], tacc[5], tacc[6], tacc[7], tacc[8], tacc[9], tacc[10]);
   }
 #endif
 }
