@@ -104,8 +104,8 @@ typedef struct {
   int32_t* qtile_col;      /* [csr_capacity] key-tile index                                    */
   uint8_t* qtile_flag;     /* [csr_capacity] DAG_TILE_PARTIAL or DAG_TILE_FULL                 */
   int32_t* qtile_nfull;    /* [total_qtiles] number of FULL tiles in the row                   */
-  int32_t* qtile_order;    /* [total_qtiles] launch order: sequences in order, inside a sequence
-                              the query tiles by descending tile count (ties: ascending index) */
+  int32_t* qtile_order;    /* [total_qtiles] launch order: all query tiles by descending tile
+                              count (ties: ascending index)                                    */
   int32_t* qtile_desc;     /* [total_qtiles][8] per launch slot: token offset of the sequence,
                               its token count, first row of the tile, CSR row start, tiles in
                               the row, leading tiles that need no mask (FULL and not ragged),
@@ -157,7 +157,11 @@ int dag_attn_prefill(const dag_meta_t* meta, const void* q, const void* k, const
  * produced.  dag_prefill_prepare_v writes the key-tile-wise transposed copy of v [T][hkv][head_dim]
  * into `ws` (a no-op for DAG_F32); dag_attn_prefill_prepared is dag_attn_prefill without that
  * step: it expects `ws` as dag_prefill_prepare_v left it for the same meta, v, hkv, head_dim and
- * dtype.  Arguments, layouts, errors and the workspace size are those of dag_attn_prefill. */
+ * dtype.  Arguments, layouts, errors and the workspace size are those of dag_attn_prefill.
+ * The workspace also holds the attention kernel's work-distribution counters: dag_prefill_prepare_v
+ * zeroes them and every attention launch leaves them zeroed, so a workspace must go through
+ * dag_prefill_prepare_v (or dag_attn_prefill) once before dag_attn_prefill_prepared uses it, and
+ * two attention launches must not use one workspace at the same time. */
 int dag_prefill_prepare_v(const dag_meta_t* meta, const void* v, int32_t hq, int32_t hkv,
                           int32_t head_dim, dag_dtype_t dtype, void* ws, size_t ws_bytes, void* stream);
 int dag_attn_prefill_prepared(const dag_meta_t* meta, const void* q, const void* k, const void* v,

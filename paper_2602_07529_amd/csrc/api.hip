@@ -5,8 +5,9 @@
 extern "C" size_t dag_prefill_workspace_bytes(const dag_meta_t* m, int32_t hkv, int32_t head_dim,
                                               dag_dtype_t dtype) {
   if (!m || dtype != DAG_BF16 || hkv < 1 || head_dim < 1 || m->sizes.total_ktiles < 0) return 0;
-  // key-tile-wise transposed copy of V: [key tile][kv head][head_dim][tile_n] bf16
-  return (size_t)m->sizes.total_ktiles * hkv * head_dim * m->tile_n * 2 + 256;
+  // key-tile-wise transposed copy of V: [key tile][kv head][head_dim][tile_n] bf16, then the
+  // work-distribution counters, plus slack for aligning the caller's pointer to 256 bytes
+  return (size_t)m->sizes.total_ktiles * hkv * head_dim * m->tile_n * 2 + DAG_SCHED_INTS * 4 + 256;
 }
 
 namespace {
@@ -43,6 +44,7 @@ int prefill_args(const dag_meta_t* m, const void* q, const void* k, const void* 
   a->out = out;
   a->lse = lse;
   a->vt = need > 0 ? (void*)dag_align_up((size_t)(uintptr_t)ws, 256) : nullptr;
+  a->sched = need > 0 ? (int32_t*)((char*)a->vt + (size_t)m->sizes.total_ktiles * hkv * head_dim * m->tile_n * 2) : nullptr;
   a->cu_seqlens = m->cu_seqlens;
   a->node_start = m->node_start;
   a->tok_node = m->tok_node;

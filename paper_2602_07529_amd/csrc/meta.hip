@@ -318,22 +318,27 @@ __global__ void __launch_bounds__(64) k_csr_fill(int n_seqs, const int32_t* qtil
   }
 }
 
-// One thread per query tile: launch order = sequences in order, inside a sequence the query
-// tiles by (tile count descending, index ascending).  Query tiles that run at the same time then
-// read the same sequence's K/V (L2 locality) and have similar amounts of work.
-__global__ void k_order(int n_seqs, int total_qtiles, const int32_t* qtile_start, const int32_t* cnt,
-                        int32_t* order) {
-  const int qt = blockIdx.x * blockDim.x + threadIdx.x;
-  if (qt >= total_qtiles) return;
-  const int b = dag_find_segment(qtile_start, n_seqs, qt);
-  const int q0 = qtile_start[b], q1 = qtile_start[b + 1];
-  const int mine = cnt[qt];
-  int rank = q0;
-  for (int j = q0; j < q1; ++j) {
-    const int o = cnt[j];
-    rank += (o > mine) || (o == mine && j < qt);
+// One thread per query tile: launch order = all query tiles by (tile count descending, index
+// ascending), i.e. the rank of a tile is the number of tiles in front of it.  The prefill kernel
+// hands the list out dynamically, and with the heaviest items first the workgroups finish within
+// the duration of one of the lightest.  The counts pass through LDS 256 at a time (blockDim.x
+// must be 256).
+__global__ void __launch_bounds__(256) k_order(int total_qtiles, const int32_t* cnt, int32_t* order) {
+  __shared__ int32_t s_cnt[256];
+  const int qt = blockIdx.x * 256 + threadIdx.x;
+  const int mine = qt < total_qtiles ? cnt[qt] : 0;
+  int rank = 0;
+  for (int j0 = 0; j0 < total_qtiles; j0 += 256) {
+    const int n = min(256, total_qtiles - j0);
+    __syncthreads();
+    if ((int)threadIdx.x < n) s_cnt[threadIdx.x] = cnt[j0 + threadIdx.x];
+    __syncthreads();
+    for (int j = 0; j < n; ++j) {
+      const int o = s_cnt[j];
+      rank += (o > mine) || (o == mine && j0 + j < qt);
+    }
   }
-  order[rank] = qt;
+  if (qt < total_qtiles) order[rank] = qt;
 }
 
 // One thread per launch slot: everything the prefill kernel needs to start a query tile, in one
@@ -458,8 +463,7 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
                      m->cu_seqlens, d->tile_n, m->block_map, m->qtile_rowptr, m->qtile_col, m->qtile_flag,
                      m->qtile_nfull);
   DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_order, dim3((QT + 255) / 256), dim3(256), 0, stream, d->n_seqs, (int)QT, m->qtile_start, d_cnt,
-                     m->qtile_order);
+  hipLaunchKernelGGL(k_order, dim3((QT + 255) / 256), dim3(256), 0, stream, (int)QT, d_cnt, m->qtile_order);
   DAG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_desc, dim3((QT + 255) / 256), dim3(256), 0, stream, d->n_seqs, (int)QT, d->tile_m, d->tile_n,
                      m->qtile_order, m->qtile_start, m->cu_seqlens, m->node_start, m->ktile_start, m->qtile_rowptr,

@@ -4,10 +4,10 @@
 // head's query heads stacked, so every wave of the workgroup consumes the same K/V tiles.  A wave
 // owns RB 32-row blocks of one head (RB = 2: four waves, one per SIMD, each K/V operand read from
 // LDS feeds two MFMAs; RB = 1: eight waves).  The kernel is persistent: the grid has one
-// workgroup per CU and workgroup g processes items g, g + grid, ... of the launch list (sequences
-// in order, heavy query tiles first).  The K/V stream of the next item is prefetched while the
-// current one finishes; and because workgroups are placed round-robin on the eight XCDs, an XCD
-// keeps working on one KV head of one sequence at a time, whose K/V then stay in its L2.
+// workgroup per CU; workgroup g processes items g and g + grid of the launch list (query tiles
+// heavy first, the head groups of a tile next to each other) and takes every further item from a
+// counter, one item ahead of its use.  The K/V stream of the next item is prefetched while the
+// current one finishes.
 //
 // Only the key tiles the block map lists are visited.  The CSR row of a query tile lists its FULL
 // tiles first: those need no mask and run through the software pipeline below; PARTIAL tiles (and
@@ -117,10 +117,12 @@ struct Item {  // wave-uniform description of a work item
 template <int D>
 __global__ void __launch_bounds__(256) k_vt_prepare(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
                                                     const int32_t* __restrict__ ktile_start,
-                                                    const int32_t* __restrict__ cu_seqlens, int n_seqs, int hkv) {
+                                                    const int32_t* __restrict__ cu_seqlens, int n_seqs, int hkv,
+                                                    int32_t* __restrict__ sched) {
   constexpr int LD = D + 8;  // padded row (elements)
   __shared__ __attribute__((aligned(16))) uint16_t s[TN * LD];
   const int tile = blockIdx.x, h = blockIdx.y;
+  if (tile == 0 && h == 0 && threadIdx.x < DAG_SCHED_INTS) sched[threadIdx.x] = 0;  // work counters of the attention kernel
   const int b = dag_find_segment(ktile_start, n_seqs, tile);
   const int T = cu_seqlens[b + 1] - cu_seqlens[b];
   const int j0 = (tile - ktile_start[b]) * TN;
@@ -143,6 +145,9 @@ __global__ void __launch_bounds__(256) k_vt_prepare(const uint16_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
+#ifdef DAGATTN_TIMING
+__device__ unsigned long long g_tlog[4096];
+#endif
 template <int D, int HG, int RB>
 __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillArgs a) {
   constexpr int NRG = 2 / RB;                // groups of RB row blocks, spread over waves
@@ -185,6 +190,15 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   const unsigned char* vtg = (const unsigned char*)a.vt;
   const uint32_t rowbytes = (uint32_t)a.hkv * D * 2;
 
+  // Work distribution.  The items are the (query tile, head group) pairs in launch order, the
+  // head groups of a query tile next to each other; the list is sorted heavy first.  Workgroup b
+  // takes items b and b + grid statically and every further one from a counter in the workspace,
+  // so whoever is free next takes the heaviest item left (the compute units do not all run at the
+  // same speed, and the items differ by more than a factor of ten).
+  const int nb = (int)gridDim.x;
+  const int my_rank = (int)blockIdx.x;
+  const long n_list = n_items;
+  int32_t* const ctr = a.sched;
   auto load_item = [&](long it) {
     const int oi = (int)(it / nhw), hw = (int)(it % nhw);
     const int32_t* d = a.qtile_desc + (size_t)oi * 8;
@@ -451,11 +465,16 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   };
 
   // ---------------------------------------------------------------- persistent loop over items
-  long item = blockIdx.x;
-  if (item >= n_items) return;
-  Item cur = load_item(item);
-  bool has_next = item + gridDim.x < n_items;
-  Item nxt = has_next ? load_item(item + gridDim.x) : cur;
+  // (the launch has at most one workgroup per item, so the first item always exists)
+  Item cur = load_item(my_rank);
+  bool has_next = (long)my_rank + nb < n_list;
+  Item nxt = has_next ? load_item(my_rank + nb) : cur;
+  // The last wave takes the items after the second from the counter, one item ahead: asked for
+  // at the start of an item, handed to the other waves through `mbox` before its last tile.
+  const bool grabber = w == NW - 1;
+  int grabbed = 0;
+  uint32_t* const mbox = (uint32_t*)(Abase + NSTAGE * 256);
+  int mslot = 0;
 
   // The K/V tile stream runs ahead of the computation, across the item boundary: `ti` tiles have
   // been issued, tile `tc` is the one being consumed; tile t lives in ring slot t % NSTAGE.
@@ -593,6 +612,9 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       asm volatile("" ::"v"(vis0[r]), "v"(rnode_nxt[r]));
     }
     asm volatile("" ::"v"(col_iss), "v"(col_nxt));
+    TCOUNT(11);
+    if (grabber && has_next && lane == 0)  // the item after `nxt`; the answer is needed at the end of this item only
+      grabbed = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     const int F = cur.nfast;
     f32x16 SA[RB], SB[RB];
@@ -728,6 +750,17 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     };
 #pragma unroll 1
     for (int n = F; n + 1 < cur.N; ++n) partial_tile(n, no_t());
+    // The item after `nxt`: the last wave publishes what the counter gave it (-1: the list is
+    // exhausted).  Done in front of the item's last tile: the barrier that ends that tile (or the
+    // one in front of the output when there is none) makes it visible, and a wait on the answer
+    // placed later would also wait for the next item's Q rows or for the output stores.  Two
+    // slots, used in turn: a wave may still have to read the one written an item ago.
+    if (grabber && has_next) {
+      asm volatile("" ::"v"(grabbed));  // the wait for the counter's answer belongs here
+      const long g = 2L * nb + __builtin_amdgcn_readfirstlane(grabbed);
+      const int v = g < n_list ? (int)g : -1;
+      asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" ::"v"(lds_addr(mbox + mslot)), "v"(v) : "memory");
+    }
     if (F < cur.N) {
       partial_tile(cur.N - 1, yes_t());
     } else if (has_next) {
@@ -794,10 +827,13 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     TACC(6, t_p1, t_o);
     if (!has_next) break;
     reset_acc();
-    item += gridDim.x;
+    int after_next;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(after_next) : "v"(lds_addr(mbox + mslot)) : "memory");
+    mslot ^= 1;
+    after_next = sgpr(after_next);
     cur = nxt;
-    has_next = item + gridDim.x < n_items;
-    if (has_next) nxt = load_item(item + gridDim.x);
+    has_next = after_next >= 0;
+    if (has_next) nxt = load_item(after_next);
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
       rnode[r] = rnode_nxt[r];
@@ -812,12 +848,41 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     while (ti - tc < NSTAGE - 1 && try_issue()) {
     }
   }
+  // Every answer from the counters has arrived by now (each was waited for at the end of its
+  // item), so this workgroup's requests were served before it reports itself done, and the
+  // workgroup that finishes last can put the counters back to zero for the next launch.  Relaxed
+  // on purpose: only the order of these atomic operations matters, and a release would write
+  // back and invalidate the L2 under the workgroups that are still running.
 #ifdef DAGATTN_TIMING
-  if (tid == 0 && (blockIdx.x & 7) == 1) {
-    const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
-    printf("blk %d begin %llu end %llu total %llu tiles %llu\n", (int)blockIdx.x, t_begin % 1000000ull, t_end % 1000000ull,
-           t_end - t_begin, tacc[7]);
+  if (tid == 0) {  // begin, end and tile count of every workgroup, printed by the one that finishes last
+    __hip_atomic_store(&g_tlog[blockIdx.x * 4 + 0], t_begin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&g_tlog[blockIdx.x * 4 + 1], __builtin_amdgcn_s_memrealtime(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&g_tlog[blockIdx.x * 4 + 2], tacc[7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&g_tlog[blockIdx.x * 4 + 3], tacc[11], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0);
   }
+#endif
+  if (tid == 0) {
+    int32_t* const done = a.sched + DAG_SCHED_INTS / 2;
+    if (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
+      __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#ifdef DAGATTN_TIMING
+      unsigned long long t0 = ~0ull;
+      for (unsigned b = 0; b < gridDim.x; ++b) {
+        const unsigned long long x = __hip_atomic_load(&g_tlog[b * 4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t0 = x < t0 ? x : t0;
+      }
+      for (unsigned b = 0; b < gridDim.x; ++b)
+        printf("blk %u begin %llu end %llu tiles %llu items %llu\n", b,
+               __hip_atomic_load(&g_tlog[b * 4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - t0,
+               __hip_atomic_load(&g_tlog[b * 4 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - t0,
+               __hip_atomic_load(&g_tlog[b * 4 + 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+               __hip_atomic_load(&g_tlog[b * 4 + 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+#endif
+    }
+  }
+#ifdef DAGATTN_TIMING
   if (blockIdx.x == 0 && lane == 0) {
     const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
     printf("wave %d total %llu | prologue %llu sync %llu stepA %llu stepB %llu epi %llu partial %llu out %llu | pipelined tiles %llu vmwait %llu A1 %llu B1 %llu (x10ns)\n",
@@ -829,7 +894,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
 template <int D, int HG, int RB>
 int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
   constexpr int KPB = 64 / (D / 8);
-  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256);
+  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256) + 16;  // ring + item mailbox
   if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, RB>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sm) != hipSuccess)
     return DAG_ERR_HIP;
@@ -861,7 +926,7 @@ int launch_d(const PrefillArgs& a, hipStream_t stream) {
 template <int D>
 int launch_prepare_v(const PrefillArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL((k_vt_prepare<D>), dim3((unsigned)a.total_ktiles, (unsigned)a.hkv), dim3(256), 0, stream,
-                     (const uint16_t*)a.v, (uint16_t*)a.vt, a.ktile_start, a.cu_seqlens, a.n_seqs, a.hkv);
+                     (const uint16_t*)a.v, (uint16_t*)a.vt, a.ktile_start, a.cu_seqlens, a.n_seqs, a.hkv, a.sched);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }

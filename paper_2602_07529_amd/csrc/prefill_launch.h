@@ -2,6 +2,8 @@
 #pragma once
 #include "common.h"
 
+constexpr int DAG_SCHED_INTS = 128;  // [0..63] item counters, [64] finished workgroups
+
 struct PrefillArgs {
   const void* q;
   const void* k;
@@ -9,6 +11,7 @@ struct PrefillArgs {
   void* out;
   float* lse;
   void* vt;  // workspace: key-tile-wise transposed V in the LDS tile order (bf16 path)
+  int32_t* sched;  // workspace: work-distribution counters of the bf16 kernel, DAG_SCHED_INTS ints, zero between launches
   const int32_t* cu_seqlens;
   const int32_t* node_start;
   const int32_t* tok_node;

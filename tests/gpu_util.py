@@ -65,9 +65,9 @@ def oracle_meta(dag_list, tm, tn):
         qtile_nfull=cat(out.get("nfull", []), np.int64),
         useful_pairs=np.array(out["useful_pairs"], dtype=np.int64))
     cnt = np.array(out["cnt"], dtype=np.int64)
-    # launch order: sequences in order; inside a sequence descending tile count, ties by ascending index
+    # launch order: all query tiles by descending tile count, ties by ascending index
     seq_of = np.repeat(np.arange(len(dag_list)), np.diff(res["qtile_start"]))
-    order = sorted(range(len(cnt)), key=lambda i: (seq_of[i], -cnt[i], i))
+    order = sorted(range(len(cnt)), key=lambda i: (-cnt[i], i))
     res["qtile_order"] = np.array(order, dtype=np.int64)
     # launch descriptors: {token offset, tokens, first row, CSR start, tiles, mask-free tiles, node offset, tile id}
     node_start = np.concatenate([[0], np.cumsum([len(L) for L, _ in dag_list])])
