@@ -318,40 +318,31 @@ __global__ void __launch_bounds__(64) k_csr_fill(int n_seqs, const int32_t* qtil
   }
 }
 
-// One thread per query tile: launch order = all query tiles by (tile count descending, index
-// ascending), i.e. the rank of a tile is the number of tiles in front of it.  The prefill kernel
-// hands the list out dynamically, and with the heaviest items first the workgroups finish within
-// the duration of one of the lightest.  The counts pass through LDS 256 at a time (blockDim.x
-// must be 256).
-__global__ void __launch_bounds__(256) k_order(int total_qtiles, const int32_t* cnt, int32_t* order) {
-  __shared__ int32_t s_cnt[256];
-  const int qt = blockIdx.x * 256 + threadIdx.x;
-  const int mine = qt < total_qtiles ? cnt[qt] : 0;
-  int rank = 0;
-  for (int j0 = 0; j0 < total_qtiles; j0 += 256) {
-    const int n = min(256, total_qtiles - j0);
-    __syncthreads();
-    if ((int)threadIdx.x < n) s_cnt[threadIdx.x] = cnt[j0 + threadIdx.x];
-    __syncthreads();
-    for (int j = 0; j < n; ++j) {
-      const int o = s_cnt[j];
-      rank += (o > mine) || (o == mine && j0 + j < qt);
-    }
-  }
-  if (qt < total_qtiles) order[rank] = qt;
-}
-
-// One thread per launch slot: everything the prefill kernel needs to start a query tile, in one
-// 32-byte record {token offset of the sequence, tokens in the sequence, first row of the tile,
+// One wave per query tile: launch order = all query tiles by (tile count descending, index
+// ascending), i.e. the slot of a tile is the number of tiles in front of it; the lanes share the
+// comparisons.  The prefill kernel hands the list out dynamically, and with the heaviest items
+// first the workgroups finish within the duration of one of the lightest.  The wave also writes
+// the tile's launch record into its slot: everything the prefill kernel needs to start the query
+// tile, in 32 bytes {token offset of the sequence, tokens in the sequence, first row of the tile,
 // CSR row start, tiles in the row, tiles that need no mask, node offset of the sequence, first key
 // tile of the sequence}.
-__global__ void k_desc(int n_seqs, int total_qtiles, int tile_m, int tile_n, const int32_t* order,
-                       const int32_t* qtile_start, const int32_t* cu_seqlens, const int32_t* node_start,
-                       const int32_t* ktile_start, const int32_t* rowptr, const int32_t* col,
-                       const int32_t* nfull, int32_t* desc) {
-  const int oi = blockIdx.x * blockDim.x + threadIdx.x;
-  if (oi >= total_qtiles) return;
-  const int qt = order[oi];
+__global__ void __launch_bounds__(256) k_order_desc(int n_seqs, int total_qtiles, int tile_m, int tile_n,
+                                                    const int32_t* cnt, const int32_t* qtile_start,
+                                                    const int32_t* cu_seqlens, const int32_t* node_start,
+                                                    const int32_t* ktile_start, const int32_t* rowptr,
+                                                    const int32_t* col, const int32_t* nfull, int32_t* order,
+                                                    int32_t* desc) {
+  const int qt = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (qt >= total_qtiles) return;
+  const int mine = cnt[qt];
+  int oi = 0;
+  for (int j = lane; j < total_qtiles; j += 64) {
+    const int o = cnt[j];
+    oi += (o > mine) || (o == mine && j < qt);
+  }
+  for (int off = 32; off; off >>= 1) oi += __shfl_xor(oi, off);
+  if (lane != 0) return;
+  order[oi] = qt;
   const int b = dag_find_segment(qtile_start, n_seqs, qt);
   const int T = cu_seqlens[b + 1] - cu_seqlens[b];
   const int c0 = rowptr[qt];
@@ -463,11 +454,9 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
                      m->cu_seqlens, d->tile_n, m->block_map, m->qtile_rowptr, m->qtile_col, m->qtile_flag,
                      m->qtile_nfull);
   DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_order, dim3((QT + 255) / 256), dim3(256), 0, stream, (int)QT, d_cnt, m->qtile_order);
-  DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_desc, dim3((QT + 255) / 256), dim3(256), 0, stream, d->n_seqs, (int)QT, d->tile_m, d->tile_n,
-                     m->qtile_order, m->qtile_start, m->cu_seqlens, m->node_start, m->ktile_start, m->qtile_rowptr,
-                     m->qtile_col, m->qtile_nfull, m->qtile_desc);
+  hipLaunchKernelGGL(k_order_desc, dim3((QT + 3) / 4), dim3(256), 0, stream, d->n_seqs, (int)QT, d->tile_m, d->tile_n,
+                     d_cnt, m->qtile_start, m->cu_seqlens, m->node_start, m->ktile_start, m->qtile_rowptr, m->qtile_col,
+                     m->qtile_nfull, m->qtile_order, m->qtile_desc);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
