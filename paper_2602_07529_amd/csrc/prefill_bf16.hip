@@ -99,12 +99,6 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {  // byte address i
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
-#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 4)
-#define DAGATTN_ABL_EX 1
-#else
-#define DAGATTN_ABL_EX 0
-#endif
-
 struct Item {  // wave-uniform description of a work item
   int cu, T, row0, c0, N, nfast, nstart, ktb, hk, hs;
 };
@@ -344,11 +338,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     constexpr bool QK = decltype(qk_c)::value, PV = decltype(pv_c)::value, EX = decltype(ex_c)::value;
     constexpr int HQ = decltype(hq_c)::value, HV = decltype(hv_c)::value;
     constexpr int NQ = QK ? KSTEPS : 0, NSLOT = NQ + (PV ? 2 * DB : 0), NU = EX ? 8 * RB : 0;
-#ifdef DAGATTN_PF
-    constexpr int PF = DAGATTN_PF;
-#else
-    constexpr int PF = 3;
-#endif
+    constexpr int PF = 3;  // operand reads in flight ahead of the MFMA that uses them
     constexpr int MAXSLOT = NQ + 2 < NSLOT ? NQ + 2 : NSLOT;  // where the row maxima are taken
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 opnd[NSLOT];
@@ -364,10 +354,6 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     // (the compiler's own bookkeeping waits for all of them, which exposes the LDS latency).
     const uint32_t kaddr = QK ? lds_addr(Kb) + koff : 0, vaddr = PV ? lds_addr(Vb) + voff : 0;
     auto fetch = [&](int i) {
-#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 2)
-      opnd[i] = __builtin_bit_cast(bf16x8, u32x4{(uint32_t)i, 0u, 0u, 0u});
-      return;
-#endif
       if (i < NQ)
         asm volatile("ds_read_b128 %0, %1 offset:%2"
                      : "=v"(opnd[i])
@@ -387,20 +373,13 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r = 0; r < RB; ++r) {
-#if defined(DAGATTN_ABL) && (DAGATTN_ABL & 1)
-        if (i < NQ) Sn[r][i] = (i == 0 ? 0.f : Sn[r][i]) + (float)opnd[i][0];
-        else O[r][(i - NQ) % DB][i] += (float)opnd[i][0];
-        continue;
-#endif
         if (i < NQ) Sn[r] = mfma32(opnd[i], qf[r][i], i == 0 ? zero : Sn[r]);
         else O[r][(i - NQ) % DB] = mfma32(opnd[i], Pp[r][(i - NQ) / DB], O[r][(i - NQ) % DB]);
       }
-#if !defined(DAGATTN_ABL) || !(DAGATTN_ABL & 8)
       extra(i, NSLOT);
-#endif
       if (QK && i == MAXSLOT) need = row_max(Sn);
 #pragma unroll
-      for (int u = (DAGATTN_ABL_EX ? 0 : i * NU / NSLOT); u < (DAGATTN_ABL_EX ? 0 : (i + 1) * NU / NSLOT); ++u) {  // two probabilities of one row
+      for (int u = i * NU / NSLOT; u < (i + 1) * NU / NSLOT; ++u) {  // two probabilities of one row
         const int r = u / 8, e = 2 * (u % 8);
         f32x2 p;
         p[0] = __builtin_amdgcn_exp2f(fmaf(Sc[r][e], sc, -msc[r]));
