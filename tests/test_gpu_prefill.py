@@ -120,6 +120,32 @@ def test_prepare_v_then_prepared_attention_equals_the_combined_call():
     check_close(o2[rows], ref[rows], torch.bfloat16, "prepared prefill")
 
 
+def test_repeated_launches_on_one_workspace_hand_out_every_item_once():
+    """The attention kernel hands its work items out through counters in the workspace and leaves
+    them zeroed: three launches in a row after one prepare_v (more items than compute units, so
+    the counters are really used) all give the bits of the first one, which match the oracle; a
+    workspace filled with ones beforehand shows that prepare_v is what zeroes the counters."""
+    from tests.gpu_util import build_meta
+    dag_list = [dags.fork_join(1024, [256] * 6, 320), dags.fork_join(700, [130, 260, 90], 200)]
+    T = int(sum(int(np.sum(L)) for L, _ in dag_list))
+    hq, hkv, d = 32, 8, 128
+    q, k, v = dags.make_qkv(91, T, hq, hkv, d, 0.5, torch.bfloat16)
+    _, meta = build_meta(dag_list, hq, hkv, d, torch.bfloat16)
+    n_items = meta.sizes.total_qtiles * hkv
+    assert n_items > 2 * torch.cuda.get_device_properties(0).multi_processor_count
+    qd, kd, vd = q.to(DEV).clone(), k.to(DEV).clone(), v.to(DEV)
+    B.dag_rope_qk(meta.get("pos_ids"), qd, kd, 5e5)
+    ws = torch.full((B.dag_prefill_workspace_bytes(meta, hkv, d, B.DAG_BF16),), 1, dtype=torch.uint8, device=DEV)
+    B.dag_prefill_prepare_v(meta, vd, hq, workspace=ws)
+    outs = [torch.zeros_like(qd) for _ in range(3)]
+    for o in outs:
+        B.dag_attn_prefill(meta, qd, kd, vd, o, workspace=ws, prepared=True)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    ref, _, rows = oracle_prefill(dag_list, q, k, v, 5e5, rows_per_seq=96, seed=5)
+    check_close(outs[2][rows], ref[rows], torch.bfloat16, "repeated prepared prefill")
+
+
 def test_config5_qwen_shape_full_size_sampled_rows():
     """Benchmark config 5 prefill at full size (2 x 50,176 tokens, 40 query heads in groups of 5):
     sampled rows against the oracle, which gets only those query rows (compact mode)."""
