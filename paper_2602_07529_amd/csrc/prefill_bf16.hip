@@ -171,7 +171,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   unsigned char* const Abase = smem + NSTAGE * (KTILE + VTILE);  // node ids of the keys [NSTAGE][64]
 
   const int G = a.hq / a.hkv;
-  const int HS = G / HG;  // items per (query tile, KV head)
+  const int HS = (G + HG - 1) / HG;  // items per (query tile, KV head); the last one may be partly filled
   const int nhw = a.hkv * HS;
   const long n_items = (long)a.total_qtiles * nhw;
 
@@ -204,7 +204,10 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   };
   auto row_of = [&](const Item& I, int r) { return I.row0 + 32 * (rg * RB + r) + L; };  // row inside the sequence
   auto token_of = [&](const Item& I, int r) { return I.cu + min(row_of(I, r), I.T - 1); };
-  auto head_of = [&](const Item& I) { return I.hk * G + I.hs * HG + hj; };
+  // When G is no multiple of HG the waves beyond the last head of the group repeat that head (they
+  // load valid rows and take part in every barrier) and store nothing.
+  auto head_of = [&](const Item& I) { return I.hk * G + min(I.hs * HG + hj, G - 1); };
+  auto head_is_mine = [&](const Item& I) { return I.hs * HG + hj < G; };
 
   // What this lane fetches in a wave-level load (LDS position 16*lane inside the block):
   //   K:   key (lane / 4) % KPB of the block, chunk 4 * (lane / (4 * KPB)) + lane % 4: four
@@ -760,6 +763,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     // by the row so that writes and reads are conflict free), and stores full rows: 16 lanes x 16
     // bytes per row.
     const int head = head_of(cur);
+    const bool store = head_is_mine(cur);
     if (F == cur.N) {  // no PARTIAL tile: the last P V steps came after the last barrier
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
@@ -773,7 +777,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       for (int r = 0; r < RB; ++r) {
         const float l_tot = l[r] + __shfl_xor(l[r], 32);
         const float inv = 1.f / l_tot;
-        if (a.lse && H == 0 && row_of(cur, r) < cur.T)
+        if (a.lse && store && H == 0 && row_of(cur, r) < cur.T)
           a.lse[(size_t)token_of(cur, r) * a.hq + head] = m[r] * a.scale + logf(l_tot);
 #pragma unroll
         for (int half = 0; half < 2; ++half) {  // rows 16 half .. 16 half + 15 of the block
@@ -796,7 +800,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
             const int rr = k * (64 / CPR) + lane / CPR, c = lane % CPR;
             const u32x4 o = *(const u32x4*)(stage + rr * (D * 2) + ((c ^ rr) % CPR) * 16);
             const int row = cur.row0 + 32 * (rg * RB + r) + 16 * half + rr;
-            if (row < cur.T)
+            if (row < cur.T && store)
               *(u32x4*)((uint16_t*)a.out + ((size_t)(cur.cu + row) * a.hq + head) * D + c * 8) = o;
           }
         }
@@ -891,13 +895,15 @@ int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
 template <int D>
 int launch_d(const PrefillArgs& a, hipStream_t stream) {
   const int g = a.hq / a.hkv;
+  // Eight waves = 2 row blocks x 4 query heads of the KV head; a group size that is no multiple
+  // of 4 pads its last item (5 heads: 4 + 1 of 4), which beats narrower workgroups: a workgroup
+  // has the compute unit to itself whatever its width.
 #ifdef DAGATTN_RB2  // development variant: four waves (one per SIMD), 64 rows each; measured slower so far
   if (g % 4 == 0) return launch_one<D, 4, 2>(a, g / 4, stream);
-#else
-  if (g % 4 == 0) return launch_one<D, 4, 1>(a, g / 4, stream);  // eight waves, 32 rows each
 #endif
-  if (g % 2 == 0) return launch_one<D, 2, 1>(a, g / 2, stream);  // four waves, 32 rows each
-  return launch_one<D, 1, 1>(a, g, stream);                       // two waves
+  if (g >= 3) return launch_one<D, 4, 1>(a, (g + 3) / 4, stream);
+  if (g == 2) return launch_one<D, 2, 1>(a, 1, stream);  // four waves
+  return launch_one<D, 1, 1>(a, 1, stream);              // two waves
 }
 
 }  // namespace

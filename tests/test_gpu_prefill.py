@@ -31,7 +31,8 @@ def test_config1_tiny_fork_join_fp32():
 
 
 @pytest.mark.parametrize("hq,hkv,d", [(4, 1, 128), (8, 2, 64), (5, 1, 128), (2, 1, 128), (6, 3, 64),
-                                      (3, 3, 128), (1, 1, 64), (8, 1, 128), (5, 1, 64)])
+                                      (3, 3, 128), (1, 1, 64), (8, 1, 128), (5, 1, 64), (3, 1, 128), (6, 1, 64),
+                                      (14, 2, 128)])
 def test_bf16_small_dags_every_kernel_variant(hq, hkv, d):
     rng = np.random.Generator(np.random.PCG64(1000 + hq * 10 + d))
     dag_list = [dags.fork_join(100, [37, 64, 5], 70),               # ragged everywhere
