@@ -95,6 +95,15 @@ __device__ __forceinline__ void wait_lgkmcnt(int n) {  // s_waitcnt lgkmcnt(n) o
 
 __device__ __forceinline__ int sgpr(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// f(integral_constant<int, I>) for I = A .. B - 1, each a separate instantiation
+template <int A, int B, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (A < B) {
+    f(std::integral_constant<int, A>{});
+    static_for<A + 1, B>(f);
+  }
+}
+
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {  // byte address inside LDS of a __shared__ pointer
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
@@ -326,6 +335,25 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     return __builtin_amdgcn_ballot_w64(need) != 0;
   };
 
+  // Mask of the key tile whose scores are being computed, for PARTIAL and ragged tiles: bit j of
+  // rmsk[r] says whether this lane's row r may see key j + 8 H of the tile (set by tile_mask in the
+  // item loop); msk_on is wave-uniform and false for the tiles that need no mask.
+  bool msk_on = false;
+  uint64_t rmsk[RB];
+#pragma unroll
+  for (int r = 0; r < RB; ++r) rmsk[r] = 0;
+  auto apply_mask = [&](f32x16* S, int half) {  // masked scores become -inf
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const uint32_t word = half ? (uint32_t)(rmsk[r] >> 32) : (uint32_t)rmsk[r];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {  // this lane's key 32 half + 16 (e / 8) + 8 H + e % 8
+        const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)word, 16 * (e >> 3) + (e & 7), 1);
+        S[r][e] = __uint_as_float((__float_as_uint(S[r][e]) & keep) | (0xff800000u & ~keep));
+      }
+    }
+  };
+
   // ---- one pipeline step, written slot by slot (a scheduling barrier after every slot keeps the
   // order): slot = the LDS read of the operand needed PF slots later, RB MFMAs on one operand,
   // and a share of the step's exponentials.  Pieces (each optional):
@@ -334,8 +362,9 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   //   EX: Pc[r]  = exp2(sc (Sc[r] - m[r]))  probabilities of a half, row sums added to l
   // `extra(slot, slots)` runs in every slot (used to issue the next K/V tile loads piecewise, in
   // the shadow of the MFMAs).
-  // With QK, the row maxima of Sn are taken two slots after the last score MFMA and the return
-  // value says whether they call for a rescale.
+  // With QK, the row maxima of Sn are taken two slots after the last score MFMA (after the mask of
+  // the tile, if it has one, has been applied to Sn) and the return value says whether they call
+  // for a rescale.
   auto step = [&](auto qk_c, auto pv_c, auto ex_c, auto hq_c, auto hv_c, const unsigned char* Kb, f32x16* Sn,
                   const unsigned char* Vb, const bf16x8 (*Pp)[2], const f32x16* Sc, bf16x8 (*Pc)[2], auto&& extra) {
     constexpr bool QK = decltype(qk_c)::value, PV = decltype(pv_c)::value, EX = decltype(ex_c)::value;
@@ -356,31 +385,38 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     // order, so before the MFMA of slot i exactly the reads of the slots after it may be pending
     // (the compiler's own bookkeeping waits for all of them, which exposes the LDS latency).
     const uint32_t kaddr = QK ? lds_addr(Kb) + koff : 0, vaddr = PV ? lds_addr(Vb) + voff : 0;
-    auto fetch = [&](int i) {
-      if (i < NQ)
+    auto fetch = [&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      const uint32_t ka = kaddr, va = vaddr;  // (named here: captures inside discarded branches trip the compiler)
+      bf16x8* const op = opnd;
+      if constexpr (i < NQ)
         asm volatile("ds_read_b128 %0, %1 offset:%2"
-                     : "=v"(opnd[i])
-                     : "v"(kaddr), "n"(HQ * (32 / KPB) * BLKK + (i >> 1) * 64 * KPB + (i & 1) * 32));
-      else
+                     : "=v"(op[i])
+                     : "v"(ka), "n"(HQ * (32 / KPB) * BLKK + (i >> 1) * 64 * KPB + (i & 1) * 32));
+      else if constexpr (i < NSLOT)
         asm volatile("ds_read_b128 %0, %1 offset:%2"
-                     : "=v"(opnd[i])
-                     : "v"(vaddr), "n"(((i - NQ) % DB) * 4 * BLKV + (2 * HV + (i - NQ) / DB) * 256));
+                     : "=v"(op[i])
+                     : "v"(va), "n"(((i - NQ) % DB) * 4 * BLKV + (2 * HV + (i - NQ) / DB) * 256));
     };
-#pragma unroll
-    for (int i = 0; i < PF && i < NSLOT; ++i) fetch(i);
+    static_for<0, (PF < NSLOT ? PF : NSLOT)>(fetch);
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < NSLOT; ++i) {
-      if (i + PF < NSLOT) fetch(i + PF);
+    // (the slots are instantiated one by one, not left to the loop unroller: the immediate offsets
+    // of the reads above have to be compile-time constants whatever `extra` contains)
+    static_for<0, NSLOT>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      fetch(std::integral_constant<int, i + PF>{});
       wait_lgkmcnt(NSLOT - 1 - i < PF ? NSLOT - 1 - i : PF);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r = 0; r < RB; ++r) {
-        if (i < NQ) Sn[r] = mfma32(opnd[i], qf[r][i], i == 0 ? zero : Sn[r]);
+        if (i < NQ) Sn[r] = mfma32(opnd[i], qf[r][i < NQ ? i : 0], i == 0 ? zero : Sn[r]);
         else O[r][(i - NQ) % DB] = mfma32(opnd[i], Pp[r][(i - NQ) / DB], O[r][(i - NQ) % DB]);
       }
       extra(i, NSLOT);
-      if (QK && i == MAXSLOT) need = row_max(Sn);
+      if (QK && i == MAXSLOT) {
+        if (msk_on) apply_mask(Sn, HQ);
+        need = row_max(Sn);
+      }
 #pragma unroll
       for (int u = i * NU / NSLOT; u < (i + 1) * NU / NSLOT; ++u) {  // two probabilities of one row
         const int r = u / 8, e = 2 * (u % 8);
@@ -394,8 +430,11 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
         Pc[r][e >> 3][(e & 7) + 1] = pk[1];
       }
       __builtin_amdgcn_sched_barrier(0);
+    });
+    if (QK && MAXSLOT == NSLOT) {
+      if (msk_on) apply_mask(Sn, HQ);
+      need = row_max(Sn);
     }
-    if (QK && MAXSLOT == NSLOT) need = row_max(Sn);
     if (EX) {
 #pragma unroll
       for (int r = 0; r < RB; ++r) l[r] += rs[r];
@@ -427,25 +466,6 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     }
   };
   // probabilities of a half whose scores are in S (relative to the running maxima)
-  auto exp_half = [&](const f32x16* S, bf16x8 (*P)[2]) {
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      const float msc = m[r] * sc;
-      float rowsum = 0.f;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        f32x8 p;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          p[e] = __builtin_amdgcn_exp2f(fmaf(S[r][8 * j + e], sc, -msc));
-          rowsum += p[e];
-        }
-        P[r][j] = __builtin_convertvector(p, bf16x8);
-      }
-      l[r] += rowsum;
-    }
-  };
-
   // ---------------------------------------------------------------- persistent loop over items
   // (the launch has at most one workgroup per item, so the first item always exists)
   Item cur = load_item(my_rank);
@@ -534,10 +554,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
-  auto refill = [&]() {  // after sync_next: one more tile into the slot that became free
-    if (ti - tc < NSTAGE - 1) try_issue();
-  };
-  // The same, spread over the slots of a pipeline step with NS slots (slot 1: set-up, the slots
+  // One more tile into the slot that a sync_next has freed, spread over the slots of a pipeline step with NS slots (slot 1: set-up, the slots
   // after it: the loads), so that the scalar work and the load issue hide behind the MFMAs.
   // The texture path takes a 1 KiB load every 16 cycles at best, so the loads are spaced out: the
   // K loads over the first step of a tile, the V^T loads over the second.
@@ -557,10 +574,6 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       for (int x = 0; x < IPV; ++x)
         if (x * NS / IPV == i) issue_part(IPK + x);
     }
-  };
-  auto advance = [&]() {
-    sync_next();
-    refill();
   };
 
 #pragma unroll 1
@@ -595,6 +608,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     }
     asm volatile("" ::"v"(col_iss), "v"(col_nxt));
     TCOUNT(11);
+    TSTAMP(t_top);
     if (grabber && has_next && lane == 0)  // the item after `nxt`; the answer is needed at the end of this item only
       grabbed = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
@@ -608,65 +622,12 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     const h1_t H1;
     const bf16x8 (*const nop)[2] = nullptr;
 
-    TSTAMP(t_item0);
-    if (F > 0) {
-      // ---- FULL tiles: software pipeline in steps of half a tile
-      if (step(Y, N_, N_, H0, H0, Kt(tc), SA, nullptr, nop, nullptr, nullptr, nothing)) rescale();
-      bool need = step(Y, N_, Y, H1, H0, Kt(tc), SB, nullptr, nop, SA, P0, nothing);
-      TSTAMP(t_a);
-      TACC(0, t_item0, t_a);
-#pragma unroll 1
-      for (int n = 0; n + 1 < F; ++n) {
-        TSTAMP(t0);
-        sync_next();  // tile tc - 1 is the one in flight through the pipeline, tc the new one
-        TSTAMP(t1);
-        if (need) rescale();
-#ifdef DAGATTN_TIMING
-        need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, [&](int i, int NS) {
-          if (i == NS / 2) t_mid = __builtin_amdgcn_s_memrealtime();
-          refill_slot(i, NS);
-        });
-        TACC(9, t1, t_mid);
-#else
-        need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, refill_slot);
-#endif
-        TSTAMP(t2);
-        if (need) rescale();
-#ifdef DAGATTN_TIMING
-        need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, [&](int i, int NS) {
-          if (i == NS / 2) t_mid = __builtin_amdgcn_s_memrealtime();
-          refill_slot_v(i, NS);
-        });
-        TACC(10, t2, t_mid);
-#else
-        need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, refill_slot_v);
-#endif
-        TSTAMP(t3);
-        TACC(1, t0, t1);
-        TACC(2, t1, t2);
-        TACC(3, t2, t3);
-        TCOUNT(7);
-      }
-      TSTAMP(t_b);
-      sync_next();
-      if (need) rescale();
-      step(N_, Y, Y, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill_slot);
-      step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc - 1), P1, nullptr, nullptr, refill_slot_v);
-      TSTAMP(t_c);
-      TACC(4, t_b, t_c);
-    }
-    TSTAMP(t_p0);
-
-    // ---- PARTIAL tiles (and a ragged last tile): per-token mask, plain loop.  The mask of a row
-    // is built as a 64-bit word over the keys of the tile: the key tile is cut into its node
-    // segments (node ids come with the tile, through the ring) and each segment is switched on
-    // for the rows whose node sees the segment's node (Eq. 3); the causal / length limit is one
-    // more AND.
-    auto partial_tile = [&](int n, auto last_c) {
-      constexpr bool LAST = decltype(last_c)::value;
-      step(Y, N_, N_, H0, H0, Kt(tc), SA, nullptr, nop, nullptr, nullptr, nothing);
-      step(Y, N_, N_, H1, H0, Kt(tc), SB, nullptr, nop, nullptr, nullptr, nothing);
-      if (LAST && has_next) load_q(nxt);  // the Q registers are free from here on
+    // ---- PARTIAL tiles (and a ragged last tile) carry a per-token mask.  The mask of a row is built
+    // as a 64-bit word over the keys of the tile: the key tile is cut into its node segments (node
+    // ids come with the tile, through the ring) and each segment is switched on for the rows whose
+    // node sees the segment's node (Eq. 3); the causal / length limit is one more AND.  Called
+    // when tile n of the row (ring tile tc) has become visible, before its scores are masked.
+    auto tile_mask = [&](int n) {
       int kt;
       const int32_t* cp = a.col + sgpr(cur.c0 + n);
       asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(kt) : "s"(cp) : "memory");
@@ -704,70 +665,80 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       for (int r = 0; r < RB; ++r) {
         const int cnt = min(row_of(cur, r), cur.T - 1) - j0 + 1;  // keys j0 .. j0 + cnt - 1 are not in the future
         const uint64_t lim = cnt >= 64 ? ~0ull : (cnt <= 0 ? 0ull : ((1ull << cnt) - 1));
-        const uint64_t rm = (rowmask[r] & lim) >> (8 * H);
-        const uint32_t half[2] = {(uint32_t)rm, (uint32_t)(rm >> 32)};
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {  // this lane's key 32 kb + 16 (e / 8) + 8 H + e % 8
-            const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)half[kb], 16 * (e >> 3) + (e & 7), 1);
-            const float x = kb == 0 ? SA[r][e] : SB[r][e];
-            const float y = __uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep));
-            if (kb == 0) SA[r][e] = y;
-            else SB[r][e] = y;
-          }
+        rmsk[r] = (rowmask[r] & lim) >> (8 * H);
       }
-      const bool na = row_max(SA);
-      if (na) rescale();
-      if (row_max(SB)) rescale();
-      exp_half(SA, P0);
-      exp_half(SB, P1);
-      if (LAST && has_next) {  // row data of the next item (its node ids were loaded an item ago)
-#pragma unroll
-        for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
-      }
-      step(N_, Y, N_, H0, H0, nullptr, nullptr, Vt(tc), P0, nullptr, nullptr, nothing);
-      step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc), P1, nullptr, nullptr, nothing);
-      advance();
     };
+
+    // ---- every tile of the row goes through the software pipeline, in steps of half a tile;
+    // the CSR row lists the tiles that need no mask first (F of them)
+    // The mask of a tile is needed only after the score MFMAs of its first half, so it is built
+    // inside that step, in the shadow of the MFMAs, and the two waves of a SIMD do it in different
+    // slots (while one builds its mask the other one keeps the matrix pipe busy).
+    const int NT = cur.N;
+    int mask_n = 0;
+    const int mask_slot = w < NW / 2 ? KSTEPS - 2 : 0;  // (a slot of the score part: the first tile's step has no other)
+    auto first_half_extra = [&](int i, int NS) {
+      if (msk_on && i == mask_slot) tile_mask(mask_n);
+      refill_slot(i, NS);
+    };
+    auto first_tile_extra = [&](int i, int) {
+      if (msk_on && i == mask_slot) tile_mask(0);
+    };
+    msk_on = F == 0;
+    if (step(Y, N_, N_, H0, H0, Kt(tc), SA, nullptr, nop, nullptr, nullptr, first_tile_extra)) rescale();
+    bool need = step(Y, N_, Y, H1, H0, Kt(tc), SB, nullptr, nop, SA, P0, nothing);
+    TSTAMP(t_first);
+    TACC(0, t_top, t_first);
 #pragma unroll 1
-    for (int n = F; n + 1 < cur.N; ++n) partial_tile(n, no_t());
+    for (int n = 0; n + 1 < NT; ++n) {
+      sync_next();  // tile tc - 1 is the one in flight through the pipeline, tc the new one
+      msk_on = n + 1 >= F;
+      mask_n = n + 1;
+      if (need) rescale();
+      need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, first_half_extra);
+      if (need) rescale();
+      need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, refill_slot_v);
+      TCOUNT(7);
+    }
+    msk_on = false;
+    TSTAMP(t_loop);
+    TACC(2, t_first, t_loop);
     // The item after `nxt`: the last wave publishes what the counter gave it (-1: the list is
-    // exhausted).  Done in front of the item's last tile: the barrier that ends that tile (or the
-    // one in front of the output when there is none) makes it visible, and a wait on the answer
-    // placed later would also wait for the next item's Q rows or for the output stores.  Two
-    // slots, used in turn: a wave may still have to read the one written an item ago.
+    // exhausted).  Done here, in front of the item's last two barriers, which make it visible: a
+    // wait on the answer placed later would also wait for the next item's Q rows or for the
+    // output stores.  Two slots, used in turn: a wave may still have to read the one written an
+    // item ago.
     if (grabber && has_next) {
       asm volatile("" ::"v"(grabbed));  // the wait for the counter's answer belongs here
       const long g = 2L * nb + __builtin_amdgcn_readfirstlane(grabbed);
       const int v = g < n_list ? (int)g : -1;
       asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" ::"v"(lds_addr(mbox + mslot)), "v"(v) : "memory");
     }
-    if (F < cur.N) {
-      partial_tile(cur.N - 1, yes_t());
-    } else if (has_next) {
-      // No PARTIAL tile (cannot happen with 64 x 64 tiles, whose diagonal tile is never FULL):
-      // fetch the next item's rows here.  Placed after the loop above on purpose: a load of the Q
-      // registers in front of it would make the compiler wait for everything in flight there.
+    // The last scores of the item are done: the Q registers and the mask words are free for the
+    // next item's rows (its node ids were loaded an item ago).  Placed after the loop above on
+    // purpose: a load of the Q registers in front of it would make the compiler wait for
+    // everything in flight there.
+    if (has_next) {
       load_q(nxt);
 #pragma unroll
       for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
     }
-
+    sync_next();
+    if (need) rescale();
+    step(N_, Y, Y, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill_slot);
+    step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc - 1), P1, nullptr, nullptr, refill_slot_v);
     TSTAMP(t_p1);
-    TACC(5, t_p0, t_p1);
+    TACC(4, t_loop, t_p1);
     // ---- output.  A lane holds one row in 8-byte pieces scattered over the head dimension;
     // stored like that, every store instruction would touch 32 rows.  The wave transposes its
     // rows through a private 4 KiB piece of the ring slot of the tile that was finished last
-    // (free since the barrier of the last advance; 16 rows at a time, 16-byte chunks XOR-swizzled
+    // (free after the barrier below: the last P V steps read it; 16 rows at a time, 16-byte chunks XOR-swizzled
     // by the row so that writes and reads are conflict free), and stores full rows: 16 lanes x 16
     // bytes per row.
     const int head = head_of(cur);
     const bool store = head_is_mine(cur);
-    if (F == cur.N) {  // no PARTIAL tile: the last P V steps came after the last barrier
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     {
       constexpr int CPR = D / 8;  // 16-byte chunks per row
       unsigned char* stage = (w < NW / 2 || NW == 1 ? Kbase + ((tc - 1) % NSTAGE) * KTILE
@@ -830,6 +801,8 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
 #pragma unroll 1
     while (ti - tc < NSTAGE - 1 && try_issue()) {
     }
+    TSTAMP(t_sw);
+    TACC(5, t_o, t_sw);
   }
   // Every answer from the counters has arrived by now (each was waited for at the end of its
   // item), so this workgroup's requests were served before it reports itself done, and the
@@ -868,8 +841,8 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
 #ifdef DAGATTN_TIMING
   if (blockIdx.x == 0 && lane == 0) {
     const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
-    printf("wave %d total %llu | prologue %llu sync %llu stepA %llu stepB %llu epi %llu partial %llu out %llu | pipelined tiles %llu vmwait %llu A1 %llu B1 %llu (x10ns)\n",
-           w, t_end - t_begin, tacc[0], tacc[1], tacc[2], tacc[3], tacc[4], tacc[5], tacc[6], tacc[7], tacc[8], tacc[9], tacc[10]);
+    printf("wave %d total %llu | first tile %llu tile loop %llu last tile + epilogue %llu out %llu switch %llu | tiles in the loop %llu items %llu load waits %llu (x10ns)\n",
+           w, t_end - t_begin, tacc[0], tacc[2], tacc[4], tacc[6], tacc[5], tacc[7], tacc[11], tacc[8]);
   }
 #endif
 }
