@@ -21,6 +21,8 @@
 // B-operand layout of the second (O^T = V^T P^T).
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -47,7 +49,9 @@ struct DecodeArgs {
   int rb_max;        // 32-row blocks per (group, kv head)
   int chunk_a, splits_a, chunk_b, splits_b;
   int items_a, items_b;
+  int item_base;     // first work item of this launch (k_decode)
   float sc;          // softmax_scale * log2(e)
+  float th;          // 8 / sc: how far a score may exceed the reference maximum before it is raised
   float scale;
 };
 
@@ -90,17 +94,17 @@ __device__ __forceinline__ void load_block(KVBlock<D>& blk, const DecodeArgs& a,
   }
 }
 
-// qs: the query operands of the item in LDS, qs[s * 64 + lane] (they are needed once per 32-key
-// block; keeping them out of the register file lets two waves share a SIMD, which doubles the
-// bytes in flight)
-template <int D>
-__device__ __forceinline__ void compute_block(const KVBlock<D>& blk, const bf16x8* qs, f32x16* O, float& m, float& l,
-                                              float sc, int key0, int len, int H) {
+// qop(s): the query operand of MFMA step s.  k_decode keeps the operands in LDS, qs[s * 64 + lane]
+// (they are needed once per 32-key block; keeping them out of the register file lets two waves
+// share a SIMD, which doubles the bytes in flight); k_decode_wide keeps them in registers.
+template <int D, typename QF>
+__device__ __forceinline__ void compute_block(const KVBlock<D>& blk, QF&& qop, f32x16* O, float& m, float& l,
+                                              float sc, float th, int key0, int len, int H) {
   f32x16 S;
 #pragma unroll
   for (int r = 0; r < 16; ++r) S[r] = 0.f;
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) S = mfma32(blk.k[s], qs[s * 64], S);
+  for (int s = 0; s < D / 16; ++s) S = mfma32(blk.k[s], qop(s), S);
   if (key0 + 32 > len) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -112,10 +116,20 @@ __device__ __forceinline__ void compute_block(const KVBlock<D>& blk, const bf16x
 #pragma unroll
   for (int r = 1; r < 16; ++r) bm = fmaxf(bm, S[r]);
   bm = fmaxf(bm, __shfl_xor(bm, 32));
-  const float m_new = fmaxf(m, bm);
-  const float alpha = __builtin_amdgcn_exp2f((m - m_new) * sc);
-  const float msc = m_new * sc;
-  m = m_new;
+  // The reference maximum m is raised only when some row of the wave exceeds it by more than 2^8
+  // (in the exponent's units); the rescale of the accumulators is then rare, and probabilities up
+  // to 2^8 are absorbed exactly by fp32 accumulation and the final division.
+  if (__builtin_amdgcn_ballot_w64(bm > m + th) != 0) {
+    const float m_new = fmaxf(m, bm);
+    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * sc);
+    m = m_new;
+    l *= alpha;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) O[db][r] *= alpha;
+  }
+  const float msc = m * sc;
   f32x8 p0, p1;
   float rowsum = 0.f;
 #pragma unroll
@@ -124,13 +138,11 @@ __device__ __forceinline__ void compute_block(const KVBlock<D>& blk, const bf16x
     p1[r] = __builtin_amdgcn_exp2f(fmaf(S[8 + r], sc, -msc));
     rowsum += p0[r] + p1[r];
   }
-  l = l * alpha + rowsum;
+  l += rowsum;
   const bf16x8 pb0 = __builtin_convertvector(p0, bf16x8);
   const bf16x8 pb1 = __builtin_convertvector(p1, bf16x8);
 #pragma unroll
   for (int db = 0; db < D / 32; ++db) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) O[db][r] *= alpha;
     O[db] = mfma32(blk.v[0][db], pb0, O[db]);
     O[db] = mfma32(blk.v[1][db], pb1, O[db]);
   }
@@ -139,7 +151,7 @@ __device__ __forceinline__ void compute_block(const KVBlock<D>& blk, const bf16x
 template <int D>
 __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
   __shared__ bf16x8 qs_all[(D / 16) * 64];
-  const int item = blockIdx.x;
+  const int item = blockIdx.x + a.item_base;
   const int lane = threadIdx.x, L = lane & 31, H = lane >> 5;
   const bool is_a = item < a.items_a;
   int hk, split, chunk, len, nrows, row0, branch0;
@@ -197,6 +209,7 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) qs_all[s * 64 + lane] = *(const bf16x8*)(qp + 16 * s);
   }
+  auto qop = [&](int s) { return qf[s * 64]; };
   const int kr = key_of_row(L);
   const int kpage_sel = kr >> 4, kslot = kr & 15;
 
@@ -219,16 +232,180 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
       if (((pb + 2) & 63) == 0) pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
       load_block<D>(b1, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
     }
-    compute_block<D>(b0, qf, O, m, l, a.sc, (p0 + pb) * PAGE, len, H);
+    compute_block<D>(b0, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
     pb += 2;
     if (pb >= np) break;
     if (pb + 2 < np) {
       if (((pb + 2) & 63) == 0) pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
       load_block<D>(b0, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
     }
-    compute_block<D>(b1, qf, O, m, l, a.sc, (p0 + pb) * PAGE, len, H);
+    compute_block<D>(b1, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
     pb += 2;
     if (pb >= np) break;
+  }
+
+  const float l_tot = l + __shfl_xor(l, 32);
+  if (row_ok) {
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 o = {O[db][4 * r4], O[db][4 * r4 + 1], O[db][4 * r4 + 2], O[db][4 * r4 + 3]};
+        *(f32x4*)(po + 32 * db + 8 * r4 + 4 * H) = o;
+      }
+    if (H == 0) {
+      pml[0] = m;
+      pml[1] = l_tot;
+    }
+  }
+}
+
+// Shared items of wide sibling groups (more than 32 stacked query rows per KV head, e.g. 32 siblings
+// x 5 query heads): one workgroup per (group, kv head, page split) with one wave per 32-row
+// block.  The waves share the K/V blocks through a ring in LDS (global -> LDS directly, 16 bytes
+// per lane; a page of the pools is already the operand image), so the shared pages are streamed
+// once per group whatever the number of rows, and RING - 1 blocks are in flight per workgroup
+// instead of one per wave.  Writes the same partials as the shared items of k_decode.
+constexpr int WIDE_RING = 8;                    // 32-key blocks in the ring
+constexpr int WIDE_MAX_WAVES = 8;
+template <int D>
+constexpr int wide_block_bytes() { return 4 * PAGE * D * 2; }  // K and V of two pages
+
+__device__ __forceinline__ void wait_vmcnt_dyn(int n) {  // s_waitcnt vmcnt(n), n <= 56, wave-uniform
+  // vmcnt is split over bits 3:0 and 15:14 of the immediate (gfx9 encoding)
+  switch (n >> 2) {
+#define DAG_VM_CASE(q)                                                                         \
+  case q:                                                                                       \
+    switch (n & 3) {                                                                            \
+      case 0: __builtin_amdgcn_s_waitcnt(0x0F70 | ((4 * q + 0) & 15) | (((4 * q + 0) >> 4) << 14)); break; \
+      case 1: __builtin_amdgcn_s_waitcnt(0x0F70 | ((4 * q + 1) & 15) | (((4 * q + 1) >> 4) << 14)); break; \
+      case 2: __builtin_amdgcn_s_waitcnt(0x0F70 | ((4 * q + 2) & 15) | (((4 * q + 2) >> 4) << 14)); break; \
+      default: __builtin_amdgcn_s_waitcnt(0x0F70 | ((4 * q + 3) & 15) | (((4 * q + 3) >> 4) << 14)); break; \
+    }                                                                                           \
+    break;
+    DAG_VM_CASE(0) DAG_VM_CASE(1) DAG_VM_CASE(2) DAG_VM_CASE(3) DAG_VM_CASE(4) DAG_VM_CASE(5) DAG_VM_CASE(6)
+    DAG_VM_CASE(7) DAG_VM_CASE(8) DAG_VM_CASE(9) DAG_VM_CASE(10) DAG_VM_CASE(11) DAG_VM_CASE(12) DAG_VM_CASE(13)
+#undef DAG_VM_CASE
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;  // vmcnt(0)
+  }
+}
+
+template <int D>
+__global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
+  constexpr int BB = wide_block_bytes<D>();       // bytes of a block in the ring: K page 0, K page 1, V page 0, V page 1
+  constexpr int PB = PAGE * D * 2;                // bytes of one page of one kv head in a pool
+  constexpr int LOADS = BB / 1024;                // wave-level loads per block
+  const int nw = blockDim.x >> 6;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int L = lane & 31, H = lane >> 5;
+  int x = blockIdx.x;
+  const int split = x % a.splits_a; x /= a.splits_a;
+  const int hk = x % a.hkv;
+  const int g = x / a.hkv;
+  const int branch0 = a.group_branch_off[g];
+  const int nrows = (a.group_branch_off[g + 1] - branch0) * a.G;
+  const int32_t* pages = a.shared_pages + a.shared_page_off[g];
+  const int len = a.shared_len[g];
+  const int npages = (len + PAGE - 1) / PAGE;
+  const int p0 = split * a.chunk_a, p1 = min(p0 + a.chunk_a, npages);
+  const int row = 32 * w + L;
+  const bool row_ok = row < nrows;
+  const size_t item = (((size_t)g * a.hkv + hk) * a.rb_max + w) * a.splits_a + split;
+  float* po = a.part_o_a + (item * 32 + L) * D;
+  float* pml = a.part_ml_a + (item * 32 + L) * 2;
+  if (p0 >= p1) {  // empty slice (the same for every wave of the workgroup): neutral partials
+    if (row_ok && H == 0) {
+      pml[0] = -1e30f;
+      pml[1] = 0.f;
+    }
+    return;
+  }
+
+  bf16x8 qreg[D / 16];
+  {
+    const int rr = row_ok ? row : 0;
+    const int br = branch0 + rr / a.G, head = hk * a.G + rr % a.G;
+    const uint16_t* qp = a.q + ((size_t)br * a.hq + head) * D + 8 * H;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) qreg[s] = *(const bf16x8*)(qp + 16 * s);
+  }
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(qreg[s]));  // arrived: no other load of this wave returns into registers
+
+  // Loads of a block: piece j (0 .. LOADS - 1) = 1 KiB number j % (LOADS / 4) of {K page 0, K page 1,
+  // V page 0, V page 1}[j / (LOADS / 4)]; wave w issues the pieces w, w + nw, ...  Every wave
+  // issues the same number of loads per block (the last ones of some waves repeat a piece), so
+  // that the number of loads a wave may leave in flight is the same for all.
+  const int lpw = (LOADS + nw - 1) / nw;
+  const int np = p1 - p0, nblk = (np + 1) / 2;
+  int pgv = pages[p0 + min(lane, np - 1)];  // page ids, a 64-page window per register (as in k_decode)
+  asm volatile("" ::"v"(pgv));             // arrived (a wait for it inside the loops would drain the ring's loads)
+  int pgv_first = 0;                        // first page (relative) of the window in pgv
+  auto issue_block = [&](int b) {
+    const int pr = 2 * b;
+    if (pr - pgv_first >= 64) {  // next window (blocks are issued in order)
+      pgv_first += 64;
+      pgv = pages[p0 + min(pgv_first + lane, np - 1)];
+      asm volatile("" ::"v"(pgv));
+    }
+    const int pg0 = __builtin_amdgcn_readlane(pgv, (pr - pgv_first) & 63);
+    const int pg1 = __builtin_amdgcn_readlane(pgv, (min(pr + 1, np - 1) - pgv_first) & 63);
+    const size_t base0 = ((size_t)pg0 * a.hkv + hk) * (size_t)PB, base1 = ((size_t)pg1 * a.hkv + hk) * (size_t)PB;
+    unsigned char* slot = ring + (b % WIDE_RING) * BB;
+    for (int i = 0; i < lpw; ++i) {
+      const int j = min(w + i * nw, LOADS - 1);
+      const int part = j / (LOADS / 4), piece = j % (LOADS / 4);
+      const unsigned char* src = (const unsigned char*)(part < 2 ? a.k_pool : a.v_pool) + ((part & 1) ? base1 : base0) +
+                                 piece * 1024 + lane * 16;
+      __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) const void*)src,
+                                       (__attribute__((address_space(3))) void*)(slot + j * 1024), 16, 0, 0);
+    }
+  };
+
+  const int kr = key_of_row(L);
+  // operand addresses inside a block: K[s] = chunk 2 s + H of key pi(L); V[page][db] = keys 8 H .. of dimension 32 db + L
+  const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;
+  const uint32_t koff = (kr >> 4) * PB + H * (PAGE * 16) + (kr & 15) * 16;
+  const uint32_t voff = 2 * PB + L * (PAGE * 2) + H * 16;
+
+  f32x16 O[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
+  float m = -1e30f, l = 0.f;
+  auto qop = [&](int s) { return qreg[s]; };
+
+  int issued = 0;
+  for (; issued < nblk && issued < WIDE_RING - 1; ++issued) issue_block(issued);
+  for (int b = 0; b < nblk; ++b) {
+    // this wave's loads of block b have landed when at most the loads of the blocks after it are in flight
+    wait_vmcnt_dyn((issued - 1 - b) * lpw);
+    __builtin_amdgcn_s_barrier();  // block b is complete; every wave has finished block b - 1
+    asm volatile("" ::: "memory");
+    KVBlock<D> blk;
+    const uint32_t sb = ring0 + (b % WIDE_RING) * BB;
+    // (inline assembly: for plain LDS reads the compiler would first wait for every global-to-LDS
+    // load in flight)
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(blk.k[s]) : "v"(sb + koff), "n"(s * 2 * PAGE * 16));
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(blk.v[0][db]) : "v"(sb + voff), "n"(db * 32 * PAGE * 2));
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(blk.v[1][db]) : "v"(sb + voff), "n"(PB + db * 32 * PAGE * 2));
+    }
+    if (issued < nblk) {  // the next loads, into the slot of block b - 1, while the operand reads are under way
+      issue_block(issued);
+      ++issued;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(blk.k[s]));
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) asm volatile("" : "+v"(blk.v[0][db]), "+v"(blk.v[1][db]));
+    compute_block<D>(blk, qop, O, m, l, a.sc, a.th, (p0 + 2 * b) * PAGE, len, H);
   }
 
   const float l_tot = l + __shfl_xor(l, 32);
@@ -327,6 +504,7 @@ __global__ void __launch_bounds__(256) k_kv_append(const int32_t* branch_page_of
 
 struct DecodePlan {
   int rb_max, chunk_a, splits_a, chunk_b, splits_b, items_a, items_b;
+  bool wide;  // shared items by k_decode_wide (one workgroup per group, kv head and split)
   size_t off_o_a, off_ml_a, off_o_b, off_ml_b, bytes;
 };
 
@@ -355,8 +533,13 @@ int make_plan(const dag_decode_desc_t* d, int hq, int hkv, int D, DecodePlan* p)
   int ca = env_int("DAGATTN_DECODE_CHUNK_A", 128), cb = env_int("DAGATTN_DECODE_CHUNK_B", 64);
   ca += ca & 1;
   cb += cb & 1;
-  if (!getenv("DAGATTN_DECODE_CHUNK_A"))
-    while (ca > 8 && base_a * dag_ceil_div(d->max_shared_pages, ca) < 512) ca /= 2;
+  p->wide = p->rb_max >= 2 && p->rb_max <= WIDE_MAX_WAVES;
+  if (!getenv("DAGATTN_DECODE_CHUNK_A")) {
+    if (p->wide)  // about one workgroup per compute unit
+      while (ca > 8 && (int64_t)d->n_groups * hkv * dag_ceil_div(d->max_shared_pages, ca) < 256) ca /= 2;
+    else
+      while (ca > 8 && base_a * dag_ceil_div(d->max_shared_pages, ca) < 512) ca /= 2;
+  }
   if (!getenv("DAGATTN_DECODE_CHUNK_B"))
     while (cb > 4 && base_b * dag_ceil_div(d->max_branch_pages, cb) < 1024) cb /= 2;
   p->chunk_a = ca;
@@ -374,6 +557,33 @@ int make_plan(const dag_decode_desc_t* d, int hq, int hkv, int D, DecodePlan* p)
   p->off_ml_b = off; off += dag_align_up((size_t)ib * G * 2 * 4, 256);
   p->bytes = off + 256;
   return DAG_OK;
+}
+
+// A second stream per device, created at the first decode call that needs it and kept until the
+// process ends, with the two events of the fork/join.  Calls on one device share it; they are
+// ordered by the caller's streams through the events.
+struct SideStream {
+  hipStream_t stream;
+  hipEvent_t fork, join;
+};
+SideStream* side_stream() {
+  constexpr int MAX_DEV = 64;
+  static SideStream table[MAX_DEV];
+  static bool ready[MAX_DEV];
+  static std::mutex mu;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ready[dev]) {
+    SideStream t;
+    if (hipStreamCreateWithFlags(&t.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&t.join, hipEventDisableTiming) != hipSuccess)
+      return nullptr;
+    table[dev] = t;
+    ready[dev] = true;
+  }
+  return &table[dev];
 }
 
 }  // namespace
@@ -449,18 +659,52 @@ extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const 
   a.items_b = p.items_b;
   a.scale = softmax_scale;
   a.sc = softmax_scale * 1.4426950408889634f;
+  a.th = 8.f / a.sc;
   hipStream_t stream = (hipStream_t)stream_;
-  const unsigned items = (unsigned)(p.items_a + p.items_b);
   const unsigned nout = (unsigned)(d->n_live * hq);
-  if (head_dim == 128) {
-    hipLaunchKernelGGL(k_decode<128>, dim3(items), dim3(64), 0, stream, a);
+  a.item_base = 0;
+  unsigned items = (unsigned)(p.items_a + p.items_b);
+  SideStream* side = nullptr;
+  if (p.wide && p.items_a > 0) {
+    // Wide sibling groups: the shared items as workgroups of rb_max waves that stream the shared
+    // pages once.  The own items (single waves, next launch) fit beside them on the compute
+    // units, so they run on a second stream of the library, forked from and joined to the
+    // caller's stream with events (default priority; the pattern can be captured into a graph).
+    const unsigned groups = (unsigned)(d->n_groups * hkv * p.splits_a);
+    const unsigned threads = 64u * (unsigned)p.rb_max;
+    if (p.items_b > 0) {
+      side = side_stream();
+      if (!side) return DAG_ERR_HIP;
+      DAG_HIP_CHECK(hipEventRecord(side->fork, stream));
+      DAG_HIP_CHECK(hipStreamWaitEvent(side->stream, side->fork, 0));
+    }
+    if (head_dim == 128) {
+      const int sm = WIDE_RING * wide_block_bytes<128>();
+      if (hipFuncSetAttribute((const void*)k_decode_wide<128>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
+        return DAG_ERR_HIP;
+      hipLaunchKernelGGL(k_decode_wide<128>, dim3(groups), dim3(threads), sm, stream, a);
+    } else {
+      const int sm = WIDE_RING * wide_block_bytes<64>();
+      if (hipFuncSetAttribute((const void*)k_decode_wide<64>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
+        return DAG_ERR_HIP;
+      hipLaunchKernelGGL(k_decode_wide<64>, dim3(groups), dim3(threads), sm, stream, a);
+    }
     DAG_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_decode_merge<128>, dim3(nout), dim3(64), 0, stream, a);
-  } else {
-    hipLaunchKernelGGL(k_decode<64>, dim3(items), dim3(64), 0, stream, a);
-    DAG_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_decode_merge<64>, dim3(nout), dim3(64), 0, stream, a);
+    a.item_base = p.items_a;
+    items = (unsigned)p.items_b;
   }
+  hipStream_t s_items = side ? side->stream : stream;
+  if (items > 0) {
+    if (head_dim == 128) hipLaunchKernelGGL(k_decode<128>, dim3(items), dim3(64), 0, s_items, a);
+    else hipLaunchKernelGGL(k_decode<64>, dim3(items), dim3(64), 0, s_items, a);
+    DAG_LAUNCH_CHECK();
+  }
+  if (side) {
+    DAG_HIP_CHECK(hipEventRecord(side->join, side->stream));
+    DAG_HIP_CHECK(hipStreamWaitEvent(stream, side->join, 0));
+  }
+  if (head_dim == 128) hipLaunchKernelGGL(k_decode_merge<128>, dim3(nout), dim3(64), 0, stream, a);
+  else hipLaunchKernelGGL(k_decode_merge<64>, dim3(nout), dim3(64), 0, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
