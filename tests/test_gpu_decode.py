@@ -37,6 +37,8 @@ def _oracle_pools_after_append(st, theta):
     (10, 2, 128, 7, 48, [1, 2, 3, 16, 17, 31, 33]),   # G = 5; 35 rows -> two row blocks
     (4, 4, 64, 2, 0, [40, 9]),               # no shared context at all, MHA, D = 64
     (16, 2, 128, 1, 33, [1]),                # a single branch whose own context is just its token
+    (12, 2, 64, 9, 200, [3, 40, 16, 1, 7, 64, 33, 2, 20]),   # G = 6; 54 rows -> two row blocks, D = 64
+    (24, 2, 128, 11, 77, [5] * 11),          # G = 12; 132 rows -> five row blocks, the last one partly filled
 ])
 def test_decode_small_cases_all_branches(hq, hkv, d, nb, shared, blens):
     st = dags.decode_state(500 + hq + nb, n_seqs=2, n_branches=nb, shared_len=shared, branch_len=0,
@@ -50,6 +52,21 @@ def test_decode_small_cases_all_branches(hq, hkv, d, nb, shared, blens):
     # attention: the oracle reads the GPU-written pools so that only the attention is compared
     ref = orc.attn_decode(st["desc"], dags.to_f64(st["q"]), dags.to_f64(kp), dags.to_f64(vp))
     check_close(out, ref, torch.bfloat16, "decode out")
+
+
+@pytest.mark.parametrize("hq,hkv,nb", [(8, 2, 3), (10, 2, 8)])
+def test_decode_long_slices_cross_the_page_id_window(monkeypatch, hq, hkv, nb):
+    """Slices of more than 64 pages (forced through the development knobs; the default plan cuts a
+    small batch into short slices): the kernels fetch page ids 64 at a time, here they have to
+    move on to a second and a third window.  Narrow group (12 rows) and wide group (40 rows)."""
+    monkeypatch.setenv("DAGATTN_DECODE_CHUNK_A", "200")
+    monkeypatch.setenv("DAGATTN_DECODE_CHUNK_B", "200")
+    d, theta = 128, 5e5
+    st = dags.decode_state(900 + hq, n_seqs=1, n_branches=nb, shared_len=150 * 16 + 5, branch_len=70 * 16 + 3,
+                           hq=hq, hkv=hkv, d=d)
+    out, kp, vp = _gpu_decode(st, hq, hkv, d, theta)
+    ref = orc.attn_decode(st["desc"], dags.to_f64(st["q"]), dags.to_f64(kp), dags.to_f64(vp))
+    check_close(out, ref, torch.bfloat16, "decode out, long slices")
 
 
 def test_decode_config3_full_size_sampled_branches():
