@@ -210,7 +210,11 @@ size_t dag_decode_workspace_bytes(const dag_decode_desc_t* desc, int32_t hq, int
  * other than membership.  The shared pages of a group are streamed once for all its siblings
  * (section 4.3 Fork), own pages once per branch, and the partial results are combined by
  * log-sum-exp.  q/out [n_live][hq][head_dim] bf16 DEVICE, q already rotated.  head_dim 128 or
- * 64, page_size 16, hq a multiple of hkv with hq/hkv <= 32. */
+ * 64, page_size 16, hq a multiple of hkv with hq/hkv <= 32.
+ * Everything is ordered on `stream`.  When a sibling group stacks more than 32 query rows per KV
+ * head (siblings x hq/hkv), part of the work runs on a second stream that the library creates
+ * once per device at the first such call (default priority, kept until the process ends) and
+ * that is forked from and joined to `stream` with events; the call itself allocates no memory. */
 int dag_attn_decode(const dag_decode_desc_t* desc, const void* q, const void* k_pool,
                     const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
                     float softmax_scale, void* ws, size_t ws_bytes, void* stream);
