@@ -473,26 +473,32 @@ __global__ void __launch_bounds__(64) k_decode_merge(DecodeArgs a) {
 }
 
 // One block per live branch: rotate the new key at the branch's adaptive position and scatter
-// key and value into the pool formats.
+// key and value into the pool formats.  The angles depend on the position and the frequency index
+// only, so D / 2 threads compute them once (fp64) and the block shares them through LDS.
 __global__ void __launch_bounds__(256) k_kv_append(const int32_t* branch_page_off, const int32_t* branch_pages,
                                                    const int32_t* branch_len, const int32_t* branch_pos,
                                                    const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
                                                    uint16_t* v_pool, int hkv, int D, float theta) {
+  __shared__ float s_cos[64], s_sin[64];  // D / 2 <= 64
   const int r = blockIdx.x;
   const int idx = branch_len[r] - 1;
   if (idx < 0) return;
   const int page = branch_pages[branch_page_off[r] + idx / PAGE];
   const int slot = idx % PAGE;
   const int half = D / 2;
-  const double pos = (double)branch_pos[r];
+  if ((int)threadIdx.x < half) {
+    double sn, cs;
+    sincos((double)branch_pos[r] * pow((double)theta, -2.0 * (double)threadIdx.x / (double)D), &sn, &cs);
+    s_cos[threadIdx.x] = (float)cs;
+    s_sin[threadIdx.x] = (float)sn;
+  }
+  __syncthreads();
   for (int x = threadIdx.x; x < hkv * half; x += blockDim.x) {
     const int h = x / half, mi = x % half;
-    double sn, cs;
-    sincos(pos * pow((double)theta, -2.0 * (double)mi / (double)D), &sn, &cs);
     const size_t src = ((size_t)r * hkv + h) * D;
     const float lo = __uint_as_float((uint32_t)k_new[src + mi] << 16);
     const float hi = __uint_as_float((uint32_t)k_new[src + mi + half] << 16);
-    const float c = (float)cs, s = (float)sn;
+    const float c = s_cos[mi], s = s_sin[mi];
     const size_t pb = ((size_t)page * hkv + h) * (size_t)(D * PAGE);
     const int d0 = mi, d1 = mi + half;
     k_pool[pb + (size_t)(d0 >> 3) * (PAGE * 8) + slot * 8 + (d0 & 7)] = (uint16_t)dag_f2bf(lo * c - hi * s);

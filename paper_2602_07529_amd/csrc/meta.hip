@@ -94,10 +94,12 @@ int host_validate_bits(const dag_desc_t* d) {
 }
 
 // ------------------------------------------------------------------------------------ kernels
-// One block: per-sequence token counts and the three prefix sums over sequences.
-__global__ void k_seq(int n_seqs, const int32_t* node_off, const int32_t* node_len, int tile_m, int tile_n,
-                      int32_t* cu_seqlens, int32_t* qtile_start, int64_t* block_map_off, int32_t* node_start,
-                      int32_t* ktile_start) {
+// One block: per-sequence token counts and the three prefix sums over sequences; zeroes the
+// per-row tile counts that k_blockmap adds up.
+__device__ void seq_block(int n_seqs, const int32_t* node_off, const int32_t* node_len, int tile_m, int tile_n,
+                          int32_t* cu_seqlens, int32_t* qtile_start, int64_t* block_map_off, int32_t* node_start,
+                          int32_t* ktile_start, int32_t* cnt, int total_qtiles) {
+  for (int i = threadIdx.x; i < total_qtiles; i += blockDim.x) cnt[i] = 0;
   for (int b = threadIdx.x; b <= n_seqs; b += blockDim.x) node_start[b] = node_off[b];
   for (int b = threadIdx.x; b < n_seqs; b += blockDim.x) {
     int t = 0;
@@ -129,11 +131,20 @@ __global__ void k_seq(int n_seqs, const int32_t* node_off, const int32_t* node_l
 
 // One wave per sequence: node token starts (scan), visibility sets, adaptive position starts
 // (section 4.2: 0 without ancestors, else one past the largest ancestor position), pair counts.
-__global__ void __launch_bounds__(64) k_node(const int32_t* node_off, const int32_t* node_len,
-                                             const uint64_t* anc, int W, int32_t* node_tok_start,
-                                             int32_t* node_pos_start, uint64_t* node_vis,
-                                             int64_t* useful_pairs) {
+// One more block (the last) does the per-sequence sums of seq_block.
+__global__ void __launch_bounds__(64) k_seq_node(int n_seqs, const int32_t* node_off, const int32_t* node_len,
+                                                 const uint64_t* anc, int W, int tile_m, int tile_n,
+                                                 int32_t* cu_seqlens, int32_t* qtile_start, int64_t* block_map_off,
+                                                 int32_t* node_start, int32_t* ktile_start, int32_t* cnt,
+                                                 int total_qtiles, int32_t* node_tok_start,
+                                                 int32_t* node_pos_start, uint64_t* node_vis,
+                                                 int64_t* useful_pairs) {
   extern __shared__ int32_t s_pos_end[];  // [n] last position used by each node
+  if ((int)blockIdx.x == n_seqs) {
+    seq_block(n_seqs, node_off, node_len, tile_m, tile_n, cu_seqlens, qtile_start, block_map_off, node_start,
+              ktile_start, cnt, total_qtiles);
+    return;
+  }
   const int b = blockIdx.x, lane = threadIdx.x;
   const int n0 = node_off[b], n = node_off[b + 1] - n0;
   int32_t* s_len = s_pos_end + n;  // [n]
@@ -204,67 +215,68 @@ __global__ void k_tokens(int n_seqs, const int32_t* node_off, const int32_t* nod
   }
 }
 
-// One thread per (query tile, key tile): exact count of visible pairs among the in-range pairs.
-__global__ void k_blockmap(int n_seqs, int64_t total_tiles, const int64_t* block_map_off,
-                           const int32_t* cu_seqlens, const int32_t* node_off, const int32_t* tok_node,
-                           const int32_t* node_tok_start, const uint64_t* node_vis, int W, int tile_m,
-                           int tile_n, uint8_t* block_map) {
+// One thread per (query tile, key tile): exact count of visible pairs among the in-range pairs
+// => SKIP / PARTIAL / FULL.  Also adds up the non-skip tiles of every query tile's row (cnt, zeroed
+// before): tiles are numbered row after row, so a block touches at most blockDim.x consecutive
+// rows; it counts them in LDS and adds each row's share to cnt once.
+__global__ void __launch_bounds__(256) k_blockmap(int n_seqs, int64_t total_tiles, const int64_t* block_map_off,
+                                                  const int32_t* cu_seqlens, const int32_t* node_off,
+                                                  const int32_t* tok_node, const int32_t* node_tok_start,
+                                                  const uint64_t* node_vis, int W, int tile_m, int tile_n,
+                                                  const int32_t* qtile_start, uint8_t* block_map, int32_t* cnt) {
+  __shared__ int s_rows[256];
+  __shared__ int s_first;
+  s_rows[threadIdx.x] = 0;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total_tiles) return;
-  const int b = dag_find_segment(block_map_off, n_seqs, idx);
-  const int T = cu_seqlens[b + 1] - cu_seqlens[b];
-  const int KT = (T + tile_n - 1) / tile_n;
-  const int64_t loc = idx - block_map_off[b];
-  const int a = (int)(loc / KT), kb = (int)(loc % KT);
-  const int i0 = a * tile_m, i1 = min(T, i0 + tile_m);
-  const int j0 = kb * tile_n, j1 = min(T, j0 + tile_n);
-  if (j0 > i1 - 1) {  // entirely in the future of every row
-    block_map[idx] = DAG_TILE_SKIP;
-    return;
-  }
-  const int32_t* tn = tok_node + cu_seqlens[b];
-  const int n0 = node_off[b];
-  const int nn = node_off[b + 1] - n0;
-  const int u_lo = tn[i0], u_hi = tn[i1 - 1], w_lo = tn[j0], w_hi = tn[j1 - 1];
-  long long allowed = 0;
-  for (int u = u_lo; u <= u_hi; ++u) {
-    const int us = node_tok_start[n0 + u];
-    const int ue = (u + 1 < nn) ? node_tok_start[n0 + u + 1] : T;
-    const int r0 = max(i0, us), r1 = min(i1, ue);
-    for (int w = w_lo; w <= w_hi && w <= u; ++w) {
-      const int ws = node_tok_start[n0 + w];
-      const int we = (w + 1 < nn) ? node_tok_start[n0 + w + 1] : T;
-      const int c0 = max(j0, ws), c1 = min(j1, we);
-      if (w == u) {
-        for (int i = r0; i < r1; ++i) {  // causal inside the node
-          int c = min(i + 1, c1) - c0;
-          if (c > 0) allowed += c;
+  const bool valid = idx < total_tiles;
+  int gq = 0;  // query tile (row of the block map) over the whole batch
+  uint8_t state = DAG_TILE_SKIP;
+  if (valid) {
+    const int b = dag_find_segment(block_map_off, n_seqs, idx);
+    const int T = cu_seqlens[b + 1] - cu_seqlens[b];
+    const int KT = (T + tile_n - 1) / tile_n;
+    const int64_t loc = idx - block_map_off[b];
+    const int a = (int)(loc / KT), kb = (int)(loc % KT);
+    gq = qtile_start[b] + a;
+    const int i0 = a * tile_m, i1 = min(T, i0 + tile_m);
+    const int j0 = kb * tile_n, j1 = min(T, j0 + tile_n);
+    if (j0 <= i1 - 1) {  // else entirely in the future of every row
+      const int32_t* tn = tok_node + cu_seqlens[b];
+      const int n0 = node_off[b];
+      const int nn = node_off[b + 1] - n0;
+      const int u_lo = tn[i0], u_hi = tn[i1 - 1], w_lo = tn[j0], w_hi = tn[j1 - 1];
+      long long allowed = 0;
+      for (int u = u_lo; u <= u_hi; ++u) {
+        const int us = node_tok_start[n0 + u];
+        const int ue = (u + 1 < nn) ? node_tok_start[n0 + u + 1] : T;
+        const int r0 = max(i0, us), r1 = min(i1, ue);
+        for (int w = w_lo; w <= w_hi && w <= u; ++w) {
+          const int ws = node_tok_start[n0 + w];
+          const int we = (w + 1 < nn) ? node_tok_start[n0 + w + 1] : T;
+          const int c0 = max(j0, ws), c1 = min(j1, we);
+          if (w == u) {
+            for (int i = r0; i < r1; ++i) {  // causal inside the node
+              int c = min(i + 1, c1) - c0;
+              if (c > 0) allowed += c;
+            }
+          } else if ((node_vis[(int64_t)(n0 + u) * W + (w >> 6)] >> (w & 63)) & 1) {
+            allowed += (long long)(r1 - r0) * (c1 - c0);
+          }
         }
-      } else if ((node_vis[(int64_t)(n0 + u) * W + (w >> 6)] >> (w & 63)) & 1) {
-        allowed += (long long)(r1 - r0) * (c1 - c0);
       }
+      const long long total = (long long)(i1 - i0) * (j1 - j0);
+      state = allowed == 0 ? DAG_TILE_SKIP : (allowed == total ? DAG_TILE_FULL : DAG_TILE_PARTIAL);
     }
+    block_map[idx] = state;
   }
-  const long long total = (long long)(i1 - i0) * (j1 - j0);
-  block_map[idx] = allowed == 0 ? DAG_TILE_SKIP : (allowed == total ? DAG_TILE_FULL : DAG_TILE_PARTIAL);
+  if (threadIdx.x == 0) s_first = gq;  // thread 0 is always valid (the grid covers total_tiles)
+  __syncthreads();
+  if (state != DAG_TILE_SKIP) atomicAdd(&s_rows[gq - s_first], 1);
+  __syncthreads();
+  if (s_rows[threadIdx.x] != 0) atomicAdd(cnt + s_first + threadIdx.x, s_rows[threadIdx.x]);
 }
 
-// One wave per query tile: number of non-skip key tiles.
-__global__ void __launch_bounds__(64) k_csr_count(int n_seqs, const int32_t* qtile_start,
-                                                  const int64_t* block_map_off, const int32_t* cu_seqlens,
-                                                  int tile_n, const uint8_t* block_map, int32_t* cnt) {
-  const int qt = blockIdx.x, lane = threadIdx.x;
-  const int b = dag_find_segment(qtile_start, n_seqs, qt);
-  const int T = cu_seqlens[b + 1] - cu_seqlens[b];
-  const int KT = (T + tile_n - 1) / tile_n;
-  const uint8_t* row = block_map + block_map_off[b] + (int64_t)(qt - qtile_start[b]) * KT;
-  int c = 0;
-  for (int k = lane; k < KT; k += 64) c += row[k] != DAG_TILE_SKIP;
-  for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off);
-  if (lane == 0) cnt[qt] = c;
-}
-
-// One block: exclusive scan of the per-row counts.
+// One block: exclusive scan of the per-row counts (only used for a batch without tokens).
 __global__ void __launch_bounds__(1024) k_csr_scan(int total_qtiles, const int32_t* cnt, int32_t* rowptr) {
   __shared__ int s[1024];
   __shared__ int carry;
@@ -289,18 +301,42 @@ __global__ void __launch_bounds__(1024) k_csr_scan(int total_qtiles, const int32
   if (threadIdx.x == 0) rowptr[total_qtiles] = carry;
 }
 
-// One wave per query tile: ordered compaction of the non-skip tiles -- FULL tiles first (key
-// tiles ascending), then PARTIAL tiles (ascending) -- and the number of FULL tiles.
-__global__ void __launch_bounds__(64) k_csr_fill(int n_seqs, const int32_t* qtile_start,
-                                                 const int64_t* block_map_off, const int32_t* cu_seqlens,
-                                                 int tile_n, const uint8_t* block_map, const int32_t* rowptr,
-                                                 int32_t* col, uint8_t* flag, int32_t* nfull) {
-  const int qt = blockIdx.x, lane = threadIdx.x;
+// One wave per query tile, given the number of non-skip tiles of every row (cnt):
+//  * CSR row start = sum of the counts in front of it, and launch slot = number of query tiles in
+//    front of it in the order (tile count descending, index ascending), both from one pass over
+//    cnt shared by the lanes.  The prefill kernel hands the launch list out dynamically, and with
+//    the heaviest items first the workgroups finish within the duration of one of the lightest;
+//  * ordered compaction of the row's non-skip tiles -- FULL tiles first (key tiles ascending),
+//    then PARTIAL tiles (ascending) -- and the number of FULL tiles;
+//  * the tile's launch record in its slot: everything the prefill kernel needs to start the
+//    query tile, in 32 bytes {token offset of the sequence, tokens in the sequence, first row of
+//    the tile, CSR row start, tiles in the row, tiles that need no mask, node offset of the
+//    sequence, first key tile of the sequence}.
+__global__ void __launch_bounds__(256) k_csr_order_desc(int n_seqs, int total_qtiles, int tile_m, int tile_n,
+                                                        const int32_t* cnt, const int32_t* qtile_start,
+                                                        const int64_t* block_map_off, const int32_t* cu_seqlens,
+                                                        const int32_t* node_start, const int32_t* ktile_start,
+                                                        const uint8_t* block_map, int32_t* rowptr, int32_t* col,
+                                                        uint8_t* flag, int32_t* nfull, int32_t* order,
+                                                        int32_t* desc) {
+  const int qt = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (qt >= total_qtiles) return;
+  const int mine = cnt[qt];
+  int oi = 0, c0 = 0;
+  for (int j = lane; j < total_qtiles; j += 64) {
+    const int o = cnt[j];
+    oi += (o > mine) || (o == mine && j < qt);
+    c0 += j < qt ? o : 0;
+  }
+  for (int off = 32; off; off >>= 1) {
+    oi += __shfl_xor(oi, off);
+    c0 += __shfl_xor(c0, off);
+  }
   const int b = dag_find_segment(qtile_start, n_seqs, qt);
   const int T = cu_seqlens[b + 1] - cu_seqlens[b];
   const int KT = (T + tile_n - 1) / tile_n;
   const uint8_t* row = block_map + block_map_off[b] + (int64_t)(qt - qtile_start[b]) * KT;
-  int out = rowptr[qt];
+  int out = c0, nf = 0, last_full = -1;
   for (int pass = 0; pass < 2; ++pass) {
     const uint8_t want = pass == 0 ? DAG_TILE_FULL : DAG_TILE_PARTIAL;
     for (int k0 = 0; k0 < KT; k0 += 64) {
@@ -313,47 +349,22 @@ __global__ void __launch_bounds__(64) k_csr_fill(int n_seqs, const int32_t* qtil
         flag[p] = f;
       }
       out += __popcll(m);
+      if (pass == 0 && m) last_full = k0 + 63 - __builtin_clzll(m);
     }
-    if (pass == 0 && lane == 0) nfull[qt] = out - rowptr[qt];
+    if (pass == 0) nf = out - c0;
   }
-}
-
-// One wave per query tile: launch order = all query tiles by (tile count descending, index
-// ascending), i.e. the slot of a tile is the number of tiles in front of it; the lanes share the
-// comparisons.  The prefill kernel hands the list out dynamically, and with the heaviest items
-// first the workgroups finish within the duration of one of the lightest.  The wave also writes
-// the tile's launch record into its slot: everything the prefill kernel needs to start the query
-// tile, in 32 bytes {token offset of the sequence, tokens in the sequence, first row of the tile,
-// CSR row start, tiles in the row, tiles that need no mask, node offset of the sequence, first key
-// tile of the sequence}.
-__global__ void __launch_bounds__(256) k_order_desc(int n_seqs, int total_qtiles, int tile_m, int tile_n,
-                                                    const int32_t* cnt, const int32_t* qtile_start,
-                                                    const int32_t* cu_seqlens, const int32_t* node_start,
-                                                    const int32_t* ktile_start, const int32_t* rowptr,
-                                                    const int32_t* col, const int32_t* nfull, int32_t* order,
-                                                    int32_t* desc) {
-  const int qt = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (qt >= total_qtiles) return;
-  const int mine = cnt[qt];
-  int oi = 0;
-  for (int j = lane; j < total_qtiles; j += 64) {
-    const int o = cnt[j];
-    oi += (o > mine) || (o == mine && j < qt);
-  }
-  for (int off = 32; off; off >>= 1) oi += __shfl_xor(oi, off);
   if (lane != 0) return;
+  rowptr[qt] = c0;
+  if (qt == total_qtiles - 1) rowptr[total_qtiles] = c0 + mine;
+  nfull[qt] = nf;
   order[oi] = qt;
-  const int b = dag_find_segment(qtile_start, n_seqs, qt);
-  const int T = cu_seqlens[b + 1] - cu_seqlens[b];
-  const int c0 = rowptr[qt];
-  int nf = nfull[qt];
-  if (nf > 0 && (col[c0 + nf - 1] + 1) * tile_n > T) --nf;  // a ragged last key tile needs the mask path
+  if (nf > 0 && (last_full + 1) * tile_n > T) --nf;  // a ragged last key tile needs the mask path
   int32_t* d = desc + (int64_t)oi * 8;
   d[0] = cu_seqlens[b];
   d[1] = T;
   d[2] = (qt - qtile_start[b]) * tile_m;
   d[3] = c0;
-  d[4] = rowptr[qt + 1] - c0;
+  d[4] = mine;
   d[5] = nf;
   d[6] = node_start[b];
   d[7] = ktile_start[b];
@@ -426,11 +437,11 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
     int n = d->node_offsets[b + 1] - d->node_offsets[b];
     if (n > max_nodes) max_nodes = n;
   }
-  hipLaunchKernelGGL(k_seq, dim3(1), dim3(256), 0, stream, d->n_seqs, d_off, d_len, d->tile_m, d->tile_n,
-                     m->cu_seqlens, m->qtile_start, m->block_map_off, m->node_start, m->ktile_start);
-  DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_node, dim3(d->n_seqs), dim3(64), (size_t)max_nodes * 8 + 8, stream, d_off, d_len, d_anc, W,
-                     m->node_tok_start, m->node_pos_start, m->node_vis, m->useful_pairs);
+  const unsigned QT = (unsigned)s.total_qtiles;
+  hipLaunchKernelGGL(k_seq_node, dim3(d->n_seqs + 1), dim3(64), (size_t)max_nodes * 8 + 8, stream, d->n_seqs, d_off,
+                     d_len, d_anc, W, d->tile_m, d->tile_n, m->cu_seqlens, m->qtile_start, m->block_map_off,
+                     m->node_start, m->ktile_start, d_cnt, (int)QT, m->node_tok_start, m->node_pos_start, m->node_vis,
+                     m->useful_pairs);
   DAG_LAUNCH_CHECK();
   if (s.total_tokens == 0) {
     hipLaunchKernelGGL(k_csr_scan, dim3(1), dim3(1024), 0, stream, 0, d_cnt, m->qtile_rowptr);
@@ -442,21 +453,12 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
   DAG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_blockmap, dim3((unsigned)dag_ceil_div(s.total_tiles, 256)), dim3(256), 0, stream, d->n_seqs,
                      s.total_tiles, m->block_map_off, m->cu_seqlens, d_off, m->tok_node, m->node_tok_start,
-                     m->node_vis, W, d->tile_m, d->tile_n, m->block_map);
+                     m->node_vis, W, d->tile_m, d->tile_n, m->qtile_start, m->block_map, d_cnt);
   DAG_LAUNCH_CHECK();
-  const unsigned QT = (unsigned)s.total_qtiles;
-  hipLaunchKernelGGL(k_csr_count, dim3(QT), dim3(64), 0, stream, d->n_seqs, m->qtile_start, m->block_map_off,
-                     m->cu_seqlens, d->tile_n, m->block_map, d_cnt);
-  DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_csr_scan, dim3(1), dim3(1024), 0, stream, (int)QT, d_cnt, m->qtile_rowptr);
-  DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_csr_fill, dim3(QT), dim3(64), 0, stream, d->n_seqs, m->qtile_start, m->block_map_off,
-                     m->cu_seqlens, d->tile_n, m->block_map, m->qtile_rowptr, m->qtile_col, m->qtile_flag,
-                     m->qtile_nfull);
-  DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_order_desc, dim3((QT + 3) / 4), dim3(256), 0, stream, d->n_seqs, (int)QT, d->tile_m, d->tile_n,
-                     d_cnt, m->qtile_start, m->cu_seqlens, m->node_start, m->ktile_start, m->qtile_rowptr, m->qtile_col,
-                     m->qtile_nfull, m->qtile_order, m->qtile_desc);
+  hipLaunchKernelGGL(k_csr_order_desc, dim3((QT + 3) / 4), dim3(256), 0, stream, d->n_seqs, (int)QT, d->tile_m,
+                     d->tile_n, d_cnt, m->qtile_start, m->block_map_off, m->cu_seqlens, m->node_start, m->ktile_start,
+                     m->block_map, m->qtile_rowptr, m->qtile_col, m->qtile_flag, m->qtile_nfull, m->qtile_order,
+                     m->qtile_desc);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
