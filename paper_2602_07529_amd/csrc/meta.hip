@@ -138,8 +138,8 @@ __global__ void __launch_bounds__(64) k_seq_node(int n_seqs, const int32_t* node
                                                  int32_t* node_start, int32_t* ktile_start, int32_t* cnt,
                                                  int total_qtiles, int32_t* node_tok_start,
                                                  int32_t* node_pos_start, uint64_t* node_vis,
-                                                 int64_t* useful_pairs) {
-  extern __shared__ int32_t s_pos_end[];  // [n] last position used by each node
+                                                 int64_t* useful_pairs, int anc_in_lds) {
+  extern __shared__ uint64_t s_anc[];  // [n][W] ancestor words of the sequence, then int32 [n] + [n] below
   if ((int)blockIdx.x == n_seqs) {
     seq_block(n_seqs, node_off, node_len, tile_m, tile_n, cu_seqlens, qtile_start, block_map_off, node_start,
               ktile_start, cnt, total_qtiles);
@@ -147,7 +147,13 @@ __global__ void __launch_bounds__(64) k_seq_node(int n_seqs, const int32_t* node
   }
   const int b = blockIdx.x, lane = threadIdx.x;
   const int n0 = node_off[b], n = node_off[b + 1] - n0;
-  int32_t* s_len = s_pos_end + n;  // [n]
+  // (the copy of the ancestor words is skipped for node tables too large for LDS; the walk below
+  // then reads them from global memory, one dependent load per node)
+  int32_t* s_pos_end = (int32_t*)(s_anc + (anc_in_lds ? (size_t)n * W : 0));  // [n] last position used by each node
+  int32_t* s_len = s_pos_end + n;                                              // [n]
+  const uint64_t* anc_rows = anc_in_lds ? s_anc : anc + (int64_t)n0 * W;
+  if (anc_in_lds)
+    for (int i = lane; i < n * W; i += 64) s_anc[i] = anc[(int64_t)n0 * W + i];
   int run = 0;
   for (int c = 0; c < n; c += 64) {
     int v = c + lane;
@@ -165,7 +171,7 @@ __global__ void __launch_bounds__(64) k_seq_node(int n_seqs, const int32_t* node
   }
   for (int v = lane; v < n; v += 64)
     for (int w = 0; w < W; ++w) {
-      uint64_t bits = anc[(int64_t)(n0 + v) * W + w];
+      uint64_t bits = anc[(int64_t)(n0 + v) * W + w];  // (this lane's own row: no need to wait for the LDS copy)
       if ((v >> 6) == w) bits |= 1ull << (v & 63);
       node_vis[(int64_t)(n0 + v) * W + w] = bits;
     }
@@ -175,7 +181,7 @@ __global__ void __launch_bounds__(64) k_seq_node(int n_seqs, const int32_t* node
     int best = -1;          // largest ancestor end position seen by this lane
     long long anc_tokens = 0;
     for (int w = 0; w * 64 <= v; ++w) {
-      uint64_t bits = anc[(int64_t)(n0 + v) * W + w];
+      uint64_t bits = anc_rows[(size_t)v * W + w];
       int u = w * 64 + lane;
       if (u < v && ((bits >> lane) & 1)) {
         int e = s_pos_end[u];
@@ -438,10 +444,12 @@ extern "C" int dag_build_meta(const dag_desc_t* d, const dag_meta_t* m, void* ws
     if (n > max_nodes) max_nodes = n;
   }
   const unsigned QT = (unsigned)s.total_qtiles;
-  hipLaunchKernelGGL(k_seq_node, dim3(d->n_seqs + 1), dim3(64), (size_t)max_nodes * 8 + 8, stream, d->n_seqs, d_off,
+  const size_t anc_bytes = (size_t)max_nodes * W * 8;
+  const int anc_in_lds = anc_bytes <= 32768;
+  hipLaunchKernelGGL(k_seq_node, dim3(d->n_seqs + 1), dim3(64), (size_t)max_nodes * 8 + 8 + (anc_in_lds ? anc_bytes : 0), stream, d->n_seqs, d_off,
                      d_len, d_anc, W, d->tile_m, d->tile_n, m->cu_seqlens, m->qtile_start, m->block_map_off,
                      m->node_start, m->ktile_start, d_cnt, (int)QT, m->node_tok_start, m->node_pos_start, m->node_vis,
-                     m->useful_pairs);
+                     m->useful_pairs, anc_in_lds);
   DAG_LAUNCH_CHECK();
   if (s.total_tokens == 0) {
     hipLaunchKernelGGL(k_csr_scan, dim3(1), dim3(1024), 0, stream, 0, d_cnt, m->qtile_rowptr);

@@ -73,6 +73,17 @@ def test_meta_more_than_64_nodes_uses_two_bitset_words():
     assert_meta_equal(meta, oracle_meta(dag_list, 32, 64))
 
 
+def test_meta_node_table_too_large_for_lds():
+    """700 nodes = 11 bitset words per node: the node walk keeps the ancestor words in LDS only up
+    to 32 KiB per sequence and reads them from global memory beyond that."""
+    rng = np.random.Generator(np.random.PCG64(79))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=700, depth=9, len_lo=1, len_hi=3)
+    assert anc.shape[1] == 11 and anc.size * 8 > 32768
+    dag_list = [(L, anc), dags.linear_chain([5, 1])]
+    meta = _build_with_tiles(dag_list, 64, 64)
+    assert_meta_equal(meta, oracle_meta(dag_list, 64, 64))
+
+
 def test_meta_layerwise_bitsets_literal_eq3():
     rng = np.random.Generator(np.random.PCG64(5))
     L, _, _, level = dags.random_dag(rng, n_nodes=20, depth=5, len_lo=1, len_hi=30)
