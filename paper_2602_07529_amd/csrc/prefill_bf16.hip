@@ -532,6 +532,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   unsigned long long tacc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   unsigned long long t_mid = 0;
   const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
+  const unsigned long long c_begin = __builtin_amdgcn_s_memtime();  // shader clock
 #define TSTAMP(x) const unsigned long long x = __builtin_amdgcn_s_memrealtime()
 #define TACC(i, a0, a1) tacc[i] += (a1) - (a0)
 #define TCOUNT(i) tacc[i] += 1
@@ -841,6 +842,8 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
 #ifdef DAGATTN_TIMING
   if (blockIdx.x == 0 && lane == 0) {
     const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
+    const unsigned long long c_end = __builtin_amdgcn_s_memtime();
+    if (w == 0) printf("shader clock during the kernel: %.0f MHz\n", (double)(c_end - c_begin) / (double)(t_end - t_begin) * 100.0);
     printf("wave %d total %llu | first tile %llu tile loop %llu last tile + epilogue %llu out %llu switch %llu | tiles in the loop %llu items %llu load waits %llu (x10ns)\n",
            w, t_end - t_begin, tacc[0], tacc[2], tacc[4], tacc[6], tacc[5], tacc[7], tacc[11], tacc[8]);
   }
