@@ -283,7 +283,13 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   const uint32_t voff = (L / 8) * BLKV + (L % 8) * 16 + H * 128;
 
   f32x16 O[RB][DB];
-  float m[RB], mth[RB], l[RB], bmax[RB];  // running maximum, maximum + threshold, row sum, block maximum
+  // Scores are kept relative to a reference maximum per row, in the exponent's units: the Q rows
+  // are scaled by scale * log2(e) when they are loaded, and the accumulator of the score product
+  // starts at -M (the C operand of its first MFMA), so a probability is exp2 of a score register
+  // with no further arithmetic.  M is the reference (0 until a row has seen a key), negM holds -M
+  // in all 16 registers of an accumulator.
+  float M[RB], l[RB], bmax[RB];  // reference maximum, row sum, maximum of the last score half (relative to M)
+  f32x16 negM[RB];
   bf16x8 P0[RB][2], P1[RB][2];  // probabilities of the two key halves (B operands)
   auto reset_acc = [&]() {
 #pragma unroll
@@ -292,8 +298,9 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) O[r][db][e] = 0.f;
-      m[r] = -1e30f;
-      mth[r] = -1e30f;
+      M[r] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) negM[r][e] = 0.f;
       l[r] = 0.f;
     }
   };
@@ -308,7 +315,6 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
         P1[r][j][e] = (__bf16)0.f;
       }
   const float sc = a.scale * 1.4426950408889634f;
-  const float th = TH_LOG2 / sc;  // threshold in raw score units
 
   bf16x8 qf[RB][KSTEPS];
   auto load_q = [&](const Item& I) {
@@ -316,11 +322,18 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     for (int r = 0; r < RB; ++r) {
       const uint16_t* qp = qg + ((size_t)token_of(I, r) * a.hq + head_of(I)) * D + 8 * H;
 #pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) qf[r][s] = *(const bf16x8*)(qp + 16 * s);
+      for (int s = 0; s < KSTEPS; ++s) {
+        const u32x4 raw = *(const u32x4*)(qp + 16 * s);
+        u32x4 scaled;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) scaled[e] = dag_pack_bf2(dag_bf_lo(raw[e]) * sc, dag_bf_hi(raw[e]) * sc);
+        qf[r][s] = __builtin_bit_cast(bf16x8, scaled);
+      }
     }
   };
 
-  // row maxima of a half; true when some row of the wave exceeds its running maximum by the threshold
+  // row maxima of a half; true when some row of the wave exceeds its reference maximum by the
+  // threshold (or lies that far below it while the row has not accumulated anything yet)
   auto row_max = [&](const f32x16* S) {
     bool need = false;
 #pragma unroll
@@ -330,7 +343,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       for (int e = 3; e < 15; e += 2) bm = max3(bm, S[r][e], S[r][e + 1]);
       bm = fmaxf(bm, S[r][15]);
       bmax[r] = bm;  // this lane's 16 keys only; the other half wave has the rest of the row
-      need |= bm > mth[r];
+      need |= bm > TH_LOG2 || (l[r] == 0.f && bm < -TH_LOG2 && bm > -1e30f);
     }
     return __builtin_amdgcn_ballot_w64(need) != 0;
   };
@@ -359,7 +372,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   // and a share of the step's exponentials.  Pieces (each optional):
   //   QK: Sn[r]  = K_h Q_r^T      scores of key half HQ of the tile at Kb (first KSTEPS slots)
   //   PV: O[r]  += V_h^T Pp[r]    the 32 keys of half HV of the tile at Vb (last 2 DB slots)
-  //   EX: Pc[r]  = exp2(sc (Sc[r] - m[r]))  probabilities of a half, row sums added to l
+  //   EX: Pc[r]  = exp2(Sc[r])    probabilities of a half (scores are relative to M), row sums added to l
   // `extra(slot, slots)` runs in every slot (used to issue the next K/V tile loads piecewise, in
   // the shadow of the MFMAs).
   // With QK, the row maxima of Sn are taken two slots after the last score MFMA (after the mask of
@@ -372,15 +385,11 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     constexpr int NQ = QK ? KSTEPS : 0, NSLOT = NQ + (PV ? 2 * DB : 0), NU = EX ? 8 * RB : 0;
     constexpr int PF = 3;  // operand reads in flight ahead of the MFMA that uses them
     constexpr int MAXSLOT = NQ + 2 < NSLOT ? NQ + 2 : NSLOT;  // where the row maxima are taken
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 opnd[NSLOT];
-    float msc[RB], rs[RB];
+    float rs[RB];
     bool need = false;
 #pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      msc[r] = EX ? m[r] * sc : 0.f;
-      rs[r] = 0.f;
-    }
+    for (int r = 0; r < RB; ++r) rs[r] = 0.f;
     // The operand reads are inline assembly with explicit lgkmcnt waits: LDS reads return in
     // order, so before the MFMA of slot i exactly the reads of the slots after it may be pending
     // (the compiler's own bookkeeping waits for all of them, which exposes the LDS latency).
@@ -409,7 +418,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r = 0; r < RB; ++r) {
-        if (i < NQ) Sn[r] = mfma32(opnd[i], qf[r][i < NQ ? i : 0], i == 0 ? zero : Sn[r]);
+        if (i < NQ) Sn[r] = mfma32(opnd[i], qf[r][i < NQ ? i : 0], i == 0 ? negM[r] : Sn[r]);
         else O[r][(i - NQ) % DB] = mfma32(opnd[i], Pp[r][(i - NQ) / DB], O[r][(i - NQ) % DB]);
       }
       extra(i, NSLOT);
@@ -421,8 +430,8 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       for (int u = i * NU / NSLOT; u < (i + 1) * NU / NSLOT; ++u) {  // two probabilities of one row
         const int r = u / 8, e = 2 * (u % 8);
         f32x2 p;
-        p[0] = __builtin_amdgcn_exp2f(fmaf(Sc[r][e], sc, -msc[r]));
-        p[1] = __builtin_amdgcn_exp2f(fmaf(Sc[r][e + 1], sc, -msc[r]));
+        p[0] = __builtin_amdgcn_exp2f(Sc[r][e]);
+        p[1] = __builtin_amdgcn_exp2f(Sc[r][e + 1]);
         rs[r] += p[0] + p[1];
         asm volatile("" : "+v"(rs[r]));  // keep the running sum (no sum tree at the end of the step)
         const bf16x2 pk = __builtin_convertvector(p, bf16x2);
@@ -446,14 +455,20 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   auto nothing = [](int, int) {};
   // raise the running maxima to bmax and rescale everything accumulated so far, including the
   // probabilities that are still waiting for their P V product (rare after the first tiles)
-  auto rescale = [&]() {
+  auto rescale = [&](f32x16* Sn) {  // Sn: the score half whose maxima called for it (still relative to the old M)
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-      const float m_new = fmaxf(m[r], fmaxf(bmax[r], __shfl_xor(bmax[r], 32)));
-      const float alpha = __builtin_amdgcn_exp2f((m[r] - m_new) * sc);
-      m[r] = m_new;
-      mth[r] = m_new + th;
+      float d = fmaxf(bmax[r], __shfl_xor(bmax[r], 32));  // maximum of the half over the whole row, relative to M
+      const bool fresh = l[r] + __shfl_xor(l[r], 32) == 0.f;  // nothing accumulated yet: M may go down too
+      d = d > -1e30f ? (fresh ? d : fmaxf(d, 0.f)) : 0.f;      // (a half without a visible key leaves M alone)
+      const float alpha = __builtin_amdgcn_exp2f(-d);
+      M[r] += d;
       l[r] *= alpha;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        negM[r][e] -= d;
+        Sn[r][e] -= d;
+      }
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -465,7 +480,6 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       }
     }
   };
-  // probabilities of a half whose scores are in S (relative to the running maxima)
   // ---------------------------------------------------------------- persistent loop over items
   // (the launch has at most one workgroup per item, so the first item always exists)
   Item cur = load_item(my_rank);
@@ -686,7 +700,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       if (msk_on && i == mask_slot) tile_mask(0);
     };
     msk_on = F == 0;
-    if (step(Y, N_, N_, H0, H0, Kt(tc), SA, nullptr, nop, nullptr, nullptr, first_tile_extra)) rescale();
+    if (step(Y, N_, N_, H0, H0, Kt(tc), SA, nullptr, nop, nullptr, nullptr, first_tile_extra)) rescale(SA);
     bool need = step(Y, N_, Y, H1, H0, Kt(tc), SB, nullptr, nop, SA, P0, nothing);
     TSTAMP(t_first);
     TACC(0, t_top, t_first);
@@ -695,9 +709,9 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       sync_next();  // tile tc - 1 is the one in flight through the pipeline, tc the new one
       msk_on = n + 1 >= F;
       mask_n = n + 1;
-      if (need) rescale();
+      if (need) rescale(SB);
       need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, first_half_extra);
-      if (need) rescale();
+      if (need) rescale(SA);
       need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, refill_slot_v);
       TCOUNT(7);
     }
@@ -725,7 +739,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
     }
     sync_next();
-    if (need) rescale();
+    if (need) rescale(SB);
     step(N_, Y, Y, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill_slot);
     step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc - 1), P1, nullptr, nullptr, refill_slot_v);
     TSTAMP(t_p1);
@@ -750,7 +764,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
         const float l_tot = l[r] + __shfl_xor(l[r], 32);
         const float inv = 1.f / l_tot;
         if (a.lse && store && H == 0 && row_of(cur, r) < cur.T)
-          a.lse[(size_t)token_of(cur, r) * a.hq + head] = m[r] * a.scale + logf(l_tot);
+          a.lse[(size_t)token_of(cur, r) * a.hq + head] = M[r] * 0.6931471805599453f + logf(l_tot);
 #pragma unroll
         for (int half = 0; half < 2; ++half) {  // rows 16 half .. 16 half + 15 of the block
           if ((L >> 4) == half) {
