@@ -97,14 +97,18 @@ __device__ __forceinline__ void load_block(KVBlock<D>& blk, const DecodeArgs& a,
 // qop(s): the query operand of MFMA step s.  k_decode keeps the operands in LDS, qs[s * 64 + lane]
 // (they are needed once per 32-key block; keeping them out of the register file lets two waves
 // share a SIMD, which doubles the bytes in flight); k_decode_wide keeps them in registers.
+// First phase of a 32-key block: scores against the key operands, online softmax bookkeeping
+// (accumulators rescaled when the reference maximum moves), probabilities as the two B operands
+// of the second phase.
 template <int D, typename QF>
-__device__ __forceinline__ void compute_block(const KVBlock<D>& blk, QF&& qop, f32x16* O, float& m, float& l,
-                                              float sc, float th, int key0, int len, int H) {
+__device__ __forceinline__ void block_scores(const bf16x8 (&kop)[D / 16], QF&& qop, f32x16* O, float& m, float& l,
+                                             float sc, float th, int key0, int len, int H, bf16x8& pb0,
+                                             bf16x8& pb1) {
   f32x16 S;
 #pragma unroll
   for (int r = 0; r < 16; ++r) S[r] = 0.f;
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) S = mfma32(blk.k[s], qop(s), S);
+  for (int s = 0; s < D / 16; ++s) S = mfma32(kop[s], qop(s), S);
   if (key0 + 32 > len) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -139,13 +143,27 @@ __device__ __forceinline__ void compute_block(const KVBlock<D>& blk, QF&& qop, f
     rowsum += p0[r] + p1[r];
   }
   l += rowsum;
-  const bf16x8 pb0 = __builtin_convertvector(p0, bf16x8);
-  const bf16x8 pb1 = __builtin_convertvector(p1, bf16x8);
+  pb0 = __builtin_convertvector(p0, bf16x8);
+  pb1 = __builtin_convertvector(p1, bf16x8);
+}
+
+// Second phase: O^T += V^T P^T with the value operands of the block's two pages.
+template <int D>
+__device__ __forceinline__ void block_pv(const bf16x8 (&v0)[D / 32], const bf16x8 (&v1)[D / 32], bf16x8 pb0,
+                                         bf16x8 pb1, f32x16* O) {
 #pragma unroll
   for (int db = 0; db < D / 32; ++db) {
-    O[db] = mfma32(blk.v[0][db], pb0, O[db]);
-    O[db] = mfma32(blk.v[1][db], pb1, O[db]);
+    O[db] = mfma32(v0[db], pb0, O[db]);
+    O[db] = mfma32(v1[db], pb1, O[db]);
   }
+}
+
+template <int D, typename QF>
+__device__ __forceinline__ void compute_block(const KVBlock<D>& blk, QF&& qop, f32x16* O, float& m, float& l,
+                                              float sc, float th, int key0, int len, int H) {
+  bf16x8 pb0, pb1;
+  block_scores<D>(blk.k, qop, O, m, l, sc, th, key0, len, H, pb0, pb1);
+  block_pv<D>(blk.v[0], blk.v[1], pb0, pb1, O);
 }
 
 template <int D>
@@ -224,19 +242,26 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
   // because windows and blocks both start at even offsets.
   const int np = p1 - p0;
   int pgv = pages[p0 + min(lane, np - 1)];
+  asm volatile("" ::"v"(pgv));  // arrived: a wait for it inside the loop would also wait for the K/V loads in flight
   KVBlock<D> b0, b1;
   load_block<D>(b0, a, pgv, 0, np - 1, hk, L, H, kpage_sel, kslot);
   int pb = 0;  // relative to p0
   while (true) {
     if (pb + 2 < np) {
-      if (((pb + 2) & 63) == 0) pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
+      if (((pb + 2) & 63) == 0) {
+        pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
+        asm volatile("" ::"v"(pgv));
+      }
       load_block<D>(b1, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
     }
     compute_block<D>(b0, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
     pb += 2;
     if (pb >= np) break;
     if (pb + 2 < np) {
-      if (((pb + 2) & 63) == 0) pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
+      if (((pb + 2) & 63) == 0) {
+        pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
+        asm volatile("" ::"v"(pgv));
+      }
       load_block<D>(b0, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
     }
     compute_block<D>(b1, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
@@ -266,7 +291,7 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
 // per lane; a page of the pools is already the operand image), so the shared pages are streamed
 // once per group whatever the number of rows, and RING - 1 blocks are in flight per workgroup
 // instead of one per wave.  Writes the same partials as the shared items of k_decode.
-constexpr int WIDE_RING = 8;                    // 32-key blocks in the ring
+constexpr int WIDE_RING = 8;                    // 32-key blocks in the ring (128 KiB of LDS at head_dim 128: one workgroup per CU)
 constexpr int WIDE_MAX_WAVES = 8;
 template <int D>
 constexpr int wide_block_bytes() { return 4 * PAGE * D * 2; }  // K and V of two pages
@@ -384,28 +409,32 @@ __global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeAr
     wait_vmcnt_dyn((issued - 1 - b) * lpw);
     __builtin_amdgcn_s_barrier();  // block b is complete; every wave has finished block b - 1
     asm volatile("" ::: "memory");
-    KVBlock<D> blk;
     const uint32_t sb = ring0 + (b % WIDE_RING) * BB;
-    // (inline assembly: for plain LDS reads the compiler would first wait for every global-to-LDS
-    // load in flight)
+    // Operands come from LDS right before their product (inline assembly: for plain LDS reads the
+    // compiler would first wait for every global-to-LDS load in flight); the value operands are
+    // read after the score MFMAs have been issued, so they can take the key operands' registers,
+    // and their latency hides behind the softmax arithmetic.
+    bf16x8 kop[D / 16], v0[D / 32], v1[D / 32], pb0, pb1;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(blk.k[s]) : "v"(sb + koff), "n"(s * 2 * PAGE * 16));
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) {
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(blk.v[0][db]) : "v"(sb + voff), "n"(db * 32 * PAGE * 2));
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(blk.v[1][db]) : "v"(sb + voff), "n"(PB + db * 32 * PAGE * 2));
-    }
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kop[s]) : "v"(sb + koff), "n"(s * 2 * PAGE * 16));
     if (issued < nblk) {  // the next loads, into the slot of block b - 1, while the operand reads are under way
       issue_block(issued);
       ++issued;
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(blk.k[s]));
+    for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(kop[s]));
+    block_scores<D>(kop, qop, O, m, l, a.sc, a.th, (p0 + 2 * b) * PAGE, len, H, pb0, pb1);
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db) asm volatile("" : "+v"(blk.v[0][db]), "+v"(blk.v[1][db]));
-    compute_block<D>(blk, qop, O, m, l, a.sc, a.th, (p0 + 2 * b) * PAGE, len, H);
+    for (int db = 0; db < D / 32; ++db) {
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v0[db]) : "v"(sb + voff), "n"(db * 32 * PAGE * 2));
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v1[db]) : "v"(sb + voff), "n"(PB + db * 32 * PAGE * 2));
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) asm volatile("" : "+v"(v0[db]), "+v"(v1[db]));
+    block_pv<D>(v0, v1, pb0, pb1, O);
   }
 
   const float l_tot = l + __shfl_xor(l, 32);
