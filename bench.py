@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
 # what the same counters read for a plain 256 MiB copy (profiles/k_prefill_bf16__*.txt and
 # profiles/k_decode__*.txt hold the commands and the raw readings); measured, not computed here.
-TRAFFIC_PREFILL_KERNEL = (1241637 + 147528) * 1024      # k_prefill_bf16, read + written
-TRAFFIC_DECODE_KERNELS = (1054916 + 11552 + 11819 + 1024) * 1024   # k_decode + k_decode_merge
+TRAFFIC_PREFILL_KERNEL = (1237150 + 147528) * 1024      # k_prefill_bf16, read + written
+TRAFFIC_DECODE_KERNELS = (1053639 + 10400 + 11819 + 1024) * 1024   # k_decode + k_decode_merge
 
 
 def _ensure_built():
