@@ -312,6 +312,44 @@ def attn_decode(desc, q, k_pool, v_pool, scale=None, branches=None):
     return O
 
 
+def gather_segments(sdesc, r, h, k_pool, v_pool):
+    """K, V [ctx][D] seen by live branch r on KV head h when contexts are lists of KV segments
+    (section 3.2: a token carries references to cached blocks; section 4.3: a Fork hands the same
+    context to every child, a Join the histories of all its predecessors): the first seg_len[s]
+    tokens of every segment s the branch reads, in the order listed."""
+    Ks, Vs = [], []
+    for e in range(int(sdesc["branch_seg_off"][r]), int(sdesc["branch_seg_off"][r + 1])):
+        s = int(sdesc["branch_segs"][e])
+        for t in range(int(sdesc["seg_len"][s])):
+            page = int(sdesc["seg_pages"][int(sdesc["seg_page_off"][s]) + t // PAGE])
+            Ks.append(pool_get_k(k_pool, page, h, t % PAGE))
+            Vs.append(pool_get_v(v_pool, page, h, t % PAGE))
+    return np.array(Ks), np.array(Vs)
+
+
+def attn_decode_segments(sdesc, q, k_pool, v_pool, scale=None, branches=None):
+    """One decode step over segment lists: o = softmax(q . K^T * scale) V over the tokens of the
+    segments each live branch reads (Eq. 2 with membership as the only mask), fp64.
+
+    q [n_live][Hq][D] already rotated.  Returns O [n_live][Hq][D] (NaN for branches not asked).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    n_live, Hq, D = q.shape
+    Hkv = k_pool.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    O = np.full((n_live, Hq, D), np.nan)
+    for r in (range(n_live) if branches is None else branches):
+        for hk in range(Hkv):
+            K, V = gather_segments(sdesc, r, hk, k_pool, v_pool)
+            for h in range(hk * G, (hk + 1) * G):
+                s = (K @ q[r, h]) * scale
+                p = np.exp(s - s.max())
+                O[r, h] = (p @ V) / p.sum()
+    return O
+
+
 # ----------------------------------------------------------------------------- log-sum-exp merge
 def partial_attention(qvec, K, V, scale):
     """Un-normalised partial over a key subset: (o = sum_j e^{s_j-m} v_j, m = max s, l = sum e^{s_j-m})."""

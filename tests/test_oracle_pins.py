@@ -415,3 +415,83 @@ def test_attn_prefill_compact_rows_mode_is_the_same_computation():
     O, lse = orc.attn_prefill(q, k, v, L, anc, rows=rows)
     Oc, lsec = orc.attn_prefill(q[rows], k, v, L, anc, rows=rows, compact=True)
     assert np.array_equal(O[rows], Oc) and np.array_equal(lse[rows], lsec)
+
+
+# ----------------------------------------------------------------------------- decode over KV segments
+def _multilevel_dag():
+    """root -> (a, b); a -> (a0, a1); b -> (b0, b1, b2); join of a0, a1 and b0; lengths ragged
+    against the page size."""
+    parents = [[], [0], [0], [1], [1], [2], [2], [2], [3, 4, 5]]
+    L = np.asarray([37, 16, 5, 21, 1, 33, 18, 7, 12], dtype=np.int32)
+    return L, dags.bits_from_sets(dags.closure_from_parents(parents))
+
+
+def _segments_fixture(seed=71, hq=4, hkv=2, d=16, live=(8, 6, 7, 4)):
+    L, anc = _multilevel_dag()
+    st = dags.decode_segments_state(seed, [(L, anc)], [list(live)], hq, hkv, d, dtype=torch.float64)
+    return L, anc, st
+
+
+def test_segment_decode_equals_the_dag_masked_prefill_row():
+    """A live node decoding its last token over the segments of its ancestors and its own gives
+    the row of DAG-masked attention (Eq. 3) of that token: pins the segment gather to the mask
+    definition (partly filled pages, several sharing levels, a join of unequal branches).  The
+    unused slots of partly filled pages hold large junk, so reading one slot too many shows."""
+    L, anc, st = _segments_fixture()
+    q_tok, k_tok, v_tok = (x.numpy() for x in st["tokens"][0])
+    O, _ = orc.attn_prefill(q_tok, k_tok, v_tok, L, anc, rows=np.asarray(st["live_tok"]))
+    Od = orc.attn_decode_segments(st["desc"], st["q"].numpy(), st["k_pool"].numpy(), st["v_pool"].numpy())
+    assert np.abs(O[st["live_tok"]] - Od).max() < 1e-12
+
+
+def test_segment_decode_context_sizes_and_reader_lists():
+    L, anc, st = _segments_fixture()
+    desc = st["desc"]
+    # live branch 0 is the join (node 8): root, a, b, a0, a1, b0 and itself
+    K, _ = orc.gather_segments(desc, 0, 0, st["k_pool"].numpy(), st["v_pool"].numpy())
+    assert K.shape[0] == 37 + 16 + 5 + 21 + 1 + 33 + 12
+    # live branch 3 is a1 (node 4): root, a, itself
+    K, _ = orc.gather_segments(desc, 3, 1, st["k_pool"].numpy(), st["v_pool"].numpy())
+    assert K.shape[0] == 37 + 16 + 1
+    readers = lambda s: list(desc["seg_readers"][desc["seg_reader_off"][s]:desc["seg_reader_off"][s + 1]])
+    assert readers(0) == [0, 1, 2, 3]          # the root is read by every live branch
+    assert readers(2) == [0, 1, 2]             # b: the join (through b0), b1, b2
+    assert readers(1) == [0, 3] and readers(4) == [0, 3] and readers(3) == [0]
+    assert readers(6) == [1] and readers(7) == [2] and readers(8) == [0]
+
+
+def test_segment_decode_is_independent_of_the_segmentation_and_its_order():
+    """Cutting a segment in two (same tokens, other page boundaries) or listing a branch's
+    segments in another order leaves the result alone: softmax over a set of keys."""
+    hq, hkv, d = 2, 1, 16
+    rng = np.random.Generator(np.random.PCG64(72))
+    k_tok, v_tok = rng.standard_normal((50, hkv, d)), rng.standard_normal((50, hkv, d))
+    q = rng.standard_normal((1, hq, d))
+    def build(cuts, order):
+        lens = [b - a for a, b in zip(cuts[:-1], cuts[1:])]
+        npg = [(n + 15) // 16 for n in lens]
+        kp = rng.standard_normal((sum(npg), hkv, d // 8, 16, 8)) * 9
+        vp = rng.standard_normal((sum(npg), hkv, d, 16)) * 9
+        off = np.concatenate([[0], np.cumsum(npg)]).astype(np.int32)
+        for s, (a, b) in enumerate(zip(cuts[:-1], cuts[1:])):
+            for t in range(a, b):
+                kp[off[s] + (t - a) // 16, :, :, (t - a) % 16, :] = k_tok[t].reshape(hkv, d // 8, 8)
+                vp[off[s] + (t - a) // 16, :, :, (t - a) % 16] = v_tok[t]
+        n = len(lens)
+        desc = dict(n_live=1, n_segments=n, page_size=16, seg_page_off=off,
+                    seg_pages=np.arange(sum(npg), dtype=np.int32), seg_len=np.asarray(lens, dtype=np.int32),
+                    seg_reader_off=np.arange(n + 1, dtype=np.int32), seg_readers=np.zeros(n, dtype=np.int32),
+                    branch_seg_off=np.asarray([0, n], dtype=np.int32), branch_segs=np.asarray(order, dtype=np.int32))
+        return orc.attn_decode_segments(desc, q, kp, vp)
+    s = np.einsum("thd,hd->th", np.repeat(k_tok, hq // hkv, axis=1), q[0]) / np.sqrt(d)
+    p = np.exp(s - s.max(axis=0))
+    ref = np.einsum("th,thd->hd", p / p.sum(axis=0), np.repeat(v_tok, hq // hkv, axis=1))
+    for cuts, order in [([0, 50], [0]), ([0, 17, 50], [0, 1]), ([0, 17, 50], [1, 0]), ([0, 1, 16, 33, 50], [2, 0, 3, 1])]:
+        assert np.abs(build(cuts, order)[0] - ref).max() < 1e-12
+
+
+def test_two_level_description_as_segments_gives_the_two_level_result():
+    st = _decode_fixture(blens=(17, 5, 32))
+    kp, vp, q = st["k_pool"].numpy(), st["v_pool"].numpy(), st["q"].numpy()
+    sdesc = dags.segments_from_decode_desc(st["desc"])
+    assert np.array_equal(orc.attn_decode_segments(sdesc, q, kp, vp), orc.attn_decode(st["desc"], q, kp, vp))

@@ -242,6 +242,103 @@ def decode_algorithmic_bytes(desc, hkv, d, elem_bytes=2):
     return toks * hkv * d * 2 * elem_bytes
 
 
+def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q_scale=1.0,
+                          dtype=torch.bfloat16, junk_scale=4.0, spare_pages=3):
+    """Decode state of a general DAG frontier: one KV *segment* per node of every DAG in
+    `dag_list` ((node_len, anc) pairs), stored in its own pages (the last page of a segment is
+    partly filled when the node length is no multiple of the page size; its unused slots hold
+    large random junk that no reader may touch).  `live_list[b]` names the live nodes of DAG b:
+    each is decoding its last token and reads the segments of its ancestors and its own.
+    Segment ids and live-branch ids are global (DAG after DAG).  Returns the pools, the query
+    of every live branch, the token-level q/k/v of every DAG (for a dense cross-check) and the
+    int32 description arrays:
+      seg_page_off/seg_pages/seg_len        pages and token count of each segment
+      seg_reader_off/seg_readers            live branches that read the segment (ascending)
+      branch_seg_off/branch_segs            segments each live branch reads (ascending node id)
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    seg_len, seg_np = [], []
+    for L, _ in dag_list:
+        for x in L:
+            seg_len.append(int(x))
+            seg_np.append((int(x) + PAGE - 1) // PAGE)
+    n_pages = int(np.sum(seg_np)) + spare_pages
+    perm = rng.permutation(n_pages).astype(np.int32)
+    k_pool = normal_tensor(rng, (n_pages, hkv, d // 8, PAGE, 8), junk_scale, dtype)
+    v_pool = normal_tensor(rng, (n_pages, hkv, d, PAGE), junk_scale, dtype)
+    seg_page_off = np.zeros(len(seg_len) + 1, dtype=np.int32)
+    seg_page_off[1:] = np.cumsum(seg_np)
+    seg_pages = perm[:seg_page_off[-1]].copy()
+    readers = [[] for _ in seg_len]
+    branch_segs, q_rows, toks, live_tok = [], [], [], []
+    s0 = 0
+    for (L, anc), live in zip(dag_list, live_list):
+        T = int(np.sum(L))
+        q_tok, k_tok, v_tok = make_qkv(int(rng.integers(1 << 30)), T, hq, hkv, d, 1.0, dtype)
+        q_tok, k_tok, v_tok = q_tok * q_scale, k_tok * kv_scale, v_tok * kv_scale
+        toks.append((q_tok, k_tok, v_tok))
+        start = np.concatenate([[0], np.cumsum(L)]).astype(np.int64)
+        for u, n in enumerate(L):
+            pg = torch.from_numpy(seg_pages[seg_page_off[s0 + u]:seg_page_off[s0 + u + 1]].astype(np.int64))
+            i = torch.arange(int(n))
+            k_pool[pg[i // PAGE], :, :, i % PAGE, :] = k_tok[start[u]:start[u + 1]].reshape(int(n), hkv, d // 8, 8)
+            v_pool[pg[i // PAGE], :, :, i % PAGE] = v_tok[start[u]:start[u + 1]]
+        sets = sets_from_bits(anc)
+        for v in live:
+            r = len(branch_segs)
+            mine = sorted(set(int(u) for u in sets[v]) | {int(v)})
+            branch_segs.append([s0 + u for u in mine])
+            for u in mine:
+                readers[s0 + u].append(r)
+            q_rows.append(q_tok[start[v + 1] - 1])
+            live_tok.append(int(start[v + 1] - 1))
+        s0 += len(L)
+    n_live = len(branch_segs)
+    seg_reader_off = np.zeros(len(seg_len) + 1, dtype=np.int32)
+    seg_reader_off[1:] = np.cumsum([len(x) for x in readers])
+    branch_seg_off = np.zeros(n_live + 1, dtype=np.int32)
+    branch_seg_off[1:] = np.cumsum([len(x) for x in branch_segs])
+    flat = lambda ll: np.asarray([x for l in ll for x in l], dtype=np.int32)
+    desc = dict(
+        n_live=n_live, n_segments=len(seg_len), page_size=PAGE,
+        seg_page_off=seg_page_off, seg_pages=seg_pages.astype(np.int32),
+        seg_len=np.asarray(seg_len, dtype=np.int32),
+        seg_reader_off=seg_reader_off, seg_readers=flat(readers),
+        branch_seg_off=branch_seg_off, branch_segs=flat(branch_segs),
+    )
+    return dict(desc=desc, k_pool=k_pool, v_pool=v_pool, q=torch.stack(q_rows) if q_rows else
+                torch.zeros((0, hq, d), dtype=dtype), tokens=toks, live_tok=live_tok, n_pages=n_pages)
+
+
+def segments_from_decode_desc(desc):
+    """The two-level description of decode_state (shared context + own tokens per branch) written
+    as segments: one per sibling group's shared context, one per live branch."""
+    ng, nl = int(desc["n_groups"]), int(desc["n_live"])
+    gbo = np.asarray(desc["group_branch_off"])
+    sp = np.diff(np.asarray(desc["shared_page_off"]))
+    bp = np.diff(np.asarray(desc["branch_page_off"]))
+    seg_page_off = np.concatenate([[0], np.cumsum(np.concatenate([sp, bp]))]).astype(np.int32)
+    readers = [list(range(int(gbo[g]), int(gbo[g + 1]))) for g in range(ng)] + [[r] for r in range(nl)]
+    group_of = np.searchsorted(gbo, np.arange(nl), side="right") - 1
+    branch_segs = [[int(group_of[r]), ng + r] for r in range(nl)]
+    flat = lambda ll: np.asarray([x for l in ll for x in l], dtype=np.int32)
+    return dict(
+        n_live=nl, n_segments=ng + nl, page_size=PAGE,
+        seg_page_off=seg_page_off,
+        seg_pages=np.concatenate([desc["shared_pages"], desc["branch_pages"]]).astype(np.int32),
+        seg_len=np.concatenate([desc["shared_len"], desc["branch_len"]]).astype(np.int32),
+        seg_reader_off=np.concatenate([[0], np.cumsum([len(x) for x in readers])]).astype(np.int32),
+        seg_readers=flat(readers),
+        branch_seg_off=np.arange(0, 2 * nl + 1, 2, dtype=np.int32), branch_segs=flat(branch_segs),
+    )
+
+
+def decode_segments_algorithmic_bytes(desc, hkv, d, elem_bytes=2):
+    """Bytes one decode step must read: K and V of every segment that has a reader, once."""
+    has = np.diff(np.asarray(desc["seg_reader_off"])) > 0
+    return int(np.sum(np.asarray(desc["seg_len"])[has])) * hkv * d * 2 * elem_bytes
+
+
 # ----------------------------------------------------------------------------- the five configs
 def config(idx):
     """Shapes of the five benchmark configurations (index 0..4)."""
