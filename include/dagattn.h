@@ -219,6 +219,49 @@ int dag_attn_decode(const dag_decode_desc_t* desc, const void* q, const void* k_
                     const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
                     float softmax_scale, void* ws, size_t ws_bytes, void* stream);
 
+/* One decode step over a general DAG frontier, contexts given as lists of KV segments (section
+ * 3.2: a token carries references to cached blocks, not copies; section 4.3: a Fork hands every
+ * child the same context, a Join reads the histories of all its predecessors and the context
+ * before them, without padding or copying).  A segment is a page list with a token count (its last
+ * page may be partly filled) and the list of live branches that read it; a live branch's context
+ * is the union of the segments it reads, e.g. the segments of its ancestors and its own (which
+ * holds the token being decoded).  Any number of sharing levels: a root segment read by all
+ * branches, a mid-level one by a sub-group, an own one by a single branch.  The two relations
+ * (readers of a segment, segments of a branch) must be each other's inverse.
+ * The struct lives on the HOST; arrays are DEVICE int32; pools as for dag_attn_decode.
+ * Appending a branch's new token is dag_kv_append_rope with branch_page_off / branch_pages /
+ * branch_len / branch_pos describing the branches' own (tail) segments. */
+typedef struct {
+  int32_t n_live, n_segments, page_size;
+  int32_t max_seg_pages;  /* HOST upper bound on pages of any segment                            */
+  int32_t max_readers;    /* HOST upper bound on readers of any segment                          */
+  int32_t total_readers;  /* HOST: seg_reader_off[n_segments] (= branch_seg_off[n_live])         */
+  const int32_t* seg_page_off;   /* [n_segments+1] into seg_pages                               */
+  const int32_t* seg_pages;      /* page ids of each segment, in token order                    */
+  const int32_t* seg_len;        /* [n_segments] tokens in the segment (0 allowed)              */
+  const int32_t* seg_reader_off; /* [n_segments+1] into seg_readers                             */
+  const int32_t* seg_readers;    /* live branches reading each segment, each once, any order    */
+  const int32_t* branch_seg_off; /* [n_live+1] into branch_segs                                 */
+  const int32_t* branch_segs;    /* segments read by each live branch, each once, any order     */
+} dag_decode_seg_desc_t;
+
+/* Bytes of DEVICE workspace dag_attn_decode_segments needs for this description (0 on bad
+ * arguments). */
+size_t dag_decode_segments_workspace_bytes(const dag_decode_seg_desc_t* desc, int32_t hq, int32_t hkv,
+                                           int32_t head_dim);
+
+/* Attention of every live branch's query over the tokens of the segments it reads: Eq. 2 with
+ * membership as the only mask.  Every segment is streamed once per 32 stacked query rows of its
+ * readers (readers x hq/hkv rows per KV head), in slices, and the partial results of a branch are
+ * combined by log-sum-exp.  q/out [n_live][hq][head_dim] bf16 DEVICE, q already rotated; a branch
+ * that reads no token gets zeros.  head_dim 128 or 64, page_size 16, hq a multiple of hkv with
+ * hq/hkv <= 32.  Errors as dag_attn_decode; the host bounds are trusted (a reader list longer
+ * than max_readers loses rows, entries past total_readers are dropped).  Everything is enqueued
+ * on `stream`; the call allocates nothing and does not synchronise. */
+int dag_attn_decode_segments(const dag_decode_seg_desc_t* desc, const void* q, const void* k_pool,
+                             const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
+                             float softmax_scale, void* ws, size_t ws_bytes, void* stream);
+
 const char* dag_strerror(int code);
 int dag_version(void);
 

@@ -62,6 +62,16 @@ class dag_decode_desc_t(C.Structure):
                 ("branch_len", C.c_void_p), ("branch_pos", C.c_void_p)]
 
 
+_SEG_ARRAYS = ("seg_page_off", "seg_pages", "seg_len", "seg_reader_off", "seg_readers", "branch_seg_off",
+               "branch_segs")
+
+
+class dag_decode_seg_desc_t(C.Structure):
+    _fields_ = ([("n_live", C.c_int32), ("n_segments", C.c_int32), ("page_size", C.c_int32),
+                 ("max_seg_pages", C.c_int32), ("max_readers", C.c_int32), ("total_readers", C.c_int32)] +
+                [(name, C.c_void_p) for name in _SEG_ARRAYS])
+
+
 _lib = None
 
 
@@ -89,12 +99,16 @@ def lib():
         L.dag_decode_workspace_bytes.restype = C.c_size_t
         L.dag_attn_decode.argtypes = [C.POINTER(dag_decode_desc_t), vp, vp, vp, vp, i32, i32, i32, f32,
                                       vp, C.c_size_t, vp]
+        L.dag_decode_segments_workspace_bytes.argtypes = [C.POINTER(dag_decode_seg_desc_t), i32, i32, i32]
+        L.dag_decode_segments_workspace_bytes.restype = C.c_size_t
+        L.dag_attn_decode_segments.argtypes = [C.POINTER(dag_decode_seg_desc_t), vp, vp, vp, vp, i32, i32, i32, f32,
+                                               vp, C.c_size_t, vp]
         L.dag_strerror.argtypes = [C.c_int]
         L.dag_strerror.restype = C.c_char_p
         L.dag_version.restype = C.c_int
         for name in ("dag_prefill_tile_shape", "dag_meta_sizes", "dag_build_meta", "dag_rope_qk",
                      "dag_attn_prefill", "dag_attn_prefill_prepared", "dag_prefill_prepare_v",
-                     "dag_kv_append_rope", "dag_attn_decode"):
+                     "dag_kv_append_rope", "dag_attn_decode", "dag_attn_decode_segments"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -273,3 +287,35 @@ def dag_attn_decode(ddesc, q, k_pool, v_pool, out, workspace, softmax_scale=None
         softmax_scale = 1.0 / float(d) ** 0.5
     _check(lib().dag_attn_decode(C.byref(ddesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(out), hq, hkv, d,
                                  float(softmax_scale), _ptr(workspace), workspace.numel(), _stream()))
+
+
+class SegDecodeDesc:
+    """Device copies of the segment-form decode description arrays + the ctypes struct."""
+
+    def __init__(self, desc, device):
+        self.t = {}
+        for name in _SEG_ARRAYS:
+            arr = np.ascontiguousarray(desc[name], dtype=np.int32)
+            if arr.size == 0:
+                arr = np.zeros(1, dtype=np.int32)
+            self.t[name] = torch.from_numpy(arr).to(device)
+        ns, nl = int(desc["n_segments"]), int(desc["n_live"])
+        sp = np.diff(np.asarray(desc["seg_page_off"])) if ns else np.zeros(0)
+        rd = np.diff(np.asarray(desc["seg_reader_off"])) if ns else np.zeros(0)
+        self.c = dag_decode_seg_desc_t(nl, ns, int(desc["page_size"]),
+                                       int(sp.max()) if sp.size else 0, int(rd.max()) if rd.size else 0,
+                                       int(rd.sum()) if rd.size else 0,
+                                       *[self.t[n].data_ptr() for n in _SEG_ARRAYS])
+
+
+def dag_decode_segments_workspace_bytes(sdesc, hq, hkv, head_dim):
+    return int(lib().dag_decode_segments_workspace_bytes(C.byref(sdesc.c), hq, hkv, head_dim))
+
+
+def dag_attn_decode_segments(sdesc, q, k_pool, v_pool, out, workspace, softmax_scale=None):
+    n_live, hq, d = q.shape
+    hkv = k_pool.shape[1]
+    if softmax_scale is None:
+        softmax_scale = 1.0 / float(d) ** 0.5
+    _check(lib().dag_attn_decode_segments(C.byref(sdesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(out), hq, hkv,
+                                          d, float(softmax_scale), _ptr(workspace), workspace.numel(), _stream()))

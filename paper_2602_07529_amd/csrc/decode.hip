@@ -55,6 +55,28 @@ struct DecodeArgs {
   float scale;
 };
 
+// Decode over lists of KV segments: a segment is a page list with a token count and the set of
+// live branches that read it; a branch's context is the union of the segments it reads.
+struct SegArgs {
+  const int32_t* seg_page_off;
+  const int32_t* seg_pages;
+  const int32_t* seg_len;
+  const int32_t* seg_reader_off;
+  const int32_t* seg_readers;
+  const int32_t* branch_seg_off;
+  const int32_t* branch_segs;
+  const uint16_t* q;
+  const uint16_t* k_pool;
+  const uint16_t* v_pool;
+  uint16_t* out;
+  float* part_o;   // [splits][total_readers][hq][D]
+  float* part_ml;  // [splits][total_readers][hq][2]
+  int n_segments, n_live, hq, hkv, G;
+  int rb_max;      // 32-row blocks per (segment, kv head)
+  int chunk, splits, total_readers;
+  float sc, th;
+};
+
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -75,8 +97,8 @@ struct KVBlock {           // one 32-key block (2 pages) in operand layout
 
 // pgv: page ids of the item's slice, lane i holds page p0 + (i % 64) of the current 64-page window
 // (fetched once per window, so that no page-table load sits in front of every K/V load)
-template <int D>
-__device__ __forceinline__ void load_block(KVBlock<D>& blk, const DecodeArgs& a, int pgv, int pb_rel, int last_rel,
+template <int D, typename A>
+__device__ __forceinline__ void load_block(KVBlock<D>& blk, const A& a, int pgv, int pb_rel, int last_rel,
                                            int hk, int L, int H, int kpage_sel, int kslot) {
   const int pg0 = __builtin_amdgcn_readlane(pgv, pb_rel & 63);
   const int pg1 = __builtin_amdgcn_readlane(pgv, min(pb_rel + 1, last_rel) & 63);
@@ -166,6 +188,55 @@ __device__ __forceinline__ void compute_block(const KVBlock<D>& blk, QF&& qop, f
   block_pv<D>(blk.v[0], blk.v[1], pb0, pb1, O);
 }
 
+// The loop of a single-wave work item: pages [p0, p1) of one page list, 32 keys (two pages) per
+// step, the next block's loads in flight while the current one is computed.  `len` is the token
+// count of the whole list (keys at or past it are masked).  Leaves the un-normalised partial
+// (O, reference maximum m, row sum l of this lane's half) in registers.
+template <int D, typename A, typename QF>
+__device__ __forceinline__ void stream_slice(const A& a, const int32_t* pages, int p0, int p1, int len, int hk,
+                                             int lane, QF&& qop, f32x16* O, float& m, float& l) {
+  const int L = lane & 31, H = lane >> 5;
+  const int kr = key_of_row(L);
+  const int kpage_sel = kr >> 4, kslot = kr & 15;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
+  m = -1e30f;
+  l = 0.f;
+
+  // Page ids in windows of 64 (lane i: page p0 + 64 w + i); a block never straddles a window
+  // because windows and blocks both start at even offsets.
+  const int np = p1 - p0;
+  int pgv = pages[p0 + min(lane, np - 1)];
+  asm volatile("" ::"v"(pgv));  // arrived: a wait for it inside the loop would also wait for the K/V loads in flight
+  KVBlock<D> b0, b1;
+  load_block<D>(b0, a, pgv, 0, np - 1, hk, L, H, kpage_sel, kslot);
+  int pb = 0;  // relative to p0
+  while (true) {
+    if (pb + 2 < np) {
+      if (((pb + 2) & 63) == 0) {
+        pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
+        asm volatile("" ::"v"(pgv));
+      }
+      load_block<D>(b1, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
+    }
+    compute_block<D>(b0, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
+    pb += 2;
+    if (pb >= np) break;
+    if (pb + 2 < np) {
+      if (((pb + 2) & 63) == 0) {
+        pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
+        asm volatile("" ::"v"(pgv));
+      }
+      load_block<D>(b0, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
+    }
+    compute_block<D>(b1, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
+    pb += 2;
+    if (pb >= np) break;
+  }
+}
+
 template <int D>
 __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
   __shared__ bf16x8 qs_all[(D / 16) * 64];
@@ -228,46 +299,9 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
     for (int s = 0; s < D / 16; ++s) qs_all[s * 64 + lane] = *(const bf16x8*)(qp + 16 * s);
   }
   auto qop = [&](int s) { return qf[s * 64]; };
-  const int kr = key_of_row(L);
-  const int kpage_sel = kr >> 4, kslot = kr & 15;
-
   f32x16 O[D / 32];
-#pragma unroll
-  for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
-  float m = -1e30f, l = 0.f;
-
-  // Page ids in windows of 64 (lane i: page p0 + 64 w + i); a block never straddles a window
-  // because windows and blocks both start at even offsets.
-  const int np = p1 - p0;
-  int pgv = pages[p0 + min(lane, np - 1)];
-  asm volatile("" ::"v"(pgv));  // arrived: a wait for it inside the loop would also wait for the K/V loads in flight
-  KVBlock<D> b0, b1;
-  load_block<D>(b0, a, pgv, 0, np - 1, hk, L, H, kpage_sel, kslot);
-  int pb = 0;  // relative to p0
-  while (true) {
-    if (pb + 2 < np) {
-      if (((pb + 2) & 63) == 0) {
-        pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
-        asm volatile("" ::"v"(pgv));
-      }
-      load_block<D>(b1, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
-    }
-    compute_block<D>(b0, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
-    pb += 2;
-    if (pb >= np) break;
-    if (pb + 2 < np) {
-      if (((pb + 2) & 63) == 0) {
-        pgv = pages[p0 + min(pb + 2 + lane, np - 1)];
-        asm volatile("" ::"v"(pgv));
-      }
-      load_block<D>(b0, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
-    }
-    compute_block<D>(b1, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
-    pb += 2;
-    if (pb >= np) break;
-  }
+  float m, l;
+  stream_slice<D>(a, pages, p0, p1, len, hk, lane, qop, O, m, l);
 
   const float l_tot = l + __shfl_xor(l, 32);
   if (row_ok) {
@@ -282,6 +316,107 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
       pml[0] = m;
       pml[1] = l_tot;
     }
+  }
+}
+
+// Segment form: one wave per (segment, kv head, 32-row block of the stacked query rows of the
+// segment's readers, page split).  Row j * G + g of a segment is query head hk * G + g of its j-th
+// reader; the partial of a row goes to the reader's entry in the reader list, so the combination
+// step finds it without knowing the row block.  Items past the segment's pages or rows exit.
+template <int D>
+__global__ void __launch_bounds__(64, 2) k_decode_seg(SegArgs a) {
+  __shared__ bf16x8 qs_all[(D / 16) * 64];
+  const int lane = threadIdx.x, L = lane & 31, H = lane >> 5;
+  int x = blockIdx.x;
+  const int split = x % a.splits; x /= a.splits;
+  const int rb = x % a.rb_max; x /= a.rb_max;
+  const int hk = x % a.hkv;
+  const int s = x / a.hkv;
+  const int len = a.seg_len[s];
+  const int e0 = a.seg_reader_off[s];
+  const int nrows = (a.seg_reader_off[s + 1] - e0) * a.G, row0 = rb * 32;
+  const int npages = (len + PAGE - 1) / PAGE;
+  const int p0 = split * a.chunk, p1 = min(p0 + a.chunk, npages);
+  if (p0 >= p1 || row0 >= nrows) return;
+  const int row = row0 + L;
+  const bool row_ok = row < nrows;
+  const int rr = row_ok ? row : row0;
+  const int entry = e0 + rr / a.G, head = hk * a.G + rr % a.G;
+  const int br = min(max(a.seg_readers[entry], 0), a.n_live - 1);
+  const bool store_ok = row_ok && entry < a.total_readers;  // (a reader list longer than announced: no partial)
+
+  const bf16x8* qf = qs_all + lane;
+  {
+    const uint16_t* qp = a.q + ((size_t)br * a.hq + head) * D + 8 * H;
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t) qs_all[t * 64 + lane] = *(const bf16x8*)(qp + 16 * t);
+  }
+  auto qop = [&](int t) { return qf[t * 64]; };
+  f32x16 O[D / 32];
+  float m, l;
+  stream_slice<D>(a, a.seg_pages + a.seg_page_off[s], p0, p1, len, hk, lane, qop, O, m, l);
+
+  const float l_tot = l + __shfl_xor(l, 32);
+  if (store_ok) {
+    const size_t base = ((size_t)split * a.total_readers + entry) * a.hq + head;
+    float* po = a.part_o + base * D;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 o = {O[db][4 * r4], O[db][4 * r4 + 1], O[db][4 * r4 + 2], O[db][4 * r4 + 3]};
+        *(f32x4*)(po + 32 * db + 8 * r4 + 4 * H) = o;
+      }
+    if (H == 0) {
+      a.part_ml[base * 2] = m;
+      a.part_ml[base * 2 + 1] = l_tot;
+    }
+  }
+}
+
+// One wave per (branch, query head): log-sum-exp combination over the splits of every segment the
+// branch reads.  The branch's entry in a segment's reader list is found by a wave-wide search
+// (a segment missing the branch among its readers contributes nothing).  A branch without any
+// key gets zeros.
+template <int D>
+__global__ void __launch_bounds__(64) k_decode_seg_merge(SegArgs a) {
+  const int r = blockIdx.x / a.hq, head = blockIdx.x % a.hq;
+  const int lane = threadIdx.x;
+  constexpr int PER = D / 64;  // output elements per lane
+  float acc[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+  float mx = -1e30f, lsum = 0.f;
+  for (int e = a.branch_seg_off[r]; e < a.branch_seg_off[r + 1]; ++e) {
+    const int s = a.branch_segs[e];
+    if (s < 0 || s >= a.n_segments) continue;
+    const int e0 = a.seg_reader_off[s], n = a.seg_reader_off[s + 1] - e0;
+    int entry = -1;
+    for (int b = 0; b < n && entry < 0; b += 64) {
+      const unsigned long long hit = __builtin_amdgcn_ballot_w64(b + lane < n && a.seg_readers[e0 + b + lane] == r);
+      if (hit) entry = e0 + b + __builtin_ctzll(hit);
+    }
+    if (entry < 0 || entry >= a.total_readers) continue;
+    const int npages = (a.seg_len[s] + PAGE - 1) / PAGE;
+    const int nsplit = min((npages + a.chunk - 1) / a.chunk, a.splits);
+    for (int sp = 0; sp < nsplit; ++sp) {
+      const size_t base = ((size_t)sp * a.total_readers + entry) * a.hq + head;
+      const float ms = a.part_ml[base * 2], ls = a.part_ml[base * 2 + 1];
+      if (!(ls > 0.f)) continue;
+      const float mn = fmaxf(mx, ms);
+      const float keep = __builtin_amdgcn_exp2f((mx - mn) * a.sc), wgt = __builtin_amdgcn_exp2f((ms - mn) * a.sc);
+      mx = mn;
+      lsum = lsum * keep + ls * wgt;
+#pragma unroll
+      for (int t = 0; t < PER; ++t) acc[t] = acc[t] * keep + wgt * a.part_o[base * D + lane * PER + t];
+    }
+  }
+  const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+  uint16_t* o = a.out + ((size_t)r * a.hq + head) * D + lane * PER;
+  if (PER == 2) {
+    *(uint32_t*)o = dag_pack_bf2(acc[0] * inv, acc[PER - 1] * inv);
+  } else {
+    o[0] = (uint16_t)dag_f2bf(acc[0] * inv);
   }
 }
 
@@ -740,6 +875,106 @@ extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const 
   }
   if (head_dim == 128) hipLaunchKernelGGL(k_decode_merge<128>, dim3(nout), dim3(64), 0, stream, a);
   else hipLaunchKernelGGL(k_decode_merge<64>, dim3(nout), dim3(64), 0, stream, a);
+  DAG_LAUNCH_CHECK();
+  return DAG_OK;
+}
+
+namespace {
+
+struct SegPlan {
+  int rb_max, chunk, splits;
+  long items;
+  size_t off_o, off_ml, bytes;
+};
+
+// One split size for all segments (their lengths live in device memory): as long as possible
+// while the launch still has about a thousand items if every segment were the longest one.
+int make_seg_plan(const dag_decode_seg_desc_t* d, int hq, int hkv, int D, SegPlan* p) {
+  if (!d) return DAG_ERR_NULL;
+  if (d->n_live < 0 || d->n_segments < 0 || d->max_seg_pages < 0 || d->max_readers < 0 || d->total_readers < 0)
+    return DAG_ERR_BAD_LEN;
+  if (d->page_size != PAGE) return DAG_ERR_UNSUPPORTED;
+  if (hq < 1 || hkv < 1 || hq % hkv != 0 || hq / hkv > 32) return DAG_ERR_UNSUPPORTED;
+  if (D != 64 && D != 128) return DAG_ERR_UNSUPPORTED;
+  const int G = hq / hkv;
+  p->rb_max = (int)dag_ceil_div((int64_t)d->max_readers * G, 32);
+  if (p->rb_max < 1) p->rb_max = 1;
+  int c = env_int("DAGATTN_DECODE_CHUNK_SEG", 128);
+  c += c & 1;
+  const int64_t base = (int64_t)d->n_segments * hkv * p->rb_max;
+  if (!getenv("DAGATTN_DECODE_CHUNK_SEG"))
+    while (c > 8 && base * dag_ceil_div(d->max_seg_pages, c) < 1024) c /= 2;
+  p->chunk = c;
+  p->splits = d->max_seg_pages > 0 ? (int)dag_ceil_div(d->max_seg_pages, c) : 0;
+  const int64_t items = base * p->splits;
+  if (items > INT32_MAX) return DAG_ERR_UNSUPPORTED;
+  p->items = (long)items;
+  size_t off = 0;
+  const size_t rows = (size_t)p->splits * (size_t)d->total_readers * hq;
+  p->off_o = off;  off += dag_align_up(rows * D * 4, 256);
+  p->off_ml = off; off += dag_align_up(rows * 2 * 4, 256);
+  p->bytes = off + 256;
+  return DAG_OK;
+}
+
+}  // namespace
+
+extern "C" size_t dag_decode_segments_workspace_bytes(const dag_decode_seg_desc_t* desc, int32_t hq, int32_t hkv,
+                                                      int32_t head_dim) {
+  SegPlan p;
+  if (make_seg_plan(desc, hq, hkv, head_dim, &p) != DAG_OK) return 0;
+  return p.bytes;
+}
+
+extern "C" int dag_attn_decode_segments(const dag_decode_seg_desc_t* d, const void* q, const void* k_pool,
+                                        const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
+                                        float softmax_scale, void* ws, size_t ws_bytes, void* stream_) {
+  SegPlan p;
+  const int rc = make_seg_plan(d, hq, hkv, head_dim, &p);
+  if (rc != DAG_OK) return rc;
+  if (d->n_live == 0) return DAG_OK;
+  if (!q || !k_pool || !v_pool || !out || !d->branch_seg_off || !d->branch_segs) return DAG_ERR_NULL;
+  if (d->n_segments > 0 &&
+      (!d->seg_page_off || !d->seg_pages || !d->seg_len || !d->seg_reader_off || !d->seg_readers))
+    return DAG_ERR_NULL;
+  if (!dag_aligned16(q) || !dag_aligned16(k_pool) || !dag_aligned16(v_pool) || !dag_aligned16(out))
+    return DAG_ERR_ALIGN;
+  if (!ws || ws_bytes < p.bytes) return DAG_ERR_WORKSPACE;
+  char* base = (char*)dag_align_up((size_t)(uintptr_t)ws, 256);
+  SegArgs a;
+  a.seg_page_off = d->seg_page_off;
+  a.seg_pages = d->seg_pages;
+  a.seg_len = d->seg_len;
+  a.seg_reader_off = d->seg_reader_off;
+  a.seg_readers = d->seg_readers;
+  a.branch_seg_off = d->branch_seg_off;
+  a.branch_segs = d->branch_segs;
+  a.q = (const uint16_t*)q;
+  a.k_pool = (const uint16_t*)k_pool;
+  a.v_pool = (const uint16_t*)v_pool;
+  a.out = (uint16_t*)out;
+  a.part_o = (float*)(base + p.off_o);
+  a.part_ml = (float*)(base + p.off_ml);
+  a.n_segments = d->n_segments;
+  a.n_live = d->n_live;
+  a.hq = hq;
+  a.hkv = hkv;
+  a.G = hq / hkv;
+  a.rb_max = p.rb_max;
+  a.chunk = p.chunk;
+  a.splits = p.splits;
+  a.total_readers = d->total_readers;
+  a.sc = softmax_scale * 1.4426950408889634f;
+  a.th = 8.f / a.sc;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (p.items > 0) {
+    if (head_dim == 128) hipLaunchKernelGGL(k_decode_seg<128>, dim3((unsigned)p.items), dim3(64), 0, stream, a);
+    else hipLaunchKernelGGL(k_decode_seg<64>, dim3((unsigned)p.items), dim3(64), 0, stream, a);
+    DAG_LAUNCH_CHECK();
+  }
+  const unsigned nout = (unsigned)(d->n_live * hq);
+  if (head_dim == 128) hipLaunchKernelGGL(k_decode_seg_merge<128>, dim3(nout), dim3(64), 0, stream, a);
+  else hipLaunchKernelGGL(k_decode_seg_merge<64>, dim3(nout), dim3(64), 0, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }

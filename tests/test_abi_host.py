@@ -26,6 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert {"dag_meta_sizes", "dag_build_meta", "dag_rope_qk", "dag_attn_prefill", "dag_kv_append_rope",
             "dag_attn_decode", "dag_decode_workspace_bytes", "dag_prefill_workspace_bytes", "dag_prefill_tile_shape",
             "dag_prefill_prepare_v", "dag_attn_prefill_prepared",
+            "dag_attn_decode_segments", "dag_decode_segments_workspace_bytes",
             "dag_strerror",
             "dag_version"} <= set(names)
     L = C.CDLL(B.LIB_PATH)
@@ -188,3 +189,29 @@ def test_decode_argument_errors():
     empty = B.dag_decode_desc_t(0, 0, 16, 0, 0, 0, *([0] * 8))
     assert L.dag_attn_decode(C.byref(empty), p, p, p, p, 32, 8, 128, 0.1, None, 0, None) == 0
     assert L.dag_kv_append_rope(C.byref(empty), p, p, p, p, 8, 128, 1e4, None) == 0
+
+
+def test_segment_decode_argument_errors():
+    L = B.lib()
+    sd = B.dag_decode_seg_desc_t(4, 3, 16, 40, 4, 6, *([FAKE] * 7))
+    p = C.c_void_p(FAKE)
+    need = L.dag_decode_segments_workspace_bytes(C.byref(sd), 32, 8, 128)
+    # 40 pages, 3 x 8 x 1 items per split: the split size halves from 128 pages to 8 -> 5 splits
+    assert need >= 5 * 6 * 32 * (128 + 2) * 4
+    args = (32, 8, 128, 0.1)
+    assert L.dag_attn_decode_segments(C.byref(sd), p, p, p, p, *args, p, need - 1, None) == -6
+    assert L.dag_attn_decode_segments(C.byref(sd), p, p, p, p, *args, None, need, None) == -6
+    assert L.dag_attn_decode_segments(C.byref(sd), p, p, p, p, 32, 8, 96, 0.1, p, need, None) == -7
+    assert L.dag_attn_decode_segments(C.byref(sd), p, p, p, p, 30, 8, 128, 0.1, p, need, None) == -7
+    assert L.dag_attn_decode_segments(C.byref(sd), None, p, p, p, *args, p, need, None) == -1
+    assert L.dag_attn_decode_segments(C.byref(sd), C.c_void_p(FAKE + 2), p, p, p, *args, p, need, None) == -8
+    assert L.dag_attn_decode_segments(None, p, p, p, p, *args, p, need, None) == -1
+    bad_page = B.dag_decode_seg_desc_t(4, 3, 32, 40, 4, 6, *([FAKE] * 7))
+    assert L.dag_attn_decode_segments(C.byref(bad_page), p, p, p, p, *args, p, need, None) == -7
+    assert L.dag_decode_segments_workspace_bytes(C.byref(bad_page), 32, 8, 128) == 0
+    neg = B.dag_decode_seg_desc_t(4, 3, 16, -1, 4, 6, *([FAKE] * 7))
+    assert L.dag_attn_decode_segments(C.byref(neg), p, p, p, p, *args, p, need, None) == -2
+    no_arrays = B.dag_decode_seg_desc_t(4, 3, 16, 40, 4, 6, *([0] * 7))
+    assert L.dag_attn_decode_segments(C.byref(no_arrays), p, p, p, p, *args, p, need, None) == -1
+    empty = B.dag_decode_seg_desc_t(0, 0, 16, 0, 0, 0, *([0] * 7))
+    assert L.dag_attn_decode_segments(C.byref(empty), p, p, p, p, *args, None, 0, None) == 0
