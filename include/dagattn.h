@@ -226,8 +226,9 @@ int dag_attn_decode(const dag_decode_desc_t* desc, const void* q, const void* k_
  * page may be partly filled) and the list of live branches that read it; a live branch's context
  * is the union of the segments it reads, e.g. the segments of its ancestors and its own (which
  * holds the token being decoded).  Any number of sharing levels: a root segment read by all
- * branches, a mid-level one by a sub-group, an own one by a single branch.  The two relations
- * (readers of a segment, segments of a branch) must be each other's inverse.
+ * branches, a mid-level one by a sub-group, an own one by a single branch.  Each branch also
+ * lists where it appears in the reader lists (the inverse relation, as positions in seg_readers):
+ * that is how its partial results are found.
  * The struct lives on the HOST; arrays are DEVICE int32; pools as for dag_attn_decode.
  * Appending a branch's new token is dag_kv_append_rope with branch_page_off / branch_pages /
  * branch_len / branch_pos describing the branches' own (tail) segments. */
@@ -235,14 +236,15 @@ typedef struct {
   int32_t n_live, n_segments, page_size;
   int32_t max_seg_pages;  /* HOST upper bound on pages of any segment                            */
   int32_t max_readers;    /* HOST upper bound on readers of any segment                          */
-  int32_t total_readers;  /* HOST: seg_reader_off[n_segments] (= branch_seg_off[n_live])         */
+  int32_t total_readers;  /* HOST: seg_reader_off[n_segments] (= branch_entry_off[n_live])       */
   const int32_t* seg_page_off;   /* [n_segments+1] into seg_pages                               */
   const int32_t* seg_pages;      /* page ids of each segment, in token order                    */
   const int32_t* seg_len;        /* [n_segments] tokens in the segment (0 allowed)              */
   const int32_t* seg_reader_off; /* [n_segments+1] into seg_readers                             */
   const int32_t* seg_readers;    /* live branches reading each segment, each once, any order    */
-  const int32_t* branch_seg_off; /* [n_live+1] into branch_segs                                 */
-  const int32_t* branch_segs;    /* segments read by each live branch, each once, any order     */
+  const int32_t* branch_entry_off; /* [n_live+1] into branch_entries                            */
+  const int32_t* branch_entries; /* for each live branch r: the positions e in seg_readers with
+                                    seg_readers[e] == r, one per segment it reads, any order    */
 } dag_decode_seg_desc_t;
 
 /* Bytes of DEVICE workspace dag_attn_decode_segments needs for this description (0 on bad

@@ -62,8 +62,8 @@ class dag_decode_desc_t(C.Structure):
                 ("branch_len", C.c_void_p), ("branch_pos", C.c_void_p)]
 
 
-_SEG_ARRAYS = ("seg_page_off", "seg_pages", "seg_len", "seg_reader_off", "seg_readers", "branch_seg_off",
-               "branch_segs")
+_SEG_ARRAYS = ("seg_page_off", "seg_pages", "seg_len", "seg_reader_off", "seg_readers", "branch_entry_off",
+               "branch_entries")
 
 
 class dag_decode_seg_desc_t(C.Structure):

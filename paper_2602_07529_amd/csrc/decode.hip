@@ -57,20 +57,27 @@ struct DecodeArgs {
 
 // Decode over lists of KV segments: a segment is a page list with a token count and the set of
 // live branches that read it; a branch's context is the union of the segments it reads.
+struct SegItem {  // one work item: a slice of a segment's pages against one 32-row block of its readers' rows
+  int32_t page_off, len, e0, nrows, row0, split, pad0, pad1;
+};
 struct SegArgs {
   const int32_t* seg_page_off;
   const int32_t* seg_pages;
   const int32_t* seg_len;
   const int32_t* seg_reader_off;
   const int32_t* seg_readers;
-  const int32_t* branch_seg_off;
-  const int32_t* branch_segs;
+  const int32_t* branch_entry_off;
+  const int32_t* branch_entries;
   const uint16_t* q;
   const uint16_t* k_pool;
   const uint16_t* v_pool;
   uint16_t* out;
   float* part_o;   // [splits][total_readers][hq][D]
   float* part_ml;  // [splits][total_readers][hq][2]
+  SegItem* items;        // [item_cap] compact list of (segment, row block, slice), written by k_seg_plan
+  int32_t* item_total;   // number of list entries
+  int32_t* entry_nsplit; // [total_readers] slices of the segment of each reader-list entry
+  int item_cap;
   int n_segments, n_live, hq, hkv, G;
   int rb_max;      // 32-row blocks per (segment, kv head)
   int chunk, splits, total_readers;
@@ -319,31 +326,78 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
   }
 }
 
-// Segment form: one wave per (segment, kv head, 32-row block of the stacked query rows of the
-// segment's readers, page split).  Row j * G + g of a segment is query head hk * G + g of its j-th
-// reader; the partial of a row goes to the reader's entry in the reader list, so the combination
-// step finds it without knowing the row block.  Items past the segment's pages or rows exit.
+// Segment form, step 1: the work items.  Segment lengths and reader counts live in device memory,
+// so a launch sized by the host bounds would consist mostly of items that find nothing to do, and
+// those cost time even when they exit at once (they sit between the real items in the dispatch
+// order and hold wave slots while their loads return).  One workgroup therefore writes the compact
+// list: for every segment, in the caller's order, its slices x row blocks (exclusive scan of the
+// counts), and for every reader-list entry the number of slices its segment has.
+constexpr int PLAN_THREADS = 1024;
+__global__ void __launch_bounds__(PLAN_THREADS) k_seg_plan(SegArgs a) {
+  __shared__ int s_wave[PLAN_THREADS / 64];
+  __shared__ int s_carry;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < a.n_segments; base += PLAN_THREADS) {
+    const int s = base + tid;
+    int len = 0, e0 = 0, nr = 0, nsp = 0, rbs = 0;
+    if (s < a.n_segments) {
+      len = max(a.seg_len[s], 0);
+      e0 = a.seg_reader_off[s];
+      nr = max(a.seg_reader_off[s + 1] - e0, 0);
+      const int npages = (len + PAGE - 1) / PAGE;
+      nsp = min((npages + a.chunk - 1) / a.chunk, a.splits);
+      rbs = min((nr * a.G + 31) / 32, a.rb_max);
+    }
+    const int cnt = nsp * rbs;
+    int incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) s_wave[w] = incl;
+    __syncthreads();
+    int start = s_carry + incl - cnt;
+    for (int i = 0; i < w; ++i) start += s_wave[i];
+    if (s < a.n_segments) {
+      int k = start;
+      for (int sp = nsp - 1; sp >= 0; --sp)
+        for (int rb = 0; rb < rbs; ++rb, ++k)
+          if (k < a.item_cap) a.items[k] = SegItem{a.seg_page_off[s], len, e0, nr * a.G, rb * 32, sp, 0, 0};
+      for (int e = e0; e < e0 + nr; ++e)
+        if (e >= 0 && e < a.total_readers) a.entry_nsplit[e] = nsp;
+    }
+    __syncthreads();
+    if (tid == PLAN_THREADS - 1) s_carry = min(start + cnt, a.item_cap);
+    __syncthreads();
+  }
+  if (tid == 0) *a.item_total = s_carry;
+}
+
+// Step 2: one wave per (work item, kv head).  Row j * G + g of a segment is query head hk * G + g
+// of its j-th reader; the partial of a row goes to the reader's entry in the reader list, which is
+// where the combination step looks for it.  The launch covers the host's bound on the list; the
+// workgroups past its end exit.
 template <int D>
 __global__ void __launch_bounds__(64, 2) k_decode_seg(SegArgs a) {
   __shared__ bf16x8 qs_all[(D / 16) * 64];
   const int lane = threadIdx.x, L = lane & 31, H = lane >> 5;
-  int x = blockIdx.x;
-  const int split = x % a.splits; x /= a.splits;
-  const int rb = x % a.rb_max; x /= a.rb_max;
-  const int hk = x % a.hkv;
-  const int s = x / a.hkv;
-  const int len = a.seg_len[s];
-  const int e0 = a.seg_reader_off[s];
-  const int nrows = (a.seg_reader_off[s + 1] - e0) * a.G, row0 = rb * 32;
+  const int hk = blockIdx.x % a.hkv, idx = blockIdx.x / a.hkv;
+  if (idx >= *a.item_total) return;
+  const SegItem it = a.items[idx];
+  const int len = it.len, e0 = it.e0, nrows = it.nrows, row0 = it.row0, split = it.split;
   const int npages = (len + PAGE - 1) / PAGE;
   const int p0 = split * a.chunk, p1 = min(p0 + a.chunk, npages);
-  if (p0 >= p1 || row0 >= nrows) return;
+  if (row0 >= nrows || p0 >= p1) return;  // (never listed)
   const int row = row0 + L;
   const bool row_ok = row < nrows;
   const int rr = row_ok ? row : row0;
   const int entry = e0 + rr / a.G, head = hk * a.G + rr % a.G;
-  const int br = min(max(a.seg_readers[entry], 0), a.n_live - 1);
   const bool store_ok = row_ok && entry < a.total_readers;  // (a reader list longer than announced: no partial)
+  const size_t pbase = ((size_t)split * a.total_readers + entry) * a.hq + head;
+  const int br = min(max(a.seg_readers[entry], 0), a.n_live - 1);
 
   const bf16x8* qf = qs_all + lane;
   {
@@ -354,12 +408,11 @@ __global__ void __launch_bounds__(64, 2) k_decode_seg(SegArgs a) {
   auto qop = [&](int t) { return qf[t * 64]; };
   f32x16 O[D / 32];
   float m, l;
-  stream_slice<D>(a, a.seg_pages + a.seg_page_off[s], p0, p1, len, hk, lane, qop, O, m, l);
+  stream_slice<D>(a, a.seg_pages + it.page_off, p0, p1, len, hk, lane, qop, O, m, l);
 
   const float l_tot = l + __shfl_xor(l, 32);
   if (store_ok) {
-    const size_t base = ((size_t)split * a.total_readers + entry) * a.hq + head;
-    float* po = a.part_o + base * D;
+    float* po = a.part_o + pbase * D;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -368,15 +421,17 @@ __global__ void __launch_bounds__(64, 2) k_decode_seg(SegArgs a) {
         *(f32x4*)(po + 32 * db + 8 * r4 + 4 * H) = o;
       }
     if (H == 0) {
-      a.part_ml[base * 2] = m;
-      a.part_ml[base * 2 + 1] = l_tot;
+      a.part_ml[pbase * 2] = m;
+      a.part_ml[pbase * 2 + 1] = l_tot;
     }
   }
 }
 
-// One wave per (branch, query head): log-sum-exp combination over the splits of every segment the
-// branch reads.  The branch's entry in a segment's reader list is found by a wave-wide search
-// (a segment missing the branch among its readers contributes nothing).  A branch without any
+// Step 3: one wave per (branch, query head): log-sum-exp combination over the slices of every
+// segment the branch reads.  The branch's entries in the reader lists name its partials (and how
+// many slices each has); the lanes fetch the
+// (maximum, sum) pairs of up to 64 (entry, split) pairs at once, the wave agrees on the maximum
+// and the weights, and the weighted partial outputs are added pair by pair.  A branch without any
 // key gets zeros.
 template <int D>
 __global__ void __launch_bounds__(64) k_decode_seg_merge(SegArgs a) {
@@ -387,28 +442,44 @@ __global__ void __launch_bounds__(64) k_decode_seg_merge(SegArgs a) {
 #pragma unroll
   for (int e = 0; e < PER; ++e) acc[e] = 0.f;
   float mx = -1e30f, lsum = 0.f;
-  for (int e = a.branch_seg_off[r]; e < a.branch_seg_off[r + 1]; ++e) {
-    const int s = a.branch_segs[e];
-    if (s < 0 || s >= a.n_segments) continue;
-    const int e0 = a.seg_reader_off[s], n = a.seg_reader_off[s + 1] - e0;
-    int entry = -1;
-    for (int b = 0; b < n && entry < 0; b += 64) {
-      const unsigned long long hit = __builtin_amdgcn_ballot_w64(b + lane < n && a.seg_readers[e0 + b + lane] == r);
-      if (hit) entry = e0 + b + __builtin_ctzll(hit);
+  const int e0 = a.branch_entry_off[r];
+  const int npairs = (a.branch_entry_off[r + 1] - e0) * a.splits;
+  for (int b = 0; b < npairs; b += 64) {
+    const int i = b + lane;
+    float ms = -1e30f, ls = 0.f;
+    uint32_t base = 0;
+    if (i < npairs) {
+      const int entry = a.branch_entries[e0 + i / a.splits];
+      if (entry >= 0 && entry < a.total_readers && i % a.splits < a.entry_nsplit[entry]) {
+        base = (uint32_t)(((size_t)(i % a.splits) * a.total_readers + entry) * a.hq + head);
+        const float2 ml = *(const float2*)(a.part_ml + (size_t)base * 2);
+        if (ml.y > 0.f) {
+          ms = ml.x;
+          ls = ml.y;
+        }
+      }
     }
-    if (entry < 0 || entry >= a.total_readers) continue;
-    const int npages = (a.seg_len[s] + PAGE - 1) / PAGE;
-    const int nsplit = min((npages + a.chunk - 1) / a.chunk, a.splits);
-    for (int sp = 0; sp < nsplit; ++sp) {
-      const size_t base = ((size_t)sp * a.total_readers + entry) * a.hq + head;
-      const float ms = a.part_ml[base * 2], ls = a.part_ml[base * 2 + 1];
-      if (!(ls > 0.f)) continue;
-      const float mn = fmaxf(mx, ms);
-      const float keep = __builtin_amdgcn_exp2f((mx - mn) * a.sc), wgt = __builtin_amdgcn_exp2f((ms - mn) * a.sc);
-      mx = mn;
-      lsum = lsum * keep + ls * wgt;
+    float cm = ms;
 #pragma unroll
-      for (int t = 0; t < PER; ++t) acc[t] = acc[t] * keep + wgt * a.part_o[base * D + lane * PER + t];
+    for (int o = 32; o >= 1; o >>= 1) cm = fmaxf(cm, __shfl_xor(cm, o));
+    const float mn = fmaxf(mx, cm);
+    const float keep = __builtin_amdgcn_exp2f((mx - mn) * a.sc);
+    const float wgt = ls > 0.f ? __builtin_amdgcn_exp2f((ms - mn) * a.sc) : 0.f;
+    float part = ls * wgt;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o);
+    lsum = lsum * keep + part;
+    mx = mn;
+#pragma unroll
+    for (int t = 0; t < PER; ++t) acc[t] *= keep;
+    unsigned long long live = __builtin_amdgcn_ballot_w64(ls > 0.f);
+    while (live) {
+      const int j = __builtin_ctzll(live);
+      live &= live - 1;
+      const float wj = __shfl(wgt, j);
+      const uint32_t bj = (uint32_t)__shfl((int)base, j);
+#pragma unroll
+      for (int t = 0; t < PER; ++t) acc[t] += wj * a.part_o[(size_t)bj * D + lane * PER + t];
     }
   }
   const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
@@ -883,8 +954,8 @@ namespace {
 
 struct SegPlan {
   int rb_max, chunk, splits;
-  long items;
-  size_t off_o, off_ml, bytes;
+  long items;  // bound on the work items (per kv head)
+  size_t off_o, off_ml, off_items, off_total, off_nsplit, bytes;
 };
 
 // One split size for all segments (their lengths live in device memory): as long as possible
@@ -906,13 +977,17 @@ int make_seg_plan(const dag_decode_seg_desc_t* d, int hq, int hkv, int D, SegPla
     while (c > 8 && base * dag_ceil_div(d->max_seg_pages, c) < 1024) c /= 2;
   p->chunk = c;
   p->splits = d->max_seg_pages > 0 ? (int)dag_ceil_div(d->max_seg_pages, c) : 0;
-  const int64_t items = base * p->splits;
-  if (items > INT32_MAX) return DAG_ERR_UNSUPPORTED;
+  const int64_t items = (int64_t)d->n_segments * p->rb_max * p->splits;
+  if (items * hkv > INT32_MAX) return DAG_ERR_UNSUPPORTED;
   p->items = (long)items;
   size_t off = 0;
   const size_t rows = (size_t)p->splits * (size_t)d->total_readers * hq;
+  if (rows > (size_t)INT32_MAX) return DAG_ERR_UNSUPPORTED;
   p->off_o = off;  off += dag_align_up(rows * D * 4, 256);
   p->off_ml = off; off += dag_align_up(rows * 2 * 4, 256);
+  p->off_items = off;  off += dag_align_up((size_t)items * sizeof(SegItem), 256);
+  p->off_total = off;  off += 256;
+  p->off_nsplit = off; off += dag_align_up((size_t)d->total_readers * 4, 256);
   p->bytes = off + 256;
   return DAG_OK;
 }
@@ -933,7 +1008,7 @@ extern "C" int dag_attn_decode_segments(const dag_decode_seg_desc_t* d, const vo
   const int rc = make_seg_plan(d, hq, hkv, head_dim, &p);
   if (rc != DAG_OK) return rc;
   if (d->n_live == 0) return DAG_OK;
-  if (!q || !k_pool || !v_pool || !out || !d->branch_seg_off || !d->branch_segs) return DAG_ERR_NULL;
+  if (!q || !k_pool || !v_pool || !out || !d->branch_entry_off || !d->branch_entries) return DAG_ERR_NULL;
   if (d->n_segments > 0 &&
       (!d->seg_page_off || !d->seg_pages || !d->seg_len || !d->seg_reader_off || !d->seg_readers))
     return DAG_ERR_NULL;
@@ -947,14 +1022,18 @@ extern "C" int dag_attn_decode_segments(const dag_decode_seg_desc_t* d, const vo
   a.seg_len = d->seg_len;
   a.seg_reader_off = d->seg_reader_off;
   a.seg_readers = d->seg_readers;
-  a.branch_seg_off = d->branch_seg_off;
-  a.branch_segs = d->branch_segs;
+  a.branch_entry_off = d->branch_entry_off;
+  a.branch_entries = d->branch_entries;
   a.q = (const uint16_t*)q;
   a.k_pool = (const uint16_t*)k_pool;
   a.v_pool = (const uint16_t*)v_pool;
   a.out = (uint16_t*)out;
   a.part_o = (float*)(base + p.off_o);
   a.part_ml = (float*)(base + p.off_ml);
+  a.items = (SegItem*)(base + p.off_items);
+  a.item_total = (int32_t*)(base + p.off_total);
+  a.entry_nsplit = (int32_t*)(base + p.off_nsplit);
+  a.item_cap = (int)p.items;
   a.n_segments = d->n_segments;
   a.n_live = d->n_live;
   a.hq = hq;
@@ -968,8 +1047,11 @@ extern "C" int dag_attn_decode_segments(const dag_decode_seg_desc_t* d, const vo
   a.th = 8.f / a.sc;
   hipStream_t stream = (hipStream_t)stream_;
   if (p.items > 0) {
-    if (head_dim == 128) hipLaunchKernelGGL(k_decode_seg<128>, dim3((unsigned)p.items), dim3(64), 0, stream, a);
-    else hipLaunchKernelGGL(k_decode_seg<64>, dim3((unsigned)p.items), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL(k_seg_plan, dim3(1), dim3(PLAN_THREADS), 0, stream, a);
+    DAG_LAUNCH_CHECK();
+    const unsigned grid = (unsigned)(p.items * hkv);
+    if (head_dim == 128) hipLaunchKernelGGL(k_decode_seg<128>, dim3(grid), dim3(64), 0, stream, a);
+    else hipLaunchKernelGGL(k_decode_seg<64>, dim3(grid), dim3(64), 0, stream, a);
     DAG_LAUNCH_CHECK();
   }
   const unsigned nout = (unsigned)(d->n_live * hq);

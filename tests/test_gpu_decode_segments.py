@@ -107,6 +107,8 @@ def test_degenerate_descriptions():
     desc["n_live"] = 3
     desc["branch_seg_off"] = np.asarray([0, 2, 3, 3], dtype=np.int32)
     desc["branch_segs"] = np.asarray([3, 0, 2], dtype=np.int32)
+    dags.add_branch_entries(desc)
+    assert list(desc["branch_entries"]) == [2, 0, 1]
     q = torch.cat([st["q"], st["q"][:1]])
     out = _gpu_decode_segments(desc, q, st["k_pool"], st["v_pool"], hq, hkv, d)
     ref = orc.attn_decode_segments(desc, dags.to_f64(q), dags.to_f64(st["k_pool"]), dags.to_f64(st["v_pool"]),

@@ -255,6 +255,7 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
       seg_page_off/seg_pages/seg_len        pages and token count of each segment
       seg_reader_off/seg_readers            live branches that read the segment (ascending)
       branch_seg_off/branch_segs            segments each live branch reads (ascending node id)
+      branch_entry_off/branch_entries       the same relation as positions in seg_readers
     """
     rng = np.random.Generator(np.random.PCG64(seed))
     seg_len, seg_np = [], []
@@ -306,8 +307,24 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
         seg_reader_off=seg_reader_off, seg_readers=flat(readers),
         branch_seg_off=branch_seg_off, branch_segs=flat(branch_segs),
     )
+    add_branch_entries(desc)
     return dict(desc=desc, k_pool=k_pool, v_pool=v_pool, q=torch.stack(q_rows) if q_rows else
                 torch.zeros((0, hq, d), dtype=dtype), tokens=toks, live_tok=live_tok, n_pages=n_pages)
+
+
+def add_branch_entries(desc):
+    """branch_entries[e]: position in seg_readers where the branch of entry e of branch_segs is
+    listed among the readers of that segment (pure bookkeeping: the inverse of the reader lists)."""
+    off, readers = np.asarray(desc["seg_reader_off"]), np.asarray(desc["seg_readers"])
+    bso, bs = np.asarray(desc["branch_seg_off"]), np.asarray(desc["branch_segs"])
+    ent = np.zeros(len(bs), dtype=np.int32)
+    for r in range(int(desc["n_live"])):
+        for e in range(int(bso[r]), int(bso[r + 1])):
+            s = int(bs[e])
+            ent[e] = off[s] + int(np.nonzero(readers[off[s]:off[s + 1]] == r)[0][0])
+    desc["branch_entry_off"] = bso.astype(np.int32)
+    desc["branch_entries"] = ent
+    return desc
 
 
 def segments_from_decode_desc(desc):
@@ -322,7 +339,7 @@ def segments_from_decode_desc(desc):
     group_of = np.searchsorted(gbo, np.arange(nl), side="right") - 1
     branch_segs = [[int(group_of[r]), ng + r] for r in range(nl)]
     flat = lambda ll: np.asarray([x for l in ll for x in l], dtype=np.int32)
-    return dict(
+    return add_branch_entries(dict(
         n_live=nl, n_segments=ng + nl, page_size=PAGE,
         seg_page_off=seg_page_off,
         seg_pages=np.concatenate([desc["shared_pages"], desc["branch_pages"]]).astype(np.int32),
@@ -330,7 +347,7 @@ def segments_from_decode_desc(desc):
         seg_reader_off=np.concatenate([[0], np.cumsum([len(x) for x in readers])]).astype(np.int32),
         seg_readers=flat(readers),
         branch_seg_off=np.arange(0, 2 * nl + 1, 2, dtype=np.int32), branch_segs=flat(branch_segs),
-    )
+    ))
 
 
 def decode_segments_algorithmic_bytes(desc, hkv, d, elem_bytes=2):
