@@ -125,6 +125,38 @@ class DecodeWork:
             ev[2].record()
 
 
+class SegDecodeWork:
+    """A three-level decode frontier for dag_attn_decode_segments: 16 sequences, each a root of
+    4096 tokens, two mid-level nodes of 2048 and four live leaves under each with 1000..1063 own
+    tokens (ragged last pages); shapes of config 3.  Reported beside the main line, not part of
+    `value`."""
+
+    def __init__(self, cfg, dev, n_seqs=16):
+        self.cfg = cfg
+        rng = np.random.Generator(np.random.PCG64(cfg["seed"] + 77))
+        parents = [[], [0], [0]] + [[1]] * 4 + [[2]] * 4
+        anc = dags.bits_from_sets(dags.closure_from_parents(parents))
+        dag_list = [(np.asarray([4096, 2048, 2048] + [1000 + int(rng.integers(64)) for _ in range(8)], dtype=np.int32),
+                     anc) for _ in range(n_seqs)]
+        st = dags.decode_segments_state(cfg["seed"] + 78, dag_list, [list(range(3, 11))] * n_seqs, cfg["hq"],
+                                        cfg["hkv"], cfg["d"], keep_tokens=False)
+        self.sd = B.SegDecodeDesc(st["desc"], dev)
+        kp, vp = st["k_pool"].to(dev), st["v_pool"].to(dev)
+        self.pools = [(kp, vp), (kp.clone(), vp.clone())]   # used in turn, as in DecodeWork
+        self.turn = 0
+        self.q = st["q"].to(dev)
+        self.out = torch.empty_like(self.q)
+        self.ws = torch.empty(B.dag_decode_segments_workspace_bytes(self.sd, cfg["hq"], cfg["hkv"], cfg["d"]),
+                              dtype=torch.uint8, device=dev)
+        self.bytes = dags.decode_segments_algorithmic_bytes(st["desc"], cfg["hkv"], cfg["d"])
+        self.n_live, self.n_segments = st["desc"]["n_live"], st["desc"]["n_segments"]
+
+    def run(self):
+        kp, vp = self.pools[self.turn]
+        self.turn ^= 1
+        B.dag_attn_decode_segments(self.sd, self.q, kp, vp, self.out, self.ws)
+
+
 def cpu_baseline(pw, n_seq=3):
     """The oracle as it stands, timed on the host cores on a bounded sample of the prefill workload:
     the first n_seq sequences, every row, every query head (10 - 20 s of CPU work)."""
@@ -216,6 +248,19 @@ def main():
     deck_ms = [e[1].elapsed_time(e[2]) for e in dev_ev]
     step_ms = [wall * 1e3 / args.steps]
 
+    # beside the timed region: the segment form of the decode step on a three-level frontier
+    sw = SegDecodeWork(dags.config(2), dev)
+    for _ in range(args.warmup):
+        sw.run()
+    sev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    sev[0].record()
+    for _ in range(args.steps):
+        sw.run()
+    sev[1].record()
+    torch.cuda.synchronize()
+    ms_seg = sev[0].elapsed_time(sev[1]) / args.steps
+    seg_gbs = sw.bytes / (ms_seg * 1e-3) / 1e9
+
     flops, pairs = pw.useful_flops()
     mean = lambda xs: float(np.mean(xs))
     ms_step, ms_pre, ms_attn, ms_dec, ms_deck = map(mean, (step_ms, pre_ms, attn_ms, dec_ms, deck_ms))
@@ -248,6 +293,15 @@ def main():
                    "roofline": {"bound": "hbm", "kernel": "k_decode(+k_decode_merge)", "achieved": dec_gbs,
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
                                 "algorithmic_bytes": dw.bytes, "traffic": TRAFFIC_DECODE_KERNELS}},
+        "decode_segments": {"metric": "segment_decode_tok_per_s_one_attention_layer",
+                            "value": sw.n_live / (ms_seg * 1e-3), "unit": "tok/s", "ms_per_decode_step": ms_seg,
+                            "config": {"workload": "three_level_frontier_bf16", "n_seqs": 16, "segments": sw.n_segments,
+                                       "live_branches": sw.n_live, "levels": "root 4096 | 2 x 2048 | 8 x 1000..1063",
+                                       "page_size": 16},
+                            "roofline": {"bound": "hbm", "kernel": "k_seg_plan+k_decode_seg+k_decode_seg_merge",
+                                         "achieved": seg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": seg_gbs / HBM_PEAK_GBS, "algorithmic_bytes": sw.bytes,
+                                         "traffic": None}},
         "wall_s_timed_loop": wall,
     }
     if not args.no_cpu_baseline:

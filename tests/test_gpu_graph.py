@@ -64,3 +64,36 @@ def test_decode_step_in_a_graph(hq, hkv, nb):
         B.dag_attn_decode(dd, q, kp, vp, out, ws)
 
     _capture_and_replay(step, out)
+
+
+def test_segment_decode_step_in_a_graph():
+    """Plan kernel + item kernel + combination of dag_attn_decode_segments captured and replayed;
+    between replays a segment grows by one token (its length lives in device memory), so the
+    replayed plan differs from the captured one and must still match an eager call."""
+    hq, hkv, d = 8, 2, 128
+    parents = [[], [0], [0], [1], [1], [2]]
+    L = np.asarray([300, 47, 130, 15, 33, 16], dtype=np.int32)
+    anc = dags.bits_from_sets(dags.closure_from_parents(parents))
+    st = dags.decode_segments_state(23, [(L, anc)], [[3, 4, 5]], hq, hkv, d, junk_scale=0.5)
+    sd = B.SegDecodeDesc(st["desc"], DEV)
+    kp, vp, q = st["k_pool"].to(DEV), st["v_pool"].to(DEV), st["q"].to(DEV)
+    out = torch.zeros_like(q)
+    ws = torch.empty(B.dag_decode_segments_workspace_bytes(sd, hq, hkv, d), dtype=torch.uint8, device=DEV)
+    step = lambda: B.dag_attn_decode_segments(sd, q, kp, vp, out, ws)
+    _capture_and_replay(step, out)
+    # same graph, longer segment: node 3 now shows its 16th slot (junk values, finite) as a token
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            step()
+        sd.t["seg_len"][3] += 1
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        replayed = out.clone()
+        out.zero_()
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(out, replayed)
+        assert not torch.equal(out[0], torch.zeros_like(out[0]))

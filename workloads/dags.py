@@ -243,14 +243,15 @@ def decode_algorithmic_bytes(desc, hkv, d, elem_bytes=2):
 
 
 def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q_scale=1.0,
-                          dtype=torch.bfloat16, junk_scale=4.0, spare_pages=3):
+                          dtype=torch.bfloat16, junk_scale=4.0, spare_pages=3, keep_tokens=True):
     """Decode state of a general DAG frontier: one KV *segment* per node of every DAG in
     `dag_list` ((node_len, anc) pairs), stored in its own pages (the last page of a segment is
     partly filled when the node length is no multiple of the page size; its unused slots hold
     large random junk that no reader may touch).  `live_list[b]` names the live nodes of DAG b:
     each is decoding its last token and reads the segments of its ancestors and its own.
     Segment ids and live-branch ids are global (DAG after DAG).  Returns the pools, the query
-    of every live branch, the token-level q/k/v of every DAG (for a dense cross-check) and the
+    of every live branch, the token-level q/k/v of every DAG (for a dense cross-check; with
+    keep_tokens=False only the live tokens get a query and nothing token-level is kept) and the
     int32 description arrays:
       seg_page_off/seg_pages/seg_len        pages and token count of each segment
       seg_reader_off/seg_readers            live branches that read the segment (ascending)
@@ -265,8 +266,10 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
             seg_np.append((int(x) + PAGE - 1) // PAGE)
     n_pages = int(np.sum(seg_np)) + spare_pages
     perm = rng.permutation(n_pages).astype(np.int32)
-    k_pool = normal_tensor(rng, (n_pages, hkv, d // 8, PAGE, 8), junk_scale, dtype)
-    v_pool = normal_tensor(rng, (n_pages, hkv, d, PAGE), junk_scale, dtype)
+    # (without token-level arrays the pools are drawn in place with the token scale and only the
+    # unused slots of partly filled pages are overwritten with junk)
+    k_pool = normal_tensor(rng, (n_pages, hkv, d // 8, PAGE, 8), junk_scale if keep_tokens else kv_scale, dtype)
+    v_pool = normal_tensor(rng, (n_pages, hkv, d, PAGE), junk_scale if keep_tokens else kv_scale, dtype)
     seg_page_off = np.zeros(len(seg_len) + 1, dtype=np.int32)
     seg_page_off[1:] = np.cumsum(seg_np)
     seg_pages = perm[:seg_page_off[-1]].copy()
@@ -275,12 +278,21 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
     s0 = 0
     for (L, anc), live in zip(dag_list, live_list):
         T = int(np.sum(L))
-        q_tok, k_tok, v_tok = make_qkv(int(rng.integers(1 << 30)), T, hq, hkv, d, 1.0, dtype)
-        q_tok, k_tok, v_tok = q_tok * q_scale, k_tok * kv_scale, v_tok * kv_scale
-        toks.append((q_tok, k_tok, v_tok))
+        if keep_tokens:
+            q_tok, k_tok, v_tok = make_qkv(int(rng.integers(1 << 30)), T, hq, hkv, d, 1.0, dtype)
+            q_tok, k_tok, v_tok = q_tok * q_scale, k_tok * kv_scale, v_tok * kv_scale
+            toks.append((q_tok, k_tok, v_tok))
+        else:
+            q_tok = k_tok = v_tok = None
         start = np.concatenate([[0], np.cumsum(L)]).astype(np.int64)
         for u, n in enumerate(L):
             pg = torch.from_numpy(seg_pages[seg_page_off[s0 + u]:seg_page_off[s0 + u + 1]].astype(np.int64))
+            if not keep_tokens:
+                used = int(n) % PAGE
+                if used:
+                    k_pool[pg[-1], :, :, used:, :] = normal_tensor(rng, (hkv, d // 8, PAGE - used, 8), junk_scale, dtype)
+                    v_pool[pg[-1], :, :, used:] = normal_tensor(rng, (hkv, d, PAGE - used), junk_scale, dtype)
+                continue
             i = torch.arange(int(n))
             k_pool[pg[i // PAGE], :, :, i % PAGE, :] = k_tok[start[u]:start[u + 1]].reshape(int(n), hkv, d // 8, 8)
             v_pool[pg[i // PAGE], :, :, i % PAGE] = v_tok[start[u]:start[u + 1]]
@@ -291,7 +303,7 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
             branch_segs.append([s0 + u for u in mine])
             for u in mine:
                 readers[s0 + u].append(r)
-            q_rows.append(q_tok[start[v + 1] - 1])
+            q_rows.append(q_tok[start[v + 1] - 1] if keep_tokens else normal_tensor(rng, (hq, d), q_scale, dtype))
             live_tok.append(int(start[v + 1] - 1))
         s0 += len(L)
     n_live = len(branch_segs)
