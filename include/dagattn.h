@@ -231,7 +231,12 @@ int dag_attn_decode(const dag_decode_desc_t* desc, const void* q, const void* k_
  * that is how its partial results are found.
  * The struct lives on the HOST; arrays are DEVICE int32; pools as for dag_attn_decode.
  * Appending a branch's new token is dag_kv_append_rope with branch_page_off / branch_pages /
- * branch_len / branch_pos describing the branches' own (tail) segments. */
+ * branch_len / branch_pos describing the branches' own (tail) segments.
+ * seg_reader_len turns the step into the incremental prefill of newly forked or joined nodes
+ * against the cached context: the n new tokens of a node are n "live branches" that read the
+ * ancestors' segments in full and the first L - n + i + 1 tokens of the node's own segment
+ * (token i of the new ones, L the segment's length after all n were appended), which is the
+ * node's causal part of Eq. 3. */
 typedef struct {
   int32_t n_live, n_segments, page_size;
   int32_t max_seg_pages;  /* HOST upper bound on pages of any segment                            */
@@ -245,6 +250,8 @@ typedef struct {
   const int32_t* branch_entry_off; /* [n_live+1] into branch_entries                            */
   const int32_t* branch_entries; /* for each live branch r: the positions e in seg_readers with
                                     seg_readers[e] == r, one per segment it reads, any order    */
+  const int32_t* seg_reader_len; /* NULL, or [total_readers]: how many leading tokens of the
+                                    segment the reader of entry e sees (clamped to seg_len)     */
 } dag_decode_seg_desc_t;
 
 /* Bytes of DEVICE workspace dag_attn_decode_segments needs for this description (0 on bad

@@ -316,11 +316,21 @@ def gather_segments(sdesc, r, h, k_pool, v_pool):
     """K, V [ctx][D] seen by live branch r on KV head h when contexts are lists of KV segments
     (section 3.2: a token carries references to cached blocks; section 4.3: a Fork hands the same
     context to every child, a Join the histories of all its predecessors): the first seg_len[s]
-    tokens of every segment s the branch reads, in the order listed."""
+    tokens of every segment s the branch reads, in the order listed.  With "seg_reader_len" (one
+    entry per reader-list position) the branch sees only that many leading tokens of the segment:
+    a token of a node that is being prefilled sees the node's tokens up to itself (the same-node
+    case of Eq. 3)."""
     Ks, Vs = [], []
+    limits = sdesc.get("seg_reader_len")
     for e in range(int(sdesc["branch_seg_off"][r]), int(sdesc["branch_seg_off"][r + 1])):
         s = int(sdesc["branch_segs"][e])
-        for t in range(int(sdesc["seg_len"][s])):
+        n = int(sdesc["seg_len"][s])
+        if limits is not None:
+            r0, r1 = int(sdesc["seg_reader_off"][s]), int(sdesc["seg_reader_off"][s + 1])
+            pos = [x for x in range(r0, r1) if int(sdesc["seg_readers"][x]) == r]
+            assert len(pos) == 1, "branch %d must be listed once among the readers of segment %d" % (r, s)
+            n = min(n, max(0, int(limits[pos[0]])))
+        for t in range(n):
             page = int(sdesc["seg_pages"][int(sdesc["seg_page_off"][s]) + t // PAGE])
             Ks.append(pool_get_k(k_pool, page, h, t % PAGE))
             Vs.append(pool_get_v(v_pool, page, h, t % PAGE))

@@ -69,7 +69,7 @@ _SEG_ARRAYS = ("seg_page_off", "seg_pages", "seg_len", "seg_reader_off", "seg_re
 class dag_decode_seg_desc_t(C.Structure):
     _fields_ = ([("n_live", C.c_int32), ("n_segments", C.c_int32), ("page_size", C.c_int32),
                  ("max_seg_pages", C.c_int32), ("max_readers", C.c_int32), ("total_readers", C.c_int32)] +
-                [(name, C.c_void_p) for name in _SEG_ARRAYS])
+                [(name, C.c_void_p) for name in _SEG_ARRAYS] + [("seg_reader_len", C.c_void_p)])
 
 
 _lib = None
@@ -305,7 +305,11 @@ class SegDecodeDesc:
         self.c = dag_decode_seg_desc_t(nl, ns, int(desc["page_size"]),
                                        int(sp.max()) if sp.size else 0, int(rd.max()) if rd.size else 0,
                                        int(rd.sum()) if rd.size else 0,
-                                       *[self.t[n].data_ptr() for n in _SEG_ARRAYS])
+                                       *[self.t[n].data_ptr() for n in _SEG_ARRAYS], None)
+        if desc.get("seg_reader_len") is not None:
+            arr = np.ascontiguousarray(desc["seg_reader_len"], dtype=np.int32)
+            self.t["seg_reader_len"] = torch.from_numpy(arr if arr.size else np.zeros(1, np.int32)).to(device)
+            self.c.seg_reader_len = self.t["seg_reader_len"].data_ptr()
 
 
 def dag_decode_segments_workspace_bytes(sdesc, hq, hkv, head_dim):

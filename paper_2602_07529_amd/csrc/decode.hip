@@ -66,6 +66,7 @@ struct SegArgs {
   const int32_t* seg_len;
   const int32_t* seg_reader_off;
   const int32_t* seg_readers;
+  const int32_t* seg_reader_len;  // optional: leading tokens of the segment each reader-list entry sees
   const int32_t* branch_entry_off;
   const int32_t* branch_entries;
   const uint16_t* q;
@@ -131,18 +132,18 @@ __device__ __forceinline__ void load_block(KVBlock<D>& blk, const A& a, int pgv,
 // of the second phase.
 template <int D, typename QF>
 __device__ __forceinline__ void block_scores(const bf16x8 (&kop)[D / 16], QF&& qop, f32x16* O, float& m, float& l,
-                                             float sc, float th, int key0, int len, int H, bf16x8& pb0,
-                                             bf16x8& pb1) {
+                                             float sc, float th, int key0, int len, int lim, int H,
+                                             bf16x8& pb0, bf16x8& pb1) {
   f32x16 S;
 #pragma unroll
   for (int r = 0; r < 16; ++r) S[r] = 0.f;
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) S = mfma32(kop[s], qop(s), S);
-  if (key0 + 32 > len) {
+  if (key0 + 32 > len) {  // len: wave-uniform, the smallest of the rows' limits; lim: this lane's row
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int key = key0 + 16 * (r >> 3) + 8 * H + (r & 7);
-      S[r] = key < len ? S[r] : -INFINITY;
+      S[r] = key < lim ? S[r] : -INFINITY;
     }
   }
   float bm = S[0];
@@ -189,19 +190,20 @@ __device__ __forceinline__ void block_pv(const bf16x8 (&v0)[D / 32], const bf16x
 
 template <int D, typename QF>
 __device__ __forceinline__ void compute_block(const KVBlock<D>& blk, QF&& qop, f32x16* O, float& m, float& l,
-                                              float sc, float th, int key0, int len, int H) {
+                                              float sc, float th, int key0, int len, int lim, int H) {
   bf16x8 pb0, pb1;
-  block_scores<D>(blk.k, qop, O, m, l, sc, th, key0, len, H, pb0, pb1);
+  block_scores<D>(blk.k, qop, O, m, l, sc, th, key0, len, lim, H, pb0, pb1);
   block_pv<D>(blk.v[0], blk.v[1], pb0, pb1, O);
 }
 
 // The loop of a single-wave work item: pages [p0, p1) of one page list, 32 keys (two pages) per
-// step, the next block's loads in flight while the current one is computed.  `len` is the token
-// count of the whole list (keys at or past it are masked).  Leaves the un-normalised partial
+// step, the next block's loads in flight while the current one is computed.  `lim` is the number
+// of leading tokens of the list that this lane's row sees (keys at or past it are masked), `len`
+// the smallest `lim` of the wave.  Leaves the un-normalised partial
 // (O, reference maximum m, row sum l of this lane's half) in registers.
 template <int D, typename A, typename QF>
-__device__ __forceinline__ void stream_slice(const A& a, const int32_t* pages, int p0, int p1, int len, int hk,
-                                             int lane, QF&& qop, f32x16* O, float& m, float& l) {
+__device__ __forceinline__ void stream_slice(const A& a, const int32_t* pages, int p0, int p1, int len, int lim,
+                                             int hk, int lane, QF&& qop, f32x16* O, float& m, float& l) {
   const int L = lane & 31, H = lane >> 5;
   const int kr = key_of_row(L);
   const int kpage_sel = kr >> 4, kslot = kr & 15;
@@ -228,7 +230,7 @@ __device__ __forceinline__ void stream_slice(const A& a, const int32_t* pages, i
       }
       load_block<D>(b1, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
     }
-    compute_block<D>(b0, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
+    compute_block<D>(b0, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, lim, H);
     pb += 2;
     if (pb >= np) break;
     if (pb + 2 < np) {
@@ -238,7 +240,7 @@ __device__ __forceinline__ void stream_slice(const A& a, const int32_t* pages, i
       }
       load_block<D>(b0, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
     }
-    compute_block<D>(b1, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, H);
+    compute_block<D>(b1, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, lim, H);
     pb += 2;
     if (pb >= np) break;
   }
@@ -308,7 +310,7 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
   auto qop = [&](int s) { return qf[s * 64]; };
   f32x16 O[D / 32];
   float m, l;
-  stream_slice<D>(a, pages, p0, p1, len, hk, lane, qop, O, m, l);
+  stream_slice<D>(a, pages, p0, p1, len, len, hk, lane, qop, O, m, l);
 
   const float l_tot = l + __shfl_xor(l, 32);
   if (row_ok) {
@@ -389,7 +391,8 @@ __global__ void __launch_bounds__(64, 2) k_decode_seg(SegArgs a) {
   const SegItem it = a.items[idx];
   const int len = it.len, e0 = it.e0, nrows = it.nrows, row0 = it.row0, split = it.split;
   const int npages = (len + PAGE - 1) / PAGE;
-  const int p0 = split * a.chunk, p1 = min(p0 + a.chunk, npages);
+  const int p0 = split * a.chunk;
+  int p1 = min(p0 + a.chunk, npages);
   if (row0 >= nrows || p0 >= p1) return;  // (never listed)
   const int row = row0 + L;
   const bool row_ok = row < nrows;
@@ -397,6 +400,27 @@ __global__ void __launch_bounds__(64, 2) k_decode_seg(SegArgs a) {
   const int entry = e0 + rr / a.G, head = hk * a.G + rr % a.G;
   const bool store_ok = row_ok && entry < a.total_readers;  // (a reader list longer than announced: no partial)
   const size_t pbase = ((size_t)split * a.total_readers + entry) * a.hq + head;
+  // per-reader visible prefix of the segment (a token of a node being prefilled sees the node's
+  // tokens up to itself): the slice ends at the longest prefix of the wave's rows
+  int lim = len, lim_min = len;
+  if (a.seg_reader_len) {
+    lim = min(max(a.seg_reader_len[entry], 0), len);
+    int lim_max = lim;
+    lim_min = lim;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      lim_max = max(lim_max, __shfl_xor(lim_max, o));
+      lim_min = min(lim_min, __shfl_xor(lim_min, o));
+    }
+    p1 = min(p1, (lim_max + PAGE - 1) / PAGE);
+    if (p0 >= p1) {  // no row of this block sees a token of the slice: neutral partial
+      if (store_ok && H == 0) {
+        a.part_ml[pbase * 2] = -1e30f;
+        a.part_ml[pbase * 2 + 1] = 0.f;
+      }
+      return;
+    }
+  }
   const int br = min(max(a.seg_readers[entry], 0), a.n_live - 1);
 
   const bf16x8* qf = qs_all + lane;
@@ -408,7 +432,7 @@ __global__ void __launch_bounds__(64, 2) k_decode_seg(SegArgs a) {
   auto qop = [&](int t) { return qf[t * 64]; };
   f32x16 O[D / 32];
   float m, l;
-  stream_slice<D>(a, a.seg_pages + it.page_off, p0, p1, len, hk, lane, qop, O, m, l);
+  stream_slice<D>(a, a.seg_pages + it.page_off, p0, p1, lim_min, lim, hk, lane, qop, O, m, l);
 
   const float l_tot = l + __shfl_xor(l, 32);
   if (store_ok) {
@@ -631,7 +655,7 @@ __global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeAr
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(kop[s]));
-    block_scores<D>(kop, qop, O, m, l, a.sc, a.th, (p0 + 2 * b) * PAGE, len, H, pb0, pb1);
+    block_scores<D>(kop, qop, O, m, l, a.sc, a.th, (p0 + 2 * b) * PAGE, len, len, H, pb0, pb1);
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) {
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v0[db]) : "v"(sb + voff), "n"(db * 32 * PAGE * 2));
@@ -1022,6 +1046,7 @@ extern "C" int dag_attn_decode_segments(const dag_decode_seg_desc_t* d, const vo
   a.seg_len = d->seg_len;
   a.seg_reader_off = d->seg_reader_off;
   a.seg_readers = d->seg_readers;
+  a.seg_reader_len = d->seg_reader_len;
   a.branch_entry_off = d->branch_entry_off;
   a.branch_entries = d->branch_entries;
   a.q = (const uint16_t*)q;

@@ -193,7 +193,7 @@ def test_decode_argument_errors():
 
 def test_segment_decode_argument_errors():
     L = B.lib()
-    sd = B.dag_decode_seg_desc_t(4, 3, 16, 40, 4, 6, *([FAKE] * 7))
+    sd = B.dag_decode_seg_desc_t(4, 3, 16, 40, 4, 6, *([FAKE] * 7), None)
     p = C.c_void_p(FAKE)
     need = L.dag_decode_segments_workspace_bytes(C.byref(sd), 32, 8, 128)
     # 40 pages, 3 x 8 x 1 items per split: the split size halves from 128 pages to 8 -> 5 splits
@@ -206,12 +206,12 @@ def test_segment_decode_argument_errors():
     assert L.dag_attn_decode_segments(C.byref(sd), None, p, p, p, *args, p, need, None) == -1
     assert L.dag_attn_decode_segments(C.byref(sd), C.c_void_p(FAKE + 2), p, p, p, *args, p, need, None) == -8
     assert L.dag_attn_decode_segments(None, p, p, p, p, *args, p, need, None) == -1
-    bad_page = B.dag_decode_seg_desc_t(4, 3, 32, 40, 4, 6, *([FAKE] * 7))
+    bad_page = B.dag_decode_seg_desc_t(4, 3, 32, 40, 4, 6, *([FAKE] * 7), None)
     assert L.dag_attn_decode_segments(C.byref(bad_page), p, p, p, p, *args, p, need, None) == -7
     assert L.dag_decode_segments_workspace_bytes(C.byref(bad_page), 32, 8, 128) == 0
-    neg = B.dag_decode_seg_desc_t(4, 3, 16, -1, 4, 6, *([FAKE] * 7))
+    neg = B.dag_decode_seg_desc_t(4, 3, 16, -1, 4, 6, *([FAKE] * 7), None)
     assert L.dag_attn_decode_segments(C.byref(neg), p, p, p, p, *args, p, need, None) == -2
-    no_arrays = B.dag_decode_seg_desc_t(4, 3, 16, 40, 4, 6, *([0] * 7))
+    no_arrays = B.dag_decode_seg_desc_t(4, 3, 16, 40, 4, 6, *([0] * 7), None)
     assert L.dag_attn_decode_segments(C.byref(no_arrays), p, p, p, p, *args, p, need, None) == -1
-    empty = B.dag_decode_seg_desc_t(0, 0, 16, 0, 0, 0, *([0] * 7))
+    empty = B.dag_decode_seg_desc_t(0, 0, 16, 0, 0, 0, *([0] * 7), None)
     assert L.dag_attn_decode_segments(C.byref(empty), p, p, p, p, *args, None, 0, None) == 0

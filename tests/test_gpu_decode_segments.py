@@ -139,3 +139,38 @@ def test_config3_as_segments_sampled_branches_and_against_the_two_level_entry_po
     ref = orc.attn_decode_segments(sdesc, dags.to_f64(st["q"]), dags.to_f64(st["k_pool"]), dags.to_f64(st["v_pool"]),
                                    branches=branches)
     check_close(out[branches], ref[branches], torch.bfloat16, "config 3 as segments")
+
+
+@pytest.mark.parametrize("hq,hkv,d,scale_len,new", [(8, 2, 128, 1, [12, 5, 1]), (4, 1, 64, 1, [12, 18, 1]),
+                                                    (8, 2, 128, 12, [150, 64, 1]), (5, 1, 128, 3, [40, 33, 2])])
+def test_incremental_prefill_of_new_nodes_against_the_cached_context(hq, hkv, d, scale_len, new):
+    """Per-reader visible lengths: the last n tokens of a join, of a leaf and of an inner node are
+    prefilled together against the paged context (each new token sees its node up to itself and
+    the ancestors' segments in full); every row against the oracle, which is pinned to the
+    DAG-masked prefill rows.  150 new tokens x 4 heads = 19 row blocks over a 153-token segment:
+    row blocks that see nothing of a slice, blocks that end inside a page."""
+    dag_list = [_multilevel(scale_len)]
+    st = dags.decode_segments_state(600 + hq + scale_len, dag_list, [[8, 6, 4]], hq, hkv, d, kv_scale=0.7,
+                                    q_scale=0.7, new_tokens=[new])
+    out = _gpu_decode_segments(st["desc"], st["q"], st["k_pool"], st["v_pool"], hq, hkv, d)
+    ref = orc.attn_decode_segments(st["desc"], dags.to_f64(st["q"]), dags.to_f64(st["k_pool"]), dags.to_f64(st["v_pool"]))
+    check_close(out, ref, torch.bfloat16, "incremental prefill out")
+
+
+def test_incremental_prefill_in_slices_equals_the_prefill_kernel(monkeypatch):
+    """A 700-token node prefilled whole against a 1,000-token parent, in page slices of 20 (so
+    that slices lie entirely past the first rows' limits): against the oracle and against the
+    prefill kernel's rows for the same tokens."""
+    from tests.gpu_util import run_prefill
+    monkeypatch.setenv("DAGATTN_DECODE_CHUNK_SEG", "20")
+    hq, hkv, d = 4, 1, 128
+    dag = dags.linear_chain([1000, 700])
+    st = dags.decode_segments_state(81, [dag], [[1]], hq, hkv, d, kv_scale=0.7, q_scale=0.7, new_tokens=[[700]])
+    out = _gpu_decode_segments(st["desc"], st["q"], st["k_pool"], st["v_pool"], hq, hkv, d)
+    rows = [0, 1, 15, 16, 17, 319, 320, 321, 350, 698, 699]
+    ref = orc.attn_decode_segments(st["desc"], dags.to_f64(st["q"]), dags.to_f64(st["k_pool"]), dags.to_f64(st["v_pool"]),
+                                   branches=rows)
+    check_close(out[rows], ref[rows], torch.bfloat16, "sliced incremental prefill out")
+    q_tok, k_tok, v_tok = st["tokens"][0]
+    o_pre, _, _, _, _ = run_prefill([dag], q_tok, k_tok, v_tok, 1e4, rope=False)
+    assert (out.float().cpu() - o_pre.float().cpu()[1000:]).abs().max().item() < 4e-2

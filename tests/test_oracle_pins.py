@@ -495,3 +495,28 @@ def test_two_level_description_as_segments_gives_the_two_level_result():
     kp, vp, q = st["k_pool"].numpy(), st["v_pool"].numpy(), st["q"].numpy()
     sdesc = dags.segments_from_decode_desc(st["desc"])
     assert np.array_equal(orc.attn_decode_segments(sdesc, q, kp, vp), orc.attn_decode(st["desc"], q, kp, vp))
+
+
+def test_segment_decode_with_reader_lengths_is_chunked_prefill_of_new_nodes():
+    """The last n tokens of a node as n live branches, each seeing the node's own segment up to
+    itself and the ancestors' segments in full: every such row equals the DAG-masked prefill row
+    (Eq. 3: causal inside the node, full visibility of ancestors).  A join prefilled whole, a leaf
+    prefilled over its last 5 tokens, a single-token decode beside them."""
+    L, anc = _multilevel_dag()
+    live, new = [8, 6, 4], [12, 5, 1]
+    st = dags.decode_segments_state(73, [(L, anc)], [live], 4, 2, 16, dtype=torch.float64, new_tokens=[new])
+    desc = st["desc"]
+    assert desc["n_live"] == 18 and len(desc["seg_reader_len"]) == len(desc["seg_readers"])
+    # node 8 (12 tokens, all new): its readers see 1..12 of its segment; the root in full
+    r8 = desc["seg_reader_len"][desc["seg_reader_off"][8]:desc["seg_reader_off"][9]]
+    assert list(r8) == list(range(1, 13))
+    assert set(desc["seg_reader_len"][desc["seg_reader_off"][0]:desc["seg_reader_off"][1]]) == {37}
+    q_tok, k_tok, v_tok = (x.numpy() for x in st["tokens"][0])
+    O, _ = orc.attn_prefill(q_tok, k_tok, v_tok, L, anc, rows=np.asarray(st["live_tok"]))
+    Od = orc.attn_decode_segments(desc, st["q"].numpy(), st["k_pool"].numpy(), st["v_pool"].numpy())
+    assert np.abs(O[st["live_tok"]] - Od).max() < 1e-12
+    # a planted mistake (every reader sees the whole own segment: no causality inside the node) shows
+    bad = dict(desc)
+    bad["seg_reader_len"] = np.full_like(desc["seg_reader_len"], 1 << 20)
+    Ob = orc.attn_decode_segments(bad, st["q"].numpy(), st["k_pool"].numpy(), st["v_pool"].numpy())
+    assert np.abs(O[st["live_tok"]] - Ob).max() > 1e-3

@@ -243,12 +243,17 @@ def decode_algorithmic_bytes(desc, hkv, d, elem_bytes=2):
 
 
 def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q_scale=1.0,
-                          dtype=torch.bfloat16, junk_scale=4.0, spare_pages=3, keep_tokens=True):
+                          dtype=torch.bfloat16, junk_scale=4.0, spare_pages=3, keep_tokens=True,
+                          new_tokens=None):
     """Decode state of a general DAG frontier: one KV *segment* per node of every DAG in
     `dag_list` ((node_len, anc) pairs), stored in its own pages (the last page of a segment is
     partly filled when the node length is no multiple of the page size; its unused slots hold
     large random junk that no reader may touch).  `live_list[b]` names the live nodes of DAG b:
     each is decoding its last token and reads the segments of its ancestors and its own.
+    With `new_tokens[b][i]` = n > 1 the last n tokens of live node i of DAG b are all live (the
+    node is being prefilled n tokens at a time against the cached context): n branches, oldest
+    first, each seeing the node's segment up to itself ("seg_reader_len", one entry per
+    reader-list position; the full segment length for every other reader).
     Segment ids and live-branch ids are global (DAG after DAG).  Returns the pools, the query
     of every live branch, the token-level q/k/v of every DAG (for a dense cross-check; with
     keep_tokens=False only the live tokens get a query and nothing token-level is kept) and the
@@ -274,6 +279,8 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
     seg_page_off[1:] = np.cumsum(seg_np)
     seg_pages = perm[:seg_page_off[-1]].copy()
     readers = [[] for _ in seg_len]
+    reader_len = [[] for _ in seg_len]
+    dag_index = 0
     branch_segs, q_rows, toks, live_tok = [], [], [], []
     s0 = 0
     for (L, anc), live in zip(dag_list, live_list):
@@ -297,15 +304,20 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
             k_pool[pg[i // PAGE], :, :, i % PAGE, :] = k_tok[start[u]:start[u + 1]].reshape(int(n), hkv, d // 8, 8)
             v_pool[pg[i // PAGE], :, :, i % PAGE] = v_tok[start[u]:start[u + 1]]
         sets = sets_from_bits(anc)
-        for v in live:
-            r = len(branch_segs)
+        for li, v in enumerate(live):
+            n_new = 1 if new_tokens is None else int(new_tokens[dag_index][li])
             mine = sorted(set(int(u) for u in sets[v]) | {int(v)})
-            branch_segs.append([s0 + u for u in mine])
-            for u in mine:
-                readers[s0 + u].append(r)
-            q_rows.append(q_tok[start[v + 1] - 1] if keep_tokens else normal_tensor(rng, (hq, d), q_scale, dtype))
-            live_tok.append(int(start[v + 1] - 1))
+            for i in range(n_new):
+                r = len(branch_segs)
+                tok = int(start[v + 1]) - n_new + i
+                branch_segs.append([s0 + u for u in mine])
+                for u in mine:
+                    readers[s0 + u].append(r)
+                    reader_len[s0 + u].append(int(L[u]) if u != v else tok - int(start[v]) + 1)
+                q_rows.append(q_tok[tok] if keep_tokens else normal_tensor(rng, (hq, d), q_scale, dtype))
+                live_tok.append(tok)
         s0 += len(L)
+        dag_index += 1
     n_live = len(branch_segs)
     seg_reader_off = np.zeros(len(seg_len) + 1, dtype=np.int32)
     seg_reader_off[1:] = np.cumsum([len(x) for x in readers])
@@ -319,6 +331,8 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
         seg_reader_off=seg_reader_off, seg_readers=flat(readers),
         branch_seg_off=branch_seg_off, branch_segs=flat(branch_segs),
     )
+    if new_tokens is not None:
+        desc["seg_reader_len"] = flat(reader_len)
     add_branch_entries(desc)
     return dict(desc=desc, k_pool=k_pool, v_pool=v_pool, q=torch.stack(q_rows) if q_rows else
                 torch.zeros((0, hq, d), dtype=dtype), tokens=toks, live_tok=live_tok, n_pages=n_pages)
