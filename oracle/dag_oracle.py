@@ -375,3 +375,46 @@ def lse_merge(partials):
     l = sum(p[2] * np.exp(p[1] - m) for p in partials)
     o = sum(p[0] * np.exp(p[1] - m) for p in partials)
     return o / l
+
+
+# ----------------------------------------------------------------------------- scheduling (section 3.3)
+def frontier_layers(parents):
+    """Enabled-transition frontiers F_0, F_1, ... of Eq. 1 under the execution loop of section 3.3.
+
+    Node v is the output place of one transition whose input places are parents[v] (converging
+    edges form one transition, diverging edges one transition per child); nodes without parents
+    have an empty pre-set.  The marking is the set of places that hold a token; a transition is
+    enabled when every input place is marked and its output place is empty; all enabled
+    transitions fire, then the marking advances and the frontier is recomputed, until nothing is
+    enabled.  Returns the list of frontiers (lists of node ids, ascending)."""
+    n = len(parents)
+    marked = [False] * n
+    layers = []
+    while True:
+        frontier = [v for v in range(n) if not marked[v] and all(marked[p] for p in parents[v])]
+        if not frontier:
+            return layers
+        layers.append(frontier)
+        for v in frontier:
+            marked[v] = True
+
+
+def schedule_steps(parents, node_len, chunk=None):
+    """The engine's steps: frontier after frontier; within a frontier every transition advances
+    by chunk[v] tokens per step (1 = token-by-token generation; more = a node whose text is
+    given and is prefilled in pieces) until its node_len[v] tokens exist, and the frontier is
+    complete when its longest transition is.  Returns a list of steps, each a list of
+    (node, first new token inside the node, number of new tokens), nodes ascending."""
+    chunk = [1] * len(parents) if chunk is None else chunk
+    steps = []
+    for frontier in frontier_layers(parents):
+        done = {v: 0 for v in frontier}
+        while any(done[v] < int(node_len[v]) for v in frontier):
+            step = []
+            for v in frontier:
+                n = min(int(chunk[v]), int(node_len[v]) - done[v])
+                if n > 0:
+                    step.append((v, done[v], n))
+                    done[v] += n
+            steps.append(step)
+    return steps

@@ -520,3 +520,49 @@ def test_segment_decode_with_reader_lengths_is_chunked_prefill_of_new_nodes():
     bad["seg_reader_len"] = np.full_like(desc["seg_reader_len"], 1 << 20)
     Ob = orc.attn_decode_segments(bad, st["q"].numpy(), st["k_pool"].numpy(), st["v_pool"].numpy())
     assert np.abs(O[st["live_tok"]] - Ob).max() > 1e-3
+
+
+# ----------------------------------------------------------------------------- scheduling
+def test_frontiers_of_textbook_nets():
+    # chain: one transition per frontier
+    assert orc.frontier_layers([[], [0], [1], [2]]) == [[0], [1], [2], [3]]
+    # fork / join: siblings fire together, the join after all of them (A, B -> C is one transition)
+    assert orc.frontier_layers([[], [0], [0], [0], [1, 2, 3]]) == [[0], [1, 2, 3], [4]]
+    # two roots, a join of both and a child of one: the child does not wait for the other root's join
+    assert orc.frontier_layers([[], [], [0, 1], [0]]) == [[0, 1], [2, 3]]
+    # an edge that skips a level does not let a node fire before its slowest parent
+    assert orc.frontier_layers([[], [0], [1], [0, 2]]) == [[0], [1], [2], [3]]
+    assert orc.frontier_layers([]) == []
+
+
+def test_frontier_index_is_the_longest_path_and_every_node_fires_once():
+    rng = np.random.Generator(np.random.PCG64(90))
+    for _ in range(20):
+        n = int(rng.integers(1, 40))
+        parents = [sorted(set(int(x) for x in rng.integers(0, v, size=int(rng.integers(0, 4))))) if v else []
+                   for v in range(n)]
+        layers = orc.frontier_layers(parents)
+        assert sorted(v for f in layers for v in f) == list(range(n))
+        depth = [0] * n                       # longest path to v, by dynamic programming over the topological order
+        for v in range(n):
+            depth[v] = 1 + max([depth[p] for p in parents[v]], default=-1)
+        for k, f in enumerate(layers):
+            assert all(depth[v] == k for v in f)
+
+
+def test_step_counts_parallel_against_serial():
+    """Token-by-token generation of prefix -> branches -> join takes prefix + longest branch + join
+    steps (the depth of the plan), a chain with the same tokens takes their sum (section 5,
+    latency argument); chunks shorten a frontier to ceil(len / chunk)."""
+    parents = [[], [0], [0], [0], [1, 2, 3]]
+    L = [7, 5, 11, 3, 4]
+    steps = orc.schedule_steps(parents, L)
+    assert len(steps) == 7 + 11 + 4
+    assert sum(n for s in steps for _, _, n in s) == sum(L)
+    assert steps[7] == [(1, 0, 1), (2, 0, 1), (3, 0, 1)] and steps[7 + 3] == [(1, 3, 1), (2, 3, 1)]
+    assert steps[7 + 10] == [(2, 10, 1)] and steps[-1] == [(4, 3, 1)]
+    chain = [[]] + [[v] for v in range(4)]
+    assert len(orc.schedule_steps(chain, L)) == sum(L)
+    chunked = orc.schedule_steps(parents, L, chunk=[4, 1, 1, 1, 3])
+    assert len(chunked) == 2 + 11 + 2
+    assert chunked[0] == [(0, 0, 4)] and chunked[1] == [(0, 4, 3)] and chunked[-1] == [(4, 3, 1)]
