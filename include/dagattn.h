@@ -271,6 +271,57 @@ int dag_attn_decode_segments(const dag_decode_seg_desc_t* desc, const void* q, c
                              const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
                              float softmax_scale, void* ws, size_t ws_bytes, void* stream);
 
+/* Host-side scheduler of the execution phase (section 3.2: the plan as a Petri net whose places
+ * are the DAG nodes, one transition per node with its parents as input places; section 3.3, Eq. 1:
+ * the enabled-transition frontier fires as a whole and the marking advances when all of it is
+ * complete; Fork = children read the parent's pages by reference, Join = a node reads the
+ * histories of all its predecessors).  Pure HOST code, no GPU call: it decides which transitions
+ * are live, hands out pages of the KV pool (never copied, never moved), assigns adaptive positions
+ * (section 4.2) and writes, per step, the descriptions dag_kv_append_rope and
+ * dag_attn_decode_segments take.  The caller uploads them and runs the model between steps.
+ *
+ * dag_sched_create: nodes in topological order (parents[parent_off[v] .. parent_off[v+1]) < v,
+ * else DAG_ERR_NOT_TOPOLOGICAL); node_len[v] >= 1 tokens to produce for node v; chunk[v] >= 1
+ * tokens per step (NULL: 1 everywhere = token-by-token generation; more for a node whose text is
+ * given, e.g. the prompt or a step header, which is then prefilled in pieces); n_pages pages of
+ * page_size (16) tokens in the pool, handed out in ascending order.  All arrays HOST, copied.
+ * dag_sched_destroy frees the object (NULL allowed). */
+typedef struct dag_sched dag_sched_t;
+int dag_sched_create(int32_t n_nodes, const int32_t* parent_off, const int32_t* parents,
+                     const int32_t* node_len, const int32_t* chunk, int32_t n_pages, int32_t page_size,
+                     dag_sched_t** out);
+void dag_sched_destroy(dag_sched_t* sched);
+
+/* One step: n_live new tokens ("live branches"; 0 = the net has no enabled transition left).
+ * Entry r is token live_token[r] of node live_node[r]; the caller feeds the model with these
+ * tokens, stores their K/V with dag_kv_append_rope (branch_* arrays: the node's page list, the
+ * token count of the node including entry r, its adaptive position) and attends with
+ * dag_attn_decode_segments (seg_* / branch_entr* arrays and the four host bounds; segment i holds
+ * node seg_node[i]).  All pointers are HOST memory owned by the scheduler, valid until the next
+ * call on it; the caller copies them to the device.  DAG_ERR_WORKSPACE when the pool has too few
+ * free pages for the step (nothing is changed then). */
+typedef struct {
+  int32_t n_live, layer;          /* layer: index k of the frontier F_k the step belongs to         */
+  int32_t n_segments, max_seg_pages, max_readers, total_readers;
+  int32_t n_branch_pages, n_seg_pages, pages_in_use;
+  const int32_t* live_node;       /* [n_live]                                                       */
+  const int32_t* live_token;      /* [n_live] index of the token inside its node                    */
+  const int32_t* branch_page_off; /* [n_live+1] into branch_pages                                   */
+  const int32_t* branch_pages;    /* [n_branch_pages]                                               */
+  const int32_t* branch_len;      /* [n_live]                                                       */
+  const int32_t* branch_pos;      /* [n_live]                                                       */
+  const int32_t* seg_node;        /* [n_segments]                                                   */
+  const int32_t* seg_page_off;    /* [n_segments+1] into seg_pages                                  */
+  const int32_t* seg_pages;       /* [n_seg_pages]                                                  */
+  const int32_t* seg_len;         /* [n_segments]                                                   */
+  const int32_t* seg_reader_off;  /* [n_segments+1]                                                 */
+  const int32_t* seg_readers;     /* [total_readers]                                                */
+  const int32_t* seg_reader_len;  /* [total_readers]                                                */
+  const int32_t* branch_entry_off;/* [n_live+1]                                                     */
+  const int32_t* branch_entries;  /* [total_readers]                                                */
+} dag_sched_step_t;
+int dag_sched_step(dag_sched_t* sched, dag_sched_step_t* out);
+
 const char* dag_strerror(int code);
 int dag_version(void);
 

@@ -72,6 +72,17 @@ class dag_decode_seg_desc_t(C.Structure):
                 [(name, C.c_void_p) for name in _SEG_ARRAYS] + [("seg_reader_len", C.c_void_p)])
 
 
+_SCHED_ARRAYS = ("live_node", "live_token", "branch_page_off", "branch_pages", "branch_len", "branch_pos",
+                 "seg_node", "seg_page_off", "seg_pages", "seg_len", "seg_reader_off", "seg_readers",
+                 "seg_reader_len", "branch_entry_off", "branch_entries")
+
+
+class dag_sched_step_t(C.Structure):
+    _fields_ = ([(name, C.c_int32) for name in ("n_live", "layer", "n_segments", "max_seg_pages", "max_readers",
+                                                "total_readers", "n_branch_pages", "n_seg_pages", "pages_in_use")] +
+                [(name, C.POINTER(C.c_int32)) for name in _SCHED_ARRAYS])
+
+
 _lib = None
 
 
@@ -103,12 +114,17 @@ def lib():
         L.dag_decode_segments_workspace_bytes.restype = C.c_size_t
         L.dag_attn_decode_segments.argtypes = [C.POINTER(dag_decode_seg_desc_t), vp, vp, vp, vp, i32, i32, i32, f32,
                                                vp, C.c_size_t, vp]
+        L.dag_sched_create.argtypes = [i32, vp, vp, vp, vp, i32, i32, C.POINTER(vp)]
+        L.dag_sched_destroy.argtypes = [vp]
+        L.dag_sched_destroy.restype = None
+        L.dag_sched_step.argtypes = [vp, C.POINTER(dag_sched_step_t)]
         L.dag_strerror.argtypes = [C.c_int]
         L.dag_strerror.restype = C.c_char_p
         L.dag_version.restype = C.c_int
         for name in ("dag_prefill_tile_shape", "dag_meta_sizes", "dag_build_meta", "dag_rope_qk",
                      "dag_attn_prefill", "dag_attn_prefill_prepared", "dag_prefill_prepare_v",
-                     "dag_kv_append_rope", "dag_attn_decode", "dag_attn_decode_segments"):
+                     "dag_kv_append_rope", "dag_attn_decode", "dag_attn_decode_segments", "dag_sched_create",
+                     "dag_sched_step"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -323,3 +339,48 @@ def dag_attn_decode_segments(sdesc, q, k_pool, v_pool, out, workspace, softmax_s
         softmax_scale = 1.0 / float(d) ** 0.5
     _check(lib().dag_attn_decode_segments(C.byref(sdesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(out), hq, hkv,
                                           d, float(softmax_scale), _ptr(workspace), workspace.numel(), _stream()))
+
+
+class Scheduler:
+    """dag_sched_*: the host-side scheduler of the execution phase.  step() returns a dict of
+    numpy copies of the step's arrays (None when the net is finished)."""
+
+    def __init__(self, parents, node_len, n_pages, chunk=None, page_size=16):
+        n = len(parents)
+        off = np.zeros(n + 1, dtype=np.int32)
+        off[1:] = np.cumsum([len(p) for p in parents])
+        flat = np.asarray([x for p in parents for x in p] or [0], dtype=np.int32)
+        ln = np.ascontiguousarray(node_len, dtype=np.int32)
+        ch = None if chunk is None else np.ascontiguousarray(chunk, dtype=np.int32)
+        self.h = C.c_void_p()
+        _check(lib().dag_sched_create(n, off.ctypes.data, flat.ctypes.data, ln.ctypes.data if n else None,
+                                      None if ch is None else ch.ctypes.data, int(n_pages), int(page_size),
+                                      C.byref(self.h)))
+
+    def step(self):
+        st = dag_sched_step_t()
+        _check(lib().dag_sched_step(self.h, C.byref(st)))
+        if st.n_live == 0:
+            return None
+        sizes = dict(live_node=st.n_live, live_token=st.n_live, branch_page_off=st.n_live + 1,
+                     branch_pages=st.n_branch_pages, branch_len=st.n_live, branch_pos=st.n_live,
+                     seg_node=st.n_segments, seg_page_off=st.n_segments + 1, seg_pages=st.n_seg_pages,
+                     seg_len=st.n_segments, seg_reader_off=st.n_segments + 1, seg_readers=st.total_readers,
+                     seg_reader_len=st.total_readers, branch_entry_off=st.n_live + 1,
+                     branch_entries=st.total_readers)
+        out = {k: np.ctypeslib.as_array(getattr(st, k), shape=(n,)).copy() if n else np.zeros(0, np.int32)
+               for k, n in sizes.items()}
+        out.update(n_live=st.n_live, layer=st.layer, n_segments=st.n_segments, page_size=16,
+                   pages_in_use=st.pages_in_use)
+        return out
+
+    def close(self):
+        if self.h:
+            lib().dag_sched_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -215,3 +215,109 @@ def test_segment_decode_argument_errors():
     assert L.dag_attn_decode_segments(C.byref(no_arrays), p, p, p, p, *args, p, need, None) == -1
     empty = B.dag_decode_seg_desc_t(0, 0, 16, 0, 0, 0, *([0] * 7), None)
     assert L.dag_attn_decode_segments(C.byref(empty), p, p, p, p, *args, None, 0, None) == 0
+
+
+# ----------------------------------------------------------------------------- scheduler (host only)
+def _run_schedule(parents, node_len, chunk=None, n_pages=4096):
+    sch = B.Scheduler(parents, node_len, n_pages, chunk)
+    steps = []
+    while True:
+        st = sch.step()
+        if st is None:
+            break
+        steps.append(st)
+    assert sch.step() is None          # stays finished
+    sch.close()
+    return steps
+
+
+def _as_oracle_steps(steps):
+    out = []
+    for st in steps:
+        cur = []
+        for v, t in zip(st["live_node"], st["live_token"]):
+            if cur and cur[-1][0] == v:
+                cur[-1] = (v, cur[-1][1], cur[-1][2] + 1)
+            else:
+                cur.append((int(v), int(t), 1))
+        out.append(cur)
+    return out
+
+
+def test_scheduler_steps_equal_the_oracle_schedule():
+    from oracle import dag_oracle as orc
+    rng = np.random.Generator(np.random.PCG64(91))
+    cases = [([[], [0], [0], [0], [1, 2, 3]], [7, 5, 11, 3, 4], None),
+             ([[], [0], [0], [0], [1, 2, 3]], [7, 5, 11, 3, 4], [4, 1, 1, 1, 3]),
+             ([[], [], [0, 1], [0]], [20, 3, 2, 9], [16, 16, 1, 1])]
+    for _ in range(6):
+        n = int(rng.integers(1, 30))
+        parents = [sorted(set(int(x) for x in rng.integers(0, v, size=int(rng.integers(0, 4))))) if v else []
+                   for v in range(n)]
+        cases.append((parents, [int(x) for x in rng.integers(1, 40, size=n)],
+                      [int(x) for x in rng.integers(1, 9, size=n)]))
+    for parents, L, chunk in cases:
+        steps = _run_schedule(parents, L, chunk)
+        assert _as_oracle_steps(steps) == orc.schedule_steps(parents, L, chunk)
+        layers = orc.frontier_layers(parents)
+        for st in steps:
+            assert set(int(v) for v in st["live_node"]) <= set(layers[st["layer"]])
+
+
+def test_scheduler_pages_positions_and_descriptions():
+    """Fork/join on pages and positions: children start one past the parent's last position,
+    the join one past the longest branch; pages are never shared between nodes nor moved; every
+    live token reads exactly its ancestors in full and its own node up to itself."""
+    from oracle import dag_oracle as orc
+    from workloads import dags
+    parents = [[], [0], [0], [0], [1, 2, 3]]
+    L = [37, 5, 40, 16, 20]
+    steps = _run_schedule(parents, L, chunk=[16, 1, 1, 1, 8])
+    anc = dags.bits_from_sets(dags.closure_from_parents(parents))
+    pos_start = orc.node_tables(np.asarray(L), anc)[1]
+    pages_of, seen_pos = {}, {}
+    for st in steps:
+        for r in range(st["n_live"]):
+            v, t = int(st["live_node"][r]), int(st["live_token"][r])
+            assert st["branch_pos"][r] == pos_start[v] + t and st["branch_len"][r] == t + 1
+            pl = list(st["branch_pages"][st["branch_page_off"][r]:st["branch_page_off"][r + 1]])
+            assert len(pl) == (st["seg_len"][list(st["seg_node"]).index(v)] + 15) // 16
+            old = pages_of.get(v, [])
+            assert pl[:len(old)] == old            # a node's pages only grow
+            pages_of[v] = pl
+            seen_pos[(v, t)] = True
+            mine = st["branch_entries"][st["branch_entry_off"][r]:st["branch_entry_off"][r + 1]]
+            read = {}
+            for e in mine:
+                assert st["seg_readers"][e] == r
+                si = int(np.searchsorted(st["seg_reader_off"], e, side="right") - 1)
+                read[int(st["seg_node"][si])] = int(st["seg_reader_len"][e])
+            want = {u: L[u] for u in orc.ancestors(anc, v)}
+            want[v] = t + 1
+            assert read == want
+        assert st["pages_in_use"] == sum(len(p) for p in pages_of.values())
+    flat = [p for pl in pages_of.values() for p in pl]
+    assert len(flat) == len(set(flat)) == sum((x + 15) // 16 for x in L)
+    assert len(seen_pos) == sum(L)
+
+
+def test_scheduler_argument_errors_and_page_exhaustion():
+    L = B.lib()
+    h = C.c_void_p()
+    off = (C.c_int32 * 3)(0, 0, 1)
+    par = (C.c_int32 * 1)(0)
+    ln = (C.c_int32 * 2)(20, 5)
+    assert L.dag_sched_create(2, off, par, ln, None, 8, 16, None) == -1
+    assert L.dag_sched_create(2, off, par, ln, None, 8, 32, C.byref(h)) == -7
+    bad_par = (C.c_int32 * 1)(1)
+    assert L.dag_sched_create(2, off, bad_par, ln, None, 8, 16, C.byref(h)) == -3
+    bad_len = (C.c_int32 * 2)(20, 0)
+    assert L.dag_sched_create(2, off, par, bad_len, None, 8, 16, C.byref(h)) == -2
+    assert L.dag_sched_create(2, off, par, ln, None, 2, 16, C.byref(h)) == 0      # 3 pages needed, 2 in the pool
+    st = B.dag_sched_step_t()
+    rcs = []
+    for _ in range(26):
+        rcs.append(L.dag_sched_step(h, C.byref(st)))
+    assert rcs[:20] == [0] * 20 and rcs[20] == -6 and rcs[25] == -6      # node 1 never gets its page
+    L.dag_sched_destroy(h)
+    L.dag_sched_destroy(None)
