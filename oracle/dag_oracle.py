@@ -244,6 +244,40 @@ def attn_prefill(q, k, v, node_len, anc, scale=None, row_block=128, rows=None, h
     return O, lse
 
 
+def attn_prefill_bwd(q, k, v, dout, node_len, anc, scale=None):
+    """Gradients of L = sum(dout * O) for O = attn_prefill(q, k, v) (Eq. 2 + Eq. 3; the paper
+    fine-tunes through this mask, section 4.2), written out from the definition in fp64:
+        P = softmax_row(scale * Q K^T + M),  O = P V,  delta_i = sum_d dO_id O_id,
+        dV = P^T dO,  dP = dO V^T,  dS = P * (dP - delta),  dQ = scale * dS K,  dK = scale * dS^T Q,
+    the gradients of a KV head summed over its query heads.  q and k are the rotated tensors;
+    returns (dq, dk, dv) with their shapes."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    allow = explicit_mask(node_len, anc)
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for h in range(Hq):
+        hk = h // G
+        S = (q[:, h, :] @ k[:, hk, :].T) * scale
+        S[~allow] = -np.inf
+        P = np.exp(S - S.max(axis=1, keepdims=True))
+        P /= P.sum(axis=1, keepdims=True)
+        O = P @ v[:, hk, :]
+        delta = np.sum(dout[:, h, :] * O, axis=1, keepdims=True)
+        dP = dout[:, h, :] @ v[:, hk, :].T
+        dS = P * (dP - delta)
+        dv[:, hk, :] += P.T @ dout[:, h, :]
+        dq[:, h, :] = (dS @ k[:, hk, :]) * scale
+        dk[:, hk, :] += (dS.T @ q[:, h, :]) * scale
+    return dq, dk, dv
+
+
 # ----------------------------------------------------------------------------- paged KV
 def pool_get_k(k_pool, page, h, slot):
     """Key vector [D] of (page, kv head, slot) from the K pool format [P][Hkv][D/8][16][8]."""

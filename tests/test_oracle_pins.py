@@ -566,3 +566,68 @@ def test_step_counts_parallel_against_serial():
     chunked = orc.schedule_steps(parents, L, chunk=[4, 1, 1, 1, 3])
     assert len(chunked) == 2 + 11 + 2
     assert chunked[0] == [(0, 0, 4)] and chunked[1] == [(0, 4, 3)] and chunked[-1] == [(4, 3, 1)]
+
+
+# ----------------------------------------------------------------------------- backward
+def _bwd_fixture(seed=95, hq=4, hkv=2, d=8):
+    L, anc = _multilevel_dag()
+    L = np.asarray([5, 3, 2, 4, 1, 3, 2, 2, 3], dtype=np.int32)
+    T = int(L.sum())
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q, k, v = rng.standard_normal((T, hq, d)), rng.standard_normal((T, hkv, d)), rng.standard_normal((T, hkv, d))
+    dout = rng.standard_normal((T, hq, d))
+    return L, anc, q, k, v, dout
+
+
+def test_backward_equals_central_differences_of_the_forward_oracle():
+    """d/dx sum(dout * O(x)) by central differences on sampled entries of q, k and v (GQA: a KV
+    entry feeds two query heads; a node with a join: masked pairs carry no gradient)."""
+    L, anc, q, k, v, dout = _bwd_fixture()
+    dq, dk, dv = orc.attn_prefill_bwd(q, k, v, dout, L, anc, scale=0.4)
+    loss = lambda q_, k_, v_: float(np.sum(dout * orc.attn_prefill(q_, k_, v_, L, anc, scale=0.4)[0]))
+    rng = np.random.Generator(np.random.PCG64(96))
+    eps = 1e-6
+    for name, x, g in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        for _ in range(12):
+            idx = tuple(int(rng.integers(n)) for n in x.shape)
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += eps
+            xm[idx] -= eps
+            args_p = {"q": (xp, k, v), "k": (q, xp, v), "v": (q, k, xp)}[name]
+            args_m = {"q": (xm, k, v), "k": (q, xm, v), "v": (q, k, xm)}[name]
+            num = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            assert abs(num - g[idx]) < 1e-7 * max(1.0, abs(num)), (name, idx, num, g[idx])
+
+
+def test_backward_equals_library_autograd_on_the_explicit_mask():
+    L, anc, q, k, v, dout = _bwd_fixture(seed=97, hq=6, hkv=2, d=4)
+    dq, dk, dv = orc.attn_prefill_bwd(q, k, v, dout, L, anc)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    allow = torch.from_numpy(orc.explicit_mask(L, anc))
+    G = q.shape[1] // k.shape[1]
+    kk, vv = tk.repeat_interleave(G, dim=1), tv.repeat_interleave(G, dim=1)
+    S = torch.einsum("ihd,jhd->hij", tq, kk) / np.sqrt(q.shape[2])
+    P = torch.softmax(S.masked_fill(~allow[None], float("-inf")), dim=-1)
+    O = torch.einsum("hij,jhd->ihd", P, vv)
+    (O * torch.from_numpy(dout)).sum().backward()
+    for a, b in ((dq, tq.grad), (dk, tk.grad), (dv, tv.grad)):
+        assert np.abs(a - b.numpy()).max() < 1e-12
+
+
+def test_backward_structure():
+    """A token nobody but itself sees gets dk, dv only from its own row; masked pairs carry
+    nothing: the last token of a leaf node is seen only by itself."""
+    L, anc, q, k, v, dout = _bwd_fixture(seed=98)
+    dq, dk, dv = orc.attn_prefill_bwd(q, k, v, dout, L, anc)
+    t = int(np.cumsum(L)[6] - 1)          # last token of node 6 (a leaf)
+    G = q.shape[1] // k.shape[1]
+    allow = orc.explicit_mask(L, anc)
+    assert allow[:, t].sum() == 1
+    for hk in range(k.shape[1]):
+        want = np.zeros(v.shape[2])
+        for h in range(hk * G, (hk + 1) * G):
+            s = (k[allow[t], hk] @ q[t, h]) / np.sqrt(q.shape[2])
+            p = np.exp(s - s.max()); p /= p.sum()
+            want += p[-1] * dout[t, h]     # the token is the last visible key of its own row
+        assert np.abs(dv[t, hk] - want).max() < 1e-12
+    assert np.isfinite(dq).all() and np.isfinite(dk).all()
