@@ -173,6 +173,23 @@ int dag_attn_prefill_prepared(const dag_meta_t* meta, const void* q, const void*
 size_t dag_prefill_workspace_bytes(const dag_meta_t* meta, int32_t hkv, int32_t head_dim,
                                    dag_dtype_t dtype);
 
+/* Backward of dag_attn_prefill (section 4.2: the model is fine-tuned through the mask of Eq. 3):
+ * from the incoming gradient dout [T][hq][head_dim] of the attention output, the forward's inputs
+ * (q and k rotated, as the forward took them), its output `out` and log-sum-exp `lse` [T][hq]
+ * (natural log, as dag_attn_prefill writes it), compute
+ *   dq [T][hq][head_dim], dk and dv [T][hkv][head_dim]   (gradients w.r.t. the rotated q and k; a KV
+ *   head's gradient is the sum over its query heads)
+ * with P recomputed from lse: dV = P^T dO, dS = P o (dO V^T - rowsum(dO o O)), dQ = scale dS K,
+ * dK = scale dS^T Q, only over the tiles the block map marks visible.  DAG_BF16 only (fp32
+ * accumulation), head_dim 128 or 64; all tensors DEVICE, 16-byte aligned; `ws` DEVICE scratch of
+ * dag_prefill_bwd_workspace_bytes.  No atomics: results are bit-identical from run to run.
+ * Errors as dag_attn_prefill. */
+size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* meta, int32_t hq);
+int dag_attn_prefill_bwd(const dag_meta_t* meta, const void* q, const void* k, const void* v,
+                         const void* out, const void* dout, const float* lse, void* dq, void* dk,
+                         void* dv, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale,
+                         dag_dtype_t dtype, void* ws, size_t ws_bytes, void* stream);
+
 /* One decode step over a paged KV cache (section 3.2: a token carries KV-cache indices, not
  * copies; section 4.3 Fork: sibling branches share the prefix KV without copying).  The struct
  * lives on the HOST; arrays are DEVICE int32.  A sibling group is a set of live branches that

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libdagattn.so")
-SOURCES = ["api.hip", "meta.hip", "rope.hip", "prefill_f32.hip", "prefill_bf16.hip", "decode.hip", "sched.hip"]
+SOURCES = ["api.hip", "meta.hip", "rope.hip", "prefill_f32.hip", "prefill_bf16.hip", "prefill_bwd.hip", "decode.hip", "sched.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -1,0 +1,95 @@
+"""GPU parity: dag_attn_prefill_bwd (through the C ABI) against the fp64 oracle's gradients."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dag_oracle as orc
+from paper_2602_07529_amd import binding as B
+from workloads import dags
+from tests.gpu_util import DEV, build_meta
+
+pytestmark = pytest.mark.gpu
+
+
+def check_close(got, ref, dtype, what=""):
+    """The forward's tolerances (max |diff| <= 2e-2, Frobenius ratio <= 1e-2) with the absolute
+    bound scaled by the largest reference magnitude: gradients are sums over rows and query heads
+    and reach several units, where the bf16 rounding of the result alone is 2^-9 of the value."""
+    g = got.detach().cpu().to(torch.float64).numpy()
+    assert np.isfinite(g).all(), what + ": non-finite output"
+    max_abs = float(np.abs(g - ref).max())
+    rel = float(np.linalg.norm(g - ref) / max(np.linalg.norm(ref), 1e-30))
+    atol = 2e-2 * max(1.0, float(np.abs(ref).max()))
+    assert max_abs <= atol and rel <= 1e-2, "%s: max_abs %.3e (tol %.1e) rel %.3e (tol 1e-2)" % (what, max_abs, atol, rel)
+    return max_abs, rel
+
+
+def _forward_backward(dag_list, hq, hkv, d, seed, scale=None, theta=5e5):
+    T = int(sum(int(np.sum(L)) for L, _ in dag_list))
+    q, k, v = dags.make_qkv(seed, T, hq, hkv, d, 0.7, torch.bfloat16)
+    dout = dags.make_qkv(seed + 1, T, hq, hkv, d, 1.0, torch.bfloat16)[0]
+    _, meta = build_meta(dag_list, hq, hkv, d, torch.bfloat16)
+    qd, kd, vd, dod = q.to(DEV).clone(), k.to(DEV).clone(), v.to(DEV), dout.to(DEV)
+    B.dag_rope_qk(meta.get("pos_ids"), qd, kd, theta)
+    out = torch.empty_like(qd)
+    lse = torch.empty(T, hq, dtype=torch.float32, device=DEV)
+    B.dag_attn_prefill(meta, qd, kd, vd, out, lse, softmax_scale=scale)
+    dq, dk, dv = torch.full_like(qd, float("nan")), torch.full_like(kd, float("nan")), torch.full_like(vd, float("nan"))
+    B.dag_attn_prefill_bwd(meta, qd, kd, vd, out, dod, lse, dq, dk, dv, softmax_scale=scale)
+    torch.cuda.synchronize()
+    return (qd, kd, v, dout), (dq, dk, dv)
+
+
+def _check_against_oracle(dag_list, inputs, grads, scale=None):
+    """The oracle takes one sequence at a time; the tolerances apply to the whole tensors (a
+    single-token sequence has dq = dk = 0 exactly, against which no ratio can be taken)."""
+    qd, kd, v, dout = inputs
+    refs, t0 = [], 0
+    for L, anc in dag_list:
+        Tb = int(np.sum(L))
+        sl = slice(t0, t0 + Tb)
+        refs.append(orc.attn_prefill_bwd(dags.to_f64(qd[sl]), dags.to_f64(kd[sl]), dags.to_f64(v[sl]),
+                                         dags.to_f64(dout[sl]), L, anc, scale=scale))
+        t0 += Tb
+    for x, (name, g) in enumerate(zip(("dq", "dk", "dv"), grads)):
+        check_close(g, np.concatenate([r[x] for r in refs]), torch.bfloat16, name)
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 1, 128), (8, 2, 64), (5, 1, 128), (2, 2, 64), (3, 1, 64), (8, 2, 128)])
+def test_bwd_small_dags_every_head_grouping(hq, hkv, d):
+    rng = np.random.Generator(np.random.PCG64(3000 + hq * 10 + d))
+    dag_list = [dags.fork_join(100, [37, 64, 5], 70),               # ragged everywhere
+                dags.random_dag(rng, n_nodes=14, depth=4, len_lo=1, len_hi=45)[:2],
+                dags.linear_chain([1]),
+                dags.linear_chain([200])]
+    inputs, grads = _forward_backward(dag_list, hq, hkv, d, 4000 + hq + d)
+    _check_against_oracle(dag_list, inputs, grads)
+
+
+def test_bwd_more_than_64_nodes_and_a_scale():
+    rng = np.random.Generator(np.random.PCG64(79))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=90, depth=6, len_lo=1, len_hi=12)
+    inputs, grads = _forward_backward([(L, anc)], 4, 1, 128, 35, scale=0.05)
+    _check_against_oracle([(L, anc)], inputs, grads, scale=0.05)
+
+
+def test_bwd_is_deterministic_run_to_run():
+    dag_list = [dags.fork_join(300, [100, 90], 50)]
+    _, g1 = _forward_backward(dag_list, 8, 2, 128, 52)
+    _, g2 = _forward_backward(dag_list, 8, 2, 128, 52)
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)
+
+
+def test_bwd_linear_chain_equals_library_autograd_of_causal_attention():
+    """Independent of the oracle: torch autograd (fp32, CPU) of causal SDPA on the GPU-rotated inputs."""
+    dag_list = [dags.linear_chain([50, 150, 56])]
+    (qd, kd, v, dout), (dq, dk, dv) = _forward_backward(dag_list, 8, 2, 128, 41)
+    tq = qd.float().cpu().permute(1, 0, 2)[None].requires_grad_(True)
+    tk = kd.float().cpu().permute(1, 0, 2)[None].requires_grad_(True)
+    tv = v.float().permute(1, 0, 2)[None].requires_grad_(True)
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk.repeat_interleave(4, dim=1), tv.repeat_interleave(4, dim=1),
+                                                         is_causal=True)
+    (o * dout.float().permute(1, 0, 2)[None]).sum().backward()
+    for name, g, r in (("dq", dq, tq.grad), ("dk", dk, tk.grad), ("dv", dv, tv.grad)):
+        check_close(g, r[0].permute(1, 0, 2).double().numpy(), torch.bfloat16, name + " vs autograd")
