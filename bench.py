@@ -261,6 +261,25 @@ def main():
     ms_seg = sev[0].elapsed_time(sev[1]) / args.steps
     seg_gbs = sw.bytes / (ms_seg * 1e-3) / 1e9
 
+    # beside the timed region: the backward of the prefill attention on the same workload
+    lse = torch.empty(pw.T, pw.cfg["hq"], dtype=torch.float32, device=dev)
+    B.dag_attn_prefill(pw.meta, pw.q, pw.k, pw.v, pw.out, lse)
+    dout = torch.randn(pw.q.shape, device=dev, generator=torch.Generator(device=dev).manual_seed(pw.cfg["seed"])).to(pw.q.dtype)
+    dq, dk, dv = torch.empty_like(pw.q), torch.empty_like(pw.k), torch.empty_like(pw.v)
+    bws = torch.empty(B.dag_prefill_bwd_workspace_bytes(pw.meta, pw.cfg["hq"], pw.cfg["hkv"], pw.cfg["d"]),
+                      dtype=torch.uint8, device=dev)
+    bwd = lambda: B.dag_attn_prefill_bwd(pw.meta, pw.q, pw.k, pw.v, pw.out, dout, lse, dq, dk, dv, workspace=bws)
+    n_bwd = max(1, min(args.steps, 10))
+    for _ in range(min(args.warmup, 3)):
+        bwd()
+    bev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    bev[0].record()
+    for _ in range(n_bwd):
+        bwd()
+    bev[1].record()
+    torch.cuda.synchronize()
+    ms_bwd = bev[0].elapsed_time(bev[1]) / n_bwd
+
     flops, pairs = pw.useful_flops()
     mean = lambda xs: float(np.mean(xs))
     ms_step, ms_pre, ms_attn, ms_dec, ms_deck = map(mean, (step_ms, pre_ms, attn_ms, dec_ms, deck_ms))
@@ -302,6 +321,13 @@ def main():
                                          "achieved": seg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                          "frac": seg_gbs / HBM_PEAK_GBS, "algorithmic_bytes": sw.bytes,
                                          "traffic": None}},
+        "prefill_bwd": {"metric": "dag_attn_prefill_bwd_useful_tflops", "value": 2.5 * flops / (ms_bwd * 1e-3) / 1e12,
+                        "unit": "TFLOP/s", "ms_per_call": ms_bwd, "calls": n_bwd,
+                        "useful_flops": "2.5 x forward (five products per visible pair)",
+                        "roofline": {"bound": "mfma", "kernel": "k_bwd_delta+k_bwd_transpose+k_bwd_dq+k_bwd_dkv",
+                                     "achieved": 2.5 * flops / (ms_bwd * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                     "unit": "TFLOP/s", "frac": 2.5 * flops / (ms_bwd * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                     "traffic": None}},
         "wall_s_timed_loop": wall,
     }
     if not args.no_cpu_baseline:

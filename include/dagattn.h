@@ -184,7 +184,7 @@ size_t dag_prefill_workspace_bytes(const dag_meta_t* meta, int32_t hkv, int32_t 
  * accumulation), head_dim 128 or 64; all tensors DEVICE, 16-byte aligned; `ws` DEVICE scratch of
  * dag_prefill_bwd_workspace_bytes.  No atomics: results are bit-identical from run to run.
  * Errors as dag_attn_prefill. */
-size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* meta, int32_t hq);
+size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* meta, int32_t hq, int32_t hkv, int32_t head_dim);
 int dag_attn_prefill_bwd(const dag_meta_t* meta, const void* q, const void* k, const void* v,
                          const void* out, const void* dout, const float* lse, void* dq, void* dk,
                          void* dv, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale,

@@ -244,13 +244,14 @@ def attn_prefill(q, k, v, node_len, anc, scale=None, row_block=128, rows=None, h
     return O, lse
 
 
-def attn_prefill_bwd(q, k, v, dout, node_len, anc, scale=None):
+def attn_prefill_bwd(q, k, v, dout, node_len, anc, scale=None, kv_heads=None):
     """Gradients of L = sum(dout * O) for O = attn_prefill(q, k, v) (Eq. 2 + Eq. 3; the paper
     fine-tunes through this mask, section 4.2), written out from the definition in fp64:
         P = softmax_row(scale * Q K^T + M),  O = P V,  delta_i = sum_d dO_id O_id,
         dV = P^T dO,  dP = dO V^T,  dS = P * (dP - delta),  dQ = scale * dS K,  dK = scale * dS^T Q,
     the gradients of a KV head summed over its query heads.  q and k are the rotated tensors;
-    returns (dq, dk, dv) with their shapes."""
+    returns (dq, dk, dv) with their shapes (with kv_heads given, only those KV heads and their
+    query heads are computed, the rest stays zero)."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
@@ -264,6 +265,8 @@ def attn_prefill_bwd(q, k, v, dout, node_len, anc, scale=None):
     dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
     for h in range(Hq):
         hk = h // G
+        if kv_heads is not None and hk not in kv_heads:
+            continue
         S = (q[:, h, :] @ k[:, hk, :].T) * scale
         S[~allow] = -np.inf
         P = np.exp(S - S.max(axis=1, keepdims=True))

@@ -105,7 +105,7 @@ def lib():
         L.dag_prefill_prepare_v.argtypes = [C.POINTER(dag_meta_t), vp, i32, i32, i32, C.c_int, vp, C.c_size_t, vp]
         L.dag_prefill_workspace_bytes.argtypes = [C.POINTER(dag_meta_t), i32, i32, C.c_int]
         L.dag_prefill_workspace_bytes.restype = C.c_size_t
-        L.dag_prefill_bwd_workspace_bytes.argtypes = [C.POINTER(dag_meta_t), i32]
+        L.dag_prefill_bwd_workspace_bytes.argtypes = [C.POINTER(dag_meta_t), i32, i32, i32]
         L.dag_prefill_bwd_workspace_bytes.restype = C.c_size_t
         L.dag_attn_prefill_bwd.argtypes = [C.POINTER(dag_meta_t), vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32,
                                            f32, C.c_int, vp, C.c_size_t, vp]
@@ -391,14 +391,18 @@ class Scheduler:
             pass
 
 
+def dag_prefill_bwd_workspace_bytes(meta, hq, hkv, head_dim):
+    return int(lib().dag_prefill_bwd_workspace_bytes(C.byref(meta.c), hq, hkv, head_dim))
+
+
 def dag_attn_prefill_bwd(meta, q, k, v, out, dout, lse, dq, dk, dv, softmax_scale=None, workspace=None):
     T, hq, d = q.shape
     hkv = k.shape[1]
     if softmax_scale is None:
         softmax_scale = 1.0 / float(d) ** 0.5
     if workspace is None:
-        workspace = torch.empty(int(lib().dag_prefill_bwd_workspace_bytes(C.byref(meta.c), hq)), dtype=torch.uint8,
-                                device=q.device)
+        workspace = torch.empty(int(lib().dag_prefill_bwd_workspace_bytes(C.byref(meta.c), hq, hkv, d)),
+                                dtype=torch.uint8, device=q.device)
     _check(lib().dag_attn_prefill_bwd(C.byref(meta.c), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(dout), _ptr(lse),
                                       _ptr(dq), _ptr(dk), _ptr(dv), hq, hkv, d, float(softmax_scale),
                                       _dtype_code(q), _ptr(workspace), workspace.numel(), _stream()))

@@ -5,16 +5,21 @@
 // P is recomputed from the forward's log-sum-exp; the block map of the forward skips the tiles
 // without a visible pair.  bf16 operands on the 32x32x16 MFMA, fp32 accumulation.  Three kernels:
 //   k_bwd_delta   delta per (token, query head)
-//   k_bwd_dq      one workgroup per (64-row query tile, query head), loop over its key tiles
-//   k_bwd_dkv     one workgroup per (64-key tile, KV head), loop over the query tiles that see it
-//                 and the query heads of the group; nothing is accumulated through atomics, so
-//                 the results do not depend on the order of execution.
+//   k_bwd_transpose  the transposed tile images of K, Q and dO
+//   k_bwd_dq      one workgroup per (64-row query tile, KV head, up to 4 of its query heads), loop
+//                 over the tile's key tiles, which the heads share
+//   k_bwd_dkv     one workgroup per (pair of 64-key tiles, KV head), loop over the query tiles that
+//                 see it and the query heads of the group; nothing is accumulated through atomics,
+//                 so the results do not depend on the order of execution.
 // Register layout of a 32x32 MFMA result C = A B:  lane (L, H) = (lane % 32, lane / 32) holds
 // column L and the 16 rows rho_H(e) = 8 (e / 4) + 4 H + e % 4.  A result is used again as the B
 // operand of the next product (contraction over its rows) straight from the registers; the A
 // operand of that product is then gathered from LDS in the same row order.
-// First version: tiles are staged with plain loads between two workgroup barriers (no software
-// pipeline) and the transposed operands are gathered element by element from LDS.
+// Those A operands are transposed tiles (K^T for dQ; Q^T and dO^T for dK and dV): a pre-pass
+// writes them once into the workspace, tile by tile, as [D][64] images whose 64 columns are already
+// in the order rho asks for, so that the main kernels stage them with linear copies and read every
+// operand with one 16-byte LDS read.
+// Tiles are staged with plain loads between two workgroup barriers (no software pipeline yet).
 #include "common.h"
 
 namespace {
@@ -27,6 +32,7 @@ struct BwdArgs {
   const float* lse;
   uint16_t *dq, *dk, *dv;
   float* delta;  // [T][hq]
+  uint16_t *kt_img, *qt_img, *dot_img;  // transposed tile images [tile][head][D][64]
   const int32_t *cu_seqlens, *node_start, *tok_node, *qtile_start, *ktile_start;
   const uint64_t* node_vis;
   const int64_t* block_map_off;
@@ -54,21 +60,56 @@ __device__ __forceinline__ bool visible(const BwdArgs& a, int nbase, int ni, int
   return (w >> (nj & 63)) & 1u;
 }
 
-// 8 elements of column `col` of a row-major LDS tile (row stride LD), rows r0 + rho_H(8 ks + e):
-// the A operand of a product whose contraction runs over the rows of a previous result
-template <int LD>
-__device__ __forceinline__ bf16x8 gather_col(const uint16_t* tile, int r0, int ks, int H, int col) {
-  typedef __attribute__((ext_vector_type(8))) uint16_t u16x8;
-  u16x8 x;
+constexpr int LT = BN + 8;  // padded row of a transposed tile in LDS (elements)
+
+// Column order of a transposed tile: column c = 32 hh + 16 ks + 8 H + e holds row
+// 32 hh + rho_H(8 ks + e) of the tile, so the 8 elements lane (., H) needs for contraction step ks
+// of half hh are consecutive.
+__device__ __forceinline__ int row_of_column(int c) {
+  return (c & 32) + rho(8 * ((c >> 4) & 1) + (c & 7), (c >> 3) & 1);
+}
+
+// Pre-pass: src [T][heads][D] -> img [tile][head][D][64 columns in the order above]; rows past the
+// end of the sequence are zero.  One workgroup per (64-row tile, head).
+template <int D>
+__global__ void __launch_bounds__(256) k_bwd_transpose(const uint16_t* __restrict__ src, uint16_t* __restrict__ img,
+                                                       int heads, BwdArgs a) {
+  constexpr int LD = D + 8;
+  __shared__ __attribute__((aligned(16))) uint16_t s[BM * LD];
+  const int tile = blockIdx.x, h = blockIdx.y;
+  const int b = dag_find_segment(a.qtile_start, a.n_seqs, tile);
+  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
+  const int r0 = (tile - a.qtile_start[b]) * BM;
+  for (int c = threadIdx.x; c < BM * (D / 8); c += 256) {
+    const int r = c / (D / 8), ch = c % (D / 8);
+    u32x4 x = {0, 0, 0, 0};
+    if (r0 + r < T) x = *(const u32x4*)(src + ((size_t)(cu + r0 + r) * heads + h) * D + ch * 8);
+    *(u32x4*)(s + r * LD + ch * 8) = x;
+  }
+  __syncthreads();
+  uint16_t* o = img + ((size_t)tile * heads + h) * (size_t)(D * BM);
+  for (int p = threadIdx.x; p < D * (BM / 8); p += 256) {  // 16-byte piece: 8 columns of row d of the image
+    const int d = p % D, cg = p / D;
+    uint32_t w[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) x[e] = tile[(r0 + rho(8 * ks + e, H)) * LD + col];
-  return __builtin_bit_cast(bf16x8, x);
+    for (int e = 0; e < 4; ++e)
+      w[e] = (uint32_t)s[row_of_column(8 * cg + 2 * e) * LD + d] |
+             ((uint32_t)s[row_of_column(8 * cg + 2 * e + 1) * LD + d] << 16);
+    *(u32x4*)(o + (size_t)d * BM + 8 * cg) = u32x4{w[0], w[1], w[2], w[3]};
+  }
+}
+
+// stage one transposed image ([D][64], contiguous) into LDS rows of LT elements
+template <int D, int NT>
+__device__ __forceinline__ void stage_image(uint16_t* dst, const uint16_t* img, int tid) {
+  for (int p = tid; p < D * (BM / 8); p += NT) *(u32x4*)(dst + (p >> 3) * LT + (p & 7) * 8) = *(const u32x4*)(img + (size_t)p * 8);
 }
 
 template <int D>
-__global__ void __launch_bounds__(64) k_bwd_delta(BwdArgs a) {
-  const long row = blockIdx.x;  // (token, query head)
-  const int lane = threadIdx.x;
+__global__ void __launch_bounds__(256) k_bwd_delta(BwdArgs a) {
+  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);  // (token, query head)
+  if (row >= a.total_rows) return;
+  const int lane = threadIdx.x & 63;
   constexpr int PER = D / 64;
   float s = 0.f;
 #pragma unroll
@@ -81,22 +122,28 @@ __global__ void __launch_bounds__(64) k_bwd_delta(BwdArgs a) {
   if (lane == 0) a.delta[row] = s;
 }
 
-template <int D>
-__global__ void __launch_bounds__(128) k_bwd_dq(BwdArgs a) {
+template <int D, int HG>
+__global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
   constexpr int LD = D + 8;  // padded rows: the 16-byte operand reads of 32 consecutive rows spread over the banks
-  __shared__ __attribute__((aligned(16))) uint16_t sK[BN * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[BN * LD];
-  __shared__ int sNode[BN];
-  const int qt = blockIdx.x, h = blockIdx.y, hk = h / a.G;
+  constexpr int NT = 128 * HG;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* const sK = (uint16_t*)smem;   // [BN][LD]
+  uint16_t* const sV = sK + BN * LD;      // [BN][LD]
+  uint16_t* const sKT = sV + BN * LD;     // [D][LT]
+  int* const sNode = (int*)(sKT + D * LT);
+  const int qt = blockIdx.x, hk = blockIdx.y;
+  const int g = blockIdx.z * HG + (threadIdx.x >> 7);  // two waves per query head
+  const bool head_ok = g < a.G;
+  const int h = hk * a.G + min(g, a.G - 1);
   const int b = dag_find_segment(a.qtile_start, a.n_seqs, qt);
   const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
   const int qtl = qt - a.qtile_start[b];
   const int KT = (T + BN - 1) / BN;
   const uint8_t* bm = a.block_map + a.block_map_off[b] + (int64_t)qtl * KT;
   const int nbase = a.node_start[b];
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, L = lane & 31, H = lane >> 5;
+  const int tid = threadIdx.x, w = (tid >> 6) & 1, lane = tid & 63, L = lane & 31, H = lane >> 5;
   const int i = qtl * BM + 32 * w + L;  // this lane's query row
-  const bool row_ok = i < T;
+  const bool row_ok = i < T && head_ok;
   const int ic = min(i, T - 1);
   const size_t qoff = ((size_t)(cu + ic) * a.hq + h) * D;
   bf16x8 qf[D / 16], dof[D / 16];
@@ -120,7 +167,7 @@ __global__ void __launch_bounds__(128) k_bwd_dq(BwdArgs a) {
     if (flag == 0) continue;
     const int j0 = kt * BN;
     __syncthreads();
-    for (int c = tid; c < BN * (D / 8); c += 128) {
+    for (int c = tid; c < BN * (D / 8); c += NT) {
       const int r = c / (D / 8), ch = c % (D / 8);
       u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
       if (j0 + r < T) {
@@ -131,6 +178,7 @@ __global__ void __launch_bounds__(128) k_bwd_dq(BwdArgs a) {
       *(u32x4*)(sK + r * LD + ch * 8) = x;
       *(u32x4*)(sV + r * LD + ch * 8) = y;
     }
+    stage_image<D, NT>(sKT, a.kt_img + ((size_t)(a.ktile_start[b] + kt) * a.hkv + hk) * (size_t)(D * BN), tid);
     if (tid < BN) sNode[tid] = a.tok_node[cu + min(j0 + tid, T - 1)];
     __syncthreads();
     const bool need_mask = flag == 1;
@@ -156,8 +204,8 @@ __global__ void __launch_bounds__(128) k_bwd_dq(BwdArgs a) {
       const bf16x8 b0 = pack8(ds), b1 = pack8(ds + 8);
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {  // dQ^T += K^T dS^T
-        dQ[db] = mfma32(gather_col<LD>(sK, 32 * hh, 0, H, 32 * db + L), b0, dQ[db]);
-        dQ[db] = mfma32(gather_col<LD>(sK, 32 * hh, 1, H, 32 * db + L), b1, dQ[db]);
+        dQ[db] = mfma32(*(const bf16x8*)(sKT + (32 * db + L) * LT + 32 * hh + 8 * H), b0, dQ[db]);
+        dQ[db] = mfma32(*(const bf16x8*)(sKT + (32 * db + L) * LT + 32 * hh + 16 + 8 * H), b1, dQ[db]);
       }
     }
   }
@@ -176,31 +224,42 @@ __global__ void __launch_bounds__(128) k_bwd_dq(BwdArgs a) {
 
 template <int D>
 constexpr int dkv_smem_bytes() {
-  // Q and dO rows of one query tile for two query heads, their lse / delta, node ids and first
-  // visibility words of the rows; the area is reused for the final reduction over the two head sets
-  return 2 * 2 * BM * (D + 8) * 2 + 2 * 2 * BM * 4 + BM * 4 + BM * 8;
+  // Q and dO rows of one query tile for one query head and their transposed images, lse / delta of
+  // the rows, node ids and first visibility words of the rows
+  return 2 * BM * (D + 8) * 2 + 2 * D * LT * 2 + 2 * BM * 4 + BM * 4 + BM * 8;
 }
 
+// One workgroup per pair of key tiles (128 keys) and KV head: wave w owns keys 32 w .. 32 w + 31 of
+// the pair, with their K and V rows as B operands in registers and dK^T, dV^T accumulators for
+// them.  The workgroup walks over the query tiles that see either key tile and over the query
+// heads of the group, one (tile, head) at a time: its Q and dO rows and their transposed images go
+// through LDS for all four waves.  The next (tile, head) is fetched into registers while the
+// current one is computed.
 template <int D>
 __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   constexpr int LD = D + 8, DB = D / 32;
+  constexpr int NP = BM * (D / 8) / 256;  // 16-byte pieces per thread and staged tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* const sQ = (uint16_t*)smem;                  // [2][BM][LD]
-  uint16_t* const sdO = sQ + 2 * BM * LD;                // [2][BM][LD]
-  float* const sLse = (float*)(sdO + 2 * BM * LD);       // [2][BM]  (log2 units)
-  float* const sDl = sLse + 2 * BM;                      // [2][BM]
-  int* const sNodeR = (int*)(sDl + 2 * BM);              // [BM]
+  uint16_t* const sQ = (uint16_t*)smem;                  // [BM][LD]
+  uint16_t* const sdO = sQ + BM * LD;                    // [BM][LD]
+  uint16_t* const sQT = sdO + BM * LD;                   // [D][LT]
+  uint16_t* const sdOT = sQT + D * LT;                   // [D][LT]
+  float* const sLse = (float*)(sdOT + D * LT);           // [BM]  (log2 units)
+  float* const sDl = sLse + BM;                          // [BM]
+  int* const sNodeR = (int*)(sDl + BM);                  // [BM]
   uint64_t* const sVis0 = (uint64_t*)(sNodeR + BM);      // [BM]
   const int kt = blockIdx.x, hk = blockIdx.y;
   const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
-  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
   const int ktl = kt - a.ktile_start[b];
+  if (ktl & 1) return;  // the workgroup of the even tile takes the pair
+  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
   const int QT = (T + BM - 1) / BM, KT = (T + BN - 1) / BN;
   const uint8_t* bm = a.block_map + a.block_map_off[b];
   const int nbase = a.node_start[b];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, L = lane & 31, H = lane >> 5;
-  const int kh = w & 1, hs = w >> 1;  // key half of the tile, set of query heads (even / odd within the group)
-  const int j = ktl * BN + 32 * kh + L;  // this lane's key
+  const int my_kt = ktl + (w >> 1);          // this wave's key tile
+  const bool tile_ok = my_kt < KT;
+  const int j = ktl * BN + 32 * w + L;       // this lane's key
   const bool key_ok = j < T;
   const int jc = min(j, T - 1);
   const size_t koff = ((size_t)(cu + jc) * a.hkv + hk) * D;
@@ -217,118 +276,152 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) dK[db][e] = dV[db][e] = 0.f;
 
-  for (int qt = 0; qt < QT; ++qt) {
-    const int flag = bm[(int64_t)qt * KT + ktl];
-    if (flag == 0) continue;
+  // iteration space: (query tile that sees the pair, query head of the group)
+  auto pair_flag = [&](int qt) {
+    const int f0 = bm[(int64_t)qt * KT + ktl];
+    const int f1 = ktl + 1 < KT ? bm[(int64_t)qt * KT + ktl + 1] : 0;
+    return f0 | (f1 << 2);
+  };
+  auto next_tile = [&](int qt) {  // first query tile >= qt with a visible pair, QT if none
+    while (qt < QT && pair_flag(qt) == 0) ++qt;
+    return qt;
+  };
+  // register stage of one (tile, head)
+  u32x4 rq[NP], rdo[NP], rqt[NP], rdot[NP];
+  float r_lse = 0.f, r_dl = 0.f;
+  int r_node = 0;
+  uint64_t r_vis = 0;
+  auto fetch = [&](int qt, int g) {
     const int r0 = qt * BM;
-    const bool need_mask = flag == 1;
-    for (int gi = 0; 2 * gi < a.G; ++gi) {
-      __syncthreads();
-      for (int c = tid; c < 2 * BM * (D / 8); c += 256) {  // rows of the tile for heads 2 gi and 2 gi + 1 of the group
-        const int sub = c / (BM * (D / 8)), r = (c / (D / 8)) % BM, ch = c % (D / 8);
-        const int g = 2 * gi + sub;
-        u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
-        if (r0 + r < T && g < a.G) {
-          const size_t off = ((size_t)(cu + r0 + r) * a.hq + hk * a.G + g) * D + ch * 8;
-          x = *(const u32x4*)(a.q + off);
-          y = *(const u32x4*)(a.dout + off);
-        }
-        *(u32x4*)(sQ + (sub * BM + r) * LD + ch * 8) = x;
-        *(u32x4*)(sdO + (sub * BM + r) * LD + ch * 8) = y;
+    const int h = hk * a.G + g;
+#pragma unroll
+    for (int x = 0; x < NP; ++x) {
+      const int c = tid + 256 * x, r = c / (D / 8), ch = c % (D / 8);
+      rq[x] = rdo[x] = u32x4{0, 0, 0, 0};
+      if (r0 + r < T) {
+        const size_t off = ((size_t)(cu + r0 + r) * a.hq + h) * D + ch * 8;
+        rq[x] = *(const u32x4*)(a.q + off);
+        rdo[x] = *(const u32x4*)(a.dout + off);
       }
-      if (tid < 2 * BM) {
-        const int sub = tid / BM, r = tid % BM, g = 2 * gi + sub;
-        float l2 = 0.f, dl = 0.f;
-        if (r0 + r < T && g < a.G) {
-          const size_t row = (size_t)(cu + r0 + r) * a.hq + hk * a.G + g;
-          l2 = a.lse[row] * LOG2E;
-          dl = a.delta[row];
-        }
-        sLse[tid] = l2;
-        sDl[tid] = dl;
-      }
-      if (tid < BM) {
-        const int n = a.tok_node[cu + min(r0 + tid, T - 1)];
-        sNodeR[tid] = n;
-        sVis0[tid] = a.node_vis[(int64_t)(nbase + n) * a.W];
-      }
-      __syncthreads();
-      if (2 * gi + hs < a.G) {
-        const uint16_t* tQ = sQ + hs * BM * LD;
-        const uint16_t* tdO = sdO + hs * BM * LD;
+      const size_t t_off = ((size_t)(a.qtile_start[b] + qt) * a.hq + h) * (size_t)(D * BM) + (size_t)c * 8;
+      rqt[x] = *(const u32x4*)(a.qt_img + t_off);
+      rdot[x] = *(const u32x4*)(a.dot_img + t_off);
+    }
+    if (tid < BM) {
+      const bool in = r0 + tid < T;
+      const size_t row = (size_t)(cu + min(r0 + tid, T - 1)) * a.hq + h;
+      r_lse = in ? a.lse[row] * LOG2E : 0.f;
+      r_dl = in ? a.delta[row] : 0.f;
+      r_node = a.tok_node[cu + min(r0 + tid, T - 1)];
+      r_vis = a.node_vis[(int64_t)(nbase + r_node) * a.W];
+    }
+  };
+  auto commit = [&]() {
+#pragma unroll
+    for (int x = 0; x < NP; ++x) {
+      const int c = tid + 256 * x, r = c / (D / 8), ch = c % (D / 8);
+      *(u32x4*)(sQ + r * LD + ch * 8) = rq[x];
+      *(u32x4*)(sdO + r * LD + ch * 8) = rdo[x];
+      *(u32x4*)(sQT + (c >> 3) * LT + (c & 7) * 8) = rqt[x];
+      *(u32x4*)(sdOT + (c >> 3) * LT + (c & 7) * 8) = rdot[x];
+    }
+    if (tid < BM) {
+      sLse[tid] = r_lse;
+      sDl[tid] = r_dl;
+      sNodeR[tid] = r_node;
+      sVis0[tid] = r_vis;
+    }
+  };
+
+  int qt = next_tile(0), g = 0;
+  if (qt < QT) fetch(qt, g);
+  while (qt < QT) {
+    __syncthreads();  // everybody is done with the tile in LDS
+    commit();
+    __syncthreads();
+    const int cur_qt = qt;
+    if (++g == a.G) {
+      g = 0;
+      qt = next_tile(qt + 1);
+    }
+    if (qt < QT) fetch(qt, g);  // in flight during the products below
+    const int flag = tile_ok ? bm[(int64_t)cur_qt * KT + my_kt] : 0;
+    if (flag != 0) {
+      const int r0 = cur_qt * BM;
+      const bool need_mask = flag == 1;
 #pragma unroll 1
-        for (int rb = 0; rb < BM / 32; ++rb) {
-          f32x16 S, dP;
+      for (int rb = 0; rb < BM / 32; ++rb) {
+        f32x16 S, dP;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) S[e] = dP[e] = 0.f;
+        for (int e = 0; e < 16; ++e) S[e] = dP[e] = 0.f;
 #pragma unroll
-          for (int s = 0; s < D / 16; ++s) {  // S = Q K^T, dP = dO V^T: rows = query rows, column = this lane's key
-            S = mfma32(*(const bf16x8*)(tQ + (32 * rb + L) * LD + 16 * s + 8 * H), kf[s], S);
-            dP = mfma32(*(const bf16x8*)(tdO + (32 * rb + L) * LD + 16 * s + 8 * H), vf[s], dP);
-          }
-          float p[16], ds[16];
+        for (int s = 0; s < D / 16; ++s) {  // S = Q K^T, dP = dO V^T: rows = query rows, column = this lane's key
+          S = mfma32(*(const bf16x8*)(sQ + (32 * rb + L) * LD + 16 * s + 8 * H), kf[s], S);
+          dP = mfma32(*(const bf16x8*)(sdO + (32 * rb + L) * LD + 16 * s + 8 * H), vf[s], dP);
+        }
+        float p[16], ds[16];
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int r = 32 * rb + rho(e, H), i = r0 + r;
-            bool ok = key_ok && i < T;
-            if (need_mask && ok) ok = visible(a, nbase, sNodeR[r], i, nj, j, sVis0[r]);
-            p[e] = ok ? __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -sLse[hs * BM + r])) : 0.f;
-            ds[e] = p[e] * (dP[e] - sDl[hs * BM + r]);
-          }
-          const bf16x8 p0 = pack8(p), p1 = pack8(p + 8), s0 = pack8(ds), s1 = pack8(ds + 8);
+        for (int e = 0; e < 16; ++e) {
+          const int r = 32 * rb + rho(e, H), i = r0 + r;
+          bool ok = key_ok && i < T;
+          if (need_mask && ok) ok = visible(a, nbase, sNodeR[r], i, nj, j, sVis0[r]);
+          p[e] = ok ? __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -sLse[r])) : 0.f;
+          ds[e] = p[e] * (dP[e] - sDl[r]);
+        }
+        const bf16x8 p0 = pack8(p), p1 = pack8(p + 8), s0 = pack8(ds), s1 = pack8(ds + 8);
 #pragma unroll
-          for (int db = 0; db < DB; ++db) {  // dV^T += dO^T P, dK^T += Q^T dS
-            dV[db] = mfma32(gather_col<LD>(tdO, 32 * rb, 0, H, 32 * db + L), p0, dV[db]);
-            dV[db] = mfma32(gather_col<LD>(tdO, 32 * rb, 1, H, 32 * db + L), p1, dV[db]);
-            dK[db] = mfma32(gather_col<LD>(tQ, 32 * rb, 0, H, 32 * db + L), s0, dK[db]);
-            dK[db] = mfma32(gather_col<LD>(tQ, 32 * rb, 1, H, 32 * db + L), s1, dK[db]);
-          }
+        for (int db = 0; db < DB; ++db) {  // dV^T += dO^T P, dK^T += Q^T dS
+          dV[db] = mfma32(*(const bf16x8*)(sdOT + (32 * db + L) * LT + 32 * rb + 8 * H), p0, dV[db]);
+          dV[db] = mfma32(*(const bf16x8*)(sdOT + (32 * db + L) * LT + 32 * rb + 16 + 8 * H), p1, dV[db]);
+          dK[db] = mfma32(*(const bf16x8*)(sQT + (32 * db + L) * LT + 32 * rb + 8 * H), s0, dK[db]);
+          dK[db] = mfma32(*(const bf16x8*)(sQT + (32 * db + L) * LT + 32 * rb + 16 + 8 * H), s1, dK[db]);
         }
       }
     }
   }
-  // the two head sets of a key half add up through LDS, then the even set writes the rows out
-  __syncthreads();
-  float* const red = (float*)smem;  // [2 key halves][2 tensors][DB][16][64 lanes]
-  if (hs == 1) {
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        red[(((kh * 2 + 0) * DB + db) * 16 + e) * 64 + lane] = dK[db][e];
-        red[(((kh * 2 + 1) * DB + db) * 16 + e) * 64 + lane] = dV[db][e];
-      }
-  }
-  __syncthreads();
-  if (hs == 0 && key_ok) {
+  if (key_ok) {  // column = this lane's key, rows = d: every lane writes its key's row
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
-        float xk[4], xv[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int e = 4 * e4 + t;
-          xk[t] = (dK[db][e] + red[(((kh * 2 + 0) * DB + db) * 16 + e) * 64 + lane]) * a.scale;
-          xv[t] = dV[db][e] + red[(((kh * 2 + 1) * DB + db) * 16 + e) * 64 + lane];
-        }
         u32x2 ok2, ov2;
-        ok2[0] = dag_pack_bf2(xk[0], xk[1]); ok2[1] = dag_pack_bf2(xk[2], xk[3]);
-        ov2[0] = dag_pack_bf2(xv[0], xv[1]); ov2[1] = dag_pack_bf2(xv[2], xv[3]);
+        ok2[0] = dag_pack_bf2(dK[db][4 * e4] * a.scale, dK[db][4 * e4 + 1] * a.scale);
+        ok2[1] = dag_pack_bf2(dK[db][4 * e4 + 2] * a.scale, dK[db][4 * e4 + 3] * a.scale);
+        ov2[0] = dag_pack_bf2(dV[db][4 * e4], dV[db][4 * e4 + 1]);
+        ov2[1] = dag_pack_bf2(dV[db][4 * e4 + 2], dV[db][4 * e4 + 3]);
         *(u32x2*)(a.dk + koff + 32 * db + 8 * e4 + 4 * H) = ok2;
         *(u32x2*)(a.dv + koff + 32 * db + 8 * e4 + 4 * H) = ov2;
       }
   }
 }
 
+template <int D, int HG>
+int launch_dq(const BwdArgs& a, long total_qtiles, hipStream_t stream) {
+  constexpr int sm = 2 * BN * (D + 8) * 2 + D * LT * 2 + BN * 4;
+  if (hipFuncSetAttribute((const void*)k_bwd_dq<D, HG>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
+    return DAG_ERR_HIP;
+  hipLaunchKernelGGL((k_bwd_dq<D, HG>), dim3((unsigned)total_qtiles, (unsigned)a.hkv, (unsigned)((a.G + HG - 1) / HG)),
+                     dim3(128 * HG), sm, stream, a);
+  DAG_LAUNCH_CHECK();
+  return DAG_OK;
+}
+
 template <int D>
 int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream_t stream) {
-  hipLaunchKernelGGL((k_bwd_delta<D>), dim3((unsigned)a.total_rows), dim3(64), 0, stream, a);
+  hipLaunchKernelGGL((k_bwd_delta<D>), dim3((unsigned)((a.total_rows + 3) / 4)), dim3(256), 0, stream, a);
   DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL((k_bwd_dq<D>), dim3((unsigned)total_qtiles, (unsigned)a.hq), dim3(128), 0, stream, a);
+  // (query and key tiles are both 64 rows, so one tiling serves the three images)
+  hipLaunchKernelGGL((k_bwd_transpose<D>), dim3((unsigned)total_ktiles, (unsigned)a.hkv), dim3(256), 0, stream, a.k,
+                     a.kt_img, a.hkv, a);
+  hipLaunchKernelGGL((k_bwd_transpose<D>), dim3((unsigned)total_qtiles, (unsigned)a.hq), dim3(256), 0, stream, a.q,
+                     a.qt_img, a.hq, a);
+  hipLaunchKernelGGL((k_bwd_transpose<D>), dim3((unsigned)total_qtiles, (unsigned)a.hq), dim3(256), 0, stream, a.dout,
+                     a.dot_img, a.hq, a);
   DAG_LAUNCH_CHECK();
+  const int rc = a.G >= 3 ? launch_dq<D, 4>(a, total_qtiles, stream)
+                          : a.G == 2 ? launch_dq<D, 2>(a, total_qtiles, stream) : launch_dq<D, 1>(a, total_qtiles, stream);
+  if (rc != DAG_OK) return rc;
   constexpr int sm = dkv_smem_bytes<D>();
-  static_assert(sm >= 2 * 2 * (D / 32) * 16 * 64 * 4, "the staging area also holds the final reduction");
   if (hipFuncSetAttribute((const void*)k_bwd_dkv<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
     return DAG_ERR_HIP;
   hipLaunchKernelGGL((k_bwd_dkv<D>), dim3((unsigned)total_ktiles, (unsigned)a.hkv), dim3(256), sm, stream, a);
@@ -338,9 +431,14 @@ int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream
 
 }  // namespace
 
-extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t hq) {
-  if (!m || hq < 1 || m->sizes.total_tokens < 0) return 0;
-  return (size_t)m->sizes.total_tokens * hq * 4 + 256;
+extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t hq, int32_t hkv, int32_t head_dim) {
+  if (!m || hq < 1 || hkv < 1 || head_dim < 1 || m->sizes.total_tokens < 0 || m->sizes.total_qtiles < 0 ||
+      m->sizes.total_ktiles < 0)
+    return 0;
+  // delta [T][hq] fp32, then the transposed tile images of K, Q and dO (bf16)
+  const size_t tile = (size_t)head_dim * BM * 2;
+  return dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) + (size_t)m->sizes.total_ktiles * hkv * tile +
+         2 * (size_t)m->sizes.total_qtiles * hq * tile + 256;
 }
 
 extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const void* k, const void* v, const void* out,
@@ -361,7 +459,8 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
       !dag_aligned16(dq) || !dag_aligned16(dk) || !dag_aligned16(dv))
     return DAG_ERR_ALIGN;
   if (m->sizes.total_tokens * (int64_t)hq > INT32_MAX) return DAG_ERR_UNSUPPORTED;
-  const size_t need = dag_prefill_bwd_workspace_bytes(m, hq);
+  if (m->sizes.total_qtiles != m->sizes.total_ktiles) return DAG_ERR_BAD_LEN;  // (both tilings are 64 rows)
+  const size_t need = dag_prefill_bwd_workspace_bytes(m, hq, hkv, head_dim);
   if (!ws || ws_bytes < need) return DAG_ERR_WORKSPACE;
   BwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
@@ -369,6 +468,10 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   a.lse = lse;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
   a.delta = (float*)dag_align_up((size_t)(uintptr_t)ws, 256);
+  const size_t tile = (size_t)head_dim * BM;  // elements
+  a.kt_img = (uint16_t*)((char*)a.delta + dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256));
+  a.qt_img = a.kt_img + (size_t)m->sizes.total_ktiles * hkv * tile;
+  a.dot_img = a.qt_img + (size_t)m->sizes.total_qtiles * hq * tile;
   a.cu_seqlens = m->cu_seqlens; a.node_start = m->node_start; a.tok_node = m->tok_node;
   a.qtile_start = m->qtile_start; a.ktile_start = m->ktile_start;
   a.node_vis = m->node_vis; a.block_map_off = m->block_map_off; a.block_map = m->block_map;

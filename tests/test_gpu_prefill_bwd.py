@@ -93,3 +93,20 @@ def test_bwd_linear_chain_equals_library_autograd_of_causal_attention():
     (o * dout.float().permute(1, 0, 2)[None]).sum().backward()
     for name, g, r in (("dq", dq, tq.grad), ("dk", dk, tk.grad), ("dv", dv, tv.grad)):
         check_close(g, r[0].permute(1, 0, 2).double().numpy(), torch.bfloat16, name + " vs autograd")
+
+
+def test_bwd_config2_one_sequence_one_kv_group_every_row():
+    """Benchmark config 2's DAG (2048 -> 8 x 256 -> 512) at full head counts: the whole batch runs
+    on the GPU, one sequence's gradients of KV head 1 and its four query heads against the oracle."""
+    c = dags.config(1)
+    dag_list = dags.config_dags(c)
+    inputs, grads = _forward_backward(dag_list, c["hq"], c["hkv"], c["d"], c["seed"] + 5, theta=c["theta"])
+    qd, kd, v, dout = inputs
+    L, anc = dag_list[1]
+    Tb = int(np.sum(L))
+    sl = slice(Tb, 2 * Tb)
+    ref = orc.attn_prefill_bwd(dags.to_f64(qd[sl]), dags.to_f64(kd[sl]), dags.to_f64(v[sl]), dags.to_f64(dout[sl]),
+                               L, anc, kv_heads=[1])
+    check_close(grads[0][sl][:, 4:8], ref[0][:, 4:8], torch.bfloat16, "config 2 dq")
+    check_close(grads[1][sl][:, 1], ref[1][:, 1], torch.bfloat16, "config 2 dk")
+    check_close(grads[2][sl][:, 1], ref[2][:, 1], torch.bfloat16, "config 2 dv")
