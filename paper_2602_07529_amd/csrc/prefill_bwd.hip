@@ -61,6 +61,7 @@ __device__ __forceinline__ bool visible(const BwdArgs& a, int nbase, int ni, int
 }
 
 constexpr int LT = BN + 8;  // padded row of a transposed tile in LDS (elements)
+constexpr int MAX_QT_LDS = 4096;  // query tiles of a sequence whose block-map column is kept in LDS (262,144 tokens)
 
 // Column order of a transposed tile: column c = 32 hh + 16 ks + 8 H + e holds row
 // 32 hh + rho_H(8 ks + e) of the tile, so the 8 elements lane (., H) needs for contraction step ks
@@ -131,6 +132,7 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
   uint16_t* const sV = sK + BN * LD;      // [BN][LD]
   uint16_t* const sKT = sV + BN * LD;     // [D][LT]
   int* const sNode = (int*)(sKT + D * LT);
+  __shared__ uint8_t sFlag[MAX_QT_LDS];  // the tile's row of the block map
   const int qt = blockIdx.x, hk = blockIdx.y;
   const int g = blockIdx.z * HG + (threadIdx.x >> 7);  // two waves per query head
   const bool head_ok = g < a.G;
@@ -162,8 +164,13 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) dQ[db][e] = 0.f;
 
+  const bool flags_in_lds = KT <= MAX_QT_LDS;
+  if (flags_in_lds) {
+    for (int x = tid; x < KT; x += NT) sFlag[x] = bm[x];
+    __syncthreads();
+  }
   for (int kt = 0; kt < KT; ++kt) {
-    const int flag = bm[kt];
+    const int flag = flags_in_lds ? (int)sFlag[kt] : (int)bm[kt];
     if (flag == 0) continue;
     const int j0 = kt * BN;
     __syncthreads();
@@ -193,13 +200,18 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
         dP = mfma32(*(const bf16x8*)(sV + (32 * hh + L) * LD + 16 * s + 8 * H), dof[s], dP);
       }
       float ds[16];
+      if (!need_mask && j0 + BN <= T) {  // every in-range row sees every key of the tile: no tests
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int kk = 32 * hh + rho(e, H), j = j0 + kk;
-        bool ok = row_ok && j < T;
-        if (need_mask && ok) ok = visible(a, nbase, ni, i, sNode[kk], j, vis0);
-        const float p = ok ? __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -lse2)) : 0.f;
-        ds[e] = p * (dP[e] - dl);
+        for (int e = 0; e < 16; ++e) ds[e] = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -lse2)) * (dP[e] - dl);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int kk = 32 * hh + rho(e, H), j = j0 + kk;
+          bool ok = row_ok && j < T;
+          if (need_mask && ok) ok = visible(a, nbase, ni, i, sNode[kk], j, vis0);
+          const float p = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -lse2));
+          ds[e] = ok ? p * (dP[e] - dl) : 0.f;
+        }
       }
       const bf16x8 b0 = pack8(ds), b1 = pack8(ds + 8);
 #pragma unroll
@@ -248,7 +260,11 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   float* const sDl = sLse + BM;                          // [BM]
   int* const sNodeR = (int*)(sDl + BM);                  // [BM]
   uint64_t* const sVis0 = (uint64_t*)(sNodeR + BM);      // [BM]
-  const int kt = blockIdx.x, hk = blockIdx.y;
+  __shared__ uint8_t sFlag[MAX_QT_LDS];                  // block-map column of the pair: flag of tile 0 | flag of tile 1 << 2
+  // (the KV head is the fast index of the launch: workgroups go to the XCDs round robin, so with 8
+  // KV heads every XCD's L2 holds the Q / dO tiles of one head group only, and the workgroups of a
+  // group walk over the query tiles from the last one down, i.e. side by side)
+  const int hk = blockIdx.x % a.hkv, kt = blockIdx.x / a.hkv;
   const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
   const int ktl = kt - a.ktile_start[b];
   if (ktl & 1) return;  // the workgroup of the even tile takes the pair
@@ -277,13 +293,25 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
     for (int e = 0; e < 16; ++e) dK[db][e] = dV[db][e] = 0.f;
 
   // iteration space: (query tile that sees the pair, query head of the group)
+  // (read once: a load of the map inside the loop would sit, with its full latency, in front of
+  // every tile; sequences with more query tiles than the array holds read the map directly)
+  const bool flags_in_lds = QT <= MAX_QT_LDS;
+  if (flags_in_lds) {
+    for (int x = tid; x < QT; x += 256) {
+      const int f0 = bm[(int64_t)x * KT + ktl];
+      const int f1 = ktl + 1 < KT ? bm[(int64_t)x * KT + ktl + 1] : 0;
+      sFlag[x] = (uint8_t)(f0 | (f1 << 2));
+    }
+    __syncthreads();
+  }
   auto pair_flag = [&](int qt) {
+    if (flags_in_lds) return (int)sFlag[qt];
     const int f0 = bm[(int64_t)qt * KT + ktl];
     const int f1 = ktl + 1 < KT ? bm[(int64_t)qt * KT + ktl + 1] : 0;
     return f0 | (f1 << 2);
   };
-  auto next_tile = [&](int qt) {  // first query tile >= qt with a visible pair, QT if none
-    while (qt < QT && pair_flag(qt) == 0) ++qt;
+  auto next_tile = [&](int qt) {  // last query tile <= qt with a visible pair, -1 if none
+    while (qt >= 0 && pair_flag(qt) == 0) --qt;
     return qt;
   };
   // register stage of one (tile, head)
@@ -333,19 +361,21 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
     }
   };
 
-  int qt = next_tile(0), g = 0;
-  if (qt < QT) fetch(qt, g);
-  while (qt < QT) {
+  int qt = next_tile(QT - 1), g = 0;
+  if (qt >= 0) fetch(qt, g);
+  while (qt >= 0) {
     __syncthreads();  // everybody is done with the tile in LDS
     commit();
     __syncthreads();
     const int cur_qt = qt;
+    // (every global load the products depend on comes before the fetch: a wait for a later load
+    // would also wait for the fetch, the counter being in order)
+    const int flag = __builtin_amdgcn_readfirstlane((pair_flag(cur_qt) >> (2 * (w >> 1))) & 3);
     if (++g == a.G) {
       g = 0;
-      qt = next_tile(qt + 1);
+      qt = next_tile(qt - 1);
     }
-    if (qt < QT) fetch(qt, g);  // in flight during the products below
-    const int flag = tile_ok ? bm[(int64_t)cur_qt * KT + my_kt] : 0;
+    if (qt >= 0) fetch(qt, g);  // in flight during the products below
     if (flag != 0) {
       const int r0 = cur_qt * BM;
       const bool need_mask = flag == 1;
@@ -360,13 +390,29 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
           dP = mfma32(*(const bf16x8*)(sdO + (32 * rb + L) * LD + 16 * s + 8 * H), vf[s], dP);
         }
         float p[16], ds[16];
+        // lse and delta of the 16 rows of this lane: four groups of four consecutive rows
+        f32x4 l4[4], d4[4];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int r = 32 * rb + rho(e, H), i = r0 + r;
-          bool ok = key_ok && i < T;
-          if (need_mask && ok) ok = visible(a, nbase, sNodeR[r], i, nj, j, sVis0[r]);
-          p[e] = ok ? __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -sLse[r])) : 0.f;
-          ds[e] = p[e] * (dP[e] - sDl[r]);
+        for (int e4 = 0; e4 < 4; ++e4) {
+          l4[e4] = *(const f32x4*)(sLse + 32 * rb + 8 * e4 + 4 * H);
+          d4[e4] = *(const f32x4*)(sDl + 32 * rb + 8 * e4 + 4 * H);
+        }
+        if (!need_mask && r0 + BM <= T && (my_kt + 1) * BN <= T) {  // every pair of the tile is visible: no tests
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -l4[e >> 2][e & 3]));
+            ds[e] = p[e] * (dP[e] - d4[e >> 2][e & 3]);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int r = 32 * rb + rho(e, H), i = r0 + r;
+            bool ok = key_ok && i < T;
+            if (need_mask && ok) ok = visible(a, nbase, sNodeR[r], i, nj, j, sVis0[r]);
+            const float pe = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -l4[e >> 2][e & 3]));
+            p[e] = ok ? pe : 0.f;
+            ds[e] = p[e] * (dP[e] - d4[e >> 2][e & 3]);
+          }
         }
         const bf16x8 p0 = pack8(p), p1 = pack8(p + 8), s0 = pack8(ds), s1 = pack8(ds + 8);
 #pragma unroll
@@ -424,7 +470,7 @@ int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream
   constexpr int sm = dkv_smem_bytes<D>();
   if (hipFuncSetAttribute((const void*)k_bwd_dkv<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
     return DAG_ERR_HIP;
-  hipLaunchKernelGGL((k_bwd_dkv<D>), dim3((unsigned)total_ktiles, (unsigned)a.hkv), dim3(256), sm, stream, a);
+  hipLaunchKernelGGL((k_bwd_dkv<D>), dim3((unsigned)(total_ktiles * a.hkv)), dim3(256), sm, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
