@@ -259,7 +259,6 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   float* const sLse = (float*)(sdOT + D * LT);           // [BM]  (log2 units)
   float* const sDl = sLse + BM;                          // [BM]
   int* const sNodeR = (int*)(sDl + BM);                  // [BM]
-  uint64_t* const sVis0 = (uint64_t*)(sNodeR + BM);      // [BM]
   __shared__ uint8_t sFlag[MAX_QT_LDS];                  // block-map column of the pair: flag of tile 0 | flag of tile 1 << 2
   // (the KV head is the fast index of the launch: workgroups go to the XCDs round robin, so with 8
   // KV heads every XCD's L2 holds the Q / dO tiles of one head group only, and the workgroups of a
@@ -315,58 +314,84 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
     return qt;
   };
   // register stage of one (tile, head)
+  // (addresses: a wave-uniform 64-bit base per tile and head plus 32-bit per-thread offsets that
+  // never change; rows past the end of the sequence re-read its last row and are zeroed afterwards,
+  // so no load sits under a branch; no load depends on another one: a wait for the first would
+  // also wait for everything issued before it)
   u32x4 rq[NP], rdo[NP], rqt[NP], rdot[NP];
   float r_lse = 0.f, r_dl = 0.f;
   int r_node = 0;
-  uint64_t r_vis = 0;
+  uint32_t row_off[NP];  // element offset of this thread's piece x inside a 64-row slab of q / dout
+#pragma unroll
+  for (int x = 0; x < NP; ++x) {
+    const int c = tid + 256 * x;
+    row_off[x] = (uint32_t)(c / (D / 8)) * (uint32_t)(a.hq * D) + (uint32_t)(c % (D / 8)) * 8;
+  }
+  const uint32_t last_off = (uint32_t)(a.hq * D);  // one row
   auto fetch = [&](int qt, int g) {
     const int r0 = qt * BM;
     const int h = hk * a.G + g;
+    const size_t slab = ((size_t)(cu + r0) * a.hq + h) * D;
+    const uint16_t* pq = a.q + slab;
+    const uint16_t* pdo = a.dout + slab;
+    const size_t t_off = ((size_t)(a.qtile_start[b] + qt) * a.hq + h) * (size_t)(D * BM);
+    const uint16_t* pqt = a.qt_img + t_off;
+    const uint16_t* pdot = a.dot_img + t_off;
+    const int n_in = min(BM, T - r0);  // rows of the tile inside the sequence (>= 1)
 #pragma unroll
     for (int x = 0; x < NP; ++x) {
-      const int c = tid + 256 * x, r = c / (D / 8), ch = c % (D / 8);
-      rq[x] = rdo[x] = u32x4{0, 0, 0, 0};
-      if (r0 + r < T) {
-        const size_t off = ((size_t)(cu + r0 + r) * a.hq + h) * D + ch * 8;
-        rq[x] = *(const u32x4*)(a.q + off);
-        rdo[x] = *(const u32x4*)(a.dout + off);
-      }
-      const size_t t_off = ((size_t)(a.qtile_start[b] + qt) * a.hq + h) * (size_t)(D * BM) + (size_t)c * 8;
-      rqt[x] = *(const u32x4*)(a.qt_img + t_off);
-      rdot[x] = *(const u32x4*)(a.dot_img + t_off);
+      const int c = tid + 256 * x, r = c / (D / 8);
+      const uint32_t off = r < n_in ? row_off[x] : row_off[x] - (uint32_t)(r - (n_in - 1)) * last_off;
+      rq[x] = *(const u32x4*)(pq + off);
+      rdo[x] = *(const u32x4*)(pdo + off);
+      rqt[x] = *(const u32x4*)(pqt + (uint32_t)c * 8);
+      rdot[x] = *(const u32x4*)(pdot + (uint32_t)c * 8);
     }
     if (tid < BM) {
-      const bool in = r0 + tid < T;
-      const size_t row = (size_t)(cu + min(r0 + tid, T - 1)) * a.hq + h;
-      r_lse = in ? a.lse[row] * LOG2E : 0.f;
-      r_dl = in ? a.delta[row] : 0.f;
-      r_node = a.tok_node[cu + min(r0 + tid, T - 1)];
-      r_vis = a.node_vis[(int64_t)(nbase + r_node) * a.W];
+      const int rr = min(tid, n_in - 1);
+      const size_t row = (size_t)(cu + r0 + rr) * a.hq + h;
+      r_lse = a.lse[row];
+      r_dl = a.delta[row];
+      r_node = a.tok_node[cu + r0 + rr];
     }
   };
-  auto commit = [&]() {
+  auto commit = [&](int qt_of_regs) {
+    const int n_in = min(BM, T - qt_of_regs * BM);
 #pragma unroll
     for (int x = 0; x < NP; ++x) {
       const int c = tid + 256 * x, r = c / (D / 8), ch = c % (D / 8);
+      if (r >= n_in) rq[x] = rdo[x] = u32x4{0, 0, 0, 0};
       *(u32x4*)(sQ + r * LD + ch * 8) = rq[x];
       *(u32x4*)(sdO + r * LD + ch * 8) = rdo[x];
       *(u32x4*)(sQT + (c >> 3) * LT + (c & 7) * 8) = rqt[x];
       *(u32x4*)(sdOT + (c >> 3) * LT + (c & 7) * 8) = rdot[x];
     }
     if (tid < BM) {
-      sLse[tid] = r_lse;
-      sDl[tid] = r_dl;
+      sLse[tid] = tid < n_in ? r_lse * LOG2E : 0.f;
+      sDl[tid] = tid < n_in ? r_dl : 0.f;
       sNodeR[tid] = r_node;
-      sVis0[tid] = r_vis;
     }
   };
 
   int qt = next_tile(QT - 1), g = 0;
   if (qt >= 0) fetch(qt, g);
+#ifdef BWD_TIMING
+  long long tacc[6] = {0, 0, 0, 0, 0, 0}, t0, t1;
+  long long t_begin = clock64();
+#define TT(k) t1 = clock64(); tacc[k] += t1 - t0; t0 = t1;
+#else
+#define TT(k)
+#endif
   while (qt >= 0) {
+#ifdef BWD_TIMING
+    t0 = clock64();
+#endif
     __syncthreads();  // everybody is done with the tile in LDS
-    commit();
+    TT(0)
+    commit(qt);
+    TT(1)
     __syncthreads();
+    TT(2)
     const int cur_qt = qt;
     // (every global load the products depend on comes before the fetch: a wait for a later load
     // would also wait for the fetch, the counter being in order)
@@ -376,6 +401,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
       qt = next_tile(qt - 1);
     }
     if (qt >= 0) fetch(qt, g);  // in flight during the products below
+    TT(3)
     if (flag != 0) {
       const int r0 = cur_qt * BM;
       const bool need_mask = flag == 1;
@@ -408,7 +434,10 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
           for (int e = 0; e < 16; ++e) {
             const int r = 32 * rb + rho(e, H), i = r0 + r;
             bool ok = key_ok && i < T;
-            if (need_mask && ok) ok = visible(a, nbase, sNodeR[r], i, nj, j, sVis0[r]);
+            if (need_mask && ok) {
+              const int ni = sNodeR[r];
+              ok = visible(a, nbase, ni, i, nj, j, a.node_vis[(int64_t)(nbase + ni) * a.W]);
+            }
             const float pe = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -l4[e >> 2][e & 3]));
             p[e] = ok ? pe : 0.f;
             ds[e] = p[e] * (dP[e] - d4[e >> 2][e & 3]);
@@ -424,7 +453,16 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
         }
       }
     }
+    TT(4)
+#ifdef BWD_TIMING
+    tacc[5]++;
+#endif
   }
+#ifdef BWD_TIMING
+  if ((blockIdx.x == 0 || blockIdx.x == 8 * 40) && lane == 0)
+    printf("block %d wave %d: total %lld | sync1 %lld commit %lld sync2 %lld fetch-issue %lld compute %lld | iterations %lld\n",
+           (int)blockIdx.x, w, clock64() - t_begin, tacc[0], tacc[1], tacc[2], tacc[3], tacc[4], tacc[5]);
+#endif
   if (key_ok) {  // column = this lane's key, rows = d: every lane writes its key's row
 #pragma unroll
     for (int db = 0; db < DB; ++db)
