@@ -321,3 +321,40 @@ def test_scheduler_argument_errors_and_page_exhaustion():
     assert rcs[:20] == [0] * 20 and rcs[20] == -6 and rcs[25] == -6      # node 1 never gets its page
     L.dag_sched_destroy(h)
     L.dag_sched_destroy(None)
+
+
+def test_backward_argument_errors():
+    L = B.lib()
+    d = _desc([dags.linear_chain([10, 10])])
+    m = B.dag_meta_t()
+    m.n_seqs, m.words_per_node, m.tile_m, m.tile_n = 1, 1, 64, 64
+    m.sizes = B.dag_meta_sizes(d)
+    for name, _ in B._META_ARRAYS:
+        setattr(m, name, FAKE)
+    p = C.c_void_p(FAKE)
+    need = L.dag_prefill_bwd_workspace_bytes(C.byref(m), 32, 8, 128)
+    # delta [20][32] fp32 (rounded up to 256 bytes), one K^T image per KV head, Q^T and dO^T images per query head
+    assert need == 2560 + 8 * 128 * 64 * 2 + 2 * 32 * 128 * 64 * 2 + 256
+    args = (32, 8, 128, 0.1, B.DAG_BF16)
+    call = lambda *ptrs, a=args, ws=p, nb=need, meta=m: L.dag_attn_prefill_bwd(
+        C.byref(meta) if meta is not None else None, *ptrs, *a, ws, nb, None)
+    nine = [p] * 9
+    assert call(*nine, nb=need - 1) == -6
+    assert call(*nine, ws=None) == -6
+    assert call(*nine, a=(32, 8, 128, 0.1, B.DAG_F32)) == -7
+    assert call(*nine, a=(32, 8, 96, 0.1, B.DAG_BF16)) == -7
+    assert call(*nine, a=(30, 8, 128, 0.1, B.DAG_BF16)) == -7
+    for missing in range(9):
+        ptrs = list(nine)
+        ptrs[missing] = None
+        assert call(*ptrs) == -1
+    ptrs = list(nine)
+    ptrs[7] = C.c_void_p(FAKE + 2)
+    assert call(*ptrs) == -8
+    assert call(*nine, meta=None) == -1
+    m.tile_m = 32
+    assert call(*nine) == -7
+    m.tile_m = 64
+    empty = B.dag_meta_t()
+    empty.tile_m, empty.tile_n, empty.words_per_node = 64, 64, 1
+    assert call(*nine, ws=None, nb=0, meta=empty) == 0
