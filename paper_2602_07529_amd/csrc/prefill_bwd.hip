@@ -33,7 +33,10 @@ struct BwdArgs {
   uint16_t *dq, *dk, *dv;
   float* delta;  // [T][hq]
   uint16_t *kt_img, *qt_img, *dot_img;  // transposed tile images [tile][head][D][64]
+  int32_t *kt_weight, *kt_order;        // [total key tiles] launch order of the dK/dV workgroups
+  int total_ktiles;
   const int32_t *cu_seqlens, *node_start, *tok_node, *qtile_start, *ktile_start;
+  const int32_t* qtile_order;  // the forward's launch order: query tiles by descending number of visible key tiles
   const uint64_t* node_vis;
   const int64_t* block_map_off;
   const uint8_t* block_map;
@@ -133,7 +136,7 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
   uint16_t* const sKT = sV + BN * LD;     // [D][LT]
   int* const sNode = (int*)(sKT + D * LT);
   __shared__ uint8_t sFlag[MAX_QT_LDS];  // the tile's row of the block map
-  const int qt = blockIdx.x, hk = blockIdx.y;
+  const int qt = a.qtile_order[blockIdx.x], hk = blockIdx.y;  // heaviest tiles first
   const int g = blockIdx.z * HG + (threadIdx.x >> 7);  // two waves per query head
   const bool head_ok = g < a.G;
   const int h = hk * a.G + min(g, a.G - 1);
@@ -234,6 +237,39 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
   }
 }
 
+// Launch order of the dK/dV workgroups: heaviest first.  A workgroup takes a pair of key tiles
+// (the even tile of a sequence and its successor); its weight is the number of query tiles that
+// see the pair (the prefix keys of a plan are seen by every later tile, the keys of a branch by a
+// few), odd tiles get -1 and sort last.  One wave per key tile, twice: weights, then ranks by
+// counting (ties by index), which is fine for the few thousand tiles of a batch.
+__global__ void __launch_bounds__(64) k_bwd_weights(BwdArgs a) {
+  const int kt = blockIdx.x, lane = threadIdx.x;
+  const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
+  const int ktl = kt - a.ktile_start[b];
+  const int T = a.cu_seqlens[b + 1] - a.cu_seqlens[b];
+  const int QT = (T + BM - 1) / BM, KT = (T + BN - 1) / BN;
+  const uint8_t* bm = a.block_map + a.block_map_off[b];
+  int n = 0;
+  if (!(ktl & 1))
+    for (int qt = lane; qt < QT; qt += 64)
+      n += (bm[(int64_t)qt * KT + ktl] | (ktl + 1 < KT ? bm[(int64_t)qt * KT + ktl + 1] : 0)) != 0;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) n += __shfl_xor(n, o);
+  if (lane == 0) a.kt_weight[kt] = (ktl & 1) ? -1 : n;
+}
+__global__ void __launch_bounds__(64) k_bwd_order(BwdArgs a) {
+  const int kt = blockIdx.x, lane = threadIdx.x;
+  const int mine = a.kt_weight[kt];
+  int rank = 0;
+  for (int x = lane; x < a.total_ktiles; x += 64) {
+    const int w = a.kt_weight[x];
+    rank += w > mine || (w == mine && x < kt);
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) rank += __shfl_xor(rank, o);
+  if (lane == 0) a.kt_order[rank] = kt;
+}
+
 template <int D>
 constexpr int dkv_smem_bytes() {
   // Q and dO rows of one query tile for one query head and their transposed images, lse / delta of
@@ -263,10 +299,10 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   // (the KV head is the fast index of the launch: workgroups go to the XCDs round robin, so with 8
   // KV heads every XCD's L2 holds the Q / dO tiles of one head group only, and the workgroups of a
   // group walk over the query tiles from the last one down, i.e. side by side)
-  const int hk = blockIdx.x % a.hkv, kt = blockIdx.x / a.hkv;
+  const int hk = blockIdx.x % a.hkv, kt = a.kt_order[blockIdx.x / a.hkv];  // heaviest pairs first
   const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
   const int ktl = kt - a.ktile_start[b];
-  if (ktl & 1) return;  // the workgroup of the even tile takes the pair
+  if (ktl & 1) return;  // the workgroup of the even tile takes the pair (odd tiles come last in the order)
   const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
   const int QT = (T + BM - 1) / BM, KT = (T + BN - 1) / BN;
   const uint8_t* bm = a.block_map + a.block_map_off[b];
@@ -508,6 +544,9 @@ int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream
   constexpr int sm = dkv_smem_bytes<D>();
   if (hipFuncSetAttribute((const void*)k_bwd_dkv<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
     return DAG_ERR_HIP;
+  hipLaunchKernelGGL(k_bwd_weights, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
+  hipLaunchKernelGGL(k_bwd_order, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
+  DAG_LAUNCH_CHECK();
   hipLaunchKernelGGL((k_bwd_dkv<D>), dim3((unsigned)(total_ktiles * a.hkv)), dim3(256), sm, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
@@ -519,10 +558,10 @@ extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t h
   if (!m || hq < 1 || hkv < 1 || head_dim < 1 || m->sizes.total_tokens < 0 || m->sizes.total_qtiles < 0 ||
       m->sizes.total_ktiles < 0)
     return 0;
-  // delta [T][hq] fp32, then the transposed tile images of K, Q and dO (bf16)
+  // delta [T][hq] fp32, the transposed tile images of K, Q and dO (bf16), weight and launch order of the key tiles
   const size_t tile = (size_t)head_dim * BM * 2;
   return dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) + (size_t)m->sizes.total_ktiles * hkv * tile +
-         2 * (size_t)m->sizes.total_qtiles * hq * tile + 256;
+         2 * (size_t)m->sizes.total_qtiles * hq * tile + 2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) + 256;
 }
 
 extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const void* k, const void* v, const void* out,
@@ -537,7 +576,7 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   if (m->n_seqs == 0 || m->sizes.total_tokens == 0) return DAG_OK;
   if (!q || !k || !v || !out || !dout || !lse || !dq || !dk || !dv) return DAG_ERR_NULL;
   if (!m->cu_seqlens || !m->node_start || !m->tok_node || !m->node_vis || !m->qtile_start || !m->ktile_start ||
-      !m->block_map_off || !m->block_map)
+      !m->block_map_off || !m->block_map || !m->qtile_order)
     return DAG_ERR_NULL;
   if (!dag_aligned16(q) || !dag_aligned16(k) || !dag_aligned16(v) || !dag_aligned16(out) || !dag_aligned16(dout) ||
       !dag_aligned16(dq) || !dag_aligned16(dk) || !dag_aligned16(dv))
@@ -556,8 +595,12 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   a.kt_img = (uint16_t*)((char*)a.delta + dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256));
   a.qt_img = a.kt_img + (size_t)m->sizes.total_ktiles * hkv * tile;
   a.dot_img = a.qt_img + (size_t)m->sizes.total_qtiles * hq * tile;
+  a.kt_weight = (int32_t*)(a.dot_img + (size_t)m->sizes.total_qtiles * hq * tile);
+  a.kt_order = a.kt_weight + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4;
+  a.total_ktiles = (int)m->sizes.total_ktiles;
   a.cu_seqlens = m->cu_seqlens; a.node_start = m->node_start; a.tok_node = m->tok_node;
   a.qtile_start = m->qtile_start; a.ktile_start = m->ktile_start;
+  a.qtile_order = m->qtile_order;
   a.node_vis = m->node_vis; a.block_map_off = m->block_map_off; a.block_map = m->block_map;
   a.n_seqs = m->n_seqs; a.W = m->words_per_node; a.hq = hq; a.hkv = hkv; a.G = hq / hkv;
   a.total_rows = (long)m->sizes.total_tokens * hq;
