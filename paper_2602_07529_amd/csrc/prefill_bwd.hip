@@ -172,25 +172,65 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
     for (int x = tid; x < KT; x += NT) sFlag[x] = bm[x];
     __syncthreads();
   }
-  for (int kt = 0; kt < KT; ++kt) {
-    const int flag = flags_in_lds ? (int)sFlag[kt] : (int)bm[kt];
-    if (flag == 0) continue;
-    const int j0 = kt * BN;
-    __syncthreads();
-    for (int c = tid; c < BN * (D / 8); c += NT) {
-      const int r = c / (D / 8), ch = c % (D / 8);
-      u32x4 x = {0, 0, 0, 0}, y = {0, 0, 0, 0};
-      if (j0 + r < T) {
-        const size_t off = ((size_t)(cu + j0 + r) * a.hkv + hk) * D + ch * 8;
-        x = *(const u32x4*)(a.k + off);
-        y = *(const u32x4*)(a.v + off);
-      }
-      *(u32x4*)(sK + r * LD + ch * 8) = x;
-      *(u32x4*)(sV + r * LD + ch * 8) = y;
+  // The key tiles go through a register stage: the next visible tile is fetched while the current
+  // one is multiplied (constant per-thread offsets, rows past the end re-read the last row and are
+  // zeroed on the way to LDS, no load depends on another).
+  constexpr int NPQ = (BN * (D / 8) + NT - 1) / NT;  // 16-byte pieces per thread and staged tile
+  u32x4 rk[NPQ], rv[NPQ], rkt[NPQ];
+  int r_node = 0;
+  uint32_t row_off[NPQ];
+#pragma unroll
+  for (int x = 0; x < NPQ; ++x) {
+    const int c = min(tid + NT * x, BN * (D / 8) - 1);
+    row_off[x] = (uint32_t)(c / (D / 8)) * (uint32_t)(a.hkv * D) + (uint32_t)(c % (D / 8)) * 8;
+  }
+  const uint32_t one_row = (uint32_t)(a.hkv * D);
+  auto tile_flag = [&](int kt) { return flags_in_lds ? (int)sFlag[kt] : (int)bm[kt]; };
+  auto next_tile = [&](int kt) {
+    while (kt < KT && tile_flag(kt) == 0) ++kt;
+    return kt;
+  };
+  auto fetch = [&](int kt) {
+    const int j0 = kt * BN, n_in = min(BN, T - j0);
+    const size_t slab = ((size_t)(cu + j0) * a.hkv + hk) * D;
+    const uint16_t* pk = a.k + slab;
+    const uint16_t* pv = a.v + slab;
+    const uint16_t* pt = a.kt_img + ((size_t)(a.ktile_start[b] + kt) * a.hkv + hk) * (size_t)(D * BN);
+#pragma unroll
+    for (int x = 0; x < NPQ; ++x) {
+      const int c = min(tid + NT * x, BN * (D / 8) - 1), r = c / (D / 8);
+      const uint32_t off = r < n_in ? row_off[x] : row_off[x] - (uint32_t)(r - (n_in - 1)) * one_row;
+      rk[x] = *(const u32x4*)(pk + off);
+      rv[x] = *(const u32x4*)(pv + off);
+      rkt[x] = *(const u32x4*)(pt + (uint32_t)c * 8);
     }
-    stage_image<D, NT>(sKT, a.kt_img + ((size_t)(a.ktile_start[b] + kt) * a.hkv + hk) * (size_t)(D * BN), tid);
-    if (tid < BN) sNode[tid] = a.tok_node[cu + min(j0 + tid, T - 1)];
+    if (tid < BN) r_node = a.tok_node[cu + j0 + min(tid, n_in - 1)];
+  };
+  auto commit = [&](int kt) {
+    const int n_in = min(BN, T - kt * BN);
+#pragma unroll
+    for (int x = 0; x < NPQ; ++x) {
+      const int c = tid + NT * x, r = c / (D / 8), ch = c % (D / 8);
+      if (c < BN * (D / 8)) {
+        if (r >= n_in) rk[x] = rv[x] = u32x4{0, 0, 0, 0};
+        *(u32x4*)(sK + r * LD + ch * 8) = rk[x];
+        *(u32x4*)(sV + r * LD + ch * 8) = rv[x];
+        *(u32x4*)(sKT + (c >> 3) * LT + (c & 7) * 8) = rkt[x];
+      }
+    }
+    if (tid < BN) sNode[tid] = r_node;
+  };
+  int kt_next = next_tile(0);
+  if (kt_next < KT) fetch(kt_next);
+  while (kt_next < KT) {
+    const int kt = kt_next;
+    const int flag = tile_flag(kt);
+    const int j0 = kt * BN;
+    __syncthreads();  // everybody is done with the tile in LDS
+    commit(kt);
     __syncthreads();
+    kt_next = next_tile(kt + 1);
+    if (kt_next < KT) fetch(kt_next);  // in flight during the products below
     const bool need_mask = flag == 1;
 #pragma unroll 1
     for (int hh = 0; hh < 2; ++hh) {
