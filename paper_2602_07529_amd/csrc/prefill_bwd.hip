@@ -34,6 +34,7 @@ struct BwdArgs {
   float* delta;  // [T][hq]
   uint16_t *kt_img, *qt_img, *dot_img;  // transposed tile images [tile][head][D][64]
   int32_t *kt_weight, *kt_order;        // [total key tiles] launch order of the dK/dV workgroups
+  uint64_t* tok_vis0;                   // [T] first visibility word of every token's node
   int total_ktiles;
   const int32_t *cu_seqlens, *node_start, *tok_node, *qtile_start, *ktile_start;
   const int32_t* qtile_order;  // the forward's launch order: query tiles by descending number of visible key tiles
@@ -56,8 +57,13 @@ __device__ __forceinline__ bf16x8 pack8(const float* x) {
   return __builtin_convertvector(f, bf16x8);
 }
 
-// Eq. 3 for a (query token i of node ni, key token j of node nj) pair of one sequence
+// Eq. 3 for a (query token i of node ni, key token j of node nj) pair of one sequence.  With at
+// most 64 nodes per sequence (one visibility word) the test is a few selects, no branch and no load.
 __device__ __forceinline__ bool visible(const BwdArgs& a, int nbase, int ni, int i, int nj, int j, uint64_t vis0) {
+  if (a.W == 1) {
+    const bool anc = (vis0 >> (nj & 63)) & 1u;
+    return nj == ni ? j <= i : anc;
+  }
   if (nj == ni) return j <= i;
   const uint64_t w = nj < 64 ? vis0 : a.node_vis[(int64_t)(nbase + ni) * a.W + (nj >> 6)];
   return (w >> (nj & 63)) & 1u;
@@ -251,7 +257,7 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
         for (int e = 0; e < 16; ++e) {
           const int kk = 32 * hh + rho(e, H), j = j0 + kk;
           bool ok = row_ok && j < T;
-          if (need_mask && ok) ok = visible(a, nbase, ni, i, sNode[kk], j, vis0);
+          if (need_mask) ok = ok & visible(a, nbase, ni, i, sNode[kk], j, vis0);
           const float p = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -lse2));
           ds[e] = ok ? p * (dP[e] - dl) : 0.f;
         }
@@ -297,6 +303,14 @@ __global__ void __launch_bounds__(64) k_bwd_weights(BwdArgs a) {
   for (int o = 32; o >= 1; o >>= 1) n += __shfl_xor(n, o);
   if (lane == 0) a.kt_weight[kt] = (ktl & 1) ? -1 : n;
 }
+// First visibility word of every token's node, so that the dK/dV kernel can fetch it for the rows
+// of a tile without a load that depends on another load.
+__global__ void __launch_bounds__(256) k_bwd_tokvis(BwdArgs a, int total_tokens) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= total_tokens) return;
+  const int b = dag_find_segment(a.cu_seqlens, a.n_seqs, t);
+  a.tok_vis0[t] = a.node_vis[(int64_t)(a.node_start[b] + a.tok_node[t]) * a.W];
+}
 __global__ void __launch_bounds__(64) k_bwd_order(BwdArgs a) {
   const int kt = blockIdx.x, lane = threadIdx.x;
   const int mine = a.kt_weight[kt];
@@ -335,6 +349,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   float* const sLse = (float*)(sdOT + D * LT);           // [BM]  (log2 units)
   float* const sDl = sLse + BM;                          // [BM]
   int* const sNodeR = (int*)(sDl + BM);                  // [BM]
+  uint64_t* const sVis0 = (uint64_t*)(sNodeR + BM);      // [BM]
   __shared__ uint8_t sFlag[MAX_QT_LDS];                  // block-map column of the pair: flag of tile 0 | flag of tile 1 << 2
   // (the KV head is the fast index of the launch: workgroups go to the XCDs round robin, so with 8
   // KV heads every XCD's L2 holds the Q / dO tiles of one head group only, and the workgroups of a
@@ -397,6 +412,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   u32x4 rq[NP], rdo[NP], rqt[NP], rdot[NP];
   float r_lse = 0.f, r_dl = 0.f;
   int r_node = 0;
+  uint64_t r_vis = 0;
   uint32_t row_off[NP];  // element offset of this thread's piece x inside a 64-row slab of q / dout
 #pragma unroll
   for (int x = 0; x < NP; ++x) {
@@ -429,6 +445,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
       r_lse = a.lse[row];
       r_dl = a.delta[row];
       r_node = a.tok_node[cu + r0 + rr];
+      r_vis = a.tok_vis0[cu + r0 + rr];
     }
   };
   auto commit = [&](int qt_of_regs) {
@@ -446,6 +463,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
       sLse[tid] = tid < n_in ? r_lse * LOG2E : 0.f;
       sDl[tid] = tid < n_in ? r_dl : 0.f;
       sNodeR[tid] = r_node;
+      sVis0[tid] = r_vis;
     }
   };
 
@@ -510,10 +528,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
           for (int e = 0; e < 16; ++e) {
             const int r = 32 * rb + rho(e, H), i = r0 + r;
             bool ok = key_ok && i < T;
-            if (need_mask && ok) {
-              const int ni = sNodeR[r];
-              ok = visible(a, nbase, ni, i, nj, j, a.node_vis[(int64_t)(nbase + ni) * a.W]);
-            }
+            if (need_mask) ok = ok & visible(a, nbase, sNodeR[r], i, nj, j, sVis0[r]);
             const float pe = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -l4[e >> 2][e & 3]));
             p[e] = ok ? pe : 0.f;
             ds[e] = p[e] * (dP[e] - d4[e >> 2][e & 3]);
@@ -584,6 +599,8 @@ int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream
   constexpr int sm = dkv_smem_bytes<D>();
   if (hipFuncSetAttribute((const void*)k_bwd_dkv<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
     return DAG_ERR_HIP;
+  const int total_tokens = (int)(a.total_rows / a.hq);
+  hipLaunchKernelGGL(k_bwd_tokvis, dim3((unsigned)((total_tokens + 255) / 256)), dim3(256), 0, stream, a, total_tokens);
   hipLaunchKernelGGL(k_bwd_weights, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
   hipLaunchKernelGGL(k_bwd_order, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
   DAG_LAUNCH_CHECK();
@@ -598,10 +615,12 @@ extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t h
   if (!m || hq < 1 || hkv < 1 || head_dim < 1 || m->sizes.total_tokens < 0 || m->sizes.total_qtiles < 0 ||
       m->sizes.total_ktiles < 0)
     return 0;
-  // delta [T][hq] fp32, the transposed tile images of K, Q and dO (bf16), weight and launch order of the key tiles
+  // delta [T][hq] fp32, the transposed tile images of K, Q and dO (bf16), weight and launch order of
+  // the key tiles, first visibility word per token
   const size_t tile = (size_t)head_dim * BM * 2;
   return dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) + (size_t)m->sizes.total_ktiles * hkv * tile +
-         2 * (size_t)m->sizes.total_qtiles * hq * tile + 2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) + 256;
+         2 * (size_t)m->sizes.total_qtiles * hq * tile + 2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) +
+         dag_align_up((size_t)m->sizes.total_tokens * 8, 256) + 256;
 }
 
 extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const void* k, const void* v, const void* out,
@@ -638,6 +657,7 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   a.kt_weight = (int32_t*)(a.dot_img + (size_t)m->sizes.total_qtiles * hq * tile);
   a.kt_order = a.kt_weight + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4;
   a.total_ktiles = (int)m->sizes.total_ktiles;
+  a.tok_vis0 = (uint64_t*)(a.kt_order + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4);
   a.cu_seqlens = m->cu_seqlens; a.node_start = m->node_start; a.tok_node = m->tok_node;
   a.qtile_start = m->qtile_start; a.ktile_start = m->ktile_start;
   a.qtile_order = m->qtile_order;
