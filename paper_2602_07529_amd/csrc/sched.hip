@@ -54,6 +54,7 @@ extern "C" int dag_sched_create(int32_t n_nodes, const int32_t* parent_off, cons
   }
   dag_sched* s = new (std::nothrow) dag_sched;
   if (!s) return DAG_ERR_WORKSPACE;
+  try {  // (no exception may cross the C boundary: running out of host memory is reported as an error)
   s->n = n_nodes;
   s->words = std::max(1, (n_nodes + 63) / 64);
   s->page_size = page_size;
@@ -76,14 +77,28 @@ extern "C" int dag_sched_create(int32_t n_nodes, const int32_t* parent_off, cons
   s->pos_start.assign(n_nodes, 0);
   s->marked.assign(n_nodes, 0);
   s->seg_of_node.assign(n_nodes, -1);
+  } catch (...) {
+    delete s;
+    return DAG_ERR_WORKSPACE;
+  }
   *out = s;
   return DAG_OK;
 }
 
 extern "C" void dag_sched_destroy(dag_sched_t* s) { delete s; }
 
+static int sched_step(dag_sched_t* s, dag_sched_step_t* out);
+
 extern "C" int dag_sched_step(dag_sched_t* s, dag_sched_step_t* out) {
   if (!s || !out) return DAG_ERR_NULL;
+  try {
+    return sched_step(s, out);
+  } catch (...) {  // host memory exhausted while growing the step's arrays
+    return DAG_ERR_WORKSPACE;
+  }
+}
+
+static int sched_step(dag_sched_t* s, dag_sched_step_t* out) {
   // advance the marking when the whole frontier is complete, then recompute the frontier (Eq. 1)
   bool complete = true;
   for (int v : s->frontier) complete = complete && s->done[v] >= s->len[v];
