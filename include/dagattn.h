@@ -180,8 +180,9 @@ size_t dag_prefill_workspace_bytes(const dag_meta_t* meta, int32_t hkv, int32_t 
  *   dq [T][hq][head_dim], dk and dv [T][hkv][head_dim]   (gradients w.r.t. the rotated q and k; a KV
  *   head's gradient is the sum over its query heads)
  * with P recomputed from lse: dV = P^T dO, dS = P o (dO V^T - rowsum(dO o O)), dQ = scale dS K,
- * dK = scale dS^T Q, only over the tiles the block map marks visible.  DAG_BF16 only (fp32
- * accumulation), head_dim 128 or 64; all tensors DEVICE, 16-byte aligned; `ws` DEVICE scratch of
+ * dK = scale dS^T Q, only over the tiles the block map marks visible.  DAG_BF16 (MFMA, fp32
+ * accumulation; gradients bf16) or DAG_F32 (plain fp32 arithmetic, the accuracy path; gradients
+ * fp32), head_dim 128 or 64; all tensors DEVICE, 16-byte aligned; `ws` DEVICE scratch of
  * dag_prefill_bwd_workspace_bytes.  No atomics: results are bit-identical from run to run.
  * Errors as dag_attn_prefill. */
 size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* meta, int32_t hq, int32_t hkv, int32_t head_dim);

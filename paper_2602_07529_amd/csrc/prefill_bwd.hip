@@ -609,6 +609,186 @@ int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream
   return DAG_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// fp32 backward: the accuracy path beside k_prefill_f32 (plain vector arithmetic, exact expf, the
+// same 64 x 64 tiles and block map).  Four threads share a row (a query row in k_bwd_dq_f32, a key
+// in k_bwd_dkv_f32), each owning a quarter of the head dimension.  Not a performance path.
+struct BwdArgsF32 {
+  const float *q, *k, *v, *out, *dout, *lse;
+  float *dq, *dk, *dv, *delta;
+  const int32_t *cu_seqlens, *node_start, *tok_node, *qtile_start, *ktile_start;
+  const uint64_t* node_vis;
+  const int64_t* block_map_off;
+  const uint8_t* block_map;
+  int n_seqs, W, hq, hkv, G;
+  float scale;
+};
+
+__device__ __forceinline__ float quad_sum(float x) {  // over the four threads of a row
+  x += __shfl_xor(x, 1);
+  x += __shfl_xor(x, 2);
+  return x;
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) k_bwd_dq_f32(BwdArgsF32 a) {
+  extern __shared__ float smem_f[];
+  float* Ks = smem_f;            // [BN][D]
+  float* Vs = smem_f + BN * D;   // [BN][D]
+  int* s_node = (int*)(Vs + BN * D);
+  constexpr int DP = D / 4;
+  const int qt = blockIdx.x, head = blockIdx.y, hk = head / a.G;
+  const int b = dag_find_segment(a.qtile_start, a.n_seqs, qt);
+  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
+  const int qtl = qt - a.qtile_start[b], KT = (T + BN - 1) / BN;
+  const uint8_t* bm = a.block_map + a.block_map_off[b] + (int64_t)qtl * KT;
+  const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
+  const int i = qtl * BM + r, ic = min(i, T - 1);
+  const int ni = a.tok_node[cu + ic];
+  const uint64_t* vis_row = a.node_vis + (int64_t)(a.node_start[b] + ni) * a.W;
+  const size_t row = (size_t)(cu + ic) * a.hq + head;
+  float qr[DP], dor[DP], dq[DP];
+  float dl = 0.f;
+#pragma unroll
+  for (int d = 0; d < DP; ++d) {
+    qr[d] = a.q[row * D + part * DP + d];
+    dor[d] = a.dout[row * D + part * DP + d];
+    dl += dor[d] * a.out[row * D + part * DP + d];
+    dq[d] = 0.f;
+  }
+  dl = quad_sum(dl);
+  if (i < T && part == 0) a.delta[row] = dl;  // for the dK / dV kernel
+  const float lse = a.lse[row];
+  for (int kt = 0; kt < KT; ++kt) {
+    const int flag = bm[kt];
+    if (flag == 0) continue;
+    const int j0 = kt * BN;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < BN * (D / 4); idx += 256) {
+      const int rr = idx / (D / 4), c4 = idx % (D / 4);
+      const size_t g = ((size_t)(cu + min(j0 + rr, T - 1)) * a.hkv + hk) * D + c4 * 4;
+      *(f32x4*)(Ks + rr * D + c4 * 4) = *(const f32x4*)(a.k + g);
+      *(f32x4*)(Vs + rr * D + c4 * 4) = *(const f32x4*)(a.v + g);
+    }
+    if (threadIdx.x < BN) s_node[threadIdx.x] = a.tok_node[cu + min(j0 + (int)threadIdx.x, T - 1)];
+    __syncthreads();
+    const int jn = min(BN, T - j0);
+    for (int jj = 0; jj < jn; ++jj) {
+      const int j = j0 + jj, nj = s_node[jj];
+      const bool ok = flag == 2 || (nj == ni ? j <= i : (bool)((vis_row[nj >> 6] >> (nj & 63)) & 1));
+      float s = 0.f, dp = 0.f;
+#pragma unroll
+      for (int d = 0; d < DP; ++d) {
+        s += qr[d] * Ks[jj * D + part * DP + d];
+        dp += dor[d] * Vs[jj * D + part * DP + d];
+      }
+      s = quad_sum(s);
+      dp = quad_sum(dp);
+      if (ok) {
+        const float ds = expf(s * a.scale - lse) * (dp - dl);
+#pragma unroll
+        for (int d = 0; d < DP; ++d) dq[d] += ds * Ks[jj * D + part * DP + d];
+      }
+    }
+  }
+  if (i < T)
+#pragma unroll
+    for (int d = 0; d < DP; ++d) a.dq[row * D + part * DP + d] = dq[d] * a.scale;
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) k_bwd_dkv_f32(BwdArgsF32 a) {
+  extern __shared__ float smem_f[];
+  float* Qs = smem_f;             // [BM][D]
+  float* dOs = smem_f + BM * D;   // [BM][D]
+  float* s_lse = dOs + BM * D;    // [BM]
+  float* s_dl = s_lse + BM;       // [BM]
+  int* s_node = (int*)(s_dl + BM);
+  constexpr int DP = D / 4;
+  const int kt = blockIdx.x, hk = blockIdx.y;
+  const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
+  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
+  const int ktl = kt - a.ktile_start[b];
+  const int QT = (T + BM - 1) / BM, KT = (T + BN - 1) / BN;
+  const uint8_t* bm = a.block_map + a.block_map_off[b];
+  const int nbase = a.node_start[b];
+  const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
+  const int j = ktl * BN + r, jc = min(j, T - 1);
+  const int nj = a.tok_node[cu + jc];
+  const size_t krow = (size_t)(cu + jc) * a.hkv + hk;
+  float kr[DP], vr[DP], dk[DP], dv[DP];
+#pragma unroll
+  for (int d = 0; d < DP; ++d) {
+    kr[d] = a.k[krow * D + part * DP + d];
+    vr[d] = a.v[krow * D + part * DP + d];
+    dk[d] = dv[d] = 0.f;
+  }
+  for (int qt = 0; qt < QT; ++qt) {
+    const int flag = bm[(int64_t)qt * KT + ktl];
+    if (flag == 0) continue;
+    const int r0 = qt * BM;
+    for (int g = 0; g < a.G; ++g) {
+      const int head = hk * a.G + g;
+      __syncthreads();
+      for (int idx = threadIdx.x; idx < BM * (D / 4); idx += 256) {
+        const int rr = idx / (D / 4), c4 = idx % (D / 4);
+        const size_t o = ((size_t)(cu + min(r0 + rr, T - 1)) * a.hq + head) * D + c4 * 4;
+        *(f32x4*)(Qs + rr * D + c4 * 4) = *(const f32x4*)(a.q + o);
+        *(f32x4*)(dOs + rr * D + c4 * 4) = *(const f32x4*)(a.dout + o);
+      }
+      if (threadIdx.x < BM) {
+        const size_t o = (size_t)(cu + min(r0 + (int)threadIdx.x, T - 1)) * a.hq + head;
+        s_lse[threadIdx.x] = a.lse[o];
+        s_dl[threadIdx.x] = a.delta[o];
+        s_node[threadIdx.x] = a.tok_node[cu + min(r0 + (int)threadIdx.x, T - 1)];
+      }
+      __syncthreads();
+      const int in = min(BM, T - r0);
+      for (int ii = 0; ii < in; ++ii) {
+        const int i = r0 + ii, ni = s_node[ii];
+        bool ok = j < T;
+        if (flag != 2 && ok)
+          ok = nj == ni ? j <= i : (bool)((a.node_vis[(int64_t)(nbase + ni) * a.W + (nj >> 6)] >> (nj & 63)) & 1);
+        float s = 0.f, dp = 0.f;
+#pragma unroll
+        for (int d = 0; d < DP; ++d) {
+          s += kr[d] * Qs[ii * D + part * DP + d];
+          dp += vr[d] * dOs[ii * D + part * DP + d];
+        }
+        s = quad_sum(s);
+        dp = quad_sum(dp);
+        if (ok) {
+          const float p = expf(s * a.scale - s_lse[ii]);
+          const float ds = p * (dp - s_dl[ii]);
+#pragma unroll
+          for (int d = 0; d < DP; ++d) {
+            dv[d] += p * dOs[ii * D + part * DP + d];
+            dk[d] += ds * Qs[ii * D + part * DP + d];
+          }
+        }
+      }
+    }
+  }
+  if (j < T)
+#pragma unroll
+    for (int d = 0; d < DP; ++d) {
+      a.dk[krow * D + part * DP + d] = dk[d] * a.scale;
+      a.dv[krow * D + part * DP + d] = dv[d];
+    }
+}
+
+template <int D>
+int launch_bwd_f32(const BwdArgsF32& a, long total_qtiles, long total_ktiles, hipStream_t stream) {
+  const int sm_q = 2 * BN * D * 4 + BN * 4, sm_k = 2 * BM * D * 4 + 3 * BM * 4;
+  if (hipFuncSetAttribute((const void*)k_bwd_dq_f32<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sm_q) != hipSuccess ||
+      hipFuncSetAttribute((const void*)k_bwd_dkv_f32<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sm_k) != hipSuccess)
+    return DAG_ERR_HIP;
+  hipLaunchKernelGGL((k_bwd_dq_f32<D>), dim3((unsigned)total_qtiles, (unsigned)a.hq), dim3(256), sm_q, stream, a);
+  hipLaunchKernelGGL((k_bwd_dkv_f32<D>), dim3((unsigned)total_ktiles, (unsigned)a.hkv), dim3(256), sm_k, stream, a);
+  DAG_LAUNCH_CHECK();
+  return DAG_OK;
+}
+
 }  // namespace
 
 extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t hq, int32_t hkv, int32_t head_dim) {
@@ -628,7 +808,7 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
                                     int32_t hkv, int32_t head_dim, float softmax_scale, dag_dtype_t dtype, void* ws,
                                     size_t ws_bytes, void* stream) {
   if (!m) return DAG_ERR_NULL;
-  if (dtype != DAG_BF16) return DAG_ERR_UNSUPPORTED;
+  if (dtype != DAG_BF16 && dtype != DAG_F32) return DAG_ERR_UNSUPPORTED;
   if (hq < 1 || hkv < 1 || hq % hkv != 0 || (head_dim != 64 && head_dim != 128)) return DAG_ERR_UNSUPPORTED;
   if (m->tile_m != BM || m->tile_n != BN) return DAG_ERR_UNSUPPORTED;
   if (m->n_seqs < 0 || m->sizes.total_tokens < 0 || m->words_per_node < 1) return DAG_ERR_BAD_LEN;
@@ -644,6 +824,21 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   if (m->sizes.total_qtiles != m->sizes.total_ktiles) return DAG_ERR_BAD_LEN;  // (both tilings are 64 rows)
   const size_t need = dag_prefill_bwd_workspace_bytes(m, hq, hkv, head_dim);
   if (!ws || ws_bytes < need) return DAG_ERR_WORKSPACE;
+  if (dtype == DAG_F32) {
+    BwdArgsF32 f;
+    f.q = (const float*)q; f.k = (const float*)k; f.v = (const float*)v;
+    f.out = (const float*)out; f.dout = (const float*)dout; f.lse = lse;
+    f.dq = (float*)dq; f.dk = (float*)dk; f.dv = (float*)dv;
+    f.delta = (float*)dag_align_up((size_t)(uintptr_t)ws, 256);
+    f.cu_seqlens = m->cu_seqlens; f.node_start = m->node_start; f.tok_node = m->tok_node;
+    f.qtile_start = m->qtile_start; f.ktile_start = m->ktile_start;
+    f.node_vis = m->node_vis; f.block_map_off = m->block_map_off; f.block_map = m->block_map;
+    f.n_seqs = m->n_seqs; f.W = m->words_per_node; f.hq = hq; f.hkv = hkv; f.G = hq / hkv;
+    f.scale = softmax_scale;
+    hipStream_t s32 = (hipStream_t)stream;
+    return head_dim == 128 ? launch_bwd_f32<128>(f, m->sizes.total_qtiles, m->sizes.total_ktiles, s32)
+                           : launch_bwd_f32<64>(f, m->sizes.total_qtiles, m->sizes.total_ktiles, s32);
+  }
   BwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.out = (const uint16_t*)out; a.dout = (const uint16_t*)dout;

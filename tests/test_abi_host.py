@@ -341,7 +341,7 @@ def test_backward_argument_errors():
     nine = [p] * 9
     assert call(*nine, nb=need - 1) == -6
     assert call(*nine, ws=None) == -6
-    assert call(*nine, a=(32, 8, 128, 0.1, B.DAG_F32)) == -7
+    assert call(*nine, a=(32, 8, 128, 0.1, 7)) == -7            # no such dtype
     assert call(*nine, a=(32, 8, 96, 0.1, B.DAG_BF16)) == -7
     assert call(*nine, a=(30, 8, 128, 0.1, B.DAG_BF16)) == -7
     for missing in range(9):

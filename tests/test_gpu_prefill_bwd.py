@@ -110,3 +110,40 @@ def test_bwd_config2_one_sequence_one_kv_group_every_row():
     check_close(grads[0][sl][:, 4:8], ref[0][:, 4:8], torch.bfloat16, "config 2 dq")
     check_close(grads[1][sl][:, 1], ref[1][:, 1], torch.bfloat16, "config 2 dk")
     check_close(grads[2][sl][:, 1], ref[2][:, 1], torch.bfloat16, "config 2 dv")
+
+
+def test_bwd_fp32_config1_and_ragged_dags():
+    """The fp32 accuracy path (benchmark config 1: 128 -> 4 x 64 -> 64, 4 heads, D 64; then ragged
+    DAGs with GQA at D 128): gradients within 1e-4 of the oracle's (absolute bound scaled by the
+    largest reference magnitude, as for bf16)."""
+    c = dags.config(0)
+    rng = np.random.Generator(np.random.PCG64(77))
+    for dag_list, hq, hkv, d, scale, theta in [
+            (dags.config_dags(c), c["hq"], c["hkv"], c["d"], c["scale"], c["theta"]),
+            ([dags.fork_join(70, [33, 64], 31), dags.random_dag(rng, n_nodes=10, depth=4, len_lo=1, len_hi=30)[:2]],
+             4, 2, 128, 1.0, 1e4)]:
+        T = int(sum(int(np.sum(L)) for L, _ in dag_list))
+        q, k, v = dags.make_qkv(61, T, hq, hkv, d, scale, torch.float32)
+        dout = dags.make_qkv(62, T, hq, hkv, d, 1.0, torch.float32)[0]
+        _, meta = build_meta(dag_list, hq, hkv, d, torch.float32)
+        qd, kd, vd, dod = q.to(DEV).clone(), k.to(DEV).clone(), v.to(DEV), dout.to(DEV)
+        B.dag_rope_qk(meta.get("pos_ids"), qd, kd, theta)
+        out = torch.empty_like(qd)
+        lse = torch.empty(T, hq, dtype=torch.float32, device=DEV)
+        B.dag_attn_prefill(meta, qd, kd, vd, out, lse)
+        dq, dk, dv = torch.full_like(qd, float("nan")), torch.full_like(kd, float("nan")), torch.full_like(vd, float("nan"))
+        B.dag_attn_prefill_bwd(meta, qd, kd, vd, out, dod, lse, dq, dk, dv)
+        torch.cuda.synchronize()
+        refs, t0 = [], 0
+        for L, anc in dag_list:
+            Tb = int(np.sum(L))
+            sl = slice(t0, t0 + Tb)
+            refs.append(orc.attn_prefill_bwd(dags.to_f64(qd[sl]), dags.to_f64(kd[sl]), dags.to_f64(v[sl]),
+                                             dags.to_f64(dout[sl]), L, anc))
+            t0 += Tb
+        for x, (name, g) in enumerate(zip(("dq", "dk", "dv"), (dq, dk, dv))):
+            ref = np.concatenate([r[x] for r in refs])
+            got = g.cpu().double().numpy()
+            assert np.isfinite(got).all()
+            assert np.abs(got - ref).max() <= 1e-4 * max(1.0, np.abs(ref).max()), name
+            assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-4, name
