@@ -504,11 +504,30 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
         f32x16 S, dP;
 #pragma unroll
         for (int e = 0; e < 16; ++e) S[e] = dP[e] = 0.f;
+        // (all operand reads of a phase are issued before its first MFMA: one wave per SIMD has
+        // nobody to hide the LDS latency behind, so the reads are kept far ahead of their use)
+        bf16x8 aq[D / 16], ado[D / 16];
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+          aq[s] = *(const bf16x8*)(sQ + (32 * rb + L) * LD + 16 * s + 8 * H);
+          ado[s] = *(const bf16x8*)(sdO + (32 * rb + L) * LD + 16 * s + 8 * H);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) {  // S = Q K^T, dP = dO V^T: rows = query rows, column = this lane's key
-          S = mfma32(*(const bf16x8*)(sQ + (32 * rb + L) * LD + 16 * s + 8 * H), kf[s], S);
-          dP = mfma32(*(const bf16x8*)(sdO + (32 * rb + L) * LD + 16 * s + 8 * H), vf[s], dP);
+          S = mfma32(aq[s], kf[s], S);
+          dP = mfma32(ado[s], vf[s], dP);
         }
+        // the transposed operands of the second phase: on their way during the exponentials
+        bf16x8 at_do[2 * DB], at_q[2 * DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          at_do[2 * db] = *(const bf16x8*)(sdOT + (32 * db + L) * LT + 32 * rb + 8 * H);
+          at_do[2 * db + 1] = *(const bf16x8*)(sdOT + (32 * db + L) * LT + 32 * rb + 16 + 8 * H);
+          at_q[2 * db] = *(const bf16x8*)(sQT + (32 * db + L) * LT + 32 * rb + 8 * H);
+          at_q[2 * db + 1] = *(const bf16x8*)(sQT + (32 * db + L) * LT + 32 * rb + 16 + 8 * H);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         float p[16], ds[16];
         // lse and delta of the 16 rows of this lane: four groups of four consecutive rows
         f32x4 l4[4], d4[4];
@@ -537,10 +556,10 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
         const bf16x8 p0 = pack8(p), p1 = pack8(p + 8), s0 = pack8(ds), s1 = pack8(ds + 8);
 #pragma unroll
         for (int db = 0; db < DB; ++db) {  // dV^T += dO^T P, dK^T += Q^T dS
-          dV[db] = mfma32(*(const bf16x8*)(sdOT + (32 * db + L) * LT + 32 * rb + 8 * H), p0, dV[db]);
-          dV[db] = mfma32(*(const bf16x8*)(sdOT + (32 * db + L) * LT + 32 * rb + 16 + 8 * H), p1, dV[db]);
-          dK[db] = mfma32(*(const bf16x8*)(sQT + (32 * db + L) * LT + 32 * rb + 8 * H), s0, dK[db]);
-          dK[db] = mfma32(*(const bf16x8*)(sQT + (32 * db + L) * LT + 32 * rb + 16 + 8 * H), s1, dK[db]);
+          dV[db] = mfma32(at_do[2 * db], p0, dV[db]);
+          dV[db] = mfma32(at_do[2 * db + 1], p1, dV[db]);
+          dK[db] = mfma32(at_q[2 * db], s0, dK[db]);
+          dK[db] = mfma32(at_q[2 * db + 1], s1, dK[db]);
         }
       }
     }
