@@ -33,6 +33,9 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # profiles/k_decode__*.txt hold the commands and the raw readings); measured, not computed here.
 TRAFFIC_PREFILL_KERNEL = (1237150 + 147528) * 1024      # k_prefill_bf16, read + written
 TRAFFIC_DECODE_KERNELS = (1053639 + 10400 + 11819 + 1024) * 1024   # k_decode + k_decode_merge
+# (profiles/k_decode_seg__*.txt and profiles/k_bwd__*.txt)
+TRAFFIC_SEG_DECODE_KERNELS = (8 + 8 + 1058683 + 8322 + 9290 + 1024) * 1024   # k_seg_plan + k_decode_seg + k_decode_seg_merge
+TRAFFIC_BWD_KERNELS = (294940 + 4608 + 331840 + 332792 + 1012962 + 165890 + 4507546 + 73728) * 1024   # delta, transposes, dq, dkv
 
 
 def _ensure_built():
@@ -320,14 +323,14 @@ def main():
                             "roofline": {"bound": "hbm", "kernel": "k_seg_plan+k_decode_seg+k_decode_seg_merge",
                                          "achieved": seg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                          "frac": seg_gbs / HBM_PEAK_GBS, "algorithmic_bytes": sw.bytes,
-                                         "traffic": None}},
+                                         "traffic": TRAFFIC_SEG_DECODE_KERNELS}},
         "prefill_bwd": {"metric": "dag_attn_prefill_bwd_useful_tflops", "value": 2.5 * flops / (ms_bwd * 1e-3) / 1e12,
                         "unit": "TFLOP/s", "ms_per_call": ms_bwd, "calls": n_bwd,
                         "useful_flops": "2.5 x forward (five products per visible pair)",
                         "roofline": {"bound": "mfma", "kernel": "k_bwd_delta+k_bwd_transpose+k_bwd_dq+k_bwd_dkv",
                                      "achieved": 2.5 * flops / (ms_bwd * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                                      "unit": "TFLOP/s", "frac": 2.5 * flops / (ms_bwd * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                                     "traffic": None}},
+                                     "traffic": TRAFFIC_BWD_KERNELS}},
         "wall_s_timed_loop": wall,
     }
     if not args.no_cpu_baseline:
