@@ -117,19 +117,20 @@ __device__ __forceinline__ void stage_image(uint16_t* dst, const uint16_t* img, 
 
 template <int D>
 __global__ void __launch_bounds__(256) k_bwd_delta(BwdArgs a) {
-  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);  // (token, query head)
-  if (row >= a.total_rows) return;
-  const int lane = threadIdx.x & 63;
-  constexpr int PER = D / 64;
+  // D / 8 lanes per (token, query head) row, 16 bytes of out and of dout per lane
+  constexpr int LPR = D / 8, RPB = 256 / LPR;
+  const long row = (long)blockIdx.x * RPB + threadIdx.x / LPR;
+  const int part = threadIdx.x % LPR;
   float s = 0.f;
+  if (row < a.total_rows) {
+    const u32x4 o = *(const u32x4*)(a.out + (size_t)row * D + part * 8);
+    const u32x4 g = *(const u32x4*)(a.dout + (size_t)row * D + part * 8);
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const size_t idx = (size_t)row * D + lane * PER + e;
-    s += __uint_as_float((uint32_t)a.out[idx] << 16) * __uint_as_float((uint32_t)a.dout[idx] << 16);
+    for (int e = 0; e < 4; ++e) s += dag_bf_lo(o[e]) * dag_bf_lo(g[e]) + dag_bf_hi(o[e]) * dag_bf_hi(g[e]);
   }
 #pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
-  if (lane == 0) a.delta[row] = s;
+  for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+  if (part == 0 && row < a.total_rows) a.delta[row] = s;
 }
 
 template <int D, int HG>
@@ -602,7 +603,8 @@ int launch_dq(const BwdArgs& a, long total_qtiles, hipStream_t stream) {
 
 template <int D>
 int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream_t stream) {
-  hipLaunchKernelGGL((k_bwd_delta<D>), dim3((unsigned)((a.total_rows + 3) / 4)), dim3(256), 0, stream, a);
+  constexpr int RPB = 256 / (D / 8);  // rows per workgroup of k_bwd_delta
+  hipLaunchKernelGGL((k_bwd_delta<D>), dim3((unsigned)((a.total_rows + RPB - 1) / RPB)), dim3(256), 0, stream, a);
   DAG_LAUNCH_CHECK();
   // (query and key tiles are both 64 rows, so one tiling serves the three images)
   hipLaunchKernelGGL((k_bwd_transpose<D>), dim3((unsigned)total_ktiles, (unsigned)a.hkv), dim3(256), 0, stream, a.k,
