@@ -5,7 +5,6 @@
 // P is recomputed from the forward's log-sum-exp; the block map of the forward skips the tiles
 // without a visible pair.  bf16 operands on the 32x32x16 MFMA, fp32 accumulation.  Three kernels:
 //   k_bwd_delta   delta per (token, query head)
-//   k_bwd_transpose  the transposed tile images of K, Q and dO
 //   k_bwd_dq      one workgroup per (64-row query tile, KV head, up to 4 of its query heads), loop
 //                 over the tile's key tiles, which the heads share
 //   k_bwd_dkv     one workgroup per (pair of 64-key tiles, KV head), loop over the query tiles that
@@ -15,10 +14,9 @@
 // column L and the 16 rows rho_H(e) = 8 (e / 4) + 4 H + e % 4.  A result is used again as the B
 // operand of the next product (contraction over its rows) straight from the registers; the A
 // operand of that product is then gathered from LDS in the same row order.
-// Those A operands are transposed tiles (K^T for dQ; Q^T and dO^T for dK and dV): a pre-pass
-// writes them once into the workspace, tile by tile, as [D][64] images whose 64 columns are already
-// in the order rho asks for, so that the main kernels stage them with linear copies and read every
-// operand with one 16-byte LDS read.
+// Those A operands are transposed tiles (K^T for dQ; Q^T and dO^T for dK and dV): they are read
+// from the row-major tiles in LDS with the transposing LDS load of gfx950, two 8-byte reads per
+// operand, in the row order rho asks for.
 // Tiles are staged with plain loads between two workgroup barriers (no software pipeline yet).
 #include "common.h"
 
@@ -32,7 +30,6 @@ struct BwdArgs {
   const float* lse;
   uint16_t *dq, *dk, *dv;
   float* delta;  // [T][hq]
-  uint16_t *kt_img, *qt_img, *dot_img;  // transposed tile images [tile][head][D][64]
   int32_t *kt_weight, *kt_order;        // [total key tiles] launch order of the dK/dV workgroups
   uint64_t* tok_vis0;                   // [T] first visibility word of every token's node
   int total_ktiles;
@@ -69,50 +66,27 @@ __device__ __forceinline__ bool visible(const BwdArgs& a, int nbase, int ni, int
   return (w >> (nj & 63)) & 1u;
 }
 
-constexpr int LT = BN + 8;  // padded row of a transposed tile in LDS (elements)
 constexpr int MAX_QT_LDS = 4096;  // query tiles of a sequence whose block-map column is kept in LDS (262,144 tokens)
 
-// Column order of a transposed tile: column c = 32 hh + 16 ks + 8 H + e holds row
-// 32 hh + rho_H(8 ks + e) of the tile, so the 8 elements lane (., H) needs for contraction step ks
-// of half hh are consecutive.
-__device__ __forceinline__ int row_of_column(int c) {
-  return (c & 32) + rho(8 * ((c >> 4) & 1) + (c & 7), (c >> 3) & 1);
-}
-
-// Pre-pass: src [T][heads][D] -> img [tile][head][D][64 columns in the order above]; rows past the
-// end of the sequence are zero.  One workgroup per (64-row tile, head).
-template <int D>
-__global__ void __launch_bounds__(256) k_bwd_transpose(const uint16_t* __restrict__ src, uint16_t* __restrict__ img,
-                                                       int heads, BwdArgs a) {
-  constexpr int LD = D + 8;
-  __shared__ __attribute__((aligned(16))) uint16_t s[BM * LD];
-  const int tile = blockIdx.x, h = blockIdx.y;
-  const int b = dag_find_segment(a.qtile_start, a.n_seqs, tile);
-  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
-  const int r0 = (tile - a.qtile_start[b]) * BM;
-  for (int c = threadIdx.x; c < BM * (D / 8); c += 256) {
-    const int r = c / (D / 8), ch = c % (D / 8);
-    u32x4 x = {0, 0, 0, 0};
-    if (r0 + r < T) x = *(const u32x4*)(src + ((size_t)(cu + r0 + r) * heads + h) * D + ch * 8);
-    *(u32x4*)(s + r * LD + ch * 8) = x;
-  }
-  __syncthreads();
-  uint16_t* o = img + ((size_t)tile * heads + h) * (size_t)(D * BM);
-  for (int p = threadIdx.x; p < D * (BM / 8); p += 256) {  // 16-byte piece: 8 columns of row d of the image
-    const int d = p % D, cg = p / D;
-    uint32_t w[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      w[e] = (uint32_t)s[row_of_column(8 * cg + 2 * e) * LD + d] |
-             ((uint32_t)s[row_of_column(8 * cg + 2 * e + 1) * LD + d] << 16);
-    *(u32x4*)(o + (size_t)d * BM + 8 * cg) = u32x4{w[0], w[1], w[2], w[3]};
-  }
-}
-
-// stage one transposed image ([D][64], contiguous) into LDS rows of LT elements
-template <int D, int NT>
-__device__ __forceinline__ void stage_image(uint16_t* dst, const uint16_t* img, int tid) {
-  for (int p = tid; p < D * (BM / 8); p += NT) *(u32x4*)(dst + (p >> 3) * LT + (p & 7) * 8) = *(const u32x4*)(img + (size_t)p * 8);
+// A operand of a product whose contraction runs over the ROWS of a row-major LDS tile (K^T for dQ;
+// Q^T and dO^T for dK and dV), read with the transposing LDS load of gfx950 (ds_read_b64_tr_b16):
+// within 16 consecutive lanes, lane p hands in the address of four consecutive 16-bit elements and
+// lane i receives, as component j, element i % 4 of the four that lane 4 j + i / 4 pointed at.
+// With lane p pointing at tile[row 4 H + p / 4 (+ 8)][col 16 (lane / 16 % 2) + 4 (p % 4)], lane
+// (L, H) of the wave gets tile[4 H + j (+ 8)][L], j = 0 .. 3: column L of the rows rho_H(0 .. 7), the
+// row order in which the B operand (a previous result) holds its eight contraction elements.
+// `tile` points at the first of the 16 rows and the first of the 32 columns of the operand.
+template <int LD>
+__device__ __forceinline__ bf16x8 read_transposed(const uint16_t* tile, int lane) {
+  typedef short v4i16 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) v4i16* lds_v4_t;
+  const int p = lane & 15, g = lane >> 4;
+  const uint16_t* a0 = tile + (4 * (g >> 1) + (p >> 2)) * LD + 16 * (g & 1) + 4 * (p & 3);
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)a0);
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)(a0 + 8 * LD));
+  typedef short v8i16 __attribute__((ext_vector_type(8)));
+  const v8i16 x = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, x);
 }
 
 template <int D>
@@ -140,8 +114,7 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* const sK = (uint16_t*)smem;   // [BN][LD]
   uint16_t* const sV = sK + BN * LD;      // [BN][LD]
-  uint16_t* const sKT = sV + BN * LD;     // [D][LT]
-  int* const sNode = (int*)(sKT + D * LT);
+  int* const sNode = (int*)(sV + BN * LD);
   __shared__ uint8_t sFlag[MAX_QT_LDS];  // the tile's row of the block map
   const int qt = a.qtile_order[blockIdx.x], hk = blockIdx.y;  // heaviest tiles first
   const int g = blockIdx.z * HG + (threadIdx.x >> 7);  // two waves per query head
@@ -183,7 +156,7 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
   // one is multiplied (constant per-thread offsets, rows past the end re-read the last row and are
   // zeroed on the way to LDS, no load depends on another).
   constexpr int NPQ = (BN * (D / 8) + NT - 1) / NT;  // 16-byte pieces per thread and staged tile
-  u32x4 rk[NPQ], rv[NPQ], rkt[NPQ];
+  u32x4 rk[NPQ], rv[NPQ];
   int r_node = 0;
   uint32_t row_off[NPQ];
 #pragma unroll
@@ -202,14 +175,12 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
     const size_t slab = ((size_t)(cu + j0) * a.hkv + hk) * D;
     const uint16_t* pk = a.k + slab;
     const uint16_t* pv = a.v + slab;
-    const uint16_t* pt = a.kt_img + ((size_t)(a.ktile_start[b] + kt) * a.hkv + hk) * (size_t)(D * BN);
 #pragma unroll
     for (int x = 0; x < NPQ; ++x) {
       const int c = min(tid + NT * x, BN * (D / 8) - 1), r = c / (D / 8);
       const uint32_t off = r < n_in ? row_off[x] : row_off[x] - (uint32_t)(r - (n_in - 1)) * one_row;
       rk[x] = *(const u32x4*)(pk + off);
       rv[x] = *(const u32x4*)(pv + off);
-      rkt[x] = *(const u32x4*)(pt + (uint32_t)c * 8);
     }
     if (tid < BN) r_node = a.tok_node[cu + j0 + min(tid, n_in - 1)];
   };
@@ -222,7 +193,6 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
         if (r >= n_in) rk[x] = rv[x] = u32x4{0, 0, 0, 0};
         *(u32x4*)(sK + r * LD + ch * 8) = rk[x];
         *(u32x4*)(sV + r * LD + ch * 8) = rv[x];
-        *(u32x4*)(sKT + (c >> 3) * LT + (c & 7) * 8) = rkt[x];
       }
     }
     if (tid < BN) sNode[tid] = r_node;
@@ -266,8 +236,8 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
       const bf16x8 b0 = pack8(ds), b1 = pack8(ds + 8);
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {  // dQ^T += K^T dS^T
-        dQ[db] = mfma32(*(const bf16x8*)(sKT + (32 * db + L) * LT + 32 * hh + 8 * H), b0, dQ[db]);
-        dQ[db] = mfma32(*(const bf16x8*)(sKT + (32 * db + L) * LT + 32 * hh + 16 + 8 * H), b1, dQ[db]);
+        dQ[db] = mfma32(read_transposed<LD>(sK + (32 * hh) * LD + 32 * db, lane), b0, dQ[db]);
+        dQ[db] = mfma32(read_transposed<LD>(sK + (32 * hh + 16) * LD + 32 * db, lane), b1, dQ[db]);
       }
     }
   }
@@ -329,7 +299,7 @@ template <int D>
 constexpr int dkv_smem_bytes() {
   // Q and dO rows of one query tile for one query head and their transposed images, lse / delta of
   // the rows, node ids and first visibility words of the rows
-  return 2 * BM * (D + 8) * 2 + 2 * D * LT * 2 + 2 * BM * 4 + BM * 4 + BM * 8;
+  return 2 * BM * (D + 8) * 2 + 2 * BM * 4 + BM * 4 + BM * 8;
 }
 
 // One workgroup per pair of key tiles (128 keys) and KV head: wave w owns keys 32 w .. 32 w + 31 of
@@ -345,9 +315,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* const sQ = (uint16_t*)smem;                  // [BM][LD]
   uint16_t* const sdO = sQ + BM * LD;                    // [BM][LD]
-  uint16_t* const sQT = sdO + BM * LD;                   // [D][LT]
-  uint16_t* const sdOT = sQT + D * LT;                   // [D][LT]
-  float* const sLse = (float*)(sdOT + D * LT);           // [BM]  (log2 units)
+  float* const sLse = (float*)(sdO + BM * LD);           // [BM]  (log2 units)
   float* const sDl = sLse + BM;                          // [BM]
   int* const sNodeR = (int*)(sDl + BM);                  // [BM]
   uint64_t* const sVis0 = (uint64_t*)(sNodeR + BM);      // [BM]
@@ -410,7 +378,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   // never change; rows past the end of the sequence re-read its last row and are zeroed afterwards,
   // so no load sits under a branch; no load depends on another one: a wait for the first would
   // also wait for everything issued before it)
-  u32x4 rq[NP], rdo[NP], rqt[NP], rdot[NP];
+  u32x4 rq[NP], rdo[NP];
   float r_lse = 0.f, r_dl = 0.f;
   int r_node = 0;
   uint64_t r_vis = 0;
@@ -427,9 +395,6 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
     const size_t slab = ((size_t)(cu + r0) * a.hq + h) * D;
     const uint16_t* pq = a.q + slab;
     const uint16_t* pdo = a.dout + slab;
-    const size_t t_off = ((size_t)(a.qtile_start[b] + qt) * a.hq + h) * (size_t)(D * BM);
-    const uint16_t* pqt = a.qt_img + t_off;
-    const uint16_t* pdot = a.dot_img + t_off;
     const int n_in = min(BM, T - r0);  // rows of the tile inside the sequence (>= 1)
 #pragma unroll
     for (int x = 0; x < NP; ++x) {
@@ -437,8 +402,6 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
       const uint32_t off = r < n_in ? row_off[x] : row_off[x] - (uint32_t)(r - (n_in - 1)) * last_off;
       rq[x] = *(const u32x4*)(pq + off);
       rdo[x] = *(const u32x4*)(pdo + off);
-      rqt[x] = *(const u32x4*)(pqt + (uint32_t)c * 8);
-      rdot[x] = *(const u32x4*)(pdot + (uint32_t)c * 8);
     }
     if (tid < BM) {
       const int rr = min(tid, n_in - 1);
@@ -457,8 +420,6 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
       if (r >= n_in) rq[x] = rdo[x] = u32x4{0, 0, 0, 0};
       *(u32x4*)(sQ + r * LD + ch * 8) = rq[x];
       *(u32x4*)(sdO + r * LD + ch * 8) = rdo[x];
-      *(u32x4*)(sQT + (c >> 3) * LT + (c & 7) * 8) = rqt[x];
-      *(u32x4*)(sdOT + (c >> 3) * LT + (c & 7) * 8) = rdot[x];
     }
     if (tid < BM) {
       sLse[tid] = tid < n_in ? r_lse * LOG2E : 0.f;
@@ -523,10 +484,10 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
         bf16x8 at_do[2 * DB], at_q[2 * DB];
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          at_do[2 * db] = *(const bf16x8*)(sdOT + (32 * db + L) * LT + 32 * rb + 8 * H);
-          at_do[2 * db + 1] = *(const bf16x8*)(sdOT + (32 * db + L) * LT + 32 * rb + 16 + 8 * H);
-          at_q[2 * db] = *(const bf16x8*)(sQT + (32 * db + L) * LT + 32 * rb + 8 * H);
-          at_q[2 * db + 1] = *(const bf16x8*)(sQT + (32 * db + L) * LT + 32 * rb + 16 + 8 * H);
+          at_do[2 * db] = read_transposed<LD>(sdO + (32 * rb) * LD + 32 * db, lane);
+          at_do[2 * db + 1] = read_transposed<LD>(sdO + (32 * rb + 16) * LD + 32 * db, lane);
+          at_q[2 * db] = read_transposed<LD>(sQ + (32 * rb) * LD + 32 * db, lane);
+          at_q[2 * db + 1] = read_transposed<LD>(sQ + (32 * rb + 16) * LD + 32 * db, lane);
         }
         __builtin_amdgcn_sched_barrier(0);
         float p[16], ds[16];
@@ -592,7 +553,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
 
 template <int D, int HG>
 int launch_dq(const BwdArgs& a, long total_qtiles, hipStream_t stream) {
-  constexpr int sm = 2 * BN * (D + 8) * 2 + D * LT * 2 + BN * 4;
+  constexpr int sm = 2 * BN * (D + 8) * 2 + BN * 4;
   if (hipFuncSetAttribute((const void*)k_bwd_dq<D, HG>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
     return DAG_ERR_HIP;
   hipLaunchKernelGGL((k_bwd_dq<D, HG>), dim3((unsigned)total_qtiles, (unsigned)a.hkv, (unsigned)((a.G + HG - 1) / HG)),
@@ -605,14 +566,6 @@ template <int D>
 int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream_t stream) {
   constexpr int RPB = 256 / (D / 8);  // rows per workgroup of k_bwd_delta
   hipLaunchKernelGGL((k_bwd_delta<D>), dim3((unsigned)((a.total_rows + RPB - 1) / RPB)), dim3(256), 0, stream, a);
-  DAG_LAUNCH_CHECK();
-  // (query and key tiles are both 64 rows, so one tiling serves the three images)
-  hipLaunchKernelGGL((k_bwd_transpose<D>), dim3((unsigned)total_ktiles, (unsigned)a.hkv), dim3(256), 0, stream, a.k,
-                     a.kt_img, a.hkv, a);
-  hipLaunchKernelGGL((k_bwd_transpose<D>), dim3((unsigned)total_qtiles, (unsigned)a.hq), dim3(256), 0, stream, a.q,
-                     a.qt_img, a.hq, a);
-  hipLaunchKernelGGL((k_bwd_transpose<D>), dim3((unsigned)total_qtiles, (unsigned)a.hq), dim3(256), 0, stream, a.dout,
-                     a.dot_img, a.hq, a);
   DAG_LAUNCH_CHECK();
   const int rc = a.G >= 3 ? launch_dq<D, 4>(a, total_qtiles, stream)
                           : a.G == 2 ? launch_dq<D, 2>(a, total_qtiles, stream) : launch_dq<D, 1>(a, total_qtiles, stream);
@@ -816,11 +769,9 @@ extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t h
   if (!m || hq < 1 || hkv < 1 || head_dim < 1 || m->sizes.total_tokens < 0 || m->sizes.total_qtiles < 0 ||
       m->sizes.total_ktiles < 0)
     return 0;
-  // delta [T][hq] fp32, the transposed tile images of K, Q and dO (bf16), weight and launch order of
-  // the key tiles, first visibility word per token
-  const size_t tile = (size_t)head_dim * BM * 2;
-  return dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) + (size_t)m->sizes.total_ktiles * hkv * tile +
-         2 * (size_t)m->sizes.total_qtiles * hq * tile + 2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) +
+  // delta [T][hq] fp32, weight and launch order of the key tiles, first visibility word per token
+  return dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) +
+         2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) +
          dag_align_up((size_t)m->sizes.total_tokens * 8, 256) + 256;
 }
 
@@ -866,11 +817,7 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   a.lse = lse;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
   a.delta = (float*)dag_align_up((size_t)(uintptr_t)ws, 256);
-  const size_t tile = (size_t)head_dim * BM;  // elements
-  a.kt_img = (uint16_t*)((char*)a.delta + dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256));
-  a.qt_img = a.kt_img + (size_t)m->sizes.total_ktiles * hkv * tile;
-  a.dot_img = a.qt_img + (size_t)m->sizes.total_qtiles * hq * tile;
-  a.kt_weight = (int32_t*)(a.dot_img + (size_t)m->sizes.total_qtiles * hq * tile);
+  a.kt_weight = (int32_t*)((char*)a.delta + dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256));
   a.kt_order = a.kt_weight + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4;
   a.total_ktiles = (int)m->sizes.total_ktiles;
   a.tok_vis0 = (uint64_t*)(a.kt_order + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4);
