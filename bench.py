@@ -35,7 +35,7 @@ TRAFFIC_PREFILL_KERNEL = (1237150 + 147528) * 1024      # k_prefill_bf16, read +
 TRAFFIC_DECODE_KERNELS = (1053639 + 10400 + 11819 + 1024) * 1024   # k_decode + k_decode_merge
 # (profiles/k_decode_seg__*.txt and profiles/k_bwd__*.txt)
 TRAFFIC_SEG_DECODE_KERNELS = (8 + 8 + 1058683 + 8322 + 9290 + 1024) * 1024   # k_seg_plan + k_decode_seg + k_decode_seg_merge
-TRAFFIC_BWD_KERNELS = (294940 + 4608 + 331840 + 332792 + 1012962 + 165890 + 4507546 + 73728) * 1024   # delta, transposes, dq, dkv
+TRAFFIC_BWD_KERNELS = (294941 + 2304 + 769233 + 165872 + 2536551 + 73728 + 256 + 156) * 1024   # delta, dq, dkv, the three small ones
 
 
 def _ensure_built():
