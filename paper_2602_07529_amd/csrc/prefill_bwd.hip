@@ -3,8 +3,10 @@
 //     delta_i = sum_d dO_id O_id,   dV = P^T dO,   dP = dO V^T,   dS = P o (dP - delta),
 //     dQ = scale dS K,   dK = scale dS^T Q        (a KV head sums over its query heads).
 // P is recomputed from the forward's log-sum-exp; the block map of the forward skips the tiles
-// without a visible pair.  bf16 operands on the 32x32x16 MFMA, fp32 accumulation.  Three kernels:
+// without a visible pair.  bf16 operands on the 32x32x16 MFMA, fp32 accumulation.  The kernels:
 //   k_bwd_delta   delta per (token, query head)
+//   k_bwd_tokvis, k_bwd_weights, k_bwd_order   small tables: first visibility word per token; weight
+//                 and launch rank of the key-tile pairs (the dK/dV workgroups start heaviest first)
 //   k_bwd_dq      one workgroup per (64-row query tile, KV head, up to 4 of its query heads), loop
 //                 over the tile's key tiles, which the heads share
 //   k_bwd_dkv     one workgroup per (pair of 64-key tiles, KV head), loop over the query tiles that
@@ -17,7 +19,9 @@
 // Those A operands are transposed tiles (K^T for dQ; Q^T and dO^T for dK and dV): they are read
 // from the row-major tiles in LDS with the transposing LDS load of gfx950, two 8-byte reads per
 // operand, in the row order rho asks for.
-// Tiles are staged with plain loads between two workgroup barriers (no software pipeline yet).
+// Tiles go global -> registers -> LDS: the next tile is fetched into registers while the current
+// one is multiplied, and stored to LDS between two workgroup barriers.
+// fp32 inputs take the plain kernels at the end of the file (the accuracy path).
 #include "common.h"
 
 namespace {
