@@ -33,7 +33,7 @@ def _multilevel(scale_len=1):
 
 
 @pytest.mark.parametrize("hq,hkv,d,scale_len", [(8, 2, 128, 1), (4, 1, 64, 1), (5, 1, 128, 1), (32, 8, 128, 1),
-                                                (8, 2, 128, 40), (6, 2, 64, 23)])
+                                                (8, 2, 128, 40), (6, 2, 64, 23), (16, 1, 64, 5), (24, 2, 128, 2)])
 def test_multilevel_dags_every_live_branch(hq, hkv, d, scale_len):
     """Two multi-level DAGs and a random one: live leaves, a live join and a live inner node; the
     junk in the unused slots of partly filled pages must not leak (the oracle never reads it)."""

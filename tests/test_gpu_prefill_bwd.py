@@ -55,7 +55,8 @@ def _check_against_oracle(dag_list, inputs, grads, scale=None):
         check_close(g, np.concatenate([r[x] for r in refs]), torch.bfloat16, name)
 
 
-@pytest.mark.parametrize("hq,hkv,d", [(4, 1, 128), (8, 2, 64), (5, 1, 128), (2, 2, 64), (3, 1, 64), (8, 2, 128)])
+@pytest.mark.parametrize("hq,hkv,d", [(4, 1, 128), (8, 2, 64), (5, 1, 128), (2, 2, 64), (3, 1, 64), (8, 2, 128),
+                                      (8, 1, 64), (9, 1, 128), (14, 2, 64)])   # the last three: more than four query heads per KV head
 def test_bwd_small_dags_every_head_grouping(hq, hkv, d):
     rng = np.random.Generator(np.random.PCG64(3000 + hq * 10 + d))
     dag_list = [dags.fork_join(100, [37, 64, 5], 70),               # ragged everywhere
