@@ -39,6 +39,8 @@ def _oracle_pools_after_append(st, theta):
     (16, 2, 128, 1, 33, [1]),                # a single branch whose own context is just its token
     (12, 2, 64, 9, 200, [3, 40, 16, 1, 7, 64, 33, 2, 20]),   # G = 6; 54 rows -> two row blocks, D = 64
     (24, 2, 128, 11, 77, [5] * 11),          # G = 12; 132 rows -> five row blocks, the last one partly filled
+    (12, 2, 128, 30, 330, [3, 17, 1] * 10),  # G = 6; 180 rows -> six row blocks: two of them split over wave pairs
+    (10, 2, 64, 16, 1000, [2] * 16),         # G = 5; 160 rows -> five row blocks at D = 64, 63 pages of shared context
 ])
 def test_decode_small_cases_all_branches(hq, hkv, d, nb, shared, blens):
     st = dags.decode_state(500 + hq + nb, n_seqs=2, n_branches=nb, shared_len=shared, branch_len=0,
