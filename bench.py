@@ -203,8 +203,8 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE give the scale of those counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (one-GPU boxes; the path shards without "
-              "exchange inside attention, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path shards by sequence or KV head without any "
+              "exchange inside attention, so N GPUs run N copies of this job); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
