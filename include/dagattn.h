@@ -19,7 +19,12 @@
  *   - Tensors are token-major packed variable-length: q [T][Hq][D], k/v [T][Hkv][D], contiguous,
  *     16-byte aligned.  Sequences are concatenated; tokens of a sequence are stored node after
  *     node in node-id order and node ids must be a topological order of the DAG.
- *   - No global state; calls on different streams may overlap if their buffers do not.
+ *   - Process-wide state: none that a result depends on.  What the library keeps per device until
+ *     the process ends is (a) a second stream with two events, created at the first
+ *     dag_attn_decode call with wide sibling groups (see there), (b) attributes set once on its
+ *     own kernels, and (c) the development knobs of the decode split sizes, read from the
+ *     environment once.  Calls on different streams may overlap if their buffers do not; the
+ *     decode calls that use the second stream serialise their enqueue phase on a mutex.
  */
 #ifndef DAGATTN_H
 #define DAGATTN_H
@@ -213,9 +218,12 @@ typedef struct {
   const int32_t* branch_pos;       /* [n_live] adaptive position of the token being decoded    */
 } dag_decode_desc_t;
 
-/* Section 3.2 ("maps the corresponding memory blocks to k"): store the new token of every live
- * branch -- key rotated at branch_pos (Eq. 2's P(i)), value as is -- into slot branch_len-1 of
- * the branch's own page list.  k_new/v_new [n_live][hkv][head_dim] bf16 DEVICE. */
+/* Section 3.2 (a fired transition's new KV blocks are added to the cache references its token
+ * carries): store the new token of every live branch -- key rotated at branch_pos (Eq. 2's P(i)),
+ * value as is -- into slot branch_len-1 of the branch's own page list.  k_new/v_new
+ * [n_live][hkv][head_dim] bf16 DEVICE; head_dim 64 or 128 (DAG_ERR_UNSUPPORTED otherwise).
+ * Slots of a page that no token has been stored in yet may hold anything, non-finite bit patterns
+ * included: the decode kernels never let them reach a result. */
 int dag_kv_append_rope(const dag_decode_desc_t* desc, const void* k_new, const void* v_new,
                        void* k_pool, void* v_pool, int32_t hkv, int32_t head_dim, float theta,
                        void* stream);
@@ -299,7 +307,8 @@ int dag_attn_decode_segments(const dag_decode_seg_desc_t* desc, const void* q, c
  * dag_attn_decode_segments take.  The caller uploads them and runs the model between steps.
  *
  * dag_sched_create: nodes in topological order (parents[parent_off[v] .. parent_off[v+1]) < v,
- * else DAG_ERR_NOT_TOPOLOGICAL); node_len[v] >= 1 tokens to produce for node v; chunk[v] >= 1
+ * else DAG_ERR_NOT_TOPOLOGICAL; DAG_ERR_POS_OVERFLOW when an adaptive position would not fit an
+ * int32 -- positions depend on the plan only, so this is the one place where that is reported); node_len[v] >= 1 tokens to produce for node v; chunk[v] >= 1
  * tokens per step (NULL: 1 everywhere = token-by-token generation; more for a node whose text is
  * given, e.g. the prompt or a step header, which is then prefilled in pieces); n_pages pages of
  * page_size (16) tokens in the pool, handed out in ascending order.  All arrays HOST, copied.
@@ -317,7 +326,8 @@ void dag_sched_destroy(dag_sched_t* sched);
  * dag_attn_decode_segments (seg_* / branch_entr* arrays and the four host bounds; segment i holds
  * node seg_node[i]).  All pointers are HOST memory owned by the scheduler, valid until the next
  * call on it; the caller copies them to the device.  DAG_ERR_WORKSPACE when the pool has too few
- * free pages for the step (nothing is changed then). */
+ * free pages for the step: no page is handed out and no token is counted then (the marking may
+ * already have advanced to the step's frontier, which a repeated call finds unchanged). */
 typedef struct {
   int32_t n_live, layer;          /* layer: index k of the frontier F_k the step belongs to         */
   int32_t n_segments, max_seg_pages, max_readers, total_readers;

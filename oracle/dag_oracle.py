@@ -175,6 +175,25 @@ def block_map_csr_full_first(bmap):
     return row_ptr, np.array(col, dtype=np.int64), np.array(flag, dtype=np.uint8), nfull
 
 
+def launch_tables(bmaps, seq_tokens, tile_n):
+    """How the library starts its prefill work, written out from its stated rules (no passage of
+    the paper; the block map and everything derived from it is the library's own device).  For a
+    batch of dense block maps (one per sequence, query tiles numbered sequence after sequence):
+      order     -- every query tile of the batch, most non-skip key tiles first, ties by index;
+      mask_free -- per query tile, how many of its FULL tiles need no mask at all: a FULL tile
+                   whose keys run past the end of the sequence (ragged last key tile) still needs
+                   the length limit and does not count.
+    Returns (order, mask_free) as int64 arrays."""
+    counts, mask_free = [], []
+    for bmap, T in zip(bmaps, seq_tokens):
+        for a in range(bmap.shape[0]):
+            counts.append(sum(1 for b in range(bmap.shape[1]) if bmap[a, b] != SKIP))
+            mask_free.append(sum(1 for b in range(bmap.shape[1])
+                                 if bmap[a, b] == FULL and (b + 1) * tile_n <= int(T)))
+    order = sorted(range(len(counts)), key=lambda i: (-counts[i], i))
+    return np.array(order, dtype=np.int64), np.array(mask_free, dtype=np.int64)
+
+
 # ----------------------------------------------------------------------------- rotary embedding
 def rope(x, pos, theta):
     """Rotate x[T][H][D] (any float dtype, upcast to fp64) by angle pos[t] * theta^(-2m/D).

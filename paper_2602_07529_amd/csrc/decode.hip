@@ -188,22 +188,53 @@ __device__ __forceinline__ void block_pv(const bf16x8 (&v0)[D / 32], const bf16x
   }
 }
 
+// Value operands of a block that reaches past the `vlen` tokens its page list holds: the slots
+// behind the last token (and the page that a slice with an odd page count reads twice) may hold
+// anything, NaN or infinity bit patterns included, and a zero probability does not neutralise
+// those in the product, so their elements are cleared.  v0 / v1 hold keys 8 H .. 8 H + 7 of the
+// block's first / second page.
+template <int D>
+__device__ __forceinline__ void clear_unused_values(bf16x8 (&v0)[D / 32], bf16x8 (&v1)[D / 32], int key0, int vlen,
+                                                    int H) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const bool ok0 = key0 + 8 * H + e < vlen, ok1 = key0 + 16 + 8 * H + e < vlen;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+      if (!ok0) v0[db][e] = (__bf16)0.f;
+      if (!ok1) v1[db][e] = (__bf16)0.f;
+    }
+  }
+}
+
+// vlen: tokens the page list holds (wave-uniform); len <= vlen: the smallest of the rows' limits.
 template <int D, typename QF>
 __device__ __forceinline__ void compute_block(const KVBlock<D>& blk, QF&& qop, f32x16* O, float& m, float& l,
-                                              float sc, float th, int key0, int len, int lim, int H) {
+                                              float sc, float th, int key0, int len, int lim, int vlen, int H) {
   bf16x8 pb0, pb1;
   block_scores<D>(blk.k, qop, O, m, l, sc, th, key0, len, lim, H, pb0, pb1);
-  block_pv<D>(blk.v[0], blk.v[1], pb0, pb1, O);
+  if (key0 + 32 > vlen) {
+    bf16x8 v0[D / 32], v1[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+      v0[db] = blk.v[0][db];
+      v1[db] = blk.v[1][db];
+    }
+    clear_unused_values<D>(v0, v1, key0, vlen, H);
+    block_pv<D>(v0, v1, pb0, pb1, O);
+  } else {
+    block_pv<D>(blk.v[0], blk.v[1], pb0, pb1, O);
+  }
 }
 
 // The loop of a single-wave work item: pages [p0, p1) of one page list, 32 keys (two pages) per
 // step, the next block's loads in flight while the current one is computed.  `lim` is the number
 // of leading tokens of the list that this lane's row sees (keys at or past it are masked), `len`
-// the smallest `lim` of the wave.  Leaves the un-normalised partial
+// the smallest `lim` of the wave, `vlen` the number of tokens the list holds.  Leaves the un-normalised partial
 // (O, reference maximum m, row sum l of this lane's half) in registers.
 template <int D, typename A, typename QF>
 __device__ __forceinline__ void stream_slice(const A& a, const int32_t* pages, int p0, int p1, int len, int lim,
-                                             int hk, int lane, QF&& qop, f32x16* O, float& m, float& l) {
+                                             int vlen, int hk, int lane, QF&& qop, f32x16* O, float& m, float& l) {
   const int L = lane & 31, H = lane >> 5;
   const int kr = key_of_row(L);
   const int kpage_sel = kr >> 4, kslot = kr & 15;
@@ -230,7 +261,7 @@ __device__ __forceinline__ void stream_slice(const A& a, const int32_t* pages, i
       }
       load_block<D>(b1, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
     }
-    compute_block<D>(b0, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, lim, H);
+    compute_block<D>(b0, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, lim, vlen, H);
     pb += 2;
     if (pb >= np) break;
     if (pb + 2 < np) {
@@ -240,7 +271,7 @@ __device__ __forceinline__ void stream_slice(const A& a, const int32_t* pages, i
       }
       load_block<D>(b0, a, pgv, pb + 2, np - 1, hk, L, H, kpage_sel, kslot);
     }
-    compute_block<D>(b1, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, lim, H);
+    compute_block<D>(b1, qop, O, m, l, a.sc, a.th, (p0 + pb) * PAGE, len, lim, vlen, H);
     pb += 2;
     if (pb >= np) break;
   }
@@ -310,7 +341,7 @@ __global__ void __launch_bounds__(64, 2) k_decode(DecodeArgs a) {
   auto qop = [&](int s) { return qf[s * 64]; };
   f32x16 O[D / 32];
   float m, l;
-  stream_slice<D>(a, pages, p0, p1, len, len, hk, lane, qop, O, m, l);
+  stream_slice<D>(a, pages, p0, p1, len, len, len, hk, lane, qop, O, m, l);
 
   const float l_tot = l + __shfl_xor(l, 32);
   if (row_ok) {
@@ -432,7 +463,7 @@ __global__ void __launch_bounds__(64, 2) k_decode_seg(SegArgs a) {
   auto qop = [&](int t) { return qf[t * 64]; };
   f32x16 O[D / 32];
   float m, l;
-  stream_slice<D>(a, a.seg_pages + it.page_off, p0, p1, lim_min, lim, hk, lane, qop, O, m, l);
+  stream_slice<D>(a, a.seg_pages + it.page_off, p0, p1, lim_min, lim, len, hk, lane, qop, O, m, l);
 
   const float l_tot = l + __shfl_xor(l, 32);
   if (store_ok) {
@@ -664,6 +695,7 @@ __global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeAr
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) asm volatile("" : "+v"(v0[db]), "+v"(v1[db]));
+    if ((p0 + 2 * b) * PAGE + 32 > len) clear_unused_values<D>(v0, v1, (p0 + 2 * b) * PAGE, len, H);
     block_pv<D>(v0, v1, pb0, pb1, O);
   }
 
@@ -738,7 +770,7 @@ __global__ void __launch_bounds__(256) k_kv_append(const int32_t* branch_page_of
                                                    const int32_t* branch_len, const int32_t* branch_pos,
                                                    const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
                                                    uint16_t* v_pool, int hkv, int D, float theta) {
-  __shared__ float s_cos[64], s_sin[64];  // D / 2 <= 64
+  __shared__ float s_cos[64], s_sin[64];  // D / 2 <= 64 (the entry point admits head_dim 64 and 128 only)
   const int r = blockIdx.x;
   const int idx = branch_len[r] - 1;
   if (idx < 0) return;
@@ -773,11 +805,21 @@ struct DecodePlan {
   size_t off_o_a, off_ml_a, off_o_b, off_ml_b, bytes;
 };
 
-int env_int(const char* name, int dflt) {
+// Development knobs (pages per decode work item), read from the environment once per process;
+// 0 = not set, the split sizes then follow the shape of the batch.
+struct DecodeKnobs {
+  int chunk_a, chunk_b, chunk_seg;
+};
+int env_int(const char* name) {
   const char* s = getenv(name);
-  if (!s || !*s) return dflt;
+  if (!s || !*s) return 0;
   const int v = atoi(s);
-  return v > 0 ? v : dflt;
+  return v > 0 ? v : 0;
+}
+const DecodeKnobs& decode_knobs() {
+  static const DecodeKnobs k = {env_int("DAGATTN_DECODE_CHUNK_A"), env_int("DAGATTN_DECODE_CHUNK_B"),
+                                env_int("DAGATTN_DECODE_CHUNK_SEG")};
+  return k;
 }
 
 // Split sizes: slices as long as the batch allows (every work item pays a start-up latency and
@@ -795,17 +837,18 @@ int make_plan(const dag_decode_desc_t* d, int hq, int hkv, int D, DecodePlan* p)
   if (p->rb_max < 1) p->rb_max = 1;
   const int64_t base_a = (int64_t)d->n_groups * hkv * p->rb_max;
   const int64_t base_b = (int64_t)d->n_live * hkv;
-  int ca = env_int("DAGATTN_DECODE_CHUNK_A", 128), cb = env_int("DAGATTN_DECODE_CHUNK_B", 64);
+  const DecodeKnobs& knobs = decode_knobs();
+  int ca = knobs.chunk_a ? knobs.chunk_a : 128, cb = knobs.chunk_b ? knobs.chunk_b : 64;
   ca += ca & 1;
   cb += cb & 1;
   p->wide = p->rb_max >= 2 && p->rb_max <= WIDE_MAX_WAVES;
-  if (!getenv("DAGATTN_DECODE_CHUNK_A")) {
+  if (!knobs.chunk_a) {
     if (p->wide)  // about one workgroup per compute unit
       while (ca > 8 && (int64_t)d->n_groups * hkv * dag_ceil_div(d->max_shared_pages, ca) < 256) ca /= 2;
     else
       while (ca > 8 && base_a * dag_ceil_div(d->max_shared_pages, ca) < 512) ca /= 2;
   }
-  if (!getenv("DAGATTN_DECODE_CHUNK_B"))
+  if (!knobs.chunk_b)
     while (cb > 4 && base_b * dag_ceil_div(d->max_branch_pages, cb) < 1024) cb /= 2;
   p->chunk_a = ca;
   p->chunk_b = cb;
@@ -831,20 +874,31 @@ struct SideStream {
   hipStream_t stream;
   hipEvent_t fork, join;
 };
-SideStream* side_stream() {
+// One mutex for the table and for the enqueue phase of every call that uses a side stream: the
+// fork event, the launches and the join event of a call must not interleave with another
+// thread's, or one call's own-page items could be ordered behind the other call's event.
+std::mutex& side_mutex() {
+  static std::mutex mu;
+  return mu;
+}
+SideStream* side_stream_locked() {  // the caller holds side_mutex()
   constexpr int MAX_DEV = 64;
   static SideStream table[MAX_DEV];
   static bool ready[MAX_DEV];
-  static std::mutex mu;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
-  std::lock_guard<std::mutex> lock(mu);
   if (!ready[dev]) {
     SideStream t;
     if (hipStreamCreateWithFlags(&t.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-    if (hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&t.join, hipEventDisableTiming) != hipSuccess)
+    if (hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) != hipSuccess) {
+      (void)hipStreamDestroy(t.stream);
       return nullptr;
+    }
+    if (hipEventCreateWithFlags(&t.join, hipEventDisableTiming) != hipSuccess) {
+      (void)hipEventDestroy(t.fork);
+      (void)hipStreamDestroy(t.stream);
+      return nullptr;
+    }
     table[dev] = t;
     ready[dev] = true;
   }
@@ -865,7 +919,7 @@ extern "C" int dag_kv_append_rope(const dag_decode_desc_t* d, const void* k_new,
   if (!d) return DAG_ERR_NULL;
   if (d->n_live < 0) return DAG_ERR_BAD_LEN;
   if (d->page_size != PAGE) return DAG_ERR_UNSUPPORTED;
-  if (hkv < 1 || head_dim < 16 || head_dim % 16 != 0 || head_dim > 256 || !(theta > 0.f)) return DAG_ERR_UNSUPPORTED;
+  if (hkv < 1 || (head_dim != 64 && head_dim != 128) || !(theta > 0.f)) return DAG_ERR_UNSUPPORTED;
   if (d->n_live == 0) return DAG_OK;
   if (!k_new || !v_new || !k_pool || !v_pool || !d->branch_page_off || !d->branch_pages || !d->branch_len ||
       !d->branch_pos)
@@ -930,6 +984,7 @@ extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const 
   a.item_base = 0;
   unsigned items = (unsigned)(p.items_a + p.items_b);
   SideStream* side = nullptr;
+  std::unique_lock<std::mutex> side_lock(side_mutex(), std::defer_lock);
   if (p.wide && p.items_a > 0) {
     // Wide sibling groups: the shared items as workgroups of rb_max waves that stream the shared
     // pages once.  The own items (single waves, next launch) fit beside them on the compute
@@ -938,7 +993,8 @@ extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const 
     const unsigned groups = (unsigned)(d->n_groups * hkv * p.splits_a);
     const unsigned threads = 64u * (unsigned)p.rb_max;
     if (p.items_b > 0) {
-      side = side_stream();
+      side_lock.lock();  // held until the join has been enqueued
+      side = side_stream_locked();
       if (!side) return DAG_ERR_HIP;
       DAG_HIP_CHECK(hipEventRecord(side->fork, stream));
       DAG_HIP_CHECK(hipStreamWaitEvent(side->stream, side->fork, 0));
@@ -994,10 +1050,11 @@ int make_seg_plan(const dag_decode_seg_desc_t* d, int hq, int hkv, int D, SegPla
   const int G = hq / hkv;
   p->rb_max = (int)dag_ceil_div((int64_t)d->max_readers * G, 32);
   if (p->rb_max < 1) p->rb_max = 1;
-  int c = env_int("DAGATTN_DECODE_CHUNK_SEG", 128);
+  const int knob = decode_knobs().chunk_seg;
+  int c = knob ? knob : 128;
   c += c & 1;
   const int64_t base = (int64_t)d->n_segments * hkv * p->rb_max;
-  if (!getenv("DAGATTN_DECODE_CHUNK_SEG"))
+  if (!knob)
     while (c > 8 && base * dag_ceil_div(d->max_seg_pages, c) < 1024) c /= 2;
   p->chunk = c;
   p->splits = d->max_seg_pages > 0 ? (int)dag_ceil_div(d->max_seg_pages, c) : 0;

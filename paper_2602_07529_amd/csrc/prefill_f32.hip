@@ -100,12 +100,8 @@ int launch_prefill_f32(const PrefillArgs& a, int head_dim, hipStream_t stream) {
     hipLaunchKernelGGL(k_prefill_f32<64>, dim3(grid), dim3(256), sm, stream, a);
   } else {
     const size_t sm = (size_t)2 * TN * 128 * 4 + TN * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-      if (hipFuncSetAttribute((const void*)k_prefill_f32<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm) != hipSuccess)
-        return DAG_ERR_HIP;
-      attr_set = true;
-    }
+    if (hipFuncSetAttribute((const void*)k_prefill_f32<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm) != hipSuccess)
+      return DAG_ERR_HIP;
     hipLaunchKernelGGL(k_prefill_f32<128>, dim3(grid), dim3(256), sm, stream, a);
   }
   DAG_LAUNCH_CHECK();

@@ -74,7 +74,20 @@ extern "C" int dag_sched_create(int32_t n_nodes, const int32_t* parent_off, cons
   for (int i = 0; i < n_pages; ++i) s->free_pages[i] = n_pages - 1 - i;  // handed out in ascending order
   s->pages.resize(n_nodes);
   s->done.assign(n_nodes, 0);
+  // adaptive positions (section 4.2): one past the largest position of any predecessor, 0 without
+  // one; the parents suffice because positions grow along every edge.  They depend on the plan
+  // only, so they are fixed (and checked against the int32 range) here, not while stepping.
   s->pos_start.assign(n_nodes, 0);
+  for (int v = 0; v < n_nodes; ++v) {
+    int64_t start = 0;
+    for (int e = parent_off[v]; e < parent_off[v + 1]; ++e)
+      start = std::max<int64_t>(start, (int64_t)s->pos_start[parents[e]] + node_len[parents[e]]);
+    if (start + node_len[v] > INT32_MAX) {
+      delete s;
+      return DAG_ERR_POS_OVERFLOW;
+    }
+    s->pos_start[v] = (int32_t)start;
+  }
   s->marked.assign(n_nodes, 0);
   s->seg_of_node.assign(n_nodes, -1);
   } catch (...) {
@@ -109,17 +122,7 @@ static int sched_step(dag_sched_t* s, dag_sched_step_t* out) {
       if (s->marked[v]) continue;  // output place already holds a token
       bool enabled = true;
       for (int e = s->parent_off[v]; e < s->parent_off[v + 1]; ++e) enabled = enabled && s->marked[s->parents[e]];
-      if (!enabled) continue;
-      // adaptive position: one past the largest position of any predecessor (0 without one);
-      // the parents suffice because positions grow along every edge
-      int64_t start = 0;
-      for (int e = s->parent_off[v]; e < s->parent_off[v + 1]; ++e) {
-        const int p = s->parents[e];
-        start = std::max<int64_t>(start, (int64_t)s->pos_start[p] + s->len[p]);
-      }
-      if (start + s->len[v] > INT32_MAX) return DAG_ERR_POS_OVERFLOW;
-      s->pos_start[v] = (int32_t)start;
-      s->frontier.push_back(v);
+      if (enabled) s->frontier.push_back(v);
     }
     if (!s->frontier.empty()) s->layer++;
   }

@@ -35,6 +35,7 @@ def oracle_meta(dag_list, tm, tn):
         tok_start, pos_start = orc.node_tables(L, anc)
         tn_, pos = orc.token_meta(L, anc)
         bm = orc.block_map(L, anc, tm, tn)
+        out.setdefault("bmaps", []).append(bm)
         rp, col, flag, nfull = orc.block_map_csr_full_first(bm)
         out.setdefault("nfull", []).append(nfull)
         out["cu_seqlens"].append(out["cu_seqlens"][-1] + len(tn_))
@@ -65,10 +66,11 @@ def oracle_meta(dag_list, tm, tn):
         qtile_nfull=cat(out.get("nfull", []), np.int64),
         useful_pairs=np.array(out["useful_pairs"], dtype=np.int64))
     cnt = np.array(out["cnt"], dtype=np.int64)
-    # launch order: all query tiles by descending tile count, ties by ascending index
+    # launch order and mask-free counts: the oracle's statement of the library's rules
     seq_of = np.repeat(np.arange(len(dag_list)), np.diff(res["qtile_start"]))
-    order = sorted(range(len(cnt)), key=lambda i: (-cnt[i], i))
-    res["qtile_order"] = np.array(order, dtype=np.int64)
+    seq_T = np.diff(res["cu_seqlens"])
+    order, mask_free = orc.launch_tables(out["bmaps"], seq_T, tn)
+    res["qtile_order"] = order
     # launch descriptors: {token offset, tokens, first row, CSR start, tiles, mask-free tiles, node offset, tile id}
     node_start = np.concatenate([[0], np.cumsum([len(L) for L, _ in dag_list])])
     ktiles = [-(-int(np.sum(L)) // tn) for L, _ in dag_list]
@@ -76,13 +78,8 @@ def oracle_meta(dag_list, tm, tn):
     desc = np.zeros((len(cnt), 8), dtype=np.int64)
     for oi, qt in enumerate(order):
         b = int(seq_of[qt])
-        T = int(res["cu_seqlens"][b + 1] - res["cu_seqlens"][b])
-        c0 = int(res["qtile_rowptr"][qt])
-        nf = int(res["qtile_nfull"][qt])
-        if nf > 0 and (int(res["qtile_col"][c0 + nf - 1]) + 1) * tn > T:
-            nf -= 1
-        desc[oi] = [res["cu_seqlens"][b], T, (qt - res["qtile_start"][b]) * tm, c0, cnt[qt], nf, node_start[b],
-                    res["ktile_start"][b]]
+        desc[oi] = [res["cu_seqlens"][b], seq_T[b], (qt - res["qtile_start"][b]) * tm, res["qtile_rowptr"][qt],
+                    cnt[qt], mask_free[qt], node_start[b], res["ktile_start"][b]]
     res["qtile_desc"] = desc.reshape(-1)
     return res
 

@@ -186,6 +186,9 @@ def test_decode_argument_errors():
     assert L.dag_decode_workspace_bytes(C.byref(bad_page), 32, 8, 128) == 0
     assert L.dag_kv_append_rope(C.byref(bad_page), p, p, p, p, 8, 128, 1e4, None) == -7
     assert L.dag_kv_append_rope(C.byref(dd), None, p, p, p, 8, 128, 1e4, None) == -1
+    # head dimensions other than 64 and 128 are refused (the kernel's angle tables hold 64 pairs)
+    for bad_d in (16, 96, 144, 192, 256):
+        assert L.dag_kv_append_rope(C.byref(dd), p, p, p, p, 8, bad_d, 1e4, None) == -7
     empty = B.dag_decode_desc_t(0, 0, 16, 0, 0, 0, *([0] * 8))
     assert L.dag_attn_decode(C.byref(empty), p, p, p, p, 32, 8, 128, 0.1, None, 0, None) == 0
     assert L.dag_kv_append_rope(C.byref(empty), p, p, p, p, 8, 128, 1e4, None) == 0
@@ -313,6 +316,9 @@ def test_scheduler_argument_errors_and_page_exhaustion():
     assert L.dag_sched_create(2, off, bad_par, ln, None, 8, 16, C.byref(h)) == -3
     bad_len = (C.c_int32 * 2)(20, 0)
     assert L.dag_sched_create(2, off, par, bad_len, None, 8, 16, C.byref(h)) == -2
+    # a chain whose positions leave the int32 range is refused when the plan is created
+    big = (C.c_int32 * 2)(2 ** 31 - 8, 16)
+    assert L.dag_sched_create(2, off, par, big, None, 8, 16, C.byref(h)) == -5 and not h.value
     assert L.dag_sched_create(2, off, par, ln, None, 2, 16, C.byref(h)) == 0      # 3 pages needed, 2 in the pool
     st = B.dag_sched_step_t()
     rcs = []

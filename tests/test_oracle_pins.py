@@ -180,6 +180,68 @@ def test_block_map_consistent_with_mask_on_ragged_random_dag():
         assert bm.shape == (-(-T // tm), -(-T // tn))
 
 
+def test_full_first_csr_and_launch_tables_golden():
+    """The FULL-first row order, the FULL counts, the launch order and the mask-free counts against
+    values enumerated by hand (the diamond, and a DAG whose row of D lists a PARTIAL tile in front
+    of a FULL one, so that the two row orders differ)."""
+    for name in ("diamond", "partial_before_full"):
+        g = GOLDEN[name]
+        L, anc = _dag_from_parents(g["node_len"], g["parents"])
+        tok_node, pos = orc.token_meta(L, anc)
+        assert tok_node.tolist() == g["tok_node"] and pos.tolist() == g["pos_ids"]
+        m = orc.explicit_mask(L, anc)
+        assert [np.nonzero(r)[0].tolist() for r in m] == g["allowed"]
+        assert orc.useful_pairs(L, anc) == g["useful_pairs"]
+        bm = orc.block_map(L, anc, *g["tile"])
+        assert bm.tolist() == g["block_map"]
+        want = g["csr_full_first"]
+        rp, col, flag, nfull = orc.block_map_csr_full_first(bm)
+        assert rp.tolist() == want["rowptr"] and col.tolist() == want["col"]
+        assert flag.tolist() == want["flag"] and nfull.tolist() == want["nfull"]
+        order, mask_free = orc.launch_tables([bm], [int(np.sum(L))], g["tile"][1])
+        assert order.tolist() == want["launch_order"] and mask_free.tolist() == want["mask_free"]
+    asc = GOLDEN["partial_before_full"]["csr_ascending"]
+    L, anc = _dag_from_parents(GOLDEN["partial_before_full"]["node_len"], GOLDEN["partial_before_full"]["parents"])
+    rp, col, flag = orc.block_map_csr(orc.block_map(L, anc, 2, 2))
+    assert rp.tolist() == asc["rowptr"] and col.tolist() == asc["col"] and flag.tolist() == asc["flag"]
+
+
+def test_full_first_csr_properties_on_ragged_random_dags():
+    """Same multiset per row as the ascending CSR, FULL before PARTIAL, each group ascending, flags
+    equal to the dense map; launch order = a permutation sorted by tile count; mask-free counts by
+    brute force over the explicit mask (a tile counts iff all tile_m x tile_n pairs exist and are
+    visible)."""
+    rng = np.random.Generator(np.random.PCG64(17))
+    for tm, tn in [(4, 8), (8, 4), (5, 3), (6, 6)]:
+        dag_list = [dags.random_dag(rng, n_nodes=14, depth=4, len_lo=1, len_hi=11)[:2] for _ in range(3)]
+        bmaps, Ts, all_counts, brute_free = [], [], [], []
+        for L, anc in dag_list:
+            bm = orc.block_map(L, anc, tm, tn)
+            m = orc.explicit_mask(L, anc)
+            T = m.shape[0]
+            rp, col, flag = orc.block_map_csr(bm)
+            rp2, col2, flag2, nfull = orc.block_map_csr_full_first(bm)
+            assert rp.tolist() == rp2.tolist()
+            for a in range(bm.shape[0]):
+                c, f = col2[rp2[a]:rp2[a + 1]], flag2[rp2[a]:rp2[a + 1]]
+                assert sorted(c.tolist()) == col[rp[a]:rp[a + 1]].tolist()
+                nf = int(nfull[a])
+                assert (f[:nf] == orc.FULL).all() and (f[nf:] == orc.PARTIAL).all()
+                assert (np.diff(c[:nf]) > 0).all() and (np.diff(c[nf:]) > 0).all()
+                assert all(bm[a, b] == x for b, x in zip(c, f))
+                all_counts.append(len(c))
+                rows = m[a * tm:(a + 1) * tm]
+                brute_free.append(sum(1 for b in range(bm.shape[1]) if (b + 1) * tn <= T and
+                                      rows[:, b * tn:(b + 1) * tn].all()))
+            bmaps.append(bm)
+            Ts.append(T)
+        order, mask_free = orc.launch_tables(bmaps, Ts, tn)
+        assert sorted(order.tolist()) == list(range(len(all_counts)))
+        keys = [(-all_counts[i], i) for i in order]
+        assert keys == sorted(keys)
+        assert mask_free.tolist() == brute_free
+
+
 # ------------------------------------------------------------------ rotary embedding
 def test_rope_closed_forms():
     # D = 2: one pair, frequency 1: (1, 0) at position p -> (cos p, sin p); (0, 1) -> (-sin p, cos p)
