@@ -8,6 +8,10 @@ One step = one pass of the whole hot path over one batch of seeded synthetic inp
       dag_kv_append_rope -> dag_attn_decode (shared-prefix items + own items + LSE merge)
 Inputs are resident in HBM before the timed region.  `value` is the prefill segment's useful
 TFLOP/s (4*D*Hq*visible pairs / segment time); the decode segment is reported in "decode".
+Beside the timed region, each with a roofline object of its own: the largest configuration
+(benchmark config 5: prefill of 2 x 50,176 tokens with 40 query heads, and its 64-branch decode
+over a 32,768-token prefix), the random multi-level DAGs of config 4, the segment form of the
+decode step and the backward of the prefill attention.
 Prints ONE JSON line on stdout.
 """
 import argparse
@@ -28,14 +32,70 @@ from workloads import dags  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
-# what the same counters read for a plain 256 MiB copy (profiles/k_prefill_bf16__*.txt and
-# profiles/k_decode__*.txt hold the commands and the raw readings); measured, not computed here.
-TRAFFIC_PREFILL_KERNEL = (1237150 + 147528) * 1024      # k_prefill_bf16, read + written
-TRAFFIC_DECODE_KERNELS = (1053639 + 10400 + 11819 + 1024) * 1024   # k_decode + k_decode_merge
-# (profiles/k_decode_seg__*.txt and profiles/k_bwd__*.txt)
-TRAFFIC_SEG_DECODE_KERNELS = (8 + 8 + 1058683 + 8322 + 9290 + 1024) * 1024   # k_seg_plan + k_decode_seg + k_decode_seg_merge
-TRAFFIC_BWD_KERNELS = (294941 + 2304 + 769233 + 165872 + 2536551 + 73728 + 256 + 156) * 1024   # delta, dq, dkv, the three small ones
+# HBM bytes per launch come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file (one
+# counter per run), scaled by what the same counter reads for a plain 256 MiB copy.  They are
+# measured, not computed here: `python bench.py --write-traffic <fetch csv> <write csv>` turns the
+# two counter files into profiles/traffic.json, which a normal run reads (kernels that are not in
+# the file report null).
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
+CALIBRATION_KIB = 256 * 1024
+
+
+def write_traffic(workload, fetch_csv, write_csv, out_path=TRAFFIC_JSON):
+    """Per kernel of one workload (a `--only` choice): mean FETCH_SIZE / WRITE_SIZE per dispatch,
+    scaled so that the calibration copy (--copy-calibration: one 256 MiB device copy) reads and
+    writes exactly its size.  Other workloads' entries in the file are kept."""
+    import csv
+    import collections
+    import re
+
+    def per_kernel(path):
+        agg = collections.defaultdict(list)
+        for r in csv.DictReader(open(path)):
+            agg[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+        return agg
+
+    def short(name):   # "void (anonymous namespace)::k_decode<128>(DecodeArgs)" -> "k_decode<128>"
+        m = re.search(r"(k_[A-Za-z0-9_]+(<[^>]*>)?)", name)
+        return m.group(1).replace(" ", "") if m else None
+
+    try:
+        out = json.load(open(out_path))
+    except Exception:
+        out = {}
+    out["_about"] = ("HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of "
+                     "`bench.py --only WORKLOAD --steps 3 --warmup 1 --copy-calibration --no-cpu-baseline`, "
+                     "written by bench.py --write-traffic; scale = 256 MiB / what the counter reads for a "
+                     "plain 256 MiB copy")
+    entry = out.setdefault("workloads", {})[workload] = {"kernels": {}}
+    for key, path in (("fetch", fetch_csv), ("write", write_csv)):
+        agg = per_kernel(path)
+        # the calibration copy is the largest dispatch of a copy / elementwise kernel
+        cal = max((max(v) for k, v in agg.items() if short(k) is None and
+                   ("copy" in k.lower() or "elementwise" in k.lower())), default=None)
+        scale = CALIBRATION_KIB / cal if cal else None
+        entry[key + "_scale"] = scale
+        for k, v in agg.items():
+            name = short(k)
+            if name is None or scale is None:
+                continue
+            v = v[len(v) // 2:]   # the later dispatches: steady state
+            d = entry["kernels"].setdefault(name, {})
+            d[key + "_bytes"] = int(sum(v) / len(v) * scale * 1024)
+            d[key + "_dispatches"] = len(v)
+    with open(out_path, "w") as f:
+        json.dump(out, f, indent=1, sort_keys=True)
+    return out
+
+
+def traffic_of(workload, *kernels):
+    """Measured bytes per launch (read + written) of the named kernels of a workload, summed; None
+    when the summary file has no entry for one of them."""
+    try:
+        t = json.load(open(TRAFFIC_JSON))["workloads"][workload]["kernels"]
+        return int(sum(t[k]["fetch_bytes"] + t[k]["write_bytes"] for k in kernels))
+    except Exception:
+        return None
 
 
 def _ensure_built():
@@ -48,14 +108,22 @@ CLOCK_RAMP_STEPS = 40
 
 
 class PrefillWork:
-    def __init__(self, cfg, dev):
+    def __init__(self, cfg, dev, device_values=False):
+        """device_values: draw Q/K/V with torch's seeded generator on the GPU (same distribution,
+        N(0,1) x scale rounded to bf16) instead of numpy on the host; used for the large legs, whose
+        host generation alone would take longer than their timed work."""
         self.cfg = cfg
         self.dag_list = dags.config_dags(cfg)
         self.T = int(sum(int(np.sum(L)) for L, _ in self.dag_list))
         hq, hkv, d = cfg["hq"], cfg["hkv"], cfg["d"]
         dtype = torch.float32 if cfg["dtype"] == "f32" else torch.bfloat16
-        q, k, v = dags.make_qkv(cfg["seed"], self.T, hq, hkv, d, cfg["scale"], dtype)
-        self.q0, self.k0, self.v = q.to(dev), k.to(dev), v.to(dev)
+        if device_values:
+            gen = torch.Generator(device=dev).manual_seed(cfg["seed"])
+            draw = lambda h: (torch.randn(self.T, h, d, device=dev, generator=gen) * cfg["scale"]).to(dtype)
+            self.q0, self.k0, self.v = draw(hq), draw(hkv), draw(hkv)
+        else:
+            q, k, v = dags.make_qkv(cfg["seed"], self.T, hq, hkv, d, cfg["scale"], dtype)
+            self.q0, self.k0, self.v = q.to(dev), k.to(dev), v.to(dev)
         self.q, self.k = torch.empty_like(self.q0), torch.empty_like(self.k0)
         self.out = torch.empty_like(self.q0)
         code = B.DAG_F32 if dtype == torch.float32 else B.DAG_BF16
@@ -97,16 +165,17 @@ class PrefillWork:
 
 
 class DecodeWork:
-    def __init__(self, cfg, dev):
+    def __init__(self, cfg, dev, copies=2):
         self.cfg = cfg
         st = dags.decode_state(cfg["seed"], cfg["n_seqs"], cfg["n_branch"], cfg["shared"], cfg["branch"],
                                cfg["hq"], cfg["hkv"], cfg["d"])
         self.desc_np = st["desc"]
         self.dd = B.DecodeDesc(st["desc"], dev)
-        # two copies of the pools, used in turn, so that no step finds any of its 1 GiB of K/V in the
-        # 256 MB last-level cache from the step before
+        # several copies of the pools, used in turn, so that no step finds its K/V in the 256 MB
+        # last-level cache from the step before (two copies of 1 GiB for config 3; the 0.4 GiB of
+        # config 5 needs more turns)
         kp, vp = st["k_pool"].to(dev), st["v_pool"].to(dev)
-        self.pools = [(kp, vp), (kp.clone(), vp.clone())]
+        self.pools = [(kp, vp)] + [(kp.clone(), vp.clone()) for _ in range(copies - 1)]
         self.turn = 0
         self.q, self.k_new, self.v_new = st["q"].to(dev), st["k_new"].to(dev), st["v_new"].to(dev)
         self.out = torch.empty_like(self.q)
@@ -117,7 +186,7 @@ class DecodeWork:
 
     def run(self, ev=None):
         kp, vp = self.pools[self.turn]
-        self.turn ^= 1
+        self.turn = (self.turn + 1) % len(self.pools)
         if ev:
             ev[0].record()
         B.dag_kv_append_rope(self.dd, self.k_new, self.v_new, kp, vp, self.cfg["theta"])
@@ -192,16 +261,94 @@ def cpu_baseline(pw, n_seq=3):
                       % (n_seq - 1, cfg["batch"], rows, len(heads), cfg["hq"], dt)}
 
 
+def _events(n):
+    return [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
+
+
+def prefill_leg(cfg, dev, launches, warmup, workload_key):
+    """An extra prefill workload beside the timed region: the whole prefill path `launches` times,
+    the attention kernel bracketed by events of its own.  Returns the JSON object of the leg."""
+    pw = PrefillWork(cfg, dev, device_values=True)
+    pw.refresh_inputs()
+    for _ in range(warmup):
+        pw.run()
+    ev = _events(launches)
+    for e in ev:
+        pw.run(e)
+    torch.cuda.synchronize()
+    ms_path = float(np.mean([e[0].elapsed_time(e[2]) for e in ev]))
+    attn = [e[1].elapsed_time(e[2]) for e in ev]
+    ms_attn = float(np.mean(attn))
+    flops, pairs = pw.useful_flops()
+    tf = flops / (ms_attn * 1e-3) / 1e12
+    bmap = pw.meta.get("block_map")
+    census = {"full": int((bmap == B.TILE_FULL).sum().item()), "partial": int((bmap == B.TILE_PARTIAL).sum().item())}
+    g = cfg["hq"] // cfg["hkv"]
+    kern = "k_prefill_bf16<%d,%d,1>" % (cfg["d"], 4 if g >= 3 else g)
+    return {"metric": "dag_attn_prefill_useful_tflops", "value": flops / (ms_path * 1e-3) / 1e12, "unit": "TFLOP/s",
+            "launches": launches, "ms_prefill_path(meta+rope+attn)": ms_path, "ms_attn_kernel": ms_attn,
+            "min_ms_attn_kernel": float(np.min(attn)),
+            "config": {"workload": cfg["name"], "batch": cfg["batch"], "tokens": pw.T, "hq": cfg["hq"],
+                       "hkv": cfg["hkv"], "head_dim": cfg["d"], "useful_pairs": pairs, "tiles_64x64": census,
+                       "values": "torch generator on the device, seed %d" % cfg["seed"]},
+            "roofline": {"bound": "mfma", "kernel": kern, "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS,
+                         "traffic": traffic_of(workload_key, kern), "algorithmic_bytes": pw.algorithmic_bytes()}}
+
+
+def decode_leg(cfg, dev, steps, warmup, workload_key, kernels, copies):
+    """An extra decode workload beside the timed region: `steps` decode steps one after the other,
+    dag_attn_decode bracketed by events of its own."""
+    dw = DecodeWork(cfg, dev, copies=copies)
+    for _ in range(warmup):
+        dw.run()
+    ev = _events(steps)
+    for e in ev:
+        dw.run(e)
+    torch.cuda.synchronize()
+    ms_step = float(np.mean([e[0].elapsed_time(e[2]) for e in ev]))
+    att = [e[1].elapsed_time(e[2]) for e in ev]
+    ms_att = float(np.mean(att))
+    gbs = dw.bytes / (ms_att * 1e-3) / 1e9
+    return {"metric": "branch_decode_tok_per_s_one_attention_layer", "value": dw.n_live / (ms_step * 1e-3),
+            "unit": "tok/s", "ms_per_decode_step": ms_step, "ms_attn_kernels": ms_att,
+            "min_ms_attn_kernels": float(np.min(att)), "steps": steps,
+            "config": {"workload": cfg["name"], "n_seqs": cfg["n_seqs"], "live_branches": dw.n_live,
+                       "shared_prefix": cfg["shared"], "branch_len": cfg["branch"], "hq": cfg["hq"], "hkv": cfg["hkv"],
+                       "page_size": 16, "pool_copies_used_in_turn": copies},
+            "roofline": {"bound": "hbm", "kernel": "+".join(kernels), "achieved": gbs, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "algorithmic_bytes": dw.bytes,
+                         "traffic": traffic_of(workload_key, *kernels)}}
+
+
+def config5_decode_cfg():
+    """Decode state of benchmark config 5: 2 sequences x 32 live branches at own length 640 (the
+    middle of the 256 steps, 513..768) over the 32768-token prefix, 40 query / 8 KV heads."""
+    c = dags.config(4)
+    return dict(name="qwen32b_long_decode_bf16", seed=c["seed"] + 1000, n_seqs=c["batch"], n_branch=c["n_branch"],
+                shared=c["prefix"], branch=c["branch"] + c["decode_steps"] // 2, hq=c["hq"], hkv=c["hkv"], d=c["d"],
+                theta=c["theta"])
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", choices=["all", "main", "config4", "config5"], default="all",
+                    help="main = the timed region (configs 2 and 3) with the segment decode and the backward; "
+                         "config4 / config5 = only that leg (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (untimed): under rocprofv3 --pmc its "
                          "FETCH_SIZE / WRITE_SIZE give the scale of those counters")
+    ap.add_argument("--write-traffic", nargs=3, metavar=("WORKLOAD", "FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: turn two rocprofv3 counter files of a `--only WORKLOAD "
+                         "--copy-calibration` run into that workload's entry of profiles/traffic.json")
     args = ap.parse_args()
+    if args.write_traffic:
+        print(json.dumps(write_traffic(*args.write_traffic)["workloads"][args.write_traffic[0]], indent=1))
+        return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards by sequence or KV head without any "
               "exchange inside attention, so N GPUs run N copies of this job); run with --gpus 1", file=sys.stderr)
@@ -212,15 +359,31 @@ def main():
     _ensure_built()
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    pw = PrefillWork(dags.config(1), dev)
-    dw = DecodeWork(dags.config(2), dev)
-
     if args.copy_calibration:
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    extra = {}
+    if args.only in ("all", "config5"):
+        c5 = dags.config(4)
+        c5["name"] = "qwen32b_long_prefill_bf16"
+        n5 = max(1, min(args.steps, 4))
+        extra["config5_prefill"] = prefill_leg(c5, dev, n5, min(args.warmup, 2), "config5")
+        torch.cuda.empty_cache()
+        extra["config5_decode"] = decode_leg(config5_decode_cfg(), dev, args.steps, args.warmup + 20, "config5",
+                                             ("k_decode_wide<128>", "k_decode<128>", "k_decode_merge<128>"), copies=4)
+    if args.only in ("all", "config4"):
+        extra["config4_prefill"] = prefill_leg(dags.config(3), dev, max(1, min(args.steps, 20)),
+                                               min(args.warmup, 5) + 10, "config4")
+    if args.only in ("config4", "config5"):
+        print(json.dumps(extra))
+        return
+    torch.cuda.empty_cache()
+
+    pw = PrefillWork(dags.config(1), dev)
+    dw = DecodeWork(dags.config(2), dev)
     pw.refresh_inputs()
     # From a cold start the GPU needs some tens of milliseconds of load to reach its sustained
     # clocks (the first ~20 steps run about 12 % slower than all later ones), so a fixed number of
@@ -228,9 +391,8 @@ def main():
     for _ in range(CLOCK_RAMP_STEPS + args.warmup):
         pw.run()
         dw.run()
-    new_events = lambda: [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    pev = [new_events() for _ in range(args.steps)]
-    dev_ev = [new_events() for _ in range(args.steps)]
+    pev = _events(args.steps)
+    dev_ev = _events(args.steps)
 
     # exactly `steps` steps between two synchronisations; the host runs ahead of the GPU, so the
     # per-kernel event intervals below contain no launch gaps
@@ -289,7 +451,9 @@ def main():
     tflops_seg = flops / (ms_pre * 1e-3) / 1e12
     tflops_kernel = flops / (ms_attn * 1e-3) / 1e12
     dec_gbs = dw.bytes / (ms_deck * 1e-3) / 1e9
+    bwd_tf = 2.5 * flops / (ms_bwd * 1e-3) / 1e12
     cfg = pw.cfg
+    bwd_kernels = ("k_bwd_delta", "k_bwd_weights", "k_bwd_tokvis", "k_bwd_order", "k_bwd_dq<128,4>", "k_bwd_dkv<128>")
     res = {
         "metric": "dag_attn_prefill_useful_tflops",
         "value": tflops_seg,
@@ -305,34 +469,37 @@ def main():
         "segments_ms": {"prefill_path(meta+rope+attn)": ms_pre, "prefill_attn_kernel": ms_attn,
                         "decode_path(append+attn+merge)": ms_dec, "decode_attn_kernels": ms_deck,
                         "min_prefill_attn_kernel": float(np.min(attn_ms)), "min_decode_attn_kernels": float(np.min(deck_ms))},
-        "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16", "achieved": tflops_kernel,
+        "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16<128,4,1>", "achieved": tflops_kernel,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops_kernel / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": TRAFFIC_PREFILL_KERNEL, "algorithmic_bytes": pw.algorithmic_bytes()},
+                     "traffic": traffic_of("main", "k_prefill_bf16<128,4,1>"), "algorithmic_bytes": pw.algorithmic_bytes()},
         "decode": {"metric": "branch_decode_tok_per_s_one_attention_layer",
                    "value": dw.n_live / (ms_dec * 1e-3), "unit": "tok/s", "ms_per_decode_step": ms_dec,
                    "config": {"workload": dw.cfg["name"], "n_seqs": dw.cfg["n_seqs"], "live_branches": dw.n_live,
                               "shared_prefix": dw.cfg["shared"], "branch_len": dw.cfg["branch"], "page_size": 16},
-                   "roofline": {"bound": "hbm", "kernel": "k_decode(+k_decode_merge)", "achieved": dec_gbs,
+                   "roofline": {"bound": "hbm", "kernel": "k_decode<128>+k_decode_merge<128>", "achieved": dec_gbs,
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
-                                "algorithmic_bytes": dw.bytes, "traffic": TRAFFIC_DECODE_KERNELS}},
+                                "algorithmic_bytes": dw.bytes,
+                                "traffic": traffic_of("main", "k_decode<128>", "k_decode_merge<128>")}},
         "decode_segments": {"metric": "segment_decode_tok_per_s_one_attention_layer",
                             "value": sw.n_live / (ms_seg * 1e-3), "unit": "tok/s", "ms_per_decode_step": ms_seg,
                             "config": {"workload": "three_level_frontier_bf16", "n_seqs": 16, "segments": sw.n_segments,
                                        "live_branches": sw.n_live, "levels": "root 4096 | 2 x 2048 | 8 x 1000..1063",
                                        "page_size": 16},
-                            "roofline": {"bound": "hbm", "kernel": "k_seg_plan+k_decode_seg+k_decode_seg_merge",
+                            "roofline": {"bound": "hbm", "kernel": "k_seg_plan+k_decode_seg<128>+k_decode_seg_merge<128>",
                                          "achieved": seg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                          "frac": seg_gbs / HBM_PEAK_GBS, "algorithmic_bytes": sw.bytes,
-                                         "traffic": TRAFFIC_SEG_DECODE_KERNELS}},
-        "prefill_bwd": {"metric": "dag_attn_prefill_bwd_useful_tflops", "value": 2.5 * flops / (ms_bwd * 1e-3) / 1e12,
+                                         "traffic": traffic_of("main", "k_seg_plan", "k_decode_seg<128>",
+                                                               "k_decode_seg_merge<128>")}},
+        "prefill_bwd": {"metric": "dag_attn_prefill_bwd_useful_tflops", "value": bwd_tf,
                         "unit": "TFLOP/s", "ms_per_call": ms_bwd, "calls": n_bwd,
                         "useful_flops": "2.5 x forward (five products per visible pair)",
-                        "roofline": {"bound": "mfma", "kernel": "k_bwd_delta+k_bwd_transpose+k_bwd_dq+k_bwd_dkv",
-                                     "achieved": 2.5 * flops / (ms_bwd * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-                                     "unit": "TFLOP/s", "frac": 2.5 * flops / (ms_bwd * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                                     "traffic": TRAFFIC_BWD_KERNELS}},
+                        "roofline": {"bound": "mfma", "kernel": "+".join(bwd_kernels),
+                                     "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                     "unit": "TFLOP/s", "frac": bwd_tf / MFMA_BF16_PEAK_TFLOPS,
+                                     "traffic": traffic_of("main", *bwd_kernels)}},
         "wall_s_timed_loop": wall,
     }
+    res.update(extra)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(pw)
     print(json.dumps(res))

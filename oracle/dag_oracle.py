@@ -346,10 +346,11 @@ def gather_context(desc, r, h, k_pool, v_pool):
     return np.array(Ks), np.array(Vs)
 
 
-def attn_decode(desc, q, k_pool, v_pool, scale=None, branches=None):
+def attn_decode(desc, q, k_pool, v_pool, scale=None, branches=None, kv_heads=None):
     """One decode step: o = softmax(q . K^T * scale) V over each branch's context, fp64.
 
-    q [n_live][Hq][D] already rotated.  Returns O [n_live][Hq][D] (NaN for branches not asked).
+    q [n_live][Hq][D] already rotated.  Returns O [n_live][Hq][D] (NaN for the branches and the
+    query heads of the KV heads not asked for).
     """
     q = np.asarray(q, dtype=np.float64)
     n_live, Hq, D = q.shape
@@ -359,7 +360,7 @@ def attn_decode(desc, q, k_pool, v_pool, scale=None, branches=None):
         scale = 1.0 / np.sqrt(D)
     O = np.full((n_live, Hq, D), np.nan)
     for r in (range(n_live) if branches is None else branches):
-        for hk in range(Hkv):
+        for hk in (range(Hkv) if kv_heads is None else kv_heads):
             K, V = gather_context(desc, r, hk, k_pool, v_pool)
             for h in range(hk * G, (hk + 1) * G):
                 s = (K @ q[r, h]) * scale

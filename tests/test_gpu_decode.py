@@ -152,3 +152,49 @@ def test_decode_config5_full_size_sampled_branches(own_len):
     ref = orc.attn_decode(st["desc"], dags.to_f64(st["q"]), dags.to_f64(kp), dags.to_f64(vp), branches=branches)
     check_close(out[branches], ref[branches], torch.bfloat16, "config 5 decode")
     assert torch.isfinite(out.float()).all()
+
+
+def test_decode_config5_every_branch_of_one_kv_head():
+    """Benchmark config 5 decode at full size, middle of its 256 steps (own length 640): all 64
+    live branches, the five query heads of one KV head, against the oracle."""
+    c = dags.config(4)
+    st = dags.decode_state(c["seed"] + 640, 2, c["n_branch"], c["prefix"], 640, c["hq"], c["hkv"], c["d"],
+                           kv_scale=0.5, q_scale=0.5)
+    out, kp, vp = _gpu_decode(st, c["hq"], c["hkv"], c["d"], c["theta"])
+    ref = orc.attn_decode(st["desc"], dags.to_f64(st["q"]), dags.to_f64(kp), dags.to_f64(vp), kv_heads=[6])
+    check_close(out[:, 30:35], ref[:, 30:35], torch.bfloat16, "config 5 decode, kv head 6")
+
+
+@pytest.mark.parametrize("hq,hkv,d,nb,shared,blens", [
+    (8, 2, 128, 3, 100, [17, 5, 32]),             # single-wave items, ragged shared context and tails
+    (10, 2, 128, 16, 1000, [2, 19, 33, 16] * 4),  # 80 stacked rows: the wide kernel for the shared context
+])
+def test_decode_ignores_non_finite_bits_in_unused_slots(hq, hkv, d, nb, shared, blens):
+    """The slots of a partly filled last page that hold no token yet (and pages of the pool that
+    belong to nobody) carry NaN and infinity bit patterns: no result may depend on them."""
+    st = dags.decode_state(900 + nb, n_seqs=2, n_branches=nb, shared_len=shared, branch_len=0,
+                           hq=hq, hkv=hkv, d=d, branch_len_list=blens * 2, spare_pages=2)
+    desc = st["desc"]
+    kp, vp = st["k_pool"], st["v_pool"]
+    poison = [float("nan"), float("inf"), float("-inf")]
+
+    def poison_tail(pages, n_tok, salt):
+        used = n_tok % 16
+        if used and len(pages):
+            kp[int(pages[-1]), :, :, used:, :] = poison[salt % 3]
+            vp[int(pages[-1]), :, :, used:] = poison[(salt + 1) % 3]
+
+    for g in range(int(desc["n_groups"])):
+        poison_tail(desc["shared_pages"][desc["shared_page_off"][g]:desc["shared_page_off"][g + 1]],
+                    int(desc["shared_len"][g]), g)
+    for r in range(int(desc["n_live"])):
+        poison_tail(desc["branch_pages"][desc["branch_page_off"][r]:desc["branch_page_off"][r + 1]],
+                    int(desc["branch_len"][r]), r)
+    unused = sorted(set(range(st["n_pages"])) - set(desc["shared_pages"].tolist()) - set(desc["branch_pages"].tolist()))
+    assert len(unused) == 2
+    kp[unused] = float("nan")
+    vp[unused] = float("nan")
+    out, kpd, vpd = _gpu_decode(st, hq, hkv, d, 5e5, append=False)
+    assert torch.isfinite(out.float()).all()
+    ref = orc.attn_decode(desc, dags.to_f64(st["q"]), dags.to_f64(kpd), dags.to_f64(vpd))
+    check_close(out, ref, torch.bfloat16, "decode with poisoned unused slots")

@@ -170,3 +170,31 @@ def test_config5_qwen_shape_full_size_sampled_rows():
         ref, _ = orc.attn_prefill(qs, ks, dags.to_f64(v[t0:t0 + Tb]), L, anc, rows=rows, compact=True)
         check_close(out[t0 + rows], ref, torch.bfloat16, "config 5 prefill")
         t0 += Tb
+
+
+def test_config4_one_sequence_every_row_of_one_kv_group():
+    """Benchmark config 4 (random multi-level DAGs, half of the visited tiles PARTIAL): the whole
+    batch runs on the GPU; every row of one sequence, the four query heads of one KV group,
+    against the oracle."""
+    c = dags.config(3)
+    dag_list = dags.config_dags(c)
+    T = int(sum(int(np.sum(L)) for L, _ in dag_list))
+    q, k, v = dags.make_qkv(c["seed"] + 200, T, c["hq"], c["hkv"], c["d"], c["scale"], torch.bfloat16)
+    out, lse, meta, _, _ = run_prefill(dag_list, q, k, v, c["theta"], want_lse=True)
+    t0 = int(sum(int(np.sum(L)) for L, _ in dag_list[:5]))
+    L, anc = dag_list[5]
+    Tb = int(np.sum(L))
+    heads = [8, 9, 10, 11]
+    sl = slice(t0, t0 + Tb)
+    ref, ref_lse, _ = oracle_prefill([(L, anc)], q[sl], k[sl], v[sl], c["theta"], heads=heads)
+    check_close(out[sl][:, heads], ref[:, heads], torch.bfloat16, "config 4, sequence 5, kv group 2")
+    assert np.abs(lse[sl][:, heads].cpu().double().numpy() - ref_lse[:, heads]).max() < 2e-2
+
+
+def test_bf16_two_visibility_words_many_tiles():
+    """More than 64 nodes (two visibility words per node) at several thousand tokens: the masked
+    tiles fetch their visibility word inside the pipeline, here with dozens of tiles per row."""
+    rng = np.random.Generator(np.random.PCG64(177))
+    L, anc, _, _ = dags.random_dag(rng, n_nodes=100, depth=7, len_lo=16, len_hi=80)
+    assert anc.shape[1] == 2 and int(np.sum(L)) >= 4000
+    _run_and_check([(L, anc), dags.fork_join(300, [70, 41], 90)], 8, 2, 128, torch.bfloat16, 0.5, 5e5, 178)

@@ -113,6 +113,32 @@ def test_bwd_config2_one_sequence_one_kv_group_every_row():
     check_close(grads[2][sl][:, 1], ref[2][:, 1], torch.bfloat16, "config 2 dv")
 
 
+def test_bwd_config4_one_sequence_one_kv_group_every_row():
+    """Benchmark config 4 (random multi-level DAGs; half of the visited tiles take the per-element
+    path): the whole batch runs on the GPU, one sequence's gradients of one KV head and its four
+    query heads against the oracle."""
+    c = dags.config(3)
+    dag_list = dags.config_dags(c)
+    inputs, grads = _forward_backward(dag_list, c["hq"], c["hkv"], c["d"], c["seed"] + 6, theta=c["theta"])
+    qd, kd, v, dout = inputs
+    t0 = int(sum(int(np.sum(L)) for L, _ in dag_list[:2]))
+    L, anc = dag_list[2]
+    sl = slice(t0, t0 + int(np.sum(L)))
+    ref = orc.attn_prefill_bwd(dags.to_f64(qd[sl]), dags.to_f64(kd[sl]), dags.to_f64(v[sl]), dags.to_f64(dout[sl]),
+                               L, anc, kv_heads=[3])
+    check_close(grads[0][sl][:, 12:16], ref[0][:, 12:16], torch.bfloat16, "config 4 dq")
+    check_close(grads[1][sl][:, 3], ref[1][:, 3], torch.bfloat16, "config 4 dk")
+    check_close(grads[2][sl][:, 3], ref[2][:, 3], torch.bfloat16, "config 4 dv")
+
+
+def test_bwd_five_query_heads_per_kv_head_at_4k_tokens():
+    """The head grouping of benchmark config 5 (five query heads per KV head) on a fork-join of
+    4096 tokens: every gradient element against the oracle."""
+    dag_list = [dags.fork_join(2048, [256] * 6, 512)]
+    inputs, grads = _forward_backward(dag_list, 10, 2, 128, 88, theta=1e6)
+    _check_against_oracle(dag_list, inputs, grads)
+
+
 def test_bwd_fp32_config1_and_ragged_dags():
     """The fp32 accuracy path (benchmark config 1: 128 -> 4 x 64 -> 64, 4 heads, D 64; then ragged
     DAGs with GQA at D 128): gradients within 1e-4 of the oracle's (absolute bound scaled by the
