@@ -197,34 +197,31 @@ template <int D>
 __device__ __forceinline__ void clear_unused_values(bf16x8 (&v0)[D / 32], bf16x8 (&v1)[D / 32], int key0, int vlen,
                                                     int H) {
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const bool ok0 = key0 + 8 * H + e < vlen, ok1 = key0 + 16 + 8 * H + e < vlen;
+  for (int w = 0; w < 4; ++w) {  // 32-bit word w of an operand = keys 8 H + 2 w, 8 H + 2 w + 1 of the page
+    const int k0 = key0 + 8 * H + 2 * w, k1 = k0 + 16;
+    const uint32_t m0 = (k0 < vlen ? 0x0000ffffu : 0u) | (k0 + 1 < vlen ? 0xffff0000u : 0u);
+    const uint32_t m1 = (k1 < vlen ? 0x0000ffffu : 0u) | (k1 + 1 < vlen ? 0xffff0000u : 0u);
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) {
-      if (!ok0) v0[db][e] = (__bf16)0.f;
-      if (!ok1) v1[db][e] = (__bf16)0.f;
+      u32x4 a = __builtin_bit_cast(u32x4, v0[db]), b = __builtin_bit_cast(u32x4, v1[db]);
+      a[w] &= m0;
+      b[w] &= m1;
+      v0[db] = __builtin_bit_cast(bf16x8, a);
+      v1[db] = __builtin_bit_cast(bf16x8, b);
     }
   }
 }
 
 // vlen: tokens the page list holds (wave-uniform); len <= vlen: the smallest of the rows' limits.
+// The block's value operands are cleared in place where they reach past vlen (the block is dead
+// after this call: its registers are refilled by the next load).
 template <int D, typename QF>
-__device__ __forceinline__ void compute_block(const KVBlock<D>& blk, QF&& qop, f32x16* O, float& m, float& l,
+__device__ __forceinline__ void compute_block(KVBlock<D>& blk, QF&& qop, f32x16* O, float& m, float& l,
                                               float sc, float th, int key0, int len, int lim, int vlen, int H) {
   bf16x8 pb0, pb1;
   block_scores<D>(blk.k, qop, O, m, l, sc, th, key0, len, lim, H, pb0, pb1);
-  if (key0 + 32 > vlen) {
-    bf16x8 v0[D / 32], v1[D / 32];
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) {
-      v0[db] = blk.v[0][db];
-      v1[db] = blk.v[1][db];
-    }
-    clear_unused_values<D>(v0, v1, key0, vlen, H);
-    block_pv<D>(v0, v1, pb0, pb1, O);
-  } else {
-    block_pv<D>(blk.v[0], blk.v[1], pb0, pb1, O);
-  }
+  if (key0 + 32 > vlen) clear_unused_values<D>(blk.v[0], blk.v[1], key0, vlen, H);
+  block_pv<D>(blk.v[0], blk.v[1], pb0, pb1, O);
 }
 
 // The loop of a single-wave work item: pages [p0, p1) of one page list, 32 keys (two pages) per
