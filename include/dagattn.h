@@ -245,6 +245,24 @@ int dag_attn_decode(const dag_decode_desc_t* desc, const void* q, const void* k_
                     const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
                     float softmax_scale, void* ws, size_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): dag_attn_decode with its partial
+ * results kept in a device array of the library itself, DAG_DECODE_STATIC_SCRATCH_BYTES long,
+ * which every GPU the library runs on holds until the process ends.  Arguments, results (bit for
+ * bit), layouts and errors as dag_attn_decode, except:
+ *   - DAG_ERR_WORKSPACE when dag_decode_workspace_bytes() for this description exceeds
+ *     DAG_DECODE_STATIC_SCRATCH_BYTES (benchmark configs 3 and 5 need 11 and 24 MiB);
+ *   - everything runs on `stream`, wide sibling groups included: no second stream is created;
+ *   - the call allocates nothing and frees nothing.  Its first call on a device looks up the
+ *     array's address there (hipGetSymbolAddress), so make one call per device outside a capture;
+ *   - all calls on one GPU share the array, which keeps the last call's contents (every partial
+ *     that is read has been written by the same call, so nothing needs clearing): calls that
+ *     overlap on one GPU, on whatever streams, race -- order them. */
+#define DAG_DECODE_STATIC_SCRATCH_BYTES (32u << 20)
+int dag_attn_decode_static(const dag_decode_desc_t* desc, const void* q, const void* k_pool,
+                           const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
+                           float softmax_scale, void* stream);
+
 /* One decode step over a general DAG frontier, contexts given as lists of KV segments (section
  * 3.2: a token carries references to cached blocks, not copies; section 4.3: a Fork hands every
  * child the same context, a Join reads the histories of all its predecessors and the context

@@ -114,6 +114,7 @@ def lib():
         L.dag_decode_workspace_bytes.restype = C.c_size_t
         L.dag_attn_decode.argtypes = [C.POINTER(dag_decode_desc_t), vp, vp, vp, vp, i32, i32, i32, f32,
                                       vp, C.c_size_t, vp]
+        L.dag_attn_decode_static.argtypes = [C.POINTER(dag_decode_desc_t), vp, vp, vp, vp, i32, i32, i32, f32, vp]
         L.dag_decode_segments_workspace_bytes.argtypes = [C.POINTER(dag_decode_seg_desc_t), i32, i32, i32]
         L.dag_decode_segments_workspace_bytes.restype = C.c_size_t
         L.dag_attn_decode_segments.argtypes = [C.POINTER(dag_decode_seg_desc_t), vp, vp, vp, vp, i32, i32, i32, f32,
@@ -127,7 +128,8 @@ def lib():
         L.dag_version.restype = C.c_int
         for name in ("dag_prefill_tile_shape", "dag_meta_sizes", "dag_build_meta", "dag_rope_qk",
                      "dag_attn_prefill", "dag_attn_prefill_prepared", "dag_prefill_prepare_v",
-                     "dag_kv_append_rope", "dag_attn_decode", "dag_attn_decode_segments", "dag_sched_create",
+                     "dag_kv_append_rope", "dag_attn_decode", "dag_attn_decode_static", "dag_attn_decode_segments",
+                     "dag_sched_create",
                      "dag_attn_prefill_bwd",
                      "dag_sched_step"):
             getattr(L, name).restype = C.c_int
@@ -308,6 +310,20 @@ def dag_attn_decode(ddesc, q, k_pool, v_pool, out, workspace, softmax_scale=None
         softmax_scale = 1.0 / float(d) ** 0.5
     _check(lib().dag_attn_decode(C.byref(ddesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(out), hq, hkv, d,
                                  float(softmax_scale), _ptr(workspace), workspace.numel(), _stream()))
+
+
+DECODE_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def dag_attn_decode_static(ddesc, q, k_pool, v_pool, out, softmax_scale=None):
+    """dag_attn_decode without a workspace: the partial results live in the library's own device
+    array (DAG_ERR_WORKSPACE when the description needs more than DECODE_STATIC_SCRATCH_BYTES)."""
+    n_live, hq, d = q.shape
+    hkv = k_pool.shape[1]
+    if softmax_scale is None:
+        softmax_scale = 1.0 / float(d) ** 0.5
+    _check(lib().dag_attn_decode_static(C.byref(ddesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(out), hq, hkv, d,
+                                        float(softmax_scale), _stream()))
 
 
 class SegDecodeDesc:

@@ -928,9 +928,37 @@ extern "C" int dag_kv_append_rope(const dag_decode_desc_t* d, const void* k_new,
   return DAG_OK;
 }
 
-extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const void* k_pool, const void* v_pool,
-                               void* out, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale, void* ws,
-                               size_t ws_bytes, void* stream_) {
+namespace {
+
+// Scratch of dag_attn_decode_static: the partial results live in this array instead of a caller
+// workspace.  Every GPU the library runs on holds its own copy at its own address until the
+// process ends; host code never uses the array's name as an address, only what
+// hipGetSymbolAddress returned for the current device.
+static __device__ __align__(256) unsigned char scratch[DAG_DECODE_STATIC_SCRATCH_BYTES];
+
+int static_scratch(void** out) {
+  constexpr int MAX_DEV = 64;
+  static void* ptr[MAX_DEV];
+  static bool ready[MAX_DEV];
+  static std::mutex mu;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return DAG_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ready[dev]) {  // once per device, with that device current
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DAG_ERR_HIP;
+    ptr[dev] = p;
+    ready[dev] = true;
+  }
+  *out = ptr[dev];
+  return DAG_OK;
+}
+
+// static_ws: the partials go to the library's own scratch array (ws / ws_bytes ignored), and the
+// own-page items stay on the caller's stream (no second stream is created or used).
+int decode_impl(const dag_decode_desc_t* d, const void* q, const void* k_pool, const void* v_pool, void* out,
+                int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale, void* ws, size_t ws_bytes,
+                void* stream_, bool static_ws) {
   DecodePlan p;
   const int rc = make_plan(d, hq, hkv, head_dim, &p);
   if (rc != DAG_OK) return rc;
@@ -943,7 +971,13 @@ extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const 
   if (p.items_a + p.items_b == 0) return DAG_ERR_BAD_LEN;  // a query needs at least its own token
   if (!dag_aligned16(q) || !dag_aligned16(k_pool) || !dag_aligned16(v_pool) || !dag_aligned16(out))
     return DAG_ERR_ALIGN;
-  if (!ws || ws_bytes < p.bytes) return DAG_ERR_WORKSPACE;
+  if (static_ws) {
+    if (p.bytes > (size_t)DAG_DECODE_STATIC_SCRATCH_BYTES) return DAG_ERR_WORKSPACE;
+    const int rs = static_scratch(&ws);
+    if (rs != DAG_OK) return rs;
+  } else if (!ws || ws_bytes < p.bytes) {
+    return DAG_ERR_WORKSPACE;
+  }
   char* base = (char*)dag_align_up((size_t)(uintptr_t)ws, 256);
   DecodeArgs a;
   a.group_branch_off = d->group_branch_off;
@@ -989,7 +1023,7 @@ extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const 
     // caller's stream with events (default priority; the pattern can be captured into a graph).
     const unsigned groups = (unsigned)(d->n_groups * hkv * p.splits_a);
     const unsigned threads = 64u * (unsigned)p.rb_max;
-    if (p.items_b > 0) {
+    if (p.items_b > 0 && !static_ws) {
       side_lock.lock();  // held until the join has been enqueued
       side = side_stream_locked();
       if (!side) return DAG_ERR_HIP;
@@ -1025,6 +1059,20 @@ extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const 
   else hipLaunchKernelGGL(k_decode_merge<64>, dim3(nout), dim3(64), 0, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
+}
+
+}  // namespace
+
+extern "C" int dag_attn_decode(const dag_decode_desc_t* d, const void* q, const void* k_pool, const void* v_pool,
+                               void* out, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale, void* ws,
+                               size_t ws_bytes, void* stream_) {
+  return decode_impl(d, q, k_pool, v_pool, out, hq, hkv, head_dim, softmax_scale, ws, ws_bytes, stream_, false);
+}
+
+extern "C" int dag_attn_decode_static(const dag_decode_desc_t* d, const void* q, const void* k_pool,
+                                      const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
+                                      float softmax_scale, void* stream_) {
+  return decode_impl(d, q, k_pool, v_pool, out, hq, hkv, head_dim, softmax_scale, nullptr, 0, stream_, true);
 }
 
 namespace {

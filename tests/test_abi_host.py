@@ -183,6 +183,13 @@ def test_decode_argument_errors():
     assert L.dag_attn_decode(C.byref(dd), None, p, p, p, 32, 8, 128, 0.1, p, need, None) == -1
     bad_page = B.dag_decode_desc_t(1, 2, 32, 4, 2, 2, *([FAKE] * 8))
     assert L.dag_attn_decode(C.byref(bad_page), p, p, p, p, 32, 8, 128, 0.1, p, need, None) == -7
+    # the variant without a workspace validates the same way and refuses what its array cannot hold
+    assert L.dag_attn_decode_static(C.byref(dd), p, p, p, p, 32, 8, 96, 0.1, None) == -7
+    assert L.dag_attn_decode_static(C.byref(dd), None, p, p, p, 32, 8, 128, 0.1, None) == -1
+    assert L.dag_attn_decode_static(C.byref(bad_page), p, p, p, p, 32, 8, 128, 0.1, None) == -7
+    huge = B.dag_decode_desc_t(64, 64 * 32, 16, 1 << 16, 64, 32, *([FAKE] * 8))
+    assert L.dag_decode_workspace_bytes(C.byref(huge), 32, 8, 128) > B.DECODE_STATIC_SCRATCH_BYTES
+    assert L.dag_attn_decode_static(C.byref(huge), p, p, p, p, 32, 8, 128, 0.1, None) == -6
     assert L.dag_decode_workspace_bytes(C.byref(bad_page), 32, 8, 128) == 0
     assert L.dag_kv_append_rope(C.byref(bad_page), p, p, p, p, 8, 128, 1e4, None) == -7
     assert L.dag_kv_append_rope(C.byref(dd), None, p, p, p, 8, 128, 1e4, None) == -1
