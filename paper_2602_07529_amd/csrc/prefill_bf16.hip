@@ -161,10 +161,10 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   constexpr int KPB = 64 / CH;               // keys per K block
   constexpr int NBK = TN / KPB;              // K blocks per tile
   constexpr int NBV = D / 8;                 // V^T blocks per tile (8 output dimensions each)
-  // Only the first NISS waves (one per SIMD) issue the K/V loads: the scalar work of an issue
-  // would otherwise run in both waves of a SIMD at the same time, right after the barrier, and
-  // leave the matrix pipe idle; this way the other wave of the SIMD computes meanwhile.
-  constexpr int NISS = NW == 8 ? 4 : NW;
+  // Every wave issues its share of the K/V loads of a tile: the waves meet at a barrier once per
+  // tile, so the tile takes as long as its slowest wave, and the load issue (with the cursor
+  // arithmetic in front of it) is what makes a wave slow.
+  constexpr int NISS = NW;
   constexpr int IPK = NBK / NISS, IPV = NBV / NISS;  // blocks per tile and issuing wave
   constexpr int LPT = IPK + IPV;             // loads per tile and wave
   constexpr int BLKK = 1024 + 16;            // block strides (skewed so that reads are conflict free)
@@ -178,6 +178,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   unsigned char* const Kbase = smem;                    // K[NSTAGE][KTILE]
   unsigned char* const Vbase = smem + NSTAGE * KTILE;   // V^T[NSTAGE][VTILE]
   unsigned char* const Abase = smem + NSTAGE * (KTILE + VTILE);  // node ids of the keys [NSTAGE][64]
+  // after them: the two-slot item mailbox (16 bytes)
 
   const int G = a.hq / a.hkv;
   const int HS = (G + HG - 1) / HG;  // items per (query tile, KV head); the last one may be partly filled
@@ -202,7 +203,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   const int my_rank = (int)blockIdx.x;
   const long n_list = n_items;
   int32_t* const ctr = a.sched;
-  auto load_item = [&](long it) {
+  auto load_item = [&](long it) __attribute__((always_inline)) {
     const int oi = (int)(it / nhw), hw = (int)(it % nhw);
     const int32_t* d = a.qtile_desc + (size_t)oi * 8;
     Item I;
@@ -211,12 +212,12 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     I.hk = sgpr(hw / HS); I.hs = sgpr(hw % HS);
     return I;
   };
-  auto row_of = [&](const Item& I, int r) { return I.row0 + 32 * (rg * RB + r) + L; };  // row inside the sequence
-  auto token_of = [&](const Item& I, int r) { return I.cu + min(row_of(I, r), I.T - 1); };
+  auto row_of = [&](const Item& I, int r) __attribute__((always_inline)) { return I.row0 + 32 * (rg * RB + r) + L; };  // row inside the sequence
+  auto token_of = [&](const Item& I, int r) __attribute__((always_inline)) { return I.cu + min(row_of(I, r), I.T - 1); };
   // When G is no multiple of HG the waves beyond the last head of the group repeat that head (they
   // load valid rows and take part in every barrier) and store nothing.
-  auto head_of = [&](const Item& I) { return I.hk * G + min(I.hs * HG + hj, G - 1); };
-  auto head_is_mine = [&](const Item& I) { return I.hs * HG + hj < G; };
+  auto head_of = [&](const Item& I) __attribute__((always_inline)) { return I.hk * G + min(I.hs * HG + hj, G - 1); };
+  auto head_is_mine = [&](const Item& I) __attribute__((always_inline)) { return I.hs * HG + hj < G; };
 
   // What this lane fetches in a wave-level load (LDS position 16*lane inside the block):
   //   K:   key (lane / 4) % KPB of the block, chunk 4 * (lane / (4 * KPB)) + lane % 4: four
@@ -227,6 +228,15 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   const uint32_t kchunk = (4 * (lane / (4 * KPB)) + (lane & 3)) * 16;
   const uint32_t ksrc = kkey * rowbytes + kchunk;
   const uint32_t vsrc = lane * 16;
+  // The steady state issues its loads without a decision: the row a lane fetches in K load i of
+  // a tile (clamped to the tile's last valid row, which only matters in a ragged tile) and the
+  // per-lane offset of V^T load i.
+  int kvrow[IPK];
+  uint32_t vvo[IPV];
+#pragma unroll
+  for (int i = 0; i < IPK; ++i) kvrow[i] = (w + NISS * i) * KPB + kkey;
+#pragma unroll
+  for (int i = 0; i < IPV; ++i) vvo[i] = (uint32_t)i * (NISS * 1024) + vsrc;
 
   // kbase / vbase: the cursor item's K rows (token cu, head hk) and V^T tiles (tile ktb, head hk,
   // this wave's block); the tile adds a multiple of its index.
@@ -234,25 +244,41 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   // Issuing a tile is split into a set-up (addresses of the tile, optional node-id record) and
   // LPT single loads, so that the pipeline can spread them over the slots of a step, in the
   // shadow of the MFMAs; issue_loads does all of it at once.
-  const unsigned char *p_ktile = nullptr, *p_vtile = nullptr;  // pending tile (wave-uniform)
+  // The tiles of all items of a workgroup form one stream; "group" g of the stream is the K tile g
+  // together with the V^T tile g - 1: the scores of a tile are computed one tile before its P V
+  // product, and the first K operands of the next tile are read at the end of the current one, so
+  // K is needed a tile earlier than V^T.  Group g lives in K slot g % NSTAGE and V^T slot
+  // (g - 1) % NSTAGE.  Every group has the same number of loads (the vmcnt waits count loads): the
+  // first group of the stream fetches its own V^T tile into the slot in front of it, the last one
+  // (V^T of the last tile) fetches that tile's K once more; neither copy is ever read.
+  const unsigned char *p_ktile = nullptr, *p_vtile = nullptr;  // pending group (wave-uniform)
+  const unsigned char* v_saved = nullptr;                      // V^T tile of the group issued last
   unsigned char *p_kl = nullptr, *p_vl = nullptr;
   int p_last = 0;
   bool p_ragged = false;
-  auto issue_setup = [&](unsigned slot, const unsigned char* kbase, const unsigned char* vbase, int cu, int T, int kt,
-                         bool with_nodes) {
+  auto issue_setup = [&](unsigned g, const unsigned char* kbase, const unsigned char* vbase, int cu, int T, int kt,
+                         bool with_nodes) __attribute__((always_inline)) {
+    const unsigned slot = g % NSTAGE, vslot = (g + NSTAGE - 1) % NSTAGE;
     const int j0 = kt * TN;
     if (with_nodes) {  // a tile that needs the mask: node ids of its 64 keys (every wave writes the same record)
       const int32_t* np = a.tok_node + cu + min(j0 + lane, T - 1);
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)np, (lds_ptr_t)(Abase + slot * 256), 4, 0, 0);
     }
     p_ktile = kbase + (uint64_t)(uint32_t)kt * kt_kstride;
-    p_vtile = vbase + (uint64_t)(uint32_t)kt * kt_vstride;
+    const unsigned char* const v_mine = vbase + (uint64_t)(uint32_t)kt * kt_vstride;
+    p_vtile = g == 0 ? v_mine : v_saved;
+    v_saved = v_mine;
     p_kl = Kbase + slot * KTILE + w * BLKK;
-    p_vl = Vbase + slot * VTILE + w * BLKV;
+    p_vl = Vbase + vslot * VTILE + w * BLKV;
     p_ragged = j0 + TN > T;  // ragged last tile: rows past the end re-read the last valid row (masked later)
     p_last = T - 1 - j0;
   };
-  auto issue_part = [&](int i) {  // i = 0 .. LPT - 1, a compile-time constant at every call site
+  auto issue_setup_flush = [&](unsigned g) __attribute__((always_inline)) {  // the stream's last group: V^T of the last tile (its K once more)
+    p_vtile = v_saved;
+    p_kl = Kbase + (g % NSTAGE) * KTILE + w * BLKK;
+    p_vl = Vbase + ((g + NSTAGE - 1) % NSTAGE) * VTILE + w * BLKV;
+  };
+  auto issue_part = [&](int i) __attribute__((always_inline)) {  // i = 0 .. LPT - 1, a compile-time constant at every call site
     if (i < IPK) {
       if (!p_ragged) {
         __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_ktile + (size_t)((w + NISS * i) * KPB) * rowbytes + ksrc),
@@ -267,12 +293,6 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_vtile + iv * (NISS * 1024) + vsrc),
                                        (lds_ptr_t)(p_vl + iv * NISS * BLKV), 16, 0, 0);
     }
-  };
-  auto issue_loads = [&](unsigned slot, const unsigned char* kbase, const unsigned char* vbase, int cu, int T, int kt,
-                         bool with_nodes) {
-    issue_setup(slot, kbase, vbase, cu, T, kt, with_nodes);
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) issue_part(i);
   };
 
   // LDS read addresses (bytes inside a tile); every other read of the tile is an immediate away.
@@ -291,7 +311,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   float M[RB], l[RB], bmax[RB];  // reference maximum, row sum, maximum of the last score half (relative to M)
   f32x16 negM[RB];
   bf16x8 P0[RB][2], P1[RB][2];  // probabilities of the two key halves (B operands)
-  auto reset_acc = [&]() {
+  auto reset_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
 #pragma unroll
@@ -316,25 +336,35 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       }
   const float sc = a.scale * 1.4426950408889634f;
 
+  // The Q rows of an item: fetched as they are into the registers they stay in (all loads of a
+  // row in flight together; with the scaling attached to each load the compiler handed them out
+  // one by one, each behind a wait for the one before and for every tile load in flight), scaled
+  // in place once they have arrived.
   bf16x8 qf[RB][KSTEPS];
-  auto load_q = [&](const Item& I) {
+  auto load_q = [&](const Item& I) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
       const uint16_t* qp = qg + ((size_t)token_of(I, r) * a.hq + head_of(I)) * D + 8 * H;
 #pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) qf[r][s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + 16 * s));
+    }
+  };
+  auto scale_q = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
       for (int s = 0; s < KSTEPS; ++s) {
-        const u32x4 raw = *(const u32x4*)(qp + 16 * s);
+        const u32x4 raw = __builtin_bit_cast(u32x4, qf[r][s]);
         u32x4 scaled;
 #pragma unroll
         for (int e = 0; e < 4; ++e) scaled[e] = dag_pack_bf2(dag_bf_lo(raw[e]) * sc, dag_bf_hi(raw[e]) * sc);
         qf[r][s] = __builtin_bit_cast(bf16x8, scaled);
       }
-    }
   };
 
   // row maxima of a half; true when some row of the wave exceeds its reference maximum by the
   // threshold (or lies that far below it while the row has not accumulated anything yet)
-  auto row_max = [&](const f32x16* S) {
+  auto row_max = [&](const f32x16* S) __attribute__((always_inline)) {
     bool need = false;
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
@@ -355,7 +385,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   uint64_t rmsk[RB];
 #pragma unroll
   for (int r = 0; r < RB; ++r) rmsk[r] = 0;
-  auto apply_mask = [&](f32x16* S, int half) {  // masked scores become -inf
+  auto apply_mask = [&](f32x16* S, int half) __attribute__((always_inline)) {  // masked scores become -inf
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
       const uint32_t word = half ? (uint32_t)(rmsk[r] >> 32) : (uint32_t)rmsk[r];
@@ -394,7 +424,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     // order, so before the MFMA of slot i exactly the reads of the slots after it may be pending
     // (the compiler's own bookkeeping waits for all of them, which exposes the LDS latency).
     const uint32_t kaddr = QK ? lds_addr(Kb) + koff : 0, vaddr = PV ? lds_addr(Vb) + voff : 0;
-    auto fetch = [&](auto ic) {
+    auto fetch = [&](auto ic) __attribute__((always_inline)) {
       constexpr int i = decltype(ic)::value;
       const uint32_t ka = kaddr, va = vaddr;  // (named here: captures inside discarded branches trip the compiler)
       bf16x8* const op = opnd;
@@ -411,7 +441,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     __builtin_amdgcn_sched_barrier(0);
     // (the slots are instantiated one by one, not left to the loop unroller: the immediate offsets
     // of the reads above have to be compile-time constants whatever `extra` contains)
-    static_for<0, NSLOT>([&](auto ic) {
+    static_for<0, NSLOT>([&](auto ic) __attribute__((always_inline)) {
       constexpr int i = decltype(ic)::value;
       fetch(std::integral_constant<int, i + PF>{});
       wait_lgkmcnt(NSLOT - 1 - i < PF ? NSLOT - 1 - i : PF);
@@ -455,7 +485,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   auto nothing = [](int, int) {};
   // raise the running maxima to bmax and rescale everything accumulated so far, including the
   // probabilities that are still waiting for their P V product (rare after the first tiles)
-  auto rescale = [&](f32x16* Sn) {  // Sn: the score half whose maxima called for it (still relative to the old M)
+  auto rescale = [&](f32x16* Sn) __attribute__((always_inline)) {  // Sn: the score half whose maxima called for it (still relative to the old M)
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
       float d = fmaxf(bmax[r], __shfl_xor(bmax[r], 32));  // maximum of the half over the whole row, relative to M
@@ -492,9 +522,11 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   uint32_t* const mbox = (uint32_t*)(Abase + NSTAGE * 256);
   int mslot = 0;
 
-  // The K/V tile stream runs ahead of the computation, across the item boundary: `ti` tiles have
-  // been issued, tile `tc` is the one being consumed; tile t lives in ring slot t % NSTAGE.
+  // The K/V tile stream runs ahead of the computation, across the item boundary: `ti` groups have
+  // been issued (group g = K tile g + V^T tile g - 1), tile `tc` is the one whose scores are being
+  // computed; tile t lives in ring slot t % NSTAGE of its ring.
   unsigned ti = 0, tc = 0;
+  bool flushed = false;  // the last group of the stream (V^T of its last tile) has been issued
   int iss_next = 0, iss_idx = 0;  // issue cursor: item (0 current / 1 next) and tile index in its row
   // The cursor's item, field by field (scalar registers), with the bases of its K rows and V^T
   // tiles, and 64 key-tile indices of its row in a vector register (lane e holds entry
@@ -502,8 +534,8 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   // prefetches with its wait).  col_nxt is the same for the first 64 entries of the next item.
   int is_cu, is_T, is_c0, is_N, is_nfast, col_iss, col_nxt;
   const unsigned char *is_kbase, *is_vbase;
-  auto load_cols = [&](const Item& I, int first) { return a.col[I.c0 + min(first + lane, I.N - 1)]; };
-  auto cursor_enter = [&](const Item& I, int cols) {
+  auto load_cols = [&](const Item& I, int first) __attribute__((always_inline)) { return a.col[I.c0 + min(first + lane, I.N - 1)]; };
+  auto cursor_enter = [&](const Item& I, int cols) __attribute__((always_inline)) {
     is_cu = I.cu; is_T = I.T; is_c0 = I.c0; is_N = I.N; is_nfast = I.nfast;
     is_kbase = kg + ((size_t)I.cu * a.hkv + I.hk) * (D * 2);
     is_vbase = vtg + ((size_t)I.ktb * a.hkv + I.hk) * (size_t)(D * TN * 2) + w * 1024;
@@ -515,33 +547,45 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   const bool issuer = w < NISS;
   // First half of issuing the next tile of the stream: cursor, tile index, addresses.  The LPT
   // loads follow through issue_part (at once in try_issue, slot by slot in the pipeline).
-  auto try_issue_begin = [&]() {
+  auto try_issue_begin = [&]() __attribute__((always_inline)) {
     if (!issuer) return false;
+    bool flush = false;
     if (iss_idx >= is_N) {
-      if (iss_next || !has_next) return false;
-      iss_next = 1;
-      cursor_enter(nxt, col_nxt);
+      if (iss_next) return false;  // (the item after the next one is not known yet)
+      if (has_next) {
+        iss_next = 1;
+        cursor_enter(nxt, col_nxt);
+      } else {                     // end of the stream: its last group
+        if (flushed) return false;
+        flushed = true;
+        flush = true;
+      }
     }
-    if ((iss_idx & 63) == 0 && iss_idx != 0) {  // rows with more than 64 tiles: next 64 entries
-      col_iss = a.col[is_c0 + min(iss_idx + lane, is_N - 1)];
-      asm volatile("" ::"v"(col_iss));  // the wait for this load belongs here, not on the common path
+    if (flush) {
+      issue_setup_flush(ti);
+    } else {
+      if ((iss_idx & 63) == 0 && iss_idx != 0) {  // rows with more than 64 tiles: next 64 entries
+        col_iss = a.col[is_c0 + min(iss_idx + lane, is_N - 1)];
+        asm volatile("" ::"v"(col_iss));  // the wait for this load belongs here, not on the common path
+      }
+      const int kt = __builtin_amdgcn_readlane(col_iss, iss_idx & 63);
+      issue_setup(ti, is_kbase, is_vbase, is_cu, is_T, kt, iss_idx >= is_nfast);
+      iss_idx = iss_idx + 1;
     }
-    const int kt = __builtin_amdgcn_readlane(col_iss, iss_idx & 63);
-    issue_setup(ti % NSTAGE, is_kbase, is_vbase, is_cu, is_T, kt, iss_idx >= is_nfast);
-    ++ti;
-    ++iss_idx;
+    ti = ti + 1;
     return true;
   };
-  auto try_issue = [&]() {
+  auto try_issue = [&]() __attribute__((always_inline)) {
     if (!try_issue_begin()) return false;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) issue_part(i);
     return true;
   };
-  // Moves on to the next tile of the stream: afterwards tile tc (if there is one) is visible to
-  // the whole workgroup, every wave has finished what it did before the call, and the ring slot
-  // that this frees is refilled.  The pipeline reads tiles tc - 1 and tc, so tiles up to
-  // tc + NSTAGE - 2 may be in the ring.
+  // Moves on to the next tile of the stream: afterwards group tc + 1 (K tile tc + 1, whose first
+  // operands are read at the end of tile tc, and V^T tile tc) is visible to the whole workgroup,
+  // every wave has finished what it did before the call, and the ring slots that this frees are
+  // refilled.  The pipeline reads K tiles tc and tc + 1 and V^T tile tc - 1, so groups up to
+  // tc + NSTAGE - 1 may be in the rings.
 #ifdef DAGATTN_TIMING
   unsigned long long tacc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   unsigned long long t_mid = 0;
@@ -555,35 +599,44 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
 #define TACC(i, a0, a1)
 #define TCOUNT(i)
 #endif
-  auto sync_next = [&]() {
+#if defined(DAGATTN_TIMING) && DAGATTN_TIMING >= 2  // stamps inside the tile loops (they disturb what they measure)
+#define TSTAMP2(x) TSTAMP(x)
+#define TACC2(i, a0, a1) TACC(i, a0, a1)
+#else
+#define TSTAMP2(x)
+#define TACC2(i, a0, a1)
+#endif
+  auto sync_next = [&]() __attribute__((always_inline)) {
     ++tc;
-    TSTAMP(tw0);
-    const int younger = (int)(ti - tc) - 1;  // tiles issued after the one needed now
+    TSTAMP2(tw0);
+    const int younger = (int)(ti - tc) - 2;  // groups issued after the one needed now (group tc + 1)
     if (!issuer) {
     } else if (younger >= 2) wait_vmcnt<2 * LPT>();
     else if (younger == 1) wait_vmcnt<LPT>();
     else wait_vmcnt<0>();
-    TSTAMP(tw1);
-    TACC(8, tw0, tw1);
+    TSTAMP2(tw1);
+    TACC2(8, tw0, tw1);
     // Bare barrier (no memory fence: __syncthreads would drain every outstanding prefetch).
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    TSTAMP2(tw2);
+    TACC2(9, tw1, tw2);
   };
   // One more tile into the slot that a sync_next has freed, spread over the slots of a pipeline step with NS slots (slot 1: set-up, the slots
   // after it: the loads), so that the scalar work and the load issue hide behind the MFMAs.
   // The texture path takes a 1 KiB load every 16 cycles at best, so the loads are spaced out: the
   // K loads over the first step of a tile, the V^T loads over the second.
   bool refill_pending = false;
-  auto refill_slot = [&](int i, int NS) {  // first step: set-up in slot 1, K load x in slot 2 + x (NS - 2) / IPK
+  auto refill_slot = [&](int i, int NS) __attribute__((always_inline)) {  // first step: set-up in slot 1, K load x in slot 2 + x (NS - 2) / IPK
     if (i == 1) {
-      refill_pending = (ti - tc < NSTAGE - 1) && try_issue_begin();
+      refill_pending = (ti - tc < NSTAGE) && try_issue_begin();
     } else if (i >= 2 && refill_pending) {
 #pragma unroll
       for (int x = 0; x < IPK; ++x)
         if (2 + x * (NS - 2) / IPK == i) issue_part(x);
     }
   };
-  auto refill_slot_v = [&](int i, int NS) {  // second step: V^T load x in slot x NS / IPV
+  auto refill_slot_v = [&](int i, int NS) __attribute__((always_inline)) {  // second step: V^T load x in slot x NS / IPV
     if (refill_pending) {
 #pragma unroll
       for (int x = 0; x < IPV; ++x)
@@ -592,7 +645,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   };
 
 #pragma unroll 1
-  while (ti < NSTAGE - 1 && try_issue()) {
+  while (ti < NSTAGE && try_issue()) {
   }
   load_q(cur);
   // Row data for the mask: node of each row (rnode), word 0 of that node's visibility bitset
@@ -622,6 +675,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       asm volatile("" ::"v"(vis0[r]), "v"(rnode_nxt[r]));
     }
     asm volatile("" ::"v"(col_iss), "v"(col_nxt));
+    scale_q();
     TCOUNT(11);
     TSTAMP(t_top);
     if (grabber && has_next && lane == 0)  // the item after `nxt`; the answer is needed at the end of this item only
@@ -629,8 +683,8 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
 
     const int F = cur.nfast;
     f32x16 SA[RB], SB[RB];
-    auto Kt = [&](unsigned t) { return Kbase + (t % NSTAGE) * KTILE; };
-    auto Vt = [&](unsigned t) { return Vbase + (t % NSTAGE) * VTILE; };
+    auto Kt = [&](unsigned t) __attribute__((always_inline)) { return Kbase + (t % NSTAGE) * KTILE; };
+    auto Vt = [&](unsigned t) __attribute__((always_inline)) { return Vbase + (t % NSTAGE) * VTILE; };
     const yes_t Y;
     const no_t N_;
     const h0_t H0;
@@ -642,7 +696,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     // ids come with the tile, through the ring) and each segment is switched on for the rows whose
     // node sees the segment's node (Eq. 3); the causal / length limit is one more AND.  Called
     // when tile n of the row (ring tile tc) has become visible, before its scores are masked.
-    auto tile_mask = [&](int n) {
+    auto tile_mask = [&](int n) __attribute__((always_inline)) {
       int kt;
       const int32_t* cp = a.col + sgpr(cur.c0 + n);
       asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(kt) : "s"(cp) : "memory");
@@ -692,11 +746,11 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     const int NT = cur.N;
     int mask_n = 0;
     const int mask_slot = w < NW / 2 ? KSTEPS - 2 : 0;  // (a slot of the score part: the first tile's step has no other)
-    auto first_half_extra = [&](int i, int NS) {
+    auto first_half_extra = [&](int i, int NS) __attribute__((always_inline)) {
       if (msk_on && i == mask_slot) tile_mask(mask_n);
       refill_slot(i, NS);
     };
-    auto first_tile_extra = [&](int i, int) {
+    auto first_tile_extra = [&](int i, int) __attribute__((always_inline)) {
       if (msk_on && i == mask_slot) tile_mask(0);
     };
     msk_on = F == 0;
@@ -704,8 +758,222 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     bool need = step(Y, N_, Y, H1, H0, Kt(tc), SB, nullptr, nop, SA, P0, nothing);
     TSTAMP(t_first);
     TACC(0, t_top, t_first);
+    int n = 0;
+    {
+      // ---- the mask-free tiles after the first one: the steady state of the kernel.  One
+      // straight run of 2 (KSTEPS + 2 DB) slots per tile with no test in it but the two overflow
+      // checks; the operand reads run PF slots ahead of their MFMAs without a break, across the
+      // two halves and into the next tile (whose K tile is published a tile ahead for that).
+#ifndef DAGATTN_NOFAST
+      if (1 < F) {
+        constexpr int NS = KSTEPS + 2 * DB;
+#ifdef DAGATTN_PF
+        constexpr int PF = DAGATTN_PF, RING = DAGATTN_PF < 4 ? 4 : 8;
+#else
+        constexpr int PF = 3, RING = 4;
+#endif
+        static_assert((2 * NS) % RING == 0 && KSTEPS >= PF - 4 && PF < RING, "operand ring");
+        if (need) rescale(SB);
+        bf16x8 opr[RING];
+        auto ffetch = [&](auto ic, uint32_t ka, uint32_t va, uint32_t kn) __attribute__((always_inline)) {  // operand of slot ic (2 NS ..: next tile)
+          constexpr int i = decltype(ic)::value;
+          bf16x8* const op = opr;
+          if constexpr (i >= 2 * NS) {
+            constexpr int q = i - 2 * NS;
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(op[i % RING]) : "v"(kn), "n"((q >> 1) * 64 * KPB + (q & 1) * 32));
+          } else if constexpr (i % NS < KSTEPS) {
+            constexpr int st = i / NS, j = i % NS;
+            asm volatile("ds_read_b128 %0, %1 offset:%2"
+                         : "=v"(op[i % RING])
+                         : "v"(ka), "n"(st * (32 / KPB) * BLKK + (j >> 1) * 64 * KPB + (j & 1) * 32));
+          } else {
+            constexpr int st = i / NS, j = i % NS - KSTEPS;
+            asm volatile("ds_read_b128 %0, %1 offset:%2"
+                         : "=v"(op[i % RING])
+                         : "v"(va), "n"((j % DB) * 4 * BLKV + (2 * st + j / DB) * 256));
+          }
+        };
+        // The reference maximum is not looked after before the exponentials here: a row's sum of
+        // the 16 probabilities a lane has just computed tells afterwards whether a score left the
+        // range (a sum above 2^10, infinity or NaN); only then are the row maxima of that half
+        // taken, the accumulators and the other half's scores shifted and the half's probabilities
+        // computed again (they have not been used yet).  Sc: the scores the probabilities Pc came
+        // from, Sn: the other half's scores (relative to the same reference), rs: this lane's sums.
+        auto overflow_fix = [&](const f32x16* Sc, bf16x8 (*Pc)[2], f32x16* Sn, float* rs) __attribute__((always_inline)) {
+#pragma unroll
+          for (int r = 0; r < RB; ++r) {
+            float bm = max3(Sc[r][0], Sc[r][1], Sc[r][2]);
+#pragma unroll
+            for (int e = 3; e < 15; e += 2) bm = max3(bm, Sc[r][e], Sc[r][e + 1]);
+            bm = fmaxf(bm, Sc[r][15]);
+            const float d = fmaxf(fmaxf(bm, __shfl_xor(bm, 32)), 0.f);  // the row's maximum relative to M (M never goes down here)
+            const float alpha = __builtin_amdgcn_exp2f(-d);
+            M[r] += d;
+            l[r] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              negM[r][e] -= d;
+              Sn[r][e] -= d;
+            }
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+              for (int e = 0; e < 16; ++e) O[r][db][e] *= alpha;
+            rs[r] = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; e += 2) {
+              f32x2 pp;
+              pp[0] = __builtin_amdgcn_exp2f(Sc[r][e] - d);
+              pp[1] = __builtin_amdgcn_exp2f(Sc[r][e + 1] - d);
+              rs[r] += pp[0] + pp[1];
+              const bf16x2 pk = __builtin_convertvector(pp, bf16x2);
+              Pc[r][e >> 3][e & 7] = pk[0];
+              Pc[r][e >> 3][(e & 7) + 1] = pk[1];
+            }
+          }
+        };
+        {
+          const uint32_t kn = lds_addr(Kt(tc + 1)) + koff;
+          static_for<0, (PF < KSTEPS ? PF : KSTEPS)>([&](auto ic) __attribute__((always_inline)) {
+            ffetch(std::integral_constant<int, 2 * NS + decltype(ic)::value>{}, 0u, 0u, kn);
+          });
+        }
+        // One tile of the steady state.  In one slot of its first half (the two waves of a SIMD
+        // take different slots, so that one of them always feeds the matrix pipe) the wave moves
+        // the cursor on: the common case -- a tile of the cursor's item that needs no mask, so it
+        // is not ragged either, inside the 64 entries of the row the wave holds -- costs a handful
+        // of scalar instructions; anything else is left to the general code after the tile
+        // (`other` set).  In its second half the tile always issues this wave's LPT loads of the
+        // group that p_ktile / p_vtile / p_kl / p_vl / p_last describe, without a test: normally
+        // the group that has just been set up; when none was (the rings are full, the stream has
+        // ended, the general code issues its group itself) the last group once more, which puts
+        // the bytes that are there already into the same places.
+        const int setup_slot = w < NW / 2 || NW == 1 ? 1 : NS / 2 + 1;
+        bool other = false;
+        auto fast_tile = [&]() __attribute__((always_inline)) {
+          const uint32_t ka = lds_addr(Kt(tc)) + koff, va = lds_addr(Vt(tc - 1)) + voff, kn = lds_addr(Kt(tc + 1)) + koff;
+          float rs[RB], pprev[RB], plast[RB];  // sums, the even partner of a pair, the exponential of the slot before
+#pragma unroll
+          for (int r = 0; r < RB; ++r) rs[r] = pprev[r] = plast[r] = 0.f;
+          // (operands KSTEPS .. PF - 1 of this tile, when the reads run further ahead than the K
+          // operands of the next tile that the previous tile could fetch)
+          static_for<(PF < KSTEPS ? PF : KSTEPS), PF>([&](auto ic) __attribute__((always_inline)) {
+            ffetch(ic, ka, va, kn);
+          });
+          static_for<0, 2 * NS>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value, st = i / NS, j = i % NS;
+            constexpr int ahead = i + PF < 2 * NS + KSTEPS ? PF : 2 * NS + KSTEPS - 1 - i;  // reads in flight after this slot's
+            if constexpr (i + PF < 2 * NS + KSTEPS) ffetch(std::integral_constant<int, i + PF>{}, ka, va, kn);
+            wait_lgkmcnt(ahead);
+            __builtin_amdgcn_sched_barrier(0);
+            f32x16* const Sn = st ? SB : SA;
+            const f32x16* const Sc = st ? SA : SB;
+            bf16x8 (*const Pp)[2] = st ? P1 : P0;
+            bf16x8 (*const Pc)[2] = st ? P0 : P1;
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+              if constexpr (j < KSTEPS) Sn[r] = mfma32(opr[i % RING], qf[r][j < KSTEPS ? j : 0], j == 0 ? negM[r] : Sn[r]);
+              else O[r][(j - KSTEPS) % DB] = mfma32(opr[i % RING], Pp[r][(j - KSTEPS) / DB], O[r][(j - KSTEPS) % DB]);
+            }
+            if constexpr (st == 0 && (j == 1 || j == NS / 2 + 1)) {
+              if (j == setup_slot && ti - tc < NSTAGE) {
+                if (iss_idx < is_nfast && ((iss_idx & 63) != 0 || iss_idx == 0)) {
+                  const uint32_t kt = (uint32_t)__builtin_amdgcn_readlane(col_iss, iss_idx & 63);
+                  p_ktile = is_kbase + (uint64_t)kt * kt_kstride;
+                  p_vtile = v_saved;  // (ti > 0 here: the first tile of the stream never runs through this loop)
+                  v_saved = is_vbase + (uint64_t)kt * kt_vstride;
+                  p_kl = Kbase + (ti % NSTAGE) * KTILE + w * BLKK;
+                  p_vl = Vbase + ((ti + NSTAGE - 1) % NSTAGE) * VTILE + w * BLKV;
+                  p_ragged = false;
+                  p_last = TN - 1;
+                  iss_idx = iss_idx + 1;
+                  ti = ti + 1;
+                } else {
+                  other = true;
+                }
+              }
+            }
+#ifndef DAGATTN_ABL_NOLOADS  // (development: timing without the steady state's loads; results are wrong)
+            if constexpr (st == 1) {  // load x of the group (K first, then V^T) in slot x NS / LPT of the second half
+              static_assert(LPT <= NS, "at most one load per slot");
+              static_for<0, LPT>([&](auto xc) __attribute__((always_inline)) {
+                constexpr int x = decltype(xc)::value;
+                if constexpr (x * NS / LPT + (NS / LPT > 1 ? 1 : 0) == j) {
+                  if constexpr (x < IPK) {
+                    const uint32_t off = __umul24((uint32_t)min(kvrow[x], p_last), rowbytes) + kchunk;  // (rows and row sizes are far below 2^24)
+                    __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_ktile + off), (lds_ptr_t)(p_kl + x * NISS * BLKK), 16, 0, 0);
+                  } else {
+                    __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_vtile + vvo[x - IPK]), (lds_ptr_t)(p_vl + (x - IPK) * NISS * BLKV), 16, 0, 0);
+                  }
+                }
+              });
+            }
+#endif
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+#pragma unroll
+              for (int e = j * 16 / NS; e < (j + 1) * 16 / NS; ++e) {
+#ifdef DAGATTN_ABL_NOEXP  // (development: timing without the exponentials; results are wrong)
+                const float pe = Sc[r][e];
+#else
+                const float pe = __builtin_amdgcn_exp2f(Sc[r][e]);
+#endif
+                rs[r] += plast[r];  // (the one before: its result is there, this one's is not yet)
+                plast[r] = pe;
+                asm volatile("" : "+v"(rs[r]));  // keep the running sum
+                if (e & 1) {
+                  const f32x2 pp = {pprev[r], pe};
+                  const bf16x2 pk = __builtin_convertvector(pp, bf16x2);
+                  Pc[r][e >> 3][(e & 7) - 1] = pk[0];
+                  Pc[r][e >> 3][e & 7] = pk[1];
+                } else {
+                  pprev[r] = pe;
+                }
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (j == NS - 1) {
+              bool over = false;
+#pragma unroll
+              for (int r = 0; r < RB; ++r) {
+                rs[r] += plast[r];
+                plast[r] = 0.f;
+                over |= !(rs[r] < 1024.f);
+              }
+              if (__builtin_amdgcn_ballot_w64(over) != 0) overflow_fix(Sc, Pc, Sn, rs);
+#pragma unroll
+              for (int r = 0; r < RB; ++r) {
+                l[r] += rs[r];
+                rs[r] = 0.f;
+              }
+            }
+          });
+        };
 #pragma unroll 1
-    for (int n = 0; n + 1 < NT; ++n) {
+        for (; n + 1 < F; ++n) {
+          TSTAMP2(tf0);
+          sync_next();
+          TSTAMP2(tf1);
+          TACC2(1, tf0, tf1);
+          fast_tile();
+          if (other) {  // (a tile with a mask or a ragged one, the next item, the next 64 entries, the end of the stream)
+            other = false;
+            try_issue();
+          }
+          TSTAMP2(tf2);
+          TACC2(3, tf1, tf2);
+          TCOUNT(10);
+          TCOUNT(7);
+        }
+        wait_lgkmcnt(0);  // (the operands fetched ahead for a tile that takes the other path)
+        need = row_max(SB);
+        TSTAMP(t_fast);
+        TACC(1, t_first, t_fast);
+      }
+#endif
+    }
+#pragma unroll 1
+    for (; n + 1 < NT; ++n) {
       sync_next();  // tile tc - 1 is the one in flight through the pipeline, tc the new one
       msk_on = n + 1 >= F;
       mask_n = n + 1;
@@ -719,7 +987,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     TSTAMP(t_loop);
     TACC(2, t_first, t_loop);
     // The item after `nxt`: the last wave publishes what the counter gave it (-1: the list is
-    // exhausted).  Done here, in front of the item's last two barriers, which make it visible: a
+    // exhausted).  Done here, in front of the item's last barrier, which makes it visible: a
     // wait on the answer placed later would also wait for the next item's Q rows or for the
     // output stores.  Two slots, used in turn: a wave may still have to read the one written an
     // item ago.
@@ -729,67 +997,51 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
       const int v = g < n_list ? (int)g : -1;
       asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" ::"v"(lds_addr(mbox + mslot)), "v"(v) : "memory");
     }
+    TSTAMP(te0);
+    sync_next();
+    TSTAMP(te1);
     // The last scores of the item are done: the Q registers and the mask words are free for the
     // next item's rows (its node ids were loaded an item ago).  Placed after the loop above on
-    // purpose: a load of the Q registers in front of it would make the compiler wait for
-    // everything in flight there.
+    // purpose (a load of the Q registers in front of it would make the compiler wait for
+    // everything in flight there) and after the wait of sync_next, which counts tile loads only.
     if (has_next) {
       load_q(nxt);
 #pragma unroll
       for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
     }
-    sync_next();
     if (need) rescale(SB);
+    TSTAMP(te2);
     step(N_, Y, Y, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill_slot);
     step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc - 1), P1, nullptr, nullptr, refill_slot_v);
     TSTAMP(t_p1);
     TACC(4, t_loop, t_p1);
-    // ---- output.  A lane holds one row in 8-byte pieces scattered over the head dimension;
-    // stored like that, every store instruction would touch 32 rows.  The wave transposes its
-    // rows through a private 4 KiB piece of the ring slot of the tile that was finished last
-    // (free after the barrier below: the last P V steps read it; 16 rows at a time, 16-byte chunks XOR-swizzled
-    // by the row so that writes and reads are conflict free), and stores full rows: 16 lanes x 16
-    // bytes per row.
+    TACC(8, t_loop, te0);
+    TACC(9, te0, te1);
+    TACC(3, te1, te2);
+    // ---- output.  A lane holds one row in 8-byte pieces (four consecutive dimensions), the two
+    // half waves next to each other: a store instruction writes 16 bytes of each of 32 rows.  The
+    // rows' cache lines are put together in the L2 (all 16 pieces of a line come from this wave,
+    // within a microsecond), and nothing here touches LDS or waits for a load in flight.
     const int head = head_of(cur);
     const bool store = head_is_mine(cur);
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    {
-      constexpr int CPR = D / 8;  // 16-byte chunks per row
-      unsigned char* stage = (w < NW / 2 || NW == 1 ? Kbase + ((tc - 1) % NSTAGE) * KTILE
-                                                     : Vbase + ((tc - 1) % NSTAGE) * VTILE) +
-                             (w % (NW > 1 ? NW / 2 : 1)) * (16 * D * 2);
 #pragma unroll
-      for (int r = 0; r < RB; ++r) {
-        const float l_tot = l[r] + __shfl_xor(l[r], 32);
-        const float inv = 1.f / l_tot;
-        if (a.lse && store && H == 0 && row_of(cur, r) < cur.T)
-          a.lse[(size_t)token_of(cur, r) * a.hq + head] = M[r] * 0.6931471805599453f + logf(l_tot);
+    for (int r = 0; r < RB; ++r) {
+      const float l_tot = l[r] + __shfl_xor(l[r], 32);
+      const float inv = 1.f / l_tot;
+      const bool mine = store && row_of(cur, r) < cur.T;
+      if (a.lse && mine && H == 0)
+        a.lse[(size_t)token_of(cur, r) * a.hq + head] = M[r] * 0.6931471805599453f + logf(l_tot);
+      uint16_t* const orow = (uint16_t*)a.out + ((size_t)token_of(cur, r) * a.hq + head) * D + 4 * H;
+      if (mine) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {  // rows 16 half .. 16 half + 15 of the block
-          if ((L >> 4) == half) {
-            const int rr = L & 15;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-              for (int r4 = 0; r4 < 4; ++r4) {
-                u32x2 o;
-                o[0] = dag_pack_bf2(O[r][db][4 * r4] * inv, O[r][db][4 * r4 + 1] * inv);
-                o[1] = dag_pack_bf2(O[r][db][4 * r4 + 2] * inv, O[r][db][4 * r4 + 3] * inv);
-                const int c = 4 * db + r4;  // chunk of dimensions 32 db + 8 r4 .. + 7; this lane has half H of it
-                *(u32x2*)(stage + rr * (D * 2) + ((c ^ rr) % CPR) * 16 + 8 * H) = o;
-              }
+          for (int r4 = 0; r4 < 4; ++r4) {  // dimensions 32 db + 8 r4 + 4 H .. + 3
+            u32x2 o;
+            o[0] = dag_pack_bf2(O[r][db][4 * r4] * inv, O[r][db][4 * r4 + 1] * inv);
+            o[1] = dag_pack_bf2(O[r][db][4 * r4 + 2] * inv, O[r][db][4 * r4 + 3] * inv);
+            *(u32x2*)(orow + 32 * db + 8 * r4) = o;
           }
-          // read back: lane = (row, chunk); a store instruction covers 64 / CPR full rows
-#pragma unroll
-          for (int k = 0; k < 16 * CPR / 64; ++k) {
-            const int rr = k * (64 / CPR) + lane / CPR, c = lane % CPR;
-            const u32x4 o = *(const u32x4*)(stage + rr * (D * 2) + ((c ^ rr) % CPR) * 16);
-            const int row = cur.row0 + 32 * (rg * RB + r) + 16 * half + rr;
-            if (row < cur.T && store)
-              *(u32x4*)((uint16_t*)a.out + ((size_t)(cur.cu + row) * a.hq + head) * D + c * 8) = o;
-          }
-        }
       }
     }
     TSTAMP(t_o);
@@ -811,10 +1063,11 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     if (iss_next) iss_next = 0;     // the cursor was already in what is now the current item
     else cursor_enter(cur, col_nxt);  // (all tiles of the old item were issued: start of the new one)
     if (has_next) col_nxt = load_cols(nxt, 0);
-    // refill the ring (the cursor could not go past the end of the old `nxt`); the slot of tile
-    // tc - 1 stays untouched: other waves may still be reading it
+    // refill the rings (the cursor could not go past the end of the old `nxt`): group g goes into
+    // the slots of K tile g - NSTAGE and V^T tile g - 1 - NSTAGE, both read for the last time before
+    // the last barrier (tile tc - 1 was the old item's last one)
 #pragma unroll 1
-    while (ti - tc < NSTAGE - 1 && try_issue()) {
+    while (ti - tc < NSTAGE && try_issue()) {
     }
     TSTAMP(t_sw);
     TACC(5, t_o, t_sw);
@@ -858,8 +1111,8 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     const unsigned long long t_end = __builtin_amdgcn_s_memrealtime();
     const unsigned long long c_end = __builtin_amdgcn_s_memtime();
     if (w == 0) printf("shader clock during the kernel: %.0f MHz\n", (double)(c_end - c_begin) / (double)(t_end - t_begin) * 100.0);
-    printf("wave %d total %llu | first tile %llu tile loop %llu last tile + epilogue %llu out %llu switch %llu | tiles in the loop %llu items %llu load waits %llu (x10ns)\n",
-           w, t_end - t_begin, tacc[0], tacc[2], tacc[4], tacc[6], tacc[5], tacc[7], tacc[11], tacc[8]);
+    printf("wave %d total %llu | first tile %llu tile loop %llu last tile + epilogue %llu out %llu switch %llu | tiles in the loop %llu items %llu epi: mailbox %llu sync %llu q+rescale %llu | fast tiles %llu fast loop %llu (epi q) %llu (x10ns)\n",
+           w, t_end - t_begin, tacc[0], tacc[2], tacc[4], tacc[6], tacc[5], tacc[7], tacc[11], tacc[8], tacc[9], tacc[10], tacc[1], tacc[3]);
   }
 #endif
 }
@@ -867,7 +1120,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
 template <int D, int HG, int RB>
 int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
   constexpr int KPB = 64 / (D / 8);
-  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256) + 16;  // ring + item mailbox
+  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256) + 16;  // rings + node-id records + item mailbox
   if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, RB>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sm) != hipSuccess)
     return DAG_ERR_HIP;
