@@ -6,8 +6,11 @@ extern "C" size_t dag_prefill_workspace_bytes(const dag_meta_t* m, int32_t hkv, 
                                               dag_dtype_t dtype) {
   if (!m || dtype != DAG_BF16 || hkv < 1 || head_dim < 1 || m->sizes.total_ktiles < 0) return 0;
   // key-tile-wise transposed copy of V: [key tile][kv head][head_dim][tile_n] bf16, then the
-  // work-distribution counters, plus slack for aligning the caller's pointer to 256 bytes
-  return (size_t)m->sizes.total_ktiles * hkv * head_dim * m->tile_n * 2 + DAG_SCHED_INTS * 4 + 256;
+  // work-distribution counters and the tables of the 256-row query tiles, plus slack for
+  // aligning the caller's pointer to 256 bytes
+  if (m->sizes.total_qtiles < 0 || m->sizes.csr_capacity < 0) return 0;
+  return (size_t)m->sizes.total_ktiles * hkv * head_dim * m->tile_n * 2 +
+         prefill_bf16_table_bytes(m->sizes.total_qtiles, m->sizes.csr_capacity) + 256;
 }
 
 namespace {
@@ -32,7 +35,8 @@ int prefill_args(const dag_meta_t* m, const void* q, const void* k, const void* 
   if (need_qko && (!q || !k || !out)) return DAG_ERR_NULL;
   if (!v) return DAG_ERR_NULL;
   if (!m->cu_seqlens || !m->node_start || !m->tok_node || !m->node_vis || !m->qtile_start || !m->ktile_start ||
-      !m->qtile_rowptr || !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order || !m->qtile_desc)
+      !m->qtile_rowptr || !m->qtile_col || !m->qtile_flag || !m->qtile_nfull || !m->qtile_order || !m->qtile_desc ||
+      !m->block_map_off || !m->block_map)
     return DAG_ERR_NULL;
   if (!dag_aligned16(q) || !dag_aligned16(k) || !dag_aligned16(v) || !dag_aligned16(out)) return DAG_ERR_ALIGN;
   if (m->sizes.total_qtiles * (int64_t)hq > INT32_MAX) return DAG_ERR_UNSUPPORTED;
@@ -45,6 +49,16 @@ int prefill_args(const dag_meta_t* m, const void* q, const void* k, const void* 
   a->lse = lse;
   a->vt = need > 0 ? (void*)dag_align_up((size_t)(uintptr_t)ws, 256) : nullptr;
   a->sched = need > 0 ? (int32_t*)((char*)a->vt + (size_t)m->sizes.total_ktiles * hkv * head_dim * m->tile_n * 2) : nullptr;
+  a->wide_count = need > 0 ? a->sched + DAG_SCHED_INTS : nullptr;
+  a->wide_cnt = need > 0 ? a->wide_count + 64 : nullptr;
+  a->wide_pre = need > 0 ? a->wide_cnt + m->sizes.total_qtiles : nullptr;
+  a->wide_desc = need > 0 ? a->wide_pre + 8 * m->sizes.total_qtiles : nullptr;
+  a->wide_col = need > 0 ? a->wide_desc + 8 * m->sizes.total_qtiles : nullptr;
+  a->head0 = 0;
+  a->heads = hq / hkv;
+  a->n_tiles_dev = nullptr;
+  a->block_map_off = m->block_map_off;
+  a->block_map = m->block_map;
   a->cu_seqlens = m->cu_seqlens;
   a->node_start = m->node_start;
   a->tok_node = m->tok_node;

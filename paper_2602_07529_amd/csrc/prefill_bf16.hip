@@ -45,6 +45,7 @@
 // Softmax.  Online softmax in the log2 domain.  The running maximum is only raised when some row
 // of the wave exceeds it by more than 2^8 (the accumulator rescale is then rare); probabilities
 // may exceed 1 by that factor, which fp32 accumulation and the final division absorb exactly.
+#include <stdlib.h>
 #include <type_traits>
 
 #include "common.h"
@@ -147,14 +148,99 @@ __global__ void __launch_bounds__(256) k_vt_prepare(const uint16_t* __restrict__
   }
 }
 
+// 256-row query tiles.  Query heads that do not fill a four-head item are computed one head at a
+// time on four stacked 64-row tiles of the block map (eight waves = eight 32-row blocks).  The row
+// of such a tile over the key tiles follows from the dense map: a key tile is skipped when all
+// four 64-row tiles skip it, needs no mask when all of them (those inside the sequence) are FULL,
+// and takes the mask path otherwise.  Rows are stored like the 64-row ones (tiles without mask
+// first, each class ascending), the row that starts at 64-row tile qt at position rowptr[qt] of
+// its own column array: it cannot be longer than the four rows it is made of.  One wave per 64-row
+// tile; those that start no 256-row tile mark themselves with a count of -1.
+__global__ void __launch_bounds__(256) k_wide_rows(int n_seqs, int total_qtiles, const int32_t* __restrict__ qtile_start,
+                                                   const int64_t* __restrict__ block_map_off,
+                                                   const int32_t* __restrict__ cu_seqlens,
+                                                   const int32_t* __restrict__ node_start,
+                                                   const int32_t* __restrict__ ktile_start,
+                                                   const uint8_t* __restrict__ block_map,
+                                                   const int32_t* __restrict__ rowptr, int32_t* __restrict__ wide_cnt,
+                                                   int32_t* __restrict__ wide_pre, int32_t* __restrict__ wide_col) {
+  const int qt = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (qt >= total_qtiles) return;
+  const int b = dag_find_segment(qtile_start, n_seqs, qt);
+  const int ql = qt - qtile_start[b];
+  if (ql % 4 != 0) {
+    if (lane == 0) wide_cnt[qt] = -1;
+    return;
+  }
+  const int T = cu_seqlens[b + 1] - cu_seqlens[b];
+  const int KT = (T + TN - 1) / TN, QT = qtile_start[b + 1] - qtile_start[b];
+  const int nsub = min(4, QT - ql);
+  const uint8_t* rows = block_map + block_map_off[b] + (int64_t)ql * KT;
+  const int c0 = rowptr[qt];
+  int out = c0, nf = 0, last_full = -1;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int k0 = 0; k0 < KT; k0 += 64) {
+      const int k = k0 + lane;
+      bool any = false, all_full = true;
+      if (k < KT)
+        for (int i = 0; i < nsub; ++i) {
+          const uint8_t f = rows[(int64_t)i * KT + k];
+          any = any || f != DAG_TILE_SKIP;
+          all_full = all_full && f == DAG_TILE_FULL;
+        }
+      const bool want = any && (pass == 0 ? all_full : !all_full);
+      const uint64_t m = __ballot(want);
+      if (want) wide_col[out + __popcll(m & ((1ull << lane) - 1))] = k;
+      out += __popcll(m);
+      if (pass == 0 && m) last_full = k0 + 63 - __builtin_clzll(m);
+    }
+    if (pass == 0) nf = out - c0;
+  }
+  if (lane != 0) return;
+  if (nf > 0 && (last_full + 1) * TN > T) --nf;  // a ragged last key tile needs the mask path
+  wide_cnt[qt] = out - c0;
+  int32_t* d = wide_pre + (int64_t)qt * 8;
+  d[0] = cu_seqlens[b];
+  d[1] = T;
+  d[2] = ql * 64;
+  d[3] = c0;
+  d[4] = out - c0;
+  d[5] = nf;
+  d[6] = node_start[b];
+  d[7] = ktile_start[b];
+}
+
+// Launch order of the 256-row tiles: by descending tile count (ties: ascending index), as for the
+// 64-row ones; also counts them.  One wave per 64-row tile.
+__global__ void __launch_bounds__(256) k_wide_order(int total_qtiles, const int32_t* __restrict__ wide_cnt,
+                                                    const int32_t* __restrict__ wide_pre,
+                                                    int32_t* __restrict__ wide_desc, int32_t* __restrict__ wide_count) {
+  const int qt = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (qt >= total_qtiles) return;
+  const int mine = wide_cnt[qt];
+  if (mine < 0) return;
+  int oi = 0, n = 0;
+  for (int j = lane; j < total_qtiles; j += 64) {
+    const int o = wide_cnt[j];
+    oi += (o > mine) || (o == mine && j < qt);
+    n += o >= 0;
+  }
+  for (int off = 32; off; off >>= 1) {
+    oi += __shfl_xor(oi, off);
+    n += __shfl_xor(n, off);
+  }
+  if (lane < 8) wide_desc[(int64_t)oi * 8 + lane] = wide_pre[(int64_t)qt * 8 + lane];
+  if (qt == 0 && lane == 0) *wide_count = n;
+}
+
 // ---------------------------------------------------------------------------------------------
 #ifdef DAGATTN_TIMING
 __device__ unsigned long long g_tlog[4096];
 #endif
-template <int D, int HG, int RB>
-__global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillArgs a) {
-  constexpr int NRG = 2 / RB;                // groups of RB row blocks, spread over waves
-  constexpr int NW = HG * NRG;               // waves
+template <int D, int HG, int NRG>
+__global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a) {
+  constexpr int RB = 1;                      // 32-row blocks per wave
+  constexpr int NW = HG * NRG;               // waves: NRG row blocks x HG query heads
   constexpr int CH = D / 8;                  // 16-byte chunks per K row
   constexpr int KSTEPS = D / 16;             // MFMA steps of the score product
   constexpr int DB = D / 32;                 // 32-row blocks of O^T
@@ -180,10 +266,14 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   unsigned char* const Abase = smem + NSTAGE * (KTILE + VTILE);  // node ids of the keys [NSTAGE][64]
   // after them: the two-slot item mailbox (16 bytes)
 
+  // The launch covers query heads head0 .. head0 + heads - 1 of every KV head's group: HS items
+  // of HG heads per (query tile, KV head), the last one padded when heads is no multiple of HG.
+  // The number of query tiles is known to the host for the 64-row tiles of the block map and
+  // read from the workspace for the 256-row tiles derived from it.
   const int G = a.hq / a.hkv;
-  const int HS = (G + HG - 1) / HG;  // items per (query tile, KV head); the last one may be partly filled
+  const int HS = (a.heads + HG - 1) / HG;
   const int nhw = a.hkv * HS;
-  const long n_items = (long)a.total_qtiles * nhw;
+  const long n_items = (long)(a.n_tiles_dev ? sgpr(*a.n_tiles_dev) : (int)a.total_qtiles) * nhw;
 
   const int tid = threadIdx.x, w = sgpr(tid >> 6), lane = tid & 63;
   const int L = lane & 31, H = lane >> 5;
@@ -214,10 +304,10 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   };
   auto row_of = [&](const Item& I, int r) __attribute__((always_inline)) { return I.row0 + 32 * (rg * RB + r) + L; };  // row inside the sequence
   auto token_of = [&](const Item& I, int r) __attribute__((always_inline)) { return I.cu + min(row_of(I, r), I.T - 1); };
-  // When G is no multiple of HG the waves beyond the last head of the group repeat that head (they
-  // load valid rows and take part in every barrier) and store nothing.
-  auto head_of = [&](const Item& I) __attribute__((always_inline)) { return I.hk * G + min(I.hs * HG + hj, G - 1); };
-  auto head_is_mine = [&](const Item& I) __attribute__((always_inline)) { return I.hs * HG + hj < G; };
+  // The waves beyond the last head of a padded item repeat that head (they load valid rows and
+  // take part in every barrier) and store nothing.
+  auto head_of = [&](const Item& I) __attribute__((always_inline)) { return I.hk * G + a.head0 + min(I.hs * HG + hj, a.heads - 1); };
+  auto head_is_mine = [&](const Item& I) __attribute__((always_inline)) { return I.hs * HG + hj < a.heads; };
 
   // What this lane fetches in a wave-level load (LDS position 16*lane inside the block):
   //   K:   key (lane / 4) % KPB of the block, chunk 4 * (lane / (4 * KPB)) + lane % 4: four
@@ -511,7 +601,24 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     }
   };
   // ---------------------------------------------------------------- persistent loop over items
-  // (the launch has at most one workgroup per item, so the first item always exists)
+  // Reporting done: the workgroup that finishes last puts the counters back to zero for the next
+  // launch.  Relaxed on purpose: only the order of these atomic operations matters, and a release
+  // would write back and invalidate the L2 under the workgroups that are still running.
+  auto report_done = [&]() __attribute__((always_inline)) {
+    int32_t* const done = a.sched + DAG_SCHED_INTS / 2;
+    const bool last = __hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1;
+    if (last) {
+      __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return last;
+  };
+  // (a launch sized on the host has at most one workgroup per item; one sized on an upper bound
+  // of the item count may have workgroups without any)
+  if (my_rank >= n_list) {
+    if (tid == 0) report_done();
+    return;
+  }
   Item cur = load_item(my_rank);
   bool has_next = (long)my_rank + nb < n_list;
   Item nxt = has_next ? load_item(my_rank + nb) : cur;
@@ -1073,10 +1180,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
     TACC(5, t_o, t_sw);
   }
   // Every answer from the counters has arrived by now (each was waited for at the end of its
-  // item), so this workgroup's requests were served before it reports itself done, and the
-  // workgroup that finishes last can put the counters back to zero for the next launch.  Relaxed
-  // on purpose: only the order of these atomic operations matters, and a release would write
-  // back and invalidate the L2 under the workgroups that are still running.
+  // item), so this workgroup's requests were served before it reports itself done.
 #ifdef DAGATTN_TIMING
   if (tid == 0) {  // begin, end and tile count of every workgroup, printed by the one that finishes last
     __hip_atomic_store(&g_tlog[blockIdx.x * 4 + 0], t_begin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1087,10 +1191,7 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
   }
 #endif
   if (tid == 0) {
-    int32_t* const done = a.sched + DAG_SCHED_INTS / 2;
-    if (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
-      __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (report_done()) {
 #ifdef DAGATTN_TIMING
       unsigned long long t0 = ~0ull;
       for (unsigned b = 0; b < gridDim.x; ++b) {
@@ -1117,36 +1218,61 @@ __global__ void __launch_bounds__(64 * HG * (2 / RB), 1) k_prefill_bf16(PrefillA
 #endif
 }
 
-template <int D, int HG, int RB>
-int launch_one(const PrefillArgs& a, int hs, hipStream_t stream) {
+// How a KV head's G query heads are divided: `narrow` heads in items of four heads x 64 rows (the
+// last item padded when narrow is no multiple of 4), `wide` heads one at a time on 256 rows.  A
+// padded item wastes (4 - narrow % 4) / 4 of its time, a 256-row tile takes the mask path in more
+// of its tiles and idles more at the end of a short sequence; one or two heads left over go wide,
+// three are padded.
+void split_heads(int g, int* narrow, int* wide) {
+  static const int force = [] {
+    const char* e = getenv("DAGATTN_WIDE_HEADS");  // development: 0 = never wide, 1 = every left-over head
+    return e ? atoi(e) : -1;
+  }();
+  const int rem = g % 4;
+  *wide = force == 0 ? 0 : (force == 1 || rem < 3) ? rem : 0;
+  *narrow = g - *wide;
+}
+
+template <int D, int HG, int NRG>
+int launch_one(const PrefillArgs& a, long max_tiles, hipStream_t stream) {
   constexpr int KPB = 64 / (D / 8);
   constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256) + 16;  // rings + node-id records + item mailbox
-  if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, RB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+  if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, NRG>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sm) != hipSuccess)
     return DAG_ERR_HIP;
   int dev = 0, n_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
     return DAG_ERR_HIP;
-  const long n_items = (long)a.total_qtiles * a.hkv * hs;
+  const long n_items = max_tiles * a.hkv * ((a.heads + HG - 1) / HG);
   const unsigned grid = (unsigned)(n_items < n_cu ? n_items : n_cu);
-  hipLaunchKernelGGL((k_prefill_bf16<D, HG, RB>), dim3(grid), dim3(64 * HG * (2 / RB)), sm, stream, a);
+  hipLaunchKernelGGL((k_prefill_bf16<D, HG, NRG>), dim3(grid), dim3(64 * HG * NRG), sm, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
 
 template <int D>
 int launch_d(const PrefillArgs& a, hipStream_t stream) {
-  const int g = a.hq / a.hkv;
-  // Eight waves = 2 row blocks x 4 query heads of the KV head; a group size that is no multiple
-  // of 4 pads its last item (5 heads: 4 + 1 of 4), which beats narrower workgroups: a workgroup
-  // has the compute unit to itself whatever its width.
-#ifdef DAGATTN_RB2  // development variant: four waves (one per SIMD), 64 rows each; measured slower so far
-  if (g % 4 == 0) return launch_one<D, 4, 2>(a, g / 4, stream);
-#endif
-  if (g >= 3) return launch_one<D, 4, 1>(a, (g + 3) / 4, stream);
-  if (g == 2) return launch_one<D, 2, 1>(a, 1, stream);  // four waves
-  return launch_one<D, 1, 1>(a, 1, stream);              // two waves
+  int narrow, wide;
+  split_heads(a.hq / a.hkv, &narrow, &wide);
+  if (narrow > 0) {  // eight waves = 2 row blocks x 4 query heads
+    PrefillArgs b = a;
+    b.head0 = 0;
+    b.heads = narrow;
+    const int rc = launch_one<D, 4, 2>(b, (long)a.total_qtiles, stream);
+    if (rc != DAG_OK) return rc;
+  }
+  if (wide > 0) {  // eight waves = 8 row blocks of one query head; starts when the launch above has ended
+    PrefillArgs b = a;
+    b.head0 = narrow;
+    b.heads = wide;
+    b.col = a.wide_col;
+    b.qtile_desc = a.wide_desc;
+    b.n_tiles_dev = a.wide_count;
+    // (every sequence has at most a quarter of its 64-row tiles, rounded up, as 256-row tiles)
+    return launch_one<D, 1, 8>(b, ((long)a.total_qtiles + 3) / 4 + a.n_seqs, stream);
+  }
+  return DAG_OK;
 }
 
 }  // namespace
@@ -1156,6 +1282,18 @@ int launch_prepare_v(const PrefillArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL((k_vt_prepare<D>), dim3((unsigned)a.total_ktiles, (unsigned)a.hkv), dim3(256), 0, stream,
                      (const uint16_t*)a.v, (uint16_t*)a.vt, a.ktile_start, a.cu_seqlens, a.n_seqs, a.hkv, a.sched);
   DAG_LAUNCH_CHECK();
+  int narrow, wide;
+  split_heads(a.hq / a.hkv, &narrow, &wide);
+  if (wide > 0) {
+    const unsigned nblk = (unsigned)((a.total_qtiles + 3) / 4);
+    hipLaunchKernelGGL(k_wide_rows, dim3(nblk), dim3(256), 0, stream, a.n_seqs, (int)a.total_qtiles, a.qtile_start,
+                       a.block_map_off, a.cu_seqlens, a.node_start, a.ktile_start, a.block_map, a.rowptr, a.wide_cnt,
+                       a.wide_pre, a.wide_col);
+    DAG_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_wide_order, dim3(nblk), dim3(256), 0, stream, (int)a.total_qtiles, a.wide_cnt, a.wide_pre,
+                       a.wide_desc, a.wide_count);
+    DAG_LAUNCH_CHECK();
+  }
   return DAG_OK;
 }
 

@@ -24,10 +24,26 @@ struct PrefillArgs {
   const int32_t* nfull;
   const int32_t* qtile_order;
   const int32_t* qtile_desc;  // [total_qtiles][8], see dag_meta_t
+  const int64_t* block_map_off;
+  const uint8_t* block_map;
   int n_seqs, W, hq, hkv;
   int64_t total_qtiles, total_ktiles;
   float scale;
+  // bf16 path: the query heads of every KV head that one launch covers (set per launch)
+  int head0, heads;
+  const int32_t* n_tiles_dev;  // null, or where the launch reads its number of query tiles
+  // bf16 path, workspace: the 256-row query tiles derived from the block map (see k_wide_rows)
+  int32_t* wide_count;  // [1] number of 256-row tiles
+  int32_t* wide_cnt;    // [total_qtiles] tiles in the row starting at this 64-row tile, -1: none starts here
+  int32_t* wide_pre;    // [total_qtiles][8] descriptor of that row
+  int32_t* wide_desc;   // [total_qtiles][8] descriptors in launch order (wide_count of them)
+  int32_t* wide_col;    // [csr_capacity] key tiles of the rows, row of tile qt at rowptr[qt]
 };
+
+// Workspace of the bf16 path behind the transposed V: counters, then the tables above.
+inline size_t prefill_bf16_table_bytes(int64_t total_qtiles, int64_t csr_capacity) {
+  return (size_t)(DAG_SCHED_INTS + 64 + 17 * total_qtiles + csr_capacity) * 4;
+}
 
 int launch_prefill_f32(const PrefillArgs& a, int head_dim, hipStream_t stream);
 int launch_prefill_bf16_prepare_v(const PrefillArgs& a, int head_dim, hipStream_t stream);  // V -> workspace copy

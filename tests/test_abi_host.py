@@ -156,7 +156,9 @@ def test_rope_and_prefill_argument_errors():
     assert L.dag_attn_prefill(None, p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, big, None) == -1
     # workspace: the bf16 path needs room for the transposed copy of V, the fp32 path needs none
     need = L.dag_prefill_workspace_bytes(C.byref(m), 8, 128, B.DAG_BF16)
-    assert need == 1 * 8 * 128 * 64 * 2 + 512 + 256    # one key tile x 8 kv heads, counters, alignment slack
+    # one key tile x 8 kv heads; counters and the tables of the 256-row query tiles (17 ints per 64-row tile,
+    # one per non-skip tile); alignment slack
+    assert need == 1 * 8 * 128 * 64 * 2 + 4 * (128 + 64 + 17 * m.sizes.total_qtiles + m.sizes.csr_capacity) + 256
     assert L.dag_prefill_workspace_bytes(C.byref(m), 8, 128, B.DAG_F32) == 0
     assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, p, need - 1, None) == -6
     assert L.dag_attn_prefill(C.byref(m), p, p, p, p, None, 32, 8, 128, 0.1, B.DAG_BF16, None, 0, None) == -6
