@@ -315,6 +315,43 @@ int dag_attn_decode_segments(const dag_decode_seg_desc_t* desc, const void* q, c
                              const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
                              float softmax_scale, void* ws, size_t ws_bytes, void* stream);
 
+/* Prefill of new tokens against cached, paged KV (section 4.3, phase II: when a step header or
+ * a join prompt is given, its tokens are prefilled in one pass over the KV of all predecessor
+ * paths and the preceding context, concatenated by reference, without padding or copying).  Each
+ * of the n_nodes nodes has n_i >= 0 new tokens whose K/V are already in the node's own pages
+ * (dag_kv_append_rope); its context is a list of pages in token order -- the segments it reads,
+ * then its own pages -- with the number of tokens each page holds (a segment's last page may be
+ * partly filled).  New token i of a node sees every token of the pages in front of its own and
+ * its own node's tokens 0 .. own_len - n_i + i: Eq. 3 for a node whose ancestors are cached.
+ * All arrays DEVICE int32; the two bounds are HOST values the launch is sized by (a node with
+ * more new tokens or pages than the bounds say loses the excess). */
+typedef struct {
+  int32_t n_nodes, page_size;  /* page_size must be 16                                            */
+  int32_t max_new;             /* HOST upper bound on the new tokens of any node                 */
+  int32_t max_ctx_pages;       /* HOST upper bound on the pages in any node's context            */
+  const int32_t* q_off;        /* [n_nodes+1] rows of q / out that are node i's new tokens       */
+  const int32_t* ctx_page_off; /* [n_nodes+1] into ctx_pages / ctx_page_len                      */
+  const int32_t* ctx_pages;    /* page ids of every context, own pages last                      */
+  const int32_t* ctx_page_len; /* tokens in each of these pages, 0..16                           */
+  const int32_t* own_page;     /* [n_nodes] index inside its context of the node's first own page */
+  const int32_t* own_len;      /* [n_nodes] tokens in the node's own pages, the new ones included */
+} dag_paged_prefill_desc_t;
+
+/* Bytes of DEVICE workspace dag_attn_prefill_paged needs (0 on bad arguments). */
+size_t dag_prefill_paged_workspace_bytes(const dag_paged_prefill_desc_t* desc);
+
+/* q / out [q_off[n_nodes]][hq][head_dim] bf16 DEVICE (q already rotated), lse NULL or
+ * [q_off[n_nodes]][hq] fp32 DEVICE (natural logarithm of the softmax denominator, as in
+ * dag_attn_prefill); pools as in dag_attn_decode, n_pages = pages in each pool (page ids outside
+ * are clamped, never followed).  head_dim 64 or 128, hq a multiple of hkv.  The tables of work
+ * items are built on the device from the description; everything is enqueued on `stream`, the
+ * call allocates nothing and does not synchronise.  Errors: DAG_ERR_NULL, DAG_ERR_BAD_LEN,
+ * DAG_ERR_UNSUPPORTED, DAG_ERR_ALIGN, DAG_ERR_WORKSPACE, DAG_ERR_HIP. */
+int dag_attn_prefill_paged(const dag_paged_prefill_desc_t* desc, const void* q, const void* k_pool,
+                           const void* v_pool, int32_t n_pages, void* out, float* lse, int32_t hq,
+                           int32_t hkv, int32_t head_dim, float softmax_scale, void* ws,
+                           size_t ws_bytes, void* stream);
+
 /* Host-side scheduler of the execution phase (section 3.2: the plan as a Petri net whose places
  * are the DAG nodes, one transition per node with its parents as input places; section 3.3, Eq. 1:
  * the enabled-transition frontier fires as a whole and the marking advances when all of it is

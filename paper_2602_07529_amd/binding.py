@@ -72,6 +72,14 @@ class dag_decode_seg_desc_t(C.Structure):
                 [(name, C.c_void_p) for name in _SEG_ARRAYS] + [("seg_reader_len", C.c_void_p)])
 
 
+_PAGED_ARRAYS = ("q_off", "ctx_page_off", "ctx_pages", "ctx_page_len", "own_page", "own_len")
+
+
+class dag_paged_prefill_desc_t(C.Structure):
+    _fields_ = ([("n_nodes", C.c_int32), ("page_size", C.c_int32), ("max_new", C.c_int32),
+                 ("max_ctx_pages", C.c_int32)] + [(name, C.c_void_p) for name in _PAGED_ARRAYS])
+
+
 _SCHED_ARRAYS = ("live_node", "live_token", "branch_page_off", "branch_pages", "branch_len", "branch_pos",
                  "seg_node", "seg_page_off", "seg_pages", "seg_len", "seg_reader_off", "seg_readers",
                  "seg_reader_len", "branch_entry_off", "branch_entries")
@@ -119,6 +127,10 @@ def lib():
         L.dag_decode_segments_workspace_bytes.restype = C.c_size_t
         L.dag_attn_decode_segments.argtypes = [C.POINTER(dag_decode_seg_desc_t), vp, vp, vp, vp, i32, i32, i32, f32,
                                                vp, C.c_size_t, vp]
+        L.dag_prefill_paged_workspace_bytes.argtypes = [C.POINTER(dag_paged_prefill_desc_t)]
+        L.dag_prefill_paged_workspace_bytes.restype = C.c_size_t
+        L.dag_attn_prefill_paged.argtypes = [C.POINTER(dag_paged_prefill_desc_t), vp, vp, vp, i32, vp, vp, i32, i32,
+                                             i32, f32, vp, C.c_size_t, vp]
         L.dag_sched_create.argtypes = [i32, vp, vp, vp, vp, i32, i32, C.POINTER(vp)]
         L.dag_sched_destroy.argtypes = [vp]
         L.dag_sched_destroy.restype = None
@@ -129,7 +141,7 @@ def lib():
         for name in ("dag_prefill_tile_shape", "dag_meta_sizes", "dag_build_meta", "dag_rope_qk",
                      "dag_attn_prefill", "dag_attn_prefill_prepared", "dag_prefill_prepare_v",
                      "dag_kv_append_rope", "dag_attn_decode", "dag_attn_decode_static", "dag_attn_decode_segments",
-                     "dag_sched_create",
+                     "dag_sched_create", "dag_attn_prefill_paged",
                      "dag_attn_prefill_bwd",
                      "dag_sched_step"):
             getattr(L, name).restype = C.c_int
@@ -360,6 +372,39 @@ def dag_attn_decode_segments(sdesc, q, k_pool, v_pool, out, workspace, softmax_s
         softmax_scale = 1.0 / float(d) ** 0.5
     _check(lib().dag_attn_decode_segments(C.byref(sdesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(out), hq, hkv,
                                           d, float(softmax_scale), _ptr(workspace), workspace.numel(), _stream()))
+
+
+class PagedPrefillDesc:
+    """Device copies of the paged-prefill description arrays + the ctypes struct.  `desc`: dict with the six
+    arrays of dag_paged_prefill_desc_t (host, int32) and page_size."""
+
+    def __init__(self, desc, device):
+        self.t = {}
+        for name in _PAGED_ARRAYS:
+            arr = np.ascontiguousarray(desc[name], dtype=np.int32)
+            self.t[name] = torch.from_numpy(arr if arr.size else np.zeros(1, np.int32)).to(device)
+        q_off = np.asarray(desc["q_off"])
+        p_off = np.asarray(desc["ctx_page_off"])
+        n_nodes = len(q_off) - 1
+        self.n_rows = int(q_off[-1])
+        self.c = dag_paged_prefill_desc_t(n_nodes, int(desc["page_size"]),
+                                          int(np.diff(q_off).max()) if n_nodes else 0,
+                                          int(np.diff(p_off).max()) if n_nodes else 0,
+                                          *[self.t[n].data_ptr() for n in _PAGED_ARRAYS])
+
+
+def dag_prefill_paged_workspace_bytes(pdesc):
+    return int(lib().dag_prefill_paged_workspace_bytes(C.byref(pdesc.c)))
+
+
+def dag_attn_prefill_paged(pdesc, q, k_pool, v_pool, out, workspace, lse=None, softmax_scale=None):
+    _, hq, d = q.shape
+    hkv = k_pool.shape[1]
+    if softmax_scale is None:
+        softmax_scale = 1.0 / float(d) ** 0.5
+    _check(lib().dag_attn_prefill_paged(C.byref(pdesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), k_pool.shape[0],
+                                        _ptr(out), _ptr(lse) if lse is not None else None, hq, hkv, d,
+                                        float(softmax_scale), _ptr(workspace), workspace.numel(), _stream()))
 
 
 class Scheduler:

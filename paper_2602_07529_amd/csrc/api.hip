@@ -119,6 +119,72 @@ extern "C" int dag_attn_prefill(const dag_meta_t* m, const void* q, const void* 
   return rp != DAG_OK ? rp : launch_prefill_bf16(a, head_dim, stream);
 }
 
+namespace {
+// slots of (node, query tile) and tiles per slot that the host bounds allow
+bool paged_dims(const dag_paged_prefill_desc_t* d, int64_t* slots, int64_t* nt_max) {
+  if (!d || d->n_nodes < 0 || d->max_new < 0 || d->max_ctx_pages < 0 || d->page_size != 16) return false;
+  *slots = (int64_t)d->n_nodes * ((d->max_new + 63) / 64);
+  *nt_max = (d->max_ctx_pages + 3) / 4;
+  return *slots * 8 * *nt_max <= INT32_MAX;  // (entries are indexed with 32-bit integers)
+}
+}  // namespace
+
+extern "C" size_t dag_prefill_paged_workspace_bytes(const dag_paged_prefill_desc_t* d) {
+  int64_t slots, nt_max;
+  if (!paged_dims(d, &slots, &nt_max)) return 0;
+  // counters, item count, per slot: tile count, two descriptors, its row of tile entries
+  return (size_t)(DAG_SCHED_INTS + 64 + slots * (17 + 8 * nt_max)) * 4 + 256;
+}
+
+extern "C" int dag_attn_prefill_paged(const dag_paged_prefill_desc_t* d, const void* q, const void* k_pool,
+                                      const void* v_pool, int32_t n_pages, void* out, float* lse, int32_t hq,
+                                      int32_t hkv, int32_t head_dim, float softmax_scale, void* ws, size_t ws_bytes,
+                                      void* stream_) {
+  if (!d) return DAG_ERR_NULL;
+  if (d->page_size != 16) return DAG_ERR_UNSUPPORTED;
+  if (hq < 1 || hkv < 1 || hq % hkv != 0 || (head_dim != 64 && head_dim != 128)) return DAG_ERR_UNSUPPORTED;
+  int64_t slots, nt_max;
+  if (d->n_nodes < 0 || d->max_new < 0 || d->max_ctx_pages < 0 || n_pages < 0) return DAG_ERR_BAD_LEN;
+  if (!paged_dims(d, &slots, &nt_max)) return DAG_ERR_UNSUPPORTED;
+  if (slots == 0) return DAG_OK;  // no new token anywhere
+  if (nt_max == 0 || n_pages == 0) return DAG_ERR_BAD_LEN;  // new tokens live in pages of their own
+  if (!q || !k_pool || !v_pool || !out || !d->q_off || !d->ctx_page_off || !d->ctx_pages || !d->ctx_page_len ||
+      !d->own_page || !d->own_len)
+    return DAG_ERR_NULL;
+  if (!dag_aligned16(q) || !dag_aligned16(k_pool) || !dag_aligned16(v_pool) || !dag_aligned16(out)) return DAG_ERR_ALIGN;
+  if (!ws || ws_bytes < dag_prefill_paged_workspace_bytes(d)) return DAG_ERR_WORKSPACE;
+  PagedPrefillArgs pa = {};
+  PrefillArgs& a = pa.a;
+  a.q = q;
+  a.k = k_pool;
+  a.vt = const_cast<void*>(v_pool);
+  a.out = out;
+  a.lse = lse;
+  a.sched = (int32_t*)dag_align_up((size_t)(uintptr_t)ws, 256);
+  a.wide_count = a.sched + DAG_SCHED_INTS;
+  a.wide_cnt = a.wide_count + 64;
+  a.wide_pre = a.wide_cnt + slots;
+  a.wide_desc = a.wide_pre + 8 * slots;
+  a.wide_col = a.wide_desc + 8 * slots;
+  a.W = 1;
+  a.hq = hq;
+  a.hkv = hkv;
+  a.head0 = 0;
+  a.heads = hq / hkv;
+  a.scale = softmax_scale;
+  pa.n_nodes = d->n_nodes;
+  pa.qt_max = (d->max_new + 63) / 64;
+  pa.nt_max = (int)nt_max;
+  pa.n_pages = n_pages;
+  pa.q_off = d->q_off;
+  pa.ctx_page_off = d->ctx_page_off;
+  pa.ctx_pages = d->ctx_pages;
+  pa.ctx_page_len = d->ctx_page_len;
+  pa.own_page = d->own_page;
+  pa.own_len = d->own_len;
+  return launch_prefill_paged(pa, head_dim, (hipStream_t)stream_);
+}
+
 extern "C" const char* dag_strerror(int code) {
   switch (code) {
     case DAG_OK: return "ok";

@@ -109,6 +109,21 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {  // byte address i
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
+// LDS byte offsets of the MFMA operands inside a tile, after the per-lane part (koff / voff in the
+// kernel, where the layouts are described): K operand of MFMA step s of key half h, and V^T
+// operand of key step st (16 keys) for output block db.
+template <int D, bool PAGED>
+__device__ constexpr int k_imm(int h, int s) {
+  constexpr int KPB = 64 / (D / 8), BLKK = 1024 + 16, IPK = (TN / KPB) / 8;
+  return PAGED ? (4 * h + (s >> 1) / IPK + 8 * ((s >> 1) % IPK)) * BLKK + (s & 1) * 512
+               : h * (32 / KPB) * BLKK + (s >> 1) * 64 * KPB + (s & 1) * 32;
+}
+template <int D, bool PAGED>
+__device__ constexpr int v_imm(int st, int db) {
+  constexpr int BLKV = 1024 + 16 * 8, IPV = (D / 8) / 8;
+  return PAGED ? (2 * st + db / IPV + 8 * (db % IPV)) * BLKV : db * 4 * BLKV + st * 256;
+}
+
 struct Item {  // wave-uniform description of a work item
   int cu, T, row0, c0, N, nfast, nstart, ktb, hk, hs;
 };
@@ -218,7 +233,7 @@ __global__ void __launch_bounds__(256) k_wide_order(int total_qtiles, const int3
   const int qt = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (qt >= total_qtiles) return;
   const int mine = wide_cnt[qt];
-  if (mine < 0) return;
+  if (mine < 0 && qt != 0) return;
   int oi = 0, n = 0;
   for (int j = lane; j < total_qtiles; j += 64) {
     const int o = wide_cnt[j];
@@ -229,15 +244,86 @@ __global__ void __launch_bounds__(256) k_wide_order(int total_qtiles, const int3
     oi += __shfl_xor(oi, off);
     n += __shfl_xor(n, off);
   }
-  if (lane < 8) wide_desc[(int64_t)oi * 8 + lane] = wide_pre[(int64_t)qt * 8 + lane];
+  if (mine >= 0 && lane < 8) wide_desc[(int64_t)oi * 8 + lane] = wide_pre[(int64_t)qt * 8 + lane];
   if (qt == 0 && lane == 0) *wide_count = n;
+}
+
+// Work items of the paged prefill (section 4.3, phase II: the new tokens of a node are prefilled
+// against the cached KV of its predecessors, which is only referenced, never copied).  One wave
+// per (node, 64-row tile of its new tokens); slots past the node's last tile mark themselves with
+// a count of -1.  The context of the node is cut into tiles of four pages in its own order; the
+// row of a query tile lists the tiles up to the last row's own position, those that need no mask
+// first (four full pages, all in front of the first row's position).  An entry is {four page
+// ids, their token counts (one byte each), tile index, 0, 0}; pages past the end of the context
+// repeat its first page with a count of zero, page ids are clamped to the pool.
+__global__ void __launch_bounds__(256) k_paged_rows(int n_nodes, int qt_max, int nt_max, int n_pages,
+                                                    const int32_t* __restrict__ q_off,
+                                                    const int32_t* __restrict__ ctx_page_off,
+                                                    const int32_t* __restrict__ ctx_pages,
+                                                    const int32_t* __restrict__ ctx_page_len,
+                                                    const int32_t* __restrict__ own_page,
+                                                    const int32_t* __restrict__ own_len, int32_t* __restrict__ sched,
+                                                    int32_t* __restrict__ cnt_out, int32_t* __restrict__ pre,
+                                                    int32_t* __restrict__ tiles) {
+  const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (blockIdx.x == 0 && threadIdx.x < DAG_SCHED_INTS) sched[threadIdx.x] = 0;  // work counters of the attention kernel
+  if (slot >= n_nodes * qt_max) return;
+  const int node = slot / qt_max, qt = slot % qt_max;
+  const int n = q_off[node + 1] - q_off[node];
+  const int p0 = ctx_page_off[node], np = ctx_page_off[node + 1] - p0;
+  if (qt * TM >= n || np < 1) {
+    if (lane == 0) cnt_out[slot] = -1;
+    return;
+  }
+  const int nstart = own_page[node] * 16 + own_len[node] - n;  // context slot of the node's first new token
+  const int lim_first = nstart + qt * TM, lim_last = nstart + min(qt * TM + TM - 1, n - 1);
+  const int NT = min(min(lim_last / TN + 1, (np + 3) / 4), nt_max);
+  int32_t* const row = tiles + (int64_t)slot * nt_max * 8;
+  int out = 0, nf = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int t0 = 0; t0 < NT; t0 += 64) {
+      const int t = t0 + lane;
+      int pg[4], ln[4];
+      bool full = t < NT && t * TN + TN - 1 <= lim_first;
+      for (int i = 0; i < 4; ++i) {
+        const bool have = t < NT && 4 * t + i < np;
+        pg[i] = min(max(ctx_pages[p0 + (have ? 4 * t + i : 0)], 0), n_pages - 1);
+        ln[i] = have ? min(max(ctx_page_len[p0 + 4 * t + i], 0), 16) : 0;
+        full = full && ln[i] == 16;
+      }
+      const bool want = t < NT && (pass == 0 ? full : !full);
+      const uint64_t m = __ballot(want);
+      if (want) {
+        int32_t* e = row + (int64_t)(out + __popcll(m & ((1ull << lane) - 1))) * 8;
+        for (int i = 0; i < 4; ++i) e[i] = pg[i];
+        e[4] = ln[0] | ln[1] << 8 | ln[2] << 16 | ln[3] << 24;
+        e[5] = t;
+        e[6] = e[7] = 0;
+      }
+      out += __popcll(m);
+    }
+    if (pass == 0) nf = out;
+  }
+  if (lane != 0) return;
+  cnt_out[slot] = out;
+  int32_t* d = pre + (int64_t)slot * 8;
+  d[0] = q_off[node];
+  d[1] = n;
+  d[2] = qt * TM;
+  d[3] = slot * nt_max;
+  d[4] = out;
+  d[5] = nf;
+  d[6] = nstart;
+  d[7] = 0;
 }
 
 // ---------------------------------------------------------------------------------------------
 #ifdef DAGATTN_TIMING
 __device__ unsigned long long g_tlog[4096];
 #endif
-template <int D, int HG, int NRG>
+// PAGED: K and V^T tiles come from the paged pools of the decode path through a list of pages per
+// work item instead of from the packed sequence (see k_paged_rows); the pipeline is the same.
+template <int D, int HG, int NRG, bool PAGED>
 __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a) {
   constexpr int RB = 1;                      // 32-row blocks per wave
   constexpr int NW = HG * NRG;               // waves: NRG row blocks x HG query heads
@@ -259,6 +345,7 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
   constexpr float TH_LOG2 = 8.f;
   static_assert(IPK >= 1 && IPK * NISS == NBK && IPV >= 1 && IPV * NISS == NBV, "tile loads must divide over the waves");
   static_assert((NSTAGE - 2) * LPT < 64 && NSTAGE >= 3, "vmcnt range / ring depth");
+  static_assert(!PAGED || NW == 8, "the paged tile layout is laid out for eight issuing waves");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* const Kbase = smem;                    // K[NSTAGE][KTILE]
@@ -314,10 +401,15 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
   //        consecutive lanes fetch 64 consecutive bytes of one row (one cache-line lookup)
   //   V^T: piece `lane` of the block (the workspace copy already has the LDS order)
   // Addresses are a wave-uniform 64-bit base plus one 32-bit per-lane offset.
+  // PAGED: a load fetches a 1 KiB piece of a page, the pools' layouts being what the MFMA operands
+  // need: K piece = 4 chunks x 16 tokens x 16 bytes, fetched as it lies; V piece = 32 dimensions x
+  // 16 tokens, of which LDS position u holds dimension 16 (u / 32) + u % 16, token half (u / 16) % 2
+  // (the 16 lanes that read an operand together then read 256 consecutive bytes).
   const int kkey = (lane >> 2) % KPB;
   const uint32_t kchunk = (4 * (lane / (4 * KPB)) + (lane & 3)) * 16;
-  const uint32_t ksrc = kkey * rowbytes + kchunk;
-  const uint32_t vsrc = lane * 16;
+  const uint32_t ksrc = PAGED ? lane * 16 : kkey * rowbytes + kchunk;
+  const uint32_t vsrc = PAGED ? (2 * (16 * (lane / 32) + lane % 16) + (lane / 16) % 2) * 16 : lane * 16;
+  constexpr uint32_t VSTEP = PAGED ? 1024 : NISS * 1024;  // from a wave's V^T load to its next one
   // The steady state issues its loads without a decision: the row a lane fetches in K load i of
   // a tile (clamped to the tile's last valid row, which only matters in a ragged tile) and the
   // per-lane offset of V^T load i.
@@ -326,11 +418,14 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
 #pragma unroll
   for (int i = 0; i < IPK; ++i) kvrow[i] = (w + NISS * i) * KPB + kkey;
 #pragma unroll
-  for (int i = 0; i < IPV; ++i) vvo[i] = (uint32_t)i * (NISS * 1024) + vsrc;
+  for (int i = 0; i < IPV; ++i) vvo[i] = (uint32_t)i * VSTEP + vsrc;
 
   // kbase / vbase: the cursor item's K rows (token cu, head hk) and V^T tiles (tile ktb, head hk,
   // this wave's block); the tile adds a multiple of its index.
-  const uint32_t kt_kstride = (uint32_t)TN * rowbytes, kt_vstride = (uint32_t)a.hkv * (D * TN * 2);
+  // PAGED: the pools' bases at the KV head and at this wave's pieces; the page adds a multiple of
+  // its id (a page holds 16 tokens: D * 32 bytes per head in either pool).
+  const uint32_t kt_kstride = PAGED ? (uint32_t)a.hkv * (D * 32) : (uint32_t)TN * rowbytes;
+  const uint32_t kt_vstride = PAGED ? (uint32_t)a.hkv * (D * 32) : (uint32_t)a.hkv * (D * TN * 2);
   // Issuing a tile is split into a set-up (addresses of the tile, optional node-id record) and
   // LPT single loads, so that the pipeline can spread them over the slots of a step, in the
   // shadow of the MFMAs; issue_loads does all of it at once.
@@ -350,7 +445,7 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
                          bool with_nodes) __attribute__((always_inline)) {
     const unsigned slot = g % NSTAGE, vslot = (g + NSTAGE - 1) % NSTAGE;
     const int j0 = kt * TN;
-    if (with_nodes) {  // a tile that needs the mask: node ids of its 64 keys (every wave writes the same record)
+    if (!PAGED && with_nodes) {  // a tile that needs the mask: node ids of its 64 keys (every wave writes the same record)
       const int32_t* np = a.tok_node + cu + min(j0 + lane, T - 1);
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)np, (lds_ptr_t)(Abase + slot * 256), 4, 0, 0);
     }
@@ -360,8 +455,8 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
     v_saved = v_mine;
     p_kl = Kbase + slot * KTILE + w * BLKK;
     p_vl = Vbase + vslot * VTILE + w * BLKV;
-    p_ragged = j0 + TN > T;  // ragged last tile: rows past the end re-read the last valid row (masked later)
-    p_last = T - 1 - j0;
+    p_ragged = !PAGED && j0 + TN > T;  // ragged last tile: rows past the end re-read the last valid row (masked later)
+    p_last = PAGED ? TN - 1 : T - 1 - j0;
   };
   auto issue_setup_flush = [&](unsigned g) __attribute__((always_inline)) {  // the stream's last group: V^T of the last tile (its K once more)
     p_vtile = v_saved;
@@ -370,7 +465,9 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
   };
   auto issue_part = [&](int i) __attribute__((always_inline)) {  // i = 0 .. LPT - 1, a compile-time constant at every call site
     if (i < IPK) {
-      if (!p_ragged) {
+      if (PAGED) {
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_ktile + (i * 1024 + ksrc)), (lds_ptr_t)(p_kl + i * NISS * BLKK), 16, 0, 0);
+      } else if (!p_ragged) {
         __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_ktile + (size_t)((w + NISS * i) * KPB) * rowbytes + ksrc),
                                          (lds_ptr_t)(p_kl + i * NISS * BLKK), 16, 0, 0);
       } else {
@@ -380,7 +477,7 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       }
     } else {  // the transposed copy is zero padded: no ragged case
       const int iv = i - IPK;
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_vtile + iv * (NISS * 1024) + vsrc),
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_vtile + (iv * VSTEP + vsrc)),
                                        (lds_ptr_t)(p_vl + iv * NISS * BLKV), 16, 0, 0);
     }
   };
@@ -388,9 +485,14 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
   // LDS read addresses (bytes inside a tile); every other read of the tile is an immediate away.
   //   K, MFMA step s of key half h:      koff + h * (32 / KPB) * BLKK + (s / 2) * 64 * KPB + (s % 2) * 32
   //   V^T, key step st, output block db: voff + db * 4 * BLKV + st * 256
+  // PAGED: wave w's load i of a tile (LDS block w + NISS i) is piece (w % 2) IPK + i of page w / 2,
+  // so piece s of page p sits in block 2 p + s / IPK + NISS (s % IPK).  K chunk 2 s + H of key k:
+  // page k / 16, piece s / 2, position (2 (s % 2) + H) 256 + (k % 16) 16; V^T dimensions of output
+  // block db, keys of step st: page st, piece db, position 512 (L / 16) + 256 H + 16 (L % 16).
   const int krow = key_of_row(L);
-  const uint32_t koff = (krow / KPB) * BLKK + (krow % KPB) * 64 + H * 16;
-  const uint32_t voff = (L / 8) * BLKV + (L % 8) * 16 + H * 128;
+  const uint32_t koff = PAGED ? 2 * (krow / 16) * BLKK + (krow % 16) * 16 + H * 256
+                              : (krow / KPB) * BLKK + (krow % KPB) * 64 + H * 16;
+  const uint32_t voff = PAGED ? (L / 16) * 512 + H * 256 + (L % 16) * 16 : (L / 8) * BLKV + (L % 8) * 16 + H * 128;
 
   f32x16 O[RB][DB];
   // Scores are kept relative to a reference maximum per row, in the exponent's units: the Q rows
@@ -521,11 +623,11 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       if constexpr (i < NQ)
         asm volatile("ds_read_b128 %0, %1 offset:%2"
                      : "=v"(op[i])
-                     : "v"(ka), "n"(HQ * (32 / KPB) * BLKK + (i >> 1) * 64 * KPB + (i & 1) * 32));
+                     : "v"(ka), "n"(k_imm<D, PAGED>(HQ, i)));
       else if constexpr (i < NSLOT)
         asm volatile("ds_read_b128 %0, %1 offset:%2"
                      : "=v"(op[i])
-                     : "v"(va), "n"(((i - NQ) % DB) * 4 * BLKV + (2 * HV + (i - NQ) / DB) * 256));
+                     : "v"(va), "n"(v_imm<D, PAGED>(2 * HV + (i - NQ) / DB, (i - NQ) % DB)));
     };
     static_for<0, (PF < NSLOT ? PF : NSLOT)>(fetch);
     __builtin_amdgcn_sched_barrier(0);
@@ -641,11 +743,22 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
   // prefetches with its wait).  col_nxt is the same for the first 64 entries of the next item.
   int is_cu, is_T, is_c0, is_N, is_nfast, col_iss, col_nxt;
   const unsigned char *is_kbase, *is_vbase;
-  auto load_cols = [&](const Item& I, int first) __attribute__((always_inline)) { return a.col[I.c0 + min(first + lane, I.N - 1)]; };
+  // PAGED: an entry of the item's list is a tile of four pages {page ids, token counts (a byte
+  // each), tile index in the context, -}; a wave only needs the page it fetches pieces of.
+  auto col_at = [&](int c0, int N, int first) __attribute__((always_inline)) {
+    const int e = c0 + min(first + lane, N - 1);
+    return PAGED ? a.col[(size_t)e * 8 + (w >> 1)] : a.col[e];
+  };
+  auto load_cols = [&](const Item& I, int first) __attribute__((always_inline)) { return col_at(I.c0, I.N, first); };
   auto cursor_enter = [&](const Item& I, int cols) __attribute__((always_inline)) {
     is_cu = I.cu; is_T = I.T; is_c0 = I.c0; is_N = I.N; is_nfast = I.nfast;
-    is_kbase = kg + ((size_t)I.cu * a.hkv + I.hk) * (D * 2);
-    is_vbase = vtg + ((size_t)I.ktb * a.hkv + I.hk) * (size_t)(D * TN * 2) + w * 1024;
+    if (PAGED) {
+      is_kbase = kg + (size_t)I.hk * (D * 32) + (w & 1) * (IPK * 1024);
+      is_vbase = vtg + (size_t)I.hk * (D * 32) + (w & 1) * (IPV * 1024);
+    } else {
+      is_kbase = kg + ((size_t)I.cu * a.hkv + I.hk) * (D * 2);
+      is_vbase = vtg + ((size_t)I.ktb * a.hkv + I.hk) * (size_t)(D * TN * 2) + w * 1024;
+    }
     col_iss = cols;
     iss_idx = 0;
   };
@@ -672,7 +785,7 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       issue_setup_flush(ti);
     } else {
       if ((iss_idx & 63) == 0 && iss_idx != 0) {  // rows with more than 64 tiles: next 64 entries
-        col_iss = a.col[is_c0 + min(iss_idx + lane, is_N - 1)];
+        col_iss = col_at(is_c0, is_N, iss_idx);
         asm volatile("" ::"v"(col_iss));  // the wait for this load belongs here, not on the common path
       }
       const int kt = __builtin_amdgcn_readlane(col_iss, iss_idx & 63);
@@ -762,11 +875,11 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
   uint64_t vis0[RB];
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
-    rnode[r] = a.tok_node[token_of(cur, r)];
-    rnode_nxt[r] = has_next ? a.tok_node[token_of(nxt, r)] : 0;
+    rnode[r] = PAGED ? 0 : a.tok_node[token_of(cur, r)];
+    rnode_nxt[r] = !PAGED && has_next ? a.tok_node[token_of(nxt, r)] : 0;
   }
 #pragma unroll
-  for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(cur.nstart + rnode[r]) * a.W];
+  for (int r = 0; r < RB; ++r) vis0[r] = PAGED ? 0 : a.node_vis[(int64_t)(cur.nstart + rnode[r]) * a.W];
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -804,6 +917,27 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
     // node sees the segment's node (Eq. 3); the causal / length limit is one more AND.  Called
     // when tile n of the row (ring tile tc) has become visible, before its scores are masked.
     auto tile_mask = [&](int n) __attribute__((always_inline)) {
+      if constexpr (PAGED) {
+        // A page of the context holds its first `count` tokens (a byte per page in the entry's word
+        // 4); row i of the node's new tokens sees the slots of the context up to nstart + i (its
+        // own position: everything in front belongs to its ancestors or to itself).
+        int cw, tix;
+        const int32_t* ep = a.col + (size_t)sgpr(cur.c0 + n) * 8 + 4;
+        asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %2, 0x4\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(cw), "=&s"(tix)
+                     : "s"(ep)
+                     : "memory");
+        uint64_t valid = 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) valid |= ((1ull << ((cw >> (8 * p)) & 31)) - 1) << (16 * p);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+          const int cnt = cur.nstart + min(row_of(cur, r), cur.T - 1) - tix * TN + 1;
+          const uint64_t lim = cnt >= 64 ? ~0ull : (cnt <= 0 ? 0ull : ((1ull << cnt) - 1));
+          rmsk[r] = (valid & lim) >> (8 * H);
+        }
+        return;
+      }
       int kt;
       const int32_t* cp = a.col + sgpr(cur.c0 + n);
       asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(kt) : "s"(cp) : "memory");
@@ -887,17 +1021,17 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
           bf16x8* const op = opr;
           if constexpr (i >= 2 * NS) {
             constexpr int q = i - 2 * NS;
-            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(op[i % RING]) : "v"(kn), "n"((q >> 1) * 64 * KPB + (q & 1) * 32));
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(op[i % RING]) : "v"(kn), "n"(k_imm<D, PAGED>(0, q)));
           } else if constexpr (i % NS < KSTEPS) {
             constexpr int st = i / NS, j = i % NS;
             asm volatile("ds_read_b128 %0, %1 offset:%2"
                          : "=v"(op[i % RING])
-                         : "v"(ka), "n"(st * (32 / KPB) * BLKK + (j >> 1) * 64 * KPB + (j & 1) * 32));
+                         : "v"(ka), "n"(k_imm<D, PAGED>(st, j)));
           } else {
             constexpr int st = i / NS, j = i % NS - KSTEPS;
             asm volatile("ds_read_b128 %0, %1 offset:%2"
                          : "=v"(op[i % RING])
-                         : "v"(va), "n"((j % DB) * 4 * BLKV + (2 * st + j / DB) * 256));
+                         : "v"(va), "n"(v_imm<D, PAGED>(2 * st + j / DB, j % DB)));
           }
         };
         // The reference maximum is not looked after before the exponentials here: a row's sum of
@@ -1007,7 +1141,7 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
                 constexpr int x = decltype(xc)::value;
                 if constexpr (x * NS / LPT + (NS / LPT > 1 ? 1 : 0) == j) {
                   if constexpr (x < IPK) {
-                    const uint32_t off = __umul24((uint32_t)min(kvrow[x], p_last), rowbytes) + kchunk;  // (rows and row sizes are far below 2^24)
+                    const uint32_t off = PAGED ? x * 1024 + ksrc : __umul24((uint32_t)min(kvrow[x], p_last), rowbytes) + kchunk;  // (rows and row sizes are far below 2^24)
                     __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_ktile + off), (lds_ptr_t)(p_kl + x * NISS * BLKK), 16, 0, 0);
                   } else {
                     __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p_vtile + vvo[x - IPK]), (lds_ptr_t)(p_vl + (x - IPK) * NISS * BLKV), 16, 0, 0);
@@ -1113,8 +1247,10 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
     // everything in flight there) and after the wait of sync_next, which counts tile loads only.
     if (has_next) {
       load_q(nxt);
+      if (!PAGED) {
 #pragma unroll
-      for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
+        for (int r = 0; r < RB; ++r) vis0[r] = a.node_vis[(int64_t)(nxt.nstart + rnode_nxt[r]) * a.W];
+      }
     }
     if (need) rescale(SB);
     TSTAMP(te2);
@@ -1165,7 +1301,7 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
       rnode[r] = rnode_nxt[r];
-      if (has_next) rnode_nxt[r] = a.tok_node[token_of(nxt, r)];
+      if (!PAGED && has_next) rnode_nxt[r] = a.tok_node[token_of(nxt, r)];
     }
     if (iss_next) iss_next = 0;     // the cursor was already in what is now the current item
     else cursor_enter(cur, col_nxt);  // (all tiles of the old item were issued: start of the new one)
@@ -1233,11 +1369,11 @@ void split_heads(int g, int* narrow, int* wide) {
   *narrow = g - *wide;
 }
 
-template <int D, int HG, int NRG>
+template <int D, int HG, int NRG, bool PAGED = false>
 int launch_one(const PrefillArgs& a, long max_tiles, hipStream_t stream) {
   constexpr int KPB = 64 / (D / 8);
   constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256) + 16;  // rings + node-id records + item mailbox
-  if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, NRG>, hipFuncAttributeMaxDynamicSharedMemorySize,
+  if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, NRG, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sm) != hipSuccess)
     return DAG_ERR_HIP;
   int dev = 0, n_cu = 0;
@@ -1246,7 +1382,7 @@ int launch_one(const PrefillArgs& a, long max_tiles, hipStream_t stream) {
     return DAG_ERR_HIP;
   const long n_items = max_tiles * a.hkv * ((a.heads + HG - 1) / HG);
   const unsigned grid = (unsigned)(n_items < n_cu ? n_items : n_cu);
-  hipLaunchKernelGGL((k_prefill_bf16<D, HG, NRG>), dim3(grid), dim3(64 * HG * NRG), sm, stream, a);
+  hipLaunchKernelGGL((k_prefill_bf16<D, HG, NRG, PAGED>), dim3(grid), dim3(64 * HG * NRG), sm, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
@@ -1299,6 +1435,25 @@ int launch_prepare_v(const PrefillArgs& a, hipStream_t stream) {
 
 int launch_prefill_bf16_prepare_v(const PrefillArgs& a, int head_dim, hipStream_t stream) {
   return head_dim == 128 ? launch_prepare_v<128>(a, stream) : launch_prepare_v<64>(a, stream);
+}
+
+int launch_prefill_paged(const PagedPrefillArgs& pa, int head_dim, hipStream_t stream) {
+  const int slots = pa.n_nodes * pa.qt_max;
+  const unsigned nblk = (unsigned)((slots + 3) / 4);
+  const PrefillArgs& a = pa.a;
+  hipLaunchKernelGGL(k_paged_rows, dim3(nblk), dim3(256), 0, stream, pa.n_nodes, pa.qt_max, pa.nt_max, pa.n_pages,
+                     pa.q_off, pa.ctx_page_off, pa.ctx_pages, pa.ctx_page_len, pa.own_page, pa.own_len, a.sched,
+                     a.wide_cnt, a.wide_pre, a.wide_col);
+  DAG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_wide_order, dim3(nblk), dim3(256), 0, stream, slots, a.wide_cnt, a.wide_pre, a.wide_desc,
+                     a.wide_count);
+  DAG_LAUNCH_CHECK();
+  PrefillArgs b = a;
+  b.col = a.wide_col;
+  b.qtile_desc = a.wide_desc;
+  b.n_tiles_dev = a.wide_count;
+  // (query heads in items of four, the last item padded)
+  return head_dim == 128 ? launch_one<128, 4, 2, true>(b, slots, stream) : launch_one<64, 4, 2, true>(b, slots, stream);
 }
 
 int launch_prefill_bf16(const PrefillArgs& a, int head_dim, hipStream_t stream) {

@@ -45,6 +45,16 @@ inline size_t prefill_bf16_table_bytes(int64_t total_qtiles, int64_t csr_capacit
   return (size_t)(DAG_SCHED_INTS + 64 + 17 * total_qtiles + csr_capacity) * 4;
 }
 
+// Paged prefill: the kernel argument block (q, k = K pool, vt = V pool, out, lse, sched, hq, hkv,
+// scale, head0 / heads, and the five table pointers, of which wide_col holds the tile entries)
+// plus what the table kernel reads.
+struct PagedPrefillArgs {
+  PrefillArgs a;
+  int n_nodes, qt_max, nt_max, n_pages;
+  const int32_t *q_off, *ctx_page_off, *ctx_pages, *ctx_page_len, *own_page, *own_len;
+};
+int launch_prefill_paged(const PagedPrefillArgs& pa, int head_dim, hipStream_t stream);
+
 int launch_prefill_f32(const PrefillArgs& a, int head_dim, hipStream_t stream);
 int launch_prefill_bf16_prepare_v(const PrefillArgs& a, int head_dim, hipStream_t stream);  // V -> workspace copy
 int launch_prefill_bf16(const PrefillArgs& a, int head_dim, hipStream_t stream);            // needs the copy

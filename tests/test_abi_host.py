@@ -256,6 +256,31 @@ def _as_oracle_steps(steps):
     return out
 
 
+def test_paged_prefill_argument_errors():
+    L = B.lib()
+    p = C.c_void_p(FAKE)
+    d = B.dag_paged_prefill_desc_t(3, 16, 100, 70, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    # counters + item count, per (node, query tile) slot 17 ints and a row of 18 tile entries of 8 ints; slack
+    need = L.dag_prefill_paged_workspace_bytes(C.byref(d))
+    assert need == 4 * (128 + 64 + 3 * 2 * (17 + 8 * 18)) + 256
+    big = 1 << 30
+    args = lambda desc=d, q=p, hq=8, hkv=2, dim=128, ws=p, wsb=big, n_pages=50: L.dag_attn_prefill_paged(
+        C.byref(desc), q, p, p, n_pages, p, None, hq, hkv, dim, 0.1, ws, wsb, None)
+    assert args(dim=96) == -7 and args(hq=7) == -7
+    assert args(q=None) == -1 and args(ws=None) == -6 and args(wsb=need - 1) == -6
+    assert args(q=C.c_void_p(FAKE + 2)) == -8
+    assert args(n_pages=0) == -2
+    bad = B.dag_paged_prefill_desc_t(3, 32, 100, 70, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    assert args(desc=bad) == -7 and L.dag_prefill_paged_workspace_bytes(C.byref(bad)) == 0
+    neg = B.dag_paged_prefill_desc_t(3, 16, -1, 70, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    assert args(desc=neg) == -2
+    nullarr = B.dag_paged_prefill_desc_t(3, 16, 100, 70, FAKE, None, FAKE, FAKE, FAKE, FAKE)
+    assert args(desc=nullarr) == -1
+    nothing = B.dag_paged_prefill_desc_t(0, 16, 0, 0, None, None, None, None, None, None)
+    assert args(desc=nothing, q=None, ws=None, wsb=0) == 0   # no node: nothing to do, nothing is read
+    assert L.dag_attn_prefill_paged(None, p, p, p, 50, p, None, 8, 2, 128, 0.1, p, big, None) == -1
+
+
 def test_scheduler_steps_equal_the_oracle_schedule():
     from oracle import dag_oracle as orc
     rng = np.random.Generator(np.random.PCG64(91))

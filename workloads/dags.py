@@ -262,9 +262,12 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
       seg_reader_off/seg_readers            live branches that read the segment (ascending)
       branch_seg_off/branch_segs            segments each live branch reads (ascending node id)
       branch_entry_off/branch_entries       the same relation as positions in seg_readers
+    and, under "paged", the same frontier as a paged-prefill description (one entry per live node:
+    its rows of q, the pages of its context with their token counts, where its own pages start).
     """
     rng = np.random.Generator(np.random.PCG64(seed))
     seg_len, seg_np = [], []
+    paged = dict(q_off=[0], ctx_page_off=[0], ctx_pages=[], ctx_page_len=[], own_page=[], own_len=[], page_size=PAGE)
     for L, _ in dag_list:
         for x in L:
             seg_len.append(int(x))
@@ -307,6 +310,17 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
         for li, v in enumerate(live):
             n_new = 1 if new_tokens is None else int(new_tokens[dag_index][li])
             mine = sorted(set(int(u) for u in sets[v]) | {int(v)})
+            # the same live node as one entry of the paged-prefill description: the pages of its
+            # ancestors' segments in node order, then its own, with the tokens each page holds
+            for u in [u for u in mine if u != v] + [int(v)]:
+                if u == v:
+                    paged["own_page"].append(len(paged["ctx_pages"]) - paged["ctx_page_off"][-1])
+                pg = seg_pages[seg_page_off[s0 + u]:seg_page_off[s0 + u + 1]]
+                paged["ctx_pages"].extend(int(x) for x in pg)
+                paged["ctx_page_len"].extend(min(PAGE, int(L[u]) - PAGE * j) for j in range(len(pg)))
+            paged["ctx_page_off"].append(len(paged["ctx_pages"]))
+            paged["own_len"].append(int(L[v]))
+            paged["q_off"].append(paged["q_off"][-1] + n_new)
             for i in range(n_new):
                 r = len(branch_segs)
                 tok = int(start[v + 1]) - n_new + i
@@ -335,7 +349,8 @@ def decode_segments_state(seed, dag_list, live_list, hq, hkv, d, kv_scale=1.0, q
         desc["seg_reader_len"] = flat(reader_len)
     add_branch_entries(desc)
     return dict(desc=desc, k_pool=k_pool, v_pool=v_pool, q=torch.stack(q_rows) if q_rows else
-                torch.zeros((0, hq, d), dtype=dtype), tokens=toks, live_tok=live_tok, n_pages=n_pages)
+                torch.zeros((0, hq, d), dtype=dtype), tokens=toks, live_tok=live_tok, n_pages=n_pages,
+                paged={k: (np.asarray(x, dtype=np.int32) if isinstance(x, list) else x) for k, x in paged.items()})
 
 
 def add_branch_entries(desc):
