@@ -229,6 +229,42 @@ class SegDecodeWork:
         B.dag_attn_decode_segments(self.sd, self.q, kp, vp, self.out, self.ws)
 
 
+def paged_prefill_leg(cfg, dev, steps, warmup, n_new=256, cached=1024):
+    """Beside the timed region: dag_attn_prefill_paged on contexts of config 3's shape -- per
+    sequence a shared prefix and 8 nodes with `cached` tokens in their pages, each prefilling
+    n_new further tokens at once (their K/V already appended).  Useful FLOPs: 4 D per (new token,
+    visible token, query head)."""
+    nb, n_seqs = cfg["n_branch"], cfg["n_seqs"]
+    dag = dags.fork_join(cfg["shared"], [cached + n_new] * nb, None)
+    st = dags.decode_segments_state(cfg["seed"] + 55, [dag] * n_seqs, [list(range(1, nb + 1))] * n_seqs, cfg["hq"],
+                                    cfg["hkv"], cfg["d"], keep_tokens=False, new_tokens=[[n_new] * nb] * n_seqs)
+    pd = B.PagedPrefillDesc(st["paged"], dev)
+    kp, vp, q = st["k_pool"].to(dev), st["v_pool"].to(dev), st["q"].to(dev)
+    out = torch.empty_like(q)
+    ws = torch.empty(B.dag_prefill_paged_workspace_bytes(pd), dtype=torch.uint8, device=dev)
+    pairs = n_seqs * nb * sum(cfg["shared"] + cached + i + 1 for i in range(n_new))
+    flops = 4.0 * cfg["d"] * cfg["hq"] * pairs
+    for _ in range(warmup):
+        B.dag_attn_prefill_paged(pd, q, kp, vp, out, ws)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in ev:
+        e0.record()
+        B.dag_attn_prefill_paged(pd, q, kp, vp, out, ws)
+        e1.record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev]))
+    tf = flops / (ms * 1e-3) / 1e12
+    kern = "k_prefill_bf16<128,4,2,true>"
+    return {"metric": "dag_attn_prefill_paged_useful_tflops", "value": tf, "unit": "TFLOP/s", "ms_per_call": ms,
+            "calls": steps,
+            "config": {"workload": "paged_node_prefill_bf16", "n_seqs": n_seqs, "nodes": n_seqs * nb,
+                       "new_tokens_per_node": n_new, "cached_tokens_per_node": cached, "shared_prefix": cfg["shared"],
+                       "hq": cfg["hq"], "hkv": cfg["hkv"], "head_dim": cfg["d"], "page_size": 16, "useful_pairs": pairs},
+            "roofline": {"bound": "mfma", "kernel": "k_paged_rows+k_wide_order+" + kern, "achieved": tf,
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS,
+                         "traffic": traffic_of("paged", kern)}}
+
+
 def cpu_baseline(pw, n_seq=3):
     """The oracle as it stands, timed on the host cores on a bounded sample of the prefill workload:
     the first n_seq sequences, every row, every query head (10 - 20 s of CPU work)."""
@@ -283,17 +319,20 @@ def prefill_leg(cfg, dev, launches, warmup, workload_key):
     tf = flops / (ms_attn * 1e-3) / 1e12
     bmap = pw.meta.get("block_map")
     census = {"full": int((bmap == B.TILE_FULL).sum().item()), "partial": int((bmap == B.TILE_PARTIAL).sum().item())}
+    # the launches of one call: four-head items on 64-row tiles, left-over heads (one or two) on 256-row tiles
     g = cfg["hq"] // cfg["hkv"]
-    kern = "k_prefill_bf16<%d,%d,1>" % (cfg["d"], 4 if g >= 3 else g)
+    wide = g % 4 if g % 4 < 3 else 0
+    kerns = (["k_prefill_bf16<%d,4,2,false>" % cfg["d"]] if g > wide else []) + \
+            (["k_prefill_bf16<%d,1,8,false>" % cfg["d"]] if wide else [])
     return {"metric": "dag_attn_prefill_useful_tflops", "value": flops / (ms_path * 1e-3) / 1e12, "unit": "TFLOP/s",
             "launches": launches, "ms_prefill_path(meta+rope+attn)": ms_path, "ms_attn_kernel": ms_attn,
             "min_ms_attn_kernel": float(np.min(attn)),
             "config": {"workload": cfg["name"], "batch": cfg["batch"], "tokens": pw.T, "hq": cfg["hq"],
                        "hkv": cfg["hkv"], "head_dim": cfg["d"], "useful_pairs": pairs, "tiles_64x64": census,
                        "values": "torch generator on the device, seed %d" % cfg["seed"]},
-            "roofline": {"bound": "mfma", "kernel": kern, "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "roofline": {"bound": "mfma", "kernel": "+".join(kerns), "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS,
-                         "traffic": traffic_of(workload_key, kern), "algorithmic_bytes": pw.algorithmic_bytes()}}
+                         "traffic": traffic_of(workload_key, *kerns), "algorithmic_bytes": pw.algorithmic_bytes()}}
 
 
 def decode_leg(cfg, dev, steps, warmup, workload_key, kernels, copies):
@@ -336,7 +375,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", choices=["all", "main", "config4", "config5"], default="all",
+    ap.add_argument("--only", choices=["all", "main", "config4", "config5", "paged"], default="all",
                     help="main = the timed region (configs 2 and 3) with the segment decode and the backward; "
                          "config4 / config5 = only that leg (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -377,7 +416,10 @@ def main():
     if args.only in ("all", "config4"):
         extra["config4_prefill"] = prefill_leg(dags.config(3), dev, max(1, min(args.steps, 20)),
                                                min(args.warmup, 5) + 10, "config4")
-    if args.only in ("config4", "config5"):
+    if args.only in ("all", "paged"):
+        extra["paged_prefill"] = paged_prefill_leg(dags.config(2), dev, max(1, min(args.steps, 10)), min(args.warmup, 3))
+        torch.cuda.empty_cache()
+    if args.only in ("config4", "config5", "paged"):
         print(json.dumps(extra))
         return
     torch.cuda.empty_cache()
@@ -469,9 +511,9 @@ def main():
         "segments_ms": {"prefill_path(meta+rope+attn)": ms_pre, "prefill_attn_kernel": ms_attn,
                         "decode_path(append+attn+merge)": ms_dec, "decode_attn_kernels": ms_deck,
                         "min_prefill_attn_kernel": float(np.min(attn_ms)), "min_decode_attn_kernels": float(np.min(deck_ms))},
-        "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16<128,4,1>", "achieved": tflops_kernel,
+        "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16<128,4,2,false>", "achieved": tflops_kernel,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops_kernel / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": traffic_of("main", "k_prefill_bf16<128,4,1>"), "algorithmic_bytes": pw.algorithmic_bytes()},
+                     "traffic": traffic_of("main", "k_prefill_bf16<128,4,2,false>"), "algorithmic_bytes": pw.algorithmic_bytes()},
         "decode": {"metric": "branch_decode_tok_per_s_one_attention_layer",
                    "value": dw.n_live / (ms_dec * 1e-3), "unit": "tok/s", "ms_per_decode_step": ms_dec,
                    "config": {"workload": dw.cfg["name"], "n_seqs": dw.cfg["n_seqs"], "live_branches": dw.n_live,
