@@ -574,10 +574,18 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
   // rmsk[r] says whether this lane's row r may see key j + 8 H of the tile (set by tile_mask in the
   // item loop); msk_on is wave-uniform and false for the tiles that need no mask.
   bool msk_on = false;
+  bool msk_full[2] = {false, false};  // (wave-uniform) the mask of that key half hides nothing from this wave's rows
+  // (wave-uniform) parts of a step that are wanted: a part whose 32 x 32 block of the mask hides
+  // everything keeps its slots and operand reads (the read counters stay as they are) and leaves
+  // out the arithmetic
+  bool qk_on = true, pv_on = true, ex_on = true;
   uint64_t rmsk[RB];
 #pragma unroll
   for (int r = 0; r < RB; ++r) rmsk[r] = 0;
   auto apply_mask = [&](f32x16* S, int half) __attribute__((always_inline)) {  // masked scores become -inf
+#ifdef DAGATTN_ABL_NOAPPLY  // (development: timing without the mask application; results are wrong)
+    return;
+#endif
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
       const uint32_t word = half ? (uint32_t)(rmsk[r] >> 32) : (uint32_t)rmsk[r];
@@ -640,14 +648,18 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r = 0; r < RB; ++r) {
-        if (i < NQ) Sn[r] = mfma32(opnd[i], qf[r][i < NQ ? i : 0], i == 0 ? negM[r] : Sn[r]);
-        else O[r][(i - NQ) % DB] = mfma32(opnd[i], Pp[r][(i - NQ) / DB], O[r][(i - NQ) % DB]);
+        if (i < NQ) {
+          if (qk_on) Sn[r] = mfma32(opnd[i], qf[r][i < NQ ? i : 0], i == 0 ? negM[r] : Sn[r]);
+        } else {
+          if (pv_on) O[r][(i - NQ) % DB] = mfma32(opnd[i], Pp[r][(i - NQ) / DB], O[r][(i - NQ) % DB]);
+        }
       }
       extra(i, NSLOT);
-      if (QK && i == MAXSLOT) {
-        if (msk_on) apply_mask(Sn, HQ);
+      if (QK && i == MAXSLOT && qk_on) {
+        if (msk_on && !msk_full[HQ]) apply_mask(Sn, HQ);
         need = row_max(Sn);
       }
+      if (ex_on)
 #pragma unroll
       for (int u = i * NU / NSLOT; u < (i + 1) * NU / NSLOT; ++u) {  // two probabilities of one row
         const int r = u / 8, e = 2 * (u % 8);
@@ -662,11 +674,11 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       }
       __builtin_amdgcn_sched_barrier(0);
     });
-    if (QK && MAXSLOT == NSLOT) {
-      if (msk_on) apply_mask(Sn, HQ);
+    if (QK && MAXSLOT == NSLOT && qk_on) {
+      if (msk_on && !msk_full[HQ]) apply_mask(Sn, HQ);
       need = row_max(Sn);
     }
-    if (EX) {
+    if (EX && ex_on) {
 #pragma unroll
       for (int r = 0; r < RB; ++r) l[r] += rs[r];
     }
@@ -916,7 +928,12 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
     // ids come with the tile, through the ring) and each segment is switched on for the rows whose
     // node sees the segment's node (Eq. 3); the causal / length limit is one more AND.  Called
     // when tile n of the row (ring tile tc) has become visible, before its scores are masked.
-    auto tile_mask = [&](int n) __attribute__((always_inline)) {
+    auto tile_mask = [&](int n, unsigned ring_tile, uint64_t* rm) __attribute__((always_inline)) {
+#ifdef DAGATTN_ABL_NOTILEMASK  // (development: timing without the mask construction; results are wrong)
+#pragma unroll
+      for (int r = 0; r < RB; ++r) rm[r] = ~0ull;
+      return;
+#endif
       if constexpr (PAGED) {
         // A page of the context holds its first `count` tokens (a byte per page in the entry's word
         // 4); row i of the node's new tokens sees the slots of the context up to nstart + i (its
@@ -934,7 +951,7 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
         for (int r = 0; r < RB; ++r) {
           const int cnt = cur.nstart + min(row_of(cur, r), cur.T - 1) - tix * TN + 1;
           const uint64_t lim = cnt >= 64 ? ~0ull : (cnt <= 0 ? 0ull : ((1ull << cnt) - 1));
-          rmsk[r] = (valid & lim) >> (8 * H);
+          rm[r] = (valid & lim) >> (8 * H);
         }
         return;
       }
@@ -948,7 +965,7 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       int nj;
       asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                    : "=v"(nj)
-                   : "v"(lds_addr(Abase + (tc % NSTAGE) * 256 + lane * 4))
+                   : "v"(lds_addr(Abase + (ring_tile % NSTAGE) * 256 + lane * 4))
                    : "memory");
       const int prev = __shfl_up(nj, 1);
       uint64_t starts = __builtin_amdgcn_ballot_w64(lane == 0 || nj != prev);
@@ -975,7 +992,23 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       for (int r = 0; r < RB; ++r) {
         const int cnt = min(row_of(cur, r), cur.T - 1) - j0 + 1;  // keys j0 .. j0 + cnt - 1 are not in the future
         const uint64_t lim = cnt >= 64 ? ~0ull : (cnt <= 0 ? 0ull : ((1ull << cnt) - 1));
-        rmsk[r] = (rowmask[r] & lim) >> (8 * H);
+        rm[r] = (rowmask[r] & lim) >> (8 * H);
+      }
+    };
+    // What a mask means for this wave's rows, per key half: hides everything (the half's score
+    // MFMAs, exponentials and P V MFMAs can be left out), hides nothing (no need to apply it).
+    auto mask_census = [&](const uint64_t* rm, bool* live, bool* full) __attribute__((always_inline)) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        bool some = false, gap = false;
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+          const uint32_t mine = (uint32_t)(rm[r] >> (32 * h)) & 0x00ff00ffu;  // this lane's 16 keys of the half
+          some |= mine != 0;
+          gap |= mine != 0x00ff00ffu;
+        }
+        live[h] = __builtin_amdgcn_ballot_w64(some) != 0;
+        full[h] = __builtin_amdgcn_ballot_w64(gap) == 0;
       }
     };
 
@@ -985,16 +1018,12 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
     // inside that step, in the shadow of the MFMAs, and the two waves of a SIMD do it in different
     // slots (while one builds its mask the other one keeps the matrix pipe busy).
     const int NT = cur.N;
-    int mask_n = 0;
     const int mask_slot = w < NW / 2 ? KSTEPS - 2 : 0;  // (a slot of the score part: the first tile's step has no other)
-    auto first_half_extra = [&](int i, int NS) __attribute__((always_inline)) {
-      if (msk_on && i == mask_slot) tile_mask(mask_n);
-      refill_slot(i, NS);
-    };
     auto first_tile_extra = [&](int i, int) __attribute__((always_inline)) {
-      if (msk_on && i == mask_slot) tile_mask(0);
+      if (msk_on && i == mask_slot) tile_mask(0, tc, rmsk);
     };
     msk_on = F == 0;
+    msk_full[0] = msk_full[1] = false;
     if (step(Y, N_, N_, H0, H0, Kt(tc), SA, nullptr, nop, nullptr, nullptr, first_tile_extra)) rescale(SA);
     bool need = step(Y, N_, Y, H1, H0, Kt(tc), SB, nullptr, nop, SA, P0, nothing);
     TSTAMP(t_first);
@@ -1213,15 +1242,52 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       }
 #endif
     }
+    // ---- the tiles with a mask.  The mask of a tile is built a tile ahead (its node ids are in
+    // the ring by then, the K tiles being published a tile ahead), in a slot of the second half's
+    // step, in the shadow of the MFMAs -- the two waves of a SIMD in different slots; only the
+    // first one is built on the spot, after the barrier that publishes its tile -- so that
+    // it is known before the tile's first step which of the wave's two 32 x 32 blocks of the tile
+    // see nothing at all: such a block's score MFMAs, its exponentials a step later and its P V
+    // MFMAs two steps later are left out (lvA / lvB / lvP0 / lvP1: whether SA, SB, P0, P1 hold
+    // something that counts); the wave still takes part in the tile's barrier and load issue.
+    uint64_t rm_nxt[RB];
+    bool lvA = true, lvB = true, lvP0 = true, lvP1 = true;
+    bool mask_built = false;  // rm_nxt holds the mask of the tile the loop turns to
+    auto step_sel = [&](bool qk, bool pv, bool ex, auto qk_c, auto hq_c, auto hv_c, const unsigned char* Kb, f32x16* Sn,
+                        const unsigned char* Vb, const bf16x8 (*Pp)[2], const f32x16* Sc, bf16x8 (*Pc)[2],
+                        auto&& extra) __attribute__((always_inline)) {
+      qk_on = qk;
+      pv_on = pv;
+      ex_on = ex;
+      const bool nd = step(qk_c, Y, Y, hq_c, hv_c, Kb, Sn, Vb, Pp, Sc, Pc, extra);
+      qk_on = pv_on = ex_on = true;
+      return nd;
+    };
 #pragma unroll 1
     for (; n + 1 < NT; ++n) {
       sync_next();  // tile tc - 1 is the one in flight through the pipeline, tc the new one
       msk_on = n + 1 >= F;
-      mask_n = n + 1;
+      bool live[2] = {true, true};
+      if (msk_on) {
+        if (!mask_built) tile_mask(n + 1, tc, rm_nxt);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) rmsk[r] = rm_nxt[r];
+        mask_census(rmsk, live, msk_full);
+      }
+      const bool mask_ahead = n + 2 < NT && n + 2 >= F;
+      mask_built = mask_ahead;
+      auto second_half_extra = [&](int i, int NS) __attribute__((always_inline)) {
+        if (mask_ahead && i == mask_slot) tile_mask(n + 2, tc + 1, rm_nxt);
+        refill_slot_v(i, NS);
+      };
       if (need) rescale(SB);
-      need = step(Y, Y, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, first_half_extra);
+      need = step_sel(live[0], lvP0, lvB, Y, H0, H0, Kt(tc), SA, Vt(tc - 1), P0, SB, P1, refill_slot);
+      lvA = live[0];
+      lvP1 = lvB;
       if (need) rescale(SA);
-      need = step(Y, Y, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, refill_slot_v);
+      need = step_sel(live[1], lvP1, lvA, Y, H1, H1, Kt(tc), SB, Vt(tc - 1), P1, SA, P0, second_half_extra);
+      lvB = live[1];
+      lvP0 = lvA;
       TCOUNT(7);
     }
     msk_on = false;
@@ -1254,8 +1320,10 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
     }
     if (need) rescale(SB);
     TSTAMP(te2);
-    step(N_, Y, Y, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill_slot);
+    step_sel(true, lvP0, lvB, N_, H0, H0, nullptr, nullptr, Vt(tc - 1), P0, SB, P1, refill_slot);
+    pv_on = lvB;  // (P1 comes from SB)
     step(N_, Y, N_, H0, H1, nullptr, nullptr, Vt(tc - 1), P1, nullptr, nullptr, refill_slot_v);
+    pv_on = true;
     TSTAMP(t_p1);
     TACC(4, t_loop, t_p1);
     TACC(8, t_loop, te0);
