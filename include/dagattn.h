@@ -19,12 +19,12 @@
  *   - Tensors are token-major packed variable-length: q [T][Hq][D], k/v [T][Hkv][D], contiguous,
  *     16-byte aligned.  Sequences are concatenated; tokens of a sequence are stored node after
  *     node in node-id order and node ids must be a topological order of the DAG.
- *   - Process-wide state: none that a result depends on.  What the library keeps per device until
- *     the process ends is (a) a second stream with two events, created at the first
- *     dag_attn_decode call with wide sibling groups (see there), (b) attributes set once on its
- *     own kernels, and (c) the development knobs of the decode split sizes, read from the
- *     environment once.  Calls on different streams may overlap if their buffers do not; the
- *     decode calls that use the second stream serialise their enqueue phase on a mutex.
+ *   - Process-wide state: none that a result depends on.  What the library keeps until the
+ *     process ends is (a) per device, the address of the scratch array of
+ *     dag_attn_decode_static (see there), (b) attributes set on its own kernels, and (c) the
+ *     development knobs of the decode split sizes and of the prefill head split, read from the
+ *     environment once.  It creates no streams and no events.  Calls on different streams may
+ *     overlap if their buffers (workspaces included) do not.
  */
 #ifndef DAGATTN_H
 #define DAGATTN_H
@@ -237,10 +237,8 @@ size_t dag_decode_workspace_bytes(const dag_decode_desc_t* desc, int32_t hq, int
  * (section 4.3 Fork), own pages once per branch, and the partial results are combined by
  * log-sum-exp.  q/out [n_live][hq][head_dim] bf16 DEVICE, q already rotated.  head_dim 128 or
  * 64, page_size 16, hq a multiple of hkv with hq/hkv <= 32.
- * Everything is ordered on `stream`.  When a sibling group stacks more than 32 query rows per KV
- * head (siblings x hq/hkv), part of the work runs on a second stream that the library creates
- * once per device at the first such call (default priority, kept until the process ends) and
- * that is forked from and joined to `stream` with events; the call itself allocates no memory. */
+ * Everything is enqueued on `stream` (two launches: the partial results, their combination);
+ * the call allocates nothing and does not synchronise. */
 int dag_attn_decode(const dag_decode_desc_t* desc, const void* q, const void* k_pool,
                     const void* v_pool, void* out, int32_t hq, int32_t hkv, int32_t head_dim,
                     float softmax_scale, void* ws, size_t ws_bytes, void* stream);
@@ -252,7 +250,6 @@ int dag_attn_decode(const dag_decode_desc_t* desc, const void* q, const void* k_
  * bit), layouts and errors as dag_attn_decode, except:
  *   - DAG_ERR_WORKSPACE when dag_decode_workspace_bytes() for this description exceeds
  *     DAG_DECODE_STATIC_SCRATCH_BYTES (benchmark configs 3 and 5 need 11 and 24 MiB);
- *   - everything runs on `stream`, wide sibling groups included: no second stream is created;
  *   - the call allocates nothing and frees nothing.  Its first call on a device looks up the
  *     array's address there (hipGetSymbolAddress), so make one call per device outside a capture;
  *   - all calls on one GPU share the array, which keeps the last call's contents (every partial

@@ -50,6 +50,7 @@ struct DecodeArgs {
   int chunk_a, splits_a, chunk_b, splits_b;
   int items_a, items_b;
   int item_base;     // first work item of this launch (k_decode)
+  int wide_shared;   // k_decode_wide: workgroups that take shared items (the rest take own pages)
   float sc;          // softmax_scale * log2(e)
   float th;          // 8 / sc: how far a score may exceed the reference maximum before it is raised
   float scale;
@@ -547,13 +548,30 @@ __global__ void __launch_bounds__(64) k_decode_seg_merge(SegArgs a) {
 // x 5 query heads): one workgroup per (group, kv head, page split) with one wave per 32-row
 // block.  The waves share the K/V blocks through a ring in LDS (global -> LDS directly, 16 bytes
 // per lane; a page of the pools is already the operand image), so the shared pages are streamed
-// once per group whatever the number of rows, and RING - 1 blocks are in flight per workgroup
-// instead of one per wave.  Writes the same partials as the shared items of k_decode.
-constexpr int WIDE_RING = 8;                    // 32-key blocks in the ring (128 KiB of LDS at head_dim 128: one workgroup per CU)
-constexpr int WIDE_MAX_WAVES = 8;
+// once per group whatever the number of rows, and up to RING blocks are in flight per workgroup
+// instead of one per wave.  A row block is served by `nsub` waves that take the key blocks in
+// turn (wave `sub` of a row block computes blocks sub, sub + nsub, ...), each with accumulators
+// of its own that are put together through LDS at the end: a wave's chain of LDS reads, score
+// MFMAs, softmax arithmetic and P V MFMAs is long and serial, so a SIMD needs two or three of
+// them to stay busy.  The workgroup meets at a barrier once per round of nsub blocks.  Writes the
+// same partials as the shared items of k_decode.
+constexpr int WIDE_RING = 6;                    // 32-key blocks in the ring (96 KiB of LDS at head_dim 128; behind it the query operands)
+constexpr int WIDE_MAX_WAVES = 8;               // row blocks of a workgroup
+constexpr int WIDE_MAX_THREADS = 768;           // three waves per SIMD (the register budget is set for that)
+constexpr int WIDE_OWN_WAVES = WIDE_RING / 2;   // waves that share the own pages of a branch
 template <int D>
 constexpr int wide_block_bytes() { return 4 * PAGE * D * 2; }  // K and V of two pages
-
+// waves per row block: as many as fit into twelve waves, and their accumulators (64 lanes x
+// (D / 2 + 4) floats per wave) into the ring for the final combination
+// (a round's blocks are issued a round ahead, so the ring holds two rounds)
+inline int wide_nsub(int rb_max, int D) {
+  int n = (WIDE_MAX_THREADS / 64) / rb_max;
+  if (n > WIDE_RING / 2) n = WIDE_RING / 2;
+  while (n > 1 && (size_t)(n - 1) * rb_max * 64 * (D / 2 + 4) * 4 > (size_t)WIDE_RING * 4 * PAGE * D * 2) --n;
+  return n < 1 ? 1 : n;
+}
+// dynamic LDS of a launch: the ring, then the query operands of every row block
+inline int wide_lds_bytes(int rb_max, int D) { return WIDE_RING * 4 * PAGE * D * 2 + rb_max * (D / 16) * 1024; }
 __device__ __forceinline__ void wait_vmcnt_dyn(int n) {  // s_waitcnt vmcnt(n), n <= 56, wave-uniform
   // vmcnt is split over bits 3:0 and 15:14 of the immediate (gfx9 encoding)
   switch (n >> 2) {
@@ -574,47 +592,86 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n) {  // s_waitcnt vmcnt(n), 
 }
 
 template <int D>
-__global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeArgs a) {
+__global__ void __launch_bounds__(WIDE_MAX_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3))) k_decode_wide(DecodeArgs a) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
   constexpr int BB = wide_block_bytes<D>();       // bytes of a block in the ring: K page 0, K page 1, V page 0, V page 1
   constexpr int PB = PAGE * D * 2;                // bytes of one page of one kv head in a pool
   constexpr int LOADS = BB / 1024;                // wave-level loads per block
-  const int nw = blockDim.x >> 6;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int L = lane & 31, H = lane >> 5;
-  int x = blockIdx.x;
-  const int split = x % a.splits_a; x /= a.splits_a;
-  const int hk = x % a.hkv;
-  const int g = x / a.hkv;
-  const int branch0 = a.group_branch_off[g];
-  const int nrows = (a.group_branch_off[g + 1] - branch0) * a.G;
-  const int32_t* pages = a.shared_pages + a.shared_page_off[g];
-  const int len = a.shared_len[g];
+  // The first wide_shared workgroups take the shared items; the ones after them take the own
+  // pages of one (branch, kv head, split) each, as a single row block whose waves (six at most,
+  // the others leave at once) take the key blocks in turn: they follow the shared items in the
+  // same launch and fill the compute units as those run out.
+  const bool own = (int)blockIdx.x >= a.wide_shared;
+#ifdef DAGATTN_ABL_NOOWN  // (development: timing of the shared items alone; results are wrong)
+  if (own) return;
+#endif
+#ifdef DAGATTN_ABL_NOSHARED
+  if (!own) return;
+#endif
+  int nw, nsub, rb, sub, split, hk, branch0, nrows, len, chunk;
+  const int32_t* pages;
+  float *po, *pml;
+  if (!own) {
+    nw = blockDim.x >> 6;
+    nsub = nw / a.rb_max; rb = w % a.rb_max; sub = w / a.rb_max;
+    int x = blockIdx.x;
+    split = x % a.splits_a; x /= a.splits_a;
+    hk = x % a.hkv;
+    const int g = x / a.hkv;
+    branch0 = a.group_branch_off[g];
+    nrows = (a.group_branch_off[g + 1] - branch0) * a.G;
+    pages = a.shared_pages + a.shared_page_off[g];
+    len = a.shared_len[g];
+    chunk = a.chunk_a;
+    const size_t item = (((size_t)g * a.hkv + hk) * a.rb_max + rb) * a.splits_a + split;
+    po = a.part_o_a + (item * 32 + L) * D;
+    pml = a.part_ml_a + (item * 32 + L) * 2;
+  } else {
+    nw = min((int)(blockDim.x >> 6), WIDE_OWN_WAVES);
+    if (w >= nw) return;
+    nsub = nw; rb = 0; sub = w;
+    int x = (int)blockIdx.x - a.wide_shared;
+    const size_t item = (size_t)x;  // the order of k_decode's own items: (branch, kv head, split)
+    split = x % a.splits_b; x /= a.splits_b;
+    hk = x % a.hkv;
+    branch0 = x / a.hkv;
+    nrows = a.G;
+    pages = a.branch_pages + a.branch_page_off[branch0];
+    len = a.branch_len[branch0];
+    chunk = a.chunk_b;
+    po = a.part_o_b + (item * a.G + L) * D;
+    pml = a.part_ml_b + (item * a.G + L) * 2;
+  }
   const int npages = (len + PAGE - 1) / PAGE;
-  const int p0 = split * a.chunk_a, p1 = min(p0 + a.chunk_a, npages);
-  const int row = 32 * w + L;
+  const int p0 = split * chunk, p1 = min(p0 + chunk, npages);
+  const int row = 32 * rb + L;
   const bool row_ok = row < nrows;
-  const size_t item = (((size_t)g * a.hkv + hk) * a.rb_max + w) * a.splits_a + split;
-  float* po = a.part_o_a + (item * 32 + L) * D;
-  float* pml = a.part_ml_a + (item * 32 + L) * 2;
+  const int rbm = own ? 1 : a.rb_max;  // row blocks of the workgroup
   if (p0 >= p1) {  // empty slice (the same for every wave of the workgroup): neutral partials
-    if (row_ok && H == 0) {
+    if (row_ok && H == 0 && sub == 0) {
       pml[0] = -1e30f;
       pml[1] = 0.f;
     }
     return;
   }
 
-  bf16x8 qreg[D / 16];
-  {
+  // The query operands of the row block live in LDS behind the ring (operand s of lane i at
+  // (s 64 + i) 16 bytes), written by the block's first wave and read again for every key block:
+  // with them in registers three waves would not fit on a SIMD.
+  const uint32_t qbase = WIDE_RING * BB + rb * (D / 16) * 1024;
+  if (sub == 0) {
     const int rr = row_ok ? row : 0;
     const int br = branch0 + rr / a.G, head = hk * a.G + rr % a.G;
     const uint16_t* qp = a.q + ((size_t)br * a.hq + head) * D + 8 * H;
+    bf16x8 qreg[D / 16];
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) qreg[s] = *(const bf16x8*)(qp + 16 * s);
-  }
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(qreg[s]));  // arrived: no other load of this wave returns into registers
+    for (int s = 0; s < D / 16; ++s) *(bf16x8*)(ring + qbase + (s * 64 + lane) * 16) = qreg[s];
+  }
+  __builtin_amdgcn_s_waitcnt(0);  // (written before the first barrier of the block loop, which every wave passes before it reads them)
 
   // Loads of a block: piece j (0 .. LOADS - 1) = 1 KiB number j % (LOADS / 4) of {K page 0, K page 1,
   // V page 0, V page 1}[j / (LOADS / 4)]; wave w issues the pieces w, w + nw, ...  Every wave
@@ -625,6 +682,11 @@ __global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeAr
   int pgv = pages[p0 + min(lane, np - 1)];  // page ids, a 64-page window per register (as in k_decode)
   asm volatile("" ::"v"(pgv));             // arrived (a wait for it inside the loops would drain the ring's loads)
   int pgv_first = 0;                        // first page (relative) of the window in pgv
+  // A V piece (32 dimensions x 16 keys) is fetched so that the 16 lanes which read an operand
+  // together find it in 256 consecutive bytes: LDS position u of the piece holds dimension
+  // 16 (u / 32) + u % 16, key half (u / 16) % 2 (a row of the pool has 32 bytes: read as it lies,
+  // those lanes would hit every bank twice).
+  const uint32_t vsrc = (2 * (16 * (lane / 32) + lane % 16) + (lane / 16) % 2) * 16;
   auto issue_block = [&](int b) {
     const int pr = 2 * b;
     if (pr - pgv_first >= 64) {  // next window (blocks are issued in order)
@@ -640,17 +702,18 @@ __global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeAr
       const int j = min(w + i * nw, LOADS - 1);
       const int part = j / (LOADS / 4), piece = j % (LOADS / 4);
       const unsigned char* src = (const unsigned char*)(part < 2 ? a.k_pool : a.v_pool) + ((part & 1) ? base1 : base0) +
-                                 piece * 1024 + lane * 16;
+                                 piece * 1024 + (part < 2 ? lane * 16 : vsrc);
       __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) const void*)src,
                                        (__attribute__((address_space(3))) void*)(slot + j * 1024), 16, 0, 0);
     }
   };
 
   const int kr = key_of_row(L);
-  // operand addresses inside a block: K[s] = chunk 2 s + H of key pi(L); V[page][db] = keys 8 H .. of dimension 32 db + L
+  // operand addresses inside a block: K[s] = chunk 2 s + H of key pi(L); V[page][db] = keys 8 H .. of
+  // dimension 32 db + L, which lies at position 32 (L / 16) + 16 H + L % 16 of its 1 KiB piece
   const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;
   const uint32_t koff = (kr >> 4) * PB + H * (PAGE * 16) + (kr & 15) * 16;
-  const uint32_t voff = 2 * PB + L * (PAGE * 2) + H * 16;
+  const uint32_t voff = 2 * PB + (L / 16) * 512 + H * 256 + (L % 16) * 16;
 
   f32x16 O[D / 32];
 #pragma unroll
@@ -658,32 +721,31 @@ __global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeAr
 #pragma unroll
     for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
   float m = -1e30f, l = 0.f;
-  auto qop = [&](int s) { return qreg[s]; };
+  bf16x8 qcur[D / 16];
+  auto qop = [&](int s) { return qcur[s]; };
 
-  int issued = 0;
-  for (; issued < nblk && issued < WIDE_RING - 1; ++issued) issue_block(issued);
-  for (int b = 0; b < nblk; ++b) {
-    // this wave's loads of block b have landed when at most the loads of the blocks after it are in flight
-    wait_vmcnt_dyn((issued - 1 - b) * lpw);
-    __builtin_amdgcn_s_barrier();  // block b is complete; every wave has finished block b - 1
-    asm volatile("" ::: "memory");
+  // Operands come from LDS right before their product (inline assembly: for plain LDS reads the
+  // compiler would first wait for every global-to-LDS load in flight).  Nothing else happens
+  // between a read and its wait: the compiler does not know that the registers are not there yet
+  // (it might spill one in between).
+  bf16x8 pb0, pb1;
+  auto score_phase = [&](int b) __attribute__((always_inline)) {  // scores and probabilities of block b
     const uint32_t sb = ring0 + (b % WIDE_RING) * BB;
-    // Operands come from LDS right before their product (inline assembly: for plain LDS reads the
-    // compiler would first wait for every global-to-LDS load in flight); the value operands are
-    // read after the score MFMAs have been issued, so they can take the key operands' registers,
-    // and their latency hides behind the softmax arithmetic.
-    bf16x8 kop[D / 16], v0[D / 32], v1[D / 32], pb0, pb1;
+    bf16x8 kop[D / 16];
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kop[s]) : "v"(sb + koff), "n"(s * 2 * PAGE * 16));
-    if (issued < nblk) {  // the next loads, into the slot of block b - 1, while the operand reads are under way
-      issue_block(issued);
-      ++issued;
-    }
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(qcur[s]) : "v"(ring0 + qbase + lane * 16), "n"(s * 1024));
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(kop[s]));
+    for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(kop[s]), "+v"(qcur[s]));
     block_scores<D>(kop, qop, O, m, l, a.sc, a.th, (p0 + 2 * b) * PAGE, len, len, H, pb0, pb1);
+  };
+  auto value_phase = [&](int b) __attribute__((always_inline)) {  // O += V^T P^T of block b
+    const uint32_t sb = ring0 + (b % WIDE_RING) * BB;
+    bf16x8 v0[D / 32], v1[D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) {
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v0[db]) : "v"(sb + voff), "n"(db * 32 * PAGE * 2));
@@ -694,6 +756,73 @@ __global__ void __launch_bounds__(64 * WIDE_MAX_WAVES, 1) k_decode_wide(DecodeAr
     for (int db = 0; db < D / 32; ++db) asm volatile("" : "+v"(v0[db]), "+v"(v1[db]));
     if ((p0 + 2 * b) * PAGE + 32 > len) clear_unused_values<D>(v0, v1, (p0 + 2 * b) * PAGE, len, H);
     block_pv<D>(v0, v1, pb0, pb1, O);
+  };
+  // The barrier of a round puts every wave at the same point, and waves that then all read LDS,
+  // all run their score MFMAs, all do the softmax arithmetic at the same time leave each of those
+  // units idle for most of the round.  When the ring holds three rounds, the waves with an odd
+  // `sub` therefore run half a block behind: after the barrier they first finish the block of the
+  // round before (its values), then take the scores of their new block, while the others do it
+  // the usual way round; a round's slots are then refilled a round later.
+  const bool skew = WIDE_RING >= 3 * nsub;
+  const bool late = skew && (sub & 1);
+  const int keep = skew ? 1 : 0;  // rounds before the current one whose blocks are still read
+  int issued = 0;
+  for (; issued < nblk && issued < WIDE_RING - keep * nsub; ++issued) issue_block(issued);
+  const int nrounds = (nblk + nsub - 1) / nsub;
+  auto round_sync = [&](int r) __attribute__((always_inline)) {
+    // this wave's loads of the round's blocks have landed when at most the loads of the blocks after them are in flight
+    wait_vmcnt_dyn(max(issued - min((r + 1) * nsub, nblk), 0) * lpw);
+    __builtin_amdgcn_s_barrier();  // the round's blocks are complete; every wave has finished the round before (late ones: its scores)
+    asm volatile("" ::: "memory");
+    // the next loads, into the slots that nobody reads any more
+    for (; issued < nblk && issued - (r - keep) * nsub < WIDE_RING; ++issued) issue_block(issued);
+  };
+  // (every wave passes one barrier per round, the late ones between the two halves of a block)
+  round_sync(0);
+  for (int r = 0; r < nrounds; ++r) {
+    const int b = r * nsub + sub;
+    const bool mine = b < nblk;
+    if (mine) score_phase(b);
+    if (late && r + 1 < nrounds) round_sync(r + 1);
+    if (mine) value_phase(b);
+    if (!late && r + 1 < nrounds) round_sync(r + 1);
+  }
+
+  // The waves of a row block put their accumulators together: waves 1 .. nsub - 1 leave theirs in
+  // LDS (the ring is free once every load has landed and every wave is past its last block), lane
+  // by lane, and wave 0 adds them in the order of `sub` with the usual change of reference maximum.
+  if (nsub > 1) {
+    wait_vmcnt_dyn(0);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    float* const slot = (float*)ring + ((size_t)((sub - 1) * rbm + rb) * 64 + lane) * (D / 2 + 4);
+    if (sub > 0) {
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          *(f32x4*)(slot + 16 * db + 4 * r4) = f32x4{O[db][4 * r4], O[db][4 * r4 + 1], O[db][4 * r4 + 2], O[db][4 * r4 + 3]};
+      slot[D / 2] = m;
+      slot[D / 2 + 1] = l;
+    }
+    __syncthreads();
+    if (sub > 0) return;
+    for (int s2 = 1; s2 < nsub; ++s2) {
+      const float* const other = (const float*)ring + ((size_t)((s2 - 1) * rbm + rb) * 64 + lane) * (D / 2 + 4);
+      const float m2 = other[D / 2], l2 = other[D / 2 + 1];
+      const float m_new = fmaxf(m, m2);
+      const float a1 = __builtin_amdgcn_exp2f((m - m_new) * a.sc), a2 = __builtin_amdgcn_exp2f((m2 - m_new) * a.sc);
+      m = m_new;
+      l = l * a1 + l2 * a2;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4 o2 = *(const f32x4*)(other + 16 * db + 4 * r4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) O[db][4 * r4 + e] = O[db][4 * r4 + e] * a1 + o2[e] * a2;
+        }
+    }
   }
 
   const float l_tot = l + __shfl_xor(l, 32);
@@ -723,32 +852,52 @@ __global__ void __launch_bounds__(64) k_decode_merge(DecodeArgs a) {
   const int rb = row >> 5, rr = row & 31;
   const size_t ia0 = (((size_t)g * a.hkv + hk) * a.rb_max + rb) * a.splits_a;
   const size_t ib0 = ((size_t)r * a.hkv + hk) * a.splits_b;
-  float mx = -1e30f;
-  for (int s = 0; s < a.splits_a; ++s) mx = fmaxf(mx, a.part_ml_a[((ia0 + s) * 32 + rr) * 2]);
-  for (int s = 0; s < a.splits_b; ++s) mx = fmaxf(mx, a.part_ml_b[((ib0 + s) * a.G + j) * 2]);
   constexpr int PER = D / 64;  // output elements per lane
+  const int np = a.splits_a + a.splits_b;
+  // partial p of this (branch, head): shared split p, then own split p - splits_a
+  auto ml_of = [&](int p) {
+    return p < a.splits_a ? a.part_ml_a + ((ia0 + p) * 32 + rr) * 2 : a.part_ml_b + ((ib0 + (p - a.splits_a)) * a.G + j) * 2;
+  };
+  auto o_of = [&](int p) {
+    return p < a.splits_a ? a.part_o_a + ((ia0 + p) * 32 + rr) * D : a.part_o_b + ((ib0 + (p - a.splits_a)) * a.G + j) * D;
+  };
   float acc[PER];
 #pragma unroll
   for (int e = 0; e < PER; ++e) acc[e] = 0.f;
-  float lsum = 0.f;
-  for (int s = 0; s < a.splits_a; ++s) {
-    const size_t base = (ia0 + s) * 32 + rr;
-    const float ls = a.part_ml_a[base * 2 + 1];
-    if (ls > 0.f) {
-      const float wgt = __builtin_amdgcn_exp2f((a.part_ml_a[base * 2] - mx) * a.sc);
-      lsum += ls * wgt;
-#pragma unroll
-      for (int e = 0; e < PER; ++e) acc[e] += wgt * a.part_o_a[base * D + lane * PER + e];
-    }
+  // The reference maximum first (64 partials at a time, one per lane, so that their loads are in
+  // flight together), then the weighted sums in the fixed order of the partials: the weights of
+  // a group of 64 come from the lanes, and the loads of the partial outputs do not depend on
+  // each other (a partial without a visible key has l = 0 and weight 0; what it holds is read
+  // and dropped).
+  float mx = -1e30f;
+  for (int p0 = 0; p0 < np; p0 += 64) {
+    const float mv = p0 + lane < np ? ml_of(p0 + lane)[0] : -1e30f;
+    mx = fmaxf(mx, mv);
   }
-  for (int s = 0; s < a.splits_b; ++s) {
-    const size_t base = (ib0 + s) * a.G + j;
-    const float ls = a.part_ml_b[base * 2 + 1];
-    if (ls > 0.f) {
-      const float wgt = __builtin_amdgcn_exp2f((a.part_ml_b[base * 2] - mx) * a.sc);
-      lsum += ls * wgt;
 #pragma unroll
-      for (int e = 0; e < PER; ++e) acc[e] += wgt * a.part_o_b[base * D + lane * PER + e];
+  for (int off = 32; off; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  float lsum = 0.f;
+  for (int p0 = 0; p0 < np; p0 += 64) {
+    float wl = 0.f, wgt = 0.f;
+    if (p0 + lane < np) {
+      const float* ml = ml_of(p0 + lane);
+      const float ls = ml[1];
+      if (ls > 0.f) {
+        wgt = __builtin_amdgcn_exp2f((ml[0] - mx) * a.sc);
+        wl = ls * wgt;
+      }
+    }
+    const int n = min(64, np - p0);
+#pragma unroll 4
+    for (int i = 0; i < n; ++i) {
+      const float wi = __shfl(wgt, i);
+      lsum += __shfl(wl, i);
+      const float* o = o_of(p0 + i) + lane * PER;  // (read in any case, so that the loads of several partials overlap)
+#pragma unroll
+      for (int e = 0; e < PER; ++e) {
+        const float x = o[e];
+        acc[e] += wi != 0.f ? wi * x : 0.f;
+      }
     }
   }
   const float inv = 1.f / lsum;
@@ -845,8 +994,8 @@ int make_plan(const dag_decode_desc_t* d, int hq, int hkv, int D, DecodePlan* p)
     else
       while (ca > 8 && base_a * dag_ceil_div(d->max_shared_pages, ca) < 512) ca /= 2;
   }
-  if (!knobs.chunk_b)
-    while (cb > 4 && base_b * dag_ceil_div(d->max_branch_pages, cb) < 1024) cb /= 2;
+  if (!knobs.chunk_b)  // (wide: the own items are workgroups of several waves, about two per compute unit)
+    while (cb > 4 && base_b * dag_ceil_div(d->max_branch_pages, cb) < (p->wide ? 512 : 1024)) cb /= 2;
   p->chunk_a = ca;
   p->chunk_b = cb;
   p->splits_a = d->max_shared_pages > 0 ? (int)dag_ceil_div(d->max_shared_pages, ca) : 0;
@@ -862,44 +1011,6 @@ int make_plan(const dag_decode_desc_t* d, int hq, int hkv, int D, DecodePlan* p)
   p->off_ml_b = off; off += dag_align_up((size_t)ib * G * 2 * 4, 256);
   p->bytes = off + 256;
   return DAG_OK;
-}
-
-// A second stream per device, created at the first decode call that needs it and kept until the
-// process ends, with the two events of the fork/join.  Calls on one device share it; they are
-// ordered by the caller's streams through the events.
-struct SideStream {
-  hipStream_t stream;
-  hipEvent_t fork, join;
-};
-// One mutex for the table and for the enqueue phase of every call that uses a side stream: the
-// fork event, the launches and the join event of a call must not interleave with another
-// thread's, or one call's own-page items could be ordered behind the other call's event.
-std::mutex& side_mutex() {
-  static std::mutex mu;
-  return mu;
-}
-SideStream* side_stream_locked() {  // the caller holds side_mutex()
-  constexpr int MAX_DEV = 64;
-  static SideStream table[MAX_DEV];
-  static bool ready[MAX_DEV];
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
-  if (!ready[dev]) {
-    SideStream t;
-    if (hipStreamCreateWithFlags(&t.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-    if (hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) != hipSuccess) {
-      (void)hipStreamDestroy(t.stream);
-      return nullptr;
-    }
-    if (hipEventCreateWithFlags(&t.join, hipEventDisableTiming) != hipSuccess) {
-      (void)hipEventDestroy(t.fork);
-      (void)hipStreamDestroy(t.stream);
-      return nullptr;
-    }
-    table[dev] = t;
-    ready[dev] = true;
-  }
-  return &table[dev];
 }
 
 }  // namespace
@@ -954,8 +1065,7 @@ int static_scratch(void** out) {
   return DAG_OK;
 }
 
-// static_ws: the partials go to the library's own scratch array (ws / ws_bytes ignored), and the
-// own-page items stay on the caller's stream (no second stream is created or used).
+// static_ws: the partials go to the library's own scratch array (ws / ws_bytes ignored).
 int decode_impl(const dag_decode_desc_t* d, const void* q, const void* k_pool, const void* v_pool, void* out,
                 int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale, void* ws, size_t ws_bytes,
                 void* stream_, bool static_ws) {
@@ -1014,46 +1124,30 @@ int decode_impl(const dag_decode_desc_t* d, const void* q, const void* k_pool, c
   const unsigned nout = (unsigned)(d->n_live * hq);
   a.item_base = 0;
   unsigned items = (unsigned)(p.items_a + p.items_b);
-  SideStream* side = nullptr;
-  std::unique_lock<std::mutex> side_lock(side_mutex(), std::defer_lock);
   if (p.wide && p.items_a > 0) {
-    // Wide sibling groups: the shared items as workgroups of rb_max waves that stream the shared
-    // pages once.  The own items (single waves, next launch) fit beside them on the compute
-    // units, so they run on a second stream of the library, forked from and joined to the
-    // caller's stream with events (default priority; the pattern can be captured into a graph).
-    const unsigned groups = (unsigned)(d->n_groups * hkv * p.splits_a);
-    const unsigned threads = 64u * (unsigned)p.rb_max;
-    if (p.items_b > 0 && !static_ws) {
-      side_lock.lock();  // held until the join has been enqueued
-      side = side_stream_locked();
-      if (!side) return DAG_ERR_HIP;
-      DAG_HIP_CHECK(hipEventRecord(side->fork, stream));
-      DAG_HIP_CHECK(hipStreamWaitEvent(side->stream, side->fork, 0));
-    }
+    // Wide sibling groups: one launch of workgroups that share their K/V blocks through LDS, the
+    // shared items first (one workgroup streams a slice of the shared pages once for all rows),
+    // the own items behind them.
+    const unsigned shared_wgs = (unsigned)(d->n_groups * hkv * p.splits_a);
+    const unsigned threads = 64u * (unsigned)(p.rb_max * wide_nsub(p.rb_max, head_dim));
+    const int sm = wide_lds_bytes(p.rb_max, head_dim);
+    a.wide_shared = (int)shared_wgs;
     if (head_dim == 128) {
-      const int sm = WIDE_RING * wide_block_bytes<128>();
       if (hipFuncSetAttribute((const void*)k_decode_wide<128>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
         return DAG_ERR_HIP;
-      hipLaunchKernelGGL(k_decode_wide<128>, dim3(groups), dim3(threads), sm, stream, a);
+      hipLaunchKernelGGL(k_decode_wide<128>, dim3(shared_wgs + (unsigned)p.items_b), dim3(threads), sm, stream, a);
     } else {
-      const int sm = WIDE_RING * wide_block_bytes<64>();
       if (hipFuncSetAttribute((const void*)k_decode_wide<64>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
         return DAG_ERR_HIP;
-      hipLaunchKernelGGL(k_decode_wide<64>, dim3(groups), dim3(threads), sm, stream, a);
+      hipLaunchKernelGGL(k_decode_wide<64>, dim3(shared_wgs + (unsigned)p.items_b), dim3(threads), sm, stream, a);
     }
     DAG_LAUNCH_CHECK();
-    a.item_base = p.items_a;
-    items = (unsigned)p.items_b;
+    items = 0;
   }
-  hipStream_t s_items = side ? side->stream : stream;
   if (items > 0) {
-    if (head_dim == 128) hipLaunchKernelGGL(k_decode<128>, dim3(items), dim3(64), 0, s_items, a);
-    else hipLaunchKernelGGL(k_decode<64>, dim3(items), dim3(64), 0, s_items, a);
+    if (head_dim == 128) hipLaunchKernelGGL(k_decode<128>, dim3(items), dim3(64), 0, stream, a);
+    else hipLaunchKernelGGL(k_decode<64>, dim3(items), dim3(64), 0, stream, a);
     DAG_LAUNCH_CHECK();
-  }
-  if (side) {
-    DAG_HIP_CHECK(hipEventRecord(side->join, side->stream));
-    DAG_HIP_CHECK(hipStreamWaitEvent(stream, side->join, 0));
   }
   if (head_dim == 128) hipLaunchKernelGGL(k_decode_merge<128>, dim3(nout), dim3(64), 0, stream, a);
   else hipLaunchKernelGGL(k_decode_merge<64>, dim3(nout), dim3(64), 0, stream, a);
