@@ -70,14 +70,13 @@ def write_traffic(workload, fetch_csv, write_csv, out_path=TRAFFIC_JSON):
     entry = out.setdefault("workloads", {})[workload] = {"kernels": {}}
     for key, path in (("fetch", fetch_csv), ("write", write_csv)):
         agg = per_kernel(path)
-        # the calibration copy is the largest dispatch of a copy / elementwise kernel
-        cal = max((max(v) for k, v in agg.items() if short(k) is None and
-                   ("copy" in k.lower() or "elementwise" in k.lower())), default=None)
-        scale = CALIBRATION_KIB / cal if cal else None
+        # the calibration copy: the library's own copy kernel on 256 MiB
+        cal = [v for k, v in agg.items() if short(k) == "k_copy_calibration"]
+        scale = CALIBRATION_KIB / (sum(cal[0]) / len(cal[0])) if cal else None
         entry[key + "_scale"] = scale
         for k, v in agg.items():
             name = short(k)
-            if name is None or scale is None:
+            if name is None or scale is None or name == "k_copy_calibration":
                 continue
             v = v[len(v) // 2:]   # the later dispatches: steady state
             d = entry["kernels"].setdefault(name, {})
@@ -379,8 +378,8 @@ def main():
                     help="main = the timed region (configs 2 and 3) with the segment decode and the backward; "
                          "config4 / config5 = only that leg (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 256 MiB device copy (untimed): under rocprofv3 --pmc its "
-                         "FETCH_SIZE / WRITE_SIZE give the scale of those counters")
+                    help="also run one plain 256 MiB device copy by the library's copy kernel (untimed): under "
+                         "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the scale of those counters")
     ap.add_argument("--write-traffic", nargs=3, metavar=("WORKLOAD", "FETCH_CSV", "WRITE_CSV"),
                     help="no GPU work: turn two rocprofv3 counter files of a `--only WORKLOAD "
                          "--copy-calibration` run into that workload's entry of profiles/traffic.json")
@@ -401,7 +400,7 @@ def main():
     if args.copy_calibration:
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        B.dag_copy_calibration(dst, src)
         torch.cuda.synchronize()
         del src, dst
     extra = {}
@@ -412,7 +411,7 @@ def main():
         extra["config5_prefill"] = prefill_leg(c5, dev, n5, min(args.warmup, 2), "config5")
         torch.cuda.empty_cache()
         extra["config5_decode"] = decode_leg(config5_decode_cfg(), dev, args.steps, args.warmup + 20, "config5",
-                                             ("k_decode_wide<128>", "k_decode<128>", "k_decode_merge<128>"), copies=4)
+                                             ("k_decode_wide<128>", "k_decode_merge<128>"), copies=4)
     if args.only in ("all", "config4"):
         extra["config4_prefill"] = prefill_leg(dags.config(3), dev, max(1, min(args.steps, 20)),
                                                min(args.warmup, 5) + 10, "config4")

@@ -402,6 +402,13 @@ typedef struct {
 } dag_sched_step_t;
 int dag_sched_step(dag_sched_t* sched, dag_sched_step_t* out);
 
+/* Measurement aid, not part of the attention path: a plain device-to-device copy of `bytes`
+ * (a multiple of 16; both pointers DEVICE, 16-byte aligned, not overlapping) by a kernel of the
+ * library's own, k_copy_calibration.  Its reading of a hardware counter (HBM bytes fetched or
+ * written) under a profiler gives the scale of that counter on the machine at hand: it reads
+ * and writes exactly `bytes`.  Enqueued on `stream`; DAG_ERR_NULL / DAG_ERR_ALIGN. */
+int dag_copy_calibration(void* dst, const void* src, size_t bytes, void* stream);
+
 const char* dag_strerror(int code);
 int dag_version(void);
 

@@ -131,6 +131,7 @@ def lib():
         L.dag_prefill_paged_workspace_bytes.restype = C.c_size_t
         L.dag_attn_prefill_paged.argtypes = [C.POINTER(dag_paged_prefill_desc_t), vp, vp, vp, i32, vp, vp, i32, i32,
                                              i32, f32, vp, C.c_size_t, vp]
+        L.dag_copy_calibration.argtypes = [vp, vp, C.c_size_t, vp]
         L.dag_sched_create.argtypes = [i32, vp, vp, vp, vp, i32, i32, C.POINTER(vp)]
         L.dag_sched_destroy.argtypes = [vp]
         L.dag_sched_destroy.restype = None
@@ -141,7 +142,7 @@ def lib():
         for name in ("dag_prefill_tile_shape", "dag_meta_sizes", "dag_build_meta", "dag_rope_qk",
                      "dag_attn_prefill", "dag_attn_prefill_prepared", "dag_prefill_prepare_v",
                      "dag_kv_append_rope", "dag_attn_decode", "dag_attn_decode_static", "dag_attn_decode_segments",
-                     "dag_sched_create", "dag_attn_prefill_paged",
+                     "dag_sched_create", "dag_attn_prefill_paged", "dag_copy_calibration",
                      "dag_attn_prefill_bwd",
                      "dag_sched_step"):
             getattr(L, name).restype = C.c_int
@@ -372,6 +373,11 @@ def dag_attn_decode_segments(sdesc, q, k_pool, v_pool, out, workspace, softmax_s
         softmax_scale = 1.0 / float(d) ** 0.5
     _check(lib().dag_attn_decode_segments(C.byref(sdesc.c), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(out), hq, hkv,
                                           d, float(softmax_scale), _ptr(workspace), workspace.numel(), _stream()))
+
+
+def dag_copy_calibration(dst, src):
+    """Plain copy by the library's own kernel (the reference point of the HBM counters)."""
+    _check(lib().dag_copy_calibration(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream()))
 
 
 class PagedPrefillDesc:

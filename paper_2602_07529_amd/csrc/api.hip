@@ -185,6 +185,22 @@ extern "C" int dag_attn_prefill_paged(const dag_paged_prefill_desc_t* d, const v
   return launch_prefill_paged(pa, head_dim, (hipStream_t)stream_);
 }
 
+namespace {
+__global__ void __launch_bounds__(256) k_copy_calibration(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+}  // namespace
+
+extern "C" int dag_copy_calibration(void* dst, const void* src, size_t bytes, void* stream_) {
+  if (!dst || !src) return DAG_ERR_NULL;
+  if (!dag_aligned16(dst) || !dag_aligned16(src) || bytes % 16 != 0) return DAG_ERR_ALIGN;
+  if (bytes == 0) return DAG_OK;
+  hipLaunchKernelGGL(k_copy_calibration, dim3(4096), dim3(256), 0, (hipStream_t)stream_, (const u32x4*)src, (u32x4*)dst,
+                     bytes / 16);
+  DAG_LAUNCH_CHECK();
+  return DAG_OK;
+}
+
 extern "C" const char* dag_strerror(int code) {
   switch (code) {
     case DAG_OK: return "ok";
