@@ -1,24 +1,25 @@
 // bf16 DAG attention prefill for gfx950 (paper Eq. 2 + Eq. 3), MFMA 32x32x16 with fp32 accumulation.
 //
-// Work decomposition.  A work item is one 64-row query tile of one KV head with HG of that KV
-// head's query heads stacked, so every wave of the workgroup consumes the same K/V tiles.  A wave
-// owns RB 32-row blocks of one head (RB = 2: four waves, one per SIMD, each K/V operand read from
-// LDS feeds two MFMAs; RB = 1: eight waves).  The kernel is persistent: the grid has one
-// workgroup per CU; workgroup g processes items g and g + grid of the launch list (query tiles
-// heavy first, the head groups of a tile next to each other) and takes every further item from a
-// counter, one item ahead of its use.  The K/V stream of the next item is prefetched while the
-// current one finishes.
+// Work decomposition.  A work item is one query tile of one KV head with some of that KV head's
+// query heads, eight waves, each wave one 32-row block of one head, so every wave of the workgroup
+// consumes the same K/V tiles: 64-row tiles x 4 heads for full groups of four heads, 256-row tiles
+// x 1 head for one or two heads left over (their rows over the key tiles are derived from the
+// 64 x 64 block map, see k_wide_rows).  The kernel is persistent: the grid has one workgroup per
+// CU; workgroup g processes items g and g + grid of the launch list (query tiles heavy first, the
+// KV heads of a tile next to each other) and takes every further item from a counter, one item
+// ahead of its use.  The K/V stream of the next item is prefetched while the current one finishes.
 //
 // Only the key tiles the block map lists are visited.  The CSR row of a query tile lists its FULL
-// tiles first: those need no mask and run through the software pipeline below; PARTIAL tiles (and
-// a ragged last tile) follow and evaluate the per-token mask in a plain loop.
+// tiles first: after the first tile they run through a steady-state loop without any test but an
+// after-the-fact overflow check; PARTIAL tiles (and a ragged last tile) follow and go through the
+// general step with a per-token mask, leaving out the 32 x 32 blocks that the mask hides entirely.
 //
 // Software pipeline.  The matrix pipe and the vector ALU of a SIMD run concurrently only if one
 // instruction stream feeds both, so a wave works in steps of half a key tile (32 keys) and each
 // step interleaves three independent pieces:  scores of half g + 1 (MFMA),  the exponentials of
 // half g (vector ALU),  and the P V product of half g - 1 (MFMA).  A step is written slot by slot
-// (one LDS operand read, the MFMAs on one operand, a few vector instructions) with a scheduling
-// barrier after every slot, so the instruction order in the binary is the one written here.
+// (one LDS operand read, one MFMA, a few vector instructions) with a scheduling barrier after
+// every slot, so the instruction order in the binary is the one written here.
 //
 // Data movement.  K tiles (64 keys x D) and V^T tiles (D x 64 keys, from a key-tile-wise
 // transposed copy of V that a small pre-pass writes into the workspace) go from global memory
@@ -42,9 +43,11 @@
 // 32-key block is mapped to key pi(i) so that registers 0..7 / 8..15 of a score block hold 8
 // consecutive keys.
 //
-// Softmax.  Online softmax in the log2 domain.  The running maximum is only raised when some row
-// of the wave exceeds it by more than 2^8 (the accumulator rescale is then rare); probabilities
-// may exceed 1 by that factor, which fp32 accumulation and the final division absorb exactly.
+// Softmax.  Online softmax in the log2 domain on scores that are relative to a per-row reference
+// maximum (the accumulator of the score product starts at minus the reference).  The reference is
+// only raised when some row of the wave exceeds it by more than 2^8 (general step) or when a row's
+// probabilities of a half sum to 2^10 or more (steady state, found afterwards); probabilities may
+// exceed 1 by such a factor, which fp32 accumulation and the final division absorb exactly.
 #include <stdlib.h>
 #include <type_traits>
 
