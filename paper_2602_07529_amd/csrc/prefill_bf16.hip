@@ -744,6 +744,9 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
   const bool grabber = w == NW - 1;
   int grabbed = 0;
   uint32_t* const mbox = (uint32_t*)(Abase + NSTAGE * 256);
+  // after the mailbox: per wave, the piece of LDS that its output rows pass through
+  constexpr int OROW = 64 + 16;
+  unsigned char* const Obase = Abase + NSTAGE * 256 + 16 + w * (32 * OROW);
   int mslot = 0;
 
   // The K/V tile stream runs ahead of the computation, across the item boundary: `ti` groups have
@@ -1332,10 +1335,13 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
     TACC(8, t_loop, te0);
     TACC(9, te0, te1);
     TACC(3, te1, te2);
-    // ---- output.  A lane holds one row in 8-byte pieces (four consecutive dimensions), the two
-    // half waves next to each other: a store instruction writes 16 bytes of each of 32 rows.  The
-    // rows' cache lines are put together in the L2 (all 16 pieces of a line come from this wave,
-    // within a microsecond), and nothing here touches LDS or waits for a load in flight.
+    // ---- output.  A lane holds one row in 8-byte pieces (four consecutive dimensions).  Stored
+    // as they are, a store instruction writes 16 bytes of each of 32 rows, 4096 such fragments per
+    // item, and the stores took 3.7 us of the item (the compute units take the fragments one by
+    // one).  So the rows go through a private piece of LDS, 32 dimensions at a time ([32 rows][64
+    // bytes + 16 of padding]), and leave as 64-byte runs: four lanes per row, 16 rows per store.
+    // LDS is reached by inline assembly only (plain accesses would make the compiler wait for
+    // every tile load in flight); the piece belongs to this wave, so no barrier is involved.
     const int head = head_of(cur);
     const bool store = head_is_mine(cur);
 #pragma unroll
@@ -1345,17 +1351,36 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       const bool mine = store && row_of(cur, r) < cur.T;
       if (a.lse && mine && H == 0)
         a.lse[(size_t)token_of(cur, r) * a.hq + head] = M[r] * 0.6931471805599453f + logf(l_tot);
-      uint16_t* const orow = (uint16_t*)a.out + ((size_t)token_of(cur, r) * a.hq + head) * D + 4 * H;
-      if (mine) {
+      const uint32_t ow = lds_addr(Obase) + L * OROW + 8 * H;          // this lane's row in the piece
+      const uint32_t ord = lds_addr(Obase) + (lane >> 2) * OROW + (lane & 3) * 16;  // row lane / 4 (+ 16), 16-byte part lane % 4
+      uint16_t* orow[2];
+      bool omine[2];
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int jj = 0; jj < 2; ++jj) {
+        const int rr = cur.row0 + 32 * (rg * RB + r) + 16 * jj + (lane >> 2);
+        omine[jj] = store && rr < cur.T;
+        orow[jj] = (uint16_t*)a.out + ((size_t)(cur.cu + min(rr, cur.T - 1)) * a.hq + head) * D + 8 * (lane & 3);
+      }
 #pragma unroll
-          for (int r4 = 0; r4 < 4; ++r4) {  // dimensions 32 db + 8 r4 + 4 H .. + 3
-            u32x2 o;
-            o[0] = dag_pack_bf2(O[r][db][4 * r4] * inv, O[r][db][4 * r4 + 1] * inv);
-            o[1] = dag_pack_bf2(O[r][db][4 * r4 + 2] * inv, O[r][db][4 * r4 + 3] * inv);
-            *(u32x2*)(orow + 32 * db + 8 * r4) = o;
-          }
+      for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {  // dimensions 32 db + 8 r4 + 4 H .. + 3
+          u32x2 o;
+          o[0] = dag_pack_bf2(O[r][db][4 * r4] * inv, O[r][db][4 * r4 + 1] * inv);
+          o[1] = dag_pack_bf2(O[r][db][4 * r4 + 2] * inv, O[r][db][4 * r4 + 3] * inv);
+          asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(ow), "v"(o), "n"(16 * r4) : "memory");
+        }
+        u32x4 x0, x1;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\tds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(x0), "=&v"(x1)
+                     : "v"(ord), "n"(16 * OROW)
+                     : "memory");
+#ifdef DAGATTN_ABL_NOSTORE  // (development: timing without the output stores; results are missing)
+        asm volatile("" ::"v"(x0), "v"(x1));
+#else
+        if (omine[0]) *(u32x4*)(orow[0] + 32 * db) = x0;
+        if (omine[1]) *(u32x4*)(orow[1] + 32 * db) = x1;
+#endif
       }
     }
     TSTAMP(t_o);
@@ -1443,7 +1468,8 @@ void split_heads(int g, int* narrow, int* wide) {
 template <int D, int HG, int NRG, bool PAGED = false>
 int launch_one(const PrefillArgs& a, long max_tiles, hipStream_t stream) {
   constexpr int KPB = 64 / (D / 8);
-  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256) + 16;  // rings + node-id records + item mailbox
+  constexpr size_t sm = (size_t)NSTAGE * ((TN / KPB) * (1024 + 16) + (D / 8) * (1024 + 128) + 256) + 16 +
+                        (size_t)HG * NRG * 32 * (64 + 16);  // rings + node-id records + item mailbox + output pieces
   if (hipFuncSetAttribute((const void*)k_prefill_bf16<D, HG, NRG, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)sm) != hipSuccess)
     return DAG_ERR_HIP;
