@@ -913,6 +913,14 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
       asm volatile("" ::"v"(vis0[r]), "v"(rnode_nxt[r]));
     }
     asm volatile("" ::"v"(col_iss), "v"(col_nxt));
+    // Refill the rings (the cursor could not go past the end of the old `nxt`): group g goes into
+    // the slots of K tile g - NSTAGE and V^T tile g - 1 - NSTAGE, both read for the last time before
+    // the old item's last barrier.  Here, behind the arrival of the row data and not at the end of
+    // the item before: that arrival waits for every load in flight, and these loads have the whole
+    // first tile to land.
+#pragma unroll 1
+    while (ti - tc < NSTAGE && try_issue()) {
+    }
     scale_q();
     TCOUNT(11);
     TSTAMP(t_top);
@@ -1402,12 +1410,6 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
     if (iss_next) iss_next = 0;     // the cursor was already in what is now the current item
     else cursor_enter(cur, col_nxt);  // (all tiles of the old item were issued: start of the new one)
     if (has_next) col_nxt = load_cols(nxt, 0);
-    // refill the rings (the cursor could not go past the end of the old `nxt`): group g goes into
-    // the slots of K tile g - NSTAGE and V^T tile g - 1 - NSTAGE, both read for the last time before
-    // the last barrier (tile tc - 1 was the old item's last one)
-#pragma unroll 1
-    while (ti - tc < NSTAGE && try_issue()) {
-    }
     TSTAMP(t_sw);
     TACC(5, t_o, t_sw);
   }
