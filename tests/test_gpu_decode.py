@@ -154,6 +154,20 @@ def test_decode_config5_full_size_sampled_branches(own_len):
     assert torch.isfinite(out.float()).all()
 
 
+@pytest.mark.parametrize("hq,hkv,d,nb,shared,own", [(40, 8, 128, 32, 3000, 2100), (12, 2, 64, 20, 777, 1300),
+                                                    (16, 2, 128, 9, 50, 4000), (10, 1, 128, 7, 0, 700)])
+def test_decode_wide_groups_with_long_own_lists(hq, hkv, d, nb, shared, own):
+    """Wide sibling groups (more than 32 stacked rows per KV head) whose own page lists are long
+    enough to be cut into several slices, odd page counts, a shared context shorter than one
+    slice, and none at all (the single-wave path then takes everything): every branch."""
+    st = dags.decode_state(7000 + hq + nb, 2, nb, shared, own, hq, hkv, d, kv_scale=0.5, q_scale=0.5)
+    out, kp, vp = _gpu_decode(st, hq, hkv, d, 5e5)
+    branches = sorted(set(range(0, 2 * nb, 3)) | {2 * nb - 1})
+    ref = orc.attn_decode(st["desc"], dags.to_f64(st["q"]), dags.to_f64(kp), dags.to_f64(vp), branches=branches)
+    check_close(out[branches], ref[branches], torch.bfloat16, "wide decode, long own lists")
+    assert torch.isfinite(out.float()).all()
+
+
 def test_decode_config5_every_branch_of_one_kv_head():
     """Benchmark config 5 decode at full size, middle of its 256 steps (own length 640): all 64
     live branches, the five query heads of one KV head, against the oracle."""

@@ -81,6 +81,32 @@ def test_config4_random_multilevel_full_size_sampled_rows():
                    rows_per_seq=64)
 
 
+@pytest.mark.parametrize("hq,hkv,d", [(5, 1, 128), (6, 1, 128), (2, 2, 64), (9, 1, 64)])
+def test_left_over_heads_on_256_row_tiles_ragged_multilevel_dags(hq, hkv, d):
+    """Head groups of 5, 6, 1 and 9 (one or two heads beside the four-head items, or alone) on
+    sequences of 1 to 19 query tiles whose lengths leave a ragged 256-row tile: the rows of those
+    tiles over the key tiles are derived from the 64 x 64 block map on the device (mixed SKIP / FULL
+    / PARTIAL quartets, fully hidden 32-row blocks inside a visited tile); sampled rows of every
+    sequence and every head."""
+    rng = np.random.Generator(np.random.PCG64(4000 + hq + d))
+    dag_list = [dags.random_dag(rng, n_nodes=40, depth=5, len_lo=1, len_hi=60)[:2],
+                dags.fork_join(517, [64, 190, 3], 131),
+                dags.linear_chain([1]),
+                dags.random_dag(rng, n_nodes=70, depth=6, len_lo=3, len_hi=30)[:2],   # two visibility words
+                dags.linear_chain([255]), dags.linear_chain([257])]
+    _run_and_check(dag_list, hq, hkv, d, torch.bfloat16, 0.5, 5e5, 4100 + hq + d, rows_per_seq=80)
+
+
+def test_config5_head_shape_reduced_length_sampled_rows():
+    """Benchmark config 5's head configuration (40 query / 8 KV heads, G = 5) on its DAG shape at an
+    eighth of the length (2 x 6272 tokens: prefix 4096 -> 32 branches x 64 -> join 128): both
+    launches of the head split at many tiles per row."""
+    c = dags.config(4)
+    dag_list = [dags.fork_join(4096, [64] * 32, 128)] * 2
+    _run_and_check(dag_list, c["hq"], c["hkv"], c["d"], torch.bfloat16, c["scale"], c["theta"], c["seed"] + 9,
+                   rows_per_seq=48)
+
+
 def test_config2_one_sequence_every_row_of_one_kv_group():
     c = dags.config(1)
     dag_list = dags.config_dags(c)[:1]
