@@ -300,7 +300,33 @@ def _events(n):
     return [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
 
 
-def prefill_leg(cfg, dev, launches, warmup, workload_key):
+def backward_timing(pw, dev, calls, warmup):
+    """dag_attn_prefill_bwd on a prefill workload (after one forward that leaves the log-sum-exp):
+    ms per call between two events, and the same as useful TFLOP/s (2.5 x the forward's)."""
+    cfg = pw.cfg
+    lse = torch.empty(pw.T, cfg["hq"], dtype=torch.float32, device=dev)
+    B.dag_attn_prefill(pw.meta, pw.q, pw.k, pw.v, pw.out, lse)
+    dout = torch.randn(pw.q.shape, device=dev, generator=torch.Generator(device=dev).manual_seed(cfg["seed"])).to(pw.q.dtype)
+    dq, dk, dv = torch.empty_like(pw.q), torch.empty_like(pw.k), torch.empty_like(pw.v)
+    ws = torch.empty(B.dag_prefill_bwd_workspace_bytes(pw.meta, cfg["hq"], cfg["hkv"], cfg["d"]), dtype=torch.uint8, device=dev)
+    bwd = lambda: B.dag_attn_prefill_bwd(pw.meta, pw.q, pw.k, pw.v, pw.out, dout, lse, dq, dk, dv, workspace=ws)
+    for _ in range(warmup):
+        bwd()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(calls):
+        bwd()
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / calls
+    flops, _ = pw.useful_flops()
+    return ms, 2.5 * flops / (ms * 1e-3) / 1e12
+
+
+BWD_KERNELS = ("k_bwd_delta<128>", "k_bwd_weights", "k_bwd_tokvis", "k_bwd_order", "k_bwd_dq<128,4>", "k_bwd_dkv<128>")
+
+
+def prefill_leg(cfg, dev, launches, warmup, workload_key, with_bwd=False):
     """An extra prefill workload beside the timed region: the whole prefill path `launches` times,
     the attention kernel bracketed by events of its own.  Returns the JSON object of the leg."""
     pw = PrefillWork(cfg, dev, device_values=True)
@@ -323,7 +349,16 @@ def prefill_leg(cfg, dev, launches, warmup, workload_key):
     wide = g % 4 if g % 4 < 3 else 0
     kerns = (["k_prefill_bf16<%d,4,2,false>" % cfg["d"]] if g > wide else []) + \
             (["k_prefill_bf16<%d,1,8,false>" % cfg["d"]] if wide else [])
+    bwd = None
+    if with_bwd:
+        ms_bwd, tf_bwd = backward_timing(pw, dev, 3, 1)
+        bwd = {"metric": "dag_attn_prefill_bwd_useful_tflops", "value": tf_bwd, "unit": "TFLOP/s", "ms_per_call": ms_bwd,
+               "calls": 3, "roofline": {"bound": "mfma", "kernel": "+".join(BWD_KERNELS), "achieved": tf_bwd,
+                                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                        "frac": tf_bwd / MFMA_BF16_PEAK_TFLOPS,
+                                        "traffic": traffic_of(workload_key, *BWD_KERNELS)}}
     return {"metric": "dag_attn_prefill_useful_tflops", "value": flops / (ms_path * 1e-3) / 1e12, "unit": "TFLOP/s",
+            "prefill_bwd": bwd,
             "launches": launches, "ms_prefill_path(meta+rope+attn)": ms_path, "ms_attn_kernel": ms_attn,
             "min_ms_attn_kernel": float(np.min(attn)),
             "config": {"workload": cfg["name"], "batch": cfg["batch"], "tokens": pw.T, "hq": cfg["hq"],
@@ -414,7 +449,7 @@ def main():
                                              ("k_decode_wide<128>", "k_decode_merge<128>"), copies=4)
     if args.only in ("all", "config4"):
         extra["config4_prefill"] = prefill_leg(dags.config(3), dev, max(1, min(args.steps, 20)),
-                                               min(args.warmup, 5) + 10, "config4")
+                                               min(args.warmup, 5) + 10, "config4", with_bwd=True)
     if args.only in ("all", "paged"):
         extra["paged_prefill"] = paged_prefill_leg(dags.config(2), dev, max(1, min(args.steps, 10)), min(args.warmup, 3))
         torch.cuda.empty_cache()
@@ -468,23 +503,8 @@ def main():
     seg_gbs = sw.bytes / (ms_seg * 1e-3) / 1e9
 
     # beside the timed region: the backward of the prefill attention on the same workload
-    lse = torch.empty(pw.T, pw.cfg["hq"], dtype=torch.float32, device=dev)
-    B.dag_attn_prefill(pw.meta, pw.q, pw.k, pw.v, pw.out, lse)
-    dout = torch.randn(pw.q.shape, device=dev, generator=torch.Generator(device=dev).manual_seed(pw.cfg["seed"])).to(pw.q.dtype)
-    dq, dk, dv = torch.empty_like(pw.q), torch.empty_like(pw.k), torch.empty_like(pw.v)
-    bws = torch.empty(B.dag_prefill_bwd_workspace_bytes(pw.meta, pw.cfg["hq"], pw.cfg["hkv"], pw.cfg["d"]),
-                      dtype=torch.uint8, device=dev)
-    bwd = lambda: B.dag_attn_prefill_bwd(pw.meta, pw.q, pw.k, pw.v, pw.out, dout, lse, dq, dk, dv, workspace=bws)
     n_bwd = max(1, min(args.steps, 10))
-    for _ in range(min(args.warmup, 3)):
-        bwd()
-    bev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    bev[0].record()
-    for _ in range(n_bwd):
-        bwd()
-    bev[1].record()
-    torch.cuda.synchronize()
-    ms_bwd = bev[0].elapsed_time(bev[1]) / n_bwd
+    ms_bwd, bwd_tf = backward_timing(pw, dev, n_bwd, min(args.warmup, 3))
 
     flops, pairs = pw.useful_flops()
     mean = lambda xs: float(np.mean(xs))
@@ -492,9 +512,8 @@ def main():
     tflops_seg = flops / (ms_pre * 1e-3) / 1e12
     tflops_kernel = flops / (ms_attn * 1e-3) / 1e12
     dec_gbs = dw.bytes / (ms_deck * 1e-3) / 1e9
-    bwd_tf = 2.5 * flops / (ms_bwd * 1e-3) / 1e12
     cfg = pw.cfg
-    bwd_kernels = ("k_bwd_delta", "k_bwd_weights", "k_bwd_tokvis", "k_bwd_order", "k_bwd_dq<128,4>", "k_bwd_dkv<128>")
+    bwd_kernels = BWD_KERNELS
     res = {
         "metric": "dag_attn_prefill_useful_tflops",
         "value": tflops_seg,
