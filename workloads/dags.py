@@ -73,6 +73,8 @@ def random_dag(rng, n_nodes=64, depth=6, fan_lo=1, fan_hi=4, join_prob=0.3,
     Node ids are assigned level by level, so they are a topological order.
     Returns (node_len int32[N], anc uint64[N][W], parents list, level list).
     """
+    if n_nodes < depth:
+        raise ValueError("random_dag: %d nodes cannot fill %d levels" % (n_nodes, depth))
     while True:
         levels = [[0]]
         parents = [[]]
