@@ -389,8 +389,8 @@ extern "C" int dag_prefill_tile_shape(int32_t hq, int32_t hkv, int32_t head_dim,
     return DAG_OK;
   }
   if (dtype != DAG_BF16) return DAG_ERR_UNSUPPORTED;
-  // A workgroup owns two 32-row blocks of up to four stacked query heads: 64 query rows, and key
-  // tiles of 64 tokens, for every head configuration.
+  // The block map is 64 x 64 for every head configuration: four-head items work on 64 query rows,
+  // and the 256-row tiles of left-over heads are derived from four rows of this map.
   *tile_m = 64;
   *tile_n = 64;
   return DAG_OK;
