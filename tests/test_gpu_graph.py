@@ -1,6 +1,6 @@
-"""GPU: the attention entry points can be captured into a HIP graph (no allocation, no memset, the
-decode's second stream forked and joined with events) and replayed: every replay, with eager work
-and synchronisations in between, gives the bits of the eager call."""
+"""GPU: the attention entry points can be captured into a HIP graph (no allocation, no memset,
+everything on the capturing stream) and replayed: every replay, with eager work and
+synchronisations in between, gives the bits of the eager call."""
 import numpy as np
 import pytest
 import torch
@@ -31,10 +31,11 @@ def _capture_and_replay(step, out, n_replays=3):
             assert torch.equal(out, eager)
 
 
-def test_prefill_prepare_and_attention_in_a_graph():
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (5, 1)])   # four-head items only; a left-over head on 256-row tiles (two launches)
+def test_prefill_prepare_and_attention_in_a_graph(hq, hkv):
     dag_list = [dags.fork_join(300, [100, 90, 64], 70), dags.linear_chain([130, 77])]
     T = int(sum(int(np.sum(L)) for L, _ in dag_list))
-    hq, hkv, d = 8, 2, 128
+    d = 128
     q, k, v = dags.make_qkv(17, T, hq, hkv, d, 0.5, torch.bfloat16)
     _, meta = build_meta(dag_list, hq, hkv, d, torch.bfloat16)
     qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
@@ -49,7 +50,7 @@ def test_prefill_prepare_and_attention_in_a_graph():
     _capture_and_replay(step, out)
 
 
-@pytest.mark.parametrize("hq,hkv,nb", [(8, 2, 4), (10, 2, 7)])   # 16 stacked rows; 35 rows -> wide groups, second stream
+@pytest.mark.parametrize("hq,hkv,nb", [(8, 2, 4), (10, 2, 7)])   # 16 stacked rows; 35 rows -> wide groups
 def test_decode_step_in_a_graph(hq, hkv, nb):
     d = 128
     st = dags.decode_state(700 + hq, n_seqs=2, n_branches=nb, shared_len=300, branch_len=45, hq=hq, hkv=hkv, d=d)
@@ -97,3 +98,16 @@ def test_segment_decode_step_in_a_graph():
         torch.cuda.synchronize()
         assert torch.equal(out, replayed)
         assert not torch.equal(out[0], torch.zeros_like(out[0]))
+
+
+def test_paged_prefill_in_a_graph():
+    """Table kernels and the attention launch of dag_attn_prefill_paged, replayed."""
+    from tests.test_gpu_prefill_paged import _multilevel
+    hq, hkv, d = 8, 2, 128
+    st = dags.decode_segments_state(33, [_multilevel(6)], [[8, 6, 4]], hq, hkv, d, kv_scale=0.7, q_scale=0.7,
+                                    new_tokens=[[72, 100, 6]])
+    pd = B.PagedPrefillDesc(st["paged"], DEV)
+    kp, vp, q = st["k_pool"].to(DEV), st["v_pool"].to(DEV), st["q"].to(DEV)
+    out = torch.zeros_like(q)
+    ws = torch.empty(B.dag_prefill_paged_workspace_bytes(pd), dtype=torch.uint8, device=DEV)
+    _capture_and_replay(lambda: B.dag_attn_prefill_paged(pd, q, kp, vp, out, ws), out)
