@@ -22,6 +22,9 @@
 // Tiles go global -> registers -> LDS: the next tile is fetched into registers while the current
 // one is multiplied, and stored to LDS between two workgroup barriers.
 // fp32 inputs take the plain kernels at the end of the file (the accuracy path).
+#include <stdlib.h>
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -34,6 +37,7 @@ struct BwdArgs {
   const float* lse;
   uint16_t *dq, *dk, *dv;
   float* delta;  // [T][hq]
+  float* nlse2;  // [T][hq]  -lse log2(e)
   int32_t *kt_weight, *kt_order;        // [total key tiles] launch order of the dK/dV workgroups
   uint64_t* tok_vis0;                   // [T] first visibility word of every token's node
   int total_ktiles;
@@ -108,7 +112,10 @@ __global__ void __launch_bounds__(256) k_bwd_delta(BwdArgs a) {
   }
 #pragma unroll
   for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o);
-  if (part == 0 && row < a.total_rows) a.delta[row] = s;
+  if (part == 0 && row < a.total_rows) {
+    a.delta[row] = s;
+    a.nlse2[row] = -a.lse[row] * LOG2E;
+  }
 }
 
 template <int D, int HG>
@@ -306,73 +313,27 @@ constexpr int dkv_smem_bytes() {
   return 2 * BM * (D + 8) * 2 + 2 * BM * 4 + BM * 4 + BM * 8;
 }
 
-// One workgroup per pair of key tiles (128 keys) and KV head: wave w owns keys 32 w .. 32 w + 31 of
-// the pair, with their K and V rows as B operands in registers and dK^T, dV^T accumulators for
-// them.  The workgroup walks over the query tiles that see either key tile and over the query
-// heads of the group, one (tile, head) at a time: its Q and dO rows and their transposed images go
-// through LDS for all four waves.  The next (tile, head) is fetched into registers while the
-// current one is computed.
-template <int D>
-__global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
+// The walk of one workgroup of the dK/dV kernels (pair of key tiles x KV head; wave w owns keys
+// 32 w .. 32 w + 31 of the pair, with their K and V rows as B operands in registers and dK^T, dV^T
+// accumulators for them) over the query tiles from the last one down and over the query heads of
+// the group, one (tile, head) at a time: its Q and dO rows go through LDS (row-major, padded) for
+// all four waves, the next (tile, head) is fetched into registers while the current one is
+// computed.  `pair_flag(qt)` returns flag of tile 0 | flag of tile 1 << 2 of the pair for query
+// tile qt, or 0 where the walk is to leave the tile out.  Pairs of a tile that are all visible
+// run without a single test, the others evaluate Eq. 3 and the sequence end per element.
+template <int D, typename PairFlag>
+__device__ __forceinline__ void dkv_general_walk(const BwdArgs& a, unsigned char* smem, PairFlag&& pair_flag, int QT, int T,
+                                                 int cu, int hk, int nbase, int my_kt, int nj, int j, bool key_ok,
+                                                 const bf16x8* kf, const bf16x8* vf, f32x16* dK, f32x16* dV) {
   constexpr int LD = D + 8, DB = D / 32;
   constexpr int NP = BM * (D / 8) / 256;  // 16-byte pieces per thread and staged tile
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* const sQ = (uint16_t*)smem;                  // [BM][LD]
   uint16_t* const sdO = sQ + BM * LD;                    // [BM][LD]
   float* const sLse = (float*)(sdO + BM * LD);           // [BM]  (log2 units)
   float* const sDl = sLse + BM;                          // [BM]
   int* const sNodeR = (int*)(sDl + BM);                  // [BM]
   uint64_t* const sVis0 = (uint64_t*)(sNodeR + BM);      // [BM]
-  __shared__ uint8_t sFlag[MAX_QT_LDS];                  // block-map column of the pair: flag of tile 0 | flag of tile 1 << 2
-  // (the KV head is the fast index of the launch: workgroups go to the XCDs round robin, so with 8
-  // KV heads every XCD's L2 holds the Q / dO tiles of one head group only, and the workgroups of a
-  // group walk over the query tiles from the last one down, i.e. side by side)
-  const int hk = blockIdx.x % a.hkv, kt = a.kt_order[blockIdx.x / a.hkv];  // heaviest pairs first
-  const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
-  const int ktl = kt - a.ktile_start[b];
-  if (ktl & 1) return;  // the workgroup of the even tile takes the pair (odd tiles come last in the order)
-  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
-  const int QT = (T + BM - 1) / BM, KT = (T + BN - 1) / BN;
-  const uint8_t* bm = a.block_map + a.block_map_off[b];
-  const int nbase = a.node_start[b];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, L = lane & 31, H = lane >> 5;
-  const int my_kt = ktl + (w >> 1);          // this wave's key tile
-  const bool tile_ok = my_kt < KT;
-  const int j = ktl * BN + 32 * w + L;       // this lane's key
-  const bool key_ok = j < T;
-  const int jc = min(j, T - 1);
-  const size_t koff = ((size_t)(cu + jc) * a.hkv + hk) * D;
-  bf16x8 kf[D / 16], vf[D / 16];
-#pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    kf[s] = *(const bf16x8*)(a.k + koff + 16 * s + 8 * H);
-    vf[s] = *(const bf16x8*)(a.v + koff + 16 * s + 8 * H);
-  }
-  const int nj = a.tok_node[cu + jc];
-  f32x16 dK[DB], dV[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) dK[db][e] = dV[db][e] = 0.f;
-
-  // iteration space: (query tile that sees the pair, query head of the group)
-  // (read once: a load of the map inside the loop would sit, with its full latency, in front of
-  // every tile; sequences with more query tiles than the array holds read the map directly)
-  const bool flags_in_lds = QT <= MAX_QT_LDS;
-  if (flags_in_lds) {
-    for (int x = tid; x < QT; x += 256) {
-      const int f0 = bm[(int64_t)x * KT + ktl];
-      const int f1 = ktl + 1 < KT ? bm[(int64_t)x * KT + ktl + 1] : 0;
-      sFlag[x] = (uint8_t)(f0 | (f1 << 2));
-    }
-    __syncthreads();
-  }
-  auto pair_flag = [&](int qt) {
-    if (flags_in_lds) return (int)sFlag[qt];
-    const int f0 = bm[(int64_t)qt * KT + ktl];
-    const int f1 = ktl + 1 < KT ? bm[(int64_t)qt * KT + ktl + 1] : 0;
-    return f0 | (f1 << 2);
-  };
   auto next_tile = [&](int qt) {  // last query tile <= qt with a visible pair, -1 if none
     while (qt >= 0 && pair_flag(qt) == 0) --qt;
     return qt;
@@ -536,23 +497,457 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
   }
 #ifdef BWD_TIMING
   if ((blockIdx.x == 0 || blockIdx.x == 8 * 40) && lane == 0)
-    printf("block %d wave %d: total %lld | sync1 %lld commit %lld sync2 %lld fetch-issue %lld compute %lld | iterations %lld\n",
+    printf("general walk, block %d wave %d: total %lld | sync1 %lld commit %lld sync2 %lld fetch-issue %lld compute %lld | iterations %lld\n",
            (int)blockIdx.x, w, clock64() - t_begin, tacc[0], tacc[1], tacc[2], tacc[3], tacc[4], tacc[5]);
 #endif
-  if (key_ok) {  // column = this lane's key, rows = d: every lane writes its key's row
+#undef TT
+}
+
+// Writes the dK and dV rows of a wave's 32 keys (column = this lane's key, rows = d: every lane
+// writes its key's row).
+template <int D>
+__device__ __forceinline__ void dkv_store(const BwdArgs& a, size_t koff, bool key_ok, int H, const f32x16* dK, const f32x16* dV) {
+  if (!key_ok) return;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+  for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        u32x2 ok2, ov2;
-        ok2[0] = dag_pack_bf2(dK[db][4 * e4] * a.scale, dK[db][4 * e4 + 1] * a.scale);
-        ok2[1] = dag_pack_bf2(dK[db][4 * e4 + 2] * a.scale, dK[db][4 * e4 + 3] * a.scale);
-        ov2[0] = dag_pack_bf2(dV[db][4 * e4], dV[db][4 * e4 + 1]);
-        ov2[1] = dag_pack_bf2(dV[db][4 * e4 + 2], dV[db][4 * e4 + 3]);
-        *(u32x2*)(a.dk + koff + 32 * db + 8 * e4 + 4 * H) = ok2;
-        *(u32x2*)(a.dv + koff + 32 * db + 8 * e4 + 4 * H) = ov2;
-      }
+    for (int e4 = 0; e4 < 4; ++e4) {
+      u32x2 ok2, ov2;
+      ok2[0] = dag_pack_bf2(dK[db][4 * e4] * a.scale, dK[db][4 * e4 + 1] * a.scale);
+      ok2[1] = dag_pack_bf2(dK[db][4 * e4 + 2] * a.scale, dK[db][4 * e4 + 3] * a.scale);
+      ov2[0] = dag_pack_bf2(dV[db][4 * e4], dV[db][4 * e4 + 1]);
+      ov2[1] = dag_pack_bf2(dV[db][4 * e4 + 2], dV[db][4 * e4 + 3]);
+      *(u32x2*)(a.dk + koff + 32 * db + 8 * e4 + 4 * H) = ok2;
+      *(u32x2*)(a.dv + koff + 32 * db + 8 * e4 + 4 * H) = ov2;
+    }
+}
+
+// First dK/dV kernel (every head dimension; the only one for 64): the general walk over all tiles.
+template <int D>
+__global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
+  constexpr int DB = D / 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ uint8_t sFlag[MAX_QT_LDS];                  // block-map column of the pair: flag of tile 0 | flag of tile 1 << 2
+  // (the KV head is the fast index of the launch: workgroups go to the XCDs round robin, so with 8
+  // KV heads every XCD's L2 holds the Q / dO tiles of one head group only, and the workgroups of a
+  // group walk over the query tiles from the last one down, i.e. side by side)
+  const int hk = blockIdx.x % a.hkv, kt = a.kt_order[blockIdx.x / a.hkv];  // heaviest pairs first
+  const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
+  const int ktl = kt - a.ktile_start[b];
+  if (ktl & 1) return;  // the workgroup of the even tile takes the pair (odd tiles come last in the order)
+  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
+  const int QT = (T + BM - 1) / BM, KT = (T + BN - 1) / BN;
+  const uint8_t* bm = a.block_map + a.block_map_off[b];
+  const int nbase = a.node_start[b];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, L = lane & 31, H = lane >> 5;
+  const int my_kt = ktl + (w >> 1);          // this wave's key tile
+  const int j = ktl * BN + 32 * w + L;       // this lane's key
+  const bool key_ok = j < T;
+  const int jc = min(j, T - 1);
+  const size_t koff = ((size_t)(cu + jc) * a.hkv + hk) * D;
+  bf16x8 kf[D / 16], vf[D / 16];
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) {
+    kf[s] = *(const bf16x8*)(a.k + koff + 16 * s + 8 * H);
+    vf[s] = *(const bf16x8*)(a.v + koff + 16 * s + 8 * H);
   }
+  const int nj = a.tok_node[cu + jc];
+  f32x16 dK[DB], dV[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dK[db][e] = dV[db][e] = 0.f;
+
+  // (the map is read once: a load of it inside the loop would sit, with its full latency, in front
+  // of every tile; sequences with more query tiles than the array holds read the map directly)
+  const bool flags_in_lds = QT <= MAX_QT_LDS;
+  if (flags_in_lds) {
+    for (int x = tid; x < QT; x += 256) {
+      const int f0 = bm[(int64_t)x * KT + ktl];
+      const int f1 = ktl + 1 < KT ? bm[(int64_t)x * KT + ktl + 1] : 0;
+      sFlag[x] = (uint8_t)(f0 | (f1 << 2));
+    }
+    __syncthreads();
+  }
+  auto pair_flag = [&](int qt) {
+    if (flags_in_lds) return (int)sFlag[qt];
+    const int f0 = bm[(int64_t)qt * KT + ktl];
+    const int f1 = ktl + 1 < KT ? bm[(int64_t)qt * KT + ktl + 1] : 0;
+    return f0 | (f1 << 2);
+  };
+  dkv_general_walk<D>(a, smem, pair_flag, QT, T, cu, hk, nbase, my_kt, nj, j, key_ok, kf, vf, dK, dV);
+  dkv_store<D>(a, koff, key_ok, H, dK, dV);
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_bwd_dkv2: the dK/dV kernel for head dimension 128 with the data movement and the instruction
+// order of the forward kernel.  Same decomposition as k_bwd_dkv (pair of key tiles x KV head, wave
+// w owns keys 32 w .. 32 w + 31, iteration = (query tile, query head)), but
+//   * the Q and dO tiles go from global memory straight into LDS (16 bytes per lane, no staging
+//     registers) through a ring of NST stages; one bare s_barrier per iteration, in its middle:
+//     it publishes the stage of the NEXT iteration (every wave has waited for its own loads of
+//     that stage before) and frees the stage of the previous one, which the loads of iteration
+//     n + NST - 1 then fill, one load per MFMA slot;
+//   * a wave-level load writes 1 KiB of consecutive LDS, a block of 4 rows laid out
+//     [chunk / 4][row % 4][chunk % 4][16 B], blocks 1024 + 16 bytes apart: four consecutive lanes
+//     fetch 64 consecutive bytes, the 16-byte row reads (A operands of S = Q K^T, dP = dO V^T) of 16
+//     consecutive rows and the 8-byte transposing reads (A operands of dV^T += dO^T P,
+//     dK^T += Q^T dS) of 16 consecutive lanes both fall into 16 different bank groups;
+//   * an iteration whose pairs are all visible is written slot by slot (operand read of the MFMA
+//     PF slots ahead, wait, one MFMA, a share of the exponentials; a scheduling barrier after
+//     every slot): scores and dP of the two 32-row halves (32 MFMAs), then dV / dK of the two
+//     halves (32 MFMAs), with the exponentials of half 0 under the score MFMAs of half 1 and
+//     those of half 1 under the dV / dK MFMAs of half 0.  The operand reads are inline assembly
+//     with explicit lgkmcnt waits (LDS reads return in order); nothing branches while such reads
+//     are in flight, so no copy of a register that is still being written can be made.
+//   * masked and ragged iterations take the per-element path of k_bwd_dkv on the same LDS layout.
+// Every iteration, whatever its kind, passes the barrier once and issues LPS loads per wave
+// (past the end of the walk: loads of the sequence's first tile, never consumed), so the vmcnt
+// waits are constants.
+namespace dkv2 {
+constexpr int NST = 4;              // ring depth
+constexpr int LPS = 10;             // wave-level loads per stage and wave: 4 Q blocks, 4 dO blocks, 2 of row data
+constexpr int PF = 5;               // operands in flight ahead of their MFMA
+constexpr int BLK = 1024 + 16;
+constexpr int TILEB = 16 * BLK;     // 64 rows x 128 dims
+constexpr int RD = 2 * TILEB;       // row data: -lse log2(e) [64], delta [64], node id [64], first visibility word [64]
+constexpr int STAGEB = RD + 1280;
+constexpr int NSLOT = 64;
+constexpr int VAHEAD = 8;           // the row values (-lse, delta) of four rows are read this many slots before their first use
+constexpr int opnd_reads(int o) { return o < 32 ? 1 : 2; }
+// the scores of rows 4 x .. 4 x + 3 of half h are taken in slots 16 + 16 h + 4 x ..; their two row-value reads
+// go out VAHEAD slots earlier, i.e. before the operand read that slot waits for, so they have arrived with it
+constexpr int extra_reads(int slot) { return slot >= 16 - VAHEAD && slot < 48 - VAHEAD && slot % 4 == 0 ? 2 : 0; }
+constexpr int issued_through(int k) {  // LDS reads issued up to and including those of operand k
+  int t = 0;
+  for (int o = 0; o <= k; ++o) t += (o >= PF ? extra_reads(o - PF) : 0) + opnd_reads(o);
+  return t;
+}
+constexpr int wait_at(int i) {  // reads that may still be pending when MFMA i starts
+  const int last = i + PF < NSLOT ? i + PF : NSLOT - 1;
+  const int n = issued_through(last) - issued_through(i);
+  return n < 15 ? n : 15;
+}
+// byte offset (after the per-lane part) of operand i of the fast iteration
+constexpr int row_imm(int i) {  // i < 32: row operand of half i / 16, k-step (i % 16) / 2, of Q (even) or dO (odd)
+  return (i & 1) * TILEB + 8 * (i / 16) * BLK + (((i % 16) / 2) / 2) * 256 + (((i % 16) / 2) % 2) * 32;
+}
+constexpr int tr_imm(int i) {  // i >= 32: transposed operand (dims 32 db .., 16 rows) of dO (even) or Q (odd)
+  const int j = i - 32, h = j / 16, jj = j % 16, db = jj / 4, hh = (jj / 2) % 2;
+  return ((jj & 1) ? 0 : TILEB) + (8 * h + 4 * hh) * BLK + db * 256;
+}
+}  // namespace dkv2
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_only() {  // s_waitcnt vmcnt(N) (gfx9 encoding)
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+template <int N>
+__device__ __forceinline__ void wait_lgkmcnt_only() {
+  __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {  // byte address inside LDS of a __shared__ pointer
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+template <int A, int B, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (A < B) {
+    f(std::integral_constant<int, A>{});
+    static_for<A + 1, B>(f);
+  }
+}
+
+__global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
+  using namespace dkv2;
+  constexpr int D = 128, DB = D / 32;
+  typedef __attribute__((address_space(3))) void* lds_ptr_t;
+  typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+  typedef short v4i16 __attribute__((ext_vector_type(4)));
+  typedef short v8i16 __attribute__((ext_vector_type(8)));
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ uint8_t sFlag[MAX_QT_LDS];  // block-map column of the pair: flag of tile 0 | flag of tile 1 << 2
+  const int hk = blockIdx.x % a.hkv, kt = a.kt_order[blockIdx.x / a.hkv];  // heaviest pairs first
+  const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
+  const int ktl = kt - a.ktile_start[b];
+  if (ktl & 1) return;  // the workgroup of the even tile takes the pair
+  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
+  const int QT = (T + BM - 1) / BM, KT = (T + BN - 1) / BN;
+  const uint8_t* bm = a.block_map + a.block_map_off[b];
+  const int nbase = a.node_start[b];
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, L = lane & 31, H = lane >> 5;
+  const int my_kt = ktl + (w >> 1);
+  const int j = ktl * BN + 32 * w + L;  // this lane's key
+  const bool key_ok = j < T;
+  const int jc = min(j, T - 1);
+  const size_t koff = ((size_t)(cu + jc) * a.hkv + hk) * D;
+  bf16x8 kf[D / 16], vf[D / 16];
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) {
+    kf[s] = *(const bf16x8*)(a.k + koff + 16 * s + 8 * H);
+    vf[s] = *(const bf16x8*)(a.v + koff + 16 * s + 8 * H);
+  }
+  const int nj = a.tok_node[cu + jc];
+#ifdef DKV2_KV_AGPR
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) asm volatile("" : "+a"(kf[s]), "+a"(vf[s]));
+#endif
+  f32x16 dK[DB], dV[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dK[db][e] = dV[db][e] = 0.f;
+
+  // bit 4 of a pair's flags: the iteration runs in the steady-state loop (both key tiles exist, every
+  // pair of both is visible, nothing reaches past the end of the sequence)
+  auto with_fast_bit = [&](int qt, int f) {
+    return f | ((f == (2 | (2 << 2)) && (qt + 1) * BM <= T && (ktl + 2) * BN <= T) ? 16 : 0);
+  };
+  const bool flags_in_lds = QT <= MAX_QT_LDS;
+  if (flags_in_lds) {
+    for (int x = tid; x < QT; x += 256) {
+      const int f0 = bm[(int64_t)x * KT + ktl];
+      const int f1 = ktl + 1 < KT ? bm[(int64_t)x * KT + ktl + 1] : 0;
+      sFlag[x] = (uint8_t)with_fast_bit(x, f0 | (f1 << 2));
+    }
+  }
+  __syncthreads();
+  const uint32_t flag_base = lds_addr(sFlag);
+  // (the flags are read with an inline-assembly LDS read that waits for itself: the ring's loads
+  // write LDS too, and a compiler-visible LDS read might be made to wait for all of them)
+  auto pair_flag = [&](int qt) {
+    if (flags_in_lds) {
+      uint32_t v;
+      asm volatile("ds_read_u8 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(flag_base + (uint32_t)qt) : "memory");
+      return __builtin_amdgcn_readfirstlane((int)v);
+    }
+    const int f0 = bm[(int64_t)qt * KT + ktl];
+    const int f1 = ktl + 1 < KT ? bm[(int64_t)qt * KT + ktl + 1] : 0;
+    return __builtin_amdgcn_readfirstlane(with_fast_bit(qt, f0 | (f1 << 2)));
+  };
+  auto next_tile = [&](int qt) {  // last query tile <= qt of the steady-state kind, -1 if none
+    while (qt >= 0 && (pair_flag(qt) & 16) == 0) --qt;
+    return qt;
+  };
+  auto advance = [&](int& qt, int& g) {
+    if (qt < 0) return;
+    if (++g == a.G) {
+      g = 0;
+      qt = next_tile(qt - 1);
+    }
+  };
+
+  // ---- loads of one stage, in LPS pieces per wave (piece p of (tile qt, head g) into stage st)
+  const uint32_t row_stride = (uint32_t)(a.hq * D);  // elements
+  const uint32_t chunk8 = (uint32_t)(4 * (lane >> 4) + (lane & 3)) * 8;  // this lane's 16-byte chunk of a row
+  const int rsub = (lane >> 2) & 3;
+  // Row data, 4 bytes per lane, two loads per wave: waves 0 and 3 fetch -lse log2(e) and delta (the
+  // same values twice, so that every wave issues the same number of loads), wave 1 the node ids
+  // (twice), wave 2 the visibility words of rows 0..31 and 32..63.  Element index in the source:
+  // (token of the row) * rd_mul + head * rd_hmul + rd_add -- no branch where the loads are issued.
+  const float *rd_src0 = a.nlse2, *rd_src1 = a.delta;
+  int rd_mul = a.hq, rd_hmul = 1, rd_add = 0, rd_row0 = lane, rd_row1 = lane, rd_dst0 = 0, rd_dst1 = 256;
+  if (w == 1) {
+    rd_src0 = rd_src1 = (const float*)a.tok_node;
+    rd_mul = 1, rd_hmul = 0, rd_dst0 = rd_dst1 = 512;
+  } else if (w == 2) {
+    rd_src0 = rd_src1 = (const float*)a.tok_vis0;
+    rd_mul = 2, rd_hmul = 0, rd_add = lane & 1, rd_row0 = lane >> 1, rd_row1 = 32 + (lane >> 1), rd_dst0 = 768, rd_dst1 = 1024;
+  }
+  // The addresses of a stage's loads are prepared once per iteration, outside the slots (wave-uniform
+  // bases, four per-lane row offsets, two per-lane row-data pointers); a slot then only sets the LDS
+  // destination and issues its load.
+  struct IssueCtx {
+    const uint16_t *qb, *dob;  // first row of the tile, this head
+    uint32_t voff[4];          // element offset of this lane's chunk in block w + 4 i (rows past the sequence end re-read its last row)
+    const float *rd0, *rd1;    // this lane's two row-data words
+  };
+  auto prepare_issue = [&](int qt, int g) __attribute__((always_inline)) {
+    IssueCtx c;
+    const int qv = max(qt, 0);
+    const int r0 = qv * BM, n_in = min(BM, T - r0), h = hk * a.G + g;
+    const size_t slab = ((size_t)(cu + r0) * a.hq + h) * D;
+    c.qb = a.q + slab;
+    c.dob = a.dout + slab;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c.voff[i] = (uint32_t)min(4 * (w + 4 * i) + rsub, n_in - 1) * row_stride + chunk8;
+    const int hterm = rd_hmul * h + rd_add;
+    c.rd0 = rd_src0 + ((size_t)(cu + r0 + min(rd_row0, n_in - 1)) * rd_mul + hterm);
+    c.rd1 = rd_src1 + ((size_t)(cu + r0 + min(rd_row1, n_in - 1)) * rd_mul + hterm);
+    return c;
+  };
+  auto issue_piece = [&](int p, const IssueCtx& c, int st) __attribute__((always_inline)) {
+    unsigned char* const sb = smem + st * STAGEB;
+    if (p < 8) {
+      const int blk = w + 4 * (p & 3);
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)((p < 4 ? c.qb : c.dob) + c.voff[p & 3]),
+                                       (lds_ptr_t)(sb + (p < 4 ? 0 : TILEB) + blk * BLK), 16, 0, 0);
+    } else {
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p == 8 ? c.rd0 : c.rd1),
+                                       (lds_ptr_t)(sb + RD + (p == 8 ? rd_dst0 : rd_dst1)), 4, 0, 0);
+    }
+  };
+  auto sync_mid = [&]() __attribute__((always_inline)) {
+    wait_vmcnt_only<LPS>();        // this wave's loads of the next iteration's stage have landed
+    __builtin_amdgcn_s_barrier();  // (bare: a __syncthreads would drain the loads in flight)
+    asm volatile("" ::: "memory");
+  };
+
+  // per-lane parts of the LDS operand addresses
+  const uint32_t roff = (uint32_t)((L >> 2) * BLK + (L & 3) * 64 + H * 16);
+  const uint32_t toff = (uint32_t)(((lane >> 5) & 1) * BLK + ((lane & 15) >> 2) * 64 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8);
+  const uint32_t smem_base = lds_addr(smem);
+  const float sc = a.sc;
+
+  // ---- the iteration without tests, slot by slot
+  auto fast_iter = [&](int cs, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
+    const uint32_t sbase = smem_base + (uint32_t)cs * STAGEB;
+    const uint32_t ra = sbase + roff, ta = sbase + toff, va = sbase + RD + 16 * H;
+    bf16x8 op[NSLOT];
+    v4i16 lo[NSLOT], hi[NSLOT];
+    f32x4 nl[2][4], dl[2][4];
+    f32x16 S[2], dP[2];
+    float pt[2][16], dt[2][16];
+    bf16x8 pp[2][2], dss[2][2];
+    auto fetch_val = [&](auto hc, auto xc) __attribute__((always_inline)) {  // x = 0..3: -lse of rows 8 x + 4 H .., 4..7: delta
+      constexpr int h = decltype(hc)::value, x = decltype(xc)::value;
+      const uint32_t v = va;  // (named here: captures inside discarded branches trip the compiler)
+      f32x4(*const nlp)[4] = nl;
+      f32x4(*const dlp)[4] = dl;
+      if constexpr (x < 4)
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(nlp[h][x]) : "v"(v), "n"(128 * h + 32 * x));
+      else
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dlp[h][x - 4]) : "v"(v), "n"(256 + 128 * h + 32 * (x - 4)));
+    };
+    auto fetch = [&](auto ic) __attribute__((always_inline)) {
+      constexpr int i = decltype(ic)::value;
+      const uint32_t r = ra, t = ta;
+      bf16x8* const opp = op;
+      v4i16* const lop = lo;
+      v4i16* const hip_ = hi;
+#ifdef DKV2_ABL_NOLDS
+      if constexpr (i < NSLOT) { opp[i] = kf[i % 8]; lop[i] = __builtin_bit_cast(v4i16, r * 3u + (uint64_t)t); hip_[i] = lop[i]; }
+      if constexpr (false)
+#endif
+      if constexpr (i < 32)
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(opp[i]) : "v"(r), "n"(row_imm(i)));
+      else if constexpr (i < NSLOT)
+        asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+                     : "=&v"(lop[i]), "=&v"(hip_[i])
+                     : "v"(t), "n"(tr_imm(i)), "n"(tr_imm(i) + 2 * BLK));
+    };
+    static_for<0, PF>(fetch);
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, NSLOT>([&](auto ic) __attribute__((always_inline)) {
+      constexpr int i = decltype(ic)::value;
+      if constexpr (i == 32) {
+        sync_mid();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (extra_reads(i) != 0) {
+        constexpr int u = (i + VAHEAD - 16) / 4;  // rows 4 u .. 4 u + 3 of the 64
+        fetch_val(std::integral_constant<int, u / 4>{}, std::integral_constant<int, u % 4>{});
+        fetch_val(std::integral_constant<int, u / 4>{}, std::integral_constant<int, 4 + u % 4>{});
+      }
+      fetch(std::integral_constant<int, i + PF>{});
+      wait_lgkmcnt_only<wait_at(i)>();
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (i < 32) {
+        constexpr int rb = i / 16, s = (i % 16) / 2;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if constexpr ((i & 1) == 0)
+          S[rb] = mfma32(op[i], kf[s], s == 0 ? zero : S[rb]);
+        else
+          dP[rb] = mfma32(op[i], vf[s], s == 0 ? zero : dP[rb]);
+      } else {
+        constexpr int jx = i - 32, h = jx / 16, jj = jx % 16, db = jj / 4, hh = (jj / 2) % 2;
+        const v8i16 x = {lo[i][0], lo[i][1], lo[i][2], lo[i][3], hi[i][0], hi[i][1], hi[i][2], hi[i][3]};
+        const bf16x8 opx = __builtin_bit_cast(bf16x8, x);
+        if constexpr ((jj & 1) == 0)
+          dV[db] = mfma32(opx, pp[h][hh], dV[db]);
+        else
+          dK[db] = mfma32(opx, dss[h][hh], dK[db]);
+      }
+#ifndef DKV2_ABL_NOISSUE
+      if constexpr (i == 15 || i == 31) asm volatile("" : "+v"(S[i / 16]), "+v"(dP[i / 16]));
+      if constexpr (i >= 32 && i < 32 + LPS) issue_piece(i - 32, ictx, is);
+#endif
+#ifdef DKV2_ABL_NOEXP
+      if constexpr (i == 16) {
+        pp[0][0] = pp[0][1] = pp[1][0] = pp[1][1] = kf[0];
+        dss[0][0] = dss[0][1] = dss[1][0] = dss[1][1] = vf[0];
+      }
+      if constexpr (i == 33) asm volatile("" ::"v"(S[0]), "v"(dP[0]));
+      if constexpr (i == 47) asm volatile("" ::"v"(S[1]), "v"(dP[1]));
+      if constexpr (false) {
+#else
+      if constexpr (i >= 16 && i < 48) {
+#endif  // one score of half 0 (slots 16..31) or half 1 (slots 32..47)
+        constexpr int h = (i - 16) / 16, e = (i - 16) % 16;
+        const float pe = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl[h][e >> 2][e & 3]));
+        pt[h][e] = pe;
+        dt[h][e] = pe * (dP[h][e] - dl[h][e >> 2][e & 3]);
+        if constexpr ((e & 1) == 1) {
+          const uint32_t pw = dag_pack_bf2(pt[h][e - 1], pt[h][e]), dw = dag_pack_bf2(dt[h][e - 1], dt[h][e]);
+          typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+          const bf16x2 pb = __builtin_bit_cast(bf16x2, pw), db2 = __builtin_bit_cast(bf16x2, dw);
+          pp[h][e >> 3][(e & 7) - 1] = pb[0];
+          pp[h][e >> 3][e & 7] = pb[1];
+          dss[h][e >> 3][(e & 7) - 1] = db2[0];
+          dss[h][e >> 3][e & 7] = db2[1];
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+  // ---- the walk: query tiles from the last one down, the heads of the group inside
+  int cq = next_tile(QT - 1), cg = 0;  // the iteration being computed
+  int iq = cq, ig = 0;                 // the iteration whose loads are issued next
+#pragma unroll 1
+  for (int st = 0; st < NST - 1; ++st) {
+    const IssueCtx c = prepare_issue(iq, ig);
+#pragma unroll
+    for (int p = 0; p < LPS; ++p) issue_piece(p, c, st);
+    advance(iq, ig);
+  }
+  wait_vmcnt_only<(NST - 2) * LPS>();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  int cs = 0, is = NST - 1;
+#ifdef BWD_TIMING
+  long long n_fast = 0;
+  const long long t_begin = clock64();
+#endif
+  while (cq >= 0) {
+    // (register classes: the dK / dV accumulators stay in the accumulation registers over the whole
+    // loop, the scores are produced where the vector instructions can read them; without these
+    // hints the allocator moves three of the eight accumulators back and forth every iteration)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) asm volatile("" : "+a"(dK[db]), "+a"(dV[db]));
+    const IssueCtx ic = prepare_issue(iq, ig);
+    fast_iter(cs, ic, is);
+    advance(cq, cg);
+    advance(iq, ig);
+    cs = cs + 1 == NST ? 0 : cs + 1;
+    is = is + 1 == NST ? 0 : is + 1;
+#ifdef BWD_TIMING
+    ++n_fast;
+#endif
+  }
+  wait_vmcnt_only<0>();  // (the loads past the end of the walk)
+#ifdef BWD_TIMING
+  if ((blockIdx.x == 0 || blockIdx.x == 8 * 40) && lane == 0)
+    printf("dkv2 block %d wave %d: %lld steady-state iterations, %lld clocks each\n", (int)blockIdx.x, w, n_fast,
+           n_fast ? (clock64() - t_begin) / n_fast : 0);
+#endif
+  __syncthreads();  // the ring is free: the general walk lays its own tiles over it
+  // ---- everything else: the general walk over the tiles the loop above left out
+  auto rest_flag = [&](int qt) {
+    const int f = pair_flag(qt);
+    return (f & 16) ? 0 : f;
+  };
+  dkv_general_walk<D>(a, smem, rest_flag, QT, T, cu, hk, nbase, my_kt, nj, j, key_ok, kf, vf, dK, dV);
+  dkv_store<D>(a, koff, key_ok, H, dK, dV);
 }
 
 template <int D, int HG>
@@ -564,6 +959,15 @@ int launch_dq(const BwdArgs& a, long total_qtiles, hipStream_t stream) {
                      dim3(128 * HG), sm, stream, a);
   DAG_LAUNCH_CHECK();
   return DAG_OK;
+}
+
+// Development switch, read once: DAGATTN_BWD_DKV1=1 runs the first dK/dV kernel for every head dimension.
+bool dkv_first_version() {
+  static const bool v = [] {
+    const char* e = getenv("DAGATTN_BWD_DKV1");
+    return e && e[0] == '1';
+  }();
+  return v;
 }
 
 template <int D>
@@ -582,7 +986,14 @@ int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream
   hipLaunchKernelGGL(k_bwd_weights, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
   hipLaunchKernelGGL(k_bwd_order, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
   DAG_LAUNCH_CHECK();
-  hipLaunchKernelGGL((k_bwd_dkv<D>), dim3((unsigned)(total_ktiles * a.hkv)), dim3(256), sm, stream, a);
+  if (D == 128 && !dkv_first_version()) {
+    constexpr int sm2 = dkv2::NST * dkv2::STAGEB;
+    if (hipFuncSetAttribute((const void*)k_bwd_dkv2, hipFuncAttributeMaxDynamicSharedMemorySize, sm2) != hipSuccess)
+      return DAG_ERR_HIP;
+    hipLaunchKernelGGL(k_bwd_dkv2, dim3((unsigned)(total_ktiles * a.hkv)), dim3(256), sm2, stream, a);
+  } else {
+    hipLaunchKernelGGL((k_bwd_dkv<D>), dim3((unsigned)(total_ktiles * a.hkv)), dim3(256), sm, stream, a);
+  }
   DAG_LAUNCH_CHECK();
   return DAG_OK;
 }
@@ -773,8 +1184,8 @@ extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t h
   if (!m || hq < 1 || hkv < 1 || head_dim < 1 || m->sizes.total_tokens < 0 || m->sizes.total_qtiles < 0 ||
       m->sizes.total_ktiles < 0)
     return 0;
-  // delta [T][hq] fp32, weight and launch order of the key tiles, first visibility word per token
-  return dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) +
+  // delta and -lse log2(e) [T][hq] fp32 each, weight and launch order of the key tiles, first visibility word per token
+  return 2 * dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) +
          2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) +
          dag_align_up((size_t)m->sizes.total_tokens * 8, 256) + 256;
 }
@@ -821,7 +1232,8 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   a.lse = lse;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
   a.delta = (float*)dag_align_up((size_t)(uintptr_t)ws, 256);
-  a.kt_weight = (int32_t*)((char*)a.delta + dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256));
+  a.nlse2 = (float*)((char*)a.delta + dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256));
+  a.kt_weight = (int32_t*)((char*)a.nlse2 + dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256));
   a.kt_order = a.kt_weight + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4;
   a.total_ktiles = (int)m->sizes.total_ktiles;
   a.tok_vis0 = (uint64_t*)(a.kt_order + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4);

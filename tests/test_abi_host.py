@@ -373,7 +373,8 @@ def test_backward_argument_errors():
         setattr(m, name, FAKE)
     p = C.c_void_p(FAKE)
     need = L.dag_prefill_bwd_workspace_bytes(C.byref(m), 32, 8, 128)
-    assert need == 2560 + 2 * 256 + 256 + 256   # delta, weight and order of the one key tile, first visibility word of the 20 tokens
+    # delta and -lse log2(e), weight and order of the one key tile, first visibility word of the 20 tokens
+    assert need == 2 * 2560 + 2 * 256 + 256 + 256
     args = (32, 8, 128, 0.1, B.DAG_BF16)
     call = lambda *ptrs, a=args, ws=p, nb=need, meta=m: L.dag_attn_prefill_bwd(
         C.byref(meta) if meta is not None else None, *ptrs, *a, ws, nb, None)
