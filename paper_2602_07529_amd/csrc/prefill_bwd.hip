@@ -43,6 +43,10 @@ struct BwdArgs {
   int total_ktiles;
   const int32_t *cu_seqlens, *node_start, *tok_node, *qtile_start, *ktile_start;
   const int32_t* qtile_order;  // the forward's launch order: query tiles by descending number of visible key tiles
+  const int32_t* qtile_desc;   // [launch slot][8]: token offset and length of the sequence, first row of the tile, CSR row start,
+                               // tiles in the row, leading tiles without mask (FULL, not reaching past the end), node offset, -
+  const int32_t* qtile_col;    // CSR of the visible key tiles of every query tile, the FULL ones first
+  const uint8_t* qtile_flag;
   const uint64_t* node_vis;
   const int64_t* block_map_off;
   const uint8_t* block_map;
@@ -118,54 +122,80 @@ __global__ void __launch_bounds__(256) k_bwd_delta(BwdArgs a) {
   }
 }
 
-template <int D, int HG>
-__global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
-  constexpr int LD = D + 8;  // padded rows: the 16-byte operand reads of 32 consecutive rows spread over the banks
-  constexpr int NT = 128 * HG;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* const sK = (uint16_t*)smem;   // [BN][LD]
-  uint16_t* const sV = sK + BN * LD;      // [BN][LD]
-  int* const sNode = (int*)(sV + BN * LD);
-  __shared__ uint8_t sFlag[MAX_QT_LDS];  // the tile's row of the block map
-  const int qt = a.qtile_order[blockIdx.x], hk = blockIdx.y;  // heaviest tiles first
-  const int g = blockIdx.z * HG + (threadIdx.x >> 7);  // two waves per query head
-  const bool head_ok = g < a.G;
-  const int h = hk * a.G + min(g, a.G - 1);
-  const int b = dag_find_segment(a.qtile_start, a.n_seqs, qt);
-  const int cu = a.cu_seqlens[b], T = a.cu_seqlens[b + 1] - cu;
-  const int qtl = qt - a.qtile_start[b];
-  const int KT = (T + BN - 1) / BN;
-  const uint8_t* bm = a.block_map + a.block_map_off[b] + (int64_t)qtl * KT;
-  const int nbase = a.node_start[b];
-  const int tid = threadIdx.x, w = (tid >> 6) & 1, lane = tid & 63, L = lane & 31, H = lane >> 5;
-  const int i = qtl * BM + 32 * w + L;  // this lane's query row
-  const bool row_ok = i < T && head_ok;
-  const int ic = min(i, T - 1);
-  const size_t qoff = ((size_t)(cu + ic) * a.hq + h) * D;
-  bf16x8 qf[D / 16], dof[D / 16];
-#pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    qf[s] = *(const bf16x8*)(a.q + qoff + 16 * s + 8 * H);
-    dof[s] = *(const bf16x8*)(a.dout + qoff + 16 * s + 8 * H);
-  }
-  const float lse2 = a.lse[(size_t)(cu + ic) * a.hq + h] * LOG2E;
-  const float dl = a.delta[(size_t)(cu + ic) * a.hq + h];
-  const int ni = a.tok_node[cu + ic];
-  const uint64_t vis0 = a.node_vis[(int64_t)(nbase + ni) * a.W];
-  f32x16 dQ[D / 32];
+// The per-wave state of a dQ workgroup (64-row query tile x KV head x up to 4 of its query heads;
+// two waves per head, each with 32 query rows: one row per lane and half wave).
+template <int D>
+struct DqLane {
+  bf16x8 qf[D / 16], dof[D / 16];  // the row's Q and dO as B operands
+  float lse2, dl;                  // its log-sum-exp (log2 units) and delta
+  int i, ni;                       // its index in the sequence and its node
+  uint64_t vis0;                   // first visibility word of that node
+  bool row_ok;
+  size_t qoff;                     // element offset of the row in q / dout / dq
+};
+
+template <int D>
+__device__ __forceinline__ void dq_store(const BwdArgs& a, const DqLane<D>& me, int H, const f32x16* dQ) {
+  if (!me.row_ok) return;
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) dQ[db][e] = 0.f;
+    for (int e4 = 0; e4 < 4; ++e4) {
+      u32x2 o;
+      o[0] = dag_pack_bf2(dQ[db][4 * e4] * a.scale, dQ[db][4 * e4 + 1] * a.scale);
+      o[1] = dag_pack_bf2(dQ[db][4 * e4 + 2] * a.scale, dQ[db][4 * e4 + 3] * a.scale);
+      *(u32x2*)(a.dq + me.qoff + 32 * db + 8 * e4 + 4 * H) = o;
+    }
+}
 
-  const bool flags_in_lds = KT <= MAX_QT_LDS;
-  if (flags_in_lds) {
-    for (int x = tid; x < KT; x += NT) sFlag[x] = bm[x];
-    __syncthreads();
+// The visible key tiles of a query tile, FULL ones first (the forward's CSR row), copied to LDS at
+// set-up; rows longer than the arrays read the rest from global memory.  get() is an
+// inline-assembly LDS read that waits for itself: the loads of k_bwd_dq2's ring write LDS too, and
+// a compiler-visible LDS read might be made to wait for all of them.
+constexpr int MAX_ROW_LDS = 4096;
+struct TileList {
+  const int32_t* col;   // the row in global memory
+  const uint8_t* flag;
+  uint32_t lds_col, lds_flag;  // LDS byte addresses of the copies
+  template <int NT>
+  __device__ __forceinline__ void fill(int32_t* sCol, uint8_t* sFlg, int n) {
+    for (int x = threadIdx.x; x < min(n, MAX_ROW_LDS); x += NT) {
+      sCol[x] = col[x];
+      sFlg[x] = flag[x];
+    }
+    lds_col = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)sCol;
+    lds_flag = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)sFlg;
   }
-  // The key tiles go through a register stage: the next visible tile is fetched while the current
-  // one is multiplied (constant per-thread offsets, rows past the end re-read the last row and are
-  // zeroed on the way to LDS, no load depends on another).
+  __device__ __forceinline__ int tile(int n) const {
+    if (n < MAX_ROW_LDS) {
+      uint32_t v;
+      asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_col + 4u * (uint32_t)n) : "memory");
+      return __builtin_amdgcn_readfirstlane((int)v);
+    }
+    return __builtin_amdgcn_readfirstlane(col[n]);
+  }
+  __device__ __forceinline__ int flag_of(int n) const {
+    if (n < MAX_ROW_LDS) {
+      uint32_t v;
+      asm volatile("ds_read_u8 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_flag + (uint32_t)n) : "memory");
+      return __builtin_amdgcn_readfirstlane((int)v);
+    }
+    return __builtin_amdgcn_readfirstlane((int)flag[n]);
+  }
+};
+
+// The walk of a dQ workgroup over entries n0 .. n1 - 1 of its tile list, one key tile at a time:
+// the tile's K and V rows go through LDS (row-major, padded) for all the waves; the next tile is
+// fetched into registers while the current one is multiplied (constant per-thread offsets, rows
+// past the end re-read the last row and are zeroed on the way to LDS, no load depends on another).
+template <int D, int NT>
+__device__ __forceinline__ void dq_general_walk(const BwdArgs& a, unsigned char* smem, const TileList& tl, int n0, int n1, int T,
+                                                int cu, int hk, int nbase, const DqLane<D>& me, f32x16* dQ) {
+  constexpr int LD = D + 8;  // padded rows: the 16-byte operand reads of 32 consecutive rows spread over the banks
+  uint16_t* const sK = (uint16_t*)smem;   // [BN][LD]
+  uint16_t* const sV = sK + BN * LD;      // [BN][LD]
+  int* const sNode = (int*)(sV + BN * LD);
+  const int tid = threadIdx.x, lane = tid & 63, L = lane & 31, H = lane >> 5;
   constexpr int NPQ = (BN * (D / 8) + NT - 1) / NT;  // 16-byte pieces per thread and staged tile
   u32x4 rk[NPQ], rv[NPQ];
   int r_node = 0;
@@ -176,11 +206,6 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
     row_off[x] = (uint32_t)(c / (D / 8)) * (uint32_t)(a.hkv * D) + (uint32_t)(c % (D / 8)) * 8;
   }
   const uint32_t one_row = (uint32_t)(a.hkv * D);
-  auto tile_flag = [&](int kt) { return flags_in_lds ? (int)sFlag[kt] : (int)bm[kt]; };
-  auto next_tile = [&](int kt) {
-    while (kt < KT && tile_flag(kt) == 0) ++kt;
-    return kt;
-  };
   auto fetch = [&](int kt) {
     const int j0 = kt * BN, n_in = min(BN, T - j0);
     const size_t slab = ((size_t)(cu + j0) * a.hkv + hk) * D;
@@ -208,17 +233,20 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
     }
     if (tid < BN) sNode[tid] = r_node;
   };
-  int kt_next = next_tile(0);
-  if (kt_next < KT) fetch(kt_next);
-  while (kt_next < KT) {
+  if (n0 >= n1) return;
+  int kt_next = tl.tile(n0);
+  fetch(kt_next);
+  for (int n = n0; n < n1; ++n) {
     const int kt = kt_next;
-    const int flag = tile_flag(kt);
+    const int flag = tl.flag_of(n);
     const int j0 = kt * BN;
     __syncthreads();  // everybody is done with the tile in LDS
     commit(kt);
     __syncthreads();
-    kt_next = next_tile(kt + 1);
-    if (kt_next < KT) fetch(kt_next);  // in flight during the products below
+    if (n + 1 < n1) {
+      kt_next = tl.tile(n + 1);
+      fetch(kt_next);  // in flight during the products below
+    }
     const bool need_mask = flag == 1;
 #pragma unroll 1
     for (int hh = 0; hh < 2; ++hh) {
@@ -227,21 +255,21 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
       for (int e = 0; e < 16; ++e) S[e] = dP[e] = 0.f;
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {  // S^T = K Q^T, dP^T = V dO^T: rows = keys, column = this lane's query row
-        S = mfma32(*(const bf16x8*)(sK + (32 * hh + L) * LD + 16 * s + 8 * H), qf[s], S);
-        dP = mfma32(*(const bf16x8*)(sV + (32 * hh + L) * LD + 16 * s + 8 * H), dof[s], dP);
+        S = mfma32(*(const bf16x8*)(sK + (32 * hh + L) * LD + 16 * s + 8 * H), me.qf[s], S);
+        dP = mfma32(*(const bf16x8*)(sV + (32 * hh + L) * LD + 16 * s + 8 * H), me.dof[s], dP);
       }
       float ds[16];
       if (!need_mask && j0 + BN <= T) {  // every in-range row sees every key of the tile: no tests
 #pragma unroll
-        for (int e = 0; e < 16; ++e) ds[e] = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -lse2)) * (dP[e] - dl);
+        for (int e = 0; e < 16; ++e) ds[e] = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -me.lse2)) * (dP[e] - me.dl);
       } else {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int kk = 32 * hh + rho(e, H), j = j0 + kk;
-          bool ok = row_ok && j < T;
-          if (need_mask) ok = ok & visible(a, nbase, ni, i, sNode[kk], j, vis0);
-          const float p = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -lse2));
-          ds[e] = ok ? p * (dP[e] - dl) : 0.f;
+          bool ok = me.row_ok && j < T;
+          if (need_mask) ok = ok & visible(a, nbase, me.ni, me.i, sNode[kk], j, me.vis0);
+          const float p = __builtin_amdgcn_exp2f(fmaf(S[e], a.sc, -me.lse2));
+          ds[e] = ok ? p * (dP[e] - me.dl) : 0.f;
         }
       }
       const bf16x8 b0 = pack8(ds), b1 = pack8(ds + 8);
@@ -252,17 +280,63 @@ __global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
       }
     }
   }
-  if (row_ok) {
+}
+
+// The set-up both dQ kernels share: the descriptor of the launch slot, then which row this lane
+// owns and what it needs of it (no load depends on more than the descriptor).
+struct DqTile {
+  int cu, T, row0, c0, N, nfast, nbase;
+};
+__device__ __forceinline__ DqTile dq_tile(const BwdArgs& a) {
+  const int32_t* d = a.qtile_desc + (size_t)blockIdx.x * 8;  // heaviest tiles first
+  DqTile t;
+  t.cu = d[0], t.T = d[1], t.row0 = d[2], t.c0 = d[3], t.N = d[4], t.nfast = d[5], t.nbase = d[6];
+  return t;
+}
+template <int D, int HG>
+__device__ __forceinline__ void dq_setup(const BwdArgs& a, const DqTile& t, int hk, DqLane<D>& me) {
+  const int g = blockIdx.z * HG + (threadIdx.x >> 7);  // two waves per query head
+  const bool head_ok = g < a.G;
+  const int h = hk * a.G + min(g, a.G - 1);
+  const int tid = threadIdx.x, w = (tid >> 6) & 1, lane = tid & 63, L = lane & 31, H = lane >> 5;
+  me.i = t.row0 + 32 * w + L;
+  me.row_ok = me.i < t.T && head_ok;
+  const int ic = min(me.i, t.T - 1);
+  me.qoff = ((size_t)(t.cu + ic) * a.hq + h) * D;
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        u32x2 o;
-        o[0] = dag_pack_bf2(dQ[db][4 * e4] * a.scale, dQ[db][4 * e4 + 1] * a.scale);
-        o[1] = dag_pack_bf2(dQ[db][4 * e4 + 2] * a.scale, dQ[db][4 * e4 + 3] * a.scale);
-        *(u32x2*)(a.dq + qoff + 32 * db + 8 * e4 + 4 * H) = o;
-      }
+  for (int s = 0; s < D / 16; ++s) {
+    me.qf[s] = *(const bf16x8*)(a.q + me.qoff + 16 * s + 8 * H);
+    me.dof[s] = *(const bf16x8*)(a.dout + me.qoff + 16 * s + 8 * H);
   }
+  me.lse2 = a.lse[(size_t)(t.cu + ic) * a.hq + h] * LOG2E;
+  me.dl = a.delta[(size_t)(t.cu + ic) * a.hq + h];
+  me.ni = a.tok_node[t.cu + ic];
+  me.vis0 = a.tok_vis0[t.cu + ic];
+}
+
+// First dQ kernel (every head dimension and head grouping): the general walk over all tiles.
+template <int D, int HG>
+__global__ void __launch_bounds__(128 * HG) k_bwd_dq(BwdArgs a) {
+  constexpr int NT = 128 * HG;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int32_t sCol[MAX_ROW_LDS];
+  __shared__ uint8_t sFlg[MAX_ROW_LDS];
+  const DqTile t = dq_tile(a);
+  const int hk = blockIdx.y;
+  DqLane<D> me;
+  dq_setup<D, HG>(a, t, hk, me);
+  f32x16 dQ[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dQ[db][e] = 0.f;
+  TileList tl;
+  tl.col = a.qtile_col + t.c0;
+  tl.flag = a.qtile_flag + t.c0;
+  tl.fill<NT>(sCol, sFlg, t.N);
+  __syncthreads();
+  dq_general_walk<D, NT>(a, smem, tl, 0, t.N, t.T, t.cu, hk, t.nbase, me, dQ);
+  dq_store<D>(a, me, (threadIdx.x & 63) >> 5, dQ);
 }
 
 // Launch order of the dK/dV workgroups: heaviest first.  A workgroup takes a pair of key tiles
@@ -950,6 +1024,224 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   dkv_store<D>(a, koff, key_ok, H, dK, dV);
 }
 
+// ---------------------------------------------------------------------------------------------
+// k_bwd_dq2: the dQ kernel for head dimension 128 and four query heads per workgroup, with the data
+// movement and instruction order of k_bwd_dkv2.  Eight waves (head g = wave / 2, query rows
+// 32 (wave % 2) ..), two per SIMD, so that the vector and LDS instructions of one overlap the
+// MFMAs of the other.  The K and V tiles of the key tiles whose pairs are all visible go through
+// a ring of NST stages in the block layout described at k_bwd_dkv2 (4 loads per wave and stage),
+// one bare barrier per tile in its middle; a tile is 48 slots: S^T = K Q^T and dP^T = V dO^T of
+// the two 32-key halves (32 MFMAs, 16-byte row reads), then dQ^T += K^T dS^T of the two halves
+// (16 MFMAs, transposing reads), with the exponentials of half 0 under the score MFMAs of half 1
+// and those of half 1 under the dQ MFMAs of half 0.  The other tiles (masked, or reaching past the
+// end of the sequence) take the general walk afterwards.
+namespace dq2 {
+constexpr int NST = 4, LPS = 4, PF = 4, NSLOT = 48;
+constexpr int BLK = dkv2::BLK, TILEB = dkv2::TILEB, STAGEB = 2 * TILEB;  // K tile, V tile
+constexpr int opnd_reads(int o) { return o < 32 ? 1 : 2; }
+constexpr int issued_through(int k) {
+  int t = 0;
+  for (int o = 0; o <= k; ++o) t += opnd_reads(o);
+  return t;
+}
+constexpr int wait_at(int i) {
+  const int last = i + PF < NSLOT ? i + PF : NSLOT - 1;
+  const int n = issued_through(last) - issued_through(i);
+  return n < 15 ? n : 15;
+}
+constexpr int row_imm(int i) { return dkv2::row_imm(i); }  // half i / 16, k-step (i % 16) / 2, of K (even) or V (odd)
+constexpr int tr_imm(int i) {  // i >= 32: K^T operand of key half (i - 32) / 8, 16-key group x, dims 32 db ..
+  const int j = i - 32, hh = j / 8, x = (j % 8) / 4, db = j % 4;
+  return (8 * hh + 4 * x) * BLK + db * 256;
+}
+}  // namespace dq2
+
+__global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
+  using namespace dq2;
+  constexpr int D = 128, HG = 4, NT = 512;
+  typedef __attribute__((address_space(3))) void* lds_ptr_t;
+  typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+  typedef short v4i16 __attribute__((ext_vector_type(4)));
+  typedef short v8i16 __attribute__((ext_vector_type(8)));
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int32_t sCol[MAX_ROW_LDS];
+  __shared__ uint8_t sFlg[MAX_ROW_LDS];
+#ifdef BWD_TIMING
+  const long long t_start = clock64();
+#endif
+  const DqTile t = dq_tile(a);
+  const int hk = blockIdx.y, cu = t.cu, T = t.T;
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, L = lane & 31, H = lane >> 5;
+  DqLane<D> me;
+  dq_setup<D, HG>(a, t, hk, me);
+  f32x16 dQ[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dQ[db][e] = 0.f;
+  TileList tl;
+  tl.col = a.qtile_col + t.c0;
+  tl.flag = a.qtile_flag + t.c0;
+  tl.fill<NT>(sCol, sFlg, t.N);
+  __syncthreads();
+  const int NF = t.nfast;  // entries 0 .. NF - 1 of the list: every pair visible, inside the sequence
+
+  // ---- loads of one stage: wave w fetches blocks w and w + 8 of the K tile and of the V tile
+  const uint32_t row_stride = (uint32_t)(a.hkv * D);
+  const uint32_t chunk8 = (uint32_t)(4 * (lane >> 4) + (lane & 3)) * 8;
+  const int rsub = (lane >> 2) & 3;
+  struct IssueCtx {
+    const uint16_t *kb, *vb;
+    uint32_t voff[2];
+  };
+  auto prepare_issue = [&](int n) __attribute__((always_inline)) {
+    IssueCtx c;
+    const int kv = n < NF ? tl.tile(n) : 0;  // (past the end of the walk: the sequence's first tile, never consumed)
+    const int j0 = kv * BN, n_in = min(BN, T - j0);
+    const size_t slab = ((size_t)(cu + j0) * a.hkv + hk) * D;
+    c.kb = a.k + slab;
+    c.vb = a.v + slab;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) c.voff[i] = (uint32_t)min(4 * (w + 8 * i) + rsub, n_in - 1) * row_stride + chunk8;
+    return c;
+  };
+  auto issue_piece = [&](int p, const IssueCtx& c, int st) __attribute__((always_inline)) {
+    unsigned char* const sb = smem + st * STAGEB;
+    const int blk = w + 8 * (p & 1);
+    __builtin_amdgcn_global_load_lds((gbl_ptr_t)((p < 2 ? c.kb : c.vb) + c.voff[p & 1]),
+                                     (lds_ptr_t)(sb + (p < 2 ? 0 : TILEB) + blk * BLK), 16, 0, 0);
+  };
+  auto sync_mid = [&]() __attribute__((always_inline)) {
+    wait_vmcnt_only<LPS>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  const uint32_t roff = (uint32_t)((L >> 2) * BLK + (L & 3) * 64 + H * 16);
+  const uint32_t toff = (uint32_t)(((lane >> 5) & 1) * BLK + ((lane & 15) >> 2) * 64 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8);
+  const uint32_t smem_base = lds_addr(smem);
+  const float sc = a.sc, nl = -me.lse2, dl = me.dl;
+
+  auto fast_tile = [&](int cs, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
+    const uint32_t sbase = smem_base + (uint32_t)cs * STAGEB;
+    const uint32_t ra = sbase + roff, ta = sbase + toff;
+    bf16x8 op[NSLOT];
+    v4i16 lo[NSLOT], hi[NSLOT];
+    f32x16 S[2], dP[2];
+    float dt[2][16];
+    bf16x8 bds[2][2];
+    auto fetch = [&](auto ic) __attribute__((always_inline)) {
+      constexpr int i = decltype(ic)::value;
+      const uint32_t r = ra, t = ta;  // (named here: captures inside discarded branches trip the compiler)
+      bf16x8* const opp = op;
+      v4i16* const lop = lo;
+      v4i16* const hip_ = hi;
+#ifdef DKV2_ABL_NOLDS
+      if constexpr (i < NSLOT) { opp[i] = me.qf[i % 8]; lop[i] = __builtin_bit_cast(v4i16, r * 3u + (uint64_t)t); hip_[i] = lop[i]; }
+      if constexpr (false)
+#endif
+      if constexpr (i < 32)
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(opp[i]) : "v"(r), "n"(row_imm(i)));
+      else if constexpr (i < NSLOT)
+        asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+                     : "=&v"(lop[i]), "=&v"(hip_[i])
+                     : "v"(t), "n"(tr_imm(i)), "n"(tr_imm(i) + 2 * BLK));
+    };
+    auto score = [&](auto hc, auto ec) __attribute__((always_inline)) {  // dS of key e of half h (this lane's row), packed in pairs
+      constexpr int h = decltype(hc)::value, e = decltype(ec)::value;
+      dt[h][e] = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl)) * (dP[h][e] - dl);
+      if constexpr ((e & 1) == 1) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        const bf16x2 pk = __builtin_bit_cast(bf16x2, dag_pack_bf2(dt[h][e - 1], dt[h][e]));
+        bds[h][e >> 3][(e & 7) - 1] = pk[0];
+        bds[h][e >> 3][e & 7] = pk[1];
+      }
+    };
+    static_for<0, PF>(fetch);
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, NSLOT>([&](auto ic) __attribute__((always_inline)) {
+      constexpr int i = decltype(ic)::value;
+      if constexpr (i == 32) {
+        sync_mid();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      fetch(std::integral_constant<int, i + PF>{});
+      wait_lgkmcnt_only<wait_at(i)>();
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (i < 32) {
+        constexpr int hh = i / 16, s = (i % 16) / 2;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if constexpr ((i & 1) == 0)
+          S[hh] = mfma32(op[i], me.qf[s], s == 0 ? zero : S[hh]);
+        else
+          dP[hh] = mfma32(op[i], me.dof[s], s == 0 ? zero : dP[hh]);
+      } else {
+        constexpr int j = i - 32, hh = j / 8, x = (j % 8) / 4, db = j % 4;
+        const v8i16 t8 = {lo[i][0], lo[i][1], lo[i][2], lo[i][3], hi[i][0], hi[i][1], hi[i][2], hi[i][3]};
+        dQ[db] = mfma32(__builtin_bit_cast(bf16x8, t8), bds[hh][x], dQ[db]);
+      }
+#ifndef DKV2_ABL_NOISSUE
+      if constexpr (i >= 32 && i < 32 + LPS) issue_piece(i - 32, ictx, is);
+#endif
+#ifdef DKV2_ABL_NOEXP
+      if constexpr (i == 16) bds[0][0] = bds[0][1] = bds[1][0] = bds[1][1] = me.qf[0];
+      if constexpr (i == 33) asm volatile("" ::"v"(S[0]), "v"(dP[0]));
+      if constexpr (i == 47) asm volatile("" ::"v"(S[1]), "v"(dP[1]));
+      if constexpr (false)
+#endif
+      if constexpr (i >= 16 && i < 32) score(std::integral_constant<int, 0>{}, std::integral_constant<int, i - 16>{});
+#ifdef DKV2_ABL_NOEXP
+      if constexpr (false)
+#endif
+      if constexpr (i >= 32 && i < 40) {
+        score(std::integral_constant<int, 1>{}, std::integral_constant<int, 2 * (i - 32)>{});
+        score(std::integral_constant<int, 1>{}, std::integral_constant<int, 2 * (i - 32) + 1>{});
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+  // ---- the steady-state loop over the key tiles whose pairs are all visible
+  int in = 0;  // list entry whose loads are issued next
+#pragma unroll 1
+  for (int st = 0; st < NST - 1; ++st, ++in) {
+    const IssueCtx c = prepare_issue(in);
+#pragma unroll
+    for (int p = 0; p < LPS; ++p) issue_piece(p, c, st);
+  }
+  wait_vmcnt_only<(NST - 2) * LPS>();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  int cs = 0, is = NST - 1;
+#ifdef BWD_TIMING
+  long long n_fast = 0;
+  const long long t_begin = clock64();
+#endif
+  for (int n = 0; n < NF; ++n, ++in) {
+#ifdef BWD_TIMING
+    ++n_fast;
+#endif
+    const IssueCtx ic = prepare_issue(in);
+    fast_tile(cs, ic, is);
+    cs = cs + 1 == NST ? 0 : cs + 1;
+    is = is + 1 == NST ? 0 : is + 1;
+  }
+  wait_vmcnt_only<0>();  // (the loads past the end of the walk)
+#ifdef BWD_TIMING
+  const long long t_steady_end = clock64();
+#endif
+  __syncthreads();       // the ring is free: the general walk lays its own tiles over it
+  dq_general_walk<D, NT>(a, smem, tl, NF, t.N, T, cu, hk, t.nbase, me, dQ);
+#ifdef BWD_TIMING
+  const long long t_general_end = clock64();
+#endif
+  dq_store<D>(a, me, H, dQ);
+#ifdef BWD_TIMING
+  if ((blockIdx.x == 0 || blockIdx.x == 200) && blockIdx.y == 0 && lane == 0 && w == 0)
+    printf("dq2 block %d: set-up %lld, %lld steady-state tiles %lld clocks each, general walk %lld, store %lld\n", (int)blockIdx.x,
+           t_begin - t_start, n_fast, n_fast ? (t_steady_end - t_begin) / n_fast : 0, t_general_end - t_steady_end, clock64() - t_general_end);
+#endif
+}
+
 template <int D, int HG>
 int launch_dq(const BwdArgs& a, long total_qtiles, hipStream_t stream) {
   constexpr int sm = 2 * BN * (D + 8) * 2 + BN * 4;
@@ -974,15 +1266,24 @@ template <int D>
 int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream_t stream) {
   constexpr int RPB = 256 / (D / 8);  // rows per workgroup of k_bwd_delta
   hipLaunchKernelGGL((k_bwd_delta<D>), dim3((unsigned)((a.total_rows + RPB - 1) / RPB)), dim3(256), 0, stream, a);
+  const int total_tokens = (int)(a.total_rows / a.hq);
+  hipLaunchKernelGGL(k_bwd_tokvis, dim3((unsigned)((total_tokens + 255) / 256)), dim3(256), 0, stream, a, total_tokens);
   DAG_LAUNCH_CHECK();
-  const int rc = a.G >= 3 ? launch_dq<D, 4>(a, total_qtiles, stream)
-                          : a.G == 2 ? launch_dq<D, 2>(a, total_qtiles, stream) : launch_dq<D, 1>(a, total_qtiles, stream);
+  int rc;
+  if (D == 128 && a.G >= 3 && !dkv_first_version()) {
+    constexpr int sm2 = dq2::NST * dq2::STAGEB;
+    if (hipFuncSetAttribute((const void*)k_bwd_dq2, hipFuncAttributeMaxDynamicSharedMemorySize, sm2) != hipSuccess)
+      return DAG_ERR_HIP;
+    hipLaunchKernelGGL(k_bwd_dq2, dim3((unsigned)total_qtiles, (unsigned)a.hkv, (unsigned)((a.G + 3) / 4)), dim3(512), sm2, stream, a);
+    rc = hipGetLastError() == hipSuccess ? DAG_OK : DAG_ERR_HIP;
+  } else {
+    rc = a.G >= 3 ? launch_dq<D, 4>(a, total_qtiles, stream)
+                  : a.G == 2 ? launch_dq<D, 2>(a, total_qtiles, stream) : launch_dq<D, 1>(a, total_qtiles, stream);
+  }
   if (rc != DAG_OK) return rc;
   constexpr int sm = dkv_smem_bytes<D>();
   if (hipFuncSetAttribute((const void*)k_bwd_dkv<D>, hipFuncAttributeMaxDynamicSharedMemorySize, sm) != hipSuccess)
     return DAG_ERR_HIP;
-  const int total_tokens = (int)(a.total_rows / a.hq);
-  hipLaunchKernelGGL(k_bwd_tokvis, dim3((unsigned)((total_tokens + 255) / 256)), dim3(256), 0, stream, a, total_tokens);
   hipLaunchKernelGGL(k_bwd_weights, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
   hipLaunchKernelGGL(k_bwd_order, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
   DAG_LAUNCH_CHECK();
@@ -1202,7 +1503,7 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   if (m->n_seqs == 0 || m->sizes.total_tokens == 0) return DAG_OK;
   if (!q || !k || !v || !out || !dout || !lse || !dq || !dk || !dv) return DAG_ERR_NULL;
   if (!m->cu_seqlens || !m->node_start || !m->tok_node || !m->node_vis || !m->qtile_start || !m->ktile_start ||
-      !m->block_map_off || !m->block_map || !m->qtile_order)
+      !m->block_map_off || !m->block_map || !m->qtile_order || !m->qtile_desc || !m->qtile_col || !m->qtile_flag)
     return DAG_ERR_NULL;
   if (!dag_aligned16(q) || !dag_aligned16(k) || !dag_aligned16(v) || !dag_aligned16(out) || !dag_aligned16(dout) ||
       !dag_aligned16(dq) || !dag_aligned16(dk) || !dag_aligned16(dv))
@@ -1240,6 +1541,7 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   a.cu_seqlens = m->cu_seqlens; a.node_start = m->node_start; a.tok_node = m->tok_node;
   a.qtile_start = m->qtile_start; a.ktile_start = m->ktile_start;
   a.qtile_order = m->qtile_order;
+  a.qtile_desc = m->qtile_desc; a.qtile_col = m->qtile_col; a.qtile_flag = m->qtile_flag;
   a.node_vis = m->node_vis; a.block_map_off = m->block_map_off; a.block_map = m->block_map;
   a.n_seqs = m->n_seqs; a.W = m->words_per_node; a.hq = hq; a.hkv = hkv; a.G = hq / hkv;
   a.total_rows = (long)m->sizes.total_tokens * hq;
