@@ -687,19 +687,23 @@ constexpr int TILEB = 16 * BLK;     // 64 rows x 128 dims
 constexpr int RD = 2 * TILEB;       // row data: -lse log2(e) [64], delta [64], node id [64], first visibility word [64]
 constexpr int STAGEB = RD + 1280;
 constexpr int NSLOT = 64;
-constexpr int VAHEAD = 8;           // the row values (-lse, delta) of four rows are read this many slots before their first use
+constexpr int VAHEAD = 8;           // the row data of four rows are read this many slots before their first use
 constexpr int opnd_reads(int o) { return o < 32 ? 1 : 2; }
-// the scores of rows 4 x .. 4 x + 3 of half h are taken in slots 16 + 16 h + 4 x ..; their two row-value reads
-// go out VAHEAD slots earlier, i.e. before the operand read that slot waits for, so they have arrived with it
-constexpr int extra_reads(int slot) { return slot >= 16 - VAHEAD && slot < 48 - VAHEAD && slot % 4 == 0 ? 2 : 0; }
+// The scores of rows 4 x .. 4 x + 3 of half h are taken in slots 16 + 16 h + 4 x ..; the XR reads of their
+// row data (-lse and delta; with masks also the node ids and the visibility words, two reads) go out
+// VAHEAD slots earlier, i.e. before the operand read that slot waits for, so they have arrived with it.
+template <int XR>
+constexpr int extra_reads(int slot) { return slot >= 16 - VAHEAD && slot < 48 - VAHEAD && slot % 4 == 0 ? XR : 0; }
+template <int XR>
 constexpr int issued_through(int k) {  // LDS reads issued up to and including those of operand k
   int t = 0;
-  for (int o = 0; o <= k; ++o) t += (o >= PF ? extra_reads(o - PF) : 0) + opnd_reads(o);
+  for (int o = 0; o <= k; ++o) t += (o >= PF ? extra_reads<XR>(o - PF) : 0) + opnd_reads(o);
   return t;
 }
+template <int XR>
 constexpr int wait_at(int i) {  // reads that may still be pending when MFMA i starts
   const int last = i + PF < NSLOT ? i + PF : NSLOT - 1;
-  const int n = issued_through(last) - issued_through(i);
+  const int n = issued_through<XR>(last) - issued_through<XR>(i);
   return n < 15 ? n : 15;
 }
 // byte offset (after the per-lane part) of operand i of the fast iteration
@@ -761,10 +765,6 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     vf[s] = *(const bf16x8*)(a.v + koff + 16 * s + 8 * H);
   }
   const int nj = a.tok_node[cu + jc];
-#ifdef DKV2_KV_AGPR
-#pragma unroll
-  for (int s = 0; s < D / 16; ++s) asm volatile("" : "+a"(kf[s]), "+a"(vf[s]));
-#endif
   f32x16 dK[DB], dV[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -798,17 +798,14 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     const int f1 = ktl + 1 < KT ? bm[(int64_t)qt * KT + ktl + 1] : 0;
     return __builtin_amdgcn_readfirstlane(with_fast_bit(qt, f0 | (f1 << 2)));
   };
-  auto next_tile = [&](int qt) {  // last query tile <= qt of the steady-state kind, -1 if none
-    while (qt >= 0 && (pair_flag(qt) & 16) == 0) --qt;
-    return qt;
-  };
-  auto advance = [&](int& qt, int& g) {
-    if (qt < 0) return;
-    if (++g == a.G) {
-      g = 0;
-      qt = next_tile(qt - 1);
-    }
-  };
+  // Two pipelined loops: the iterations without tests, then (when a node has one visibility word)
+  // the masked ones; with more words per node the masked ones go to the general walk.
+#ifdef DKV2_NO_MASKS_IN_LOOP
+  const bool masks_in_loop = false;
+#else
+  const bool masks_in_loop = a.W == 1;
+#endif
+  auto kind_of = [&](int f) { return (f & 16) ? 0 : ((f & 15) != 0 && masks_in_loop) ? 1 : 2; };  // 2: general walk or nothing
 
   // ---- loads of one stage, in LPS pieces per wave (piece p of (tile qt, head g) into stage st)
   const uint32_t row_stride = (uint32_t)(a.hq * D);  // elements
@@ -873,24 +870,34 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   const float sc = a.sc;
 
   // ---- the iteration without tests, slot by slot
-  auto fast_iter = [&](int cs, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
+  auto pipelined_iter = [&](auto msk_c, int cs, int cur_qt, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
+    constexpr bool MSK = decltype(msk_c)::value;
+    constexpr int XR = MSK ? 5 : 2;
     const uint32_t sbase = smem_base + (uint32_t)cs * STAGEB;
-    const uint32_t ra = sbase + roff, ta = sbase + toff, va = sbase + RD + 16 * H;
+    const uint32_t ra = sbase + roff, ta = sbase + toff, va = sbase + RD + 16 * H, va2 = sbase + RD + 32 * H;
+    const int i0 = cur_qt * BM + 4 * H;  // this lane's rows of the tile: i0 + 32 h + 8 (e / 4) + e % 4
     bf16x8 op[NSLOT];
     v4i16 lo[NSLOT], hi[NSLOT];
     f32x4 nl[2][4], dl[2][4];
+    u32x4 nd[2][4], vs[2][4][2];  // (with masks) node ids and first visibility words of the rows
     f32x16 S[2], dP[2];
     float pt[2][16], dt[2][16];
     bf16x8 pp[2][2], dss[2][2];
-    auto fetch_val = [&](auto hc, auto xc) __attribute__((always_inline)) {  // x = 0..3: -lse of rows 8 x + 4 H .., 4..7: delta
+    // row data of rows 32 h + 8 x + 4 H .. + 3: -lse, delta, node ids, visibility words (two reads)
+    auto fetch_val = [&](auto hc, auto xc) __attribute__((always_inline)) {
       constexpr int h = decltype(hc)::value, x = decltype(xc)::value;
-      const uint32_t v = va;  // (named here: captures inside discarded branches trip the compiler)
+      const uint32_t v = va, v2 = va2;  // (named here: captures inside discarded branches trip the compiler)
       f32x4(*const nlp)[4] = nl;
       f32x4(*const dlp)[4] = dl;
-      if constexpr (x < 4)
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(nlp[h][x]) : "v"(v), "n"(128 * h + 32 * x));
-      else
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dlp[h][x - 4]) : "v"(v), "n"(256 + 128 * h + 32 * (x - 4)));
+      u32x4(*const ndp)[4] = nd;
+      u32x4(*const vsp)[4][2] = vs;
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(nlp[h][x]) : "v"(v), "n"(128 * h + 32 * x));
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dlp[h][x]) : "v"(v), "n"(256 + 128 * h + 32 * x));
+      if constexpr (MSK) {
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(ndp[h][x]) : "v"(v), "n"(512 + 128 * h + 32 * x));
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(vsp[h][x][0]) : "v"(v2), "n"(768 + 256 * h + 64 * x));
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(vsp[h][x][1]) : "v"(v2), "n"(768 + 256 * h + 64 * x + 16));
+      }
     };
     auto fetch = [&](auto ic) __attribute__((always_inline)) {
       constexpr int i = decltype(ic)::value;
@@ -898,10 +905,6 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
       bf16x8* const opp = op;
       v4i16* const lop = lo;
       v4i16* const hip_ = hi;
-#ifdef DKV2_ABL_NOLDS
-      if constexpr (i < NSLOT) { opp[i] = kf[i % 8]; lop[i] = __builtin_bit_cast(v4i16, r * 3u + (uint64_t)t); hip_[i] = lop[i]; }
-      if constexpr (false)
-#endif
       if constexpr (i < 32)
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(opp[i]) : "v"(r), "n"(row_imm(i)));
       else if constexpr (i < NSLOT)
@@ -917,13 +920,12 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
         sync_mid();
         __builtin_amdgcn_sched_barrier(0);
       }
-      if constexpr (extra_reads(i) != 0) {
+      if constexpr (extra_reads<XR>(i) != 0) {
         constexpr int u = (i + VAHEAD - 16) / 4;  // rows 4 u .. 4 u + 3 of the 64
         fetch_val(std::integral_constant<int, u / 4>{}, std::integral_constant<int, u % 4>{});
-        fetch_val(std::integral_constant<int, u / 4>{}, std::integral_constant<int, 4 + u % 4>{});
       }
       fetch(std::integral_constant<int, i + PF>{});
-      wait_lgkmcnt_only<wait_at(i)>();
+      wait_lgkmcnt_only<wait_at<XR>(i)>();
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (i < 32) {
         constexpr int rb = i / 16, s = (i % 16) / 2;
@@ -941,23 +943,18 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
         else
           dK[db] = mfma32(opx, dss[h][hh], dK[db]);
       }
-#ifndef DKV2_ABL_NOISSUE
-      if constexpr (i == 15 || i == 31) asm volatile("" : "+v"(S[i / 16]), "+v"(dP[i / 16]));
       if constexpr (i >= 32 && i < 32 + LPS) issue_piece(i - 32, ictx, is);
-#endif
-#ifdef DKV2_ABL_NOEXP
-      if constexpr (i == 16) {
-        pp[0][0] = pp[0][1] = pp[1][0] = pp[1][1] = kf[0];
-        dss[0][0] = dss[0][1] = dss[1][0] = dss[1][1] = vf[0];
-      }
-      if constexpr (i == 33) asm volatile("" ::"v"(S[0]), "v"(dP[0]));
-      if constexpr (i == 47) asm volatile("" ::"v"(S[1]), "v"(dP[1]));
-      if constexpr (false) {
-#else
-      if constexpr (i >= 16 && i < 48) {
-#endif  // one score of half 0 (slots 16..31) or half 1 (slots 32..47)
+      if constexpr (i >= 16 && i < 48) {  // one score of half 0 (slots 16..31) or half 1 (slots 32..47)
         constexpr int h = (i - 16) / 16, e = (i - 16) % 16;
-        const float pe = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl[h][e >> 2][e & 3]));
+        float pe = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl[h][e >> 2][e & 3]));
+        if constexpr (MSK) {  // Eq. 3 (one visibility word per node) and the end of the sequence
+          const int i_row = i0 + 32 * h + 8 * (e >> 2) + (e & 3);
+          const int ni = (int)nd[h][e >> 2][e & 3];
+          const u32x4 vw = vs[h][e >> 2][(e & 3) >> 1];
+          const uint64_t v0 = ((uint64_t)vw[2 * (e & 1) + 1] << 32) | vw[2 * (e & 1)];
+          const bool vis = ni == nj ? j <= i_row : (bool)((v0 >> (nj & 63)) & 1u);
+          pe = (key_ok && i_row < T && vis) ? pe : 0.f;
+        }
         pt[h][e] = pe;
         dt[h][e] = pe * (dP[h][e] - dl[h][e >> 2][e & 3]);
         if constexpr ((e & 1) == 1) {
@@ -974,51 +971,64 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     });
   };
 
-  // ---- the walk: query tiles from the last one down, the heads of the group inside
-  int cq = next_tile(QT - 1), cg = 0;  // the iteration being computed
-  int iq = cq, ig = 0;                 // the iteration whose loads are issued next
+  // ---- the walk of one kind of iteration: query tiles from the last one down, the heads of the group inside
+  auto ring_loop = [&](auto msk_c) __attribute__((always_inline)) {
+    constexpr int KIND = decltype(msk_c)::value ? 1 : 0;
+    auto next_tile = [&](int qt) {  // last query tile <= qt of this kind, -1 if none
+      while (qt >= 0 && kind_of(pair_flag(qt)) != KIND) --qt;
+      return qt;
+    };
+    auto advance = [&](int& qt, int& g) {
+      if (qt < 0) return;
+      if (++g == a.G) {
+        g = 0;
+        qt = next_tile(qt - 1);
+      }
+    };
+    int cq = next_tile(QT - 1), cg = 0;  // the iteration being computed
+    if (cq < 0) return;
+    int iq = cq, ig = 0;                 // the iteration whose loads are issued next
 #pragma unroll 1
-  for (int st = 0; st < NST - 1; ++st) {
-    const IssueCtx c = prepare_issue(iq, ig);
+    for (int st = 0; st < NST - 1; ++st) {
+      const IssueCtx c = prepare_issue(iq, ig);
 #pragma unroll
-    for (int p = 0; p < LPS; ++p) issue_piece(p, c, st);
-    advance(iq, ig);
-  }
-  wait_vmcnt_only<(NST - 2) * LPS>();
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  int cs = 0, is = NST - 1;
-#ifdef BWD_TIMING
-  long long n_fast = 0;
-  const long long t_begin = clock64();
-#endif
-  while (cq >= 0) {
-    // (register classes: the dK / dV accumulators stay in the accumulation registers over the whole
-    // loop, the scores are produced where the vector instructions can read them; without these
-    // hints the allocator moves three of the eight accumulators back and forth every iteration)
+      for (int p = 0; p < LPS; ++p) issue_piece(p, c, st);
+      advance(iq, ig);
+    }
+    wait_vmcnt_only<(NST - 2) * LPS>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    int cs = 0, is = NST - 1;
+    while (cq >= 0) {
+      // (register classes: the dK / dV accumulators stay in the accumulation registers over the
+      // whole loop; without the hint the allocator moves three of the eight back and forth every
+      // iteration)
 #pragma unroll
-    for (int db = 0; db < DB; ++db) asm volatile("" : "+a"(dK[db]), "+a"(dV[db]));
-    const IssueCtx ic = prepare_issue(iq, ig);
-    fast_iter(cs, ic, is);
-    advance(cq, cg);
-    advance(iq, ig);
-    cs = cs + 1 == NST ? 0 : cs + 1;
-    is = is + 1 == NST ? 0 : is + 1;
-#ifdef BWD_TIMING
-    ++n_fast;
-#endif
-  }
-  wait_vmcnt_only<0>();  // (the loads past the end of the walk)
-#ifdef BWD_TIMING
-  if ((blockIdx.x == 0 || blockIdx.x == 8 * 40) && lane == 0)
-    printf("dkv2 block %d wave %d: %lld steady-state iterations, %lld clocks each\n", (int)blockIdx.x, w, n_fast,
-           n_fast ? (clock64() - t_begin) / n_fast : 0);
-#endif
+      for (int db = 0; db < DB; ++db) asm volatile("" : "+a"(dK[db]), "+a"(dV[db]));
+      const IssueCtx ic = prepare_issue(iq, ig);
+      if (KIND == 0 || ((pair_flag(cq) >> (2 * (w >> 1))) & 3) != 0) {
+        pipelined_iter(msk_c, cs, cq, ic, is);
+      } else {  // no visible pair in this wave's key tile: only the ring's business
+        sync_mid();
+#pragma unroll
+        for (int p = 0; p < LPS; ++p) issue_piece(p, ic, is);
+      }
+      advance(cq, cg);
+      advance(iq, ig);
+      cs = cs + 1 == NST ? 0 : cs + 1;
+      is = is + 1 == NST ? 0 : is + 1;
+    }
+    wait_vmcnt_only<0>();  // (the loads past the end of the walk)
+    __builtin_amdgcn_s_barrier();  // every wave is done with the ring before the next loop refills it
+    asm volatile("" ::: "memory");
+  };
+  ring_loop(std::false_type{});
+  if (masks_in_loop) ring_loop(std::true_type{});
   __syncthreads();  // the ring is free: the general walk lays its own tiles over it
   // ---- everything else: the general walk over the tiles the loop above left out
   auto rest_flag = [&](int qt) {
     const int f = pair_flag(qt);
-    return (f & 16) ? 0 : f;
+    return kind_of(f) == 2 ? (f & 15) : 0;
   };
   dkv_general_walk<D>(a, smem, rest_flag, QT, T, cu, hk, nbase, my_kt, nj, j, key_ok, kf, vf, dK, dV);
   dkv_store<D>(a, koff, key_ok, H, dK, dV);
