@@ -690,7 +690,7 @@ constexpr int NSLOT = 64;
 constexpr int VAHEAD = 8;           // the row data of four rows are read this many slots before their first use
 constexpr int opnd_reads(int o) { return o < 32 ? 1 : 2; }
 // The scores of rows 4 x .. 4 x + 3 of half h are taken in slots 16 + 16 h + 4 x ..; the XR reads of their
-// row data (-lse and delta; with masks also the node ids and the visibility words, two reads) go out
+// row data (-lse and delta; with masks also the node ids) go out
 // VAHEAD slots earlier, i.e. before the operand read that slot waits for, so they have arrived with it.
 template <int XR>
 constexpr int extra_reads(int slot) { return slot >= 16 - VAHEAD && slot < 48 - VAHEAD && slot % 4 == 0 ? XR : 0; }
@@ -715,6 +715,20 @@ constexpr int tr_imm(int i) {  // i >= 32: transposed operand (dims 32 db .., 16
   return ((jj & 1) ? 0 : TILEB) + (8 * h + 4 * hh) * BLK + db * 256;
 }
 }  // namespace dkv2
+
+// Lane masks for the element tests of the pipelined kernels: comparisons that leave their result
+// in a scalar register pair, combined with scalar logic, applied with one v_cndmask.  (A
+// conditional expression on per-lane values can be compiled into a branch, and nothing may
+// branch while operand reads are in flight; per-lane 0 / 1 integers cost vector registers.)
+__device__ __forceinline__ uint64_t lanes_eq(uint32_t x, uint32_t y) { return __builtin_amdgcn_uicmp(x, y, 32); }
+__device__ __forceinline__ uint64_t lanes_ne(uint32_t x, uint32_t y) { return __builtin_amdgcn_uicmp(x, y, 33); }
+__device__ __forceinline__ uint64_t lanes_gt(int x, int y) { return __builtin_amdgcn_sicmp(x, y, 38); }
+__device__ __forceinline__ uint64_t lanes_ge(int x, int y) { return __builtin_amdgcn_sicmp(x, y, 39); }
+__device__ __forceinline__ float keep_lanes(float x, uint64_t lanes) {  // x where the lane's bit is set, else 0
+  float r;
+  asm("v_cndmask_b32 %0, 0, %1, %2" : "=v"(r) : "v"(x), "s"(lanes));
+  return r;
+}
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt_only() {  // s_waitcnt vmcnt(N) (gfx9 encoding)
@@ -765,6 +779,19 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     vf[s] = *(const bf16x8*)(a.v + koff + 16 * s + 8 * H);
   }
   const int nj = a.tok_node[cu + jc];
+  // (one visibility word per node) the nodes that see this lane's key: bit ni of `seen_by` = bit nj
+  // of node ni's word, i.e. the key's column of the sequence's visibility matrix
+  uint64_t seen_by = 0;
+  if (a.W == 1) {
+    const int n_nodes = a.node_start[b + 1] - nbase;
+    const uint64_t word = lane < n_nodes ? a.node_vis[nbase + lane] : 0;
+#pragma unroll
+    for (int ni = 0; ni < 64; ++ni) {
+      const uint64_t wn = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(word >> 32), ni) << 32) |
+                          (uint32_t)__builtin_amdgcn_readlane((int)word, ni);
+      seen_by |= ((wn >> (nj & 63)) & 1ull) << ni;
+    }
+  }
   f32x16 dK[DB], dV[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -872,32 +899,30 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   // ---- the iteration without tests, slot by slot
   auto pipelined_iter = [&](auto msk_c, int cs, int cur_qt, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
     constexpr bool MSK = decltype(msk_c)::value;
-    constexpr int XR = MSK ? 5 : 2;
+    constexpr int XR = MSK ? 3 : 2;
     const uint32_t sbase = smem_base + (uint32_t)cs * STAGEB;
-    const uint32_t ra = sbase + roff, ta = sbase + toff, va = sbase + RD + 16 * H, va2 = sbase + RD + 32 * H;
-    const int i0 = cur_qt * BM + 4 * H;  // this lane's rows of the tile: i0 + 32 h + 8 (e / 4) + e % 4
+    const uint32_t ra = sbase + roff, ta = sbase + toff, va = sbase + RD + 16 * H;
+    // this lane's rows of the tile are i0 + c, c = 32 h + 8 (e / 4) + e % 4, with i0 = 64 qt + 4 H:
+    // row before the end of the sequence (and key in use)  <=>  c < c_end;   key <= row  <=>  c >= c_key
+    const int i0 = cur_qt * BM + 4 * H;
+    const int c_end = key_ok ? T - i0 : 0, c_key = j - i0;
     bf16x8 op[NSLOT];
     v4i16 lo[NSLOT], hi[NSLOT];
     f32x4 nl[2][4], dl[2][4];
-    u32x4 nd[2][4], vs[2][4][2];  // (with masks) node ids and first visibility words of the rows
+    u32x4 nd[2][4];  // (with masks) node ids of the rows
     f32x16 S[2], dP[2];
     float pt[2][16], dt[2][16];
     bf16x8 pp[2][2], dss[2][2];
-    // row data of rows 32 h + 8 x + 4 H .. + 3: -lse, delta, node ids, visibility words (two reads)
+    // row data of rows 32 h + 8 x + 4 H .. + 3: -lse, delta, node ids
     auto fetch_val = [&](auto hc, auto xc) __attribute__((always_inline)) {
       constexpr int h = decltype(hc)::value, x = decltype(xc)::value;
-      const uint32_t v = va, v2 = va2;  // (named here: captures inside discarded branches trip the compiler)
+      const uint32_t v = va;  // (named here: captures inside discarded branches trip the compiler)
       f32x4(*const nlp)[4] = nl;
       f32x4(*const dlp)[4] = dl;
       u32x4(*const ndp)[4] = nd;
-      u32x4(*const vsp)[4][2] = vs;
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(nlp[h][x]) : "v"(v), "n"(128 * h + 32 * x));
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dlp[h][x]) : "v"(v), "n"(256 + 128 * h + 32 * x));
-      if constexpr (MSK) {
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(ndp[h][x]) : "v"(v), "n"(512 + 128 * h + 32 * x));
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(vsp[h][x][0]) : "v"(v2), "n"(768 + 256 * h + 64 * x));
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(vsp[h][x][1]) : "v"(v2), "n"(768 + 256 * h + 64 * x + 16));
-      }
+      if constexpr (MSK) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(ndp[h][x]) : "v"(v), "n"(512 + 128 * h + 32 * x));
     };
     auto fetch = [&](auto ic) __attribute__((always_inline)) {
       constexpr int i = decltype(ic)::value;
@@ -948,12 +973,11 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
         constexpr int h = (i - 16) / 16, e = (i - 16) % 16;
         float pe = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl[h][e >> 2][e & 3]));
         if constexpr (MSK) {  // Eq. 3 (one visibility word per node) and the end of the sequence
-          const int i_row = i0 + 32 * h + 8 * (e >> 2) + (e & 3);
-          const int ni = (int)nd[h][e >> 2][e & 3];
-          const u32x4 vw = vs[h][e >> 2][(e & 3) >> 1];
-          const uint64_t v0 = ((uint64_t)vw[2 * (e & 1) + 1] << 32) | vw[2 * (e & 1)];
-          const bool vis = ni == nj ? j <= i_row : (bool)((v0 >> (nj & 63)) & 1u);
-          pe = (key_ok && i_row < T && vis) ? pe : 0.f;
+          constexpr int c = 32 * h + 8 * (e >> 2) + (e & 3);  // row i0 + c of the sequence
+          const uint32_t ni = nd[h][e >> 2][e & 3];
+          const uint64_t same = lanes_eq(ni, (uint32_t)nj), caus = lanes_ge(c, c_key), inside = lanes_gt(c_end, c);
+          const uint64_t anc = lanes_ne((uint32_t)(seen_by >> (ni & 63u)) & 1u, 0u);
+          pe = keep_lanes(pe, inside & ((same & caus) | (~same & anc)));
         }
         pt[h][e] = pe;
         dt[h][e] = pe * (dP[h][e] - dl[h][e >> 2][e & 3]);
@@ -1046,17 +1070,35 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
 // and those of half 1 under the dQ MFMAs of half 0.  The other tiles (masked, or reaching past the
 // end of the sequence) take the general walk afterwards.
 namespace dq2 {
-constexpr int NST = 4, LPS = 4, PF = 4, NSLOT = 48;
-constexpr int BLK = dkv2::BLK, TILEB = dkv2::TILEB, STAGEB = 2 * TILEB;  // K tile, V tile
+constexpr int NST = 4, NSLOT = 48;
+template <bool MSK>
+constexpr int PF = MSK ? 3 : 4;      // operands in flight ahead of their MFMA (the masked tile has fewer registers to spare)
+constexpr int BLK = dkv2::BLK, TILEB = dkv2::TILEB;
+constexpr int ND = 2 * TILEB;        // node ids of the tile's keys [64] (masked tiles)
+constexpr int STAGEB = ND + 256;     // K tile, V tile, node ids
+constexpr int NAHEAD = 5;            // the node ids of four keys are read this many slots before their first use
 constexpr int opnd_reads(int o) { return o < 32 ? 1 : 2; }
+// The scores of a half are taken one per slot from slot 16 on (half 0) and two per slot from slot 32 on
+// (half 1).  Keys 8 x + 4 H .. + 3 of half hh are first needed in slot 16 + 4 x (hh = 0) or 32 + 2 x (hh = 1);
+// with masks their node ids are read NAHEAD slots earlier.  node_group(slot) = 4 hh + x of the read issued in
+// that slot, -1 if none.
+constexpr int node_group(int slot) {
+  for (int u = 0; u < 8; ++u)
+    if (slot == (u < 4 ? 16 + 4 * u : 32 + 2 * (u - 4)) - NAHEAD) return u;
+  return -1;
+}
+template <bool MSK>
+constexpr int extra_reads(int slot) { return MSK && node_group(slot) >= 0 ? 1 : 0; }
+template <bool MSK>
 constexpr int issued_through(int k) {
   int t = 0;
-  for (int o = 0; o <= k; ++o) t += opnd_reads(o);
+  for (int o = 0; o <= k; ++o) t += (o >= PF<MSK> ? extra_reads<MSK>(o - PF<MSK>) : 0) + opnd_reads(o);
   return t;
 }
+template <bool MSK>
 constexpr int wait_at(int i) {
-  const int last = i + PF < NSLOT ? i + PF : NSLOT - 1;
-  const int n = issued_through(last) - issued_through(i);
+  const int last = i + PF<MSK> < NSLOT ? i + PF<MSK> : NSLOT - 1;
+  const int n = issued_through<MSK>(last) - issued_through<MSK>(i);
   return n < 15 ? n : 15;
 }
 constexpr int row_imm(int i) { return dkv2::row_imm(i); }  // half i / 16, k-step (i % 16) / 2, of K (even) or V (odd)
@@ -1096,46 +1138,61 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
   __syncthreads();
   const int NF = t.nfast;  // entries 0 .. NF - 1 of the list: every pair visible, inside the sequence
 
-  // ---- loads of one stage: wave w fetches blocks w and w + 8 of the K tile and of the V tile
+  // ---- loads of one stage: wave w fetches blocks w and w + 8 of the K tile and of the V tile; for
+  // masked tiles every wave also fetches the node ids of the keys (the same 256 bytes from all
+  // eight: the number of loads a wave has in flight must not depend on the wave)
   const uint32_t row_stride = (uint32_t)(a.hkv * D);
   const uint32_t chunk8 = (uint32_t)(4 * (lane >> 4) + (lane & 3)) * 8;
   const int rsub = (lane >> 2) & 3;
   struct IssueCtx {
     const uint16_t *kb, *vb;
     uint32_t voff[2];
+    const int32_t* nodes;  // this lane's key of the tile
   };
-  auto prepare_issue = [&](int n) __attribute__((always_inline)) {
+  auto prepare_issue = [&](int n, int n_end) __attribute__((always_inline)) {
     IssueCtx c;
-    const int kv = n < NF ? tl.tile(n) : 0;  // (past the end of the walk: the sequence's first tile, never consumed)
+    const int kv = n < n_end ? tl.tile(n) : 0;  // (past the end of the walk: the sequence's first tile, never consumed)
     const int j0 = kv * BN, n_in = min(BN, T - j0);
     const size_t slab = ((size_t)(cu + j0) * a.hkv + hk) * D;
     c.kb = a.k + slab;
     c.vb = a.v + slab;
 #pragma unroll
     for (int i = 0; i < 2; ++i) c.voff[i] = (uint32_t)min(4 * (w + 8 * i) + rsub, n_in - 1) * row_stride + chunk8;
+    c.nodes = a.tok_node + cu + j0 + min(lane, n_in - 1);
     return c;
   };
   auto issue_piece = [&](int p, const IssueCtx& c, int st) __attribute__((always_inline)) {
     unsigned char* const sb = smem + st * STAGEB;
-    const int blk = w + 8 * (p & 1);
-    __builtin_amdgcn_global_load_lds((gbl_ptr_t)((p < 2 ? c.kb : c.vb) + c.voff[p & 1]),
-                                     (lds_ptr_t)(sb + (p < 2 ? 0 : TILEB) + blk * BLK), 16, 0, 0);
-  };
-  auto sync_mid = [&]() __attribute__((always_inline)) {
-    wait_vmcnt_only<LPS>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    if (p < 4) {
+      const int blk = w + 8 * (p & 1);
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)((p < 2 ? c.kb : c.vb) + c.voff[p & 1]),
+                                       (lds_ptr_t)(sb + (p < 2 ? 0 : TILEB) + blk * BLK), 16, 0, 0);
+    } else {
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)c.nodes, (lds_ptr_t)(sb + ND), 4, 0, 0);
+    }
   };
   const uint32_t roff = (uint32_t)((L >> 2) * BLK + (L & 3) * 64 + H * 16);
   const uint32_t toff = (uint32_t)(((lane >> 5) & 1) * BLK + ((lane & 15) >> 2) * 64 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8);
   const uint32_t smem_base = lds_addr(smem);
   const float sc = a.sc, nl = -me.lse2, dl = me.dl;
+  const int nq = me.ni, iq_row = me.i;
+  const uint64_t vis0 = me.vis0;
+  const bool row_ok = me.row_ok;
 
-  auto fast_tile = [&](int cs, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
+  // ---- one key tile, slot by slot; MSK: with Eq. 3 (one visibility word per node) and the end of the
+  // sequence tested per element
+  auto pipelined_tile = [&](auto msk_c, int cs, int kt, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
+    constexpr bool MSK = decltype(msk_c)::value;
+    constexpr int LPS = MSK ? 5 : 4, PFM = PF<MSK>;
     const uint32_t sbase = smem_base + (uint32_t)cs * STAGEB;
-    const uint32_t ra = sbase + roff, ta = sbase + toff;
+    const uint32_t ra = sbase + roff, ta = sbase + toff, na = sbase + ND + 16 * H;
+    // this lane's keys of the tile are j_lane + c, c = 32 hh + 8 (e / 4) + e % 4, with j_lane = 64 kt + 4 H:
+    // key before the end of the sequence (and row in use)  <=>  c < c_end;   key <= row  <=>  c <= c_row
+    const int j_lane = kt * BN + 4 * H;
+    const int c_end = row_ok ? T - j_lane : 0, c_row = iq_row - j_lane;
     bf16x8 op[NSLOT];
     v4i16 lo[NSLOT], hi[NSLOT];
+    u32x4 nk[8];  // (with masks) node ids of keys 32 hh + 8 x + 4 H .. + 3, at index 4 hh + x
     f32x16 S[2], dP[2];
     float dt[2][16];
     bf16x8 bds[2][2];
@@ -1145,10 +1202,6 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
       bf16x8* const opp = op;
       v4i16* const lop = lo;
       v4i16* const hip_ = hi;
-#ifdef DKV2_ABL_NOLDS
-      if constexpr (i < NSLOT) { opp[i] = me.qf[i % 8]; lop[i] = __builtin_bit_cast(v4i16, r * 3u + (uint64_t)t); hip_[i] = lop[i]; }
-      if constexpr (false)
-#endif
       if constexpr (i < 32)
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(opp[i]) : "v"(r), "n"(row_imm(i)));
       else if constexpr (i < NSLOT)
@@ -1158,7 +1211,15 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
     };
     auto score = [&](auto hc, auto ec) __attribute__((always_inline)) {  // dS of key e of half h (this lane's row), packed in pairs
       constexpr int h = decltype(hc)::value, e = decltype(ec)::value;
-      dt[h][e] = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl)) * (dP[h][e] - dl);
+      float p = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl));
+      if constexpr (MSK) {
+        constexpr int c = 32 * h + 8 * (e >> 2) + (e & 3);
+        const uint32_t nj = nk[4 * h + (e >> 2)][e & 3];
+        const uint64_t same = lanes_eq(nj, (uint32_t)nq), caus = lanes_ge(c_row, c), inside = lanes_gt(c_end, c);
+        const uint64_t anc = lanes_ne((uint32_t)(vis0 >> (nj & 63u)) & 1u, 0u);
+        p = keep_lanes(p, inside & ((same & caus) | (~same & anc)));
+      }
+      dt[h][e] = p * (dP[h][e] - dl);
       if constexpr ((e & 1) == 1) {
         typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
         const bf16x2 pk = __builtin_bit_cast(bf16x2, dag_pack_bf2(dt[h][e - 1], dt[h][e]));
@@ -1166,16 +1227,24 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
         bds[h][e >> 3][e & 7] = pk[1];
       }
     };
-    static_for<0, PF>(fetch);
+    static_for<0, PFM>(fetch);
     __builtin_amdgcn_sched_barrier(0);
     static_for<0, NSLOT>([&](auto ic) __attribute__((always_inline)) {
       constexpr int i = decltype(ic)::value;
       if constexpr (i == 32) {
-        sync_mid();
+        wait_vmcnt_only<LPS>();        // this wave's loads of the next tile's stage have landed
+        __builtin_amdgcn_s_barrier();  // (bare: a __syncthreads would drain the loads in flight)
+        asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
       }
-      fetch(std::integral_constant<int, i + PF>{});
-      wait_lgkmcnt_only<wait_at(i)>();
+      if constexpr (extra_reads<MSK>(i) != 0) {
+        constexpr int u = node_group(i);
+        const uint32_t nn = na;
+        u32x4* const nkp = nk;
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(nkp[u]) : "v"(nn), "n"(128 * (u / 4) + 32 * (u % 4)));
+      }
+      fetch(std::integral_constant<int, i + PFM>{});
+      wait_lgkmcnt_only<wait_at<MSK>(i)>();
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (i < 32) {
         constexpr int hh = i / 16, s = (i % 16) / 2;
@@ -1189,19 +1258,8 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
         const v8i16 t8 = {lo[i][0], lo[i][1], lo[i][2], lo[i][3], hi[i][0], hi[i][1], hi[i][2], hi[i][3]};
         dQ[db] = mfma32(__builtin_bit_cast(bf16x8, t8), bds[hh][x], dQ[db]);
       }
-#ifndef DKV2_ABL_NOISSUE
       if constexpr (i >= 32 && i < 32 + LPS) issue_piece(i - 32, ictx, is);
-#endif
-#ifdef DKV2_ABL_NOEXP
-      if constexpr (i == 16) bds[0][0] = bds[0][1] = bds[1][0] = bds[1][1] = me.qf[0];
-      if constexpr (i == 33) asm volatile("" ::"v"(S[0]), "v"(dP[0]));
-      if constexpr (i == 47) asm volatile("" ::"v"(S[1]), "v"(dP[1]));
-      if constexpr (false)
-#endif
       if constexpr (i >= 16 && i < 32) score(std::integral_constant<int, 0>{}, std::integral_constant<int, i - 16>{});
-#ifdef DKV2_ABL_NOEXP
-      if constexpr (false)
-#endif
       if constexpr (i >= 32 && i < 40) {
         score(std::integral_constant<int, 1>{}, std::integral_constant<int, 2 * (i - 32)>{});
         score(std::integral_constant<int, 1>{}, std::integral_constant<int, 2 * (i - 32) + 1>{});
@@ -1210,37 +1268,44 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
     });
   };
 
-  // ---- the steady-state loop over the key tiles whose pairs are all visible
-  int in = 0;  // list entry whose loads are issued next
+  // ---- the pipelined walk over entries n0 .. n1 - 1 of the tile list
+  auto ring_loop = [&](auto msk_c, int n0, int n1) __attribute__((always_inline)) {
+    constexpr int LPS = decltype(msk_c)::value ? 5 : 4;
+    if (n0 >= n1) return;
+    int in = n0;  // list entry whose loads are issued next
 #pragma unroll 1
-  for (int st = 0; st < NST - 1; ++st, ++in) {
-    const IssueCtx c = prepare_issue(in);
+    for (int st = 0; st < NST - 1; ++st, ++in) {
+      const IssueCtx c = prepare_issue(in, n1);
 #pragma unroll
-    for (int p = 0; p < LPS; ++p) issue_piece(p, c, st);
-  }
-  wait_vmcnt_only<(NST - 2) * LPS>();
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  int cs = 0, is = NST - 1;
+      for (int p = 0; p < LPS; ++p) issue_piece(p, c, st);
+    }
+    wait_vmcnt_only<(NST - 2) * LPS>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    int cs = 0, is = NST - 1;
+    for (int n = n0; n < n1; ++n, ++in) {
+      const IssueCtx ic = prepare_issue(in, n1);
+      pipelined_tile(msk_c, cs, tl.tile(n), ic, is);
+      cs = cs + 1 == NST ? 0 : cs + 1;
+      is = is + 1 == NST ? 0 : is + 1;
+    }
+    wait_vmcnt_only<0>();          // (the loads past the end of the walk)
+    __builtin_amdgcn_s_barrier();  // every wave is done with the ring before it is filled again
+    asm volatile("" ::: "memory");
+  };
 #ifdef BWD_TIMING
-  long long n_fast = 0;
   const long long t_begin = clock64();
+  const long long n_fast = NF;
 #endif
-  for (int n = 0; n < NF; ++n, ++in) {
-#ifdef BWD_TIMING
-    ++n_fast;
-#endif
-    const IssueCtx ic = prepare_issue(in);
-    fast_tile(cs, ic, is);
-    cs = cs + 1 == NST ? 0 : cs + 1;
-    is = is + 1 == NST ? 0 : is + 1;
-  }
-  wait_vmcnt_only<0>();  // (the loads past the end of the walk)
+  ring_loop(std::false_type{}, 0, NF);
 #ifdef BWD_TIMING
   const long long t_steady_end = clock64();
 #endif
-  __syncthreads();       // the ring is free: the general walk lays its own tiles over it
-  dq_general_walk<D, NT>(a, smem, tl, NF, t.N, T, cu, hk, t.nbase, me, dQ);
+  // the masked and the ragged tiles: pipelined as well when a node has one visibility word, else the general walk
+  const int NM = a.W == 1 ? t.N : NF;
+  ring_loop(std::true_type{}, NF, NM);
+  __syncthreads();  // the ring is free: the general walk lays its own tiles over it
+  dq_general_walk<D, NT>(a, smem, tl, NM, t.N, T, cu, hk, t.nbase, me, dQ);
 #ifdef BWD_TIMING
   const long long t_general_end = clock64();
 #endif
