@@ -323,7 +323,7 @@ def backward_timing(pw, dev, calls, warmup):
     return ms, 2.5 * flops / (ms * 1e-3) / 1e12
 
 
-BWD_KERNELS = ("k_bwd_delta<128>", "k_bwd_weights", "k_bwd_tokvis", "k_bwd_order", "k_bwd_dq<128,4>", "k_bwd_dkv<128>")
+BWD_KERNELS = ("k_bwd_delta<128>", "k_bwd_tokvis", "k_bwd_dq2", "k_bwd_weights", "k_bwd_order", "k_bwd_dkv2")
 
 
 def prefill_leg(cfg, dev, launches, warmup, workload_key, with_bwd=False):

@@ -188,8 +188,9 @@ size_t dag_prefill_workspace_bytes(const dag_meta_t* meta, int32_t hkv, int32_t 
  * dK = scale dS^T Q, only over the tiles the block map marks visible.  DAG_BF16 (MFMA, fp32
  * accumulation; gradients bf16) or DAG_F32 (plain fp32 arithmetic, the accuracy path; gradients
  * fp32), head_dim 128 or 64; all tensors DEVICE, 16-byte aligned; `ws` DEVICE scratch of
- * dag_prefill_bwd_workspace_bytes.  No atomics: results are bit-identical from run to run.
- * Errors as dag_attn_prefill. */
+ * dag_prefill_bwd_workspace_bytes.  `meta` is the one dag_build_meta filled for the forward: the
+ * bf16 path reads its block map, launch order, tile descriptors and FULL-first CSR.  No atomics:
+ * results are bit-identical from run to run.  Errors as dag_attn_prefill. */
 size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* meta, int32_t hq, int32_t hkv, int32_t head_dim);
 int dag_attn_prefill_bwd(const dag_meta_t* meta, const void* q, const void* k, const void* v,
                          const void* out, const void* dout, const float* lse, void* dq, void* dk,

@@ -4,14 +4,20 @@
 //     dQ = scale dS K,   dK = scale dS^T Q        (a KV head sums over its query heads).
 // P is recomputed from the forward's log-sum-exp; the block map of the forward skips the tiles
 // without a visible pair.  bf16 operands on the 32x32x16 MFMA, fp32 accumulation.  The kernels:
-//   k_bwd_delta   delta per (token, query head)
+//   k_bwd_delta   delta and -lse log2(e) per (token, query head)
 //   k_bwd_tokvis, k_bwd_weights, k_bwd_order   small tables: first visibility word per token; weight
 //                 and launch rank of the key-tile pairs (the dK/dV workgroups start heaviest first)
-//   k_bwd_dq      one workgroup per (64-row query tile, KV head, up to 4 of its query heads), loop
-//                 over the tile's key tiles, which the heads share
-//   k_bwd_dkv     one workgroup per (pair of 64-key tiles, KV head), loop over the query tiles that
-//                 see it and the query heads of the group; nothing is accumulated through atomics,
-//                 so the results do not depend on the order of execution.
+//   k_bwd_dq2     head dimension 128, three or more query heads per KV head: one workgroup per
+//                 (64-row query tile, KV head, four of its query heads), eight waves; the K / V tiles
+//                 of the tile's row of the forward's FULL-first CSR stream through an LDS ring and
+//                 every tile is a fixed sequence of 48 slots (described at the kernel)
+//   k_bwd_dkv2    head dimension 128: one workgroup per (pair of 64-key tiles, KV head), four
+//                 waves; the Q / dO tiles of the query tiles that see the pair stream through an LDS
+//                 ring, one (tile, query head) = 64 slots (described at the kernel); nothing is
+//                 accumulated through atomics, so the results do not depend on the order of execution
+//   k_bwd_dq, k_bwd_dkv   the first versions (tiles staged through registers, compiler-scheduled):
+//                 every other shape, and inside the two kernels above the "general walk" over
+//                 masked tiles of sequences with more than one visibility word per node
 // Register layout of a 32x32 MFMA result C = A B:  lane (L, H) = (lane % 32, lane / 32) holds
 // column L and the 16 rows rho_H(e) = 8 (e / 4) + 4 H + e % 4.  A result is used again as the B
 // operand of the next product (contraction over its rows) straight from the registers; the A
@@ -19,8 +25,6 @@
 // Those A operands are transposed tiles (K^T for dQ; Q^T and dO^T for dK and dV): they are read
 // from the row-major tiles in LDS with the transposing LDS load of gfx950, two 8-byte reads per
 // operand, in the row order rho asks for.
-// Tiles go global -> registers -> LDS: the next tile is fetched into registers while the current
-// one is multiplied, and stored to LDS between two workgroup barriers.
 // fp32 inputs take the plain kernels at the end of the file (the accuracy path).
 #include <stdlib.h>
 #include <type_traits>
@@ -470,23 +474,10 @@ __device__ __forceinline__ void dkv_general_walk(const BwdArgs& a, unsigned char
 
   int qt = next_tile(QT - 1), g = 0;
   if (qt >= 0) fetch(qt, g);
-#ifdef BWD_TIMING
-  long long tacc[6] = {0, 0, 0, 0, 0, 0}, t0, t1;
-  long long t_begin = clock64();
-#define TT(k) t1 = clock64(); tacc[k] += t1 - t0; t0 = t1;
-#else
-#define TT(k)
-#endif
   while (qt >= 0) {
-#ifdef BWD_TIMING
-    t0 = clock64();
-#endif
     __syncthreads();  // everybody is done with the tile in LDS
-    TT(0)
     commit(qt);
-    TT(1)
     __syncthreads();
-    TT(2)
     const int cur_qt = qt;
     // (every global load the products depend on comes before the fetch: a wait for a later load
     // would also wait for the fetch, the counter being in order)
@@ -496,7 +487,6 @@ __device__ __forceinline__ void dkv_general_walk(const BwdArgs& a, unsigned char
       qt = next_tile(qt - 1);
     }
     if (qt >= 0) fetch(qt, g);  // in flight during the products below
-    TT(3)
     if (flag != 0) {
       const int r0 = cur_qt * BM;
       const bool need_mask = flag == 1;
@@ -564,17 +554,7 @@ __device__ __forceinline__ void dkv_general_walk(const BwdArgs& a, unsigned char
         }
       }
     }
-    TT(4)
-#ifdef BWD_TIMING
-    tacc[5]++;
-#endif
   }
-#ifdef BWD_TIMING
-  if ((blockIdx.x == 0 || blockIdx.x == 8 * 40) && lane == 0)
-    printf("general walk, block %d wave %d: total %lld | sync1 %lld commit %lld sync2 %lld fetch-issue %lld compute %lld | iterations %lld\n",
-           (int)blockIdx.x, w, clock64() - t_begin, tacc[0], tacc[1], tacc[2], tacc[3], tacc[4], tacc[5]);
-#endif
-#undef TT
 }
 
 // Writes the dK and dV rows of a wave's 32 keys (column = this lane's key, rows = d: every lane
@@ -667,17 +647,24 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
 //     fetch 64 consecutive bytes, the 16-byte row reads (A operands of S = Q K^T, dP = dO V^T) of 16
 //     consecutive rows and the 8-byte transposing reads (A operands of dV^T += dO^T P,
 //     dK^T += Q^T dS) of 16 consecutive lanes both fall into 16 different bank groups;
-//   * an iteration whose pairs are all visible is written slot by slot (operand read of the MFMA
-//     PF slots ahead, wait, one MFMA, a share of the exponentials; a scheduling barrier after
-//     every slot): scores and dP of the two 32-row halves (32 MFMAs), then dV / dK of the two
-//     halves (32 MFMAs), with the exponentials of half 0 under the score MFMAs of half 1 and
-//     those of half 1 under the dV / dK MFMAs of half 0.  The operand reads are inline assembly
-//     with explicit lgkmcnt waits (LDS reads return in order); nothing branches while such reads
-//     are in flight, so no copy of a register that is still being written can be made.
-//   * masked and ragged iterations take the per-element path of k_bwd_dkv on the same LDS layout.
-// Every iteration, whatever its kind, passes the barrier once and issues LPS loads per wave
-// (past the end of the walk: loads of the sequence's first tile, never consumed), so the vmcnt
-// waits are constants.
+//   * an iteration is written slot by slot (operand read of the MFMA PF slots ahead, wait, one
+//     MFMA, a share of the exponentials; a scheduling barrier after every slot): scores and dP of
+//     the two 32-row halves (32 MFMAs), then dV / dK of the two halves (32 MFMAs), with the
+//     exponentials of half 0 in the slots of the score MFMAs of half 1 and those of half 1 in the
+//     slots of the dV / dK MFMAs of half 0.  The operand reads are inline assembly with explicit
+//     lgkmcnt waits (LDS reads return in order); nothing branches while such reads are in flight,
+//     so no copy of a register that is still being written can be made
+//     (tests/test_asm_lds_reads.py checks the generated code for exactly that);
+//   * two such loops run one after the other: the iterations whose pairs are all visible (both key
+//     tiles FULL, nothing past the end of the sequence), then, when a node has one visibility
+//     word, the masked and ragged ones with Eq. 3 tested per element (scalar lane masks; the
+//     ancestor test uses the key's column of the visibility matrix, built once per workgroup).
+//     With more words per node the masked iterations take the general walk of k_bwd_dkv.
+// Every iteration passes the barrier once and issues LPS loads per wave (past the end of the walk:
+// loads of the sequence's first tile, never consumed), so the vmcnt waits are constants.
+// With one wave per SIMD (the accumulators and the K / V operands of 32 keys need 192 registers)
+// nothing of a wave overlaps its own MFMAs: an iteration costs the 64 MFMAs plus the time to
+// issue everything else.
 namespace dkv2 {
 constexpr int NST = 4;              // ring depth
 constexpr int LPS = 10;             // wave-level loads per stage and wave: 4 Q blocks, 4 dO blocks, 2 of row data
@@ -827,11 +814,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   };
   // Two pipelined loops: the iterations without tests, then (when a node has one visibility word)
   // the masked ones; with more words per node the masked ones go to the general walk.
-#ifdef DKV2_NO_MASKS_IN_LOOP
-  const bool masks_in_loop = false;
-#else
   const bool masks_in_loop = a.W == 1;
-#endif
   auto kind_of = [&](int f) { return (f & 16) ? 0 : ((f & 15) != 0 && masks_in_loop) ? 1 : 2; };  // 2: general walk or nothing
 
   // ---- loads of one stage, in LPS pieces per wave (piece p of (tile qt, head g) into stage st)
@@ -1118,9 +1101,6 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int32_t sCol[MAX_ROW_LDS];
   __shared__ uint8_t sFlg[MAX_ROW_LDS];
-#ifdef BWD_TIMING
-  const long long t_start = clock64();
-#endif
   const DqTile t = dq_tile(a);
   const int hk = blockIdx.y, cu = t.cu, T = t.T;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, L = lane & 31, H = lane >> 5;
@@ -1293,28 +1273,13 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
     __builtin_amdgcn_s_barrier();  // every wave is done with the ring before it is filled again
     asm volatile("" ::: "memory");
   };
-#ifdef BWD_TIMING
-  const long long t_begin = clock64();
-  const long long n_fast = NF;
-#endif
   ring_loop(std::false_type{}, 0, NF);
-#ifdef BWD_TIMING
-  const long long t_steady_end = clock64();
-#endif
   // the masked and the ragged tiles: pipelined as well when a node has one visibility word, else the general walk
   const int NM = a.W == 1 ? t.N : NF;
   ring_loop(std::true_type{}, NF, NM);
   __syncthreads();  // the ring is free: the general walk lays its own tiles over it
   dq_general_walk<D, NT>(a, smem, tl, NM, t.N, T, cu, hk, t.nbase, me, dQ);
-#ifdef BWD_TIMING
-  const long long t_general_end = clock64();
-#endif
   dq_store<D>(a, me, H, dQ);
-#ifdef BWD_TIMING
-  if ((blockIdx.x == 0 || blockIdx.x == 200) && blockIdx.y == 0 && lane == 0 && w == 0)
-    printf("dq2 block %d: set-up %lld, %lld steady-state tiles %lld clocks each, general walk %lld, store %lld\n", (int)blockIdx.x,
-           t_begin - t_start, n_fast, n_fast ? (t_steady_end - t_begin) / n_fast : 0, t_general_end - t_steady_end, clock64() - t_general_end);
-#endif
 }
 
 template <int D, int HG>
@@ -1328,10 +1293,10 @@ int launch_dq(const BwdArgs& a, long total_qtiles, hipStream_t stream) {
   return DAG_OK;
 }
 
-// Development switch, read once: DAGATTN_BWD_DKV1=1 runs the first dK/dV kernel for every head dimension.
-bool dkv_first_version() {
+// Development switch, read once: DAGATTN_BWD_V1=1 runs the first dQ and dK/dV kernels for every shape.
+bool bwd_first_version() {
   static const bool v = [] {
-    const char* e = getenv("DAGATTN_BWD_DKV1");
+    const char* e = getenv("DAGATTN_BWD_V1");
     return e && e[0] == '1';
   }();
   return v;
@@ -1345,7 +1310,7 @@ int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream
   hipLaunchKernelGGL(k_bwd_tokvis, dim3((unsigned)((total_tokens + 255) / 256)), dim3(256), 0, stream, a, total_tokens);
   DAG_LAUNCH_CHECK();
   int rc;
-  if (D == 128 && a.G >= 3 && !dkv_first_version()) {
+  if (D == 128 && a.G >= 3 && !bwd_first_version()) {
     constexpr int sm2 = dq2::NST * dq2::STAGEB;
     if (hipFuncSetAttribute((const void*)k_bwd_dq2, hipFuncAttributeMaxDynamicSharedMemorySize, sm2) != hipSuccess)
       return DAG_ERR_HIP;
@@ -1362,7 +1327,7 @@ int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream
   hipLaunchKernelGGL(k_bwd_weights, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
   hipLaunchKernelGGL(k_bwd_order, dim3((unsigned)total_ktiles), dim3(64), 0, stream, a);
   DAG_LAUNCH_CHECK();
-  if (D == 128 && !dkv_first_version()) {
+  if (D == 128 && !bwd_first_version()) {
     constexpr int sm2 = dkv2::NST * dkv2::STAGEB;
     if (hipFuncSetAttribute((const void*)k_bwd_dkv2, hipFuncAttributeMaxDynamicSharedMemorySize, sm2) != hipSuccess)
       return DAG_ERR_HIP;
