@@ -174,3 +174,33 @@ def test_bwd_fp32_config1_and_ragged_dags():
             assert np.isfinite(got).all()
             assert np.abs(got - ref).max() <= 1e-4 * max(1.0, np.abs(ref).max()), name
             assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-4, name
+
+
+def test_bwd_random_batches_on_the_pipelined_kernels():
+    """Head dimension 128 with three or more query heads per KV head (the shapes the two pipelined
+    kernels take): batches of random DAGs, fork-joins with ragged and with tile-aligned nodes,
+    chains; one to three sequences, up to 90 nodes (more than one visibility word), G = 3, 4, 5, 8."""
+    rng = np.random.Generator(np.random.PCG64(2026))
+    for case in range(12):
+        hkv = int(rng.integers(1, 3))
+        hq = hkv * int(rng.choice([3, 4, 5, 8]))
+        dag_list = []
+        for _ in range(int(rng.integers(1, 4))):
+            kind = int(rng.integers(0, 4))
+            if kind == 0:
+                n = int(rng.integers(6, 90))
+                L, anc, _, _ = dags.random_dag(rng, n_nodes=n, depth=int(rng.integers(2, min(n, 7))), len_lo=1,
+                                               len_hi=int(rng.integers(3, 40)))
+                dag_list.append((L, anc))
+            elif kind == 1:
+                dag_list.append(dags.fork_join(int(rng.integers(1, 400)),
+                                               [int(rng.integers(1, 200)) for _ in range(int(rng.integers(1, 6)))],
+                                               int(rng.integers(1, 150))))
+            elif kind == 2:
+                dag_list.append(dags.fork_join(64 * int(rng.integers(1, 5)),
+                                               [64 * int(rng.integers(1, 3)) for _ in range(int(rng.integers(2, 5)))],
+                                               64 * int(rng.integers(1, 3))))
+            else:
+                dag_list.append(dags.linear_chain([int(rng.integers(1, 300)) for _ in range(int(rng.integers(1, 4)))]))
+        inputs, grads = _forward_backward(dag_list, hq, hkv, 128, 9000 + case)
+        _check_against_oracle(dag_list, inputs, grads)
