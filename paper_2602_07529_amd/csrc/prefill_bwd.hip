@@ -82,7 +82,12 @@ __device__ __forceinline__ bool visible(const BwdArgs& a, int nbase, int ni, int
   return (w >> (nj & 63)) & 1u;
 }
 
-constexpr int MAX_QT_LDS = 4096;  // query tiles of a sequence whose block-map column is kept in LDS (262,144 tokens)
+// Tables kept in LDS per workgroup hold this many tiles (262,144 tokens); longer sequences read the
+// rest from global memory.  (A build with a small DAG_BWD_LDS_TILES runs the tests through that path.)
+#ifndef DAG_BWD_LDS_TILES
+#define DAG_BWD_LDS_TILES 4096
+#endif
+constexpr int MAX_QT_LDS = DAG_BWD_LDS_TILES;  // query tiles of a sequence whose block-map column is kept in LDS
 
 // A operand of a product whose contraction runs over the ROWS of a row-major LDS tile (K^T for dQ;
 // Q^T and dO^T for dK and dV), read with the transposing LDS load of gfx950 (ds_read_b64_tr_b16):
@@ -156,7 +161,7 @@ __device__ __forceinline__ void dq_store(const BwdArgs& a, const DqLane<D>& me, 
 // set-up; rows longer than the arrays read the rest from global memory.  get() is an
 // inline-assembly LDS read that waits for itself: the loads of k_bwd_dq2's ring write LDS too, and
 // a compiler-visible LDS read might be made to wait for all of them.
-constexpr int MAX_ROW_LDS = 4096;
+constexpr int MAX_ROW_LDS = DAG_BWD_LDS_TILES;
 struct TileList {
   const int32_t* col;   // the row in global memory
   const uint8_t* flag;
