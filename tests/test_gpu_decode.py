@@ -119,6 +119,45 @@ def test_decode_growing_branches_over_steps_config5_shape_reduced():
         check_close(out[branches], ref[branches], torch.bfloat16, "step %d" % step)
 
 
+def test_decode_48_steps_of_growing_branches_every_branch_every_step():
+    """A run of decode steps as the execution phase makes them (config-3 shape at a reduced context:
+    two sibling groups of 8 branches, G = 4): every step appends one token per branch (a fresh page
+    whenever a tail page is full: three times per branch here), decodes, and every branch is
+    checked against the oracle on the pools as they stand."""
+    hq, hkv, d, nb, n_seqs = 32, 8, 128, 8, 2
+    st = dags.decode_state(91, n_seqs=n_seqs, n_branches=nb, shared_len=300, branch_len=7, hq=hq, hkv=hkv, d=d,
+                           kv_scale=0.5, q_scale=0.5, spare_pages=n_seqs * nb * 4)
+    desc = st["desc"]
+    kp, vp = st["k_pool"].to(DEV), st["v_pool"].to(DEV)
+    rng = np.random.Generator(np.random.PCG64(92))
+    spare = list(range(st["n_pages"] - n_seqs * nb * 4, st["n_pages"]))
+    R = n_seqs * nb
+    group_of = np.repeat(np.arange(n_seqs), nb)
+    for step in range(48):
+        new_pages, off = [], [0]
+        for r in range(R):
+            pages = list(desc["branch_pages"][desc["branch_page_off"][r]:desc["branch_page_off"][r + 1]])
+            if desc["branch_len"][r] % 16 == 0:
+                pages.append(spare.pop())
+            new_pages += pages
+            off.append(len(new_pages))
+        desc["branch_pages"] = np.array(new_pages, dtype=np.int32)
+        desc["branch_page_off"] = np.array(off, dtype=np.int32)
+        desc["branch_len"] = desc["branch_len"] + 1
+        desc["branch_pos"] = (desc["shared_len"][group_of] + desc["branch_len"] - 1).astype(np.int32)
+        k_new = dags.normal_tensor(rng, (R, hkv, d), 0.5, torch.bfloat16)
+        v_new = dags.normal_tensor(rng, (R, hkv, d), 0.5, torch.bfloat16)
+        q = dags.normal_tensor(rng, (R, hq, d), 0.5, torch.bfloat16)
+        dd = B.DecodeDesc(desc, DEV)
+        B.dag_kv_append_rope(dd, k_new.to(DEV), v_new.to(DEV), kp, vp, 1e6)
+        out = torch.empty(R, hq, d, dtype=torch.bfloat16, device=DEV)
+        ws = torch.empty(B.dag_decode_workspace_bytes(dd, hq, hkv, d), dtype=torch.uint8, device=DEV)
+        B.dag_attn_decode(dd, q.to(DEV), kp, vp, out, ws)
+        torch.cuda.synchronize()
+        ref = orc.attn_decode(desc, dags.to_f64(q), dags.to_f64(kp), dags.to_f64(vp))
+        check_close(out, ref, torch.bfloat16, "step %d" % step)
+
+
 def test_decode_equals_last_row_of_gpu_prefill():
     """Cross-check of the two GPU paths: decoding the last token of a branch equals the last row of a
     prefill over [prefix, branch] (both within tolerance of the same oracle value)."""
