@@ -196,6 +196,17 @@ def test_config5_qwen_shape_full_size_sampled_rows():
         ref, _ = orc.attn_prefill(qs, ks, dags.to_f64(v[t0:t0 + Tb]), L, anc, rows=rows, compact=True)
         check_close(out[t0 + rows], ref, torch.bfloat16, "config 5 prefill")
         t0 += Tb
+    # whole tiles of the first sequence inside the branches: the 256 rows of one
+    # tile of the left-over heads (the fifth head of two KV groups), the 64 rows of one tile of a four-head item
+    L, anc = dag_list[0]
+    Tb = int(np.sum(L))
+    _, pos = orc.token_meta(L, anc)
+    ks = orc.rope(dags.to_f64(k[:Tb]), pos, c["theta"])
+    for first, n_rows, heads in ((32768 + 3 * 512 - 256, 256, [4, 39]), (32768 + 9 * 512, 64, [10, 11, 12, 13])):
+        rows = np.arange(first, first + n_rows)
+        qs = orc.rope(dags.to_f64(q[:Tb][rows]), pos[rows], c["theta"])
+        ref, _ = orc.attn_prefill(qs, ks, dags.to_f64(v[:Tb]), L, anc, rows=rows, heads=heads, compact=True)
+        check_close(out[rows][:, heads], ref[:, heads], torch.bfloat16, "config 5 prefill, whole tile at row %d" % first)
 
 
 def test_config4_one_sequence_every_row_of_one_kv_group():
