@@ -1,4 +1,4 @@
-"""Static check of the generated code of the hand-pipelined backward kernels (no GPU needed).
+"""Static checks of the generated code of kernels with inline-assembly LDS reads (no GPU needed).
 
 The operand reads of k_bwd_dkv2 and k_bwd_dq2 are inline-assembly LDS reads whose completion the
 compiler does not track: the kernels wait for them with explicit lgkmcnt counts.  That is only
@@ -106,6 +106,109 @@ def test_pipelined_backward_blocks_keep_pending_reads_untouched(tmp_path):
         assert sorted(found) == sorted(expected), "%s: pipelined blocks with %s reads, expected %s" % (kernel, found, expected)
 
 
+def _cfg(lines):
+    """Basic blocks with successors, from labels and branches."""
+    blocks, cur = [], {"labels": [], "insts": []}
+    for raw in lines:
+        l = raw.split(";")[0].strip()
+        if not l:
+            continue
+        m = re.match(r"^(\.?[A-Za-z_][\w.$]*):$", l)
+        if m:
+            if cur["insts"]:
+                blocks.append(cur)
+                cur = {"labels": [], "insts": []}
+            cur["labels"].append(m.group(1))
+            continue
+        if l.startswith("."):
+            continue
+        cur["insts"].append(l)
+        if l.startswith(("s_cbranch", "s_branch", "s_endpgm", "s_setpc")):
+            blocks.append(cur)
+            cur = {"labels": [], "insts": []}
+    if cur["insts"]:
+        blocks.append(cur)
+    where = {x: i for i, b in enumerate(blocks) for x in b["labels"]}
+    for i, b in enumerate(blocks):
+        last = b["insts"][-1]
+        if last.startswith(("s_endpgm", "s_setpc")):
+            b["succ"] = []
+        elif last.startswith("s_branch"):
+            b["succ"] = [where[last.split()[1]]]
+        elif last.startswith("s_cbranch"):
+            b["succ"] = [where[last.split()[1]]] + ([i + 1] if i + 1 < len(blocks) else [])
+        else:
+            b["succ"] = [i + 1] if i + 1 < len(blocks) else []
+    return blocks
+
+
+def _run_block(insts, inherited):
+    """Registers with a read possibly in flight at the end of the block, and the instructions that touch such
+    a register.  `inherited`: registers possibly in flight at the entry (all older than this block's reads, so
+    a wait that leaves at most as many reads as the block has issued itself covers them)."""
+    inherited, local, issued, conflicts = set(inherited), [], 0, []
+    for l in insts:
+        op = l.split()[0]
+        args = l[len(op):]
+        if op.startswith("ds_read"):
+            parts = args.split(",")
+            dst, src = _regs(parts[0]), _regs(",".join(parts[1:]))
+            if (dst | src) & inherited or any(d & (dst | src) for d in local):
+                conflicts.append(l)
+            local.append(dst)
+            issued += 1
+        elif op == "s_waitcnt":
+            m = re.search(r"lgkmcnt\((\d+)\)", l)
+            if m:
+                n = int(m.group(1))
+                if n <= issued:
+                    inherited = set()
+                if n < len(local):
+                    local = local[len(local) - n:] if n else []
+        else:
+            t = _regs(args)
+            if t & inherited or any(d & t for d in local):
+                conflicts.append(l)
+    out = set(inherited)
+    for d in local:
+        out |= d
+    return out, conflicts
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="no hipcc")
+def test_wide_decode_kernel_reads_are_waited_for_on_every_path(tmp_path):
+    """k_decode_wide has branches between its inline reads' blocks (waves without a block in the
+    last round, the skewed half of the waves): the registers that may have a read in flight are
+    propagated over the control-flow graph (conservatively: the union over the predecessors), and
+    no instruction may touch one."""
+    src = os.path.join(os.path.dirname(SRC), "decode.hip")
+    asm = tmp_path / "decode.s"
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fno-gpu-rdc", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
+           "-I" + os.path.join(ROOT, "include"), "-I" + os.path.dirname(SRC), "-S", "--cuda-device-only", "-o", str(asm), src]
+    subprocess.run(cmd, check=True, capture_output=True, timeout=900)
+    text = asm.read_text().split("\n")
+    starts = [i for i, l in enumerate(text) if re.match(r"^_Z\w*k_decode_wide\w*:", l)]
+    assert len(starts) == 2  # head dimensions 128 and 64
+    for st in starts:
+        end = next(i for i in range(st, len(text)) if text[i].startswith(".Lfunc_end"))
+        blocks = _cfg(text[st + 1:end + 1])
+        entry = [set() for _ in blocks]
+        changed = True
+        while changed:
+            changed = False
+            for i, b in enumerate(blocks):
+                out, _ = _run_block(b["insts"], entry[i])
+                for nxt in b["succ"]:
+                    if not out <= entry[nxt]:
+                        entry[nxt] |= out
+                        changed = True
+        assert sum(1 for b in blocks for l in b["insts"] if l.startswith("ds_read_b128")) >= 12
+        for i, b in enumerate(blocks):
+            _, conflicts = _run_block(b["insts"], entry[i])
+            assert not conflicts, conflicts[:3]
+
+
 def test_the_checker_finds_a_planted_mistake():
     good = ["ds_read_b128 v[4:7], v1 offset:16", "ds_read_b128 v[8:11], v1 offset:32", "s_waitcnt lgkmcnt(1)",
             "v_mfma_f32_32x32x16_bf16 a[0:15], v[4:7], v[20:23], a[0:15]", "s_waitcnt lgkmcnt(0)",
@@ -118,3 +221,10 @@ def test_the_checker_finds_a_planted_mistake():
     assert _check_block(copied)[1]
     cut = good[:2]  # a block that ends (a branch) with reads in flight
     assert _check_block(cut)[2] == 2
+    # over a branch: the read of the first block is still in flight when the second one copies its register
+    two = ["ds_read_b128 v[4:7], v1", "s_cbranch_scc1 .LBB0_2", ".LBB0_1:", "s_waitcnt lgkmcnt(0)", ".LBB0_2:",
+           "v_mov_b32_e32 v30, v5", "s_endpgm"]
+    blocks = _cfg(two)
+    out0, _ = _run_block(blocks[0]["insts"], set())
+    assert out0 == {4, 5, 6, 7} and _run_block(blocks[2]["insts"], out0)[1]
+    assert not _run_block(blocks[1]["insts"] + blocks[2]["insts"], out0)[1]   # after the wait it is fine
