@@ -1249,7 +1249,11 @@ __global__ void __launch_bounds__(64 * HG * NRG, 1) k_prefill_bf16(PrefillArgs a
           TCOUNT(10);
           TCOUNT(7);
         }
-        wait_lgkmcnt(0);  // (the operands fetched ahead for a tile that takes the other path)
+        // The operands fetched ahead for a tile that takes the other path: nobody will use them, so
+        // the compiler takes their registers for the temporaries of what follows -- which must not
+        // start before these reads have written them (the scheduling barrier keeps it behind the wait).
+        wait_lgkmcnt(0);
+        __builtin_amdgcn_sched_barrier(0);
         need = row_max(SB);
         TSTAMP(t_fast);
         TACC(1, t_first, t_fast);
