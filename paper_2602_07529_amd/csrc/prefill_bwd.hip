@@ -672,12 +672,12 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
 // issue everything else.
 namespace dkv2 {
 constexpr int NST = 4;              // ring depth
-constexpr int LPS = 10;             // wave-level loads per stage and wave: 4 Q blocks, 4 dO blocks, 2 of row data
+constexpr int LPS = 9;              // wave-level loads per stage and wave: 4 Q blocks, 4 dO blocks, 1 of row data
 constexpr int PF = 5;               // operands in flight ahead of their MFMA
 constexpr int BLK = 1024 + 16;
 constexpr int TILEB = 16 * BLK;     // 64 rows x 128 dims
-constexpr int RD = 2 * TILEB;       // row data: -lse log2(e) [64], delta [64], node id [64], first visibility word [64]
-constexpr int STAGEB = RD + 1280;
+constexpr int RD = 2 * TILEB;       // row data: -lse log2(e) [64], delta [64], node id [64]
+constexpr int STAGEB = RD + 768;
 constexpr int NSLOT = 64;
 constexpr int VAHEAD = 8;           // the row data of four rows are read this many slots before their first use
 constexpr int opnd_reads(int o) { return o < 32 ? 1 : 2; }
@@ -826,26 +826,20 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   const uint32_t row_stride = (uint32_t)(a.hq * D);  // elements
   const uint32_t chunk8 = (uint32_t)(4 * (lane >> 4) + (lane & 3)) * 8;  // this lane's 16-byte chunk of a row
   const int rsub = (lane >> 2) & 3;
-  // Row data, 4 bytes per lane, two loads per wave: waves 0 and 3 fetch -lse log2(e) and delta (the
-  // same values twice, so that every wave issues the same number of loads), wave 1 the node ids
-  // (twice), wave 2 the visibility words of rows 0..31 and 32..63.  Element index in the source:
-  // (token of the row) * rd_mul + head * rd_hmul + rd_add -- no branch where the loads are issued.
-  const float *rd_src0 = a.nlse2, *rd_src1 = a.delta;
-  int rd_mul = a.hq, rd_hmul = 1, rd_add = 0, rd_row0 = lane, rd_row1 = lane, rd_dst0 = 0, rd_dst1 = 256;
-  if (w == 1) {
-    rd_src0 = rd_src1 = (const float*)a.tok_node;
-    rd_mul = 1, rd_hmul = 0, rd_dst0 = rd_dst1 = 512;
-  } else if (w == 2) {
-    rd_src0 = rd_src1 = (const float*)a.tok_vis0;
-    rd_mul = 2, rd_hmul = 0, rd_add = lane & 1, rd_row0 = lane >> 1, rd_row1 = 32 + (lane >> 1), rd_dst0 = 768, rd_dst1 = 1024;
-  }
+  // Row data, 4 bytes per lane, one load per wave: wave 0 fetches -lse log2(e), wave 1 delta, wave 2
+  // the node ids of the rows (for the masked iterations), wave 3 -lse log2(e) once more (every wave
+  // issues the same number of loads, so that the vmcnt waits are the same constants for all).
+  // Element index in the source: (token of the row) * rd_mul + head * rd_hmul -- no branch where
+  // the loads are issued.
+  const float* rd_src = w == 1 ? a.delta : w == 2 ? (const float*)a.tok_node : a.nlse2;
+  const int rd_mul = w == 2 ? 1 : a.hq, rd_hmul = w == 2 ? 0 : 1, rd_dst = w == 1 ? 256 : w == 2 ? 512 : 0;
   // The addresses of a stage's loads are prepared once per iteration, outside the slots (wave-uniform
-  // bases, four per-lane row offsets, two per-lane row-data pointers); a slot then only sets the LDS
+  // bases, four per-lane row offsets, one per-lane row-data pointer); a slot then only sets the LDS
   // destination and issues its load.
   struct IssueCtx {
     const uint16_t *qb, *dob;  // first row of the tile, this head
     uint32_t voff[4];          // element offset of this lane's chunk in block w + 4 i (rows past the sequence end re-read its last row)
-    const float *rd0, *rd1;    // this lane's two row-data words
+    const float* rd;           // this lane's row-data word
   };
   auto prepare_issue = [&](int qt, int g) __attribute__((always_inline)) {
     IssueCtx c;
@@ -856,9 +850,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     c.dob = a.dout + slab;
 #pragma unroll
     for (int i = 0; i < 4; ++i) c.voff[i] = (uint32_t)min(4 * (w + 4 * i) + rsub, n_in - 1) * row_stride + chunk8;
-    const int hterm = rd_hmul * h + rd_add;
-    c.rd0 = rd_src0 + ((size_t)(cu + r0 + min(rd_row0, n_in - 1)) * rd_mul + hterm);
-    c.rd1 = rd_src1 + ((size_t)(cu + r0 + min(rd_row1, n_in - 1)) * rd_mul + hterm);
+    c.rd = rd_src + ((size_t)(cu + r0 + min(lane, n_in - 1)) * rd_mul + rd_hmul * h);
     return c;
   };
   auto issue_piece = [&](int p, const IssueCtx& c, int st) __attribute__((always_inline)) {
@@ -868,8 +860,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)((p < 4 ? c.qb : c.dob) + c.voff[p & 3]),
                                        (lds_ptr_t)(sb + (p < 4 ? 0 : TILEB) + blk * BLK), 16, 0, 0);
     } else {
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p == 8 ? c.rd0 : c.rd1),
-                                       (lds_ptr_t)(sb + RD + (p == 8 ? rd_dst0 : rd_dst1)), 4, 0, 0);
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)c.rd, (lds_ptr_t)(sb + RD + rd_dst), 4, 0, 0);
     }
   };
   auto sync_mid = [&]() __attribute__((always_inline)) {
