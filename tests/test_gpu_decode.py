@@ -119,21 +119,22 @@ def test_decode_growing_branches_over_steps_config5_shape_reduced():
         check_close(out[branches], ref[branches], torch.bfloat16, "step %d" % step)
 
 
-def test_decode_48_steps_of_growing_branches_every_branch_every_step():
+def test_decode_256_steps_of_growing_branches_every_branch_every_step():
     """A run of decode steps as the execution phase makes them (config-3 shape at a reduced context:
     two sibling groups of 8 branches, G = 4): every step appends one token per branch (a fresh page
-    whenever a tail page is full: three times per branch here), decodes, and every branch is
-    checked against the oracle on the pools as they stand."""
+    whenever a tail page is full: sixteen times per branch here), decodes, and every branch is
+    checked against the oracle on the pools as they stand; 256 steps, the length of a decode run of
+    the benchmark configurations."""
     hq, hkv, d, nb, n_seqs = 32, 8, 128, 8, 2
     st = dags.decode_state(91, n_seqs=n_seqs, n_branches=nb, shared_len=300, branch_len=7, hq=hq, hkv=hkv, d=d,
-                           kv_scale=0.5, q_scale=0.5, spare_pages=n_seqs * nb * 4)
+                           kv_scale=0.5, q_scale=0.5, spare_pages=n_seqs * nb * 17)
     desc = st["desc"]
     kp, vp = st["k_pool"].to(DEV), st["v_pool"].to(DEV)
     rng = np.random.Generator(np.random.PCG64(92))
-    spare = list(range(st["n_pages"] - n_seqs * nb * 4, st["n_pages"]))
+    spare = list(range(st["n_pages"] - n_seqs * nb * 17, st["n_pages"]))
     R = n_seqs * nb
     group_of = np.repeat(np.arange(n_seqs), nb)
-    for step in range(48):
+    for step in range(256):
         new_pages, off = [], [0]
         for r in range(R):
             pages = list(desc["branch_pages"][desc["branch_page_off"][r]:desc["branch_page_off"][r + 1]])
