@@ -680,22 +680,20 @@ constexpr int RD = 2 * TILEB;       // row data: -lse log2(e) [64], delta [64], 
 constexpr int STAGEB = RD + 768;
 constexpr int NSLOT = 64;
 constexpr int VAHEAD = 8;           // the row data of four rows are read this many slots before their first use
+constexpr int XR = 2;               // row-data reads per group of four rows: -lse and delta
 constexpr int opnd_reads(int o) { return o < 32 ? 1 : 2; }
 // The scores of rows 4 x .. 4 x + 3 of half h are taken in slots 16 + 16 h + 4 x ..; the XR reads of their
-// row data (-lse and delta; with masks also the node ids) go out
-// VAHEAD slots earlier, i.e. before the operand read that slot waits for, so they have arrived with it.
-template <int XR>
+// row data go out VAHEAD slots earlier, i.e. before the operand read that slot waits for, so they have
+// arrived with it.
 constexpr int extra_reads(int slot) { return slot >= 16 - VAHEAD && slot < 48 - VAHEAD && slot % 4 == 0 ? XR : 0; }
-template <int XR>
 constexpr int issued_through(int k) {  // LDS reads issued up to and including those of operand k
   int t = 0;
-  for (int o = 0; o <= k; ++o) t += (o >= PF ? extra_reads<XR>(o - PF) : 0) + opnd_reads(o);
+  for (int o = 0; o <= k; ++o) t += (o >= PF ? extra_reads(o - PF) : 0) + opnd_reads(o);
   return t;
 }
-template <int XR>
 constexpr int wait_at(int i) {  // reads that may still be pending when MFMA i starts
   const int last = i + PF < NSLOT ? i + PF : NSLOT - 1;
-  const int n = issued_through<XR>(last) - issued_through<XR>(i);
+  const int n = issued_through(last) - issued_through(i);
   return n < 15 ? n : 15;
 }
 // byte offset (after the per-lane part) of operand i of the fast iteration
@@ -708,17 +706,42 @@ constexpr int tr_imm(int i) {  // i >= 32: transposed operand (dims 32 db .., 16
 }
 }  // namespace dkv2
 
-// Lane masks for the element tests of the pipelined kernels: comparisons that leave their result
-// in a scalar register pair, combined with scalar logic, applied with one v_cndmask.  (A
-// conditional expression on per-lane values can be compiled into a branch, and nothing may
-// branch while operand reads are in flight; per-lane 0 / 1 integers cost vector registers.)
-__device__ __forceinline__ uint64_t lanes_eq(uint32_t x, uint32_t y) { return __builtin_amdgcn_uicmp(x, y, 32); }
-__device__ __forceinline__ uint64_t lanes_ne(uint32_t x, uint32_t y) { return __builtin_amdgcn_uicmp(x, y, 33); }
-__device__ __forceinline__ uint64_t lanes_gt(int x, int y) { return __builtin_amdgcn_sicmp(x, y, 38); }
-__device__ __forceinline__ uint64_t lanes_ge(int x, int y) { return __builtin_amdgcn_sicmp(x, y, 39); }
-__device__ __forceinline__ float keep_lanes(float x, uint64_t lanes) {  // x where the lane's bit is set, else 0
+// Eq. 3 for one 64 x 64 tile as a 64-bit word per lane (one visibility word per node): bit c says
+// whether element c of the tile -- query row c for a lane that holds a key, key c for a lane that
+// holds a query row -- and the lane's own token see each other.  The tokens of a sequence lie node
+// after node, so the tile's 64 elements are a few runs of one node each: the runs are found with
+// one ballot over the node ids (LDS, `ids`: byte address of the 64 ids) and every run is switched
+// on as a whole -- for the lane's own node the elements that pass the causal test (`own`), for
+// another node n all or nothing by bit n of `word` (the lane's row or column of the visibility
+// matrix).  Elements from n_in on lie behind the end of the sequence.  Called where no operand read
+// is in flight (the LDS reads here wait for themselves; the loop branches on wave-uniform values).
+__device__ __forceinline__ uint64_t tile_visibility(uint32_t ids, int lane, uint32_t my_node, uint64_t word, uint64_t own,
+                                                    int n_in) {
+  uint32_t n_here, n_before;
+  asm volatile("ds_read_b32 %0, %2\n\tds_read_b32 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+               : "=&v"(n_here), "=&v"(n_before)
+               : "v"(ids + 4u * (uint32_t)lane), "v"(ids + 4u * (uint32_t)max(lane - 1, 0))
+               : "memory");
+  uint64_t starts = __builtin_amdgcn_ballot_w64(lane == 0 || n_here != n_before);
+  uint64_t m = 0;
+  while (starts != 0) {
+    const int s0 = __builtin_ctzll(starts);
+    starts &= starts - 1;
+    const int s1 = starts != 0 ? __builtin_ctzll(starts) : 64;
+    const uint32_t n = (uint32_t)__builtin_amdgcn_readlane((int)n_here, s0);
+    const uint64_t run = (s1 == 64 ? ~0ull : (1ull << s1) - 1) & ~((1ull << s0) - 1);
+    const uint64_t sel = n == my_node ? own : 0ull - ((word >> (n & 63u)) & 1ull);
+    m |= run & sel;
+  }
+  return n_in >= 64 ? m : m & ((1ull << n_in) - 1);
+}
+// x when bit BIT of the word is set, else 0: the bit as a signed one-bit field (0 or all ones), then
+// one AND -- no comparison, no condition register (written out: from the plain expression the
+// compiler makes a test, a compare and a select).
+template <int BIT>
+__device__ __forceinline__ float keep_if_bit(float x, uint32_t word) {
   float r;
-  asm("v_cndmask_b32 %0, 0, %1, %2" : "=v"(r) : "v"(x), "s"(lanes));
+  asm("v_bfe_i32 %0, %2, %3, 1\n\tv_and_b32 %0, %0, %1" : "=&v"(r) : "v"(x), "v"(word), "n"(BIT));
   return r;
 }
 
@@ -749,7 +772,9 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   typedef short v4i16 __attribute__((ext_vector_type(4)));
   typedef short v8i16 __attribute__((ext_vector_type(8)));
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int KIND_WORDS = (MAX_QT_LDS + 63) / 64;
   __shared__ uint8_t sFlag[MAX_QT_LDS];  // block-map column of the pair: flag of tile 0 | flag of tile 1 << 2
+  __shared__ uint64_t sKind[3][KIND_WORDS];
   const int hk = blockIdx.x % a.hkv, kt = a.kt_order[blockIdx.x / a.hkv];  // heaviest pairs first
   const int b = dag_find_segment(a.ktile_start, a.n_seqs, kt);
   const int ktl = kt - a.ktile_start[b];
@@ -795,16 +820,34 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   auto with_fast_bit = [&](int qt, int f) {
     return f | ((f == (2 | (2 << 2)) && (qt + 1) * BM <= T && (ktl + 2) * BN <= T) ? 16 : 0);
   };
+  // Two pipelined loops: the iterations without tests, then (when a node has one visibility word)
+  // the masked ones; with more words per node the masked ones go to the general walk.
+  const bool masks_in_loop = a.W == 1;
+  auto kind_of = [&](int f) { return (f & 16) ? 0 : ((f & 15) != 0 && masks_in_loop) ? 1 : 2; };  // 2: general walk or nothing
+  // The column is kept in LDS as the flags and as one bitmap per kind of iteration (bit qt % 64 of
+  // word qt / 64: tile qt has a visible pair and is of that kind), so that a walk finds its next
+  // tile with one 64-bit read per 64 tiles instead of one probe per tile.
   const bool flags_in_lds = QT <= MAX_QT_LDS;
   if (flags_in_lds) {
-    for (int x = tid; x < QT; x += 256) {
-      const int f0 = bm[(int64_t)x * KT + ktl];
-      const int f1 = ktl + 1 < KT ? bm[(int64_t)x * KT + ktl + 1] : 0;
-      sFlag[x] = (uint8_t)with_fast_bit(x, f0 | (f1 << 2));
+    for (int x0 = 0; x0 < QT; x0 += 256) {
+      const int x = x0 + tid;
+      int f = 0;
+      if (x < QT) {
+        const int f0 = bm[(int64_t)x * KT + ktl];
+        const int f1 = ktl + 1 < KT ? bm[(int64_t)x * KT + ktl + 1] : 0;
+        f = with_fast_bit(x, f0 | (f1 << 2));
+        sFlag[x] = (uint8_t)f;
+      }
+      const int kind = (f & 15) != 0 ? kind_of(f) : 3;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const uint64_t word = __builtin_amdgcn_ballot_w64(kind == k);
+        if (lane == 0 && x0 + 64 * w < QT) sKind[k][(x0 >> 6) + w] = word;
+      }
     }
   }
   __syncthreads();
-  const uint32_t flag_base = lds_addr(sFlag);
+  const uint32_t flag_base = lds_addr(sFlag), kind_base = lds_addr(sKind);
   // (the flags are read with an inline-assembly LDS read that waits for itself: the ring's loads
   // write LDS too, and a compiler-visible LDS read might be made to wait for all of them)
   auto pair_flag = [&](int qt) {
@@ -817,10 +860,29 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     const int f1 = ktl + 1 < KT ? bm[(int64_t)qt * KT + ktl + 1] : 0;
     return __builtin_amdgcn_readfirstlane(with_fast_bit(qt, f0 | (f1 << 2)));
   };
-  // Two pipelined loops: the iterations without tests, then (when a node has one visibility word)
-  // the masked ones; with more words per node the masked ones go to the general walk.
-  const bool masks_in_loop = a.W == 1;
-  auto kind_of = [&](int f) { return (f & 16) ? 0 : ((f & 15) != 0 && masks_in_loop) ? 1 : 2; };  // 2: general walk or nothing
+  auto kind_word = [&](int kind, int wi) {
+    uint64_t v;
+    asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(kind_base + (uint32_t)(kind * KIND_WORDS + wi) * 8u) : "memory");
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
+           (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+  };
+  auto last_of_kind = [&](int kind, int qt) {  // last query tile <= qt of the kind (with a visible pair), -1 if none
+    if (!flags_in_lds) {
+      for (; qt >= 0; --qt) {
+        const int f = pair_flag(qt);
+        if ((f & 15) != 0 && kind_of(f) == kind) break;
+      }
+      return qt;
+    }
+    if (qt < 0) return -1;
+    int wi = qt >> 6;
+    uint64_t word = kind_word(kind, wi) & (~0ull >> (63 - (qt & 63)));
+    while (word == 0) {
+      if (--wi < 0) return -1;
+      word = kind_word(kind, wi);
+    }
+    return 64 * wi + 63 - __builtin_clzll(word);
+  };
 
   // ---- loads of one stage, in LPS pieces per wave (piece p of (tile qt, head g) into stage st)
   const uint32_t row_stride = (uint32_t)(a.hq * D);  // elements
@@ -876,19 +938,15 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   const float sc = a.sc;
 
   // ---- the iteration without tests, slot by slot
-  auto pipelined_iter = [&](auto msk_c, int cs, int cur_qt, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
+  // (with masks: vis_lo / vis_hi = this lane's visibility word of the tile, shifted so that bit
+  // 32 h + 8 (e / 4) + e % 4 belongs to element e of half h, i.e. to row 64 qt + 4 H + that number)
+  auto pipelined_iter = [&](auto msk_c, int cs, const IssueCtx& ictx, int is, uint32_t vis_lo, uint32_t vis_hi) __attribute__((always_inline)) {
     constexpr bool MSK = decltype(msk_c)::value;
-    constexpr int XR = MSK ? 3 : 2;
     const uint32_t sbase = smem_base + (uint32_t)cs * STAGEB;
     const uint32_t ra = sbase + roff, ta = sbase + toff, va = sbase + RD + 16 * H;
-    // this lane's rows of the tile are i0 + c, c = 32 h + 8 (e / 4) + e % 4, with i0 = 64 qt + 4 H:
-    // row before the end of the sequence (and key in use)  <=>  c < c_end;   key <= row  <=>  c >= c_key
-    const int i0 = cur_qt * BM + 4 * H;
-    const int c_end = key_ok ? T - i0 : 0, c_key = j - i0;
     bf16x8 op[NSLOT];
     v4i16 lo[NSLOT], hi[NSLOT];
     f32x4 nl[2][4], dl[2][4];
-    u32x4 nd[2][4];  // (with masks) node ids of the rows
     f32x16 S[2], dP[2];
     float pt[2][16], dt[2][16];
     bf16x8 pp[2][2], dss[2][2];
@@ -898,10 +956,8 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
       const uint32_t v = va;  // (named here: captures inside discarded branches trip the compiler)
       f32x4(*const nlp)[4] = nl;
       f32x4(*const dlp)[4] = dl;
-      u32x4(*const ndp)[4] = nd;
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(nlp[h][x]) : "v"(v), "n"(128 * h + 32 * x));
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dlp[h][x]) : "v"(v), "n"(256 + 128 * h + 32 * x));
-      if constexpr (MSK) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(ndp[h][x]) : "v"(v), "n"(512 + 128 * h + 32 * x));
     };
     auto fetch = [&](auto ic) __attribute__((always_inline)) {
       constexpr int i = decltype(ic)::value;
@@ -924,12 +980,12 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
         sync_mid();
         __builtin_amdgcn_sched_barrier(0);
       }
-      if constexpr (extra_reads<XR>(i) != 0) {
+      if constexpr (extra_reads(i) != 0) {
         constexpr int u = (i + VAHEAD - 16) / 4;  // rows 4 u .. 4 u + 3 of the 64
         fetch_val(std::integral_constant<int, u / 4>{}, std::integral_constant<int, u % 4>{});
       }
       fetch(std::integral_constant<int, i + PF>{});
-      wait_lgkmcnt_only<wait_at<XR>(i)>();
+      wait_lgkmcnt_only<wait_at(i)>();
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (i < 32) {
         constexpr int rb = i / 16, s = (i % 16) / 2;
@@ -951,13 +1007,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
       if constexpr (i >= 16 && i < 48) {  // one score of half 0 (slots 16..31) or half 1 (slots 32..47)
         constexpr int h = (i - 16) / 16, e = (i - 16) % 16;
         float pe = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl[h][e >> 2][e & 3]));
-        if constexpr (MSK) {  // Eq. 3 (one visibility word per node) and the end of the sequence
-          constexpr int c = 32 * h + 8 * (e >> 2) + (e & 3);  // row i0 + c of the sequence
-          const uint32_t ni = nd[h][e >> 2][e & 3];
-          const uint64_t same = lanes_eq(ni, (uint32_t)nj), caus = lanes_ge(c, c_key), inside = lanes_gt(c_end, c);
-          const uint64_t anc = lanes_ne((uint32_t)(seen_by >> (ni & 63u)) & 1u, 0u);
-          pe = keep_lanes(pe, inside & ((same & caus) | (~same & anc)));
-        }
+        if constexpr (MSK) pe = keep_if_bit<8 * (e >> 2) + (e & 3)>(pe, h == 0 ? vis_lo : vis_hi);  // Eq. 3 and the end of the sequence
         pt[h][e] = pe;
         dt[h][e] = pe * (dP[h][e] - dl[h][e >> 2][e & 3]);
         if constexpr ((e & 1) == 1) {
@@ -977,10 +1027,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   // ---- the walk of one kind of iteration: query tiles from the last one down, the heads of the group inside
   auto ring_loop = [&](auto msk_c) __attribute__((always_inline)) {
     constexpr int KIND = decltype(msk_c)::value ? 1 : 0;
-    auto next_tile = [&](int qt) {  // last query tile <= qt of this kind, -1 if none
-      while (qt >= 0 && kind_of(pair_flag(qt)) != KIND) --qt;
-      return qt;
-    };
+    auto next_tile = [&](int qt) { return last_of_kind(KIND, qt); };
     auto advance = [&](int& qt, int& g) {
       if (qt < 0) return;
       if (++g == a.G) {
@@ -990,6 +1037,7 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     };
     int cq = next_tile(QT - 1), cg = 0;  // the iteration being computed
     if (cq < 0) return;
+    int cflag = pair_flag(cq);           // the flags of tile cq
     int iq = cq, ig = 0;                 // the iteration whose loads are issued next
 #pragma unroll 1
     for (int st = 0; st < NST - 1; ++st) {
@@ -1009,14 +1057,24 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
 #pragma unroll
       for (int db = 0; db < DB; ++db) asm volatile("" : "+a"(dK[db]), "+a"(dV[db]));
       const IssueCtx ic = prepare_issue(iq, ig);
-      if (KIND == 0 || ((pair_flag(cq) >> (2 * (w >> 1))) & 3) != 0) {
-        pipelined_iter(msk_c, cs, cq, ic, is);
+      if (KIND == 0 || ((cflag >> (2 * (w >> 1))) & 3) != 0) {
+        uint64_t vis = 0;
+        if constexpr (KIND == 1) {
+          // the rows of tile cq that this lane's key is visible to: own node from the key's row on
+          const int first = j - cq * BM;  // first such row of the tile (may lie before or behind it)
+          const uint64_t own = first <= 0 ? ~0ull : first >= 64 ? 0ull : ~0ull << first;
+          vis = tile_visibility(smem_base + (uint32_t)cs * STAGEB + RD + 512, lane, (uint32_t)nj, seen_by, own, T - cq * BM);
+          vis = key_ok ? vis >> (4 * H) : 0ull;
+        }
+        pipelined_iter(msk_c, cs, ic, is, (uint32_t)vis, (uint32_t)(vis >> 32));
       } else {  // no visible pair in this wave's key tile: only the ring's business
         sync_mid();
 #pragma unroll
         for (int p = 0; p < LPS; ++p) issue_piece(p, ic, is);
       }
+      const int cq_before = cq;
       advance(cq, cg);
+      if (KIND == 1 && cq != cq_before && cq >= 0) cflag = pair_flag(cq);
       advance(iq, ig);
       cs = cs + 1 == NST ? 0 : cs + 1;
       is = is + 1 == NST ? 0 : is + 1;
@@ -1033,7 +1091,8 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     const int f = pair_flag(qt);
     return kind_of(f) == 2 ? (f & 15) : 0;
   };
-  dkv_general_walk<D>(a, smem, rest_flag, QT, T, cu, hk, nbase, my_kt, nj, j, key_ok, kf, vf, dK, dV);
+  if (last_of_kind(2, QT - 1) >= 0)  // (the same for every thread)
+    dkv_general_walk<D>(a, smem, rest_flag, QT, T, cu, hk, nbase, my_kt, nj, j, key_ok, kf, vf, dK, dV);
   dkv_store<D>(a, koff, key_ok, H, dK, dV);
 }
 
@@ -1050,34 +1109,19 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
 // end of the sequence) take the general walk afterwards.
 namespace dq2 {
 constexpr int NST = 4, NSLOT = 48;
-template <bool MSK>
-constexpr int PF = MSK ? 3 : 4;      // operands in flight ahead of their MFMA (the masked tile has fewer registers to spare)
+constexpr int PF = 4;                // operands in flight ahead of their MFMA
 constexpr int BLK = dkv2::BLK, TILEB = dkv2::TILEB;
 constexpr int ND = 2 * TILEB;        // node ids of the tile's keys [64] (masked tiles)
 constexpr int STAGEB = ND + 256;     // K tile, V tile, node ids
-constexpr int NAHEAD = 5;            // the node ids of four keys are read this many slots before their first use
 constexpr int opnd_reads(int o) { return o < 32 ? 1 : 2; }
-// The scores of a half are taken one per slot from slot 16 on (half 0) and two per slot from slot 32 on
-// (half 1).  Keys 8 x + 4 H .. + 3 of half hh are first needed in slot 16 + 4 x (hh = 0) or 32 + 2 x (hh = 1);
-// with masks their node ids are read NAHEAD slots earlier.  node_group(slot) = 4 hh + x of the read issued in
-// that slot, -1 if none.
-constexpr int node_group(int slot) {
-  for (int u = 0; u < 8; ++u)
-    if (slot == (u < 4 ? 16 + 4 * u : 32 + 2 * (u - 4)) - NAHEAD) return u;
-  return -1;
-}
-template <bool MSK>
-constexpr int extra_reads(int slot) { return MSK && node_group(slot) >= 0 ? 1 : 0; }
-template <bool MSK>
-constexpr int issued_through(int k) {
+constexpr int issued_through(int k) {  // LDS reads issued up to and including those of operand k
   int t = 0;
-  for (int o = 0; o <= k; ++o) t += (o >= PF<MSK> ? extra_reads<MSK>(o - PF<MSK>) : 0) + opnd_reads(o);
+  for (int o = 0; o <= k; ++o) t += opnd_reads(o);
   return t;
 }
-template <bool MSK>
-constexpr int wait_at(int i) {
-  const int last = i + PF<MSK> < NSLOT ? i + PF<MSK> : NSLOT - 1;
-  const int n = issued_through<MSK>(last) - issued_through<MSK>(i);
+constexpr int wait_at(int i) {  // reads that may still be pending when MFMA i starts
+  const int last = i + PF < NSLOT ? i + PF : NSLOT - 1;
+  const int n = issued_through(last) - issued_through(i);
   return n < 15 ? n : 15;
 }
 constexpr int row_imm(int i) { return dkv2::row_imm(i); }  // half i / 16, k-step (i % 16) / 2, of K (even) or V (odd)
@@ -1157,18 +1201,15 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
 
   // ---- one key tile, slot by slot; MSK: with Eq. 3 (one visibility word per node) and the end of the
   // sequence tested per element
-  auto pipelined_tile = [&](auto msk_c, int cs, int kt, const IssueCtx& ictx, int is) __attribute__((always_inline)) {
+  // (with masks: vis_lo / vis_hi = this lane's visibility word of the tile, shifted so that bit
+  // 32 hh + 8 (e / 4) + e % 4 belongs to element e of half hh, i.e. to key 64 kt + 4 H + that number)
+  auto pipelined_tile = [&](auto msk_c, int cs, const IssueCtx& ictx, int is, uint32_t vis_lo, uint32_t vis_hi) __attribute__((always_inline)) {
     constexpr bool MSK = decltype(msk_c)::value;
-    constexpr int LPS = MSK ? 5 : 4, PFM = PF<MSK>;
+    constexpr int LPS = MSK ? 5 : 4, PFM = PF;
     const uint32_t sbase = smem_base + (uint32_t)cs * STAGEB;
-    const uint32_t ra = sbase + roff, ta = sbase + toff, na = sbase + ND + 16 * H;
-    // this lane's keys of the tile are j_lane + c, c = 32 hh + 8 (e / 4) + e % 4, with j_lane = 64 kt + 4 H:
-    // key before the end of the sequence (and row in use)  <=>  c < c_end;   key <= row  <=>  c <= c_row
-    const int j_lane = kt * BN + 4 * H;
-    const int c_end = row_ok ? T - j_lane : 0, c_row = iq_row - j_lane;
+    const uint32_t ra = sbase + roff, ta = sbase + toff;
     bf16x8 op[NSLOT];
     v4i16 lo[NSLOT], hi[NSLOT];
-    u32x4 nk[8];  // (with masks) node ids of keys 32 hh + 8 x + 4 H .. + 3, at index 4 hh + x
     f32x16 S[2], dP[2];
     float dt[2][16];
     bf16x8 bds[2][2];
@@ -1188,13 +1229,7 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
     auto score = [&](auto hc, auto ec) __attribute__((always_inline)) {  // dS of key e of half h (this lane's row), packed in pairs
       constexpr int h = decltype(hc)::value, e = decltype(ec)::value;
       float p = __builtin_amdgcn_exp2f(fmaf(S[h][e], sc, nl));
-      if constexpr (MSK) {
-        constexpr int c = 32 * h + 8 * (e >> 2) + (e & 3);
-        const uint32_t nj = nk[4 * h + (e >> 2)][e & 3];
-        const uint64_t same = lanes_eq(nj, (uint32_t)nq), caus = lanes_ge(c_row, c), inside = lanes_gt(c_end, c);
-        const uint64_t anc = lanes_ne((uint32_t)(vis0 >> (nj & 63u)) & 1u, 0u);
-        p = keep_lanes(p, inside & ((same & caus) | (~same & anc)));
-      }
+      if constexpr (MSK) p = keep_if_bit<8 * (e >> 2) + (e & 3)>(p, h == 0 ? vis_lo : vis_hi);  // Eq. 3 and the end of the sequence
       dt[h][e] = p * (dP[h][e] - dl);
       if constexpr ((e & 1) == 1) {
         typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -1213,14 +1248,8 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
       }
-      if constexpr (extra_reads<MSK>(i) != 0) {
-        constexpr int u = node_group(i);
-        const uint32_t nn = na;
-        u32x4* const nkp = nk;
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(nkp[u]) : "v"(nn), "n"(128 * (u / 4) + 32 * (u % 4)));
-      }
       fetch(std::integral_constant<int, i + PFM>{});
-      wait_lgkmcnt_only<wait_at<MSK>(i)>();
+      wait_lgkmcnt_only<wait_at(i)>();
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (i < 32) {
         constexpr int hh = i / 16, s = (i % 16) / 2;
@@ -1261,7 +1290,16 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
     int cs = 0, is = NST - 1;
     for (int n = n0; n < n1; ++n, ++in) {
       const IssueCtx ic = prepare_issue(in, n1);
-      pipelined_tile(msk_c, cs, tl.tile(n), ic, is);
+      uint64_t vis = 0;
+      if constexpr (decltype(msk_c)::value) {
+        // the keys of the tile that this lane's row sees: own node up to the row itself
+        const int kt = tl.tile(n);
+        const int last = iq_row - kt * BN;  // last such key of the tile (may lie before or behind it)
+        const uint64_t own = last < 0 ? 0ull : last >= 63 ? ~0ull : (2ull << last) - 1;
+        vis = tile_visibility(smem_base + (uint32_t)cs * STAGEB + ND, lane, (uint32_t)nq, vis0, own, T - kt * BN);
+        vis = row_ok ? vis >> (4 * H) : 0ull;
+      }
+      pipelined_tile(msk_c, cs, ic, is, (uint32_t)vis, (uint32_t)(vis >> 32));
       cs = cs + 1 == NST ? 0 : cs + 1;
       is = is + 1 == NST ? 0 : is + 1;
     }

@@ -22,10 +22,10 @@ CSRC = os.path.join(ROOT, "paper_2602_07529_amd", "csrc")
 HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
 CAP = 24  # reads remembered per path (the hardware counter holds 15)
 
-# pipelined blocks of the backward kernels: LDS reads without masks, with masks
-#   k_bwd_dkv2: 32 row operands + 32 transposed operands (two reads each) + 8 groups of row data (2 or 3 reads)
-#   k_bwd_dq2:  32 row operands + 16 transposed operands (two reads each) (+ 8 reads of node ids)
-PIPELINED = {"k_bwd_dkv2": [112, 120], "k_bwd_dq2": [64, 72]}
+# pipelined blocks of the backward kernels (one without masks, one with): LDS reads of each
+#   k_bwd_dkv2: 32 row operands + 32 transposed operands (two reads each) + 8 groups of row data (2 reads)
+#   k_bwd_dq2:  32 row operands + 16 transposed operands (two reads each)
+PIPELINED = {"k_bwd_dkv2": [112, 112], "k_bwd_dq2": [64, 64]}
 
 
 def _regs(text):
