@@ -1037,7 +1037,6 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     };
     int cq = next_tile(QT - 1), cg = 0;  // the iteration being computed
     if (cq < 0) return;
-    int cflag = pair_flag(cq);           // the flags of tile cq
     int iq = cq, ig = 0;                 // the iteration whose loads are issued next
 #pragma unroll 1
     for (int st = 0; st < NST - 1; ++st) {
@@ -1050,34 +1049,39 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     int cs = 0, is = NST - 1;
-    while (cq >= 0) {
-      // (register classes: the dK / dV accumulators stay in the accumulation registers over the
-      // whole loop; without the hint the allocator moves three of the eight back and forth every
-      // iteration)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) asm volatile("" : "+a"(dK[db]), "+a"(dV[db]));
-      const IssueCtx ic = prepare_issue(iq, ig);
-      if (KIND == 0 || ((cflag >> (2 * (w >> 1))) & 3) != 0) {
-        uint64_t vis = 0;
-        if constexpr (KIND == 1) {
+    // (register classes, at the top of every iteration: the dK / dV accumulators stay in the
+    // accumulation registers over the whole loop; without the hint the allocator moves three of
+    // the eight back and forth every iteration)
+    while (cq >= 0) {  // one query tile: (with masks) its visibility word once, then an iteration per head
+      bool active = true;  // a visible pair in this wave's key tile
+      uint64_t vis = 0;
+      if constexpr (KIND == 1) {
+        active = ((pair_flag(cq) >> (2 * (w >> 1))) & 3) != 0;
+        if (active) {
           // the rows of tile cq that this lane's key is visible to: own node from the key's row on
           const int first = j - cq * BM;  // first such row of the tile (may lie before or behind it)
           const uint64_t own = first <= 0 ? ~0ull : first >= 64 ? 0ull : ~0ull << first;
           vis = tile_visibility(smem_base + (uint32_t)cs * STAGEB + RD + 512, lane, (uint32_t)nj, seen_by, own, T - cq * BM);
-          vis = key_ok ? vis >> (4 * H) : 0ull;
+          vis = key_ok ? vis >> (4 * H) : 0ull;  // bit 32 h + 8 (e / 4) + e % 4: element e of half h
         }
-        pipelined_iter(msk_c, cs, ic, is, (uint32_t)vis, (uint32_t)(vis >> 32));
-      } else {  // no visible pair in this wave's key tile: only the ring's business
-        sync_mid();
-#pragma unroll
-        for (int p = 0; p < LPS; ++p) issue_piece(p, ic, is);
       }
-      const int cq_before = cq;
-      advance(cq, cg);
-      if (KIND == 1 && cq != cq_before && cq >= 0) cflag = pair_flag(cq);
-      advance(iq, ig);
-      cs = cs + 1 == NST ? 0 : cs + 1;
-      is = is + 1 == NST ? 0 : is + 1;
+#pragma unroll 1
+      for (int g = 0; g < a.G; ++g) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) asm volatile("" : "+a"(dK[db]), "+a"(dV[db]));
+        const IssueCtx ic = prepare_issue(iq, ig);
+        if (KIND == 0 || active) {
+          pipelined_iter(msk_c, cs, ic, is, (uint32_t)vis, (uint32_t)(vis >> 32));
+        } else {  // only the ring's business
+          sync_mid();
+#pragma unroll
+          for (int p = 0; p < LPS; ++p) issue_piece(p, ic, is);
+        }
+        advance(iq, ig);
+        cs = cs + 1 == NST ? 0 : cs + 1;
+        is = is + 1 == NST ? 0 : is + 1;
+      }
+      cq = next_tile(cq - 1);
     }
     wait_vmcnt_only<0>();  // (the loads past the end of the walk)
     __builtin_amdgcn_s_barrier();  // every wave is done with the ring before the next loop refills it
