@@ -662,8 +662,11 @@ __global__ void __launch_bounds__(256) k_bwd_dkv(BwdArgs a) {
 //     (tests/test_asm_lds_reads.py checks the generated code for exactly that);
 //   * two such loops run one after the other: the iterations whose pairs are all visible (both key
 //     tiles FULL, nothing past the end of the sequence), then, when a node has one visibility
-//     word, the masked and ragged ones with Eq. 3 tested per element (scalar lane masks; the
-//     ancestor test uses the key's column of the visibility matrix, built once per workgroup).
+//     word, the masked and ragged ones: Eq. 3 of a (query tile, key) pair is one 64-bit word per
+//     lane, built once per query tile from the runs of equal node ids among its rows
+//     (tile_visibility) and applied with two instructions per element; the ancestor test uses the
+//     key's column of the visibility matrix, built once per workgroup.  Both loops find their
+//     tiles through a bitmap per kind of the pair's block-map column.
 //     With more words per node the masked iterations take the general walk of k_bwd_dkv.
 // Every iteration passes the barrier once and issues LPS loads per wave (past the end of the walk:
 // loads of the sequence's first tile, never consumed), so the vmcnt waits are constants.
@@ -1109,8 +1112,10 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
 // one bare barrier per tile in its middle; a tile is 48 slots: S^T = K Q^T and dP^T = V dO^T of
 // the two 32-key halves (32 MFMAs, 16-byte row reads), then dQ^T += K^T dS^T of the two halves
 // (16 MFMAs, transposing reads), with the exponentials of half 0 under the score MFMAs of half 1
-// and those of half 1 under the dQ MFMAs of half 0.  The other tiles (masked, or reaching past the
-// end of the sequence) take the general walk afterwards.
+// and those of half 1 under the dQ MFMAs of half 0.  The masked and ragged tiles follow in a second
+// such loop when a node has one visibility word (Eq. 3 of the tile as one 64-bit word per lane, a
+// lane being a query row here: tile_visibility over the node ids of the tile's keys, which ride
+// the ring as a fifth load), else in the general walk.
 namespace dq2 {
 constexpr int NST = 4, NSLOT = 48;
 constexpr int PF = 4;                // operands in flight ahead of their MFMA
@@ -1204,7 +1209,7 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
   const bool row_ok = me.row_ok;
 
   // ---- one key tile, slot by slot; MSK: with Eq. 3 (one visibility word per node) and the end of the
-  // sequence tested per element
+  // sequence applied per element from the lane's visibility word of the tile
   // (with masks: vis_lo / vis_hi = this lane's visibility word of the tile, shifted so that bit
   // 32 hh + 8 (e / 4) + e % 4 belongs to element e of half hh, i.e. to key 64 kt + 4 H + that number)
   auto pipelined_tile = [&](auto msk_c, int cs, const IssueCtx& ictx, int is, uint32_t vis_lo, uint32_t vis_hi) __attribute__((always_inline)) {
