@@ -204,3 +204,18 @@ def test_bwd_random_batches_on_the_pipelined_kernels():
                 dag_list.append(dags.linear_chain([int(rng.integers(1, 300)) for _ in range(int(rng.integers(1, 4)))]))
         inputs, grads = _forward_backward(dag_list, hq, hkv, 128, 9000 + case)
         _check_against_oracle(dag_list, inputs, grads)
+
+
+def test_bwd_tiles_made_of_many_short_nodes():
+    """The masked iterations build Eq. 3 of a tile from the runs of equal node ids among its 64
+    tokens: here tiles of up to 64 runs (64 nodes of one or two tokens), a tile that is one long run
+    cut by the diagonal, nodes that end exactly on tile boundaries, and a ragged last tile; one
+    visibility word per node, head shapes of both pipelined kernels."""
+    rng = np.random.Generator(np.random.PCG64(777))
+    L1, anc1, _, _ = dags.random_dag(rng, n_nodes=64, depth=6, len_lo=1, len_hi=2)
+    L2, anc2, _, _ = dags.random_dag(rng, n_nodes=40, depth=5, len_lo=1, len_hi=9)
+    dag_list = [(L1, anc1), dags.fork_join(64, [1] * 40 + [64, 63], 5), (L2, anc2),
+                dags.fork_join(130, [64, 64, 2, 62], 64), dags.linear_chain([1] * 64)]
+    for hq, hkv in ((4, 1), (10, 2)):
+        inputs, grads = _forward_backward(dag_list, hq, hkv, 128, 600 + hq)
+        _check_against_oracle(dag_list, inputs, grads)
