@@ -443,7 +443,7 @@ def main():
         c5 = dags.config(4)
         c5["name"] = "qwen32b_long_prefill_bf16"
         n5 = max(1, min(args.steps, 4))
-        extra["config5_prefill"] = prefill_leg(c5, dev, n5, min(args.warmup, 2), "config5")
+        extra["config5_prefill"] = prefill_leg(c5, dev, n5, min(args.warmup, 2), "config5", with_bwd=True)
         torch.cuda.empty_cache()
         extra["config5_decode"] = decode_leg(config5_decode_cfg(), dev, args.steps, args.warmup + 20, "config5",
                                              ("k_decode_wide<128>", "k_decode_merge<128>"), copies=4)
