@@ -93,3 +93,63 @@ def test_random_shapes_forward_and_backward_against_dense_torch_attention(seed):
                 assert (err / r.abs().clamp_min(1.0)).max().item() < 2e-2, what + " " + name
                 if Tb > 1:
                     assert ((g - r).norm() / r.norm().clamp_min(1e-30)).item() < 1e-2, what + " " + name
+
+
+def test_backward_at_config5_full_size_one_kv_group_against_dense_torch():
+    """The largest configuration (2 x 50,176 tokens, 40 query heads on 8 KV heads) through prefill and
+    backward; the five query heads of one KV head of one sequence are compared element by element
+    with dense fp32 attention and its gradient formulas written out with torch on the GPU (a
+    50,176 x 50,176 score matrix per head)."""
+    c = dags.config(4)
+    dag_list = dags.config_dags(c)
+    hq, hkv, d = c["hq"], c["hkv"], c["d"]
+    G = hq // hkv
+    T = sum(int(np.sum(L)) for L, _ in dag_list)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    draw = lambda heads, scale: (torch.randn(T, heads, d, generator=gen, device=DEV) * scale).to(torch.bfloat16)
+    q, k, v, dout = draw(hq, 0.5), draw(hkv, 0.5), draw(hkv, 0.5), draw(hq, 1.0)
+    from tests.gpu_util import build_meta
+    _, meta = build_meta(dag_list, hq, hkv, d, torch.bfloat16)
+    B.dag_rope_qk(meta.get("pos_ids"), q, k, c["theta"])
+    out = torch.empty_like(q)
+    lse = torch.empty(T, hq, dtype=torch.float32, device=DEV)
+    B.dag_attn_prefill(meta, q, k, v, out, lse)
+    dq, dk, dv = (torch.full_like(x, float("nan")) for x in (q, k, v))
+    B.dag_attn_prefill_bwd(meta, q, k, v, out, dout, lse, dq, dk, dv)
+    torch.cuda.synchronize()
+    for x in (dq, dk, dv):
+        assert torch.isfinite(x.float()).all()
+    seq, hk = 1, 3
+    L, anc = dag_list[seq]
+    t0, Tb = sum(int(np.sum(x[0])) for x in dag_list[:seq]), int(np.sum(L))
+    sl = slice(t0, t0 + Tb)
+    mask = _dense_mask(L, anc)
+    kk, vv = k[sl, hk].float(), v[sl, hk].float()
+    ref_dk, ref_dv, sum_p2 = torch.zeros_like(kk), torch.zeros_like(vv), torch.zeros(Tb, device=DEV)
+    for j in range(G):
+        h = hk * G + j
+        qq, do = q[sl, h].float(), dout[sl, h].float()
+        s = (qq @ kk.T) / np.sqrt(d)
+        s.masked_fill_(~mask, float("-inf"))
+        p = torch.softmax(s, dim=-1)
+        del s
+        o = p @ vv
+        assert (out[sl, h].float() - o).abs().max().item() < 2e-2
+        ref_dv += p.T @ do
+        ds = do @ vv.T
+        ds.sub_((do * o).sum(-1, keepdim=True)).mul_(p)
+        sum_p2 += p.square().sum(0)
+        del p
+        ref_dq = (ds @ kk) / np.sqrt(d)
+        ref_dk += (ds.T @ qq) / np.sqrt(d)
+        del ds
+        got = dq[sl, h].float()
+        assert ((got - ref_dq).abs() / ref_dq.abs().clamp_min(1.0)).max().item() < 2e-2, "dq of head %d" % h
+        assert ((got - ref_dq).norm() / ref_dq.norm()).item() < 1e-2, "dq of head %d" % h
+    sigma = 2.26e-3 * sum_p2.sqrt()[:, None]  # (see the test above: bf16 probabilities in P^T dO and dS^T Q)
+    for name, got, ref in (("dk", dk[sl, hk].float(), ref_dk), ("dv", dv[sl, hk].float(), ref_dv)):
+        err = (got - ref).abs()
+        err = torch.where(err < 6 * sigma, torch.zeros_like(err), err)
+        assert (err / ref.abs().clamp_min(1.0)).max().item() < 2e-2, name
+        assert ((got - ref).norm() / ref.norm()).item() < 1e-2, name
