@@ -748,6 +748,28 @@ __device__ __forceinline__ float keep_if_bit(float x, uint32_t word) {
   return r;
 }
 
+// The score MFMAs of k_bwd_dkv2 written out, with their results in vector registers and the B
+// operand (the K / V rows of the wave's keys, fixed for the workgroup) in accumulation registers.
+// A kernel with more than 256 registers gets the accumulation-register form for every MFMA the
+// compiler selects, and the vector instructions that turn scores into probabilities would first
+// have to copy every score out of there; the dK / dV accumulators stay where they are.  The
+// compiler does not know what these statements are: the last MFMA of a chain is followed by 20
+// idle states, more than the 19 a vector instruction must keep from a 16-pass MFMA whose result
+// it reads; a chain's own accumulation is two MFMAs apart (the S and dP chains alternate).
+__device__ __forceinline__ f32x16 mfma32_first_v(bf16x8 a, bf16x8 b_acc) {
+  f32x16 d;
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b_acc));
+  return d;
+}
+__device__ __forceinline__ f32x16 mfma32_next_v(bf16x8 a, bf16x8 b_acc, f32x16 c) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b_acc));
+  return c;
+}
+__device__ __forceinline__ f32x16 mfma32_last_v(bf16x8 a, bf16x8 b_acc, f32x16 c) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 3" : "+v"(c) : "v"(a), "v"(b_acc));
+  return c;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt_only() {  // s_waitcnt vmcnt(N) (gfx9 encoding)
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
@@ -992,11 +1014,14 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (i < 32) {
         constexpr int rb = i / 16, s = (i % 16) / 2;
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if constexpr ((i & 1) == 0)
-          S[rb] = mfma32(op[i], kf[s], s == 0 ? zero : S[rb]);
+        const bf16x8 b_acc = (i & 1) == 0 ? kf[s] : vf[s];
+        f32x16& acc = (i & 1) == 0 ? S[rb] : dP[rb];
+        if constexpr (s == 0)
+          acc = mfma32_first_v(op[i], b_acc);
+        else if constexpr (s < D / 16 - 1)
+          acc = mfma32_next_v(op[i], b_acc, acc);
         else
-          dP[rb] = mfma32(op[i], vf[s], s == 0 ? zero : dP[rb]);
+          acc = mfma32_last_v(op[i], b_acc, acc);
       } else {
         constexpr int jx = i - 32, h = jx / 16, jj = jx % 16, db = jj / 4, hh = (jj / 2) % 2;
         const v8i16 x = {lo[i][0], lo[i][1], lo[i][2], lo[i][3], hi[i][0], hi[i][1], hi[i][2], hi[i][3]};
