@@ -323,7 +323,12 @@ def backward_timing(pw, dev, calls, warmup):
     return ms, 2.5 * flops / (ms * 1e-3) / 1e12
 
 
-BWD_KERNELS = ("k_bwd_delta<128>", "k_bwd_tokvis", "k_bwd_dq2", "k_bwd_weights", "k_bwd_order", "k_bwd_dkv2")
+def bwd_kernels(G):
+    """The launches of dag_attn_prefill_bwd at head dimension 128 with G query heads per KV head: groups of
+    four heads on one query tile (k_bwd_dq2<false>), one or two left-over heads on four query tiles each."""
+    wide = G % 4 if G % 4 in (1, 2) else 0
+    dq = (("k_bwd_dq2<false>",) if G - wide > 0 else ()) + (("k_bwd_wide_rows", "k_bwd_dq2<true>") if wide else ())
+    return ("k_bwd_delta<128>", "k_bwd_tokvis") + dq + ("k_bwd_weights", "k_bwd_order", "k_bwd_dkv2")
 
 
 def prefill_leg(cfg, dev, launches, warmup, workload_key, with_bwd=False):
@@ -353,10 +358,10 @@ def prefill_leg(cfg, dev, launches, warmup, workload_key, with_bwd=False):
     if with_bwd:
         ms_bwd, tf_bwd = backward_timing(pw, dev, 3, 1)
         bwd = {"metric": "dag_attn_prefill_bwd_useful_tflops", "value": tf_bwd, "unit": "TFLOP/s", "ms_per_call": ms_bwd,
-               "calls": 3, "roofline": {"bound": "mfma", "kernel": "+".join(BWD_KERNELS), "achieved": tf_bwd,
+               "calls": 3, "roofline": {"bound": "mfma", "kernel": "+".join(bwd_kernels(cfg["hq"] // cfg["hkv"])), "achieved": tf_bwd,
                                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                         "frac": tf_bwd / MFMA_BF16_PEAK_TFLOPS,
-                                        "traffic": traffic_of(workload_key, *BWD_KERNELS)}}
+                                        "traffic": traffic_of(workload_key, *bwd_kernels(cfg["hq"] // cfg["hkv"]))}}
     return {"metric": "dag_attn_prefill_useful_tflops", "value": flops / (ms_path * 1e-3) / 1e12, "unit": "TFLOP/s",
             "prefill_bwd": bwd,
             "launches": launches, "ms_prefill_path(meta+rope+attn)": ms_path, "ms_attn_kernel": ms_attn,
@@ -513,7 +518,7 @@ def main():
     tflops_kernel = flops / (ms_attn * 1e-3) / 1e12
     dec_gbs = dw.bytes / (ms_deck * 1e-3) / 1e9
     cfg = pw.cfg
-    bwd_kernels = BWD_KERNELS
+    bwd_k = bwd_kernels(cfg["hq"] // cfg["hkv"])
     res = {
         "metric": "dag_attn_prefill_useful_tflops",
         "value": tflops_seg,
@@ -553,10 +558,10 @@ def main():
         "prefill_bwd": {"metric": "dag_attn_prefill_bwd_useful_tflops", "value": bwd_tf,
                         "unit": "TFLOP/s", "ms_per_call": ms_bwd, "calls": n_bwd,
                         "useful_flops": "2.5 x forward (five products per visible pair)",
-                        "roofline": {"bound": "mfma", "kernel": "+".join(bwd_kernels),
+                        "roofline": {"bound": "mfma", "kernel": "+".join(bwd_k),
                                      "achieved": bwd_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
                                      "unit": "TFLOP/s", "frac": bwd_tf / MFMA_BF16_PEAK_TFLOPS,
-                                     "traffic": traffic_of("main", *bwd_kernels)}},
+                                     "traffic": traffic_of("main", *bwd_k)}},
         "wall_s_timed_loop": wall,
     }
     res.update(extra)

@@ -7,16 +7,18 @@
 //   k_bwd_delta   delta and -lse log2(e) per (token, query head)
 //   k_bwd_tokvis, k_bwd_weights, k_bwd_order   small tables: first visibility word per token; weight
 //                 and launch rank of the key-tile pairs (the dK/dV workgroups start heaviest first)
-//   k_bwd_dq2     head dimension 128, three or more query heads per KV head: one workgroup per
-//                 (64-row query tile, KV head, four of its query heads), eight waves; the K / V tiles
-//                 of the tile's row of the forward's FULL-first CSR stream through an LDS ring and
-//                 every tile is a fixed sequence of 48 slots (described at the kernel)
+//   k_bwd_dq2     head dimension 128: one workgroup per (64-row query tile, KV head, four of its
+//                 query heads), eight waves; the K / V tiles of the tile's row of the forward's
+//                 FULL-first CSR stream through an LDS ring and every tile is a fixed sequence of
+//                 48 slots (described at the kernel).  One or two heads that the groups of four
+//                 leave over (G = 1, 2, 5, 6, ...) run as k_bwd_dq2<true>: one head on four
+//                 consecutive query tiles per workgroup, with tile lists from k_bwd_wide_rows
 //   k_bwd_dkv2    head dimension 128: one workgroup per (pair of 64-key tiles, KV head), four
 //                 waves; the Q / dO tiles of the query tiles that see the pair stream through an LDS
 //                 ring, one (tile, query head) = 64 slots (described at the kernel); nothing is
 //                 accumulated through atomics, so the results do not depend on the order of execution
 //   k_bwd_dq, k_bwd_dkv   the first versions (tiles staged through registers, compiler-scheduled):
-//                 every other shape, and inside the two kernels above the "general walk" over
+//                 head dimension 64, and inside the two kernels above the "general walk" over
 //                 masked tiles of sequences with more than one visibility word per node
 // Register layout of a 32x32 MFMA result C = A B:  lane (L, H) = (lane % 32, lane / 32) holds
 // column L and the 16 rows rho_H(e) = 8 (e / 4) + 4 H + e % 4.  A result is used again as the B
@@ -57,6 +59,15 @@ struct BwdArgs {
   int n_seqs, W, hq, hkv, G;
   long total_rows;  // T * hq
   float scale, sc;  // sc = scale * log2(e)
+  // dQ: heads 0 .. dq_narrow - 1 of a KV head run four at a time on one query tile, the others one
+  // at a time on four query tiles (k_bwd_dq2<true>), whose tile lists k_bwd_wide_rows writes: the
+  // list of the tiles 4 c .. 4 c + 3 of a sequence lies where row 4 c of its dense block map does
+  int dq_narrow;
+  int total_qtiles;
+  int32_t* wide_col;    // [dense map] key tiles that one of the four query tiles sees, those that all four see in full first
+  uint8_t* wide_flag;   // [dense map] block-map entries of the four query tiles, two bits each
+  int32_t *wide_n, *wide_nfast;  // [total query tiles] length of the list, leading entries without tests (at every fourth tile)
+  int32_t* wide_list;   // [total query tiles + 1] the first tiles of the groups of four, sequence after sequence; last element: their number
 };
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -197,9 +208,11 @@ struct TileList {
 // the tile's K and V rows go through LDS (row-major, padded) for all the waves; the next tile is
 // fetched into registers while the current one is multiplied (constant per-thread offsets, rows
 // past the end re-read the last row and are zeroed on the way to LDS, no load depends on another).
+// (fshift >= 0: a list entry's flag holds the block-map entries of four query tiles, this wave's at
+// that bit; a wave whose query tile does not see the key tile only helps to stage it)
 template <int D, int NT>
 __device__ __forceinline__ void dq_general_walk(const BwdArgs& a, unsigned char* smem, const TileList& tl, int n0, int n1, int T,
-                                                int cu, int hk, int nbase, const DqLane<D>& me, f32x16* dQ) {
+                                                int cu, int hk, int nbase, const DqLane<D>& me, f32x16* dQ, int fshift = -1) {
   constexpr int LD = D + 8;  // padded rows: the 16-byte operand reads of 32 consecutive rows spread over the banks
   uint16_t* const sK = (uint16_t*)smem;   // [BN][LD]
   uint16_t* const sV = sK + BN * LD;      // [BN][LD]
@@ -247,7 +260,8 @@ __device__ __forceinline__ void dq_general_walk(const BwdArgs& a, unsigned char*
   fetch(kt_next);
   for (int n = n0; n < n1; ++n) {
     const int kt = kt_next;
-    const int flag = tl.flag_of(n);
+    int flag = tl.flag_of(n);
+    if (fshift >= 0) flag = (flag >> fshift) & 3;
     const int j0 = kt * BN;
     __syncthreads();  // everybody is done with the tile in LDS
     commit(kt);
@@ -256,6 +270,7 @@ __device__ __forceinline__ void dq_general_walk(const BwdArgs& a, unsigned char*
       kt_next = tl.tile(n + 1);
       fetch(kt_next);  // in flight during the products below
     }
+    if (flag == 0) continue;
     const bool need_mask = flag == 1;
 #pragma unroll 1
     for (int hh = 0; hh < 2; ++hh) {
@@ -302,13 +317,12 @@ __device__ __forceinline__ DqTile dq_tile(const BwdArgs& a) {
   t.cu = d[0], t.T = d[1], t.row0 = d[2], t.c0 = d[3], t.N = d[4], t.nfast = d[5], t.nbase = d[6];
   return t;
 }
-template <int D, int HG>
-__device__ __forceinline__ void dq_setup(const BwdArgs& a, const DqTile& t, int hk, DqLane<D>& me) {
-  const int g = blockIdx.z * HG + (threadIdx.x >> 7);  // two waves per query head
-  const bool head_ok = g < a.G;
+// (g: query head of the KV head, row0: first row of this wave pair's 64-row query tile)
+template <int D>
+__device__ __forceinline__ void dq_setup_at(const BwdArgs& a, const DqTile& t, int hk, int g, bool head_ok, int row0, DqLane<D>& me) {
   const int h = hk * a.G + min(g, a.G - 1);
   const int tid = threadIdx.x, w = (tid >> 6) & 1, lane = tid & 63, L = lane & 31, H = lane >> 5;
-  me.i = t.row0 + 32 * w + L;
+  me.i = row0 + 32 * w + L;
   me.row_ok = me.i < t.T && head_ok;
   const int ic = min(me.i, t.T - 1);
   me.qoff = ((size_t)(t.cu + ic) * a.hq + h) * D;
@@ -321,6 +335,11 @@ __device__ __forceinline__ void dq_setup(const BwdArgs& a, const DqTile& t, int 
   me.dl = a.delta[(size_t)(t.cu + ic) * a.hq + h];
   me.ni = a.tok_node[t.cu + ic];
   me.vis0 = a.tok_vis0[t.cu + ic];
+}
+template <int D, int HG>
+__device__ __forceinline__ void dq_setup(const BwdArgs& a, const DqTile& t, int hk, DqLane<D>& me) {
+  const int g = blockIdx.z * HG + (threadIdx.x >> 7);  // two waves per query head
+  dq_setup_at<D>(a, t, hk, g, g < a.dq_narrow, t.row0, me);
 }
 
 // First dQ kernel (every head dimension and head grouping): the general walk over all tiles.
@@ -1128,6 +1147,61 @@ __global__ void __launch_bounds__(256) k_bwd_dkv2(BwdArgs a) {
   dkv_store<D>(a, koff, key_ok, H, dK, dV);
 }
 
+// Tile lists of the dQ workgroups that take one query head on four query tiles (the heads that do
+// not fill a group of four): one wave per query tile of the batch, those of every fourth tile of a
+// sequence work.  The list of tiles 4 c .. 4 c + 3 holds every key tile that one of them sees, with
+// the four block-map entries as its flag; the key tiles that all four see in full, with all their
+// rows and keys inside the sequence, come first (they run without tests), both parts ascending.
+__global__ void __launch_bounds__(64) k_bwd_wide_rows(BwdArgs a) {
+  const int x = blockIdx.x, lane = threadIdx.x;
+  const int b = dag_find_segment(a.qtile_start, a.n_seqs, x);
+  const int qt = x - a.qtile_start[b];
+  if (qt & 3) return;
+  const int T = a.cu_seqlens[b + 1] - a.cu_seqlens[b];
+  const int QT = (T + BM - 1) / BM, KT = (T + BN - 1) / BN;
+  const uint8_t* bm = a.block_map + a.block_map_off[b];
+  const int64_t base = a.block_map_off[b] + (int64_t)qt * KT;
+  const bool rows_in = (qt + 4) * BM <= T;
+  auto entries = [&](int kt) {
+    int f8 = 0;
+    if (kt < KT)
+      for (int i = 0; i < 4; ++i)
+        if (qt + i < QT) f8 |= (int)bm[(int64_t)(qt + i) * KT + kt] << (2 * i);
+    return f8;
+  };
+  int n = 0, nfast = 0;
+  for (int k0 = 0; k0 < KT; k0 += 64) {
+    const int kt = k0 + lane, f8 = entries(kt);
+    nfast += __builtin_popcountll(__builtin_amdgcn_ballot_w64(rows_in && f8 == 0xAA && (kt + 1) * BN <= T));
+    n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(f8 != 0));
+  }
+  int at_fast = 0, at_rest = nfast;
+  const uint64_t below = (1ull << lane) - 1;
+  for (int k0 = 0; k0 < KT; k0 += 64) {
+    const int kt = k0 + lane, f8 = entries(kt);
+    const bool fast = rows_in && f8 == 0xAA && (kt + 1) * BN <= T, rest = f8 != 0 && !fast;
+    const uint64_t mf = __builtin_amdgcn_ballot_w64(fast), mr = __builtin_amdgcn_ballot_w64(rest);
+    if (fast || rest) {
+      const int64_t at = base + (fast ? at_fast + __builtin_popcountll(mf & below) : at_rest + __builtin_popcountll(mr & below));
+      a.wide_col[at] = kt;
+      a.wide_flag[at] = (uint8_t)f8;
+    }
+    at_fast += __builtin_popcountll(mf);
+    at_rest += __builtin_popcountll(mr);
+  }
+  if (lane == 0) {
+    a.wide_n[x] = n;
+    a.wide_nfast[x] = nfast;
+    // the groups of the batch, numbered through (the launch of the dQ workgroups runs over these
+    // numbers: over the query tiles, with three of four workgroups leaving at once, the ones that
+    // stay would all have the same index modulo four and land on two of the eight XCDs)
+    int before = 0;
+    for (int bb = 0; bb < b; ++bb) before += (a.qtile_start[bb + 1] - a.qtile_start[bb] + 3) / 4;
+    a.wide_list[before + qt / 4] = x;
+    if (qt == 0 && a.qtile_start[b + 1] == a.total_qtiles) a.wide_list[a.total_qtiles] = before + (QT + 3) / 4;  // (the last sequence with tokens)
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // k_bwd_dq2: the dQ kernel for head dimension 128 and four query heads per workgroup, with the data
 // movement and instruction order of k_bwd_dkv2.  Eight waves (head g = wave / 2, query rows
@@ -1165,6 +1239,10 @@ constexpr int tr_imm(int i) {  // i >= 32: K^T operand of key half (i - 32) / 8,
 }
 }  // namespace dq2
 
+// WIDE: the same workgroup turned by ninety degrees -- one query head on four consecutive query
+// tiles (wave pair p takes tile 4 c + p), for the heads that do not fill a group of four: the
+// waves still share every staged K / V tile.  The tile list is the one k_bwd_wide_rows wrote.
+template <bool WIDE>
 __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
   using namespace dq2;
   constexpr int D = 128, HG = 4, NT = 512;
@@ -1175,19 +1253,36 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int32_t sCol[MAX_ROW_LDS];
   __shared__ uint8_t sFlg[MAX_ROW_LDS];
-  const DqTile t = dq_tile(a);
-  const int hk = blockIdx.y, cu = t.cu, T = t.T;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, L = lane & 31, H = lane >> 5;
+  const int pair = w >> 1;  // (WIDE) which of the four query tiles
+  DqTile t;
+  int64_t wide_base = 0;
+  if constexpr (!WIDE) {
+    t = dq_tile(a);
+  } else {
+    const int groups = a.wide_list[a.total_qtiles];
+    if ((int)blockIdx.x >= groups) return;  // (the whole workgroup: the launch is sized by a bound)
+    const int x = a.wide_list[groups - 1 - (int)blockIdx.x];  // the long rows at the end of a sequence first
+    const int b = dag_find_segment(a.qtile_start, a.n_seqs, x);
+    const int qt = x - a.qtile_start[b];
+    t.cu = a.cu_seqlens[b], t.T = a.cu_seqlens[b + 1] - t.cu, t.row0 = qt * BM, t.c0 = 0;
+    t.N = a.wide_n[x], t.nfast = a.wide_nfast[x], t.nbase = a.node_start[b];
+    wide_base = a.block_map_off[b] + (int64_t)qt * ((t.T + BN - 1) / BN);
+  }
+  const int hk = blockIdx.y, cu = t.cu, T = t.T;
   DqLane<D> me;
-  dq_setup<D, HG>(a, t, hk, me);
+  if constexpr (!WIDE)
+    dq_setup<D, HG>(a, t, hk, me);
+  else
+    dq_setup_at<D>(a, t, hk, a.dq_narrow + (int)blockIdx.z, true, t.row0 + BM * pair, me);
   f32x16 dQ[D / 32];
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
     for (int e = 0; e < 16; ++e) dQ[db][e] = 0.f;
   TileList tl;
-  tl.col = a.qtile_col + t.c0;
-  tl.flag = a.qtile_flag + t.c0;
+  tl.col = WIDE ? a.wide_col + wide_base : a.qtile_col + t.c0;
+  tl.flag = WIDE ? a.wide_flag + wide_base : a.qtile_flag + t.c0;
   tl.fill<NT>(sCol, sFlg, t.N);
   __syncthreads();
   const int NF = t.nfast;  // entries 0 .. NF - 1 of the list: every pair visible, inside the sequence
@@ -1327,6 +1422,8 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
       uint64_t vis = 0;
       if constexpr (decltype(msk_c)::value) {
         // the keys of the tile that this lane's row sees: own node up to the row itself
+        // (WIDE: none at all when the wave pair's own query tile does not see the key tile -- the
+        // few such tiles along the diagonal are multiplied through with zeros)
         const int kt = tl.tile(n);
         const int last = iq_row - kt * BN;  // last such key of the tile (may lie before or behind it)
         const uint64_t own = last < 0 ? 0ull : last >= 63 ? ~0ull : (2ull << last) - 1;
@@ -1346,7 +1443,7 @@ __global__ void __launch_bounds__(512) k_bwd_dq2(BwdArgs a) {
   const int NM = a.W == 1 ? t.N : NF;
   ring_loop(std::true_type{}, NF, NM);
   __syncthreads();  // the ring is free: the general walk lays its own tiles over it
-  dq_general_walk<D, NT>(a, smem, tl, NM, t.N, T, cu, hk, t.nbase, me, dQ);
+  dq_general_walk<D, NT>(a, smem, tl, NM, t.N, T, cu, hk, t.nbase, me, dQ, WIDE ? 2 * pair : -1);
   dq_store<D>(a, me, H, dQ);
 }
 
@@ -1361,6 +1458,9 @@ int launch_dq(const BwdArgs& a, long total_qtiles, hipStream_t stream) {
   return DAG_OK;
 }
 
+// Query heads per KV head that the dQ kernel takes one at a time on four query tiles.
+int bwd_wide_heads(int G) { return (G % 4 == 1 || G % 4 == 2) ? G % 4 : 0; }
+
 // Development switch, read once: DAGATTN_BWD_V1=1 runs the first dQ and dK/dV kernels for every shape.
 bool bwd_first_version() {
   static const bool v = [] {
@@ -1371,18 +1471,32 @@ bool bwd_first_version() {
 }
 
 template <int D>
-int launch_bwd(const BwdArgs& a, long total_qtiles, long total_ktiles, hipStream_t stream) {
+int launch_bwd(const BwdArgs& args, long total_qtiles, long total_ktiles, hipStream_t stream) {
+  BwdArgs a = args;
   constexpr int RPB = 256 / (D / 8);  // rows per workgroup of k_bwd_delta
   hipLaunchKernelGGL((k_bwd_delta<D>), dim3((unsigned)((a.total_rows + RPB - 1) / RPB)), dim3(256), 0, stream, a);
   const int total_tokens = (int)(a.total_rows / a.hq);
   hipLaunchKernelGGL(k_bwd_tokvis, dim3((unsigned)((total_tokens + 255) / 256)), dim3(256), 0, stream, a, total_tokens);
   DAG_LAUNCH_CHECK();
   int rc;
-  if (D == 128 && a.G >= 3 && !bwd_first_version()) {
+  a.dq_narrow = a.G;
+  if (D == 128 && !bwd_first_version()) {
+    // one or two heads left over by the groups of four (G = 1, 2, 5, 6, ...) take four query tiles each;
+    // three left over (G = 3, 7, ...) run as a group of four with one idle wave pair
+    const int wide = bwd_wide_heads(a.G);
+    a.dq_narrow = a.G - wide;
     constexpr int sm2 = dq2::NST * dq2::STAGEB;
-    if (hipFuncSetAttribute((const void*)k_bwd_dq2, hipFuncAttributeMaxDynamicSharedMemorySize, sm2) != hipSuccess)
+    if (hipFuncSetAttribute((const void*)k_bwd_dq2<false>, hipFuncAttributeMaxDynamicSharedMemorySize, sm2) != hipSuccess ||
+        hipFuncSetAttribute((const void*)k_bwd_dq2<true>, hipFuncAttributeMaxDynamicSharedMemorySize, sm2) != hipSuccess)
       return DAG_ERR_HIP;
-    hipLaunchKernelGGL(k_bwd_dq2, dim3((unsigned)total_qtiles, (unsigned)a.hkv, (unsigned)((a.G + 3) / 4)), dim3(512), sm2, stream, a);
+    if (a.dq_narrow > 0)
+      hipLaunchKernelGGL(k_bwd_dq2<false>, dim3((unsigned)total_qtiles, (unsigned)a.hkv, (unsigned)((a.dq_narrow + 3) / 4)),
+                         dim3(512), sm2, stream, a);
+    if (wide > 0) {
+      hipLaunchKernelGGL(k_bwd_wide_rows, dim3((unsigned)total_qtiles), dim3(64), 0, stream, a);
+      const long groups_bound = std::min(total_qtiles, (total_qtiles + 3) / 4 + a.n_seqs);
+      hipLaunchKernelGGL(k_bwd_dq2<true>, dim3((unsigned)groups_bound, (unsigned)a.hkv, (unsigned)wide), dim3(512), sm2, stream, a);
+    }
     rc = hipGetLastError() == hipSuccess ? DAG_OK : DAG_ERR_HIP;
   } else {
     rc = a.G >= 3 ? launch_dq<D, 4>(a, total_qtiles, stream)
@@ -1594,9 +1708,16 @@ extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t h
       m->sizes.total_ktiles < 0)
     return 0;
   // delta and -lse log2(e) [T][hq] fp32 each, weight and launch order of the key tiles, first visibility word per token
-  return 2 * dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) +
-         2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) +
-         dag_align_up((size_t)m->sizes.total_tokens * 8, 256) + 256;
+  size_t n = 2 * dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) +
+             2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) +
+             dag_align_up((size_t)m->sizes.total_tokens * 8, 256) + 256;
+  // head groupings that leave one or two heads over at head dimension 128: the tile lists of the dQ
+  // workgroups that take four query tiles (an int32 and a byte per entry of the dense block map,
+  // three int32 per query tile)
+  if (head_dim == 128 && hq % hkv == 0 && bwd_wide_heads(hq / hkv) > 0 && m->sizes.total_tiles >= 0)
+    n += dag_align_up((size_t)m->sizes.total_tiles * 4, 256) + dag_align_up((size_t)m->sizes.total_tiles, 256) +
+         3 * dag_align_up((size_t)(m->sizes.total_qtiles + 1) * 4, 256);
+  return n;
 }
 
 extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const void* k, const void* v, const void* out,
@@ -1646,6 +1767,13 @@ extern "C" int dag_attn_prefill_bwd(const dag_meta_t* m, const void* q, const vo
   a.kt_order = a.kt_weight + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4;
   a.total_ktiles = (int)m->sizes.total_ktiles;
   a.tok_vis0 = (uint64_t*)(a.kt_order + dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) / 4);
+  a.wide_col = (int32_t*)((char*)a.tok_vis0 + dag_align_up((size_t)m->sizes.total_tokens * 8, 256));
+  a.wide_flag = (uint8_t*)((char*)a.wide_col + dag_align_up((size_t)m->sizes.total_tiles * 4, 256));
+  a.wide_n = (int32_t*)((char*)a.wide_flag + dag_align_up((size_t)m->sizes.total_tiles, 256));
+  a.wide_nfast = a.wide_n + dag_align_up((size_t)(m->sizes.total_qtiles + 1) * 4, 256) / 4;
+  a.wide_list = a.wide_nfast + dag_align_up((size_t)(m->sizes.total_qtiles + 1) * 4, 256) / 4;
+  a.total_qtiles = (int)m->sizes.total_qtiles;
+  a.dq_narrow = hq / hkv;
   a.cu_seqlens = m->cu_seqlens; a.node_start = m->node_start; a.tok_node = m->tok_node;
   a.qtile_start = m->qtile_start; a.ktile_start = m->ktile_start;
   a.qtile_order = m->qtile_order;

@@ -375,6 +375,9 @@ def test_backward_argument_errors():
     need = L.dag_prefill_bwd_workspace_bytes(C.byref(m), 32, 8, 128)
     # delta and -lse log2(e), weight and order of the one key tile, first visibility word of the 20 tokens
     assert need == 2 * 2560 + 2 * 256 + 256 + 256
+    # five query heads per KV head leave one over: the tile lists of the dQ workgroups that take four query tiles
+    # (one entry of the dense block map here, one query tile)
+    assert L.dag_prefill_bwd_workspace_bytes(C.byref(m), 40, 8, 128) == 2 * 3328 + 2 * 256 + 256 + 256 + (256 + 256 + 3 * 256)
     args = (32, 8, 128, 0.1, B.DAG_BF16)
     call = lambda *ptrs, a=args, ws=p, nb=need, meta=m: L.dag_attn_prefill_bwd(
         C.byref(meta) if meta is not None else None, *ptrs, *a, ws, nb, None)
