@@ -219,3 +219,19 @@ def test_bwd_tiles_made_of_many_short_nodes():
     for hq, hkv in ((4, 1), (10, 2)):
         inputs, grads = _forward_backward(dag_list, hq, hkv, 128, 600 + hq)
         _check_against_oracle(dag_list, inputs, grads)
+
+
+@pytest.mark.parametrize("hq,hkv", [(1, 1), (2, 1), (5, 1), (6, 1), (10, 2)])
+def test_bwd_left_over_heads_on_four_query_tiles(hq, hkv):
+    """Head groupings that leave one or two heads over run dQ workgroups of one head on four
+    consecutive query tiles: sequences of 1, 2, 3, 4, 5 and 9 query tiles and one of a single token
+    (groups that end before their fourth tile), a sequence with more than 64 nodes (two visibility
+    words: its masked tiles take the general walk with one block-map entry per wave pair), tiles
+    that only some of the four query tiles see."""
+    rng = np.random.Generator(np.random.PCG64(4242 + hq))
+    many = dags.random_dag(rng, n_nodes=90, depth=6, len_lo=1, len_hi=14)[:2]
+    dag_list = [dags.linear_chain([1]), dags.linear_chain([50]), dags.fork_join(70, [30, 20], 8),
+                dags.fork_join(64, [64, 40], 20), many, dags.fork_join(100, [90, 64, 33], 17),
+                dags.random_dag(rng, n_nodes=30, depth=5, len_lo=1, len_hi=40)[:2], dags.fork_join(256, [64] * 4, 64)]
+    inputs, grads = _forward_backward(dag_list, hq, hkv, 128, 800 + hq)
+    _check_against_oracle(dag_list, inputs, grads)
