@@ -325,8 +325,8 @@ def backward_timing(pw, dev, calls, warmup):
 
 def bwd_kernels(G):
     """The launches of dag_attn_prefill_bwd at head dimension 128 with G query heads per KV head: groups of
-    four heads on one query tile (k_bwd_dq2<false>), one or two left-over heads on four query tiles each."""
-    wide = G % 4 if G % 4 in (1, 2) else 0
+    four heads on one query tile (k_bwd_dq2<false>), the left-over heads on four query tiles each."""
+    wide = G % 4
     dq = (("k_bwd_dq2<false>",) if G - wide > 0 else ()) + (("k_bwd_wide_rows", "k_bwd_dq2<true>") if wide else ())
     return ("k_bwd_delta<128>", "k_bwd_tokvis") + dq + ("k_bwd_weights", "k_bwd_order", "k_bwd_dkv2")
 

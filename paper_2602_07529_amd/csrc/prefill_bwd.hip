@@ -10,8 +10,8 @@
 //   k_bwd_dq2     head dimension 128: one workgroup per (64-row query tile, KV head, four of its
 //                 query heads), eight waves; the K / V tiles of the tile's row of the forward's
 //                 FULL-first CSR stream through an LDS ring and every tile is a fixed sequence of
-//                 48 slots (described at the kernel).  One or two heads that the groups of four
-//                 leave over (G = 1, 2, 5, 6, ...) run as k_bwd_dq2<true>: one head on four
+//                 48 slots (described at the kernel).  The heads that the groups of four leave
+//                 over (G not a multiple of four) run as k_bwd_dq2<true>: one head on four
 //                 consecutive query tiles per workgroup, with tile lists from k_bwd_wide_rows
 //   k_bwd_dkv2    head dimension 128: one workgroup per (pair of 64-key tiles, KV head), four
 //                 waves; the Q / dO tiles of the query tiles that see the pair stream through an LDS
@@ -1459,7 +1459,7 @@ int launch_dq(const BwdArgs& a, long total_qtiles, hipStream_t stream) {
 }
 
 // Query heads per KV head that the dQ kernel takes one at a time on four query tiles.
-int bwd_wide_heads(int G) { return (G % 4 == 1 || G % 4 == 2) ? G % 4 : 0; }
+int bwd_wide_heads(int G) { return G % 4; }
 
 // Development switch, read once: DAGATTN_BWD_V1=1 runs the first dQ and dK/dV kernels for every shape.
 bool bwd_first_version() {
@@ -1481,8 +1481,7 @@ int launch_bwd(const BwdArgs& args, long total_qtiles, long total_ktiles, hipStr
   int rc;
   a.dq_narrow = a.G;
   if (D == 128 && !bwd_first_version()) {
-    // one or two heads left over by the groups of four (G = 1, 2, 5, 6, ...) take four query tiles each;
-    // three left over (G = 3, 7, ...) run as a group of four with one idle wave pair
+    // the heads left over by the groups of four take four query tiles each
     const int wide = bwd_wide_heads(a.G);
     a.dq_narrow = a.G - wide;
     constexpr int sm2 = dq2::NST * dq2::STAGEB;
@@ -1711,7 +1710,7 @@ extern "C" size_t dag_prefill_bwd_workspace_bytes(const dag_meta_t* m, int32_t h
   size_t n = 2 * dag_align_up((size_t)m->sizes.total_tokens * hq * 4, 256) +
              2 * dag_align_up((size_t)m->sizes.total_ktiles * 4, 256) +
              dag_align_up((size_t)m->sizes.total_tokens * 8, 256) + 256;
-  // head groupings that leave one or two heads over at head dimension 128: the tile lists of the dQ
+  // head groupings that leave heads over (G not a multiple of four) at head dimension 128: the tile lists of the dQ
   // workgroups that take four query tiles (an int32 and a byte per entry of the dense block map,
   // three int32 per query tile)
   if (head_dim == 128 && hq % hkv == 0 && bwd_wide_heads(hq / hkv) > 0 && m->sizes.total_tiles >= 0)

@@ -221,9 +221,9 @@ def test_bwd_tiles_made_of_many_short_nodes():
         _check_against_oracle(dag_list, inputs, grads)
 
 
-@pytest.mark.parametrize("hq,hkv", [(1, 1), (2, 1), (5, 1), (6, 1), (10, 2)])
+@pytest.mark.parametrize("hq,hkv", [(1, 1), (2, 1), (3, 1), (5, 1), (6, 1), (7, 1), (10, 2)])
 def test_bwd_left_over_heads_on_four_query_tiles(hq, hkv):
-    """Head groupings that leave one or two heads over run dQ workgroups of one head on four
+    """Head groupings that leave heads over (not a multiple of four per KV head) run dQ workgroups of one head on four
     consecutive query tiles: sequences of 1, 2, 3, 4, 5 and 9 query tiles and one of a single token
     (groups that end before their fourth tile), a sequence with more than 64 nodes (two visibility
     words: its masked tiles take the general walk with one block-map entry per wave pair), tiles
