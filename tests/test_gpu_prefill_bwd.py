@@ -235,3 +235,28 @@ def test_bwd_left_over_heads_on_four_query_tiles(hq, hkv):
                 dags.random_dag(rng, n_nodes=30, depth=5, len_lo=1, len_hi=40)[:2], dags.fork_join(256, [64] * 4, 64)]
     inputs, grads = _forward_backward(dag_list, hq, hkv, 128, 800 + hq)
     _check_against_oracle(dag_list, inputs, grads)
+
+
+@pytest.mark.parametrize("hq,hkv", [(5, 1), (4, 1), (6, 2)])
+def test_bwd_batch_with_sequences_without_nodes(hq, hkv):
+    """Sequences without a node in front of, between and behind the real ones (the tables that count
+    query tiles and groups of four query tiles over the sequences must step over them)."""
+    real = [dags.fork_join(100, [90, 64, 33], 17), dags.linear_chain([300, 40])]
+    lens = np.concatenate([real[0][0], real[1][0]]).astype(np.int32)
+    bits = np.concatenate([real[0][1], real[1][1]])
+    n0, n1 = len(real[0][0]), len(real[1][0])
+    desc = B.DagDesc(np.array([0, 0, n0, n0, n0 + n1, n0 + n1], np.int32), lens, bits, 1, 64, 64)
+    meta = B.DagMeta(desc, B.dag_meta_sizes(desc), DEV)
+    B.dag_build_meta(desc, meta)
+    T = int(lens.sum())
+    q, k, v = dags.make_qkv(7, T, hq, hkv, 128, 0.7, torch.bfloat16)
+    dout = dags.make_qkv(8, T, hq, hkv, 128, 1.0, torch.bfloat16)[0].to(DEV)
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    B.dag_rope_qk(meta.get("pos_ids"), qd, kd, 5e5)
+    out = torch.empty_like(qd)
+    lse = torch.empty(T, hq, dtype=torch.float32, device=DEV)
+    B.dag_attn_prefill(meta, qd, kd, vd, out, lse)
+    dq, dk, dv = (torch.full_like(x, float("nan")) for x in (qd, kd, vd))
+    B.dag_attn_prefill_bwd(meta, qd, kd, vd, out, dout, lse, dq, dk, dv)
+    torch.cuda.synchronize()
+    _check_against_oracle(real, (qd, kd, v, dout), (dq, dk, dv))
