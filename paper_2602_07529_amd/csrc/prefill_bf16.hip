@@ -156,13 +156,20 @@ __global__ void __launch_bounds__(256) k_vt_prepare(const uint16_t* __restrict__
   }
   __syncthreads();
   uint16_t* o = vt + ((size_t)tile * hkv + h) * (size_t)(D * TN);
-  for (int c = threadIdx.x; c < D * (TN / 8); c += 256) {  // 16-byte piece c of the tile image
-    const int d = 8 * (c / 64) + (c % 8), kc = (c / 8) % 8;
-    uint32_t w[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      w[e] = (uint32_t)s[(8 * kc + 2 * e) * LD + d] | ((uint32_t)s[(8 * kc + 2 * e + 1) * LD + d] << 16);
-    *(u32x4*)(o + (size_t)c * 8) = u32x4{w[0], w[1], w[2], w[3]};
+  // 16-byte piece c of the tile image = dimension d, keys 8 kc .. 8 kc + 7: a column of the staged
+  // tile, fetched with the transposing LDS read (16 lanes point at four rows x 16 dimensions and
+  // lane i of them receives dimension i of those four rows; two reads give the eight keys).
+  typedef short v4i16 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) v4i16* lds_v4_t;
+  const int p = threadIdx.x & 15;
+  for (int g = threadIdx.x >> 4; g < (D / 16) * (TN / 8); g += 16) {
+    const int dg = g % (D / 16), kc = g / (D / 16);
+    const uint16_t* a0 = s + (8 * kc + (p >> 2)) * LD + 16 * dg + 4 * (p & 3);
+    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)a0);
+    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)(a0 + 4 * LD));
+    const int d = 16 * dg + p, c = 64 * (d / 8) + 8 * kc + d % 8;
+    typedef short v8i16 __attribute__((ext_vector_type(8)));
+    *(v8i16*)(o + (size_t)c * 8) = v8i16{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   }
 }
 
